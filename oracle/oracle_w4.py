@@ -1,0 +1,168 @@
+"""ctypes wrapper around the scalar C oracle (``oracle_w4.c``).
+
+TEST INFRASTRUCTURE ONLY: imported by ``tests/``, by ``__graft_entry__.smoke()`` and by the
+``cpu_baseline`` leg of ``bench.py``.  The GPU library never imports or links anything from here.
+
+Every function takes and returns numpy arrays; fp16 data travels as ``numpy.float16`` (or uint16 bit
+patterns) and is reinterpreted, never converted, on the way in and out.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+import subprocess
+
+import numpy as np
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_SRC = os.path.join(_HERE, "oracle_w4.c")
+_LIB = os.path.join(_HERE, "liboracle_w4.so")
+_lib = None
+
+
+def build(force: bool = False) -> str:
+    """Compile the oracle with gcc (scalar code, no fast-math, no FMA contraction)."""
+    if force or not os.path.exists(_LIB) or os.path.getmtime(_LIB) < os.path.getmtime(_SRC):
+        cmd = ["gcc", "-std=c11", "-O2", "-fPIC", "-shared", "-fopenmp", "-ffp-contract=off",
+               "-fvisibility=hidden", "-Wall", "-Wextra", "-o", _LIB, _SRC, "-lm"]
+        subprocess.run(cmd, check=True)
+    return _LIB
+
+
+def _load():
+    global _lib
+    if _lib is None:
+        build()
+        lib = ctypes.CDLL(_LIB)
+        c = ctypes
+        vp = c.c_void_p
+        lib.orc_fp16_to_double.restype = c.c_double
+        lib.orc_fp16_to_double.argtypes = [c.c_uint16]
+        lib.orc_double_to_fp16.restype = c.c_uint16
+        lib.orc_double_to_fp16.argtypes = [c.c_double]
+        lib.orc_quantise.argtypes = [vp, c.c_int, c.c_int, c.c_int, vp, vp, vp]
+        lib.orc_pack_canonical.argtypes = [vp, c.c_int, c.c_int, vp]
+        lib.orc_unpack_canonical.argtypes = [vp, c.c_int, c.c_int, vp]
+        lib.orc_unpack_packed.argtypes = [vp, vp, c.c_int, c.c_int, c.c_int, vp, vp, vp]
+        lib.orc_dequant.argtypes = [vp, vp, vp, c.c_int, c.c_int, c.c_int, vp]
+        lib.orc_gemm.argtypes = [vp, c.c_int, vp, vp, vp, c.c_int, c.c_int, c.c_int, vp, vp]
+        lib.orc_gemm_sampled.argtypes = [vp, c.c_int, vp, vp, vp, c.c_int, c.c_int, c.c_int,
+                                         vp, vp, c.c_long, vp, vp]
+        lib.orc_num_threads.restype = c.c_int
+        _lib = lib
+    return _lib
+
+
+def _ptr(a: np.ndarray):
+    return a.ctypes.data_as(ctypes.c_void_p)
+
+
+def _as(a, dtype) -> np.ndarray:
+    a = np.ascontiguousarray(a)
+    if a.dtype == np.float16 and dtype == np.uint16:
+        a = a.view(np.uint16)
+    if a.dtype != dtype:
+        raise TypeError(f"expected {dtype}, got {a.dtype}")
+    return a
+
+
+def _check(rc: int, what: str):
+    if rc != 0:
+        raise ValueError(f"oracle {what} rejected its arguments (code {rc})")
+
+
+def num_threads() -> int:
+    return int(_load().orc_num_threads())
+
+
+def fp16_to_double(bits: int) -> float:
+    return float(_load().orc_fp16_to_double(int(bits) & 0xFFFF))
+
+
+def double_to_fp16(x: float) -> int:
+    return int(_load().orc_double_to_fp16(float(x)))
+
+
+def quantise(W: np.ndarray, group: int):
+    """W fp32 [K,N] -> (q uint8 [K,N], s float16 [K/g,N], z float16 [K/g,N])."""
+    W = _as(W, np.float32)
+    K, N = W.shape
+    q = np.empty((K, N), np.uint8)
+    s = np.empty((K // group, N), np.uint16)
+    z = np.empty((K // group, N), np.uint16)
+    _check(_load().orc_quantise(_ptr(W), K, N, group, _ptr(q), _ptr(s), _ptr(z)), "quantise")
+    return q, s.view(np.float16), z.view(np.float16)
+
+
+def pack_canonical(q: np.ndarray) -> np.ndarray:
+    q = _as(q, np.uint8)
+    K, N = q.shape
+    out = np.empty((K, N // 8), np.uint32)
+    _check(_load().orc_pack_canonical(_ptr(q), K, N, _ptr(out)), "pack_canonical")
+    return out
+
+
+def unpack_canonical(words: np.ndarray, N: int) -> np.ndarray:
+    words = _as(words, np.uint32)
+    K = words.shape[0]
+    q = np.empty((K, N), np.uint8)
+    _check(_load().orc_unpack_canonical(_ptr(words), K, N, _ptr(q)), "unpack_canonical")
+    return q
+
+
+def unpack_packed(wbuf: np.ndarray, szbuf: np.ndarray, K: int, N: int, group: int):
+    """Invert the library's fragment-ordered buffers -> (q, s, z) in the plain [K,N] / [K/g,N] layouts."""
+    wbuf = _as(wbuf, np.uint32).reshape(-1)
+    szbuf = _as(szbuf, np.uint32).reshape(-1)
+    if wbuf.size != K * N // 8 or szbuf.size != (K // group) * N:
+        raise ValueError("packed buffer sizes do not match K, N, group")
+    q = np.empty((K, N), np.uint8)
+    s = np.empty((K // group, N), np.uint16)
+    z = np.empty((K // group, N), np.uint16)
+    _check(_load().orc_unpack_packed(_ptr(wbuf), _ptr(szbuf), K, N, group, _ptr(q), _ptr(s), _ptr(z)),
+           "unpack_packed")
+    return q, s.view(np.float16), z.view(np.float16)
+
+
+def dequant(q: np.ndarray, s: np.ndarray, z: np.ndarray, group: int) -> np.ndarray:
+    q = _as(q, np.uint8)
+    s = _as(s, np.uint16)
+    z = _as(z, np.uint16)
+    K, N = q.shape
+    out = np.empty((K, N), np.float64)
+    _check(_load().orc_dequant(_ptr(q), _ptr(s), _ptr(z), K, N, group, _ptr(out)), "dequant")
+    return out
+
+
+def gemm(X: np.ndarray, q: np.ndarray, s: np.ndarray, z: np.ndarray, group: int, want_fp64: bool = False):
+    """Y = fp16(X @ dequant(q,s,z)) with fp64 accumulation; optionally also the unrounded fp64 sums."""
+    X = _as(X, np.uint16)
+    q = _as(q, np.uint8)
+    s = _as(s, np.uint16)
+    z = _as(z, np.uint16)
+    M, K = X.shape
+    K2, N = q.shape
+    if K2 != K:
+        raise ValueError("X and q disagree on K")
+    Y = np.empty((M, N), np.uint16)
+    Yd = np.empty((M, N), np.float64) if want_fp64 else None
+    _check(_load().orc_gemm(_ptr(X), M, _ptr(q), _ptr(s), _ptr(z), K, N, group, _ptr(Y),
+                            _ptr(Yd) if want_fp64 else None), "gemm")
+    return (Y.view(np.float16), Yd) if want_fp64 else Y.view(np.float16)
+
+
+def gemm_sampled(X, q, s, z, group: int, ms, ns, want_fp64: bool = False):
+    """The plain triple loop evaluated only at the listed (m, n) pairs."""
+    X = _as(X, np.uint16)
+    q = _as(q, np.uint8)
+    s = _as(s, np.uint16)
+    z = _as(z, np.uint16)
+    ms = np.ascontiguousarray(ms, dtype=np.int32)
+    ns = np.ascontiguousarray(ns, dtype=np.int32)
+    M, K = X.shape
+    _, N = q.shape
+    Y = np.empty(ms.shape, np.uint16)
+    Yd = np.empty(ms.shape, np.float64) if want_fp64 else None
+    _check(_load().orc_gemm_sampled(_ptr(X), M, _ptr(q), _ptr(s), _ptr(z), K, N, group, _ptr(ms), _ptr(ns),
+                                    ms.size, _ptr(Y), _ptr(Yd) if want_fp64 else None), "gemm_sampled")
+    return (Y.view(np.float16), Yd) if want_fp64 else Y.view(np.float16)
