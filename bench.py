@@ -1,0 +1,253 @@
+#!/usr/bin/env python3
+"""Benchmark of the W4A16 GEMM hot path on one MI355X.
+
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload decode|mlp_decode|prefill|sweep]
+                    [--sweep-out FILE] [--no-cpu-baseline] [--no-prefill]
+
+A "step" is one pass of the fused GEMM over every (layer, M) pair of the workload, weights already packed
+(packing is the paper's offline stage and is timed separately, once).  Inputs are resident in HBM before the timed
+region; every launch reads a different packed copy of its layer's weights, rotating through more than 512 MB per
+layer, so that no launch finds its weights in L2 or in the 256 MB Infinity Cache.
+
+Prints ONE JSON line.  `value` is the effective HBM bandwidth (algorithmic bytes / time) of the default decode
+workload (K=4096, N in {4096, 12288}, M in {1, 4, 8, 16}); the prefill TFLOP/s is reported beside it.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBPS = 8000.0          # MI355X HBM3E
+MFMA_F16_PEAK_TFLOPS = 2516.6   # 256 CUs x 2.4 GHz x 4096 flop/clk/CU, dense
+ROTATE_BYTES = 512 << 20
+METRIC = "W4A16 GEMM TFLOP/s + effective HBM GB/s (% roofline), M=1..4096"
+
+WORKLOADS = {
+    # name: (list of (layer case name at its largest M, Ms))
+    "decode": [("cfg2_attn_out_M16", (1, 4, 8, 16)), ("cfg2_qkv_M16", (1, 4, 8, 16))],
+    "mlp_decode": [("cfg3_gate_up_M64", (1, 16, 32, 64)), ("cfg3_down_M64", (1, 16, 32, 64))],
+    "prefill": [("cfg4_prefill_70b_mlp", (4096,))],
+    "sweep5": [("cfg5_sweep_M1024", (1, 2, 4, 8, 32, 128, 256, 1024))],
+}
+
+
+def log(*a):
+    print(*a, file=sys.stderr, flush=True)
+
+
+class Layer:
+    """One weight matrix: R packed copies on the device, X/Y buffers for each M."""
+
+    def __init__(self, tm, torch, wl, case_name, Ms, rotate_bytes=ROTATE_BYTES):
+        import numpy as np
+        self.case = wl.case_by_name(case_name)
+        c = self.case
+        t0 = time.time()
+        self.data = wl.make(c)
+        self.gen_s = time.time() - t0
+        d = self.data
+        dev = lambda a: torch.from_numpy(np.ascontiguousarray(a.view(np.int32) if a.dtype == np.uint32 else a)).cuda()
+        qw, s, z = dev(d["qweight"]), dev(d["s"]), dev(d["z"])
+        wbytes = c.K * c.N // 2 + 4 * c.K * c.N // c.group
+        self.copies = max(2, -(-rotate_bytes // wbytes))
+        torch.cuda.synchronize()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        self.packed = [tm.tm_pack_w4(qw, s, z, c.K, c.N, c.group)]          # first call also sets up the workspace
+        torch.cuda.synchronize()
+        e0.record()
+        for _ in range(self.copies - 1):
+            self.packed.append(tm.tm_pack_w4(qw, s, z, c.K, c.N, c.group))
+        e1.record()
+        torch.cuda.synchronize()
+        self.pack_ms = e0.elapsed_time(e1) / max(1, self.copies - 1)
+        self.Ms = tuple(Ms)
+        Xfull = dev(d["X"])
+        # several X/Y buffers per M so that activations rotate too
+        self.X = {M: [Xfull[:M].clone() for _ in range(4)] for M in self.Ms}
+        self.Y = {M: [torch.empty((M, c.N), dtype=torch.float16, device="cuda") for _ in range(4)] for M in self.Ms}
+        self.turn = 0
+
+    def launch(self, tm, M):
+        i = self.turn
+        self.turn += 1
+        tm.tm_gemm_w4a16(self.X[M][i % 4], self.packed[i % self.copies], self.Y[M][i % 4])
+
+
+def time_steps(torch, step_fn, steps, warmup):
+    for _ in range(warmup):
+        step_fn()
+    torch.cuda.synchronize()
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    t0 = time.perf_counter()
+    e0.record()
+    for _ in range(steps):
+        step_fn()
+    e1.record()
+    torch.cuda.synchronize()
+    wall_ms = (time.perf_counter() - t0) * 1e3
+    return e0.elapsed_time(e1), wall_ms
+
+
+def per_shape_table(tm, torch, wl, layers, iters=100, warmup=10):
+    rows = []
+    for L in layers:
+        c = L.case
+        for M in L.Ms:
+            ev_ms, _ = time_steps(torch, lambda: L.launch(tm, M), iters, warmup)
+            t = ev_ms / iters * 1e-3
+            B = wl.algorithmic_bytes(M, c.K, c.N, c.group)
+            F = wl.flops(M, c.K, c.N)
+            plan = tm.tm_get_plan(L.packed[0], M)
+            rows.append({"layer": c.name.rsplit("_M", 1)[0], "M": M, "K": c.K, "N": c.N, "group": c.group,
+                         "us": t * 1e6, "GBps": B / t / 1e9, "TFLOPs": F / t / 1e12,
+                         "hbm_frac": B / t / 1e9 / HBM_PEAK_GBPS, "mfma_frac": F / t / 1e12 / MFMA_F16_PEAK_TFLOPS,
+                         "variant": plan["name"], "split_k": plan["split_k"], "grid": plan["grid"]})
+    return rows
+
+
+def cpu_baseline(wl, layers, budget_s=25.0):
+    """The oracle as it stands, timed on this host's cores over the same workload (bounded by a time budget)."""
+    from oracle import oracle_w4
+    total_bytes = 0
+    total_flops = 0
+    total_s = 0.0
+    done = []
+    for L in layers:
+        c, d = L.case, L.data
+        for M in L.Ms:
+            if total_s > budget_s:
+                break
+            rows = M
+            est_rate = 1.5e9 * max(1, oracle_w4.num_threads())       # generous MAC/s guess to bound one call
+            if rows * c.K * c.N / est_rate > budget_s:
+                rows = max(1, int(budget_s * est_rate / (c.K * c.N)))
+            t0 = time.perf_counter()
+            oracle_w4.gemm(d["X"][:rows], d["q"], d["s"], d["z"], c.group)
+            dt = time.perf_counter() - t0
+            total_s += dt
+            total_bytes += wl.algorithmic_bytes(rows, c.K, c.N, c.group)
+            total_flops += wl.flops(rows, c.K, c.N)
+            done.append(f"{c.name.rsplit('_M', 1)[0]}:M={rows}" + ("" if rows == M else f"(of {M})"))
+    return {"seconds": total_s, "bytes": total_bytes, "flops": total_flops, "cores": oracle_w4.num_threads(),
+            "sample": "oracle.gemm (fp64, scalar C, OpenMP) over " + ", ".join(done)}
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=200)
+    ap.add_argument("--warmup", type=int, default=20)
+    ap.add_argument("--workload", default="decode", choices=sorted(WORKLOADS) + ["sweep"])
+    ap.add_argument("--sweep-out", default=None, help="with --workload sweep: write the per-shape table here (JSON)")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-prefill", action="store_true", help="skip the prefill companion measurement")
+    ap.add_argument("--variant", type=int, default=-1)
+    ap.add_argument("--split-k", type=int, default=0)
+    args = ap.parse_args()
+    if args.gpus != 1:
+        sys.exit("bench.py: this build runs on one GPU only (no sharding, no collectives); use --gpus 1")
+
+    import torch
+    import paper_2508_15601_amd as tm
+    from workloads import w4a16 as wl
+    if not torch.cuda.is_available():
+        sys.exit("bench.py needs a GPU")
+    torch.cuda.set_device(0)
+    tm.load_library()
+    tm.tm_set_variant(args.variant, args.split_k)
+
+    if args.workload == "sweep":
+        table = []
+        for name in ("decode", "mlp_decode", "sweep5", "prefill"):
+            layers = [Layer(tm, torch, wl, cn, Ms) for cn, Ms in WORKLOADS[name]]
+            rows = per_shape_table(tm, torch, wl, layers, iters=(10 if name == "prefill" else 100))
+            for r in rows:
+                r["workload"] = name
+                log(f"{r['layer']:16s} M={r['M']:5d} K={r['K']:6d} N={r['N']:6d} g={r['group']:3d} {r['us']:9.2f} us "
+                    f"{r['GBps']:8.1f} GB/s ({100 * r['hbm_frac']:5.1f}% HBM) {r['TFLOPs']:8.2f} TF "
+                    f"({100 * r['mfma_frac']:5.1f}% MFMA) {r['variant']} split={r['split_k']} grid={r['grid']}")
+            table += rows
+            for L in layers:
+                log(f"   pack {L.case.K}x{L.case.N}: {L.pack_ms:.3f} ms per matrix "
+                    f"({L.case.K * L.case.N / 2 / L.pack_ms / 1e6:.1f} GB/s of int4 out)")
+            del layers
+            torch.cuda.empty_cache()
+        if args.sweep_out:
+            os.makedirs(os.path.dirname(os.path.abspath(args.sweep_out)), exist_ok=True)
+            json.dump(table, open(args.sweep_out, "w"), indent=1)
+        print(json.dumps({"metric": METRIC, "workload": "sweep", "rows": len(table)}))
+        return
+
+    layers = [Layer(tm, torch, wl, cn, Ms) for cn, Ms in WORKLOADS[args.workload]]
+    launches_per_step = sum(len(L.Ms) for L in layers)
+
+    def step():
+        for L in layers:
+            for M in L.Ms:
+                L.launch(tm, M)
+
+    ev_ms, wall_ms = time_steps(torch, step, args.steps, args.warmup)
+    ms_per_step = ev_ms / args.steps
+    B = sum(wl.algorithmic_bytes(M, L.case.K, L.case.N, L.case.group) for L in layers for M in L.Ms)
+    F = sum(wl.flops(M, L.case.K, L.case.N) for L in layers for M in L.Ms)
+    gbps = B / (ms_per_step * 1e-3) / 1e9
+    tflops = F / (ms_per_step * 1e-3) / 1e12
+    hbm_bound = args.workload != "prefill"
+    if hbm_bound:
+        roofline = {"bound": "hbm", "achieved": gbps, "peak": HBM_PEAK_GBPS, "unit": "GB/s",
+                    "frac": gbps / HBM_PEAK_GBPS, "traffic": None}
+    else:
+        roofline = {"bound": "mfma", "achieved": tflops, "peak": MFMA_F16_PEAK_TFLOPS, "unit": "TFLOP/s",
+                    "frac": tflops / MFMA_F16_PEAK_TFLOPS, "traffic": None}
+    roofline["kernel"] = tm.tm_get_plan(layers[0].packed[0], layers[0].Ms[-1])["name"]
+    roofline["launches_per_step"] = launches_per_step
+    roofline["avg_launch_us"] = ms_per_step * 1e3 / launches_per_step
+    roofline["algorithmic_bytes_per_step"] = B
+    roofline["flops_per_step"] = F
+    traffic_file = os.path.join(ROOT, "profiles", "traffic.json")
+    if os.path.exists(traffic_file):
+        roofline["traffic"] = json.load(open(traffic_file)).get(args.workload)
+
+    out = {
+        "metric": METRIC, "value": gbps if hbm_bound else tflops, "unit": "GB/s" if hbm_bound else "TFLOP/s",
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms_per_step,
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "f16", "data": "synthetic",
+        "config": {"workload": {"decode": "configs[1]: W4A16 GEMM K=4096, N in {4096, 12288}, group=128, M in {1,4,8,16}",
+                                "mlp_decode": "configs[2]: K=4096,N=22016 and K=11008,N=4096, group=128, M in {1,16,32,64}",
+                                "prefill": "configs[3]: M=4096, K=8192, N=28672, group=128",
+                                "sweep5": "configs[4]: K=8192, N=8192, group=64, M in {1,2,4,8,32,128,256,1024}"}[args.workload],
+                   "launches_per_step": launches_per_step, "weight_copies_rotated": [L.copies for L in layers]},
+        "tflops": tflops, "effective_GBps": gbps, "host_wall_ms_per_step": wall_ms / args.steps,
+        "pack_ms_per_matrix": {f"{L.case.K}x{L.case.N}": L.pack_ms for L in layers},
+        "roofline": roofline,
+    }
+
+    if args.workload == "decode" and not args.no_prefill:
+        PL = Layer(tm, torch, wl, *WORKLOADS["prefill"][0])
+        pms, _ = time_steps(torch, lambda: PL.launch(tm, 4096), 10, 3)
+        t = pms / 10 * 1e-3
+        c = PL.case
+        ptf = wl.flops(4096, c.K, c.N) / t / 1e12
+        out["prefill"] = {"workload": "configs[3]: M=4096, K=8192, N=28672, group=128", "ms": t * 1e3, "TFLOPs": ptf,
+                          "roofline": {"bound": "mfma", "achieved": ptf, "peak": MFMA_F16_PEAK_TFLOPS,
+                                       "unit": "TFLOP/s", "frac": ptf / MFMA_F16_PEAK_TFLOPS},
+                          "kernel": tm.tm_get_plan(PL.packed[0], 4096)["name"]}
+        del PL
+
+    if not args.no_cpu_baseline:
+        cb = cpu_baseline(wl, layers)
+        v = cb["bytes"] / cb["seconds"] / 1e9 if hbm_bound else cb["flops"] / cb["seconds"] / 1e12
+        out["cpu_baseline"] = {"value": v, "unit": out["unit"], "cores": cb["cores"], "kind": "oracle",
+                               "sample": cb["sample"], "seconds": cb["seconds"]}
+    print(json.dumps(out))
+
+
+if __name__ == "__main__":
+    main()

@@ -1,0 +1,137 @@
+/*
+ * tm_w4 — W4A16 weight-only-quantised GEMM for AMD Instinct MI355X (gfx950).
+ *
+ *     Y[M,N] (fp16) = X[M,K] (fp16) * dequant(Wq)[K,N],   dequant(Wq)[k][n] = (q[k][n] - z[k/g][n]) * s[k/g][n]
+ *
+ * Two stages, following the GEMM pipeline of the paper (Sec. 3.3 "GEMM pipeline design"):
+ *   offline  tm_pack_w4      — hardware-aware weight packing (Sec. 4.1): the int4 weights are permuted once into the
+ *                              order in which the matrix-core fragments consume them, so that the online stage needs
+ *                              no run-time layout transformation;
+ *   online   tm_gemm_w4a16   — the mixed-precision GEMM (Sec. 3.1 steps (i)-(iv), Sec. 4.3): packed weights are
+ *                              loaded with coalesced 128-bit loads, converted int4 -> fp16 by bit manipulation,
+ *                              zero-point and scale are applied per K-group, and fp16 matrix-core instructions
+ *                              accumulate in fp32; the result is rounded once to fp16.
+ *
+ * Conventions
+ *   - Plain C ABI.  Every pointer is a DEVICE pointer on the current HIP device unless a parameter says "host".
+ *     The caller owns all buffers it passes in; the library owns what a tm_packed_w4 handle refers to.
+ *   - fp16 values travel as their 16-bit patterns (uint16_t).
+ *   - No call synchronises the device or the stream.  Work is enqueued on the given stream (NULL = the null stream)
+ *     and the caller keeps argument buffers alive until that work has run.
+ *   - Functions returning int return TM_OK (0) or a negative tm_status; functions returning a pointer return NULL on
+ *     error.  tm_last_error() then describes the failure (thread-local).  No C++ exception crosses this boundary.
+ *   - Shape limits: K % 128 == 0, N % 16 == 0, group in {32, 64, 128}, 0 <= M < 2^24, K*N < 2^40.
+ */
+#ifndef TM_W4_H
+#define TM_W4_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define TM_API __attribute__((visibility("default")))
+
+typedef enum tm_status {
+    TM_OK = 0,
+    TM_EINVAL = -1,        /* null pointer, bad shape, misaligned buffer, workspace too small */
+    TM_EUNSUPPORTED = -2,  /* current device is not gfx950 */
+    TM_EHIP = -3,          /* a HIP runtime call failed; tm_last_error() carries its message */
+    TM_ENOMEM = -4         /* device allocation failed */
+} tm_status;
+
+typedef struct tm_packed_w4 tm_packed_w4;  /* opaque handle; immutable after creation */
+typedef void* tm_stream;                   /* a hipStream_t */
+
+/*
+ * Offline hardware-aware weight packing (paper Sec. 4.1, steps (i)-(iv); here a closed-form permutation because the
+ * gfx950 matrix-core operand layout is an explicit lane/register index map).
+ *
+ *   qweight  u32 [K][N/8]       interchange layout "eight INT4 values per 32-bit word" (Sec. 3.2, M2):
+ *                               nibble t (bits 4t..4t+3) of word (k, j) is q[k][8j + t], values 0..15
+ *   scales   fp16 [K/group][N]  s, finite and positive
+ *   zeros    fp16 [K/group][N]  z, integer-valued in [0, 15]
+ *
+ * Allocates the handle's device buffers (K*N/2 bytes of weights, 4*K*N/group bytes of scale/zero pairs), makes sure
+ * the device-wide split-K workspace is large enough for this shape, and enqueues the repack kernels on `stream`.
+ * The inputs may be released once that stream work has completed.  Returns NULL on error.
+ *
+ * Packed layout (also what tm_packed_raw exposes):
+ *   weights: units of 16 columns x 128 rows; unit (nt, ku) is the 256 u32 words starting at ((nt*(K/128))+ku)*256;
+ *            word 4*lane + t (lane = 16*h + c, c in 0..15, h in 0..3, t in 0..3) holds column 16*nt + c, rows
+ *            128*ku + 32*t + 8*h + e (e = 0..7), weight e in nibble 4*(e&1) + (e>>1).
+ *   scale/zero: u32 word ((nt*(K/group)) + G)*16 + c = scale bits | zero bits << 16 for column 16*nt + c, group G.
+ */
+TM_API tm_packed_w4* tm_pack_w4(const uint32_t* qweight, const uint16_t* scales, const uint16_t* zeros,
+                                int K, int N, int group);
+/* Same, on an explicit stream (tm_pack_w4 uses the null stream). */
+TM_API tm_packed_w4* tm_pack_w4_on(const uint32_t* qweight, const uint16_t* scales, const uint16_t* zeros,
+                                   int K, int N, int group, tm_stream stream);
+
+/*
+ * Online mixed-precision GEMM (paper Sec. 3.1 steps (i)-(iv) and Sec. 4.3): Y = X * dequant(packed).
+ *
+ *   X  fp16 [M][K] row-major, 16-byte aligned        Y  fp16 [M][N] row-major, 4-byte aligned
+ *
+ * Picks a kernel variant and a split-K factor from (M, K, N, group) and enqueues it on `stream`.  Never allocates.
+ * Split-K partial sums go through the library's device-wide workspace and are reduced in a fixed order, so results
+ * are bit-identical from run to run.  Because that workspace is shared, calls on one device must be ordered on one
+ * stream (or serialised by the caller); use tm_gemm_w4a16_ws for concurrent streams.  M == 0 is a successful no-op.
+ */
+TM_API int tm_gemm_w4a16(const uint16_t* X, const tm_packed_w4* packed, uint16_t* Y, int M, tm_stream stream);
+
+/*
+ * Same multiply with a caller-owned workspace of at least tm_gemm_workspace_bytes(packed, M) bytes, 256-byte aligned.
+ * The workspace must be zero-filled once before its first use; every call leaves it ready for the next one.
+ * Distinct workspaces may be used concurrently on distinct streams.
+ */
+TM_API int tm_gemm_w4a16_ws(const uint16_t* X, const tm_packed_w4* packed, uint16_t* Y, int M,
+                            void* workspace, size_t workspace_bytes, tm_stream stream);
+
+/* Workspace bytes the plan for this (packed, M) needs (0 is never returned for M > 0; 0 on error or M == 0). */
+TM_API size_t tm_gemm_workspace_bytes(const tm_packed_w4* packed, int M);
+
+/* Releases the handle and its device buffers.  NULL is ignored.  The caller makes sure no enqueued work still uses it. */
+TM_API void tm_free_packed(tm_packed_w4* packed);
+
+/* Shape of a handle; any out-pointer (host) may be NULL.  `bytes` = device bytes held (weights + scale/zero pairs). */
+TM_API int tm_packed_info(const tm_packed_w4* packed, int* K, int* N, int* group, size_t* bytes);
+
+/*
+ * Test hooks for the bit-exact packing check.
+ * tm_unpack_w4 runs the inverse permutation on the device: qweight_out u32 [K][N/8], scales_out / zeros_out
+ * fp16 [K/group][N] (any of the three may be NULL).  tm_packed_raw returns the handle's device buffers (host
+ * out-pointers; the memory stays owned by the handle) so that an independent unpacker can be run on a copy.
+ */
+TM_API int tm_unpack_w4(const tm_packed_w4* packed, uint32_t* qweight_out, uint16_t* scales_out,
+                        uint16_t* zeros_out, tm_stream stream);
+TM_API int tm_packed_raw(const tm_packed_w4* packed, const void** weights, size_t* weight_bytes,
+                         const void** scale_zero, size_t* scale_zero_bytes);
+
+/*
+ * Kernel selection (the run-time counterpart of the tile configuration the paper's packing is meant to make
+ * unnecessary to hand-tune per architecture, Sec. 4.1).  tm_get_plan reports what tm_gemm_w4a16 would launch for M
+ * rows (host out-pointers, any may be NULL).  tm_set_variant overrides the choice process-wide for sweeps:
+ * variant -1 / split_k 0 restore automatic selection.  tm_variant_name(-1..) returns "" past the last variant.
+ */
+TM_API int tm_get_plan(const tm_packed_w4* packed, int M, int* variant, int* split_k, int* grid, int* block);
+TM_API int tm_set_variant(int variant, int split_k);
+TM_API const char* tm_variant_name(int variant);
+
+/*
+ * Measurement helpers (not part of the method): a plain 128-bit copy kernel of known size, used to calibrate the
+ * profiler's HBM byte counters, and a read-only streaming kernel that gives the achievable HBM read ceiling.
+ * `bytes` must be a multiple of 16; `sink` is a 4-byte device location the read kernel may write.
+ */
+TM_API int tm_bench_copy(void* dst, const void* src, size_t bytes, tm_stream stream);
+TM_API int tm_bench_read(const void* src, size_t bytes, void* sink, tm_stream stream);
+
+TM_API const char* tm_last_error(void);
+TM_API const char* tm_version(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* TM_W4_H */

@@ -1,0 +1,229 @@
+"""ctypes binding of libtm_w4.so.  Same names as the C ABI; tensors are torch CUDA(=HIP) tensors.
+
+The library is loaded from this directory and nowhere else; if it is missing the import of any entry point fails
+loudly (there is no fallback path of any kind)."""
+from __future__ import annotations
+
+import ctypes
+import os
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_LIB_PATH = os.path.join(_HERE, "libtm_w4.so")
+_lib = None
+
+TM_OK = 0
+
+
+class TmError(RuntimeError):
+    def __init__(self, code: int, message: str):
+        super().__init__(f"tm_w4 error {code}: {message}")
+        self.code = code
+
+
+def lib_path() -> str:
+    return _LIB_PATH
+
+
+def load_library():
+    """dlopen libtm_w4.so (built by paper_2508_15601_amd/build.py) and declare every entry point."""
+    global _lib
+    if _lib is not None:
+        return _lib
+    if not os.path.exists(_LIB_PATH):
+        raise ImportError(f"{_LIB_PATH} is missing: run `python -c 'import __graft_entry__ as g; g.build()'` first")
+    lib = ctypes.CDLL(_LIB_PATH)
+    c = ctypes
+    vp, sz, i = c.c_void_p, c.c_size_t, c.c_int
+    lib.tm_pack_w4.restype = vp
+    lib.tm_pack_w4.argtypes = [vp, vp, vp, i, i, i]
+    lib.tm_pack_w4_on.restype = vp
+    lib.tm_pack_w4_on.argtypes = [vp, vp, vp, i, i, i, vp]
+    lib.tm_gemm_w4a16.restype = i
+    lib.tm_gemm_w4a16.argtypes = [vp, vp, vp, i, vp]
+    lib.tm_gemm_w4a16_ws.restype = i
+    lib.tm_gemm_w4a16_ws.argtypes = [vp, vp, vp, i, vp, sz, vp]
+    lib.tm_gemm_workspace_bytes.restype = sz
+    lib.tm_gemm_workspace_bytes.argtypes = [vp, i]
+    lib.tm_free_packed.restype = None
+    lib.tm_free_packed.argtypes = [vp]
+    lib.tm_packed_info.restype = i
+    lib.tm_packed_info.argtypes = [vp, c.POINTER(i), c.POINTER(i), c.POINTER(i), c.POINTER(sz)]
+    lib.tm_unpack_w4.restype = i
+    lib.tm_unpack_w4.argtypes = [vp, vp, vp, vp, vp]
+    lib.tm_packed_raw.restype = i
+    lib.tm_packed_raw.argtypes = [vp, c.POINTER(vp), c.POINTER(sz), c.POINTER(vp), c.POINTER(sz)]
+    lib.tm_get_plan.restype = i
+    lib.tm_get_plan.argtypes = [vp, i, c.POINTER(i), c.POINTER(i), c.POINTER(i), c.POINTER(i)]
+    lib.tm_set_variant.restype = i
+    lib.tm_set_variant.argtypes = [i, i]
+    lib.tm_variant_name.restype = c.c_char_p
+    lib.tm_variant_name.argtypes = [i]
+    lib.tm_bench_copy.restype = i
+    lib.tm_bench_copy.argtypes = [vp, vp, sz, vp]
+    lib.tm_bench_read.restype = i
+    lib.tm_bench_read.argtypes = [vp, sz, vp, vp]
+    lib.tm_last_error.restype = c.c_char_p
+    lib.tm_last_error.argtypes = []
+    lib.tm_version.restype = c.c_char_p
+    lib.tm_version.argtypes = []
+    _lib = lib
+    return lib
+
+
+def tm_last_error() -> str:
+    return load_library().tm_last_error().decode()
+
+
+def tm_version() -> str:
+    return load_library().tm_version().decode()
+
+
+def _check(rc: int):
+    if rc != TM_OK:
+        raise TmError(rc, tm_last_error())
+
+
+def _stream_ptr(stream):
+    import torch
+    if stream is None:
+        stream = torch.cuda.current_stream()
+    return ctypes.c_void_p(stream.cuda_stream)
+
+
+def _dev_ptr(t, dtype, what):
+    import torch
+    if not isinstance(t, torch.Tensor) or not t.is_cuda:
+        raise TypeError(f"{what} must be a device tensor")
+    if t.dtype != dtype:
+        raise TypeError(f"{what} must have dtype {dtype}, got {t.dtype}")
+    if not t.is_contiguous():
+        raise ValueError(f"{what} must be contiguous")
+    return ctypes.c_void_p(t.data_ptr())
+
+
+class PackedW4:
+    """Owner of a tm_packed_w4 handle; freed when garbage-collected or on ``close()``."""
+
+    def __init__(self, handle: int, K: int, N: int, group: int):
+        self._h = handle
+        self.K, self.N, self.group = K, N, group
+
+    @property
+    def handle(self):
+        if not self._h:
+            raise ValueError("packed handle already freed")
+        return ctypes.c_void_p(self._h)
+
+    def close(self):
+        if self._h:
+            import torch
+            torch.cuda.synchronize()
+            load_library().tm_free_packed(ctypes.c_void_p(self._h))
+            self._h = 0
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass
+
+
+def tm_pack_w4(qweight, scales, zeros, K: int, N: int, group: int, stream=None) -> PackedW4:
+    """qweight int32 [K, N/8] (interchange nibble order), scales/zeros float16 [K/group, N] -> PackedW4."""
+    import torch
+    lib = load_library()
+    if tuple(qweight.shape) != (K, N // 8) or tuple(scales.shape) != (K // group, N) or tuple(zeros.shape) != (K // group, N):
+        raise ValueError("tensor shapes do not match K, N, group")
+    h = lib.tm_pack_w4_on(_dev_ptr(qweight, torch.int32, "qweight"), _dev_ptr(scales, torch.float16, "scales"),
+                          _dev_ptr(zeros, torch.float16, "zeros"), K, N, group, _stream_ptr(stream))
+    if not h:
+        raise TmError(-1, tm_last_error())
+    return PackedW4(h, K, N, group)
+
+
+def tm_gemm_w4a16(X, packed: PackedW4, Y, stream=None):
+    """Y[M,N] = X[M,K] * dequant(packed); X, Y float16 device tensors; enqueued on the current stream."""
+    import torch
+    M = X.shape[0]
+    if X.dim() != 2 or X.shape[1] != packed.K or tuple(Y.shape) != (M, packed.N):
+        raise ValueError("X/Y shapes do not match the packed weight")
+    if M == 0:
+        return Y
+    _check(load_library().tm_gemm_w4a16(_dev_ptr(X, torch.float16, "X"), packed.handle,
+                                        _dev_ptr(Y, torch.float16, "Y"), M, _stream_ptr(stream)))
+    return Y
+
+
+def tm_gemm_w4a16_ws(X, packed: PackedW4, Y, workspace, stream=None):
+    import torch
+    M = X.shape[0]
+    if X.dim() != 2 or X.shape[1] != packed.K or tuple(Y.shape) != (M, packed.N):
+        raise ValueError("X/Y shapes do not match the packed weight")
+    if M == 0:
+        return Y
+    _check(load_library().tm_gemm_w4a16_ws(_dev_ptr(X, torch.float16, "X"), packed.handle,
+                                           _dev_ptr(Y, torch.float16, "Y"), M,
+                                           _dev_ptr(workspace, torch.uint8, "workspace"), workspace.numel(),
+                                           _stream_ptr(stream)))
+    return Y
+
+
+def tm_gemm_workspace_bytes(packed: PackedW4, M: int) -> int:
+    return int(load_library().tm_gemm_workspace_bytes(packed.handle, M))
+
+
+def tm_unpack_w4(packed: PackedW4, stream=None):
+    """Device-side inverse permutation -> (qweight int32 [K,N/8], scales f16, zeros f16)."""
+    import torch
+    K, N, g = packed.K, packed.N, packed.group
+    q = torch.empty((K, N // 8), dtype=torch.int32, device="cuda")
+    s = torch.empty((K // g, N), dtype=torch.float16, device="cuda")
+    z = torch.empty((K // g, N), dtype=torch.float16, device="cuda")
+    _check(load_library().tm_unpack_w4(packed.handle, ctypes.c_void_p(q.data_ptr()), ctypes.c_void_p(s.data_ptr()),
+                                       ctypes.c_void_p(z.data_ptr()), _stream_ptr(stream)))
+    return q, s, z
+
+
+def tm_packed_raw(packed: PackedW4):
+    """Copies of the handle's raw device buffers as host numpy uint32 arrays (weights words, scale|zero words)."""
+    import numpy as np
+    import torch
+    lib = load_library()
+    w, sz = ctypes.c_void_p(), ctypes.c_void_p()
+    wb, szb = ctypes.c_size_t(), ctypes.c_size_t()
+    _check(lib.tm_packed_raw(packed.handle, ctypes.byref(w), ctypes.byref(wb), ctypes.byref(sz), ctypes.byref(szb)))
+    torch.cuda.synchronize()
+    outs = []
+    for ptr, nbytes in ((w, wb.value), (sz, szb.value)):
+        tmp = torch.empty(nbytes // 4, dtype=torch.int32, device="cuda")
+        _check(lib.tm_bench_copy(ctypes.c_void_p(tmp.data_ptr()), ptr, nbytes, _stream_ptr(None)))
+        outs.append(tmp.cpu().numpy().view(np.uint32))
+    return outs[0], outs[1]
+
+
+def tm_get_plan(packed: PackedW4, M: int) -> dict:
+    lib = load_library()
+    v, s, g, b = ctypes.c_int(), ctypes.c_int(), ctypes.c_int(), ctypes.c_int()
+    _check(lib.tm_get_plan(packed.handle, M, ctypes.byref(v), ctypes.byref(s), ctypes.byref(g), ctypes.byref(b)))
+    return {"variant": v.value, "name": lib.tm_variant_name(v.value).decode(), "split_k": s.value,
+            "grid": g.value, "block": b.value}
+
+
+def tm_set_variant(variant: int = -1, split_k: int = 0):
+    _check(load_library().tm_set_variant(variant, split_k))
+
+
+def tm_variant_name(variant: int) -> str:
+    return load_library().tm_variant_name(variant).decode()
+
+
+def tm_bench_copy(dst, src, stream=None):
+    nbytes = src.numel() * src.element_size()
+    _check(load_library().tm_bench_copy(ctypes.c_void_p(dst.data_ptr()), ctypes.c_void_p(src.data_ptr()), nbytes,
+                                        _stream_ptr(stream)))
+
+
+def tm_bench_read(src, sink, stream=None):
+    nbytes = src.numel() * src.element_size()
+    _check(load_library().tm_bench_read(ctypes.c_void_p(src.data_ptr()), nbytes, ctypes.c_void_p(sink.data_ptr()),
+                                        _stream_ptr(stream)))

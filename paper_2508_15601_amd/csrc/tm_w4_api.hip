@@ -1,0 +1,402 @@
+// C ABI of libtm_w4: argument checking, handle and workspace management, kernel selection.
+#include <stdarg.h>
+#include <stdio.h>
+#include <string.h>
+
+#include <mutex>
+#include <new>
+
+#include "tm_w4.h"
+#include "tm_w4_host.h"
+
+namespace tmw4 {
+
+namespace {
+
+constexpr uint32_t kMagic = 0x74573461u;              // "tW4a"
+constexpr size_t kPartialBudget = 32u << 20;          // bytes of fp32 partial sums a plan may use
+constexpr size_t kWorkspaceBytes = kCounterBytes + kPartialBudget;
+constexpr int kMaxDevices = 16;
+
+thread_local char g_error[512] = "";
+
+int fail(int code, const char* fmt, ...)
+{
+    va_list ap;
+    va_start(ap, fmt);
+    vsnprintf(g_error, sizeof(g_error), fmt, ap);
+    va_end(ap);
+    return code;
+}
+
+int fail_hip(hipError_t e, const char* what)
+{
+    return fail(e == hipErrorOutOfMemory ? TM_ENOMEM : TM_EHIP, "%s: %s", what, hipGetErrorString(e));
+}
+
+struct DeviceState {
+    bool checked = false;
+    bool supported = false;
+    void* workspace = nullptr;
+    int num_cu = 256;
+};
+DeviceState g_dev[kMaxDevices];
+std::mutex g_mutex;
+int g_force_variant = -1;
+int g_force_split = 0;
+
+// Current device must be gfx950; result cached per device.
+int check_device(int* dev_out)
+{
+    int dev = -1;
+    hipError_t e = hipGetDevice(&dev);
+    if (e != hipSuccess) return fail_hip(e, "hipGetDevice");
+    if (dev < 0 || dev >= kMaxDevices) return fail(TM_EUNSUPPORTED, "device index %d out of range", dev);
+    std::lock_guard<std::mutex> lock(g_mutex);
+    DeviceState& d = g_dev[dev];
+    if (!d.checked) {
+        hipDeviceProp_t prop;
+        e = hipGetDeviceProperties(&prop, dev);
+        if (e != hipSuccess) return fail_hip(e, "hipGetDeviceProperties");
+        d.supported = strncmp(prop.gcnArchName, "gfx950", 6) == 0;
+        d.num_cu = prop.multiProcessorCount > 0 ? prop.multiProcessorCount : 256;
+        d.checked = true;
+    }
+    if (!d.supported) return fail(TM_EUNSUPPORTED, "device %d is not gfx950", dev);
+    *dev_out = dev;
+    return TM_OK;
+}
+
+int ensure_workspace(int dev)
+{
+    std::lock_guard<std::mutex> lock(g_mutex);
+    DeviceState& d = g_dev[dev];
+    if (d.workspace) return TM_OK;
+    void* ws = nullptr;
+    hipError_t e = hipMalloc(&ws, kWorkspaceBytes);
+    if (e != hipSuccess) return fail_hip(e, "hipMalloc(workspace)");
+    e = hipMemset(ws, 0, kCounterBytes);
+    if (e != hipSuccess) {
+        (void)hipFree(ws);
+        return fail_hip(e, "hipMemset(workspace)");
+    }
+    d.workspace = ws;
+    return TM_OK;
+}
+
+}  // namespace
+
+}  // namespace tmw4
+
+struct tm_packed_w4 {
+    uint32_t magic;
+    int K, N, group, device;
+    uint32_t* w;       // K*N/8 words
+    uint32_t* sz;      // (K/group)*N words
+    size_t w_bytes, sz_bytes;
+};
+
+namespace tmw4 {
+
+namespace {
+
+bool valid(const tm_packed_w4* p) { return p && p->magic == kMagic; }
+
+int ceil_div(int a, int b) { return (a + b - 1) / b; }
+
+// Kernel and split-K selection.  Split factors are bounded so that every wave of a skinny CTA has at least one
+// unit and the partial sums fit the workspace budget.
+Plan make_plan(const tm_packed_w4* h, int M, int num_cu)
+{
+    const int KU = h->K / kUnitK, NT = h->N / kUnitN;
+    Plan pl{};
+    int variant = g_force_variant;
+    if (variant < 0) {
+        if (M <= 16) variant = kSkinny16;
+        else if (M <= 32) variant = kSkinny32;
+        else if (M <= 64) variant = kSkinny64;
+        else {
+            long big_tiles = (long)ceil_div(M, 256) * ceil_div(h->N, 256);
+            variant = big_tiles >= 2L * num_cu ? kTile256 : kTile128;
+        }
+    }
+    if (variant <= kSkinny64) {                    // a forced skinny variant must still cover M
+        int cap = variant == kSkinny16 ? 16 : (variant == kSkinny32 ? 32 : 64);
+        if (M > cap) variant = M <= 32 ? kSkinny32 : (M <= 64 ? kSkinny64 : kTile128);
+    }
+    pl.variant = variant;
+    const size_t out_bytes = (size_t)M * h->N * sizeof(float);
+    int max_split_ws = (int)(kPartialBudget / (out_bytes ? out_bytes : 1));
+    if (max_split_ws < 1) max_split_ws = 1;
+    int split = 1;
+    if (variant <= kSkinny64) {
+        const int strips = ceil_div(NT, 4);
+        pl.tiles_m = 1;
+        pl.tiles_n = strips;
+        pl.block = 512;
+        // aim for about two resident CTAs per CU while keeping >= 1 unit per wave
+        int want = ceil_div(2 * num_cu, strips);
+        int max_by_k = KU / 8 > 0 ? KU / 8 : 1;
+        split = want < max_by_k ? want : max_by_k;
+    } else {
+        const int bm = variant == kTile256 ? 256 : 128;
+        pl.tiles_m = ceil_div(M, bm);
+        pl.tiles_n = ceil_div(h->N, bm);
+        pl.block = 256;
+        int tiles = pl.tiles_m * pl.tiles_n;
+        int want = (2 * num_cu) / tiles;           // fill the chip about twice over
+        int max_by_k = KU / 4 > 0 ? KU / 4 : 1;    // keep at least four units per CTA
+        split = want < max_by_k ? want : max_by_k;
+    }
+    if (g_force_split > 0) split = g_force_split;
+    if (split > KU) split = KU;
+    if (split > max_split_ws) split = max_split_ws;
+    if (split < 1) split = 1;
+    pl.ku_per_split = ceil_div(KU, split);
+    split = ceil_div(KU, pl.ku_per_split);         // drop empty splits
+    pl.split = split;
+    pl.grid = (unsigned)(pl.tiles_m * pl.tiles_n * split);
+    pl.ws_bytes = kCounterBytes + (split > 1 ? (size_t)split * out_bytes : 0);
+    return pl;
+}
+
+int run_gemm(const uint16_t* X, const tm_packed_w4* h, uint16_t* Y, int M, void* ws, size_t ws_bytes, bool own_ws,
+             hipStream_t stream)
+{
+    if (!valid(h)) return fail(TM_EINVAL, "packed handle is null or invalid");
+    if (M < 0 || M >= (1 << 24)) return fail(TM_EINVAL, "M = %d out of range", M);
+    if (M == 0) return TM_OK;
+    if (!X || !Y) return fail(TM_EINVAL, "X or Y is null");
+    if (((uintptr_t)X & 15) || ((uintptr_t)Y & 3)) return fail(TM_EINVAL, "X must be 16-byte and Y 4-byte aligned");
+    int dev;
+    int rc = check_device(&dev);
+    if (rc != TM_OK) return rc;
+    if (dev != h->device) return fail(TM_EINVAL, "handle belongs to device %d, current device is %d", h->device, dev);
+    Plan pl = make_plan(h, M, g_dev[dev].num_cu);
+    if (own_ws) {
+        ws = g_dev[dev].workspace;
+        ws_bytes = kWorkspaceBytes;
+        if (!ws) return fail(TM_EINVAL, "library workspace missing");
+    } else {
+        if (!ws) return fail(TM_EINVAL, "workspace is null");
+        if ((uintptr_t)ws & 255) return fail(TM_EINVAL, "workspace must be 256-byte aligned");
+    }
+    if (ws_bytes < pl.ws_bytes) return fail(TM_EINVAL, "workspace too small: %zu < %zu", ws_bytes, pl.ws_bytes);
+    if (pl.tiles_m * pl.tiles_n > kMaxCounters) return fail(TM_EINVAL, "too many output tiles for split-K");
+
+    GemmParams p{};
+    p.X = X;
+    p.W = (const u32x4*)h->w;
+    p.SZ = h->sz;
+    p.Y = Y;
+    p.counters = (uint32_t*)ws;
+    p.partial = (float*)((char*)ws + kCounterBytes);
+    p.M = M;
+    p.K = h->K;
+    p.N = h->N;
+    p.KU = h->K / kUnitK;
+    p.NT = h->N / kUnitN;
+    p.G = h->K / h->group;
+    p.split = pl.split;
+    p.ku_per_split = pl.ku_per_split;
+    p.tiles_m = pl.tiles_m;
+    p.tiles_n = pl.tiles_n;
+    hipError_t e = pl.variant <= kSkinny64 ? launch_skinny(p, pl, h->group, stream)
+                                           : launch_tile(p, pl, h->group, stream);
+    if (e != hipSuccess) return fail_hip(e, "kernel launch");
+    return TM_OK;
+}
+
+}  // namespace
+
+}  // namespace tmw4
+
+using namespace tmw4;
+
+extern "C" {
+
+tm_packed_w4* tm_pack_w4_on(const uint32_t* qweight, const uint16_t* scales, const uint16_t* zeros, int K, int N,
+                            int group, tm_stream stream)
+{
+    if (!qweight || !scales || !zeros) {
+        fail(TM_EINVAL, "qweight, scales or zeros is null");
+        return nullptr;
+    }
+    if (K <= 0 || N <= 0 || K % kUnitK || N % kUnitN) {
+        fail(TM_EINVAL, "need K %% 128 == 0 and N %% 16 == 0 (K = %d, N = %d)", K, N);
+        return nullptr;
+    }
+    if (group != 32 && group != 64 && group != 128) {
+        fail(TM_EINVAL, "group must be 32, 64 or 128 (got %d)", group);
+        return nullptr;
+    }
+    if ((double)K * (double)N >= 1099511627776.0) {
+        fail(TM_EINVAL, "K*N too large");
+        return nullptr;
+    }
+    if (((uintptr_t)qweight & 3) || ((uintptr_t)scales & 1) || ((uintptr_t)zeros & 1)) {
+        fail(TM_EINVAL, "misaligned input");
+        return nullptr;
+    }
+    int dev;
+    if (check_device(&dev) != TM_OK) return nullptr;
+    if (ensure_workspace(dev) != TM_OK) return nullptr;
+    tm_packed_w4* h = new (std::nothrow) tm_packed_w4();
+    if (!h) {
+        fail(TM_ENOMEM, "host allocation failed");
+        return nullptr;
+    }
+    h->magic = kMagic;
+    h->K = K;
+    h->N = N;
+    h->group = group;
+    h->device = dev;
+    h->w_bytes = (size_t)K * N / 2;
+    h->sz_bytes = (size_t)(K / group) * N * 4;
+    hipError_t e = hipMalloc((void**)&h->w, h->w_bytes);
+    if (e == hipSuccess) {
+        e = hipMalloc((void**)&h->sz, h->sz_bytes);
+        if (e != hipSuccess) (void)hipFree(h->w);
+    }
+    if (e != hipSuccess) {
+        fail_hip(e, "hipMalloc(packed)");
+        delete h;
+        return nullptr;
+    }
+    e = launch_repack(qweight, scales, zeros, h->w, h->sz, K, N, group, (hipStream_t)stream);
+    if (e != hipSuccess) {
+        fail_hip(e, "repack launch");
+        (void)hipFree(h->w);
+        (void)hipFree(h->sz);
+        delete h;
+        return nullptr;
+    }
+    return h;
+}
+
+tm_packed_w4* tm_pack_w4(const uint32_t* qweight, const uint16_t* scales, const uint16_t* zeros, int K, int N,
+                         int group)
+{
+    return tm_pack_w4_on(qweight, scales, zeros, K, N, group, nullptr);
+}
+
+int tm_gemm_w4a16(const uint16_t* X, const tm_packed_w4* packed, uint16_t* Y, int M, tm_stream stream)
+{
+    return run_gemm(X, packed, Y, M, nullptr, 0, true, (hipStream_t)stream);
+}
+
+int tm_gemm_w4a16_ws(const uint16_t* X, const tm_packed_w4* packed, uint16_t* Y, int M, void* workspace,
+                     size_t workspace_bytes, tm_stream stream)
+{
+    return run_gemm(X, packed, Y, M, workspace, workspace_bytes, false, (hipStream_t)stream);
+}
+
+size_t tm_gemm_workspace_bytes(const tm_packed_w4* packed, int M)
+{
+    if (!valid(packed) || M <= 0 || M >= (1 << 24)) {
+        if (!valid(packed)) fail(TM_EINVAL, "packed handle is null or invalid");
+        return 0;
+    }
+    int dev = packed->device;
+    int cu = (dev >= 0 && dev < kMaxDevices && g_dev[dev].checked) ? g_dev[dev].num_cu : 256;
+    return make_plan(packed, M, cu).ws_bytes;
+}
+
+void tm_free_packed(tm_packed_w4* packed)
+{
+    if (!valid(packed)) return;
+    packed->magic = 0;
+    (void)hipFree(packed->w);
+    (void)hipFree(packed->sz);
+    delete packed;
+}
+
+int tm_packed_info(const tm_packed_w4* packed, int* K, int* N, int* group, size_t* bytes)
+{
+    if (!valid(packed)) return fail(TM_EINVAL, "packed handle is null or invalid");
+    if (K) *K = packed->K;
+    if (N) *N = packed->N;
+    if (group) *group = packed->group;
+    if (bytes) *bytes = packed->w_bytes + packed->sz_bytes;
+    return TM_OK;
+}
+
+int tm_unpack_w4(const tm_packed_w4* packed, uint32_t* qweight_out, uint16_t* scales_out, uint16_t* zeros_out,
+                 tm_stream stream)
+{
+    if (!valid(packed)) return fail(TM_EINVAL, "packed handle is null or invalid");
+    hipError_t e = launch_unpack(packed->w, packed->sz, qweight_out, scales_out, zeros_out, packed->K, packed->N,
+                                 packed->group, (hipStream_t)stream);
+    if (e != hipSuccess) return fail_hip(e, "unpack launch");
+    return TM_OK;
+}
+
+int tm_packed_raw(const tm_packed_w4* packed, const void** weights, size_t* weight_bytes, const void** scale_zero,
+                  size_t* scale_zero_bytes)
+{
+    if (!valid(packed)) return fail(TM_EINVAL, "packed handle is null or invalid");
+    if (weights) *weights = packed->w;
+    if (weight_bytes) *weight_bytes = packed->w_bytes;
+    if (scale_zero) *scale_zero = packed->sz;
+    if (scale_zero_bytes) *scale_zero_bytes = packed->sz_bytes;
+    return TM_OK;
+}
+
+int tm_get_plan(const tm_packed_w4* packed, int M, int* variant, int* split_k, int* grid, int* block)
+{
+    if (!valid(packed)) return fail(TM_EINVAL, "packed handle is null or invalid");
+    if (M <= 0 || M >= (1 << 24)) return fail(TM_EINVAL, "M = %d out of range", M);
+    int dev = packed->device;
+    int cu = (dev >= 0 && dev < kMaxDevices && g_dev[dev].checked) ? g_dev[dev].num_cu : 256;
+    Plan pl = make_plan(packed, M, cu);
+    if (variant) *variant = pl.variant;
+    if (split_k) *split_k = pl.split;
+    if (grid) *grid = (int)pl.grid;
+    if (block) *block = (int)pl.block;
+    return TM_OK;
+}
+
+int tm_set_variant(int variant, int split_k)
+{
+    if (variant < -1 || variant >= kNumVariants) return fail(TM_EINVAL, "unknown variant %d", variant);
+    if (split_k < 0 || split_k > 256) return fail(TM_EINVAL, "split_k = %d out of range", split_k);
+    g_force_variant = variant;
+    g_force_split = split_k;
+    return TM_OK;
+}
+
+const char* tm_variant_name(int variant)
+{
+    switch (variant) {
+        case kSkinny16: return "skinny16";
+        case kSkinny32: return "skinny32";
+        case kSkinny64: return "skinny64";
+        case kTile128: return "tile128x128";
+        case kTile256: return "tile256x256";
+        default: return "";
+    }
+}
+
+int tm_bench_copy(void* dst, const void* src, size_t bytes, tm_stream stream)
+{
+    if (!dst || !src) return fail(TM_EINVAL, "null pointer");
+    if ((bytes & 15) || ((uintptr_t)dst & 15) || ((uintptr_t)src & 15)) return fail(TM_EINVAL, "need 16-byte multiples");
+    hipError_t e = launch_copy(dst, src, bytes, (hipStream_t)stream);
+    if (e != hipSuccess) return fail_hip(e, "copy launch");
+    return TM_OK;
+}
+
+int tm_bench_read(const void* src, size_t bytes, void* sink, tm_stream stream)
+{
+    if (!src || !sink) return fail(TM_EINVAL, "null pointer");
+    if ((bytes & 15) || ((uintptr_t)src & 15) || ((uintptr_t)sink & 3)) return fail(TM_EINVAL, "need 16-byte multiples");
+    hipError_t e = launch_read(src, bytes, sink, (hipStream_t)stream);
+    if (e != hipSuccess) return fail_hip(e, "read launch");
+    return TM_OK;
+}
+
+const char* tm_last_error(void) { return g_error; }
+
+const char* tm_version(void) { return "tm_w4 0.1 (gfx950)"; }
+
+}  // extern "C"

@@ -1,0 +1,92 @@
+// Device-side building blocks shared by the GEMM kernels: vector types, the packed-layout index helpers,
+// the int4 -> fp16 conversion and the gfx950 matrix-core wrapper.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace tmw4 {
+
+typedef _Float16 f16x2 __attribute__((ext_vector_type(2)));
+typedef _Float16 f16x8 __attribute__((ext_vector_type(8)));
+typedef float f32x4 __attribute__((ext_vector_type(4)));
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+
+constexpr int kUnitK = 128;       // rows of one packed unit
+constexpr int kUnitN = 16;        // columns of one packed unit
+constexpr int kUnitWords = 256;   // u32 words per unit (64 lanes x 4)
+constexpr int kMaxCounters = 16384;                       // split-K arrival counters at the head of a workspace
+constexpr size_t kCounterBytes = kMaxCounters * sizeof(uint32_t);
+
+// Problem description handed to every GEMM kernel.
+struct GemmParams {
+    const uint16_t* X;        // fp16 [M][K]
+    const u32x4* W;           // packed weights, one u32x4 per (unit, lane)
+    const uint32_t* SZ;       // packed scale|zero<<16 words
+    uint16_t* Y;              // fp16 [M][N]
+    float* partial;           // split-K partial sums [split][M][N] (fp32)
+    uint32_t* counters;       // split-K arrival counters, zero between launches
+    int M, K, N;
+    int KU;                   // K / 128
+    int NT;                   // N / 16
+    int G;                    // K / group
+    int split;                // split-K factor (>= 1)
+    int ku_per_split;         // k-units per split (ceil)
+    int tiles_m, tiles_n;     // tile kernel only
+};
+
+__device__ __forceinline__ f16x2 as_f16x2(uint32_t u) { return __builtin_bit_cast(f16x2, u); }
+
+// Per-(column, K-group) constants of the conversion: the scale in both halves, and the two exact offsets that
+// remove the conversion bias together with the zero-point.
+struct GroupConst {
+    f16x2 s2;        // (s, s)
+    f16x2 off1024;   // (-(1024 + z), -(1024 + z))
+    f16x2 off64;     // (-(64 + z), -(64 + z))
+};
+
+__device__ __forceinline__ GroupConst make_group_const(uint32_t sz)
+{
+    f16x2 p = as_f16x2(sz);
+    _Float16 s = p.x, z = p.y;
+    GroupConst g;
+    g.s2 = f16x2{s, s};
+    _Float16 a = (_Float16)(-1024.0f) - z;   // exact: 1024 + z <= 1039 is an fp16 integer
+    _Float16 b = (_Float16)(-64.0f) - z;
+    g.off1024 = f16x2{a, a};
+    g.off64 = f16x2{b, b};
+    return g;
+}
+
+// Integer-to-float by bit manipulation (paper Sec. 3.1 step (iii), Sec. 4.3 "I2F conversion and FMA").
+// A nibble q OR-ed into the mantissa of 0x6400 is the fp16 number 1024 + q; a nibble sitting four bits higher
+// OR-ed into 0x5400 is 64 + q.  Adding the matching offset gives q - z exactly; one multiply applies the scale
+// (a single rounding per weight).  The packed word stores weight e at nibble 4*(e&1) + (e>>1), so the four
+// masked words below are already the fp16 pairs (e0,e1), (e2,e3), (e4,e5), (e6,e7) of a matrix-core operand.
+__device__ __forceinline__ f16x8 dequant8(uint32_t w, const GroupConst& g)
+{
+    uint32_t a0 = (w & 0x000F000Fu) | 0x64006400u;
+    uint32_t a1 = (w & 0x00F000F0u) | 0x54005400u;
+    uint32_t w8 = w >> 8;
+    uint32_t a2 = (w8 & 0x000F000Fu) | 0x64006400u;
+    uint32_t a3 = (w8 & 0x00F000F0u) | 0x54005400u;
+    f16x2 r0 = (as_f16x2(a0) + g.off1024) * g.s2;
+    f16x2 r1 = (as_f16x2(a1) + g.off64) * g.s2;
+    f16x2 r2 = (as_f16x2(a2) + g.off1024) * g.s2;
+    f16x2 r3 = (as_f16x2(a3) + g.off64) * g.s2;
+    return f16x8{r0.x, r0.y, r1.x, r1.y, r2.x, r2.y, r3.x, r3.y};
+}
+
+// D = A(16x32) * B(32x16) + C on the matrix cores.  Lane l supplies row l%16 of A and column l%16 of B, each
+// with the eight k-values 8*(l/16) .. 8*(l/16)+7; it receives D[4*(l/16) + r][l%16] in c[r].
+__device__ __forceinline__ f32x4 mfma16x16x32(f16x8 a, f16x8 b, f32x4 c)
+{
+    return __builtin_amdgcn_mfma_f32_16x16x32_f16(a, b, c, 0, 0, 0);
+}
+
+__device__ __forceinline__ uint16_t f32_to_f16_bits(float v)
+{
+    _Float16 h = (_Float16)v;          // v_cvt_f16_f32, round-to-nearest-even
+    return __builtin_bit_cast(uint16_t, h);
+}
+
+}  // namespace tmw4

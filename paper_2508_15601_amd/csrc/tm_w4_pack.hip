@@ -1,0 +1,156 @@
+// Offline hardware-aware weight packing (paper Sec. 4.1) and its inverse, plus the two measurement kernels.
+//
+// On gfx950 the operand layout of the 16x16x32 fp16 matrix-core instruction is a closed-form index map, so the
+// paper's four steps (widen, pass through the fp16 fragment-load path, compress, store coalesced) collapse into a
+// gather: a 128 x 128 block of the interchange matrix is staged in LDS with coalesced row reads, and every thread
+// assembles complete 32-bit words of the fragment-ordered buffer, which are written as contiguous 1 KiB units.
+#include "tm_w4_device.h"
+#include "tm_w4_host.h"
+
+namespace tmw4 {
+
+__global__ __launch_bounds__(256) void repack_w4_kernel(const uint32_t* __restrict__ qweight,
+                                                        uint32_t* __restrict__ out, int K, int N)
+{
+    __shared__ uint32_t tile[128][17];             // 128 rows x 16 words (128 columns), padded
+    const int KU = K / kUnitK, NT = N / kUnitN, NW = N / 8;
+    const int ku = blockIdx.y;
+    const int nt0 = blockIdx.x * 8;
+    const int tid = threadIdx.x;
+    for (int i = 0; i < 8; ++i) {
+        int idx = i * 256 + tid;
+        int row = idx >> 4, wc = idx & 15;
+        int gw = nt0 * 2 + wc;
+        tile[row][wc] = gw < NW ? qweight[(size_t)(ku * kUnitK + row) * NW + gw] : 0u;
+    }
+    __syncthreads();
+    const int lane = tid >> 2, t = tid & 3;
+    const int c = lane & 15, h = lane >> 4;
+    for (int j = 0; j < 8; ++j) {
+        int nt = nt0 + j;
+        if (nt >= NT) break;
+        int col = 16 * j + c;
+        int wc = col >> 3, sh = 4 * (col & 7);
+        uint32_t w = 0;
+#pragma unroll
+        for (int e = 0; e < 8; ++e) {
+            uint32_t nib = (tile[32 * t + 8 * h + e][wc] >> sh) & 0xFu;
+            w |= nib << (4 * (4 * (e & 1) + (e >> 1)));
+        }
+        out[((size_t)nt * KU + ku) * kUnitWords + tid] = w;
+    }
+}
+
+__global__ __launch_bounds__(256) void repack_sz_kernel(const uint16_t* __restrict__ scales,
+                                                        const uint16_t* __restrict__ zeros,
+                                                        uint32_t* __restrict__ out, int G, int N)
+{
+    size_t idx = (size_t)blockIdx.x * 256 + threadIdx.x;
+    size_t total = (size_t)G * N;
+    if (idx >= total) return;
+    int c = idx & 15;
+    size_t r = idx >> 4;
+    int g = (int)(r % G);
+    int nt = (int)(r / G);
+    size_t src = (size_t)g * N + 16 * nt + c;
+    out[idx] = (uint32_t)scales[src] | ((uint32_t)zeros[src] << 16);
+}
+
+// Inverse permutation (test hook): one thread per interchange word (k, j).
+__global__ __launch_bounds__(256) void unpack_w4_kernel(const uint32_t* __restrict__ packed,
+                                                        uint32_t* __restrict__ qweight, int K, int N)
+{
+    const int KU = K / kUnitK, NW = N / 8;
+    size_t idx = (size_t)blockIdx.x * 256 + threadIdx.x;
+    if (idx >= (size_t)K * NW) return;
+    int k = (int)(idx / NW), j = (int)(idx % NW);
+    int ku = k >> 7, kk = k & 127;
+    int t = kk >> 5, h = (kk >> 3) & 3, e = kk & 7;
+    int p = 4 * (e & 1) + (e >> 1);
+    uint32_t w = 0;
+#pragma unroll
+    for (int i = 0; i < 8; ++i) {
+        int n = 8 * j + i;
+        int nt = n >> 4, c = n & 15;
+        uint32_t src = packed[((size_t)nt * KU + ku) * kUnitWords + 4 * (16 * h + c) + t];
+        w |= ((src >> (4 * p)) & 0xFu) << (4 * i);
+    }
+    qweight[idx] = w;
+}
+
+__global__ __launch_bounds__(256) void unpack_sz_kernel(const uint32_t* __restrict__ sz, uint16_t* __restrict__ scales,
+                                                        uint16_t* __restrict__ zeros, int G, int N)
+{
+    size_t idx = (size_t)blockIdx.x * 256 + threadIdx.x;
+    if (idx >= (size_t)G * N) return;
+    int g = (int)(idx / N), n = (int)(idx % N);
+    uint32_t w = sz[((size_t)(n >> 4) * G + g) * 16 + (n & 15)];
+    if (scales) scales[idx] = (uint16_t)(w & 0xFFFFu);
+    if (zeros) zeros[idx] = (uint16_t)(w >> 16);
+}
+
+__global__ __launch_bounds__(256) void copy16_kernel(u32x4* __restrict__ dst, const u32x4* __restrict__ src, size_t n16)
+{
+    size_t stride = (size_t)gridDim.x * 256;
+    for (size_t i = (size_t)blockIdx.x * 256 + threadIdx.x; i < n16; i += stride) dst[i] = src[i];
+}
+
+__global__ __launch_bounds__(256) void read16_kernel(const u32x4* __restrict__ src, size_t n16, uint32_t* sink)
+{
+    size_t stride = (size_t)gridDim.x * 256;
+    u32x4 acc = {0, 0, 0, 0};
+    for (size_t i = (size_t)blockIdx.x * 256 + threadIdx.x; i < n16; i += stride) acc ^= src[i];
+    uint32_t v = acc.x ^ acc.y ^ acc.z ^ acc.w;
+    if (v == 0x9E3779B9u) *sink = v;               // practically never taken; keeps the loads alive
+}
+
+// ------------------------------------------------------------------------------------------ host launchers
+
+hipError_t launch_repack(const uint32_t* qweight, const uint16_t* scales, const uint16_t* zeros, uint32_t* w_out,
+                         uint32_t* sz_out, int K, int N, int group, hipStream_t stream)
+{
+    const int KU = K / kUnitK, NT = N / kUnitN, G = K / group;
+    dim3 grid((NT + 7) / 8, KU);
+    hipLaunchKernelGGL(repack_w4_kernel, grid, dim3(256), 0, stream, qweight, w_out, K, N);
+    size_t total = (size_t)G * N;
+    hipLaunchKernelGGL(repack_sz_kernel, dim3((unsigned)((total + 255) / 256)), dim3(256), 0, stream, scales, zeros,
+                       sz_out, G, N);
+    return hipGetLastError();
+}
+
+hipError_t launch_unpack(const uint32_t* w, const uint32_t* sz, uint32_t* qweight_out, uint16_t* scales_out,
+                         uint16_t* zeros_out, int K, int N, int group, hipStream_t stream)
+{
+    const int G = K / group;
+    if (qweight_out) {
+        size_t total = (size_t)K * (N / 8);
+        hipLaunchKernelGGL(unpack_w4_kernel, dim3((unsigned)((total + 255) / 256)), dim3(256), 0, stream, w,
+                           qweight_out, K, N);
+    }
+    if (scales_out || zeros_out) {
+        size_t total = (size_t)G * N;
+        hipLaunchKernelGGL(unpack_sz_kernel, dim3((unsigned)((total + 255) / 256)), dim3(256), 0, stream, sz,
+                           scales_out, zeros_out, G, N);
+    }
+    return hipGetLastError();
+}
+
+hipError_t launch_copy(void* dst, const void* src, size_t bytes, hipStream_t stream)
+{
+    size_t n16 = bytes / 16;
+    unsigned blocks = (unsigned)((n16 + 255) / 256 < 8192 ? (n16 + 255) / 256 : 8192);
+    if (blocks == 0) return hipSuccess;
+    hipLaunchKernelGGL(copy16_kernel, dim3(blocks), dim3(256), 0, stream, (u32x4*)dst, (const u32x4*)src, n16);
+    return hipGetLastError();
+}
+
+hipError_t launch_read(const void* src, size_t bytes, void* sink, hipStream_t stream)
+{
+    size_t n16 = bytes / 16;
+    unsigned blocks = (unsigned)((n16 + 255) / 256 < 8192 ? (n16 + 255) / 256 : 8192);
+    if (blocks == 0) return hipSuccess;
+    hipLaunchKernelGGL(read16_kernel, dim3(blocks), dim3(256), 0, stream, (const u32x4*)src, n16, (uint32_t*)sink);
+    return hipGetLastError();
+}
+
+}  // namespace tmw4

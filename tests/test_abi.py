@@ -1,0 +1,72 @@
+"""CPU-only checks of the C ABI: the library loads, exports every symbol the header declares, and its argument
+validation returns error codes (never aborts).  No compute call is made."""
+import ctypes
+import os
+import re
+
+import pytest
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def _declared_symbols():
+    text = open(os.path.join(ROOT, "include", "tm_w4.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(tm_[a-z0-9_]+)\s*\(", text)))
+
+
+@pytest.fixture(scope="module")
+def lib():
+    import paper_2508_15601_amd as tm
+    if not os.path.exists(tm.lib_path()):
+        from paper_2508_15601_amd import build
+        build.build()
+    return tm.load_library()
+
+
+def test_header_symbols_are_exported(lib):
+    names = _declared_symbols()
+    assert "tm_pack_w4" in names and "tm_gemm_w4a16" in names and len(names) >= 15
+    for n in names:
+        assert hasattr(lib, n), f"{n} declared in include/tm_w4.h but not exported"
+
+
+def test_binding_uses_same_names():
+    import paper_2508_15601_amd as tm
+    for n in ("tm_pack_w4", "tm_gemm_w4a16", "tm_gemm_w4a16_ws", "tm_unpack_w4", "tm_packed_raw", "tm_get_plan",
+              "tm_set_variant", "tm_gemm_workspace_bytes", "tm_last_error", "tm_version"):
+        assert callable(getattr(tm, n))
+
+
+def test_argument_validation_without_gpu(lib):
+    import paper_2508_15601_amd as tm
+    assert lib.tm_pack_w4(None, None, None, 128, 16, 128) is None
+    assert "null" in tm.tm_last_error()
+    fake = ctypes.c_void_p(4096)
+    for (K, N, g) in [(100, 16, 128), (128, 24, 128), (128, 16, 48), (0, 16, 128), (128, -16, 128)]:
+        assert lib.tm_pack_w4(fake, fake, fake, K, N, g) is None
+        assert tm.tm_last_error()
+    assert lib.tm_pack_w4(ctypes.c_void_p(4097), fake, fake, 128, 16, 128) is None
+    assert "misaligned" in tm.tm_last_error()
+    assert lib.tm_gemm_w4a16(fake, None, fake, 1, None) == -1
+    assert lib.tm_gemm_workspace_bytes(None, 4) == 0
+    assert lib.tm_packed_info(None, None, None, None, None) == -1
+    assert lib.tm_unpack_w4(None, None, None, None, None) == -1
+    assert lib.tm_get_plan(None, 1, None, None, None, None) == -1
+    lib.tm_free_packed(None)                      # must be a no-op
+    assert lib.tm_set_variant(99, 0) == -1 and lib.tm_set_variant(-1, 0) == 0
+    assert lib.tm_variant_name(0) == b"skinny16" and lib.tm_variant_name(99) == b""
+    assert lib.tm_bench_copy(None, None, 16, None) == -1
+    assert tm.tm_version().startswith("tm_w4")
+
+
+def test_product_package_does_not_touch_the_oracle():
+    """The product path must not import, link or read anything under oracle/."""
+    pkg = os.path.join(ROOT, "paper_2508_15601_amd")
+    for dirpath, _, files in os.walk(pkg):
+        if "_build" in dirpath:
+            continue
+        for f in files:
+            if f.endswith((".py", ".hip", ".h", ".cpp")):
+                text = open(os.path.join(dirpath, f)).read()
+                assert "oracle" not in text.replace("no fallback", ""), f"{f} mentions the oracle"

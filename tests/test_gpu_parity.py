@@ -1,0 +1,265 @@
+"""GPU parity tests: the HIP path, called through the C ABI, against the CPU oracle on the same seeded inputs.
+
+Packing is compared bit for bit; GEMM outputs element by element under the acceptance rule
+|Y - Yref| <= 1e-2 + 5e-3*|Yref| and relative Frobenius error <= 2e-3 (helpers.acceptance)."""
+import sys
+
+import numpy as np
+import pytest
+
+from workloads import w4a16 as wl
+from helpers import acceptance
+import gpu_util as gu
+
+pytestmark = pytest.mark.gpu
+
+
+def _say(msg):
+    print(msg, flush=True)
+    sys.stdout.flush()
+
+
+@pytest.fixture(scope="module")
+def tm():
+    import torch
+    import paper_2508_15601_amd as tm
+    assert torch.cuda.is_available(), "GPU tests need a device"
+    tm.load_library()                       # fails loudly if the HIP library was not built
+    yield tm
+    tm.tm_set_variant(-1, 0)
+
+
+def _random_problem(seed, M, K, N, g):
+    case = wl.Case(f"rand_{M}x{K}x{N}g{g}", M, K, N, g, seed=seed)
+    return wl.make(case)
+
+
+# ------------------------------------------------------------------ packing: bit-exact
+
+PACK_SHAPES = [(128, 16, 128), (384, 80, 64), (256, 48, 32), (512, 512, 128), (1152, 272, 128),
+               (4096, 4096, 128), (8192, 8192, 64)]
+
+
+@pytest.mark.parametrize("K,N,g", PACK_SHAPES)
+def test_pack_bit_exact_against_oracle_unpack(tm, oracle, K, N, g):
+    _say(f"pack K={K} N={N} g={g}")
+    rng = np.random.default_rng(K * 7 + N)
+    q = rng.integers(0, 16, (K, N), dtype=np.uint8)
+    # position codes in a second pass so that every nibble slot is distinguished
+    kk, nn = np.meshgrid(np.arange(K), np.arange(N), indexing="ij")
+    for qq in (q, ((kk * 5 + nn * 3 + (kk >> 3) + (nn >> 4)) & 15).astype(np.uint8)):
+        s = rng.uniform(0.001, 0.02, (K // g, N)).astype(np.float16)
+        z = rng.integers(0, 16, (K // g, N)).astype(np.float16)
+        d = {"q": qq, "s": s, "z": z, "qweight": wl.pack_interchange(qq)}
+        packed = gu.pack(d, g)
+        wbuf, szbuf = tm.tm_packed_raw(packed)
+        q2, s2, z2 = oracle.unpack_packed(wbuf, szbuf, K, N, g)
+        assert np.array_equal(q2, qq)
+        assert np.array_equal(s2.view(np.uint16), s.view(np.uint16))
+        assert np.array_equal(z2.view(np.uint16), z.view(np.uint16))
+        # device-side inverse permutation returns the interchange words
+        qw, sd, zd = tm.tm_unpack_w4(packed)
+        assert np.array_equal(qw.cpu().numpy().view(np.uint32), d["qweight"])
+        assert np.array_equal(sd.cpu().numpy().view(np.uint16), s.view(np.uint16))
+        assert np.array_equal(zd.cpu().numpy().view(np.uint16), z.view(np.uint16))
+        packed.close()
+
+
+# ------------------------------------------------------------------ GEMM: exact special cases
+
+@pytest.mark.parametrize("variant", [-1, 3, 4])
+def test_one_hot_rows_return_dequantised_weights_bit_exactly(tm, oracle, variant):
+    """X = one-hot rows: a single non-zero product per output, so the fp16-dequantised weight must come back
+    exactly; pins layout, nibble order, group indexing and the conversion constants on the device."""
+    K, N, g = 384, 80, 64
+    d = _random_problem(5, 1, K, N, g)
+    packed = gu.pack(d, g)
+    tm.tm_set_variant(variant, 0)
+    for k0 in range(0, K, 48):
+        rows = list(range(k0, k0 + 48))
+        X = np.zeros((len(rows), K), np.float16)
+        X[np.arange(len(rows)), rows] = 1.0
+        _say(f"one-hot variant={variant} k0={k0}")
+        Y = gu.gemm(packed, X)
+        Yref = oracle.gemm(X, d["q"], d["s"], d["z"], g)
+        assert np.array_equal(Y.view(np.uint16), Yref.view(np.uint16))
+    tm.tm_set_variant(-1, 0)
+
+
+@pytest.mark.parametrize("M,variant,split", [(4, -1, 0), (4, 0, 3), (40, -1, 0), (100, 3, 0), (100, 3, 2), (100, 4, 1)])
+def test_integer_exact_case(tm, oracle, M, variant, split):
+    """s = 1 and small integer activations: every partial sum is an exactly representable integer, so any
+    summation order gives the oracle's bits."""
+    rng = np.random.default_rng(M)
+    K, N, g = 384, 112, 128
+    q = rng.integers(0, 16, (K, N), dtype=np.uint8)
+    z = rng.integers(0, 16, (K // g, N)).astype(np.float16)
+    s = np.ones((K // g, N), np.float16)
+    X = (rng.integers(-1, 2, (M, K)) * (rng.random((M, K)) < 0.25)).astype(np.float16)
+    d = {"q": q, "s": s, "z": z, "qweight": wl.pack_interchange(q)}
+    packed = gu.pack(d, g)
+    tm.tm_set_variant(variant, split)
+    _say(f"integer-exact M={M} variant={variant} split={split} plan={tm.tm_get_plan(packed, M)}")
+    Y = gu.gemm(packed, X)
+    tm.tm_set_variant(-1, 0)
+    Yref = oracle.gemm(X, q, s, z, g)
+    assert np.abs(Yref.astype(np.float64)).max() < 2048
+    assert np.array_equal(Y.view(np.uint16), Yref.view(np.uint16))
+
+
+# ------------------------------------------------------------------ GEMM: tolerance parity on ragged small shapes
+
+SMALL = [
+    # M, K, N, group           several tiles in every dimension plus ragged tails
+    (1, 128, 16, 128), (3, 384, 80, 64), (16, 1152, 272, 128), (17, 384, 528, 32), (33, 1152, 80, 128),
+    (64, 640, 272, 64), (65, 384, 272, 128), (130, 1152, 528, 64), (300, 640, 400, 128), (257, 384, 272, 32),
+]
+
+
+@pytest.mark.parametrize("M,K,N,g", SMALL)
+def test_small_shapes_auto_plan(tm, oracle, M, K, N, g):
+    d = _random_problem(M + K + N, M, K, N, g)
+    packed = gu.pack(d, g)
+    _say(f"small auto M={M} K={K} N={N} g={g} plan={tm.tm_get_plan(packed, M)}")
+    Y = gu.gemm(packed, d["X"])
+    Yref = oracle.gemm(d["X"], d["q"], d["s"], d["z"], g)
+    ok, worst, fro = acceptance(Y, Yref)
+    assert ok, (worst, fro)
+
+
+@pytest.mark.parametrize("variant,split", [(0, 1), (0, 2), (0, 5), (1, 1), (1, 3), (2, 1), (2, 2), (3, 1), (3, 3),
+                                           (4, 1), (4, 2)])
+@pytest.mark.parametrize("g", [32, 64, 128])
+def test_every_variant_and_split(tm, oracle, variant, split, g):
+    M = {0: 13, 1: 29, 2: 50}.get(variant, 150)
+    K, N = 1152, 336
+    d = _random_problem(variant * 10 + split, M, K, N, g)
+    packed = gu.pack(d, g)
+    tm.tm_set_variant(variant, split)
+    plan = tm.tm_get_plan(packed, M)
+    _say(f"variant={variant} split={split} g={g} plan={plan}")
+    assert plan["variant"] == variant
+    Y = gu.gemm(packed, d["X"])
+    Y2 = gu.gemm(packed, d["X"])
+    tm.tm_set_variant(-1, 0)
+    Yref = oracle.gemm(d["X"], d["q"], d["s"], d["z"], g)
+    ok, worst, fro = acceptance(Y, Yref)
+    assert ok, (worst, fro)
+    assert np.array_equal(Y.view(np.uint16), Y2.view(np.uint16)), "split-K reduction must be run-to-run deterministic"
+
+
+def test_caller_workspace_entry_point(tm, oracle):
+    import torch
+    M, K, N, g = 20, 1152, 336, 128
+    d = _random_problem(77, M, K, N, g)
+    packed = gu.pack(d, g)
+    tm.tm_set_variant(1, 3)
+    need = tm.tm_gemm_workspace_bytes(packed, M)
+    ws = torch.zeros(need + 256, dtype=torch.uint8, device="cuda")
+    off = (-ws.data_ptr()) % 256
+    ws = ws[off:off + need]
+    Xd = gu.to_dev(d["X"])
+    Y = torch.empty((M, N), dtype=torch.float16, device="cuda")
+    for _ in range(2):                       # second call checks the workspace was left ready
+        Y.fill_(float("nan"))
+        tm.tm_gemm_w4a16_ws(Xd, packed, Y, ws)
+        torch.cuda.synchronize()
+        ok, worst, fro = acceptance(Y.cpu().numpy(), oracle.gemm(d["X"], d["q"], d["s"], d["z"], g))
+        assert ok, (worst, fro)
+    with pytest.raises(tm.TmError):
+        tm.tm_gemm_w4a16_ws(Xd, packed, Y, ws[:256])
+    tm.tm_set_variant(-1, 0)
+
+
+def test_edge_cases(tm, oracle):
+    import torch
+    d = _random_problem(3, 2, 128, 16, 128)
+    packed = gu.pack(d, 128)
+    # M = 0 is a no-op
+    X0 = torch.empty((0, 128), dtype=torch.float16, device="cuda")
+    Y0 = torch.empty((0, 16), dtype=torch.float16, device="cuda")
+    tm.tm_gemm_w4a16(X0, packed, Y0)
+    # misaligned X is rejected, not launched
+    buf = torch.zeros(2 * 128 + 8, dtype=torch.float16, device="cuda")
+    Xmis = buf[1:1 + 256].view(2, 128)
+    with pytest.raises(tm.TmError):
+        tm.tm_gemm_w4a16(Xmis, packed, torch.empty((2, 16), dtype=torch.float16, device="cuda"))
+    # extreme codes and zero-points: q in {0, 15}, z in {0, 15}
+    K, N, g = 256, 32, 64
+    rng = np.random.default_rng(0)
+    q = (rng.integers(0, 2, (K, N)) * 15).astype(np.uint8)
+    z = (rng.integers(0, 2, (K // g, N)) * 15).astype(np.float16)
+    s = rng.uniform(0.001, 0.02, (K // g, N)).astype(np.float16)
+    X = rng.standard_normal((5, K)).astype(np.float16)
+    dd = {"q": q, "s": s, "z": z, "qweight": wl.pack_interchange(q)}
+    p2 = gu.pack(dd, g)
+    ok, worst, fro = acceptance(gu.gemm(p2, X), oracle.gemm(X, q, s, z, g))
+    assert ok, (worst, fro)
+
+
+# ------------------------------------------------------------------ GEMM: the benchmark configurations
+
+def _check_case(tm, oracle, case, d=None, packed=None, full_limit=2.5e10):
+    d = d or wl.make(case)
+    own = packed is None
+    packed = packed or gu.pack(d, case.group)
+    X = d["X"][:case.M]
+    plan = tm.tm_get_plan(packed, case.M)
+    _say(f"{case.name}: M={case.M} K={case.K} N={case.N} g={case.group} plan={plan}")
+    Y = gu.gemm(packed, X)
+    assert not np.isnan(Y).any()
+    work = float(case.M) * case.K * case.N
+    if work <= full_limit:
+        Yref = oracle.gemm(X, d["q"], d["s"], d["z"], case.group)
+        ok, worst, fro = acceptance(Y, Yref)
+        assert ok, (case.name, worst, fro)
+    else:
+        # sampled outputs: a few complete rows spread over the M tiles, and complete columns spread over N tiles
+        rng = np.random.default_rng(1)
+        rows = np.unique(np.concatenate([[0, case.M - 1], rng.integers(0, case.M, 6)]))
+        Yref_rows = oracle.gemm(X[rows], d["q"], d["s"], d["z"], case.group)
+        ok, worst, fro = acceptance(Y[rows], Yref_rows)
+        assert ok, (case.name, "rows", worst, fro)
+        cols = np.unique(np.concatenate([[0, case.N - 1], rng.integers(0, case.N, 6)]))
+        ms = np.repeat(np.arange(case.M), cols.size)
+        ns = np.tile(cols, case.M)
+        Yref_cols = oracle.gemm_sampled(X, d["q"], d["s"], d["z"], case.group, ms, ns)
+        ok, worst, fro = acceptance(Y[ms, ns], Yref_cols)
+        assert ok, (case.name, "cols", worst, fro)
+    if own:
+        packed.close()
+    return d
+
+
+def test_config1_tiny(tm, oracle):
+    _check_case(tm, oracle, wl.case_by_name("cfg1_tiny_M1"))
+
+
+@pytest.mark.parametrize("layer,Ms", [("cfg2_attn_out", (1, 4, 8, 16)), ("cfg2_qkv", (1, 4, 8, 16)),
+                                      ("cfg3_gate_up", (1, 16, 32, 64)), ("cfg3_down", (1, 16, 32, 64))])
+def test_config2_3_decode_layers(tm, oracle, layer, Ms):
+    big = wl.case_by_name(f"{layer}_M{max(Ms)}")
+    d = wl.make(big)                           # one weight matrix per layer; X rows are shared by the smaller M
+    packed = gu.pack(d, big.group)
+    for M in Ms:
+        case = wl.Case(f"{layer}_M{M}", M, big.K, big.N, big.group, big.sigma, big.outlier_frac, big.seed)
+        _check_case(tm, oracle, case, d=d, packed=packed)
+    packed.close()
+
+
+def test_config5_dispatch_sweep(tm, oracle):
+    big = wl.case_by_name("cfg5_sweep_M1024")
+    d = wl.make(big)
+    packed = gu.pack(d, big.group)
+    seen = set()
+    for M in (1, 2, 4, 8, 32, 128, 256, 1024):
+        case = wl.Case(f"cfg5_sweep_M{M}", M, big.K, big.N, big.group, big.sigma, big.outlier_frac, big.seed)
+        _check_case(tm, oracle, case, d=d, packed=packed, full_limit=1e10)
+        seen.add(tm.tm_get_plan(packed, M)["variant"])
+    assert len(seen) >= 3, "the dispatch should switch kernel variants across the M sweep"
+    packed.close()
+
+
+def test_config4_prefill_sampled(tm, oracle):
+    case = wl.case_by_name("cfg4_prefill_70b_mlp")
+    _check_case(tm, oracle, case)
