@@ -80,27 +80,58 @@ class Layer:
         tm.tm_gemm_w4a16(self.X[M][i % 4], self.packed[i % self.copies], self.Y[M][i % 4])
 
 
-def time_steps(torch, step_fn, steps, warmup):
+def time_steps(torch, step_fn, steps, warmup, graph_steps=0):
+    """Times exactly `steps` calls of step_fn between two events on the launch stream.
+
+    graph_steps > 0: the steps are captured `graph_steps` at a time into a HIP graph and the graph is replayed
+    steps / graph_steps times, which removes the host's per-launch cost (a decode kernel runs for a few microseconds,
+    less than one eager launch costs the host) exactly as a serving loop would.  graph_steps must divide steps."""
     for _ in range(warmup):
         step_fn()
     torch.cuda.synchronize()
     e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-    t0 = time.perf_counter()
-    e0.record()
-    for _ in range(steps):
-        step_fn()
-    e1.record()
-    torch.cuda.synchronize()
-    wall_ms = (time.perf_counter() - t0) * 1e3
-    return e0.elapsed_time(e1), wall_ms
+    if graph_steps <= 0:
+        t0 = time.perf_counter()
+        e0.record()
+        for _ in range(steps):
+            step_fn()
+        e1.record()
+        torch.cuda.synchronize()
+        return e0.elapsed_time(e1), (time.perf_counter() - t0) * 1e3
+    assert steps % graph_steps == 0
+    stream = torch.cuda.Stream()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.stream(stream):
+        with torch.cuda.graph(graph, stream=stream):
+            for _ in range(graph_steps):
+                step_fn()
+        graph.replay()                       # one untimed replay: graph upload, caches in steady state
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        e0.record()
+        for _ in range(steps // graph_steps):
+            graph.replay()
+        e1.record()
+        torch.cuda.synchronize()
+    return e0.elapsed_time(e1), (time.perf_counter() - t0) * 1e3
 
 
-def per_shape_table(tm, torch, wl, layers, iters=100, warmup=10):
+def pick_graph_steps(steps, want):
+    """largest divisor of `steps` that is <= want (>= 1)"""
+    best = 1
+    for g in range(1, min(steps, want) + 1):
+        if steps % g == 0:
+            best = g
+    return best
+
+
+def per_shape_table(tm, torch, wl, layers, iters=100, warmup=10, use_graph=True):
     rows = []
     for L in layers:
         c = L.case
         for M in L.Ms:
-            ev_ms, _ = time_steps(torch, lambda: L.launch(tm, M), iters, warmup)
+            ev_ms, _ = time_steps(torch, lambda: L.launch(tm, M), iters, warmup,
+                                  graph_steps=iters if use_graph else 0)
             t = ev_ms / iters * 1e-3
             B = wl.algorithmic_bytes(M, c.K, c.N, c.group)
             F = wl.flops(M, c.K, c.N)
@@ -112,31 +143,34 @@ def per_shape_table(tm, torch, wl, layers, iters=100, warmup=10):
     return rows
 
 
-def cpu_baseline(wl, layers, budget_s=25.0):
-    """The oracle as it stands, timed on this host's cores over the same workload (bounded by a time budget)."""
+def cpu_baseline(wl, layers, min_s=5.0, budget_s=25.0):
+    """The oracle as it stands, timed on this host's cores over the same workload: whole passes over every
+    (layer, M) pair are repeated until at least `min_s` seconds have been spent; a single GEMM too large for
+    `budget_s` is cut to its first rows (and the sample string says so)."""
     from oracle import oracle_w4
-    total_bytes = 0
-    total_flops = 0
+    threads = max(1, oracle_w4.num_threads())
+    total_bytes = total_flops = 0
     total_s = 0.0
+    passes = 0
     done = []
-    for L in layers:
-        c, d = L.case, L.data
-        for M in L.Ms:
-            if total_s > budget_s:
-                break
-            rows = M
-            est_rate = 1.5e9 * max(1, oracle_w4.num_threads())       # generous MAC/s guess to bound one call
-            if rows * c.K * c.N / est_rate > budget_s:
-                rows = max(1, int(budget_s * est_rate / (c.K * c.N)))
-            t0 = time.perf_counter()
-            oracle_w4.gemm(d["X"][:rows], d["q"], d["s"], d["z"], c.group)
-            dt = time.perf_counter() - t0
-            total_s += dt
-            total_bytes += wl.algorithmic_bytes(rows, c.K, c.N, c.group)
-            total_flops += wl.flops(rows, c.K, c.N)
-            done.append(f"{c.name.rsplit('_M', 1)[0]}:M={rows}" + ("" if rows == M else f"(of {M})"))
-    return {"seconds": total_s, "bytes": total_bytes, "flops": total_flops, "cores": oracle_w4.num_threads(),
-            "sample": "oracle.gemm (fp64, scalar C, OpenMP) over " + ", ".join(done)}
+    while total_s < min_s and passes < 1000:
+        for L in layers:
+            c, d = L.case, L.data
+            for M in L.Ms:
+                rows = M
+                est_rate = 1.0e9 * threads                               # MAC/s guess, only to bound one call
+                if rows * c.K * c.N / est_rate > budget_s:
+                    rows = max(1, int(budget_s * est_rate / (c.K * c.N)))
+                t0 = time.perf_counter()
+                oracle_w4.gemm(d["X"][:rows], d["q"], d["s"], d["z"], c.group)
+                total_s += time.perf_counter() - t0
+                total_bytes += wl.algorithmic_bytes(rows, c.K, c.N, c.group)
+                total_flops += wl.flops(rows, c.K, c.N)
+                if passes == 0:
+                    done.append(f"{c.name.rsplit('_M', 1)[0]}:M={rows}" + ("" if rows == M else f"(of {M})"))
+        passes += 1
+    return {"seconds": total_s, "bytes": total_bytes, "flops": total_flops, "cores": threads,
+            "sample": f"{passes} pass(es) of oracle.gemm (fp64, scalar C, OpenMP) over " + ", ".join(done)}
 
 
 def main():
@@ -148,6 +182,7 @@ def main():
     ap.add_argument("--sweep-out", default=None, help="with --workload sweep: write the per-shape table here (JSON)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-prefill", action="store_true", help="skip the prefill companion measurement")
+    ap.add_argument("--eager", action="store_true", help="launch every kernel from the host instead of replaying HIP graphs")
     ap.add_argument("--variant", type=int, default=-1)
     ap.add_argument("--split-k", type=int, default=0)
     args = ap.parse_args()
@@ -167,7 +202,8 @@ def main():
         table = []
         for name in ("decode", "mlp_decode", "sweep5", "prefill"):
             layers = [Layer(tm, torch, wl, cn, Ms) for cn, Ms in WORKLOADS[name]]
-            rows = per_shape_table(tm, torch, wl, layers, iters=(10 if name == "prefill" else 100))
+            rows = per_shape_table(tm, torch, wl, layers, iters=(10 if name == "prefill" else 100),
+                                   use_graph=not args.eager)
             for r in rows:
                 r["workload"] = name
                 log(f"{r['layer']:16s} M={r['M']:5d} K={r['K']:6d} N={r['N']:6d} g={r['group']:3d} {r['us']:9.2f} us "
@@ -193,7 +229,10 @@ def main():
             for M in L.Ms:
                 L.launch(tm, M)
 
-    ev_ms, wall_ms = time_steps(torch, step, args.steps, args.warmup)
+    # graph long enough that every layer walks through all of its packed copies at least once per replay
+    want = max(-(-L.copies // len(L.Ms)) for L in layers)
+    graph_steps = 0 if args.eager else pick_graph_steps(args.steps, max(want, 1))
+    ev_ms, wall_ms = time_steps(torch, step, args.steps, args.warmup, graph_steps=graph_steps)
     ms_per_step = ev_ms / args.steps
     B = sum(wl.algorithmic_bytes(M, L.case.K, L.case.N, L.case.group) for L in layers for M in L.Ms)
     F = sum(wl.flops(M, L.case.K, L.case.N) for L in layers for M in L.Ms)
@@ -223,7 +262,8 @@ def main():
                                 "mlp_decode": "configs[2]: K=4096,N=22016 and K=11008,N=4096, group=128, M in {1,16,32,64}",
                                 "prefill": "configs[3]: M=4096, K=8192, N=28672, group=128",
                                 "sweep5": "configs[4]: K=8192, N=8192, group=64, M in {1,2,4,8,32,128,256,1024}"}[args.workload],
-                   "launches_per_step": launches_per_step, "weight_copies_rotated": [L.copies for L in layers]},
+                   "launches_per_step": launches_per_step, "weight_copies_rotated": [L.copies for L in layers],
+                   "launch_mode": "eager" if args.eager else f"hip_graph({graph_steps} steps per replay)"},
         "tflops": tflops, "effective_GBps": gbps, "host_wall_ms_per_step": wall_ms / args.steps,
         "pack_ms_per_matrix": {f"{L.case.K}x{L.case.N}": L.pack_ms for L in layers},
         "roofline": roofline,

@@ -118,6 +118,8 @@ TM_API int tm_packed_raw(const tm_packed_w4* packed, const void** weights, size_
  */
 TM_API int tm_get_plan(const tm_packed_w4* packed, int M, int* variant, int* split_k, int* grid, int* block);
 TM_API int tm_set_variant(int variant, int split_k);
+/* Waves per CTA of the skinny (M <= 32) kernels, which split K inside the CTA: 8, 16, or 0 for automatic. */
+TM_API int tm_set_waves(int waves);
 TM_API const char* tm_variant_name(int variant);
 
 /*

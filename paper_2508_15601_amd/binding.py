@@ -29,6 +29,9 @@ def load_library():
     global _lib
     if _lib is not None:
         return _lib
+    # PyTorch-ROCm ships its own HIP runtime (same soname as the system one).  Import torch first so that the
+    # library binds to the runtime torch's allocator and streams live in; two runtimes in one process see no device.
+    import torch  # noqa: F401
     if not os.path.exists(_LIB_PATH):
         raise ImportError(f"{_LIB_PATH} is missing: run `python -c 'import __graft_entry__ as g; g.build()'` first")
     lib = ctypes.CDLL(_LIB_PATH)
@@ -56,6 +59,8 @@ def load_library():
     lib.tm_get_plan.argtypes = [vp, i, c.POINTER(i), c.POINTER(i), c.POINTER(i), c.POINTER(i)]
     lib.tm_set_variant.restype = i
     lib.tm_set_variant.argtypes = [i, i]
+    lib.tm_set_waves.restype = i
+    lib.tm_set_waves.argtypes = [i]
     lib.tm_variant_name.restype = c.c_char_p
     lib.tm_variant_name.argtypes = [i]
     lib.tm_bench_copy.restype = i
@@ -211,6 +216,10 @@ def tm_get_plan(packed: PackedW4, M: int) -> dict:
 
 def tm_set_variant(variant: int = -1, split_k: int = 0):
     _check(load_library().tm_set_variant(variant, split_k))
+
+
+def tm_set_waves(waves: int = 0):
+    _check(load_library().tm_set_waves(waves))
 
 
 def tm_variant_name(variant: int) -> str:

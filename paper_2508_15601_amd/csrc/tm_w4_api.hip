@@ -44,6 +44,7 @@ DeviceState g_dev[kMaxDevices];
 std::mutex g_mutex;
 int g_force_variant = -1;
 int g_force_split = 0;
+int g_force_waves = 0;
 
 // Current device must be gfx950; result cached per device.
 int check_device(int* dev_out)
@@ -104,44 +105,53 @@ bool valid(const tm_packed_w4* p) { return p && p->magic == kMagic; }
 
 int ceil_div(int a, int b) { return (a + b - 1) / b; }
 
-// Kernel and split-K selection.  Split factors are bounded so that every wave of a skinny CTA has at least one
-// unit and the partial sums fit the workspace budget.
+// Kernel and split-K selection.
+//  - M <= 32: the skinny kernels.  The strip width (16/32/64 columns per wave) is the widest that still yields at
+//    least one CTA per CU, because wider strips reuse each activation fragment for more weights; K is split inside
+//    the CTA (8 or 16 waves), and across CTAs only when the strips alone cannot fill the chip.
+//  - larger M: CTA tiles; the tile grows with M, and K is split across CTAs while the tiles are too few.
+// Split factors are bounded so that every wave keeps at least one unit and the partial sums fit the workspace.
 Plan make_plan(const tm_packed_w4* h, int M, int num_cu)
 {
     const int KU = h->K / kUnitK, NT = h->N / kUnitN;
     Plan pl{};
     int variant = g_force_variant;
     if (variant < 0) {
-        if (M <= 16) variant = kSkinny16;
-        else if (M <= 32) variant = kSkinny32;
-        else if (M <= 64) variant = kSkinny64;
-        else {
+        if (M <= 32) {
+            const bool rows16 = M <= 16;
+            if (NT / 4 >= num_cu) variant = rows16 ? kSkinny16x64 : kSkinny32x64;
+            else if (NT / 2 >= num_cu || !rows16) variant = rows16 ? kSkinny16x32 : kSkinny32x32;
+            else variant = kSkinny16x16;
+        } else if (M <= 64) {
+            variant = kTile64x256;
+        } else {
             long big_tiles = (long)ceil_div(M, 256) * ceil_div(h->N, 256);
-            variant = big_tiles >= 2L * num_cu ? kTile256 : kTile128;
+            variant = big_tiles >= 2L * num_cu ? kTile256x256 : kTile128x128;
         }
     }
-    if (variant <= kSkinny64) {                    // a forced skinny variant must still cover M
-        int cap = variant == kSkinny16 ? 16 : (variant == kSkinny32 ? 32 : 64);
-        if (M > cap) variant = M <= 32 ? kSkinny32 : (M <= 64 ? kSkinny64 : kTile128);
-    }
+    if (is_skinny(variant) && M > skinny_rows(variant))        // a forced skinny variant must still cover M
+        variant = M <= 32 ? kSkinny32x64 : kTile64x256;
     pl.variant = variant;
     const size_t out_bytes = (size_t)M * h->N * sizeof(float);
     int max_split_ws = (int)(kPartialBudget / (out_bytes ? out_bytes : 1));
     if (max_split_ws < 1) max_split_ws = 1;
     int split = 1;
-    if (variant <= kSkinny64) {
-        const int strips = ceil_div(NT, 4);
+    if (is_skinny(variant)) {
+        const int ntw = skinny_ntw(variant);
+        const int strips = ceil_div(NT, ntw);
+        int waves = g_force_waves > 0 ? g_force_waves : (KU >= 32 ? 16 : 8);
+        if (waves < 2 * ntw) waves = 2 * ntw;      // the LDS reduction needs 128*ntw threads
         pl.tiles_m = 1;
         pl.tiles_n = strips;
-        pl.block = 512;
-        // aim for about two resident CTAs per CU while keeping >= 1 unit per wave
-        int want = ceil_div(2 * num_cu, strips);
-        int max_by_k = KU / 8 > 0 ? KU / 8 : 1;
-        split = want < max_by_k ? want : max_by_k;
+        pl.block = (unsigned)waves * 64;
+        if (strips * 2 <= num_cu) {                // too few strips: split K across CTAs as well
+            int want = ceil_div(num_cu, strips);
+            int max_by_k = KU / waves > 0 ? KU / waves : 1;
+            split = want < max_by_k ? want : max_by_k;
+        }
     } else {
-        const int bm = variant == kTile256 ? 256 : 128;
-        pl.tiles_m = ceil_div(M, bm);
-        pl.tiles_n = ceil_div(h->N, bm);
+        pl.tiles_m = ceil_div(M, tile_bm(variant));
+        pl.tiles_n = ceil_div(h->N, tile_bn(variant));
         pl.block = 256;
         int tiles = pl.tiles_m * pl.tiles_n;
         int want = (2 * num_cu) / tiles;           // fill the chip about twice over
@@ -155,7 +165,12 @@ Plan make_plan(const tm_packed_w4* h, int M, int num_cu)
     pl.ku_per_split = ceil_div(KU, split);
     split = ceil_div(KU, pl.ku_per_split);         // drop empty splits
     pl.split = split;
-    pl.grid = (unsigned)(pl.tiles_m * pl.tiles_n * split);
+    if (is_skinny(variant)) {
+        pl.grid = (unsigned)(pl.tiles_n * split);
+    } else {
+        int chunk = ceil_div(pl.tiles_m * pl.tiles_n, 8);      // tiles are dealt to the 8 XCDs in equal chunks
+        pl.grid = (unsigned)(chunk * 8 * split);
+    }
     pl.ws_bytes = kCounterBytes + (split > 1 ? (size_t)split * out_bytes : 0);
     return pl;
 }
@@ -201,8 +216,8 @@ int run_gemm(const uint16_t* X, const tm_packed_w4* h, uint16_t* Y, int M, void*
     p.ku_per_split = pl.ku_per_split;
     p.tiles_m = pl.tiles_m;
     p.tiles_n = pl.tiles_n;
-    hipError_t e = pl.variant <= kSkinny64 ? launch_skinny(p, pl, h->group, stream)
-                                           : launch_tile(p, pl, h->group, stream);
+    hipError_t e = is_skinny(pl.variant) ? launch_skinny(p, pl, h->group, stream)
+                                         : launch_tile(p, pl, h->group, stream);
     if (e != hipSuccess) return fail_hip(e, "kernel launch");
     return TM_OK;
 }
@@ -365,14 +380,25 @@ int tm_set_variant(int variant, int split_k)
     return TM_OK;
 }
 
+int tm_set_waves(int waves)
+{
+    if (waves != 0 && waves != 8 && waves != 16) return fail(TM_EINVAL, "waves must be 0 (auto), 8 or 16");
+    g_force_waves = waves;
+    return TM_OK;
+}
+
 const char* tm_variant_name(int variant)
 {
     switch (variant) {
-        case kSkinny16: return "skinny16";
-        case kSkinny32: return "skinny32";
-        case kSkinny64: return "skinny64";
-        case kTile128: return "tile128x128";
-        case kTile256: return "tile256x256";
+        case kSkinny16x16: return "skinny16x16";
+        case kSkinny16x32: return "skinny16x32";
+        case kSkinny16x64: return "skinny16x64";
+        case kSkinny32x32: return "skinny32x32";
+        case kSkinny32x64: return "skinny32x64";
+        case kTile32x256: return "tile32x256";
+        case kTile64x256: return "tile64x256";
+        case kTile128x128: return "tile128x128";
+        case kTile256x256: return "tile256x256";
         default: return "";
     }
 }

@@ -83,6 +83,35 @@ __device__ __forceinline__ f32x4 mfma16x16x32(f16x8 a, f16x8 b, f32x4 c)
     return __builtin_amdgcn_mfma_f32_16x16x32_f16(a, b, c, 0, 0, 0);
 }
 
+// Split-K partial sums cross CTAs (and therefore XCDs, whose L2 caches are not coherent with each other).
+// They are written and read with device-scope relaxed atomics, which the hardware performs as write-through
+// stores and cache-bypassing loads; a device-scope fence would instead write back and invalidate the whole L2 on
+// every call, which costs far more than the kernel itself.  Ordering against the arrival counter comes from
+// wait_stores_done() (every wave drains its own stores) followed by a CTA barrier before the counter is bumped.
+__device__ __forceinline__ void st_partial(float* p, float v)
+{
+    __hip_atomic_store(p, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+__device__ __forceinline__ void st_partial2(float* p, float a, float b)
+{
+    uint64_t u = (uint64_t)__builtin_bit_cast(uint32_t, a) | ((uint64_t)__builtin_bit_cast(uint32_t, b) << 32);
+    __hip_atomic_store((uint64_t*)p, u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+__device__ __forceinline__ float ld_partial(const float* p)
+{
+    return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+__device__ __forceinline__ void ld_partial2(const float* p, float& a, float& b)
+{
+    uint64_t u = __hip_atomic_load((const uint64_t*)p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    a = __builtin_bit_cast(float, (uint32_t)u);
+    b = __builtin_bit_cast(float, (uint32_t)(u >> 32));
+}
+__device__ __forceinline__ void wait_stores_done()
+{
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");           // this wave's write-through stores have completed
+}
+
 __device__ __forceinline__ uint16_t f32_to_f16_bits(float v)
 {
     _Float16 h = (_Float16)v;          // v_cvt_f16_f32, round-to-nearest-even

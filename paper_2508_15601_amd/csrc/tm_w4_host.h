@@ -10,13 +10,22 @@ namespace tmw4 {
 
 // Kernel variants the dispatcher can choose from (ids are what tm_set_variant / tm_get_plan use).
 enum Variant {
-    kSkinny16 = 0,    // M <= 16: one 16-row MFMA tile, weights streamed straight into B-operand registers
-    kSkinny32 = 1,    // M <= 32
-    kSkinny64 = 2,    // M <= 64
-    kTile128 = 3,     // 128 x 128 CTA tile, X staged through LDS
-    kTile256 = 4,     // 256 x 256 CTA tile, X staged through LDS
-    kNumVariants = 5
+    kSkinny16x16 = 0,   // M <= 16, one 16-column tile per wave: weights streamed straight into B-operand registers
+    kSkinny16x32 = 1,   // M <= 16, two 16-column tiles per wave
+    kSkinny16x64 = 2,   // M <= 16, four
+    kSkinny32x32 = 3,   // M <= 32, two
+    kSkinny32x64 = 4,   // M <= 32, four
+    kTile32x256 = 5,    // CTA tiles, X staged through LDS
+    kTile64x256 = 6,
+    kTile128x128 = 7,
+    kTile256x256 = 8,
+    kNumVariants = 9
 };
+inline bool is_skinny(int v) { return v <= kSkinny32x64; }
+inline int skinny_rows(int v) { return v <= kSkinny16x64 ? 16 : 32; }
+inline int skinny_ntw(int v) { return v == kSkinny16x16 ? 1 : ((v == kSkinny16x32 || v == kSkinny32x32) ? 2 : 4); }
+inline int tile_bm(int v) { return v == kTile32x256 ? 32 : (v == kTile64x256 ? 64 : (v == kTile128x128 ? 128 : 256)); }
+inline int tile_bn(int v) { return v == kTile128x128 ? 128 : 256; }
 
 struct Plan {
     int variant;

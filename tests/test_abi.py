@@ -55,7 +55,8 @@ def test_argument_validation_without_gpu(lib):
     assert lib.tm_get_plan(None, 1, None, None, None, None) == -1
     lib.tm_free_packed(None)                      # must be a no-op
     assert lib.tm_set_variant(99, 0) == -1 and lib.tm_set_variant(-1, 0) == 0
-    assert lib.tm_variant_name(0) == b"skinny16" and lib.tm_variant_name(99) == b""
+    assert lib.tm_variant_name(0) == b"skinny16x16" and lib.tm_variant_name(99) == b""
+    assert lib.tm_set_waves(5) == -1 and lib.tm_set_waves(0) == 0
     assert lib.tm_bench_copy(None, None, 16, None) == -1
     assert tm.tm_version().startswith("tm_w4")
 

@@ -27,6 +27,7 @@ def tm():
     tm.load_library()                       # fails loudly if the HIP library was not built
     yield tm
     tm.tm_set_variant(-1, 0)
+    tm.tm_set_waves(0)
 
 
 def _random_problem(seed, M, K, N, g):
@@ -67,7 +68,7 @@ def test_pack_bit_exact_against_oracle_unpack(tm, oracle, K, N, g):
 
 # ------------------------------------------------------------------ GEMM: exact special cases
 
-@pytest.mark.parametrize("variant", [-1, 3, 4])
+@pytest.mark.parametrize("variant", [-1, 0, 1, 2, 3, 4, 5, 6, 7, 8])
 def test_one_hot_rows_return_dequantised_weights_bit_exactly(tm, oracle, variant):
     """X = one-hot rows: a single non-zero product per output, so the fp16-dequantised weight must come back
     exactly; pins layout, nibble order, group indexing and the conversion constants on the device."""
@@ -75,8 +76,8 @@ def test_one_hot_rows_return_dequantised_weights_bit_exactly(tm, oracle, variant
     d = _random_problem(5, 1, K, N, g)
     packed = gu.pack(d, g)
     tm.tm_set_variant(variant, 0)
-    for k0 in range(0, K, 48):
-        rows = list(range(k0, k0 + 48))
+    for k0 in range(0, K, 16):
+        rows = list(range(k0, k0 + 16))
         X = np.zeros((len(rows), K), np.float16)
         X[np.arange(len(rows)), rows] = 1.0
         _say(f"one-hot variant={variant} k0={k0}")
@@ -86,7 +87,9 @@ def test_one_hot_rows_return_dequantised_weights_bit_exactly(tm, oracle, variant
     tm.tm_set_variant(-1, 0)
 
 
-@pytest.mark.parametrize("M,variant,split", [(4, -1, 0), (4, 0, 3), (40, -1, 0), (100, 3, 0), (100, 3, 2), (100, 4, 1)])
+@pytest.mark.parametrize("M,variant,split", [(4, -1, 0), (4, 0, 3), (12, 1, 2), (16, 2, 1), (30, 3, 1), (30, 4, 3),
+                                             (40, -1, 0), (31, 5, 1), (60, 6, 2), (100, 7, 0), (100, 7, 2),
+                                             (100, 8, 1)])
 def test_integer_exact_case(tm, oracle, M, variant, split):
     """s = 1 and small integer activations: every partial sum is an exactly representable integer, so any
     summation order gives the oracle's bits."""
@@ -127,11 +130,14 @@ def test_small_shapes_auto_plan(tm, oracle, M, K, N, g):
     assert ok, (worst, fro)
 
 
-@pytest.mark.parametrize("variant,split", [(0, 1), (0, 2), (0, 5), (1, 1), (1, 3), (2, 1), (2, 2), (3, 1), (3, 3),
-                                           (4, 1), (4, 2)])
+@pytest.mark.parametrize("variant,split,waves", [(0, 1, 8), (0, 2, 16), (0, 5, 8), (1, 1, 16), (1, 3, 8), (2, 1, 8),
+                                                 (2, 2, 16), (3, 1, 8), (3, 3, 16), (4, 1, 16), (4, 2, 8), (5, 1, 0),
+                                                 (5, 3, 0), (6, 1, 0), (6, 2, 0), (7, 1, 0), (7, 3, 0), (8, 1, 0),
+                                                 (8, 2, 0)])
 @pytest.mark.parametrize("g", [32, 64, 128])
-def test_every_variant_and_split(tm, oracle, variant, split, g):
-    M = {0: 13, 1: 29, 2: 50}.get(variant, 150)
+def test_every_variant_and_split(tm, oracle, variant, split, waves, g):
+    M = {0: 13, 1: 9, 2: 16, 3: 29, 4: 32, 5: 30, 6: 50}.get(variant, 150)
+    tm.tm_set_waves(waves)
     K, N = 1152, 336
     d = _random_problem(variant * 10 + split, M, K, N, g)
     packed = gu.pack(d, g)
@@ -142,6 +148,7 @@ def test_every_variant_and_split(tm, oracle, variant, split, g):
     Y = gu.gemm(packed, d["X"])
     Y2 = gu.gemm(packed, d["X"])
     tm.tm_set_variant(-1, 0)
+    tm.tm_set_waves(0)
     Yref = oracle.gemm(d["X"], d["q"], d["s"], d["z"], g)
     ok, worst, fro = acceptance(Y, Yref)
     assert ok, (worst, fro)
@@ -153,7 +160,7 @@ def test_caller_workspace_entry_point(tm, oracle):
     M, K, N, g = 20, 1152, 336, 128
     d = _random_problem(77, M, K, N, g)
     packed = gu.pack(d, g)
-    tm.tm_set_variant(1, 3)
+    tm.tm_set_variant(4, 3)
     need = tm.tm_gemm_workspace_bytes(packed, M)
     ws = torch.zeros(need + 256, dtype=torch.uint8, device="cuda")
     off = (-ws.data_ptr()) % 256
@@ -263,3 +270,37 @@ def test_config5_dispatch_sweep(tm, oracle):
 def test_config4_prefill_sampled(tm, oracle):
     case = wl.case_by_name("cfg4_prefill_70b_mlp")
     _check_case(tm, oracle, case)
+
+
+def test_hip_graph_replay_matches_eager(tm, oracle):
+    """The GEMM allocates nothing and clears its split-K counters itself, so it can be captured into a HIP graph;
+    every replay, with eager work in between, must reproduce the eager bits."""
+    import torch
+    M, K, N, g = 12, 1152, 336, 128
+    d = _random_problem(91, M, K, N, g)
+    packed = gu.pack(d, g)
+    tm.tm_set_variant(0, 3)                       # split-K path: workspace + arrival counters
+    Xd = gu.to_dev(d["X"])
+    Y_eager = torch.empty((M, N), dtype=torch.float16, device="cuda")
+    tm.tm_gemm_w4a16(Xd, packed, Y_eager)
+    torch.cuda.synchronize()
+    ok, worst, fro = acceptance(Y_eager.cpu().numpy(), oracle.gemm(d["X"], d["q"], d["s"], d["z"], g))
+    assert ok, (worst, fro)
+    Y_graph = torch.empty_like(Y_eager)
+    stream = torch.cuda.Stream()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.stream(stream):
+        with torch.cuda.graph(graph, stream=stream):
+            tm.tm_gemm_w4a16(Xd, packed, Y_graph)
+            tm.tm_gemm_w4a16(Xd, packed, Y_graph)
+    for rep in range(4):
+        Y_graph.fill_(float("nan"))
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        assert torch.equal(Y_graph.view(torch.int16), Y_eager.view(torch.int16)), f"replay {rep}"
+        Y2 = torch.empty_like(Y_eager)
+        tm.tm_gemm_w4a16(Xd, packed, Y2)           # eager work between replays
+        torch.cuda.synchronize()
+        assert torch.equal(Y2.view(torch.int16), Y_eager.view(torch.int16))
+    tm.tm_set_variant(-1, 0)
