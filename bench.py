@@ -183,6 +183,8 @@ def main():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-prefill", action="store_true", help="skip the prefill companion measurement")
     ap.add_argument("--eager", action="store_true", help="launch every kernel from the host instead of replaying HIP graphs")
+    ap.add_argument("--only", default=None, help="restrict the workload to one 'layer:M' pair, e.g. cfg3_gate_up:1 (profiling)")
+    ap.add_argument("--waves", type=int, default=0)
     ap.add_argument("--variant", type=int, default=-1)
     ap.add_argument("--split-k", type=int, default=0)
     args = ap.parse_args()
@@ -197,6 +199,7 @@ def main():
     torch.cuda.set_device(0)
     tm.load_library()
     tm.tm_set_variant(args.variant, args.split_k)
+    tm.tm_set_waves(args.waves)
 
     if args.workload == "sweep":
         table = []
@@ -221,7 +224,12 @@ def main():
         print(json.dumps({"metric": METRIC, "workload": "sweep", "rows": len(table)}))
         return
 
-    layers = [Layer(tm, torch, wl, cn, Ms) for cn, Ms in WORKLOADS[args.workload]]
+    spec = WORKLOADS[args.workload]
+    if args.only:
+        lname, m = args.only.split(":")
+        spec = [(cn, (int(m),)) for cn, Ms in spec if cn.startswith(lname)]
+        assert spec, "no layer of this workload matches --only"
+    layers = [Layer(tm, torch, wl, cn, Ms) for cn, Ms in spec]
     launches_per_step = sum(len(L.Ms) for L in layers)
 
     def step():

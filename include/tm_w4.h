@@ -73,7 +73,7 @@ TM_API tm_packed_w4* tm_pack_w4_on(const uint32_t* qweight, const uint16_t* scal
 /*
  * Online mixed-precision GEMM (paper Sec. 3.1 steps (i)-(iv) and Sec. 4.3): Y = X * dequant(packed).
  *
- *   X  fp16 [M][K] row-major, 16-byte aligned        Y  fp16 [M][N] row-major, 4-byte aligned
+ *   X  fp16 [M][K] row-major, 16-byte aligned        Y  fp16 [M][N] row-major, 16-byte aligned;  M*K < 2^31
  *
  * Picks a kernel variant and a split-K factor from (M, K, N, group) and enqueues it on `stream`.  Never allocates.
  * Split-K partial sums go through the library's device-wide workspace and are reduced in a fixed order, so results

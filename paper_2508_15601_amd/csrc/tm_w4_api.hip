@@ -118,15 +118,24 @@ Plan make_plan(const tm_packed_w4* h, int M, int num_cu)
     int variant = g_force_variant;
     if (variant < 0) {
         if (M <= 32) {
+            // widest strip that still gives about three quarters of the CUs a CTA of their own
             const bool rows16 = M <= 16;
-            if (NT / 4 >= num_cu) variant = rows16 ? kSkinny16x64 : kSkinny32x64;
-            else if (NT / 2 >= num_cu || !rows16) variant = rows16 ? kSkinny16x32 : kSkinny32x32;
+            const int enough = (3 * num_cu) / 4;
+            if (NT / 4 >= enough) variant = rows16 ? kSkinny16x64 : kSkinny32x64;
+            else if (NT / 2 >= enough || !rows16) variant = rows16 ? kSkinny16x32 : kSkinny32x32;
             else variant = kSkinny16x16;
-        } else if (M <= 64) {
-            variant = kTile64x256;
         } else {
-            long big_tiles = (long)ceil_div(M, 256) * ceil_div(h->N, 256);
-            variant = big_tiles >= 2L * num_cu ? kTile256x256 : kTile128x128;
+            // largest tile that still yields two CTAs per CU without splitting K; the smallest one otherwise
+            const int cand[3] = {kTile128x256, kTile128x128, kTile64x128};
+            variant = M <= 64 ? kTile32x256 : kTile64x128;
+            if (M > 64)
+                for (int i = 0; i < 3; ++i) {
+                    long t = (long)ceil_div(M, tile_bm(cand[i])) * ceil_div(h->N, tile_bn(cand[i]));
+                    if (t >= 2L * num_cu) {
+                        variant = cand[i];
+                        break;
+                    }
+                }
         }
     }
     if (is_skinny(variant) && M > skinny_rows(variant))        // a forced skinny variant must still cover M
@@ -139,8 +148,9 @@ Plan make_plan(const tm_packed_w4* h, int M, int num_cu)
     if (is_skinny(variant)) {
         const int ntw = skinny_ntw(variant);
         const int strips = ceil_div(NT, ntw);
-        int waves = g_force_waves > 0 ? g_force_waves : (KU >= 32 ? 16 : 8);
+        int waves = g_force_waves > 0 ? g_force_waves : ((strips <= num_cu && KU >= 32) ? 16 : 8);
         if (waves < 2 * ntw) waves = 2 * ntw;      // the LDS reduction needs 128*ntw threads
+        if (variant == kSkinny32x64) waves = 8;    // its register footprint does not fit a 16-wave CTA
         pl.tiles_m = 1;
         pl.tiles_n = strips;
         pl.block = (unsigned)waves * 64;
@@ -154,7 +164,8 @@ Plan make_plan(const tm_packed_w4* h, int M, int num_cu)
         pl.tiles_n = ceil_div(h->N, tile_bn(variant));
         pl.block = 256;
         int tiles = pl.tiles_m * pl.tiles_n;
-        int want = (2 * num_cu) / tiles;           // fill the chip about twice over
+        int want = (2 * num_cu) / tiles;           // fill the chip about twice over ...
+        if (want > 4) want = 4;                    // ... but every split costs a full fp32 pass over the output
         int max_by_k = KU / 4 > 0 ? KU / 4 : 1;    // keep at least four units per CTA
         split = want < max_by_k ? want : max_by_k;
     }
@@ -182,7 +193,8 @@ int run_gemm(const uint16_t* X, const tm_packed_w4* h, uint16_t* Y, int M, void*
     if (M < 0 || M >= (1 << 24)) return fail(TM_EINVAL, "M = %d out of range", M);
     if (M == 0) return TM_OK;
     if (!X || !Y) return fail(TM_EINVAL, "X or Y is null");
-    if (((uintptr_t)X & 15) || ((uintptr_t)Y & 3)) return fail(TM_EINVAL, "X must be 16-byte and Y 4-byte aligned");
+    if (((uintptr_t)X & 15) || ((uintptr_t)Y & 15)) return fail(TM_EINVAL, "X and Y must be 16-byte aligned");
+    if ((uint64_t)M * (uint64_t)h->K >= (1ull << 31)) return fail(TM_EINVAL, "M*K must be below 2^31");
     int dev;
     int rc = check_device(&dev);
     if (rc != TM_OK) return rc;
@@ -397,8 +409,11 @@ const char* tm_variant_name(int variant)
         case kSkinny32x64: return "skinny32x64";
         case kTile32x256: return "tile32x256";
         case kTile64x256: return "tile64x256";
-        case kTile128x128: return "tile128x128";
+        case kTile128x256: return "tile128x256";
         case kTile256x256: return "tile256x256";
+        case kTile64x128: return "tile64x128";
+        case kTile128x128: return "tile128x128";
+        case kTile192x256: return "tile192x256";
         default: return "";
     }
 }

@@ -57,23 +57,62 @@ __device__ __forceinline__ GroupConst make_group_const(uint32_t sz)
     return g;
 }
 
+// The two exponent patterns of the conversion, held in vector registers: gfx950 encodes at most one scalar or
+// literal operand per VALU instruction, so "(w & mask) | magic" only fuses into one v_and_or_b32 when the magic
+// comes from a VGPR.  Call once per kernel, outside the loops.
+struct Magic {
+    uint32_t m1024;  // 0x6400 in both halves: fp16 1024
+    uint32_t m64;    // 0x5400 in both halves: fp16 64
+};
+__device__ __forceinline__ Magic make_magic()
+{
+    Magic m{0x64006400u, 0x54005400u};
+    asm("" : "+v"(m.m1024));
+    asm("" : "+v"(m.m64));
+    return m;
+}
+
 // Integer-to-float by bit manipulation (paper Sec. 3.1 step (iii), Sec. 4.3 "I2F conversion and FMA").
 // A nibble q OR-ed into the mantissa of 0x6400 is the fp16 number 1024 + q; a nibble sitting four bits higher
 // OR-ed into 0x5400 is 64 + q.  Adding the matching offset gives q - z exactly; one multiply applies the scale
 // (a single rounding per weight).  The packed word stores weight e at nibble 4*(e&1) + (e>>1), so the four
 // masked words below are already the fp16 pairs (e0,e1), (e2,e3), (e4,e5), (e6,e7) of a matrix-core operand.
-__device__ __forceinline__ f16x8 dequant8(uint32_t w, const GroupConst& g)
+// 13 vector instructions per 8 weights: 1 shift, 4 and-or, 4 packed adds, 4 packed multiplies.
+__device__ __forceinline__ f16x8 dequant8(uint32_t w, const GroupConst& g, const Magic& mg)
 {
-    uint32_t a0 = (w & 0x000F000Fu) | 0x64006400u;
-    uint32_t a1 = (w & 0x00F000F0u) | 0x54005400u;
+    uint32_t a0 = (w & 0x000F000Fu) | mg.m1024;
+    uint32_t a1 = (w & 0x00F000F0u) | mg.m64;
     uint32_t w8 = w >> 8;
-    uint32_t a2 = (w8 & 0x000F000Fu) | 0x64006400u;
-    uint32_t a3 = (w8 & 0x00F000F0u) | 0x54005400u;
+    uint32_t a2 = (w8 & 0x000F000Fu) | mg.m1024;
+    uint32_t a3 = (w8 & 0x00F000F0u) | mg.m64;
     f16x2 r0 = (as_f16x2(a0) + g.off1024) * g.s2;
     f16x2 r1 = (as_f16x2(a1) + g.off64) * g.s2;
     f16x2 r2 = (as_f16x2(a2) + g.off1024) * g.s2;
     f16x2 r3 = (as_f16x2(a3) + g.off64) * g.s2;
     return f16x8{r0.x, r0.y, r1.x, r1.y, r2.x, r2.y, r3.x, r3.y};
+}
+
+// The bit-manipulation half of the conversion alone: the eight fp16 values (1024 + q) / (64 + q), alternating in
+// pairs (e0,e1: +1024; e2,e3: +64; e4,e5: +1024; e6,e7: +64), still carrying their conversion bias.
+__device__ __forceinline__ f16x8 biased8(uint32_t w, const Magic& mg)
+{
+    u32x4 r;
+    r.x = (w & 0x000F000Fu) | mg.m1024;
+    r.y = (w & 0x00F000F0u) | mg.m64;
+    uint32_t w8 = w >> 8;
+    r.z = (w8 & 0x000F000Fu) | mg.m1024;
+    r.w = (w8 & 0x00F000F0u) | mg.m64;
+    return __builtin_bit_cast(f16x8, r);
+}
+
+// The operand that cancels that bias together with the zero-point inside the matrix core: multiplying the same
+// activations by -(bias + z) and accumulating into the same fp32 tile leaves sum_k x_k * (q_k - z) exactly
+// (every product is exact in fp32; only the accumulation order rounds).
+__device__ __forceinline__ f16x8 bias_cancel8(_Float16 z)
+{
+    _Float16 a = (_Float16)(-1024.0f) - z;   // exact: 1024 + z <= 1039 is an fp16 integer
+    _Float16 b = (_Float16)(-64.0f) - z;
+    return f16x8{a, a, b, b, a, a, b, b};
 }
 
 // D = A(16x32) * B(32x16) + C on the matrix cores.  Lane l supplies row l%16 of A and column l%16 of B, each

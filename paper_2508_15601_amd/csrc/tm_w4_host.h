@@ -17,15 +17,18 @@ enum Variant {
     kSkinny32x64 = 4,   // M <= 32, four
     kTile32x256 = 5,    // CTA tiles, X staged through LDS
     kTile64x256 = 6,
-    kTile128x128 = 7,
+    kTile128x256 = 7,
     kTile256x256 = 8,
-    kNumVariants = 9
+    kTile64x128 = 9,
+    kTile128x128 = 10,
+    kTile192x256 = 11,
+    kNumVariants = 12
 };
 inline bool is_skinny(int v) { return v <= kSkinny32x64; }
 inline int skinny_rows(int v) { return v <= kSkinny16x64 ? 16 : 32; }
 inline int skinny_ntw(int v) { return v == kSkinny16x16 ? 1 : ((v == kSkinny16x32 || v == kSkinny32x32) ? 2 : 4); }
-inline int tile_bm(int v) { return v == kTile32x256 ? 32 : (v == kTile64x256 ? 64 : (v == kTile128x128 ? 128 : 256)); }
-inline int tile_bn(int v) { return v == kTile128x128 ? 128 : 256; }
+inline int tile_bm(int v) { return v == kTile32x256 ? 32 : ((v == kTile64x256 || v == kTile64x128) ? 64 : ((v == kTile128x256 || v == kTile128x128) ? 128 : (v == kTile192x256 ? 192 : 256))); }
+inline int tile_bn(int v) { return (v == kTile64x128 || v == kTile128x128) ? 128 : 256; }
 
 struct Plan {
     int variant;
@@ -46,5 +49,7 @@ hipError_t launch_read(const void* src, size_t bytes, void* sink, hipStream_t st
 
 hipError_t launch_skinny(const GemmParams& p, const Plan& plan, int group, hipStream_t stream);
 hipError_t launch_tile(const GemmParams& p, const Plan& plan, int group, hipStream_t stream);
+hipError_t launch_tile_small(const GemmParams& p, const Plan& plan, int group, hipStream_t stream);
+hipError_t launch_tile_large(const GemmParams& p, const Plan& plan, int group, hipStream_t stream);
 
 }  // namespace tmw4

@@ -22,60 +22,90 @@ struct Stage {
     u32x4 xf[TM][4];            // activation fragments for the four MFMA k-steps
 };
 
+// Per-lane byte offsets that do not change over the K loop; everything else in an address is wave-uniform and
+// stays in scalar registers, so a load costs no vector address arithmetic.
+template <int TM>
+struct LaneOffsets {
+    uint32_t w;                 // lane * 16 inside a 1 KiB unit
+    uint32_t sz;                // (lane % 16) * 4 inside a 64-byte scale/zero row
+    uint32_t x[TM];             // row(mt, lane) * K * 2 + (lane / 16) * 16 inside X
+};
+
 template <int TM, int NTW, int GPU>
-__device__ __forceinline__ void load_stage(Stage<TM, NTW, GPU>& st, const GemmParams& p, int nt0, int ku, int lane)
+__device__ __forceinline__ void load_stage(Stage<TM, NTW, GPU>& st, const GemmParams& p, const LaneOffsets<TM>& lo,
+                                           int nt0, int ku)
 {
-    const int c = lane & 15, h = lane >> 4;
 #pragma unroll
     for (int j = 0; j < NTW; ++j) {
-        int nt = nt0 + j;
+        const int nt = nt0 + j;                    // wave-uniform
         if (nt < p.NT) {
-            st.wq[j] = __builtin_nontemporal_load(&p.W[((size_t)nt * p.KU + ku) * 64 + lane]);
+            const char* wb = (const char*)p.W + ((size_t)nt * p.KU + ku) * 1024;
+            st.wq[j] = __builtin_nontemporal_load((const u32x4*)(wb + lo.w));
+            const char* sb = (const char*)p.SZ + ((size_t)nt * p.G + (size_t)ku * GPU) * 64;
 #pragma unroll
-            for (int g = 0; g < GPU; ++g) st.sz[j][g] = p.SZ[((size_t)nt * p.G + ku * GPU + g) * 16 + c];
+            for (int g = 0; g < GPU; ++g) st.sz[j][g] = *(const uint32_t*)(sb + g * 64 + lo.sz);
         } else {
             st.wq[j] = u32x4{0, 0, 0, 0};
 #pragma unroll
             for (int g = 0; g < GPU; ++g) st.sz[j][g] = 0;
         }
     }
+    const char* xb = (const char*)p.X + (size_t)ku * (kUnitK * 2);
 #pragma unroll
-    for (int mt = 0; mt < TM; ++mt) {
-        int row = mt * 16 + c;
-        row = row < p.M ? row : p.M - 1;           // rows past M repeat the last row; their outputs are dropped
-        const u32x4* xr = (const u32x4*)(p.X + (size_t)row * p.K + (size_t)ku * kUnitK + 8 * h);
+    for (int mt = 0; mt < TM; ++mt)
 #pragma unroll
-        for (int t = 0; t < 4; ++t) st.xf[mt][t] = xr[4 * t];   // k = 128*ku + 32*t + 8*h .. +7
-    }
+        for (int t = 0; t < 4; ++t)                // k = 128*ku + 32*t + 8*h .. +7
+            st.xf[mt][t] = *(const u32x4*)(xb + lo.x[mt] + 64 * t);
 }
 
+// One unit of NTW column tiles.  Paper Sec. 3.1 step (iii) / Sec. 4.3 split differently between the units of the
+// CU than in the paper: the vector ALU only does the bit manipulation (biased8: 5 instructions per 8 weights);
+// the conversion bias and the zero-point are removed by a second MFMA against a constant operand, and the group
+// scale multiplies the fp32 group sum.  The decode kernels are bound by HBM and by vector-ALU issue, while the
+// matrix cores idle, so moving the subtract and the multiply off the ALU is what brings the per-weight ALU cost
+// under the HBM budget.
 template <int TM, int NTW, int GPU>
-__device__ __forceinline__ void compute_stage(const Stage<TM, NTW, GPU>& st, f32x4 (&acc)[TM][NTW])
+__device__ __forceinline__ void compute_stage(const Stage<TM, NTW, GPU>& st, f32x4 (&acc)[TM][NTW], const Magic& mg)
 {
+    constexpr int T = 4 / GPU;                     // MFMA k-steps per K-group
 #pragma unroll
     for (int j = 0; j < NTW; ++j) {
-        GroupConst gc[GPU];
 #pragma unroll
-        for (int g = 0; g < GPU; ++g) gc[g] = make_group_const(st.sz[j][g]);
+        for (int g = 0; g < GPU; ++g) {
+            const f16x2 szp = as_f16x2(st.sz[j][g]);
+            const f16x8 cancel = bias_cancel8(szp.y);
+            const float scale = (float)szp.x;
+            f32x4 part[TM];
 #pragma unroll
-        for (int t = 0; t < 4; ++t) {
-            f16x8 b = dequant8(st.wq[j][t], gc[(t * GPU) / 4]);
+            for (int mt = 0; mt < TM; ++mt) part[mt] = f32x4{0.f, 0.f, 0.f, 0.f};
 #pragma unroll
-            for (int mt = 0; mt < TM; ++mt)
-                acc[mt][j] = mfma16x16x32(__builtin_bit_cast(f16x8, st.xf[mt][t]), b, acc[mt][j]);
+            for (int tt = 0; tt < T; ++tt) {
+                const int t = g * T + tt;
+                const f16x8 b = biased8(st.wq[j][t], mg);
+#pragma unroll
+                for (int mt = 0; mt < TM; ++mt) {
+                    const f16x8 a = __builtin_bit_cast(f16x8, st.xf[mt][t]);
+                    part[mt] = mfma16x16x32(a, b, part[mt]);
+                    part[mt] = mfma16x16x32(a, cancel, part[mt]);
+                }
+            }
+#pragma unroll
+            for (int mt = 0; mt < TM; ++mt) acc[mt][j] += scale * part[mt];
         }
     }
 }
 
-// TM 16-row tiles, NTW 16-column tiles per wave, GPU K-groups per 128-row unit, D units in flight per wave.
-template <int TM, int NTW, int GPU, int D>
-__global__ __launch_bounds__(1024) void skinny_kernel(GemmParams p)
+// TM 16-row tiles, NTW 16-column tiles per wave, GPU K-groups per 128-row unit, D units in flight per wave,
+// MAXW the largest CTA (in waves) this instantiation is launched with.
+template <int TM, int NTW, int GPU, int D, int MAXW>
+__global__ __launch_bounds__(MAXW * 64) void skinny_kernel(GemmParams p)
 {
     extern __shared__ float red[];                 // [waves][NTW*4][64]: one 16 x 16*NTW fp32 tile per wave
     __shared__ uint32_t s_last;
 
     const int tid = threadIdx.x;
-    const int lane = tid & 63, wave = tid >> 6;
+    const int lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);     // wave-uniform by construction
     const int waves = blockDim.x >> 6;
     const int strips = (p.NT + NTW - 1) / NTW;
     const int strip = blockIdx.x % strips;
@@ -83,6 +113,17 @@ __global__ __launch_bounds__(1024) void skinny_kernel(GemmParams p)
     const int nt0 = strip * NTW;
     const int ku0 = sk * p.ku_per_split;
     const int ku1 = min(p.KU, ku0 + p.ku_per_split);
+
+    const Magic mg = make_magic();
+    LaneOffsets<TM> lo;
+    lo.w = lane * 16;
+    lo.sz = (lane & 15) * 4;
+#pragma unroll
+    for (int mt = 0; mt < TM; ++mt) {
+        int row = mt * 16 + (lane & 15);
+        row = row < p.M ? row : p.M - 1;           // rows past M repeat the last row; their outputs are dropped
+        lo.x[mt] = (uint32_t)row * (uint32_t)p.K * 2u + (lane >> 4) * 16;
+    }
 
     f32x4 acc[TM][NTW];
 #pragma unroll
@@ -94,10 +135,10 @@ __global__ __launch_bounds__(1024) void skinny_kernel(GemmParams p)
         Stage<TM, NTW, GPU> st[D];
 #pragma unroll
         for (int d = 0; d < D; ++d)
-            if (ku + d * waves < ku1) load_stage(st[d], p, nt0, ku + d * waves, lane);
+            if (ku + d * waves < ku1) load_stage(st[d], p, lo, nt0, ku + d * waves);
 #pragma unroll
         for (int d = 0; d < D; ++d)
-            if (ku + d * waves < ku1) compute_stage(st[d], acc);
+            if (ku + d * waves < ku1) compute_stage(st[d], acc, mg);
     }
 
     // Reduce the waves' tiles through LDS, one 16-row tile at a time; thread -> (row, two adjacent columns).
@@ -163,15 +204,16 @@ __global__ __launch_bounds__(1024) void skinny_kernel(GemmParams p)
     }
 }
 
-template <int TM, int NTW, int D>
+template <int TM, int NTW, int D, int MAXW>
 hipError_t launch_cfg(const GemmParams& p, const Plan& plan, int group, hipStream_t stream)
 {
     dim3 grid(plan.grid), block(plan.block);
+    if (plan.block > MAXW * 64) return hipErrorInvalidValue;
     size_t lds = (size_t)(plan.block / 64) * NTW * 4 * 64 * sizeof(float);
     switch (group) {
-        case 128: hipLaunchKernelGGL((skinny_kernel<TM, NTW, 1, D>), grid, block, lds, stream, p); break;
-        case 64: hipLaunchKernelGGL((skinny_kernel<TM, NTW, 2, D>), grid, block, lds, stream, p); break;
-        case 32: hipLaunchKernelGGL((skinny_kernel<TM, NTW, 4, D>), grid, block, lds, stream, p); break;
+        case 128: hipLaunchKernelGGL((skinny_kernel<TM, NTW, 1, D, MAXW>), grid, block, lds, stream, p); break;
+        case 64: hipLaunchKernelGGL((skinny_kernel<TM, NTW, 2, D, MAXW>), grid, block, lds, stream, p); break;
+        case 32: hipLaunchKernelGGL((skinny_kernel<TM, NTW, 4, D, MAXW>), grid, block, lds, stream, p); break;
         default: return hipErrorInvalidValue;
     }
     return hipGetLastError();
@@ -181,12 +223,13 @@ hipError_t launch_cfg(const GemmParams& p, const Plan& plan, int group, hipStrea
 
 hipError_t launch_skinny(const GemmParams& p, const Plan& plan, int group, hipStream_t stream)
 {
+    const bool w16 = plan.block > 512;
     switch (plan.variant) {
-        case kSkinny16x16: return launch_cfg<1, 1, 4>(p, plan, group, stream);
-        case kSkinny16x32: return launch_cfg<1, 2, 2>(p, plan, group, stream);
-        case kSkinny16x64: return launch_cfg<1, 4, 1>(p, plan, group, stream);
-        case kSkinny32x32: return launch_cfg<2, 2, 1>(p, plan, group, stream);
-        case kSkinny32x64: return launch_cfg<2, 4, 1>(p, plan, group, stream);
+        case kSkinny16x16: return w16 ? launch_cfg<1, 1, 2, 16>(p, plan, group, stream) : launch_cfg<1, 1, 4, 8>(p, plan, group, stream);
+        case kSkinny16x32: return w16 ? launch_cfg<1, 2, 2, 16>(p, plan, group, stream) : launch_cfg<1, 2, 4, 8>(p, plan, group, stream);
+        case kSkinny16x64: return w16 ? launch_cfg<1, 4, 1, 16>(p, plan, group, stream) : launch_cfg<1, 4, 2, 8>(p, plan, group, stream);
+        case kSkinny32x32: return w16 ? launch_cfg<2, 2, 1, 16>(p, plan, group, stream) : launch_cfg<2, 2, 2, 8>(p, plan, group, stream);
+        case kSkinny32x64: return launch_cfg<2, 4, 1, 8>(p, plan, group, stream);
         default: return hipErrorInvalidValue;
     }
 }

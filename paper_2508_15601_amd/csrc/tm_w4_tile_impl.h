@@ -1,0 +1,250 @@
+// Fused dequantise-and-multiply for M > 32: CTA tiles with the activations staged through LDS.
+//
+// Online stage of the GEMM pipeline (paper Sec. 3.1 steps (i)-(iv)) with the software-pipelined main loop of
+// Sec. 4.3: while the matrix cores work on one 64-deep K slice, the vector ALUs convert the weight fragments of
+// that slice (I2F, then zero-point and scale: one exact subtract and one rounded multiply per weight) between the
+// MFMAs, and the memory units fetch the next X slice and the next half-unit of packed weights.
+//
+// Differences from the paper's design: packed weights go from HBM/L2 straight into registers in matrix-core operand
+// order (no shared-memory stage, no matrix-load instruction, hence nothing to swizzle); only X passes through LDS,
+// in a padded row-major layout (144-byte pitch) that makes the 16-lane 128-bit fragment reads conflict-free.
+// The four waves of a CTA split the tile along N only, so every weight fragment is converted exactly once per CTA
+// and feeds TM MFMAs.  The weight fragment is the A operand, so a lane ends up with four consecutive columns of
+// one output row and stores them as one 8-byte word.  CTAs are numbered so that the CTAs resident on one XCD
+// (one L2) cover a compact block of output tiles.
+#pragma once
+#include "tm_w4_host.h"
+
+namespace tmw4 {
+
+namespace {
+
+constexpr int kHalfK = 64;                 // K depth of one LDS stage (half a packed unit)
+constexpr int kPitch = kHalfK + 8;         // LDS row pitch in halves (144 bytes)
+constexpr int kPanelN = 8;                 // output tiles per panel row (XCD-local rasterisation)
+
+typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
+
+// CTA tile = (TM*16) rows x (4*TN*16) columns; wave w owns columns [w*TN*16, (w+1)*TN*16) and all rows.
+template <int TM, int TN, int GPU>
+__global__ __launch_bounds__(256) void tile_kernel(GemmParams p)
+{
+    constexpr int BM = TM * 16, BN = 4 * TN * 16;
+    constexpr int CH = (BM * 8 + 255) / 256;   // 16-byte chunks of one X stage per thread (BM rows x 8 chunks)
+    constexpr int GH = GPU == 4 ? 2 : 1;       // K-groups touched by one 64-deep half-step
+    __shared__ __attribute__((aligned(16))) uint16_t xs[2][BM * kPitch];
+    __shared__ uint32_t s_last;
+
+    const int tid = threadIdx.x;
+    const int lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int c = lane & 15, h = lane >> 4;
+    const Magic mg = make_magic();
+
+    // XCD-aware numbering: consecutive block ids go to different XCDs, so the ids congruent mod 8 (one XCD) are
+    // mapped to consecutive logical tiles, and logical tiles walk panels of kPanelN tiles along N.
+    const int tiles = p.tiles_m * p.tiles_n;
+    const int chunk = (tiles + 7) / 8;
+    const int sk = blockIdx.x / (chunk * 8);
+    const int b = blockIdx.x % (chunk * 8);
+    const int logical = (b % 8) * chunk + b / 8;
+    if (logical >= tiles) return;
+    const int panel_tiles = kPanelN * p.tiles_m;
+    const int panel = logical / panel_tiles;
+    const int within = logical % panel_tiles;
+    const int pw = min(kPanelN, p.tiles_n - panel * kPanelN);      // width of this panel
+    const int tile_m = within / pw, tile_n = panel * kPanelN + within % pw;
+
+    const int m0 = tile_m * BM;
+    const int nt0 = (tile_n * BN) / 16 + wave * TN;        // first 16-column tile of this wave
+    const int hs0 = 2 * sk * p.ku_per_split;
+    const int hs1 = 2 * min(p.KU, (sk + 1) * p.ku_per_split);
+
+    f32x4 acc[TM][TN];
+#pragma unroll
+    for (int i = 0; i < TM; ++i)
+#pragma unroll
+        for (int j = 0; j < TN; ++j) acc[i][j] = f32x4{0.f, 0.f, 0.f, 0.f};
+
+    // global -> register staging of one X stage: thread owns chunks idx = i*256 + tid -> (row idx/8, chunk idx%8)
+    u32x4 xreg[CH];
+    const int xrow0 = m0 + (tid >> 3);         // chunk i of this thread sits 32*i rows further down
+    const uint32_t xcol = (tid & 7) * 16;
+    auto load_x = [&](int hs) {
+        const char* xb = (const char*)p.X + (size_t)hs * (kHalfK * 2) + xcol;
+#pragma unroll
+        for (int i = 0; i < CH; ++i)
+            if (BM * 8 % 256 == 0 || i * 256 + tid < BM * 8) {
+                const int row = min(xrow0 + 32 * i, p.M - 1);          // rows past M repeat the last row
+                xreg[i] = *(const u32x4*)(xb + (uint32_t)row * (uint32_t)p.K * 2u);   // M*K < 2^31 (host check)
+            }
+    };
+    auto store_x = [&](int buf) {
+#pragma unroll
+        for (int i = 0; i < CH; ++i) {
+            int idx = i * 256 + tid;
+            if (BM * 8 % 256 == 0 || idx < BM * 8)
+                *(u32x4*)(&xs[buf][(idx >> 3) * kPitch + (idx & 7) * 8]) = xreg[i];
+        }
+    };
+
+    // packed weights of one half-step: the lane's words t = 2*half, 2*half+1 of each n-tile's unit
+    u32x2 wq[TN], wq_next[TN];
+    uint32_t sz[TN][GH], sz_next[TN][GH];
+    auto load_w = [&](u32x2 (&w)[TN], uint32_t (&s)[TN][GH], int hs) {
+        const int ku = hs >> 1, half = hs & 1;
+#pragma unroll
+        for (int j = 0; j < TN; ++j) {
+            // wave-uniform; tiles past the edge re-read the last valid tile (their results are never stored),
+            // which keeps the K loop free of branches
+            const int nt = min(nt0 + j, p.NT - 1);
+            const char* wb = (const char*)p.W + ((size_t)nt * p.KU + ku) * 1024 + half * 8;
+            w[j] = *(const u32x2*)(wb + lane * 16);
+#pragma unroll
+            for (int g = 0; g < GH; ++g) {
+                const int grp = GPU == 1 ? ku : (GPU == 2 ? 2 * ku + half : 4 * ku + 2 * half + g);
+                s[j][g] = *(const uint32_t*)((const char*)p.SZ + ((size_t)nt * p.G + grp) * 64 + c * 4);
+            }
+        }
+    };
+    // One 32-deep MFMA step over the whole CTA-row tile, software-pipelined as in paper Sec. 4.3: while the
+    // matrix cores consume the converted fragments `cur`, the vector ALU converts the fragments of the NEXT step
+    // into `nxt`, a few at a time between groups of MFMAs, and LDS reads run one row-pair ahead of their use.
+    // The scheduling barriers keep the compiler from hoisting all LDS reads and conversions to the top, which
+    // would both starve the matrix cores and blow the register budget.
+    constexpr int PAIRS = TM / 2;
+    auto step = [&](int buf, int tt, const f16x8 (&cur)[TN], f16x8 (&nxt)[TN],
+                    const u32x2 (&wsrc)[TN], const uint32_t (&ssrc)[TN][GH], int tt_next) {
+        const uint16_t* base = &xs[buf][c * kPitch + 32 * tt + 8 * h];
+        f16x8 x0 = *(const f16x8*)(base);
+        f16x8 x1 = *(const f16x8*)(base + 16 * kPitch);
+#pragma unroll
+        for (int ip = 0; ip < PAIRS; ++ip) {
+            f16x8 n0 = x0, n1 = x1;
+            if (ip + 1 < PAIRS) {
+                n0 = *(const f16x8*)(base + (2 * ip + 2) * 16 * kPitch);
+                n1 = *(const f16x8*)(base + (2 * ip + 3) * 16 * kPitch);
+            }
+#pragma unroll
+            for (int j = 0; j < TN; ++j)
+                if (j * PAIRS / TN == ip)          // spread the TN conversions over the row pairs
+                    nxt[j] = dequant8(wsrc[j][tt_next], make_group_const(ssrc[j][GH == 2 ? tt_next : 0]), mg);
+#pragma unroll
+            for (int j = 0; j < TN; ++j) acc[2 * ip][j] = mfma16x16x32(cur[j], x0, acc[2 * ip][j]);
+#pragma unroll
+            for (int j = 0; j < TN; ++j) acc[2 * ip + 1][j] = mfma16x16x32(cur[j], x1, acc[2 * ip + 1][j]);
+            __builtin_amdgcn_sched_barrier(0);
+            x0 = n0;
+            x1 = n1;
+        }
+    };
+
+    if (hs0 < hs1) {
+        f16x8 wfa[TN], wfb[TN];
+        load_x(hs0);
+        load_w(wq, sz, hs0);
+        store_x(0);
+#pragma unroll
+        for (int j = 0; j < TN; ++j) wfa[j] = dequant8(wq[j][0], make_group_const(sz[j][0]), mg);
+        __syncthreads();
+        for (int hs = hs0; hs < hs1; ++hs) {
+            // The last iteration prefetches its own slice again instead of branching; the data is never used.
+            const int hn = min(hs + 1, hs1 - 1);
+            const int buf = (hs - hs0) & 1;
+            load_x(hn);
+            load_w(wq_next, sz_next, hn);
+            step(buf, 0, wfa, wfb, wq, sz, 1);
+            step(buf, 1, wfb, wfa, wq_next, sz_next, 0);
+            store_x(buf ^ 1);
+#pragma unroll
+            for (int j = 0; j < TN; ++j) {
+                wq[j] = wq_next[j];
+#pragma unroll
+                for (int g = 0; g < GH; ++g) sz[j][g] = sz_next[j][g];
+            }
+            __syncthreads();
+        }
+    }
+
+    // Epilogue.  acc[i][j][r] = Y[m0 + 16i + c][16*(nt0 + j) + 4h + r]: four consecutive columns per lane.
+    if (p.split == 1) {
+#pragma unroll
+        for (int i = 0; i < TM; ++i) {
+            const int m = m0 + i * 16 + c;
+            if (m >= p.M) continue;
+#pragma unroll
+            for (int j = 0; j < TN; ++j) {
+                const int nt = nt0 + j;
+                if (nt >= p.NT) continue;
+                u32x2 o;
+                o.x = (uint32_t)f32_to_f16_bits(acc[i][j][0]) | ((uint32_t)f32_to_f16_bits(acc[i][j][1]) << 16);
+                o.y = (uint32_t)f32_to_f16_bits(acc[i][j][2]) | ((uint32_t)f32_to_f16_bits(acc[i][j][3]) << 16);
+                *(u32x2*)(p.Y + (size_t)m * p.N + nt * 16 + 4 * h) = o;
+            }
+        }
+        return;
+    }
+
+    const int tile = tile_m + tile_n * p.tiles_m;          // counter index
+#pragma unroll
+    for (int i = 0; i < TM; ++i) {
+        const int m = m0 + i * 16 + c;
+        if (m >= p.M) continue;
+#pragma unroll
+        for (int j = 0; j < TN; ++j) {
+            const int nt = nt0 + j;
+            if (nt >= p.NT) continue;
+            float* dst = p.partial + ((size_t)sk * p.M + m) * p.N + nt * 16 + 4 * h;
+            st_partial2(dst, acc[i][j][0], acc[i][j][1]);
+            st_partial2(dst + 2, acc[i][j][2], acc[i][j][3]);
+        }
+    }
+    wait_stores_done();
+    __syncthreads();
+    if (tid == 0) {
+        uint32_t prev = atomicAdd(&p.counters[tile], 1u);
+        s_last = (prev == (uint32_t)p.split - 1u) ? 1u : 0u;
+    }
+    __syncthreads();
+    if (!s_last) return;
+#pragma unroll
+    for (int i = 0; i < TM; ++i) {
+        const int m = m0 + i * 16 + c;
+        if (m >= p.M) continue;
+#pragma unroll
+        for (int j = 0; j < TN; ++j) {
+            const int nt = nt0 + j;
+            if (nt >= p.NT) continue;
+            float v[4] = {0.f, 0.f, 0.f, 0.f};
+            for (int s = 0; s < p.split; ++s) {
+                const float* src = p.partial + ((size_t)s * p.M + m) * p.N + nt * 16 + 4 * h;
+                float a0, a1, a2, a3;
+                ld_partial2(src, a0, a1);
+                ld_partial2(src + 2, a2, a3);
+                v[0] += a0; v[1] += a1; v[2] += a2; v[3] += a3;
+            }
+            u32x2 o;
+            o.x = (uint32_t)f32_to_f16_bits(v[0]) | ((uint32_t)f32_to_f16_bits(v[1]) << 16);
+            o.y = (uint32_t)f32_to_f16_bits(v[2]) | ((uint32_t)f32_to_f16_bits(v[3]) << 16);
+            *(u32x2*)(p.Y + (size_t)m * p.N + nt * 16 + 4 * h) = o;
+        }
+    }
+    if (tid == 0) __hip_atomic_store(&p.counters[tile], 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+
+template <int TM, int TN>
+hipError_t launch_shape(const GemmParams& p, const Plan& plan, int group, hipStream_t stream)
+{
+    dim3 grid(plan.grid), block(plan.block);
+    switch (group) {
+        case 128: hipLaunchKernelGGL((tile_kernel<TM, TN, 1>), grid, block, 0, stream, p); break;
+        case 64: hipLaunchKernelGGL((tile_kernel<TM, TN, 2>), grid, block, 0, stream, p); break;
+        case 32: hipLaunchKernelGGL((tile_kernel<TM, TN, 4>), grid, block, 0, stream, p); break;
+        default: return hipErrorInvalidValue;
+    }
+    return hipGetLastError();
+}
+
+}  // namespace
+
+}  // namespace tmw4

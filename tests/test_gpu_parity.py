@@ -68,7 +68,7 @@ def test_pack_bit_exact_against_oracle_unpack(tm, oracle, K, N, g):
 
 # ------------------------------------------------------------------ GEMM: exact special cases
 
-@pytest.mark.parametrize("variant", [-1, 0, 1, 2, 3, 4, 5, 6, 7, 8])
+@pytest.mark.parametrize("variant", [-1, 0, 1, 2, 3, 4, 5, 6, 7, 8, 9, 10, 11])
 def test_one_hot_rows_return_dequantised_weights_bit_exactly(tm, oracle, variant):
     """X = one-hot rows: a single non-zero product per output, so the fp16-dequantised weight must come back
     exactly; pins layout, nibble order, group indexing and the conversion constants on the device."""
@@ -88,7 +88,7 @@ def test_one_hot_rows_return_dequantised_weights_bit_exactly(tm, oracle, variant
 
 
 @pytest.mark.parametrize("M,variant,split", [(4, -1, 0), (4, 0, 3), (12, 1, 2), (16, 2, 1), (30, 3, 1), (30, 4, 3),
-                                             (40, -1, 0), (31, 5, 1), (60, 6, 2), (100, 7, 0), (100, 7, 2),
+                                             (40, -1, 0), (31, 5, 1), (60, 6, 2), (100, 7, 0), (200, 7, 2),
                                              (100, 8, 1)])
 def test_integer_exact_case(tm, oracle, M, variant, split):
     """s = 1 and small integer activations: every partial sum is an exactly representable integer, so any
@@ -133,10 +133,11 @@ def test_small_shapes_auto_plan(tm, oracle, M, K, N, g):
 @pytest.mark.parametrize("variant,split,waves", [(0, 1, 8), (0, 2, 16), (0, 5, 8), (1, 1, 16), (1, 3, 8), (2, 1, 8),
                                                  (2, 2, 16), (3, 1, 8), (3, 3, 16), (4, 1, 16), (4, 2, 8), (5, 1, 0),
                                                  (5, 3, 0), (6, 1, 0), (6, 2, 0), (7, 1, 0), (7, 3, 0), (8, 1, 0),
-                                                 (8, 2, 0)])
+                                                 (8, 2, 0), (9, 1, 0), (9, 2, 0), (10, 1, 0), (10, 3, 0),
+                                                 (11, 1, 0), (11, 2, 0)])
 @pytest.mark.parametrize("g", [32, 64, 128])
 def test_every_variant_and_split(tm, oracle, variant, split, waves, g):
-    M = {0: 13, 1: 9, 2: 16, 3: 29, 4: 32, 5: 30, 6: 50}.get(variant, 150)
+    M = {0: 13, 1: 9, 2: 16, 3: 29, 4: 32, 5: 30, 6: 50, 8: 300, 9: 70, 11: 200}.get(variant, 150)
     tm.tm_set_waves(waves)
     K, N = 1152, 336
     d = _random_problem(variant * 10 + split, M, K, N, g)
