@@ -8,7 +8,8 @@ import ctypes
 import os
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
-_LIB_PATH = os.path.join(_HERE, "libtm_w4.so")
+# TM_W4_LIB names another build of the same library (A/B comparisons of kernel variants); default: the in-tree build.
+_LIB_PATH = os.environ.get("TM_W4_LIB") or os.path.join(_HERE, "libtm_w4.so")
 _lib = None
 
 TM_OK = 0

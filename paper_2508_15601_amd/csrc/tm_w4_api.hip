@@ -414,6 +414,7 @@ const char* tm_variant_name(int variant)
         case kTile64x128: return "tile64x128";
         case kTile128x128: return "tile128x128";
         case kTile192x256: return "tile192x256";
+        case kTile128x512: return "tile128x512";
         default: return "";
     }
 }

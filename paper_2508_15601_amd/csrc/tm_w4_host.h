@@ -22,13 +22,14 @@ enum Variant {
     kTile64x128 = 9,
     kTile128x128 = 10,
     kTile192x256 = 11,
-    kNumVariants = 12
+    kTile128x512 = 12,
+    kNumVariants = 13
 };
 inline bool is_skinny(int v) { return v <= kSkinny32x64; }
 inline int skinny_rows(int v) { return v <= kSkinny16x64 ? 16 : 32; }
 inline int skinny_ntw(int v) { return v == kSkinny16x16 ? 1 : ((v == kSkinny16x32 || v == kSkinny32x32) ? 2 : 4); }
-inline int tile_bm(int v) { return v == kTile32x256 ? 32 : ((v == kTile64x256 || v == kTile64x128) ? 64 : ((v == kTile128x256 || v == kTile128x128) ? 128 : (v == kTile192x256 ? 192 : 256))); }
-inline int tile_bn(int v) { return (v == kTile64x128 || v == kTile128x128) ? 128 : 256; }
+inline int tile_bm(int v) { return v == kTile32x256 ? 32 : ((v == kTile64x256 || v == kTile64x128) ? 64 : ((v == kTile128x256 || v == kTile128x128 || v == kTile128x512) ? 128 : (v == kTile192x256 ? 192 : 256))); }
+inline int tile_bn(int v) { return (v == kTile64x128 || v == kTile128x128) ? 128 : (v == kTile128x512 ? 512 : 256); }
 
 struct Plan {
     int variant;

@@ -7,7 +7,7 @@
 //
 // Differences from the paper's design: packed weights go from HBM/L2 straight into registers in matrix-core operand
 // order (no shared-memory stage, no matrix-load instruction, hence nothing to swizzle); only X passes through LDS,
-// in a padded row-major layout (144-byte pitch) that makes the 16-lane 128-bit fragment reads conflict-free.
+// in a padded row-major layout (160-byte pitch) in which the 128-bit fragment reads are bank-conflict-free.
 // The four waves of a CTA split the tile along N only, so every weight fragment is converted exactly once per CTA
 // and feeds TM MFMAs.  The weight fragment is the A operand, so a lane ends up with four consecutive columns of
 // one output row and stores them as one 8-byte word.  CTAs are numbered so that the CTAs resident on one XCD
@@ -20,7 +20,12 @@ namespace tmw4 {
 namespace {
 
 constexpr int kHalfK = 64;                 // K depth of one LDS stage (half a packed unit)
-constexpr int kPitch = kHalfK + 8;         // LDS row pitch in halves (144 bytes)
+#ifndef TM_TILE_PITCH
+#define TM_TILE_PITCH (kHalfK + 16)
+#endif
+constexpr int kPitch = TM_TILE_PITCH;      // LDS row pitch in halves: 160 bytes, the pitch at which the profiler's
+                                           // SQ_LDS_BANK_CONFLICT reads zero for the 128-bit fragment reads
+                                           // (144 and 176 bytes both show 4 conflict cycles per read)
 constexpr int kPanelN = 8;                 // output tiles per panel row (XCD-local rasterisation)
 
 typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));

@@ -9,13 +9,14 @@ hipError_t launch_tile_large(const GemmParams& p, const Plan& plan, int group, h
     switch (plan.variant) {
         case kTile256x256: return launch_shape<16, 4>(p, plan, group, stream);
         case kTile192x256: return launch_shape<12, 4>(p, plan, group, stream);
+        case kTile128x512: return launch_shape<8, 8>(p, plan, group, stream);
         default: return hipErrorInvalidValue;
     }
 }
 
 hipError_t launch_tile(const GemmParams& p, const Plan& plan, int group, hipStream_t stream)
 {
-    return (plan.variant == kTile256x256 || plan.variant == kTile192x256) ? launch_tile_large(p, plan, group, stream)
+    return (plan.variant == kTile256x256 || plan.variant == kTile192x256 || plan.variant == kTile128x512) ? launch_tile_large(p, plan, group, stream)
                                         : launch_tile_small(p, plan, group, stream);
 }
 
