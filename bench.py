@@ -185,6 +185,7 @@ def main():
     ap.add_argument("--eager", action="store_true", help="launch every kernel from the host instead of replaying HIP graphs")
     ap.add_argument("--only", default=None, help="restrict the workload to one 'layer:M' pair, e.g. cfg3_gate_up:1 (profiling)")
     ap.add_argument("--waves", type=int, default=0)
+    ap.add_argument("--stage-steps", type=int, default=0)
     ap.add_argument("--variant", type=int, default=-1)
     ap.add_argument("--split-k", type=int, default=0)
     args = ap.parse_args()
@@ -199,7 +200,7 @@ def main():
     torch.cuda.set_device(0)
     tm.load_library()
     tm.tm_set_variant(args.variant, args.split_k)
-    tm.tm_set_waves(args.waves)
+    tm.tm_set_launch(args.waves, args.stage_steps)
 
     if args.workload == "copy":
         # plain 128-bit copy of known size: calibrates the profiler's FETCH_SIZE / WRITE_SIZE counters

@@ -118,8 +118,12 @@ TM_API int tm_packed_raw(const tm_packed_w4* packed, const void** weights, size_
  */
 TM_API int tm_get_plan(const tm_packed_w4* packed, int M, int* variant, int* split_k, int* grid, int* block);
 TM_API int tm_set_variant(int variant, int split_k);
-/* Waves per CTA of the skinny (M <= 32) kernels, which split K inside the CTA: 8, 16, or 0 for automatic. */
-TM_API int tm_set_waves(int waves);
+/*
+ * Two more launch parameters for sweeps, 0 = automatic: waves per CTA of the skinny (M <= 32) kernels, which split K
+ * inside the CTA (8 or 16), and MFMA steps of 32 K-rows per pipeline stage of the tile kernels (2, 4 or 8; a request
+ * the shape cannot honour falls back to the nearest valid depth).
+ */
+TM_API int tm_set_launch(int waves, int stage_steps);
 TM_API const char* tm_variant_name(int variant);
 
 /*

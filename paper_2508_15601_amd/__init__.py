@@ -5,6 +5,6 @@ every step of the method runs in the library's HIP kernels.  PyTorch supplies de
 """
 from .binding import (  # noqa: F401
     PackedW4, TmError, lib_path, load_library, tm_bench_copy, tm_bench_read, tm_gemm_w4a16, tm_gemm_w4a16_ws,
-    tm_gemm_workspace_bytes, tm_get_plan, tm_last_error, tm_pack_w4, tm_packed_raw, tm_set_variant, tm_set_waves, tm_unpack_w4,
+    tm_gemm_workspace_bytes, tm_get_plan, tm_last_error, tm_pack_w4, tm_packed_raw, tm_set_variant, tm_set_launch, tm_unpack_w4,
     tm_variant_name, tm_version,
 )

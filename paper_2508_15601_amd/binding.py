@@ -60,8 +60,8 @@ def load_library():
     lib.tm_get_plan.argtypes = [vp, i, c.POINTER(i), c.POINTER(i), c.POINTER(i), c.POINTER(i)]
     lib.tm_set_variant.restype = i
     lib.tm_set_variant.argtypes = [i, i]
-    lib.tm_set_waves.restype = i
-    lib.tm_set_waves.argtypes = [i]
+    lib.tm_set_launch.restype = i
+    lib.tm_set_launch.argtypes = [i, i]
     lib.tm_variant_name.restype = c.c_char_p
     lib.tm_variant_name.argtypes = [i]
     lib.tm_bench_copy.restype = i
@@ -219,8 +219,8 @@ def tm_set_variant(variant: int = -1, split_k: int = 0):
     _check(load_library().tm_set_variant(variant, split_k))
 
 
-def tm_set_waves(waves: int = 0):
-    _check(load_library().tm_set_waves(waves))
+def tm_set_launch(waves: int = 0, stage_steps: int = 0):
+    _check(load_library().tm_set_launch(waves, stage_steps))
 
 
 def tm_variant_name(variant: int) -> str:

@@ -45,6 +45,7 @@ std::mutex g_mutex;
 int g_force_variant = -1;
 int g_force_split = 0;
 int g_force_waves = 0;
+int g_force_stage = 0;
 
 // Current device must be gfx950; result cached per device.
 int check_device(int* dev_out)
@@ -162,7 +163,7 @@ Plan make_plan(const tm_packed_w4* h, int M, int num_cu)
     } else {
         pl.tiles_m = ceil_div(M, tile_bm(variant));
         pl.tiles_n = ceil_div(h->N, tile_bn(variant));
-        pl.block = 256;
+        pl.block = (unsigned)tile_threads(variant);
         int tiles = pl.tiles_m * pl.tiles_n;
         int want = (2 * num_cu) / tiles;           // fill the chip about twice over ...
         if (want > 4) want = 4;                    // ... but every split costs a full fp32 pass over the output
@@ -174,6 +175,22 @@ Plan make_plan(const tm_packed_w4* h, int M, int num_cu)
     if (split > max_split_ws) split = max_split_ws;
     if (split < 1) split = 1;
     pl.ku_per_split = ceil_div(KU, split);
+    pl.stage_steps = 2;
+    if (!is_skinny(variant)) {
+        // Stage depth: short tiles finish the MFMAs of a 64-deep stage long before the next stage can arrive, so
+        // they take stages one or two packed units deep; tall tiles keep 64-deep stages (smaller LDS, two CTAs/CU).
+        const int bm = tile_bm(variant);
+        int steps = bm <= 64 ? 8 : 2;
+        if (g_force_stage > 0) steps = g_force_stage;
+        if (bm > 128 || variant == kTile128x512) steps = 2;
+        if (bm == 128 && steps == 8) steps = 4;
+        if (variant == kTile128x256 && steps == 4) steps = 2;      // register budget of the 128 x 256 tile
+        if (steps == 8) {                          // two-unit stages need an even number of units in every split
+            if (pl.ku_per_split % 2) ++pl.ku_per_split;
+            if (KU % 2) steps = 4;
+        }
+        pl.stage_steps = steps;
+    }
     split = ceil_div(KU, pl.ku_per_split);         // drop empty splits
     pl.split = split;
     if (is_skinny(variant)) {
@@ -392,10 +409,13 @@ int tm_set_variant(int variant, int split_k)
     return TM_OK;
 }
 
-int tm_set_waves(int waves)
+int tm_set_launch(int waves, int stage_steps)
 {
     if (waves != 0 && waves != 8 && waves != 16) return fail(TM_EINVAL, "waves must be 0 (auto), 8 or 16");
+    if (stage_steps != 0 && stage_steps != 2 && stage_steps != 4 && stage_steps != 8)
+        return fail(TM_EINVAL, "stage_steps must be 0 (auto), 2, 4 or 8");
     g_force_waves = waves;
+    g_force_stage = stage_steps;
     return TM_OK;
 }
 
@@ -415,6 +435,7 @@ const char* tm_variant_name(int variant)
         case kTile128x128: return "tile128x128";
         case kTile192x256: return "tile192x256";
         case kTile128x512: return "tile128x512";
+        case kTile32x128: return "tile32x128";
         default: return "";
     }
 }

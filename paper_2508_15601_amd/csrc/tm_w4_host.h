@@ -23,18 +23,21 @@ enum Variant {
     kTile128x128 = 10,
     kTile192x256 = 11,
     kTile128x512 = 12,
-    kNumVariants = 13
+    kTile32x128 = 13,
+    kNumVariants = 14
 };
 inline bool is_skinny(int v) { return v <= kSkinny32x64; }
 inline int skinny_rows(int v) { return v <= kSkinny16x64 ? 16 : 32; }
 inline int skinny_ntw(int v) { return v == kSkinny16x16 ? 1 : ((v == kSkinny16x32 || v == kSkinny32x32) ? 2 : 4); }
-inline int tile_bm(int v) { return v == kTile32x256 ? 32 : ((v == kTile64x256 || v == kTile64x128) ? 64 : ((v == kTile128x256 || v == kTile128x128 || v == kTile128x512) ? 128 : (v == kTile192x256 ? 192 : 256))); }
-inline int tile_bn(int v) { return (v == kTile64x128 || v == kTile128x128) ? 128 : (v == kTile128x512 ? 512 : 256); }
+inline int tile_bm(int v) { return (v == kTile32x256 || v == kTile32x128) ? 32 : ((v == kTile64x256 || v == kTile64x128) ? 64 : ((v == kTile128x256 || v == kTile128x128 || v == kTile128x512) ? 128 : (v == kTile192x256 ? 192 : 256))); }
+inline int tile_threads(int) { return 256; }
+inline int tile_bn(int v) { return (v == kTile64x128 || v == kTile128x128 || v == kTile32x128) ? 128 : (v == kTile128x512 ? 512 : 256); }
 
 struct Plan {
     int variant;
     int split;
     int ku_per_split;
+    int stage_steps;      // tile kernels: MFMA steps (32 rows of K each) per pipeline stage: 2, 4 or 8
     int tiles_m, tiles_n;
     unsigned grid;
     unsigned block;

@@ -29,11 +29,12 @@ struct LaneOffsets {
     uint32_t w;                 // lane * 16 inside a 1 KiB unit
     uint32_t sz;                // (lane % 16) * 4 inside a 64-byte scale/zero row
     uint32_t x[TM];             // row(mt, lane) * K * 2 + (lane / 16) * 16 inside X
+    bool live[TM];              // row(mt, lane) < M: only these lanes load activations
 };
 
 template <int TM, int NTW, int GPU>
-__device__ __forceinline__ void load_stage(Stage<TM, NTW, GPU>& st, const GemmParams& p, const LaneOffsets<TM>& lo,
-                                           int nt0, int ku)
+__device__ __forceinline__ void load_weights(Stage<TM, NTW, GPU>& st, const GemmParams& p, const LaneOffsets<TM>& lo,
+                                             int nt0, int ku)
 {
 #pragma unroll
     for (int j = 0; j < NTW; ++j) {
@@ -50,12 +51,31 @@ __device__ __forceinline__ void load_stage(Stage<TM, NTW, GPU>& st, const GemmPa
             for (int g = 0; g < GPU; ++g) st.sz[j][g] = 0;
         }
     }
+}
+
+template <int TM, int NTW, int GPU>
+__device__ __forceinline__ void load_activations(Stage<TM, NTW, GPU>& st, const GemmParams& p,
+                                                 const LaneOffsets<TM>& lo, int ku)
+{
     const char* xb = (const char*)p.X + (size_t)ku * (kUnitK * 2);
 #pragma unroll
     for (int mt = 0; mt < TM; ++mt)
 #pragma unroll
-        for (int t = 0; t < 4; ++t)                // k = 128*ku + 32*t + 8*h .. +7
-            st.xf[mt][t] = *(const u32x4*)(xb + lo.x[mt] + 64 * t);
+        for (int t = 0; t < 4; ++t) {              // k = 128*ku + 32*t + 8*h .. +7
+            // Lanes whose row is past M keep an unspecified value instead of loading: row i of an MFMA result
+            // depends only on row i of this operand, and rows past M are never stored.
+            u32x4 v = __builtin_nondeterministic_value(v);
+            if (lo.live[mt]) v = *(const u32x4*)(xb + lo.x[mt] + 64 * t);
+            st.xf[mt][t] = v;
+        }
+}
+
+template <int TM, int NTW, int GPU>
+__device__ __forceinline__ void load_stage(Stage<TM, NTW, GPU>& st, const GemmParams& p, const LaneOffsets<TM>& lo,
+                                           int nt0, int ku)
+{
+    load_weights(st, p, lo, nt0, ku);
+    load_activations(st, p, lo, ku);
 }
 
 // One unit of NTW column tiles.  Paper Sec. 3.1 step (iii) / Sec. 4.3 split differently between the units of the
@@ -95,7 +115,7 @@ __device__ __forceinline__ void compute_stage(const Stage<TM, NTW, GPU>& st, f32
     }
 }
 
-// TM 16-row tiles, NTW 16-column tiles per wave, GPU K-groups per 128-row unit, D units in flight per wave,
+// TM 16-row tiles, NTW 16-column tiles per wave, GPU K-groups per 128-row unit, D register stages per wave,
 // MAXW the largest CTA (in waves) this instantiation is launched with.
 template <int TM, int NTW, int GPU, int D, int MAXW>
 __global__ __launch_bounds__(MAXW * 64) void skinny_kernel(GemmParams p)
@@ -120,8 +140,8 @@ __global__ __launch_bounds__(MAXW * 64) void skinny_kernel(GemmParams p)
     lo.sz = (lane & 15) * 4;
 #pragma unroll
     for (int mt = 0; mt < TM; ++mt) {
-        int row = mt * 16 + (lane & 15);
-        row = row < p.M ? row : p.M - 1;           // rows past M repeat the last row; their outputs are dropped
+        const int row = mt * 16 + (lane & 15);
+        lo.live[mt] = row < p.M;
         lo.x[mt] = (uint32_t)row * (uint32_t)p.K * 2u + (lane >> 4) * 16;
     }
 
@@ -131,14 +151,25 @@ __global__ __launch_bounds__(MAXW * 64) void skinny_kernel(GemmParams p)
 #pragma unroll
         for (int j = 0; j < NTW; ++j) acc[mt][j] = f32x4{0.f, 0.f, 0.f, 0.f};
 
-    for (int ku = ku0 + wave; ku < ku1; ku += D * waves) {
+    // Rolling prefetch (the memory pipeline of paper Sec. 4.3): a ring of D register stages; while the unit in
+    // stage r is converted and multiplied, the loads of the next D-1 units of this wave are in flight.
+    {
         Stage<TM, NTW, GPU> st[D];
+        const int first = ku0 + wave;
 #pragma unroll
-        for (int d = 0; d < D; ++d)
-            if (ku + d * waves < ku1) load_stage(st[d], p, lo, nt0, ku + d * waves);
+        for (int r = 0; r < D - 1; ++r)
+            if (first + r * waves < ku1) load_stage(st[r], p, lo, nt0, first + r * waves);
+        for (int base = first; base < ku1; base += D * waves) {
 #pragma unroll
-        for (int d = 0; d < D; ++d)
-            if (ku + d * waves < ku1) compute_stage(st[d], acc, mg);
+            for (int r = 0; r < D; ++r) {
+                const int cur = base + r * waves;
+                if (cur < ku1) {
+                    const int pre = cur + (D - 1) * waves;
+                    if (pre < ku1) load_stage(st[(r + D - 1) % D], p, lo, nt0, pre);
+                    compute_stage(st[r], acc, mg);
+                }
+            }
+        }
     }
 
     // Reduce the waves' tiles through LDS, one 16-row tile at a time; thread -> (row, two adjacent columns).
@@ -229,7 +260,7 @@ hipError_t launch_skinny(const GemmParams& p, const Plan& plan, int group, hipSt
         case kSkinny16x32: return w16 ? launch_cfg<1, 2, 2, 16>(p, plan, group, stream) : launch_cfg<1, 2, 4, 8>(p, plan, group, stream);
         case kSkinny16x64: return w16 ? launch_cfg<1, 4, 1, 16>(p, plan, group, stream) : launch_cfg<1, 4, 2, 8>(p, plan, group, stream);
         case kSkinny32x32: return w16 ? launch_cfg<2, 2, 1, 16>(p, plan, group, stream) : launch_cfg<2, 2, 2, 8>(p, plan, group, stream);
-        case kSkinny32x64: return launch_cfg<2, 4, 1, 8>(p, plan, group, stream);
+        case kSkinny32x64: return launch_cfg<2, 4, 2, 8>(p, plan, group, stream);
         default: return hipErrorInvalidValue;
     }
 }

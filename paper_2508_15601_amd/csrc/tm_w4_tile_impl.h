@@ -1,17 +1,21 @@
 // Fused dequantise-and-multiply for M > 32: CTA tiles with the activations staged through LDS.
 //
 // Online stage of the GEMM pipeline (paper Sec. 3.1 steps (i)-(iv)) with the software-pipelined main loop of
-// Sec. 4.3: while the matrix cores work on one 64-deep K slice, the vector ALUs convert the weight fragments of
-// that slice (I2F, then zero-point and scale: one exact subtract and one rounded multiply per weight) between the
-// MFMAs, and the memory units fetch the next X slice and the next half-unit of packed weights.
+// Sec. 4.3: while the matrix cores work on one 32-deep K step, the vector ALUs convert the weight fragments of
+// the next step (I2F, then zero-point and scale: one exact subtract and one rounded multiply per weight) between
+// the MFMAs, and the memory units fetch the next stage of X and of packed weights.
 //
 // Differences from the paper's design: packed weights go from HBM/L2 straight into registers in matrix-core operand
 // order (no shared-memory stage, no matrix-load instruction, hence nothing to swizzle); only X passes through LDS,
-// in a padded row-major layout (160-byte pitch) in which the 128-bit fragment reads are bank-conflict-free.
+// in a padded row-major layout in which the 128-bit fragment reads are bank-conflict-free.
 // The four waves of a CTA split the tile along N only, so every weight fragment is converted exactly once per CTA
 // and feeds TM MFMAs.  The weight fragment is the A operand, so a lane ends up with four consecutive columns of
 // one output row and stores them as one 8-byte word.  CTAs are numbered so that the CTAs resident on one XCD
 // (one L2) cover a compact block of output tiles.
+//
+// A pipeline stage is KW MFMA steps (32*KW rows of K) deep.  Tall tiles use 64-deep stages (their MFMA time per
+// stage already exceeds the memory latency); short tiles use 128- or 256-deep stages, because with few rows the
+// MFMAs of a 64-deep stage finish long before the next stage can arrive from L2/HBM.
 #pragma once
 #include "tm_w4_host.h"
 
@@ -19,24 +23,33 @@ namespace tmw4 {
 
 namespace {
 
-constexpr int kHalfK = 64;                 // K depth of one LDS stage (half a packed unit)
-#ifndef TM_TILE_PITCH
-#define TM_TILE_PITCH (kHalfK + 16)
-#endif
-constexpr int kPitch = TM_TILE_PITCH;      // LDS row pitch in halves: 160 bytes, the pitch at which the profiler's
-                                           // SQ_LDS_BANK_CONFLICT reads zero for the 128-bit fragment reads
-                                           // (144 and 176 bytes both show 4 conflict cycles per read)
 constexpr int kPanelN = 8;                 // output tiles per panel row (XCD-local rasterisation)
+
+// LDS row pitch in halves for a stage of `bk` halves: 16 halves (32 bytes) of padding.  With 64-deep stages that is
+// 160 bytes, the pitch at which the profiler's SQ_LDS_BANK_CONFLICT reads zero for the 128-bit fragment reads
+// (144 and 176 bytes both show 4 conflict cycles per read).
+#ifndef TM_TILE_PAD
+#define TM_TILE_PAD 16
+#endif
+constexpr int tile_pitch(int bk) { return bk + TM_TILE_PAD; }
 
 typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
 
-// CTA tile = (TM*16) rows x (4*TN*16) columns; wave w owns columns [w*TN*16, (w+1)*TN*16) and all rows.
-template <int TM, int TN, int GPU>
-__global__ __launch_bounds__(256) void tile_kernel(GemmParams p)
+// CTA tile = (TM*16) rows x (NW*TN*16) columns; wave w of NW owns columns [w*TN*16, (w+1)*TN*16) and all rows.
+// GPU = K-groups per 128-row unit, KW = MFMA steps per pipeline stage (2, 4 or 8).
+// An X fragment read from LDS (1 KiB per wave) feeds TN MFMAs.
+template <int TM, int TN, int NW, int GPU, int KW>
+__global__ __launch_bounds__(NW * 64) void tile_kernel(GemmParams p)
 {
-    constexpr int BM = TM * 16, BN = 4 * TN * 16;
-    constexpr int CH = (BM * 8 + 255) / 256;   // 16-byte chunks of one X stage per thread (BM rows x 8 chunks)
-    constexpr int GH = GPU == 4 ? 2 : 1;       // K-groups touched by one 64-deep half-step
+    constexpr int NT_ = NW * 64;                           // threads per CTA
+    constexpr int BM = TM * 16, BN = NW * TN * 16;
+    constexpr int BK = 32 * KW;                            // halves of K per stage
+    constexpr int kPitch = tile_pitch(BK);
+    constexpr int CPR = BK / 8;                            // 16-byte chunks per X row and stage
+    constexpr int CH = (BM * CPR + NT_ - 1) / NT_;         // chunks per thread and stage
+    constexpr int SG = (KW * GPU) / 4 > 0 ? (KW * GPU) / 4 : 1;   // K-groups touched by one stage
+    constexpr int UW = KW > 4 ? KW / 4 : 1;                // packed units touched by one stage
+    constexpr int WPU = KW > 4 ? 4 : KW;                   // words of a unit used by one stage
     __shared__ __attribute__((aligned(16))) uint16_t xs[2][BM * kPitch];
     __shared__ uint32_t s_last;
 
@@ -62,8 +75,9 @@ __global__ __launch_bounds__(256) void tile_kernel(GemmParams p)
 
     const int m0 = tile_m * BM;
     const int nt0 = (tile_n * BN) / 16 + wave * TN;        // first 16-column tile of this wave
-    const int hs0 = 2 * sk * p.ku_per_split;
-    const int hs1 = 2 * min(p.KU, (sk + 1) * p.ku_per_split);
+    // stages of this CTA's K range (the host makes ku_per_split a multiple of UW when KW > 4)
+    const int st0 = (sk * p.ku_per_split * 4) / KW;
+    const int st1 = (min(p.KU, (sk + 1) * p.ku_per_split) * 4) / KW;
 
     f32x4 acc[TM][TN];
 #pragma unroll
@@ -71,55 +85,69 @@ __global__ __launch_bounds__(256) void tile_kernel(GemmParams p)
 #pragma unroll
         for (int j = 0; j < TN; ++j) acc[i][j] = f32x4{0.f, 0.f, 0.f, 0.f};
 
-    // global -> register staging of one X stage: thread owns chunks idx = i*256 + tid -> (row idx/8, chunk idx%8)
+    // global -> register staging of one X stage: chunk idx = i*NT_ + tid -> (row idx / CPR, 16-byte column idx % CPR)
     u32x4 xreg[CH];
-    const int xrow0 = m0 + (tid >> 3);         // chunk i of this thread sits 32*i rows further down
-    const uint32_t xcol = (tid & 7) * 16;
-    auto load_x = [&](int hs) {
-        const char* xb = (const char*)p.X + (size_t)hs * (kHalfK * 2) + xcol;
+    auto load_x = [&](int st) {
+        const char* xb = (const char*)p.X + (size_t)st * (BK * 2);
 #pragma unroll
-        for (int i = 0; i < CH; ++i)
-            if (BM * 8 % 256 == 0 || i * 256 + tid < BM * 8) {
-                const int row = min(xrow0 + 32 * i, p.M - 1);          // rows past M repeat the last row
-                xreg[i] = *(const u32x4*)(xb + (uint32_t)row * (uint32_t)p.K * 2u);   // M*K < 2^31 (host check)
+        for (int i = 0; i < CH; ++i) {
+            const int idx = i * NT_ + tid;
+            if ((BM * CPR) % NT_ == 0 || idx < BM * CPR) {
+                const int row = min(m0 + idx / CPR, p.M - 1);          // rows past M repeat the last row
+                xreg[i] = *(const u32x4*)(xb + (uint32_t)row * (uint32_t)p.K * 2u + (idx % CPR) * 16);
             }
+        }
     };
     auto store_x = [&](int buf) {
 #pragma unroll
         for (int i = 0; i < CH; ++i) {
-            int idx = i * 256 + tid;
-            if (BM * 8 % 256 == 0 || idx < BM * 8)
-                *(u32x4*)(&xs[buf][(idx >> 3) * kPitch + (idx & 7) * 8]) = xreg[i];
+            const int idx = i * NT_ + tid;
+            if ((BM * CPR) % NT_ == 0 || idx < BM * CPR)
+                *(u32x4*)(&xs[buf][(idx / CPR) * kPitch + (idx % CPR) * 8]) = xreg[i];
         }
     };
 
-    // packed weights of one half-step: the lane's words t = 2*half, 2*half+1 of each n-tile's unit
-    u32x2 wq[TN], wq_next[TN];
-    uint32_t sz[TN][GH], sz_next[TN][GH];
-    auto load_w = [&](u32x2 (&w)[TN], uint32_t (&s)[TN][GH], int hs) {
-        const int ku = hs >> 1, half = hs & 1;
+    // packed weights of one stage: words [st*KW, st*KW + KW) of the lane's K sequence, for each n-tile
+    uint32_t wq[TN][KW], wq_next[TN][KW];
+    uint32_t sz[TN][SG], sz_next[TN][SG];
+    auto load_w = [&](uint32_t (&w)[TN][KW], uint32_t (&s)[TN][SG], int st) {
+        const int ku = (st * KW) / 4;                      // first unit of the stage
+        const int word0 = (st * KW) % 4;                   // first word inside it (non-zero only for KW == 2)
+        const int grp0 = (st * KW * GPU) / 4;              // first K-group of the stage
 #pragma unroll
         for (int j = 0; j < TN; ++j) {
             // wave-uniform; tiles past the edge re-read the last valid tile (their results are never stored),
             // which keeps the K loop free of branches
             const int nt = min(nt0 + j, p.NT - 1);
-            const char* wb = (const char*)p.W + ((size_t)nt * p.KU + ku) * 1024 + half * 8;
-            w[j] = *(const u32x2*)(wb + lane * 16);
+            const char* wb = (const char*)p.W + ((size_t)nt * p.KU + ku) * 1024 + word0 * 4 + lane * 16;
 #pragma unroll
-            for (int g = 0; g < GH; ++g) {
-                const int grp = GPU == 1 ? ku : (GPU == 2 ? 2 * ku + half : 4 * ku + 2 * half + g);
-                s[j][g] = *(const uint32_t*)((const char*)p.SZ + ((size_t)nt * p.G + grp) * 64 + c * 4);
+            for (int u = 0; u < UW; ++u) {
+                if constexpr (WPU == 2) {
+                    const u32x2 v = *(const u32x2*)(wb + u * 1024);
+                    w[j][0] = v.x;
+                    w[j][1] = v.y;
+                } else {
+                    const u32x4 v = *(const u32x4*)(wb + u * 1024);
+                    w[j][4 * u + 0] = v.x;
+                    w[j][4 * u + 1] = v.y;
+                    w[j][4 * u + 2] = v.z;
+                    w[j][4 * u + 3] = v.w;
+                }
             }
+#pragma unroll
+            for (int g = 0; g < SG; ++g)
+                s[j][g] = *(const uint32_t*)((const char*)p.SZ + ((size_t)nt * p.G + grp0 + g) * 64 + c * 4);
         }
     };
+
     // One 32-deep MFMA step over the whole CTA-row tile, software-pipelined as in paper Sec. 4.3: while the
     // matrix cores consume the converted fragments `cur`, the vector ALU converts the fragments of the NEXT step
     // into `nxt`, a few at a time between groups of MFMAs, and LDS reads run one row-pair ahead of their use.
     // The scheduling barriers keep the compiler from hoisting all LDS reads and conversions to the top, which
     // would both starve the matrix cores and blow the register budget.
     constexpr int PAIRS = TM / 2;
-    auto step = [&](int buf, int tt, const f16x8 (&cur)[TN], f16x8 (&nxt)[TN],
-                    const u32x2 (&wsrc)[TN], const uint32_t (&ssrc)[TN][GH], int tt_next) {
+    auto step = [&](int buf, int tt, const f16x8 (&cur)[TN], f16x8 (&nxt)[TN], const uint32_t (&wsrc)[TN][KW],
+                    const uint32_t (&ssrc)[TN][SG], int tt_next) {
         const uint16_t* base = &xs[buf][c * kPitch + 32 * tt + 8 * h];
         f16x8 x0 = *(const f16x8*)(base);
         f16x8 x1 = *(const f16x8*)(base + 16 * kPitch);
@@ -133,7 +161,7 @@ __global__ __launch_bounds__(256) void tile_kernel(GemmParams p)
 #pragma unroll
             for (int j = 0; j < TN; ++j)
                 if (j * PAIRS / TN == ip)          // spread the TN conversions over the row pairs
-                    nxt[j] = dequant8(wsrc[j][tt_next], make_group_const(ssrc[j][GH == 2 ? tt_next : 0]), mg);
+                    nxt[j] = dequant8(wsrc[j][tt_next], make_group_const(ssrc[j][(tt_next * GPU) / 4 % SG]), mg);
 #pragma unroll
             for (int j = 0; j < TN; ++j) acc[2 * ip][j] = mfma16x16x32(cur[j], x0, acc[2 * ip][j]);
 #pragma unroll
@@ -144,28 +172,33 @@ __global__ __launch_bounds__(256) void tile_kernel(GemmParams p)
         }
     };
 
-    if (hs0 < hs1) {
+    if (st0 < st1) {
         f16x8 wfa[TN], wfb[TN];
-        load_x(hs0);
-        load_w(wq, sz, hs0);
+        load_x(st0);
+        load_w(wq, sz, st0);
         store_x(0);
 #pragma unroll
         for (int j = 0; j < TN; ++j) wfa[j] = dequant8(wq[j][0], make_group_const(sz[j][0]), mg);
         __syncthreads();
-        for (int hs = hs0; hs < hs1; ++hs) {
-            // The last iteration prefetches its own slice again instead of branching; the data is never used.
-            const int hn = min(hs + 1, hs1 - 1);
-            const int buf = (hs - hs0) & 1;
-            load_x(hn);
-            load_w(wq_next, sz_next, hn);
-            step(buf, 0, wfa, wfb, wq, sz, 1);
-            step(buf, 1, wfb, wfa, wq_next, sz_next, 0);
+        for (int st = st0; st < st1; ++st) {
+            // The last iteration prefetches its own stage again instead of branching; the data is never used.
+            const int sn = min(st + 1, st1 - 1);
+            const int buf = (st - st0) & 1;
+            load_x(sn);
+            load_w(wq_next, sz_next, sn);
+#pragma unroll
+            for (int tt = 0; tt < KW; tt += 2) {
+                step(buf, tt, wfa, wfb, wq, sz, tt + 1);
+                if (tt + 2 < KW) step(buf, tt + 1, wfb, wfa, wq, sz, tt + 2);
+                else step(buf, tt + 1, wfb, wfa, wq_next, sz_next, 0);
+            }
             store_x(buf ^ 1);
 #pragma unroll
             for (int j = 0; j < TN; ++j) {
-                wq[j] = wq_next[j];
 #pragma unroll
-                for (int g = 0; g < GH; ++g) sz[j][g] = sz_next[j][g];
+                for (int k = 0; k < KW; ++k) wq[j][k] = wq_next[j][k];
+#pragma unroll
+                for (int g = 0; g < SG; ++g) sz[j][g] = sz_next[j][g];
             }
             __syncthreads();
         }
@@ -237,14 +270,17 @@ __global__ __launch_bounds__(256) void tile_kernel(GemmParams p)
     if (tid == 0) __hip_atomic_store(&p.counters[tile], 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
 }
 
-template <int TM, int TN>
+// KW8: stages two packed units deep (needs an even number of units per K split, which the host checks);
+// otherwise one unit deep for short tiles and half a unit for tall ones.
+template <int TM, int TN, int NW, int KW>
 hipError_t launch_shape(const GemmParams& p, const Plan& plan, int group, hipStream_t stream)
 {
-    dim3 grid(plan.grid), block(plan.block);
+    dim3 grid(plan.grid), block(NW * 64);
+    if (plan.block != NW * 64) return hipErrorInvalidValue;
     switch (group) {
-        case 128: hipLaunchKernelGGL((tile_kernel<TM, TN, 1>), grid, block, 0, stream, p); break;
-        case 64: hipLaunchKernelGGL((tile_kernel<TM, TN, 2>), grid, block, 0, stream, p); break;
-        case 32: hipLaunchKernelGGL((tile_kernel<TM, TN, 4>), grid, block, 0, stream, p); break;
+        case 128: hipLaunchKernelGGL((tile_kernel<TM, TN, NW, 1, KW>), grid, block, 0, stream, p); break;
+        case 64: hipLaunchKernelGGL((tile_kernel<TM, TN, NW, 2, KW>), grid, block, 0, stream, p); break;
+        case 32: hipLaunchKernelGGL((tile_kernel<TM, TN, NW, 4, KW>), grid, block, 0, stream, p); break;
         default: return hipErrorInvalidValue;
     }
     return hipGetLastError();

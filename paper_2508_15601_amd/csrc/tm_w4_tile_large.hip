@@ -7,9 +7,9 @@ namespace tmw4 {
 hipError_t launch_tile_large(const GemmParams& p, const Plan& plan, int group, hipStream_t stream)
 {
     switch (plan.variant) {
-        case kTile256x256: return launch_shape<16, 4>(p, plan, group, stream);
-        case kTile192x256: return launch_shape<12, 4>(p, plan, group, stream);
-        case kTile128x512: return launch_shape<8, 8>(p, plan, group, stream);
+        case kTile256x256: return launch_shape<16, 4, 4, 2>(p, plan, group, stream);
+        case kTile192x256: return launch_shape<12, 4, 4, 2>(p, plan, group, stream);
+        case kTile128x512: return launch_shape<8, 8, 4, 2>(p, plan, group, stream);
         default: return hipErrorInvalidValue;
     }
 }

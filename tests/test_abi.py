@@ -56,7 +56,7 @@ def test_argument_validation_without_gpu(lib):
     lib.tm_free_packed(None)                      # must be a no-op
     assert lib.tm_set_variant(99, 0) == -1 and lib.tm_set_variant(-1, 0) == 0
     assert lib.tm_variant_name(0) == b"skinny16x16" and lib.tm_variant_name(99) == b""
-    assert lib.tm_set_waves(5) == -1 and lib.tm_set_waves(0) == 0
+    assert lib.tm_set_launch(5, 0) == -1 and lib.tm_set_launch(0, 3) == -1 and lib.tm_set_launch(0, 0) == 0
     assert lib.tm_bench_copy(None, None, 16, None) == -1
     assert tm.tm_version().startswith("tm_w4")
 
