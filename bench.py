@@ -308,8 +308,8 @@ def main():
 
     if args.workload == "decode" and not args.no_prefill:
         PL = Layer(tm, torch, wl, *WORKLOADS["prefill"][0])
-        pms, _ = time_steps(torch, lambda: PL.launch(tm, 4096), 10, 3)
-        t = pms / 10 * 1e-3
+        pms, _ = time_steps(torch, lambda: PL.launch(tm, 4096), 20, 5, graph_steps=5)
+        t = pms / 20 * 1e-3
         c = PL.case
         ptf = wl.flops(4096, c.K, c.N) / t / 1e12
         out["prefill"] = {"workload": "configs[3]: M=4096, K=8192, N=28672, group=128", "ms": t * 1e3, "TFLOPs": ptf,

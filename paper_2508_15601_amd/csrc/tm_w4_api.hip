@@ -128,7 +128,7 @@ Plan make_plan(const tm_packed_w4* h, int M, int num_cu)
         } else {
             // largest tile that still yields two CTAs per CU without splitting K; the smallest one otherwise
             const int cand[3] = {kTile128x256, kTile128x128, kTile64x128};
-            variant = M <= 64 ? kTile32x256 : kTile64x128;
+            variant = kTile64x128;
             if (M > 64)
                 for (int i = 0; i < 3; ++i) {
                     long t = (long)ceil_div(M, tile_bm(cand[i])) * ceil_div(h->N, tile_bn(cand[i]));
@@ -180,7 +180,7 @@ Plan make_plan(const tm_packed_w4* h, int M, int num_cu)
         // Stage depth: short tiles finish the MFMAs of a 64-deep stage long before the next stage can arrive, so
         // they take stages one or two packed units deep; tall tiles keep 64-deep stages (smaller LDS, two CTAs/CU).
         const int bm = tile_bm(variant);
-        int steps = bm <= 64 ? 8 : 2;
+        int steps = bm <= 64 ? 8 : (variant == kTile128x128 ? 4 : 2);
         if (g_force_stage > 0) steps = g_force_stage;
         if (bm > 128 || variant == kTile128x512) steps = 2;
         if (bm == 128 && steps == 8) steps = 4;
