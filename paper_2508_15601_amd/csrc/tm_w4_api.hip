@@ -118,13 +118,15 @@ Plan make_plan(const tm_packed_w4* h, int M, int num_cu)
     Plan pl{};
     int variant = g_force_variant;
     if (variant < 0) {
-        if (M <= 32) {
-            // widest strip that still gives about three quarters of the CUs a CTA of their own
-            const bool rows16 = M <= 16;
+        if (M <= 16) {
+            // One CTA per CU: the column tiles are dealt evenly over min(NT, #CU) strips (widths differ by at most
+            // one tile), because a CU sustains only ~25 GB/s of weight traffic and the slowest CU sets the time.
+            const int per_cu = ceil_div(NT, num_cu);
+            variant = per_cu <= 1 ? kSkinny16x16 : per_cu <= 2 ? kSkinny16x32 : per_cu <= 3 ? kSkinny16x48
+                    : per_cu <= 4 ? kSkinny16x64 : per_cu <= 6 ? kSkinny16x96 : kSkinny16x128;
+        } else if (M <= 32) {
             const int enough = (3 * num_cu) / 4;
-            if (NT / 4 >= enough) variant = rows16 ? kSkinny16x64 : kSkinny32x64;
-            else if (NT / 2 >= enough || !rows16) variant = rows16 ? kSkinny16x32 : kSkinny32x32;
-            else variant = kSkinny16x16;
+            variant = NT / 4 >= enough ? kSkinny32x64 : kSkinny32x32;
         } else {
             // largest tile that still yields two CTAs per CU without splitting K; the smallest one otherwise
             const int cand[3] = {kTile128x256, kTile128x128, kTile64x128};
@@ -148,12 +150,15 @@ Plan make_plan(const tm_packed_w4* h, int M, int num_cu)
     int split = 1;
     if (is_skinny(variant)) {
         const int ntw = skinny_ntw(variant);
-        const int strips = ceil_div(NT, ntw);
+        // fewest strips the variant can take; when chosen automatically for M <= 16 that is one strip per CU
+        int strips = ceil_div(NT, ntw);
+        if (g_force_variant < 0 && M <= 16 && NT >= num_cu && strips < num_cu) strips = num_cu;
         int waves = g_force_waves > 0 ? g_force_waves : ((strips <= num_cu && KU >= 32) ? 16 : 8);
-        if (waves < 2 * ntw) waves = 2 * ntw;      // the LDS reduction needs 128*ntw threads
+        if (waves < 2 * ntw) waves = 2 * ntw <= 8 ? 8 : 16;    // the LDS reduction needs 128*ntw threads
         if (variant == kSkinny32x64) waves = 8;    // its register footprint does not fit a 16-wave CTA
         pl.tiles_m = 1;
         pl.tiles_n = strips;
+        pl.strips = strips;
         pl.block = (unsigned)waves * 64;
         if (strips * 2 <= num_cu) {                // too few strips: split K across CTAs as well
             int want = ceil_div(num_cu, strips);
@@ -245,6 +250,7 @@ int run_gemm(const uint16_t* X, const tm_packed_w4* h, uint16_t* Y, int M, void*
     p.ku_per_split = pl.ku_per_split;
     p.tiles_m = pl.tiles_m;
     p.tiles_n = pl.tiles_n;
+    p.strips = pl.strips;
     hipError_t e = is_skinny(pl.variant) ? launch_skinny(p, pl, h->group, stream)
                                          : launch_tile(p, pl, h->group, stream);
     if (e != hipSuccess) return fail_hip(e, "kernel launch");
@@ -427,6 +433,9 @@ const char* tm_variant_name(int variant)
         case kSkinny16x64: return "skinny16x64";
         case kSkinny32x32: return "skinny32x32";
         case kSkinny32x64: return "skinny32x64";
+        case kSkinny16x48: return "skinny16x48";
+        case kSkinny16x96: return "skinny16x96";
+        case kSkinny16x128: return "skinny16x128";
         case kTile32x256: return "tile32x256";
         case kTile64x256: return "tile64x256";
         case kTile128x256: return "tile128x256";

@@ -32,6 +32,7 @@ struct GemmParams {
     int split;                // split-K factor (>= 1)
     int ku_per_split;         // k-units per split (ceil)
     int tiles_m, tiles_n;     // tile kernel only
+    int strips;               // skinny kernel only: strip s owns tiles [s*NT/strips, (s+1)*NT/strips)
 };
 
 __device__ __forceinline__ f16x2 as_f16x2(uint32_t u) { return __builtin_bit_cast(f16x2, u); }

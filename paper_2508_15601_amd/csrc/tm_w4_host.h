@@ -24,11 +24,25 @@ enum Variant {
     kTile192x256 = 11,
     kTile128x512 = 12,
     kTile32x128 = 13,
-    kNumVariants = 14
+    kSkinny16x48 = 14,  // M <= 16, up to three / six / eight 16-column tiles per wave
+    kSkinny16x96 = 15,
+    kSkinny16x128 = 16,
+    kNumVariants = 17
 };
-inline bool is_skinny(int v) { return v <= kSkinny32x64; }
-inline int skinny_rows(int v) { return v <= kSkinny16x64 ? 16 : 32; }
-inline int skinny_ntw(int v) { return v == kSkinny16x16 ? 1 : ((v == kSkinny16x32 || v == kSkinny32x32) ? 2 : 4); }
+inline bool is_skinny(int v) { return v <= kSkinny32x64 || (v >= kSkinny16x48 && v <= kSkinny16x128); }
+inline int skinny_rows(int v) { return (v == kSkinny32x32 || v == kSkinny32x64) ? 32 : 16; }
+// widest strip (in 16-column tiles) a skinny variant can take; narrower strips run with the surplus tiles idle
+inline int skinny_ntw(int v)
+{
+    switch (v) {
+        case kSkinny16x16: return 1;
+        case kSkinny16x32: case kSkinny32x32: return 2;
+        case kSkinny16x48: return 3;
+        case kSkinny16x64: case kSkinny32x64: return 4;
+        case kSkinny16x96: return 6;
+        default: return 8;
+    }
+}
 inline int tile_bm(int v) { return (v == kTile32x256 || v == kTile32x128) ? 32 : ((v == kTile64x256 || v == kTile64x128) ? 64 : ((v == kTile128x256 || v == kTile128x128 || v == kTile128x512) ? 128 : (v == kTile192x256 ? 192 : 256))); }
 inline int tile_threads(int) { return 256; }
 inline int tile_bn(int v) { return (v == kTile64x128 || v == kTile128x128 || v == kTile32x128) ? 128 : (v == kTile128x512 ? 512 : 256); }
@@ -37,6 +51,7 @@ struct Plan {
     int variant;
     int split;
     int ku_per_split;
+    int strips;           // skinny kernels: number of column strips the 16-column tiles are dealt into
     int stage_steps;      // tile kernels: MFMA steps (32 rows of K each) per pipeline stage: 2, 4 or 8
     int tiles_m, tiles_n;
     unsigned grid;

@@ -34,12 +34,12 @@ struct LaneOffsets {
 
 template <int TM, int NTW, int GPU>
 __device__ __forceinline__ void load_weights(Stage<TM, NTW, GPU>& st, const GemmParams& p, const LaneOffsets<TM>& lo,
-                                             int nt0, int ku)
+                                             int nt0, int ntw, int ku)
 {
 #pragma unroll
     for (int j = 0; j < NTW; ++j) {
         const int nt = nt0 + j;                    // wave-uniform
-        if (nt < p.NT) {
+        if (j < ntw) {
             const char* wb = (const char*)p.W + ((size_t)nt * p.KU + ku) * 1024;
             st.wq[j] = __builtin_nontemporal_load((const u32x4*)(wb + lo.w));
             const char* sb = (const char*)p.SZ + ((size_t)nt * p.G + (size_t)ku * GPU) * 64;
@@ -72,9 +72,9 @@ __device__ __forceinline__ void load_activations(Stage<TM, NTW, GPU>& st, const 
 
 template <int TM, int NTW, int GPU>
 __device__ __forceinline__ void load_stage(Stage<TM, NTW, GPU>& st, const GemmParams& p, const LaneOffsets<TM>& lo,
-                                           int nt0, int ku)
+                                           int nt0, int ntw, int ku)
 {
-    load_weights(st, p, lo, nt0, ku);
+    load_weights(st, p, lo, nt0, ntw, ku);
     load_activations(st, p, lo, ku);
 }
 
@@ -127,10 +127,12 @@ __global__ __launch_bounds__(MAXW * 64) void skinny_kernel(GemmParams p)
     const int lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);     // wave-uniform by construction
     const int waves = blockDim.x >> 6;
-    const int strips = (p.NT + NTW - 1) / NTW;
-    const int strip = blockIdx.x % strips;
-    const int sk = blockIdx.x / strips;
-    const int nt0 = strip * NTW;
+    // The NT column tiles are dealt evenly into p.strips strips (widths differ by at most one tile), so that a
+    // shape whose tile count is not a multiple of the CU count still loads every CU almost equally.
+    const int strip = blockIdx.x % p.strips;
+    const int sk = blockIdx.x / p.strips;
+    const int nt0 = (int)(((long)strip * p.NT) / p.strips);
+    const int ntw = (int)(((long)(strip + 1) * p.NT) / p.strips) - nt0;     // <= NTW (host guarantees)
     const int ku0 = sk * p.ku_per_split;
     const int ku1 = min(p.KU, ku0 + p.ku_per_split);
 
@@ -158,14 +160,14 @@ __global__ __launch_bounds__(MAXW * 64) void skinny_kernel(GemmParams p)
         const int first = ku0 + wave;
 #pragma unroll
         for (int r = 0; r < D - 1; ++r)
-            if (first + r * waves < ku1) load_stage(st[r], p, lo, nt0, first + r * waves);
+            if (first + r * waves < ku1) load_stage(st[r], p, lo, nt0, ntw, first + r * waves);
         for (int base = first; base < ku1; base += D * waves) {
 #pragma unroll
             for (int r = 0; r < D; ++r) {
                 const int cur = base + r * waves;
                 if (cur < ku1) {
                     const int pre = cur + (D - 1) * waves;
-                    if (pre < ku1) load_stage(st[(r + D - 1) % D], p, lo, nt0, pre);
+                    if (pre < ku1) load_stage(st[(r + D - 1) % D], p, lo, nt0, ntw, pre);
                     compute_stage(st[r], acc, mg);
                 }
             }
@@ -189,7 +191,7 @@ __global__ __launch_bounds__(MAXW * 64) void skinny_kernel(GemmParams p)
             for (int r = 0; r < 4; ++r) red[(wave * NTW * 4 + j * 4 + r) * 64 + lane] = acc[mt][j][r];
         __syncthreads();
         const int m = mt * 16 + row;
-        if (owner && m < p.M && n < p.N) {
+        if (owner && m < p.M && col < ntw * 16) {
             float v0 = 0.f, v1 = 0.f;
             for (int w = 0; w < waves; ++w) {
                 float2 t = *(const float2*)&red[(w * NTW * 4 + src_reg) * 64 + src_lane];
@@ -218,7 +220,7 @@ __global__ __launch_bounds__(MAXW * 64) void skinny_kernel(GemmParams p)
 #pragma unroll
             for (int mt = 0; mt < TM; ++mt) {
                 const int m = mt * 16 + row;
-                if (owner && m < p.M && n < p.N) {
+                if (owner && m < p.M && col < ntw * 16) {
                     float v0 = 0.f, v1 = 0.f;
                     for (int s = 0; s < p.split; ++s) {
                         float a, b;
@@ -235,16 +237,18 @@ __global__ __launch_bounds__(MAXW * 64) void skinny_kernel(GemmParams p)
     }
 }
 
-template <int TM, int NTW, int D, int MAXW>
+// D128 / DSMALL: register stages per wave for group 128 and for the smaller groups (which carry more scale/zero
+// words per unit and would spill with the deeper ring).
+template <int TM, int NTW, int D128, int DSMALL, int MAXW>
 hipError_t launch_cfg(const GemmParams& p, const Plan& plan, int group, hipStream_t stream)
 {
     dim3 grid(plan.grid), block(plan.block);
     if (plan.block > MAXW * 64) return hipErrorInvalidValue;
     size_t lds = (size_t)(plan.block / 64) * NTW * 4 * 64 * sizeof(float);
     switch (group) {
-        case 128: hipLaunchKernelGGL((skinny_kernel<TM, NTW, 1, D, MAXW>), grid, block, lds, stream, p); break;
-        case 64: hipLaunchKernelGGL((skinny_kernel<TM, NTW, 2, D, MAXW>), grid, block, lds, stream, p); break;
-        case 32: hipLaunchKernelGGL((skinny_kernel<TM, NTW, 4, D, MAXW>), grid, block, lds, stream, p); break;
+        case 128: hipLaunchKernelGGL((skinny_kernel<TM, NTW, 1, D128, MAXW>), grid, block, lds, stream, p); break;
+        case 64: hipLaunchKernelGGL((skinny_kernel<TM, NTW, 2, DSMALL, MAXW>), grid, block, lds, stream, p); break;
+        case 32: hipLaunchKernelGGL((skinny_kernel<TM, NTW, 4, DSMALL, MAXW>), grid, block, lds, stream, p); break;
         default: return hipErrorInvalidValue;
     }
     return hipGetLastError();
@@ -256,11 +260,14 @@ hipError_t launch_skinny(const GemmParams& p, const Plan& plan, int group, hipSt
 {
     const bool w16 = plan.block > 512;
     switch (plan.variant) {
-        case kSkinny16x16: return w16 ? launch_cfg<1, 1, 2, 16>(p, plan, group, stream) : launch_cfg<1, 1, 4, 8>(p, plan, group, stream);
-        case kSkinny16x32: return w16 ? launch_cfg<1, 2, 2, 16>(p, plan, group, stream) : launch_cfg<1, 2, 4, 8>(p, plan, group, stream);
-        case kSkinny16x64: return w16 ? launch_cfg<1, 4, 1, 16>(p, plan, group, stream) : launch_cfg<1, 4, 2, 8>(p, plan, group, stream);
-        case kSkinny32x32: return w16 ? launch_cfg<2, 2, 1, 16>(p, plan, group, stream) : launch_cfg<2, 2, 2, 8>(p, plan, group, stream);
-        case kSkinny32x64: return launch_cfg<2, 4, 2, 8>(p, plan, group, stream);
+        case kSkinny16x16: return w16 ? launch_cfg<1, 1, 3, 2, 16>(p, plan, group, stream) : launch_cfg<1, 1, 4, 4, 8>(p, plan, group, stream);
+        case kSkinny16x32: return w16 ? launch_cfg<1, 2, 2, 2, 16>(p, plan, group, stream) : launch_cfg<1, 2, 4, 4, 8>(p, plan, group, stream);
+        case kSkinny16x48: return w16 ? launch_cfg<1, 3, 2, 2, 16>(p, plan, group, stream) : launch_cfg<1, 3, 3, 3, 8>(p, plan, group, stream);
+        case kSkinny16x64: return w16 ? launch_cfg<1, 4, 2, 1, 16>(p, plan, group, stream) : launch_cfg<1, 4, 2, 2, 8>(p, plan, group, stream);
+        case kSkinny16x96: return w16 ? launch_cfg<1, 6, 1, 1, 16>(p, plan, group, stream) : hipErrorInvalidValue;
+        case kSkinny16x128: return w16 ? launch_cfg<1, 8, 1, 1, 16>(p, plan, group, stream) : hipErrorInvalidValue;
+        case kSkinny32x32: return w16 ? launch_cfg<2, 2, 2, 1, 16>(p, plan, group, stream) : launch_cfg<2, 2, 2, 2, 8>(p, plan, group, stream);
+        case kSkinny32x64: return launch_cfg<2, 4, 2, 2, 8>(p, plan, group, stream);
         default: return hipErrorInvalidValue;
     }
 }
