@@ -124,10 +124,15 @@ Plan make_plan(const tm_packed_w4* h, int M, int num_cu)
             const int per_cu = ceil_div(NT, num_cu);
             variant = per_cu <= 1 ? kSkinny16x16 : per_cu <= 2 ? kSkinny16x32 : per_cu <= 3 ? kSkinny16x48
                     : per_cu <= 4 ? kSkinny16x64 : per_cu <= 6 ? kSkinny16x96 : kSkinny16x128;
+        } else if (M <= 64 && ceil_div(NT, 4) * 2 <= num_cu) {
+            // narrow outputs (N <= 8192 on 256 CUs): 64-column strips with K split across CTAs so that every
+            // CU gets one CTA; each CTA then re-reads only its K slice of X
+            variant = kSkinny64x64;
         } else if (M <= 32) {
             const int enough = (3 * num_cu) / 4;
             variant = NT / 4 >= enough ? kSkinny32x64 : kSkinny32x32;
         } else {
+            // (M in 33..64 with wide outputs lands here too)
             // largest tile that still yields two CTAs per CU without splitting K; the smallest one otherwise
             const int cand[3] = {kTile128x256, kTile128x128, kTile64x128};
             variant = kTile64x128;
@@ -142,7 +147,7 @@ Plan make_plan(const tm_packed_w4* h, int M, int num_cu)
         }
     }
     if (is_skinny(variant) && M > skinny_rows(variant))        // a forced skinny variant must still cover M
-        variant = M <= 32 ? kSkinny32x64 : kTile64x256;
+        variant = M <= 32 ? kSkinny32x64 : (M <= 64 ? kSkinny64x64 : kTile64x256);
     pl.variant = variant;
     const size_t out_bytes = (size_t)M * h->N * sizeof(float);
     int max_split_ws = (int)(kPartialBudget / (out_bytes ? out_bytes : 1));
@@ -155,7 +160,7 @@ Plan make_plan(const tm_packed_w4* h, int M, int num_cu)
         if (g_force_variant < 0 && M <= 16 && NT >= num_cu && strips < num_cu) strips = num_cu;
         int waves = g_force_waves > 0 ? g_force_waves : ((strips <= num_cu && KU >= 32) ? 16 : 8);
         if (waves < 2 * ntw) waves = 2 * ntw <= 8 ? 8 : 16;    // the LDS reduction needs 128*ntw threads
-        if (variant == kSkinny32x64) waves = 8;    // its register footprint does not fit a 16-wave CTA
+        if (variant == kSkinny32x64 || skinny_rows(variant) == 64) waves = 8;   // register footprint: 8-wave CTAs only
         pl.tiles_m = 1;
         pl.tiles_n = strips;
         pl.strips = strips;
@@ -436,6 +441,9 @@ const char* tm_variant_name(int variant)
         case kSkinny16x48: return "skinny16x48";
         case kSkinny16x96: return "skinny16x96";
         case kSkinny16x128: return "skinny16x128";
+        case kSkinny64x32: return "skinny64x32";
+        case kSkinny64x48: return "skinny64x48";
+        case kSkinny64x64: return "skinny64x64";
         case kTile32x256: return "tile32x256";
         case kTile64x256: return "tile64x256";
         case kTile128x256: return "tile128x256";

@@ -27,18 +27,21 @@ enum Variant {
     kSkinny16x48 = 14,  // M <= 16, up to three / six / eight 16-column tiles per wave
     kSkinny16x96 = 15,
     kSkinny16x128 = 16,
-    kNumVariants = 17
+    kSkinny64x32 = 17,  // M <= 64, two / three / four tiles per wave, conversion on the ALU
+    kSkinny64x48 = 18,
+    kSkinny64x64 = 19,
+    kNumVariants = 20
 };
-inline bool is_skinny(int v) { return v <= kSkinny32x64 || (v >= kSkinny16x48 && v <= kSkinny16x128); }
-inline int skinny_rows(int v) { return (v == kSkinny32x32 || v == kSkinny32x64) ? 32 : 16; }
+inline bool is_skinny(int v) { return v <= kSkinny32x64 || (v >= kSkinny16x48 && v <= kSkinny64x64); }
+inline int skinny_rows(int v) { return (v == kSkinny32x32 || v == kSkinny32x64) ? 32 : (v >= kSkinny64x32 && v <= kSkinny64x64) ? 64 : 16; }
 // widest strip (in 16-column tiles) a skinny variant can take; narrower strips run with the surplus tiles idle
 inline int skinny_ntw(int v)
 {
     switch (v) {
         case kSkinny16x16: return 1;
-        case kSkinny16x32: case kSkinny32x32: return 2;
-        case kSkinny16x48: return 3;
-        case kSkinny16x64: case kSkinny32x64: return 4;
+        case kSkinny16x32: case kSkinny32x32: case kSkinny64x32: return 2;
+        case kSkinny16x48: case kSkinny64x48: return 3;
+        case kSkinny16x64: case kSkinny32x64: case kSkinny64x64: return 4;
         case kSkinny16x96: return 6;
         default: return 8;
     }

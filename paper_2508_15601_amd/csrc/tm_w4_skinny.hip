@@ -1,4 +1,4 @@
-// Fused dequantise-and-multiply for the decode shapes (M <= 32): the HBM-bound regime.
+// Fused dequantise-and-multiply for the decode shapes (M <= 64): the HBM-bound regime.
 //
 // Online stage of the GEMM pipeline (paper Sec. 3.1 steps (i)-(iv), Sec. 4.3).  What differs from the paper's
 // design, which stages weights through shared memory for a 32-lane tensor-core fragment load:
@@ -84,10 +84,30 @@ __device__ __forceinline__ void load_stage(Stage<TM, NTW, GPU>& st, const GemmPa
 // scale multiplies the fp32 group sum.  The decode kernels are bound by HBM and by vector-ALU issue, while the
 // matrix cores idle, so moving the subtract and the multiply off the ALU is what brings the per-weight ALU cost
 // under the HBM budget.
+//
+// With four row tiles (M up to 64) the extra MFMAs would cost more matrix-core time than the conversion costs ALU
+// time, so that configuration converts on the ALU as the tile kernels do (dequant8: exact subtract, one rounded
+// multiply) and accumulates straight into the output tile.
 template <int TM, int NTW, int GPU>
 __device__ __forceinline__ void compute_stage(const Stage<TM, NTW, GPU>& st, f32x4 (&acc)[TM][NTW], const Magic& mg)
 {
     constexpr int T = 4 / GPU;                     // MFMA k-steps per K-group
+    if constexpr (TM >= 4) {
+#pragma unroll
+        for (int j = 0; j < NTW; ++j) {
+            GroupConst gc[GPU];
+#pragma unroll
+            for (int g = 0; g < GPU; ++g) gc[g] = make_group_const(st.sz[j][g]);
+#pragma unroll
+            for (int t = 0; t < 4; ++t) {
+                const f16x8 b = dequant8(st.wq[j][t], gc[(t * GPU) / 4], mg);
+#pragma unroll
+                for (int mt = 0; mt < TM; ++mt)
+                    acc[mt][j] = mfma16x16x32(__builtin_bit_cast(f16x8, st.xf[mt][t]), b, acc[mt][j]);
+            }
+        }
+        return;
+    }
 #pragma unroll
     for (int j = 0; j < NTW; ++j) {
 #pragma unroll
@@ -268,6 +288,9 @@ hipError_t launch_skinny(const GemmParams& p, const Plan& plan, int group, hipSt
         case kSkinny16x128: return w16 ? launch_cfg<1, 8, 1, 1, 16>(p, plan, group, stream) : hipErrorInvalidValue;
         case kSkinny32x32: return w16 ? launch_cfg<2, 2, 2, 1, 16>(p, plan, group, stream) : launch_cfg<2, 2, 2, 2, 8>(p, plan, group, stream);
         case kSkinny32x64: return launch_cfg<2, 4, 2, 2, 8>(p, plan, group, stream);
+        case kSkinny64x32: return w16 ? hipErrorInvalidValue : launch_cfg<4, 2, 2, 2, 8>(p, plan, group, stream);
+        case kSkinny64x48: return w16 ? hipErrorInvalidValue : launch_cfg<4, 3, 2, 2, 8>(p, plan, group, stream);
+        case kSkinny64x64: return w16 ? hipErrorInvalidValue : launch_cfg<4, 4, 2, 1, 8>(p, plan, group, stream);
         default: return hipErrorInvalidValue;
     }
 }
