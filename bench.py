@@ -143,6 +143,38 @@ def per_shape_table(tm, torch, wl, layers, iters=100, warmup=10, use_graph=True)
     return rows
 
 
+def dense_companion(tm, torch, wl, layers, iters=50):
+    """fp16 x fp16 companion (the paper's Fig. "int4" / Table "performance" comparison in kind): the vendor library's
+    dense GEMM (torch.matmul -> hipBLASLt) on dequantised fp16 weights of the same shapes, timed the same way
+    (HIP-graph replay, weight copies rotated).  Context for the W4A16 numbers, not part of the method."""
+    rows = []
+    for L in layers:
+        c = L.case
+        wbytes = c.K * c.N * 2
+        copies = max(2, min(L.copies, -(-ROTATE_BYTES // wbytes)))
+        W = [(torch.randn(c.K, c.N, device="cuda", dtype=torch.float16) * c.sigma) for _ in range(copies)]
+        for M in L.Ms:
+            X = L.X[M][0]
+            Y = torch.empty((M, c.N), dtype=torch.float16, device="cuda")
+            turn = [0]
+
+            def dense_step():
+                torch.matmul(X, W[turn[0] % copies], out=Y)
+                turn[0] += 1
+
+            it = iters if M < 1024 else 10
+            d_ms, _ = time_steps(torch, dense_step, it, 3, graph_steps=it)
+            o_ms, _ = time_steps(torch, lambda: L.launch(tm, M), it, 3, graph_steps=it)
+            rows.append({"layer": c.name.rsplit("_M", 1)[0], "M": M, "K": c.K, "N": c.N,
+                         "w4a16_us": o_ms / it * 1e3, "dense_fp16_us": d_ms / it * 1e3,
+                         "speedup_vs_dense": d_ms / o_ms,
+                         "w4a16_TFLOPs": wl.flops(M, c.K, c.N) / (o_ms / it * 1e-3) / 1e12,
+                         "dense_TFLOPs": wl.flops(M, c.K, c.N) / (d_ms / it * 1e-3) / 1e12})
+        del W
+        torch.cuda.empty_cache()
+    return rows
+
+
 def cpu_baseline(wl, layers, min_s=5.0, budget_s=25.0):
     """The oracle as it stands, timed on this host's cores over the same workload: whole passes over every
     (layer, M) pair are repeated until at least `min_s` seconds have been spent; a single GEMM too large for
@@ -178,7 +210,7 @@ def main():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=200)
     ap.add_argument("--warmup", type=int, default=20)
-    ap.add_argument("--workload", default="decode", choices=sorted(WORKLOADS) + ["sweep", "copy"])
+    ap.add_argument("--workload", default="decode", choices=sorted(WORKLOADS) + ["sweep", "copy", "companion"])
     ap.add_argument("--sweep-out", default=None, help="with --workload sweep: write the per-shape table here (JSON)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-prefill", action="store_true", help="skip the prefill companion measurement")
@@ -211,6 +243,24 @@ def main():
         print(json.dumps({"metric": "plain copy (counter calibration)", "bytes_read": n, "bytes_written": n,
                           "steps": args.steps, "ms_per_step": ev_ms / args.steps,
                           "GBps_read_plus_write": 2 * n / (ev_ms / args.steps * 1e-3) / 1e9}))
+        return
+
+    if args.workload == "companion":
+        table = []
+        for name in ("decode", "mlp_decode", "sweep5", "prefill"):
+            layers = [Layer(tm, torch, wl, cn, Ms) for cn, Ms in WORKLOADS[name]]
+            rows = dense_companion(tm, torch, wl, layers)
+            for r in rows:
+                log(f"{r['layer']:16s} M={r['M']:5d} K={r['K']:6d} N={r['N']:6d}  W4A16 {r['w4a16_us']:9.2f} us "
+                    f"({r['w4a16_TFLOPs']:7.1f} TF)   dense fp16 (vendor library) {r['dense_fp16_us']:9.2f} us "
+                    f"({r['dense_TFLOPs']:7.1f} TF)   speed-up {r['speedup_vs_dense']:5.2f}x")
+            table += rows
+            del layers
+            torch.cuda.empty_cache()
+        if args.sweep_out:
+            os.makedirs(os.path.dirname(os.path.abspath(args.sweep_out)), exist_ok=True)
+            json.dump(table, open(args.sweep_out, "w"), indent=1)
+        print(json.dumps({"metric": METRIC, "workload": "companion", "rows": len(table)}))
         return
 
     if args.workload == "sweep":

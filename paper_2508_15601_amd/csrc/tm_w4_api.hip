@@ -194,7 +194,7 @@ Plan make_plan(const tm_packed_w4* h, int M, int num_cu)
         if (g_force_stage > 0) steps = g_force_stage;
         if (bm > 128 || variant == kTile128x512) steps = 2;
         if (bm == 128 && steps == 8) steps = 4;
-        if (variant == kTile128x256 && steps == 4) steps = 2;      // register budget of the 128 x 256 tile
+        if (variant == kTile128x256 && steps == 4 && g_force_stage != 4) steps = 2;      // register budget of the 128 x 256 tile
         if (steps == 8) {                          // two-unit stages need an even number of units in every split
             if (pl.ku_per_split % 2) ++pl.ku_per_split;
             if (KU % 2) steps = 4;

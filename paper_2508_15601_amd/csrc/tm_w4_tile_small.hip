@@ -16,8 +16,7 @@ hipError_t launch_depth(const GemmParams& p, const Plan& plan, int group, hipStr
     switch (plan.stage_steps) {
         case 2: return launch_shape<TM, TN, 4, 2>(p, plan, group, stream);
         case 4:
-            if constexpr (TM * TN <= 16) return launch_shape<TM, TN, 4, 4>(p, plan, group, stream);
-            return hipErrorInvalidValue;
+            return launch_shape<TM, TN, 4, 4>(p, plan, group, stream);
         case 8:
             if constexpr (TM <= 4) return launch_shape<TM, TN, 4, 8>(p, plan, group, stream);
             return hipErrorInvalidValue;
