@@ -124,7 +124,11 @@ Plan make_plan(const tm_packed_w4* h, int M, int num_cu)
             const int per_cu = ceil_div(NT, num_cu);
             variant = per_cu <= 1 ? kSkinny16x16 : per_cu <= 2 ? kSkinny16x32 : per_cu <= 3 ? kSkinny16x48
                     : per_cu <= 4 ? kSkinny16x64 : per_cu <= 6 ? kSkinny16x96 : kSkinny16x128;
-        } else if (M <= 64 && ceil_div(NT, 4) * 2 <= num_cu) {
+            // Deep-and-narrow layers with many rows: every strip re-reads all M*K activations, which then outweighs
+            // the weights; 64-column strips with K split over four CTAs read a quarter of X each (measured
+            // 11.2 vs 14.2 us at K=11008, N=4096, M=16; not a gain at K=4096).
+            if (per_cu <= 1 && M > 8 && KU >= 64 && NT >= num_cu) variant = kSkinny16x64;
+        } else if (M <= 32 && ceil_div(NT, 4) * 2 <= num_cu) {
             // narrow outputs (N <= 8192 on 256 CUs): 64-column strips with K split across CTAs so that every
             // CU gets one CTA; each CTA then re-reads only its K slice of X
             variant = kSkinny64x64;
@@ -135,7 +139,7 @@ Plan make_plan(const tm_packed_w4* h, int M, int num_cu)
             // (M in 33..64 with wide outputs lands here too)
             // largest tile that still yields two CTAs per CU without splitting K; the smallest one otherwise
             const int cand[3] = {kTile128x256, kTile128x128, kTile64x128};
-            variant = kTile64x128;
+            variant = (M <= 64 && ceil_div(NT, 8) * 4 <= num_cu) ? kTile32x128 : kTile64x128;
             if (M > 64)
                 for (int i = 0; i < 3; ++i) {
                     long t = (long)ceil_div(M, tile_bm(cand[i])) * ceil_div(h->N, tile_bn(cand[i]));
@@ -157,7 +161,8 @@ Plan make_plan(const tm_packed_w4* h, int M, int num_cu)
         const int ntw = skinny_ntw(variant);
         // fewest strips the variant can take; when chosen automatically for M <= 16 that is one strip per CU
         int strips = ceil_div(NT, ntw);
-        if (g_force_variant < 0 && M <= 16 && NT >= num_cu && strips < num_cu) strips = num_cu;
+        if (g_force_variant < 0 && M <= 16 && NT >= num_cu && strips < num_cu && !(variant == kSkinny16x64 && NT / num_cu <= 1))
+            strips = num_cu;
         int waves = g_force_waves > 0 ? g_force_waves : ((strips <= num_cu && KU >= 32) ? 16 : 8);
         if (waves < 2 * ntw) waves = 2 * ntw <= 8 ? 8 : 16;    // the LDS reduction needs 128*ntw threads
         if (variant == kSkinny32x64 || skinny_rows(variant) == 64) waves = 8;   // register footprint: 8-wave CTAs only
@@ -175,8 +180,13 @@ Plan make_plan(const tm_packed_w4* h, int M, int num_cu)
         pl.tiles_n = ceil_div(h->N, tile_bn(variant));
         pl.block = (unsigned)tile_threads(variant);
         int tiles = pl.tiles_m * pl.tiles_n;
-        int want = (2 * num_cu) / tiles;           // fill the chip about twice over ...
-        if (want > 4) want = 4;                    // ... but every split costs a full fp32 pass over the output
+        // Split K only when fewer than half the CUs would get a tile, and only as far as the fp32 partial sums
+        // (written and read back once per split) stay below about half the weight bytes: split <= K / (32 M).
+        int want = tiles * 2 <= num_cu ? (2 * num_cu) / tiles : 1;
+        if (want > 4) want = 4;
+        int by_traffic = h->K / (32 * (M > 0 ? M : 1));
+        if (by_traffic < 1) by_traffic = 1;
+        if (want > by_traffic) want = by_traffic;
         int max_by_k = KU / 4 > 0 ? KU / 4 : 1;    // keep at least four units per CTA
         split = want < max_by_k ? want : max_by_k;
     }

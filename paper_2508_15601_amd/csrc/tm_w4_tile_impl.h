@@ -17,6 +17,8 @@
 // stage already exceeds the memory latency); short tiles use 128- or 256-deep stages, because with few rows the
 // MFMAs of a 64-deep stage finish long before the next stage can arrive from L2/HBM.
 #pragma once
+#include <type_traits>
+
 #include "tm_w4_host.h"
 
 namespace tmw4 {
@@ -35,10 +37,24 @@ constexpr int tile_pitch(int bk) { return bk + TM_TILE_PAD; }
 
 typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
 
+// compile-time loop: f(std::integral_constant<int, I>{}) for I = B .. E-1
+template <int B, int E, class F>
+__device__ __forceinline__ void static_for(F&& f)
+{
+    if constexpr (B < E) {
+        f(std::integral_constant<int, B>{});
+        static_for<B + 1, E>(f);
+    }
+}
+
 // CTA tile = (TM*16) rows x (NW*TN*16) columns; wave w of NW owns columns [w*TN*16, (w+1)*TN*16) and all rows.
 // GPU = K-groups per 128-row unit, KW = MFMA steps per pipeline stage (2, 4 or 8).
 // An X fragment read from LDS (1 KiB per wave) feeds TN MFMAs.
-template <int TM, int TN, int NW, int GPU, int KW>
+// PD = prefetch distance in stages (the memory pipeline depth of paper Sec. 4.3): global loads of stage s+PD are
+// issued while stage s is multiplied.  Register sets rotate by compile-time phase (the loop is unrolled PD*(PD+1)
+// times), never by copies, because a copy would wait for the load it renames.  Short tiles take PD = 2: their MFMA
+// time per stage is below the L2/HBM latency and too few of their CTAs fit a CU to cover it.
+template <int TM, int TN, int NW, int GPU, int KW, int PD = (TM <= 4 ? 2 : 1)>
 __global__ __launch_bounds__(NW * 64) void tile_kernel(GemmParams p)
 {
     constexpr int NT_ = NW * 64;                           // threads per CTA
@@ -86,30 +102,32 @@ __global__ __launch_bounds__(NW * 64) void tile_kernel(GemmParams p)
         for (int j = 0; j < TN; ++j) acc[i][j] = f32x4{0.f, 0.f, 0.f, 0.f};
 
     // global -> register staging of one X stage: chunk idx = i*NT_ + tid -> (row idx / CPR, 16-byte column idx % CPR)
-    u32x4 xreg[CH];
-    auto load_x = [&](int st) {
+    // X of stage r (relative to st0) waits in register set r % PD until it is written to LDS one stage early
+    u32x4 xset[PD][CH];
+    auto load_x = [&](u32x4 (&dst)[CH], int st) {
         const char* xb = (const char*)p.X + (size_t)st * (BK * 2);
 #pragma unroll
         for (int i = 0; i < CH; ++i) {
             const int idx = i * NT_ + tid;
             if ((BM * CPR) % NT_ == 0 || idx < BM * CPR) {
                 const int row = min(m0 + idx / CPR, p.M - 1);          // rows past M repeat the last row
-                xreg[i] = *(const u32x4*)(xb + (uint32_t)row * (uint32_t)p.K * 2u + (idx % CPR) * 16);
+                dst[i] = *(const u32x4*)(xb + (uint32_t)row * (uint32_t)p.K * 2u + (idx % CPR) * 16);
             }
         }
     };
-    auto store_x = [&](int buf) {
+    auto store_x = [&](const u32x4 (&src)[CH], int buf) {
 #pragma unroll
         for (int i = 0; i < CH; ++i) {
             const int idx = i * NT_ + tid;
             if ((BM * CPR) % NT_ == 0 || idx < BM * CPR)
-                *(u32x4*)(&xs[buf][(idx / CPR) * kPitch + (idx % CPR) * 8]) = xreg[i];
+                *(u32x4*)(&xs[buf][(idx / CPR) * kPitch + (idx % CPR) * 8]) = src[i];
         }
     };
 
     // packed weights of one stage: words [st*KW, st*KW + KW) of the lane's K sequence, for each n-tile
-    uint32_t wq[TN][KW], wq_next[TN][KW];
-    uint32_t sz[TN][SG], sz_next[TN][SG];
+    // packed weights and scale/zero words of stage r live in register set r % (PD + 1)
+    uint32_t wset[PD + 1][TN][KW];
+    uint32_t sset[PD + 1][TN][SG];
     auto load_w = [&](uint32_t (&w)[TN][KW], uint32_t (&s)[TN][SG], int st) {
         const int ku = (st * KW) / 4;                      // first unit of the stage
         const int word0 = (st * KW) % 4;                   // first word inside it (non-zero only for KW == 2)
@@ -174,33 +192,44 @@ __global__ __launch_bounds__(NW * 64) void tile_kernel(GemmParams p)
 
     if (st0 < st1) {
         f16x8 wfa[TN], wfb[TN];
-        load_x(st0);
-        load_w(wq, sz, st0);
-        store_x(0);
+        const int nst = st1 - st0, last = st1 - 1;
+        // prologue: stage 0 of X straight into LDS; stages 1..PD-1 of X and 0..PD-1 of W into their register sets
+        load_x(xset[0], st0);
+        load_w(wset[0], sset[0], st0);
+        store_x(xset[0], 0);
+        static_for<1, PD>([&](auto R) {
+            constexpr int r = decltype(R)::value;
+            load_x(xset[r % PD], min(st0 + r, last));
+            load_w(wset[r % (PD + 1)], sset[r % (PD + 1)], min(st0 + r, last));
+        });
 #pragma unroll
-        for (int j = 0; j < TN; ++j) wfa[j] = dequant8(wq[j][0], make_group_const(sz[j][0]), mg);
+        for (int j = 0; j < TN; ++j) wfa[j] = dequant8(wset[0][j][0], make_group_const(sset[0][j][0]), mg);
         __syncthreads();
-        for (int st = st0; st < st1; ++st) {
-            // The last iteration prefetches its own stage again instead of branching; the data is never used.
-            const int sn = min(st + 1, st1 - 1);
-            const int buf = (st - st0) & 1;
-            load_x(sn);
-            load_w(wq_next, sz_next, sn);
+        constexpr int PERIOD = PD * (PD + 1);
+        for (int base = 0; base < nst; base += PERIOD) {
+            static_for<0, PERIOD>([&](auto PH) {
+                constexpr int ph = decltype(PH)::value;
+                const int r = base + ph;               // stage relative to st0 (uniform)
+                if (r < nst) {
+                    constexpr int xi = ph % PD;                    // set that takes X(r + PD); it held X(r), now in LDS
+                    constexpr int xn = (ph + 1) % PD;              // set holding X(r + 1)
+                    constexpr int wi = ph % (PD + 1);              // W(r)
+                    constexpr int wn = (ph + 1) % (PD + 1);        // W(r + 1)
+                    constexpr int wf = (ph + PD) % (PD + 1);       // set that takes W(r + PD)
+                    const int buf = r & 1;
+                    // stages past the end re-fetch the last one instead of branching; that data is never used
+                    load_x(xset[xi], min(st0 + r + PD, last));
+                    load_w(wset[wf], sset[wf], min(st0 + r + PD, last));
 #pragma unroll
-            for (int tt = 0; tt < KW; tt += 2) {
-                step(buf, tt, wfa, wfb, wq, sz, tt + 1);
-                if (tt + 2 < KW) step(buf, tt + 1, wfb, wfa, wq, sz, tt + 2);
-                else step(buf, tt + 1, wfb, wfa, wq_next, sz_next, 0);
-            }
-            store_x(buf ^ 1);
-#pragma unroll
-            for (int j = 0; j < TN; ++j) {
-#pragma unroll
-                for (int k = 0; k < KW; ++k) wq[j][k] = wq_next[j][k];
-#pragma unroll
-                for (int g = 0; g < SG; ++g) sz[j][g] = sz_next[j][g];
-            }
-            __syncthreads();
+                    for (int tt = 0; tt < KW; tt += 2) {
+                        step(buf, tt, wfa, wfb, wset[wi], sset[wi], tt + 1);
+                        if (tt + 2 < KW) step(buf, tt + 1, wfb, wfa, wset[wi], sset[wi], tt + 2);
+                        else step(buf, tt + 1, wfb, wfa, wset[wn], sset[wn], 0);
+                    }
+                    store_x(xset[xn], buf ^ 1);
+                    __syncthreads();
+                }
+            });
         }
     }
 
