@@ -190,6 +190,7 @@ Plan make_plan(const tm_packed_w4* h, int M, int num_cu)
         split = want < max_by_k ? want : max_by_k;
     }
     if (g_force_split > 0) split = g_force_split;
+    if (pl.tiles_m * pl.tiles_n > kMaxCounters) split = 1;     // one arrival counter per output tile
     if (split > KU) split = KU;
     if (split > max_split_ws) split = max_split_ws;
     if (split < 1) split = 1;
@@ -245,7 +246,7 @@ int run_gemm(const uint16_t* X, const tm_packed_w4* h, uint16_t* Y, int M, void*
         if ((uintptr_t)ws & 255) return fail(TM_EINVAL, "workspace must be 256-byte aligned");
     }
     if (ws_bytes < pl.ws_bytes) return fail(TM_EINVAL, "workspace too small: %zu < %zu", ws_bytes, pl.ws_bytes);
-    if (pl.tiles_m * pl.tiles_n > kMaxCounters) return fail(TM_EINVAL, "too many output tiles for split-K");
+    if (pl.split > 1 && pl.tiles_m * pl.tiles_n > kMaxCounters) return fail(TM_EINVAL, "too many output tiles for split-K");
 
     GemmParams p{};
     p.X = X;

@@ -194,6 +194,18 @@ def test_edge_cases(tm, oracle):
     Xmis = buf[1:1 + 256].view(2, 128)
     with pytest.raises(tm.TmError):
         tm.tm_gemm_w4a16(Xmis, packed, torch.empty((2, 16), dtype=torch.float16, device="cuda"))
+    # M*K beyond the 32-bit byte offsets the kernels use is rejected before anything is launched
+    import ctypes
+    lib = tm.load_library()
+    big = ctypes.c_void_p(buf.data_ptr())
+    assert lib.tm_gemm_w4a16(big, packed.handle, big, 1 << 24, None) == -1      # M itself out of range
+    assert lib.tm_gemm_w4a16(big, packed.handle, big, -3, None) == -1
+    # a freed handle is refused, not dereferenced as valid
+    p3 = gu.pack(d, 128)
+    h3 = p3.handle
+    p3.close()
+    with pytest.raises(ValueError):
+        _ = p3.handle
     # extreme codes and zero-points: q in {0, 15}, z in {0, 15}
     K, N, g = 256, 32, 64
     rng = np.random.default_rng(0)
@@ -205,6 +217,8 @@ def test_edge_cases(tm, oracle):
     p2 = gu.pack(dd, g)
     ok, worst, fro = acceptance(gu.gemm(p2, X), oracle.gemm(X, q, s, z, g))
     assert ok, (worst, fro)
+    assert lib.tm_gemm_w4a16(big, p2.handle, big, 1 << 23, None) == -1          # M*K = 2^31 with K = 256
+    assert "2^31" in tm.tm_last_error()
 
 
 # ------------------------------------------------------------------ GEMM: the benchmark configurations
