@@ -131,22 +131,26 @@ Plan make_plan(const tm_packed_w4* h, int M, int num_cu)
         } else if (M <= 32 && ceil_div(NT, 4) * 2 <= num_cu) {
             // narrow outputs (N <= 8192 on 256 CUs): 64-column strips with K split across CTAs so that every
             // CU gets one CTA; each CTA then re-reads only its K slice of X
-            variant = kSkinny64x64;
-        } else if (M <= 32) {
-            variant = kTile32x128;                 // wide outputs: measured 21.7 us vs 29.4 us for the skinny kernel
+            variant = kSkinny32x64;
         } else {
-            // (M in 33..64 with wide outputs lands here too)
-            // largest tile that still yields two CTAs per CU without splitting K; the smallest one otherwise
-            const int cand[3] = {kTile128x256, kTile128x128, kTile64x128};
-            variant = (M <= 64 && ceil_div(NT, 8) * 4 <= num_cu) ? kTile32x128 : kTile64x128;
-            if (M > 64)
-                for (int i = 0; i < 3; ++i) {
-                    long t = (long)ceil_div(M, tile_bm(cand[i])) * ceil_div(h->N, tile_bn(cand[i]));
-                    if (t >= 2L * num_cu) {
-                        variant = cand[i];
-                        break;
-                    }
-                }
+            // CTA tiles.  ctas(v) tiles of variant v run in ceil(ctas / #CU) rounds, and a round lasts about as
+            // long as the tile is wide (a CU streams weights at a fixed rate of its own), so of two widths the one
+            // with the smaller rounds x width wins: 96 columns for N = 22016 (230 CTAs instead of 172).
+            auto ctas = [&](int v) { return (long)ceil_div(M, tile_bm(v)) * ceil_div(h->N, tile_bn(v)); };
+            auto cost = [&](int v) { return (long)ceil_div((int)ctas(v), num_cu) * tile_bn(v); };
+            if (M <= 32) {
+                variant = cost(kTile32x96) < cost(kTile32x128) ? kTile32x96 : kTile32x128;
+            } else if (M <= 64) {
+                if (ceil_div(NT, 8) * 4 <= num_cu) variant = kTile32x128;      // narrow: more CTAs, K split on top
+                else variant = cost(kTile64x96) < cost(kTile64x128) ? kTile64x96 : kTile64x128;
+            } else {
+                // the tallest tile that still fills the chip: two CTAs per CU for the 128-row tiles (their register
+                // budget allows two per CU), one for the shorter ones, which hold several wave sets instead
+                if (ctas(kTile128x256) >= 2L * num_cu) variant = kTile128x256;
+                else if (ctas(kTile128x128) >= 2L * num_cu) variant = kTile128x128;
+                else if (ctas(kTile64x128) >= num_cu) variant = kTile64x128;
+                else variant = kTile32x128;
+            }
         }
     }
     if (is_skinny(variant) && M > skinny_rows(variant))        // a forced skinny variant must still cover M
@@ -162,7 +166,7 @@ Plan make_plan(const tm_packed_w4* h, int M, int num_cu)
         int strips = ceil_div(NT, ntw);
         if (g_force_variant < 0 && M <= 16 && NT >= num_cu && strips < num_cu && !(variant == kSkinny16x64 && NT / num_cu <= 1))
             strips = num_cu;
-        int waves = g_force_waves > 0 ? g_force_waves : ((strips <= num_cu && KU >= 32) ? 16 : 8);
+        int waves = g_force_waves >= 8 ? g_force_waves : ((strips <= num_cu && KU >= 32) ? 16 : 8);
         if (waves < 2 * ntw) waves = 2 * ntw <= 8 ? 8 : 16;    // the LDS reduction needs 128*ntw threads
         if (variant == kSkinny32x64 || skinny_rows(variant) == 64) waves = 8;   // register footprint: 8-wave CTAs only
         pl.tiles_m = 1;
@@ -196,6 +200,7 @@ Plan make_plan(const tm_packed_w4* h, int M, int num_cu)
     if (split < 1) split = 1;
     pl.ku_per_split = ceil_div(KU, split);
     pl.stage_steps = 2;
+    pl.kgroups = 1;
     if (!is_skinny(variant)) {
         // Stage depth: short tiles finish the MFMAs of a 64-deep stage long before the next stage can arrive, so
         // they take stages one or two packed units deep; tall tiles keep 64-deep stages (smaller LDS, two CTAs/CU).
@@ -204,12 +209,34 @@ Plan make_plan(const tm_packed_w4* h, int M, int num_cu)
         if (g_force_stage > 0) steps = g_force_stage;
         if (bm > 128 || variant == kTile128x512) steps = 2;
         if (bm == 128 && steps == 8) steps = 4;
-        if (variant == kTile128x256 && steps == 4 && g_force_stage != 4) steps = 2;      // register budget of the 128 x 256 tile
-        if (steps == 8) {                          // two-unit stages need an even number of units in every split
-            if (pl.ku_per_split % 2) ++pl.ku_per_split;
-            if (KU % 2) steps = 4;
+        if (variant == kTile128x256) steps = 2;      // register budget of the 128 x 256 tile
+        // Wave sets per CTA (each takes its own slice of every stage): short tiles take four (two for the
+        // 96-column tiles, whose sets are two waves wide) unless there are two or more CTAs per CU anyway.
+        int kg = 1;
+        if (tile_bn(variant) == 96) kg = 2;
+        else if (bm <= 64 && (long)pl.tiles_m * pl.tiles_n * split < 2L * num_cu) kg = 4;
+        if (bm <= 64 && kg > 1 && g_force_stage == 0) steps = 4;
+        if (g_force_waves >= 4) kg = g_force_waves * 64 / tile_threads(variant);
+        if (!tile_has_kgroups(variant, kg)) kg = tile_has_kgroups(variant, 1) ? 1 : 4;
+        // both X buffers (bm rows x (32*steps*kg + 16) halves each) must fit the 160 KiB of LDS
+        while (kg > 1 && 2L * bm * (32 * steps * kg + 16) * 2 > 160 * 1024) {
+            if (steps > 2) steps /= 2; else kg /= 2;
         }
+        // depths the multi-set kernels are built with (register budget: 128 per lane in CTAs of 16 waves)
+        const int waves_total = kg * tile_threads(variant) / 64;
+        if (waves_total == 16 && steps > (bm <= 32 ? 4 : 2)) steps = bm <= 32 ? 4 : 2;
+        if (kg > 1 && waves_total > 8 && steps == 8) steps = 4;
+        if (tile_bn(variant) == 96 && steps == 8) steps = 4;       // three tiles per wave: no registers for 256-deep stages
+        if (kg == 2 && bm == 64 && steps == 8 && h->group == 32) steps = 4;
+        // the kernels assume whole stages: a stage is steps*kg/4 packed units when that is one or more
+        while (steps * kg > 4 && KU % (steps * kg / 4)) {
+            if (steps > 2) steps /= 2; else kg /= 2;
+        }
+        const int ups = steps * kg / 4;
+        if (ups > 1 && pl.ku_per_split % ups) pl.ku_per_split += ups - pl.ku_per_split % ups;
         pl.stage_steps = steps;
+        pl.kgroups = kg;
+        pl.block = (unsigned)tile_threads(variant) * kg;
     }
     split = ceil_div(KU, pl.ku_per_split);         // drop empty splits
     pl.split = split;
@@ -432,7 +459,7 @@ int tm_set_variant(int variant, int split_k)
 
 int tm_set_launch(int waves, int stage_steps)
 {
-    if (waves != 0 && waves != 8 && waves != 16) return fail(TM_EINVAL, "waves must be 0 (auto), 8 or 16");
+    if (waves != 0 && waves != 4 && waves != 8 && waves != 16) return fail(TM_EINVAL, "waves must be 0 (auto), 4, 8 or 16");
     if (stage_steps != 0 && stage_steps != 2 && stage_steps != 4 && stage_steps != 8)
         return fail(TM_EINVAL, "stage_steps must be 0 (auto), 2, 4 or 8");
     g_force_waves = waves;
@@ -463,6 +490,8 @@ const char* tm_variant_name(int variant)
         case kTile192x256: return "tile192x256";
         case kTile128x512: return "tile128x512";
         case kTile32x128: return "tile32x128";
+        case kTile32x96: return "tile32x96";
+        case kTile64x96: return "tile64x96";
         default: return "";
     }
 }

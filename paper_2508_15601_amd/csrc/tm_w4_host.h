@@ -30,7 +30,9 @@ enum Variant {
     kSkinny64x32 = 17,  // M <= 64, two / three / four tiles per wave, conversion on the ALU
     kSkinny64x48 = 18,
     kSkinny64x64 = 19,
-    kNumVariants = 20
+    kTile32x96 = 20,    // CTA tiles of two waves x three 16-column tiles, always with several wave sets per CTA
+    kTile64x96 = 21,
+    kNumVariants = 22
 };
 inline bool is_skinny(int v) { return v <= kSkinny32x64 || (v >= kSkinny16x48 && v <= kSkinny64x64); }
 inline int skinny_rows(int v) { return (v == kSkinny32x32 || v == kSkinny32x64) ? 32 : (v >= kSkinny64x32 && v <= kSkinny64x64) ? 64 : 16; }
@@ -46,16 +48,23 @@ inline int skinny_ntw(int v)
         default: return 8;
     }
 }
-inline int tile_bm(int v) { return (v == kTile32x256 || v == kTile32x128) ? 32 : ((v == kTile64x256 || v == kTile64x128) ? 64 : ((v == kTile128x256 || v == kTile128x128 || v == kTile128x512) ? 128 : (v == kTile192x256 ? 192 : 256))); }
-inline int tile_threads(int) { return 256; }
-inline int tile_bn(int v) { return (v == kTile64x128 || v == kTile128x128 || v == kTile32x128) ? 128 : (v == kTile128x512 ? 512 : 256); }
+inline int tile_bm(int v) { return (v == kTile32x256 || v == kTile32x128 || v == kTile32x96) ? 32 : ((v == kTile64x256 || v == kTile64x128 || v == kTile64x96) ? 64 : ((v == kTile128x256 || v == kTile128x128 || v == kTile128x512) ? 128 : (v == kTile192x256 ? 192 : 256))); }
+inline int tile_threads(int v) { return (v == kTile32x96 || v == kTile64x96) ? 128 : 256; }     // of one wave set
+// wave sets per CTA (in-CTA split of every K stage) a tile variant is built with, besides 1
+inline bool tile_has_kgroups(int v, int kg)
+{
+    if (v == kTile32x96 || v == kTile64x96) return kg == 2 || kg == 4;
+    return kg == 1 || (kg == 2 && (v == kTile32x128 || v == kTile64x128 || v == kTile128x128)) || (kg == 4 && (v == kTile32x128 || v == kTile64x128));
+}
+inline int tile_bn(int v) { return (v == kTile32x96 || v == kTile64x96) ? 96 : (v == kTile64x128 || v == kTile128x128 || v == kTile32x128) ? 128 : (v == kTile128x512 ? 512 : 256); }
 
 struct Plan {
     int variant;
     int split;
     int ku_per_split;
     int strips;           // skinny kernels: number of column strips the 16-column tiles are dealt into
-    int stage_steps;      // tile kernels: MFMA steps (32 rows of K each) per pipeline stage: 2, 4 or 8
+    int stage_steps;      // tile kernels: MFMA steps (32 rows of K each) per pipeline stage and wave set: 2, 4 or 8
+    int kgroups;          // tile kernels: sets of four waves per CTA, each taking its own slice of every stage
     int tiles_m, tiles_n;
     unsigned grid;
     unsigned block;
@@ -73,5 +82,6 @@ hipError_t launch_skinny(const GemmParams& p, const Plan& plan, int group, hipSt
 hipError_t launch_tile(const GemmParams& p, const Plan& plan, int group, hipStream_t stream);
 hipError_t launch_tile_small(const GemmParams& p, const Plan& plan, int group, hipStream_t stream);
 hipError_t launch_tile_large(const GemmParams& p, const Plan& plan, int group, hipStream_t stream);
+hipError_t launch_tile_kgroup(const GemmParams& p, const Plan& plan, int group, hipStream_t stream);
 
 }  // namespace tmw4

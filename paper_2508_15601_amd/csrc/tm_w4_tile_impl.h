@@ -37,6 +37,12 @@ constexpr int tile_pitch(int bk) { return bk + TM_TILE_PAD; }
 
 typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
 
+// Raw buffer descriptor over `bytes` bytes at p (gfx9 layout: 32-bit data format, no swizzle, no stride).
+__device__ __forceinline__ __amdgpu_buffer_rsrc_t make_rsrc(const void* p, uint32_t bytes)
+{
+    return __builtin_amdgcn_make_buffer_rsrc(const_cast<void*>(p), 0, (int)bytes, 0x00020000);
+}
+
 // compile-time loop: f(std::integral_constant<int, I>{}) for I = B .. E-1
 template <int B, int E, class F>
 __device__ __forceinline__ void static_for(F&& f)
@@ -48,30 +54,40 @@ __device__ __forceinline__ void static_for(F&& f)
 }
 
 // CTA tile = (TM*16) rows x (NW*TN*16) columns; wave w of NW owns columns [w*TN*16, (w+1)*TN*16) and all rows.
+// KG > 1 puts KG such sets of NW waves into one CTA: set kg multiplies the kg-th slice (32*KW rows of K) of every
+// stage, and the KG partial tiles meet in LDS at the end.  That doubles or quadruples the waves per SIMD, which
+// hide each other's LDS and memory latency, without adding CTAs (every CTA re-reads its rows of X) and without
+// partial sums in global memory.
 // GPU = K-groups per 128-row unit, KW = MFMA steps per pipeline stage (2, 4 or 8).
 // An X fragment read from LDS (1 KiB per wave) feeds TN MFMAs.
 // PD = prefetch distance in stages (the memory pipeline depth of paper Sec. 4.3): global loads of stage s+PD are
 // issued while stage s is multiplied.  Register sets rotate by compile-time phase (the loop is unrolled PD*(PD+1)
 // times), never by copies, because a copy would wait for the load it renames.  Short tiles take PD = 2: their MFMA
 // time per stage is below the L2/HBM latency and too few of their CTAs fit a CU to cover it.
-template <int TM, int TN, int NW, int GPU, int KW, int PD = (TM <= 4 ? 2 : 1)>
-__global__ __launch_bounds__(NW * 64) void tile_kernel(GemmParams p)
+template <int TM, int TN, int NW, int GPU, int KW, int PD = (TM <= 4 ? 2 : 1), int KG = 1>
+__global__ __launch_bounds__(NW * KG * 64) void tile_kernel(GemmParams p)
 {
-    constexpr int NT_ = NW * 64;                           // threads per CTA
+    constexpr int NT_ = NW * KG * 64;                      // threads per CTA
     constexpr int BM = TM * 16, BN = NW * TN * 16;
-    constexpr int BK = 32 * KW;                            // halves of K per stage
-    constexpr int kPitch = tile_pitch(BK);
-    constexpr int CPR = BK / 8;                            // 16-byte chunks per X row and stage
+    constexpr int BK = 32 * KW;                            // halves of K per stage and wave set
+    constexpr int BKS = BK * KG;                           // halves of K per stage
+    constexpr int kPitch = tile_pitch(BKS);
+    constexpr int CPR = BKS / 8;                           // 16-byte chunks per X row and stage
     constexpr int CH = (BM * CPR + NT_ - 1) / NT_;         // chunks per thread and stage
     constexpr int SG = (KW * GPU) / 4 > 0 ? (KW * GPU) / 4 : 1;   // K-groups touched by one stage
     constexpr int UW = KW > 4 ? KW / 4 : 1;                // packed units touched by one stage
     constexpr int WPU = KW > 4 ? 4 : KW;                   // words of a unit used by one stage
-    __shared__ __attribute__((aligned(16))) uint16_t xs[2][BM * kPitch];
+    // two X buffers; after the K loop the same memory carries the wave sets' partial tiles
+    constexpr size_t kXsBytes = 2 * (size_t)BM * kPitch * sizeof(uint16_t);
+    constexpr size_t kRedBytes = (size_t)(KG - 1) * NW * TM * TN * 64 * sizeof(f32x4);
+    __shared__ __attribute__((aligned(16))) unsigned char smem[kXsBytes > kRedBytes ? kXsBytes : kRedBytes];
+    uint16_t (*xs)[BM * kPitch] = (uint16_t (*)[BM * kPitch])smem;
     __shared__ uint32_t s_last;
 
     const int tid = threadIdx.x;
     const int lane = tid & 63;
-    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int wave_id = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int wave = wave_id % NW, kg = wave_id / NW;       // column slot and K slice of this wave
     const int c = lane & 15, h = lane >> 4;
     const Magic mg = make_magic();
 
@@ -90,10 +106,11 @@ __global__ __launch_bounds__(NW * 64) void tile_kernel(GemmParams p)
     const int tile_m = within / pw, tile_n = panel * kPanelN + within % pw;
 
     const int m0 = tile_m * BM;
+    const int nt_end = min(p.NT, (tile_n + 1) * (BN / 16));    // 16-column tiles of this CTA end here
     const int nt0 = (tile_n * BN) / 16 + wave * TN;        // first 16-column tile of this wave
     // stages of this CTA's K range (the host makes ku_per_split a multiple of UW when KW > 4)
-    const int st0 = (sk * p.ku_per_split * 4) / KW;
-    const int st1 = (min(p.KU, (sk + 1) * p.ku_per_split) * 4) / KW;
+    const int st0 = (sk * p.ku_per_split * 4) / (KW * KG);
+    const int st1 = (min(p.KU, (sk + 1) * p.ku_per_split) * 4) / (KW * KG);
 
     f32x4 acc[TM][TN];
 #pragma unroll
@@ -103,16 +120,24 @@ __global__ __launch_bounds__(NW * 64) void tile_kernel(GemmParams p)
 
     // global -> register staging of one X stage: chunk idx = i*NT_ + tid -> (row idx / CPR, 16-byte column idx % CPR)
     // X of stage r (relative to st0) waits in register set r % PD until it is written to LDS one stage early
+    // All global loads are buffer loads: a descriptor in scalar registers, a 32-bit per-lane byte offset that
+    // never changes, and a scalar offset that advances along K.  That leaves no vector address arithmetic in the
+    // K loop and no address register a later load could overwrite; reads past a descriptor's size return zero.
     u32x4 xset[PD][CH];
+    uint32_t x_off[CH];
+#pragma unroll
+    for (int i = 0; i < CH; ++i) {
+        const int idx = i * NT_ + tid;
+        const int row = min(m0 + idx / CPR, p.M - 1);                  // rows past M repeat the last row
+        x_off[i] = (uint32_t)row * (uint32_t)p.K * 2u + (uint32_t)(idx % CPR) * 16u;
+    }
+    const __amdgpu_buffer_rsrc_t x_rsrc = make_rsrc(p.X, (uint32_t)p.M * (uint32_t)p.K * 2u);
     auto load_x = [&](u32x4 (&dst)[CH], int st) {
-        const char* xb = (const char*)p.X + (size_t)st * (BK * 2);
 #pragma unroll
         for (int i = 0; i < CH; ++i) {
             const int idx = i * NT_ + tid;
-            if ((BM * CPR) % NT_ == 0 || idx < BM * CPR) {
-                const int row = min(m0 + idx / CPR, p.M - 1);          // rows past M repeat the last row
-                dst[i] = *(const u32x4*)(xb + (uint32_t)row * (uint32_t)p.K * 2u + (idx % CPR) * 16);
-            }
+            if ((BM * CPR) % NT_ == 0 || idx < BM * CPR)
+                dst[i] = __builtin_amdgcn_raw_buffer_load_b128(x_rsrc, x_off[i], st * (BKS * 2), 0);
         }
     };
     auto store_x = [&](const u32x4 (&src)[CH], int buf) {
@@ -126,26 +151,35 @@ __global__ __launch_bounds__(NW * 64) void tile_kernel(GemmParams p)
 
     // packed weights of one stage: words [st*KW, st*KW + KW) of the lane's K sequence, for each n-tile
     // packed weights and scale/zero words of stage r live in register set r % (PD + 1)
+    const uint32_t w_lane = (uint32_t)lane * 16u, sz_lane = (uint32_t)c * 4u;
     uint32_t wset[PD + 1][TN][KW];
     uint32_t sset[PD + 1][TN][SG];
-    auto load_w = [&](uint32_t (&w)[TN][KW], uint32_t (&s)[TN][SG], int st) {
-        const int ku = (st * KW) / 4;                      // first unit of the stage
-        const int word0 = (st * KW) % 4;                   // first word inside it (non-zero only for KW == 2)
-        const int grp0 = (st * KW * GPU) / 4;              // first K-group of the stage
+    // one descriptor per 16-column tile of this wave: its K/128 packed units, and its K/group scale/zero rows.
+    // A tile past the edge of the strip gets empty descriptors: its loads return zero without touching memory
+    // (its results are never stored), which keeps the K loop free of branches.
+    __amdgpu_buffer_rsrc_t w_rsrc[TN], s_rsrc[TN];
+#pragma unroll
+    for (int j = 0; j < TN; ++j) {
+        const bool live = nt0 + j < nt_end;                // wave-uniform
+        const int nt = min(nt0 + j, nt_end - 1);
+        w_rsrc[j] = make_rsrc((const char*)p.W + (size_t)nt * p.KU * 1024, live ? (uint32_t)p.KU * 1024u : 0u);
+        s_rsrc[j] = make_rsrc((const char*)p.SZ + (size_t)nt * p.G * 64, live ? (uint32_t)p.G * 64u : 0u);
+    }
+    auto load_w = [&](uint32_t (&w)[TN][KW], uint32_t (&s)[TN][SG], int stage) {
+        const int st = stage * KG + kg;                    // this wave set's slice of the stage
+        // packed unit of the slice, and the first of the lane's four words in it (non-zero only for KW == 2)
+        const int wbyte = ((st * KW) / 4) * 1024 + ((st * KW) % 4) * 4;
+        const int grp0 = (st * KW * GPU) / 4;              // first K-group of the slice
 #pragma unroll
         for (int j = 0; j < TN; ++j) {
-            // wave-uniform; tiles past the edge re-read the last valid tile (their results are never stored),
-            // which keeps the K loop free of branches
-            const int nt = min(nt0 + j, p.NT - 1);
-            const char* wb = (const char*)p.W + ((size_t)nt * p.KU + ku) * 1024 + word0 * 4 + lane * 16;
 #pragma unroll
             for (int u = 0; u < UW; ++u) {
                 if constexpr (WPU == 2) {
-                    const u32x2 v = *(const u32x2*)(wb + u * 1024);
+                    const u32x2 v = __builtin_amdgcn_raw_buffer_load_b64(w_rsrc[j], w_lane + u * 1024, wbyte, 0);
                     w[j][0] = v.x;
                     w[j][1] = v.y;
                 } else {
-                    const u32x4 v = *(const u32x4*)(wb + u * 1024);
+                    const u32x4 v = __builtin_amdgcn_raw_buffer_load_b128(w_rsrc[j], w_lane + u * 1024, wbyte, 0);
                     w[j][4 * u + 0] = v.x;
                     w[j][4 * u + 1] = v.y;
                     w[j][4 * u + 2] = v.z;
@@ -154,7 +188,7 @@ __global__ __launch_bounds__(NW * 64) void tile_kernel(GemmParams p)
             }
 #pragma unroll
             for (int g = 0; g < SG; ++g)
-                s[j][g] = *(const uint32_t*)((const char*)p.SZ + ((size_t)nt * p.G + grp0 + g) * 64 + c * 4);
+                s[j][g] = __builtin_amdgcn_raw_buffer_load_b32(s_rsrc[j], sz_lane, (grp0 + g) * 64, 0);
         }
     };
 
@@ -166,7 +200,7 @@ __global__ __launch_bounds__(NW * 64) void tile_kernel(GemmParams p)
     constexpr int PAIRS = TM / 2;
     auto step = [&](int buf, int tt, const f16x8 (&cur)[TN], f16x8 (&nxt)[TN], const uint32_t (&wsrc)[TN][KW],
                     const uint32_t (&ssrc)[TN][SG], int tt_next) {
-        const uint16_t* base = &xs[buf][c * kPitch + 32 * tt + 8 * h];
+        const uint16_t* base = &xs[buf][c * kPitch + kg * BK + 32 * tt + 8 * h];
         f16x8 x0 = *(const f16x8*)(base);
         f16x8 x1 = *(const f16x8*)(base + 16 * kPitch);
 #pragma unroll
@@ -188,6 +222,34 @@ __global__ __launch_bounds__(NW * 64) void tile_kernel(GemmParams p)
             x0 = n0;
             x1 = n1;
         }
+    };
+
+    // Short tiles (TM <= 4) have registers for a whole step of X fragments: every step first issues the LDS reads
+    // of the NEXT step, so that only the first step after a barrier waits for LDS.  With one or two waves per SIMD
+    // nothing else would cover that latency (measured: about 300 cycles per step before, of which 130 were the
+    // wait for the fragments just requested).
+    constexpr bool XAHEAD = TM <= 4;
+    constexpr int XF = XAHEAD ? TM : 1;
+    f16x8 xfa[XF], xfb[XF];
+    auto read_x = [&](f16x8 (&xf)[XF], int buf, int tt) {
+        const uint16_t* base = &xs[buf][c * kPitch + kg * BK + 32 * tt + 8 * h];
+#pragma unroll
+        for (int i = 0; i < XF; ++i) xf[i] = *(const f16x8*)(base + i * 16 * kPitch);
+    };
+    auto step_ahead = [&](const f16x8 (&xc)[XF], f16x8 (&xn)[XF], int buf, int tt_x_next, const f16x8 (&cur)[TN],
+                          f16x8 (&nxt)[TN], const uint32_t (&wsrc)[TN][KW], const uint32_t (&ssrc)[TN][SG],
+                          int tt_next) {
+        if (tt_x_next >= 0) read_x(xn, buf, tt_x_next);
+#pragma unroll
+        for (int i = 0; i < XF; ++i) {
+#pragma unroll
+            for (int j = 0; j < TN; ++j)
+                if (j * XF / TN == i)              // spread the TN conversions over the rows
+                    nxt[j] = dequant8(wsrc[j][tt_next], make_group_const(ssrc[j][(tt_next * GPU) / 4 % SG]), mg);
+#pragma unroll
+            for (int j = 0; j < TN; ++j) acc[i][j] = mfma16x16x32(cur[j], xc[i], acc[i][j]);
+        }
+        __builtin_amdgcn_sched_barrier(0);
     };
 
     if (st0 < st1) {
@@ -217,14 +279,31 @@ __global__ __launch_bounds__(NW * 64) void tile_kernel(GemmParams p)
                     constexpr int wn = (ph + 1) % (PD + 1);        // W(r + 1)
                     constexpr int wf = (ph + PD) % (PD + 1);       // set that takes W(r + PD)
                     const int buf = r & 1;
+                    if constexpr (XAHEAD) read_x(xfa, buf, 0);
                     // stages past the end re-fetch the last one instead of branching; that data is never used
                     load_x(xset[xi], min(st0 + r + PD, last));
                     load_w(wset[wf], sset[wf], min(st0 + r + PD, last));
+                    // The group constants derive from the scale/zero words alone, so the compiler would compute
+                    // them right after the load that fetches those words, i.e. wait for the loads just issued in
+                    // every stage.  Making the words of the NEXT stage opaque here, after the new loads are in
+                    // flight, ties that computation to a point where they are a full stage old.
+                    if constexpr (PD > 1) {
+#pragma unroll
+                        for (int j = 0; j < TN; ++j)
+#pragma unroll
+                            for (int g = 0; g < SG; ++g) asm volatile("" : "+v"(sset[wn][j][g]));
+                    }
 #pragma unroll
                     for (int tt = 0; tt < KW; tt += 2) {
-                        step(buf, tt, wfa, wfb, wset[wi], sset[wi], tt + 1);
-                        if (tt + 2 < KW) step(buf, tt + 1, wfb, wfa, wset[wi], sset[wi], tt + 2);
-                        else step(buf, tt + 1, wfb, wfa, wset[wn], sset[wn], 0);
+                        if constexpr (XAHEAD) {
+                            step_ahead(xfa, xfb, buf, tt + 1, wfa, wfb, wset[wi], sset[wi], tt + 1);
+                            if (tt + 2 < KW) step_ahead(xfb, xfa, buf, tt + 2, wfb, wfa, wset[wi], sset[wi], tt + 2);
+                            else step_ahead(xfb, xfa, buf, -1, wfb, wfa, wset[wn], sset[wn], 0);
+                        } else {
+                            step(buf, tt, wfa, wfb, wset[wi], sset[wi], tt + 1);
+                            if (tt + 2 < KW) step(buf, tt + 1, wfb, wfa, wset[wi], sset[wi], tt + 2);
+                            else step(buf, tt + 1, wfb, wfa, wset[wn], sset[wn], 0);
+                        }
                     }
                     store_x(xset[xn], buf ^ 1);
                     __syncthreads();
@@ -233,16 +312,41 @@ __global__ __launch_bounds__(NW * 64) void tile_kernel(GemmParams p)
         }
     }
 
+    // The wave sets' partial tiles meet in LDS (the X buffers are free after the loop's last barrier); set 0 adds
+    // them in a fixed order and alone runs the epilogue.
+    bool writer = true;
+    if constexpr (KG > 1) {
+        f32x4* red = (f32x4*)smem;
+        if (kg > 0) {
+#pragma unroll
+            for (int i = 0; i < TM; ++i)
+#pragma unroll
+                for (int j = 0; j < TN; ++j)
+                    red[(((kg - 1) * NW + wave) * (TM * TN) + i * TN + j) * 64 + lane] = acc[i][j];
+        }
+        __syncthreads();
+        if (kg == 0) {
+#pragma unroll
+            for (int g = 1; g < KG; ++g)
+#pragma unroll
+                for (int i = 0; i < TM; ++i)
+#pragma unroll
+                    for (int j = 0; j < TN; ++j)
+                        acc[i][j] += red[(((g - 1) * NW + wave) * (TM * TN) + i * TN + j) * 64 + lane];
+        }
+        writer = kg == 0;
+    }
+
     // Epilogue.  acc[i][j][r] = Y[m0 + 16i + c][16*(nt0 + j) + 4h + r]: four consecutive columns per lane.
     if (p.split == 1) {
 #pragma unroll
         for (int i = 0; i < TM; ++i) {
             const int m = m0 + i * 16 + c;
-            if (m >= p.M) continue;
+            if (m >= p.M || !writer) continue;
 #pragma unroll
             for (int j = 0; j < TN; ++j) {
                 const int nt = nt0 + j;
-                if (nt >= p.NT) continue;
+                if (nt >= nt_end) continue;
                 u32x2 o;
                 o.x = (uint32_t)f32_to_f16_bits(acc[i][j][0]) | ((uint32_t)f32_to_f16_bits(acc[i][j][1]) << 16);
                 o.y = (uint32_t)f32_to_f16_bits(acc[i][j][2]) | ((uint32_t)f32_to_f16_bits(acc[i][j][3]) << 16);
@@ -256,11 +360,11 @@ __global__ __launch_bounds__(NW * 64) void tile_kernel(GemmParams p)
 #pragma unroll
     for (int i = 0; i < TM; ++i) {
         const int m = m0 + i * 16 + c;
-        if (m >= p.M) continue;
+        if (m >= p.M || !writer) continue;
 #pragma unroll
         for (int j = 0; j < TN; ++j) {
             const int nt = nt0 + j;
-            if (nt >= p.NT) continue;
+            if (nt >= nt_end) continue;
             float* dst = p.partial + ((size_t)sk * p.M + m) * p.N + nt * 16 + 4 * h;
             st_partial2(dst, acc[i][j][0], acc[i][j][1]);
             st_partial2(dst + 2, acc[i][j][2], acc[i][j][3]);
@@ -277,11 +381,11 @@ __global__ __launch_bounds__(NW * 64) void tile_kernel(GemmParams p)
 #pragma unroll
     for (int i = 0; i < TM; ++i) {
         const int m = m0 + i * 16 + c;
-        if (m >= p.M) continue;
+        if (m >= p.M || !writer) continue;
 #pragma unroll
         for (int j = 0; j < TN; ++j) {
             const int nt = nt0 + j;
-            if (nt >= p.NT) continue;
+            if (nt >= nt_end) continue;
             float v[4] = {0.f, 0.f, 0.f, 0.f};
             for (int s = 0; s < p.split; ++s) {
                 const float* src = p.partial + ((size_t)s * p.M + m) * p.N + nt * 16 + 4 * h;
@@ -301,15 +405,18 @@ __global__ __launch_bounds__(NW * 64) void tile_kernel(GemmParams p)
 
 // KW8: stages two packed units deep (needs an even number of units per K split, which the host checks);
 // otherwise one unit deep for short tiles and half a unit for tall ones.
-template <int TM, int TN, int NW, int KW>
+template <int TM, int TN, int NW, int KW, int KG = 1>
 hipError_t launch_shape(const GemmParams& p, const Plan& plan, int group, hipStream_t stream)
 {
-    dim3 grid(plan.grid), block(NW * 64);
-    if (plan.block != NW * 64) return hipErrorInvalidValue;
+    constexpr int PD = TM <= 4 ? 2 : 1;
+    dim3 grid(plan.grid), block(NW * KG * 64);
+    // the kernel assumes whole stages: every K split is a multiple of the stage depth, and so is K
+    if (plan.block != NW * KG * 64 || plan.stage_steps != KW || plan.kgroups != KG) return hipErrorInvalidValue;
+    if ((plan.ku_per_split * 4) % (KW * KG) || (p.KU * 4) % (KW * KG)) return hipErrorInvalidValue;
     switch (group) {
-        case 128: hipLaunchKernelGGL((tile_kernel<TM, TN, NW, 1, KW>), grid, block, 0, stream, p); break;
-        case 64: hipLaunchKernelGGL((tile_kernel<TM, TN, NW, 2, KW>), grid, block, 0, stream, p); break;
-        case 32: hipLaunchKernelGGL((tile_kernel<TM, TN, NW, 4, KW>), grid, block, 0, stream, p); break;
+        case 128: hipLaunchKernelGGL((tile_kernel<TM, TN, NW, 1, KW, PD, KG>), grid, block, 0, stream, p); break;
+        case 64: hipLaunchKernelGGL((tile_kernel<TM, TN, NW, 2, KW, PD, KG>), grid, block, 0, stream, p); break;
+        case 32: hipLaunchKernelGGL((tile_kernel<TM, TN, NW, 4, KW, PD, KG>), grid, block, 0, stream, p); break;
         default: return hipErrorInvalidValue;
     }
     return hipGetLastError();

@@ -16,7 +16,9 @@ hipError_t launch_depth(const GemmParams& p, const Plan& plan, int group, hipStr
     switch (plan.stage_steps) {
         case 2: return launch_shape<TM, TN, 4, 2>(p, plan, group, stream);
         case 4:
-            return launch_shape<TM, TN, 4, 4>(p, plan, group, stream);
+            // the 128 x 256 tile has no registers left for 128-deep stages
+            if constexpr (!(TM == 8 && TN == 4)) return launch_shape<TM, TN, 4, 4>(p, plan, group, stream);
+            return hipErrorInvalidValue;
         case 8:
             if constexpr (TM <= 4) return launch_shape<TM, TN, 4, 8>(p, plan, group, stream);
             return hipErrorInvalidValue;

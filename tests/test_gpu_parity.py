@@ -68,7 +68,7 @@ def test_pack_bit_exact_against_oracle_unpack(tm, oracle, K, N, g):
 
 # ------------------------------------------------------------------ GEMM: exact special cases
 
-@pytest.mark.parametrize("variant", [-1] + list(range(20)))
+@pytest.mark.parametrize("variant", [-1] + list(range(22)))
 def test_one_hot_rows_return_dequantised_weights_bit_exactly(tm, oracle, variant):
     """X = one-hot rows: a single non-zero product per output, so the fp16-dequantised weight must come back
     exactly; pins layout, nibble order, group indexing and the conversion constants on the device."""
@@ -136,10 +136,11 @@ def test_small_shapes_auto_plan(tm, oracle, M, K, N, g):
                                                  (8, 2, 0), (9, 1, 0), (9, 2, 0), (10, 1, 0), (10, 3, 0),
                                                  (11, 1, 0), (11, 2, 0), (12, 1, 0), (13, 1, 0), (13, 2, 0),
                                                  (14, 1, 8), (14, 2, 16), (15, 1, 16), (15, 3, 0), (16, 1, 0), (16, 2, 16),
-                                                 (17, 1, 0), (17, 2, 0), (18, 1, 0), (18, 3, 0), (19, 1, 0), (19, 2, 0)])
+                                                 (17, 1, 0), (17, 2, 0), (18, 1, 0), (18, 3, 0), (19, 1, 0), (19, 2, 0),
+                                                 (20, 1, 0), (20, 2, 0), (21, 1, 0), (21, 3, 0)])
 @pytest.mark.parametrize("g,stage", [(32, 0), (64, 2), (128, 4), (64, 8)])
 def test_every_variant_and_split(tm, oracle, variant, split, waves, g, stage):
-    M = {0: 13, 1: 9, 2: 16, 3: 29, 4: 32, 5: 30, 6: 50, 8: 300, 9: 70, 11: 200, 12: 130, 13: 33, 14: 7, 15: 16, 16: 11, 17: 40, 18: 64, 19: 57}.get(variant, 150)
+    M = {0: 13, 1: 9, 2: 16, 3: 29, 4: 32, 5: 30, 6: 50, 8: 300, 9: 70, 11: 200, 12: 130, 13: 33, 14: 7, 15: 16, 16: 11, 17: 40, 18: 64, 19: 57, 20: 30, 21: 60}.get(variant, 150)
     tm.tm_set_launch(waves, stage)
     K, N = 1152, 336
     d = _random_problem(variant * 10 + split, M, K, N, g)
@@ -156,6 +157,36 @@ def test_every_variant_and_split(tm, oracle, variant, split, waves, g, stage):
     ok, worst, fro = acceptance(Y, Yref)
     assert ok, (worst, fro)
     assert np.array_equal(Y.view(np.uint16), Y2.view(np.uint16)), "split-K reduction must be run-to-run deterministic"
+
+
+# (variant, waves per CTA): 128-column tiles with two or four sets of four waves, 96-column tiles with two or four
+# sets of two waves; the 128-row tile is built with two sets only
+WAVE_SETS = [(13, 8), (13, 16), (9, 8), (9, 16), (10, 8), (20, 4), (20, 8), (21, 4), (21, 8)]
+
+
+@pytest.mark.parametrize("variant,waves", WAVE_SETS)
+@pytest.mark.parametrize("stage", [2, 4, 8])
+@pytest.mark.parametrize("g,split", [(32, 1), (64, 2), (128, 1), (128, 3)])
+def test_tile_wave_sets(tm, oracle, variant, waves, stage, g, split):
+    """Tile kernels with several wave sets per CTA, each set multiplying its own slice of every K stage."""
+    M = {13: 33, 9: 70, 10: 150, 20: 31, 21: 50}[variant]
+    K, N = 1536, 336                         # 12 packed units: whole stages for every depth up to four units
+    d = _random_problem(variant * 100 + waves + stage + split, M, K, N, g)
+    packed = gu.pack(d, g)
+    tm.tm_set_launch(waves, stage)
+    tm.tm_set_variant(variant, split)
+    plan = tm.tm_get_plan(packed, M)
+    _say(f"wave sets variant={variant} waves={waves} stage={stage} g={g} split={split} plan={plan}")
+    assert plan["variant"] == variant
+    assert plan["block"] == waves * 64
+    Y = gu.gemm(packed, d["X"])
+    Y2 = gu.gemm(packed, d["X"])
+    tm.tm_set_variant(-1, 0)
+    tm.tm_set_launch(0, 0)
+    Yref = oracle.gemm(d["X"], d["q"], d["s"], d["z"], g)
+    ok, worst, fro = acceptance(Y, Yref)
+    assert ok, (worst, fro)
+    assert np.array_equal(Y.view(np.uint16), Y2.view(np.uint16))
 
 
 def test_caller_workspace_entry_point(tm, oracle):
