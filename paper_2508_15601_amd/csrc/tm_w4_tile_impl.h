@@ -170,6 +170,13 @@ __global__ __launch_bounds__(NW * KG * 64) void tile_kernel(GemmParams p)
         // packed unit of the slice, and the first of the lane's four words in it (non-zero only for KW == 2)
         const int wbyte = ((st * KW) / 4) * 1024 + ((st * KW) % 4) * 4;
         const int grp0 = (st * KW * GPU) / 4;              // first K-group of the slice
+        // Issue order = order of first use one or two stages later (the load counter retires in order): the
+        // scale/zero words, then the weights; the callers issue the X loads last.
+#pragma unroll
+        for (int j = 0; j < TN; ++j)
+#pragma unroll
+            for (int g = 0; g < SG; ++g)
+                s[j][g] = __builtin_amdgcn_raw_buffer_load_b32(s_rsrc[j], sz_lane, (grp0 + g) * 64, 0);
 #pragma unroll
         for (int j = 0; j < TN; ++j) {
 #pragma unroll
@@ -186,9 +193,6 @@ __global__ __launch_bounds__(NW * KG * 64) void tile_kernel(GemmParams p)
                     w[j][4 * u + 3] = v.w;
                 }
             }
-#pragma unroll
-            for (int g = 0; g < SG; ++g)
-                s[j][g] = __builtin_amdgcn_raw_buffer_load_b32(s_rsrc[j], sz_lane, (grp0 + g) * 64, 0);
         }
     };
 
@@ -261,8 +265,8 @@ __global__ __launch_bounds__(NW * KG * 64) void tile_kernel(GemmParams p)
         store_x(xset[0], 0);
         static_for<1, PD>([&](auto R) {
             constexpr int r = decltype(R)::value;
-            load_x(xset[r % PD], min(st0 + r, last));
             load_w(wset[r % (PD + 1)], sset[r % (PD + 1)], min(st0 + r, last));
+            load_x(xset[r % PD], min(st0 + r, last));
         });
 #pragma unroll
         for (int j = 0; j < TN; ++j) wfa[j] = dequant8(wset[0][j][0], make_group_const(sset[0][j][0]), mg);
@@ -281,28 +285,36 @@ __global__ __launch_bounds__(NW * KG * 64) void tile_kernel(GemmParams p)
                     const int buf = r & 1;
                     if constexpr (XAHEAD) read_x(xfa, buf, 0);
                     // stages past the end re-fetch the last one instead of branching; that data is never used
-                    load_x(xset[xi], min(st0 + r + PD, last));
                     load_w(wset[wf], sset[wf], min(st0 + r + PD, last));
+                    load_x(xset[xi], min(st0 + r + PD, last));
                     // The group constants derive from the scale/zero words alone, so the compiler would compute
-                    // them right after the load that fetches those words, i.e. wait for the loads just issued in
-                    // every stage.  Making the words of the NEXT stage opaque here, after the new loads are in
-                    // flight, ties that computation to a point where they are a full stage old.
-                    if constexpr (PD > 1) {
+                    // them right after the load that fetches those words, i.e. wait for loads just issued.  The
+                    // words of the NEXT stage are therefore made opaque right before the stage's last step, the
+                    // first place that needs them; being first in issue order, they have landed long before.
+                    auto pin_next_sz = [&]() {
 #pragma unroll
                         for (int j = 0; j < TN; ++j)
 #pragma unroll
                             for (int g = 0; g < SG; ++g) asm volatile("" : "+v"(sset[wn][j][g]));
-                    }
+                    };
 #pragma unroll
                     for (int tt = 0; tt < KW; tt += 2) {
                         if constexpr (XAHEAD) {
                             step_ahead(xfa, xfb, buf, tt + 1, wfa, wfb, wset[wi], sset[wi], tt + 1);
-                            if (tt + 2 < KW) step_ahead(xfb, xfa, buf, tt + 2, wfb, wfa, wset[wi], sset[wi], tt + 2);
-                            else step_ahead(xfb, xfa, buf, -1, wfb, wfa, wset[wn], sset[wn], 0);
+                            if (tt + 2 < KW) {
+                                step_ahead(xfb, xfa, buf, tt + 2, wfb, wfa, wset[wi], sset[wi], tt + 2);
+                            } else {
+                                pin_next_sz();
+                                step_ahead(xfb, xfa, buf, -1, wfb, wfa, wset[wn], sset[wn], 0);
+                            }
                         } else {
                             step(buf, tt, wfa, wfb, wset[wi], sset[wi], tt + 1);
-                            if (tt + 2 < KW) step(buf, tt + 1, wfb, wfa, wset[wi], sset[wi], tt + 2);
-                            else step(buf, tt + 1, wfb, wfa, wset[wn], sset[wn], 0);
+                            if (tt + 2 < KW) {
+                                step(buf, tt + 1, wfb, wfa, wset[wi], sset[wi], tt + 2);
+                            } else {
+                                pin_next_sz();
+                                step(buf, tt + 1, wfb, wfa, wset[wn], sset[wn], 0);
+                            }
                         }
                     }
                     store_x(xset[xn], buf ^ 1);
