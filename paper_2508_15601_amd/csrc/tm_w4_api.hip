@@ -166,8 +166,10 @@ Plan make_plan(const tm_packed_w4* h, int M, int num_cu)
         int strips = ceil_div(NT, ntw);
         if (g_force_variant < 0 && M <= 16 && NT >= num_cu && strips < num_cu && !(variant == kSkinny16x64 && NT / num_cu <= 1))
             strips = num_cu;
-        int waves = g_force_waves >= 8 ? g_force_waves : ((strips <= num_cu && KU >= 32) ? 16 : 8);
-        if (waves < 2 * ntw) waves = 2 * ntw <= 8 ? 8 : 16;    // the LDS reduction needs 128*ntw threads
+        int waves = (strips <= num_cu && KU >= 32) ? 16 : 8;
+        // many rows on wide strips: 8 waves with a deeper register ring measured 2-3 % faster than 16 waves
+        if (M > 8 && ntw >= 3 && skinny_rows(variant) == 16) waves = 8;
+        if (g_force_waves >= 8) waves = g_force_waves;
         if (variant == kSkinny32x64 || skinny_rows(variant) == 64) waves = 8;   // register footprint: 8-wave CTAs only
         pl.tiles_m = 1;
         pl.tiles_n = strips;

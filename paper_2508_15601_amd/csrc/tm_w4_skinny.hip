@@ -194,14 +194,11 @@ __global__ __launch_bounds__(MAXW * 64) void skinny_kernel(GemmParams p)
         }
     }
 
-    // Reduce the waves' tiles through LDS, one 16-row tile at a time; thread -> (row, two adjacent columns).
+    // Reduce the waves' tiles through LDS, one 16-row tile at a time; every (row, two adjacent columns) slot of
+    // the 16 x 16*NTW tile is owned by one thread (threads take several slots when the CTA has fewer than 128*NTW).
     constexpr int kPairs = 8 * NTW;                // column pairs per row
-    const bool owner = tid < 16 * kPairs;
-    const int row = tid / kPairs;
-    const int col = (tid % kPairs) * 2;
-    const int src_reg = (col >> 4) * 4 + (row & 3);
-    const int src_lane = 16 * (row >> 2) + (col & 15);
-    const int n = nt0 * 16 + col;
+    constexpr int kSlots = 16 * kPairs;
+    const int nthreads = blockDim.x;
 #pragma unroll
     for (int mt = 0; mt < TM; ++mt) {
         if (mt) __syncthreads();
@@ -210,8 +207,14 @@ __global__ __launch_bounds__(MAXW * 64) void skinny_kernel(GemmParams p)
 #pragma unroll
             for (int r = 0; r < 4; ++r) red[(wave * NTW * 4 + j * 4 + r) * 64 + lane] = acc[mt][j][r];
         __syncthreads();
-        const int m = mt * 16 + row;
-        if (owner && m < p.M && col < ntw * 16) {
+        for (int slot = tid; slot < kSlots; slot += nthreads) {
+            const int row = slot / kPairs;
+            const int col = (slot % kPairs) * 2;
+            const int m = mt * 16 + row;
+            if (m >= p.M || col >= ntw * 16) continue;
+            const int src_reg = (col >> 4) * 4 + (row & 3);
+            const int src_lane = 16 * (row >> 2) + (col & 15);
+            const int n = nt0 * 16 + col;
             float v0 = 0.f, v1 = 0.f;
             for (int w = 0; w < waves; ++w) {
                 float2 t = *(const float2*)&red[(w * NTW * 4 + src_reg) * 64 + src_lane];
@@ -239,8 +242,12 @@ __global__ __launch_bounds__(MAXW * 64) void skinny_kernel(GemmParams p)
         if (s_last) {
 #pragma unroll
             for (int mt = 0; mt < TM; ++mt) {
-                const int m = mt * 16 + row;
-                if (owner && m < p.M && col < ntw * 16) {
+                for (int slot = tid; slot < kSlots; slot += nthreads) {
+                    const int row = slot / kPairs;
+                    const int col = (slot % kPairs) * 2;
+                    const int m = mt * 16 + row;
+                    if (m >= p.M || col >= ntw * 16) continue;
+                    const int n = nt0 * 16 + col;
                     float v0 = 0.f, v1 = 0.f;
                     for (int s = 0; s < p.split; ++s) {
                         float a, b;
@@ -284,8 +291,8 @@ hipError_t launch_skinny(const GemmParams& p, const Plan& plan, int group, hipSt
         case kSkinny16x32: return w16 ? launch_cfg<1, 2, 2, 2, 16>(p, plan, group, stream) : launch_cfg<1, 2, 4, 4, 8>(p, plan, group, stream);
         case kSkinny16x48: return w16 ? launch_cfg<1, 3, 2, 2, 16>(p, plan, group, stream) : launch_cfg<1, 3, 3, 3, 8>(p, plan, group, stream);
         case kSkinny16x64: return w16 ? launch_cfg<1, 4, 2, 1, 16>(p, plan, group, stream) : launch_cfg<1, 4, 2, 2, 8>(p, plan, group, stream);
-        case kSkinny16x96: return w16 ? launch_cfg<1, 6, 1, 1, 16>(p, plan, group, stream) : hipErrorInvalidValue;
-        case kSkinny16x128: return w16 ? launch_cfg<1, 8, 1, 1, 16>(p, plan, group, stream) : hipErrorInvalidValue;
+        case kSkinny16x96: return w16 ? launch_cfg<1, 6, 1, 1, 16>(p, plan, group, stream) : launch_cfg<1, 6, 3, 2, 8>(p, plan, group, stream);
+        case kSkinny16x128: return w16 ? launch_cfg<1, 8, 1, 1, 16>(p, plan, group, stream) : launch_cfg<1, 8, 2, 2, 8>(p, plan, group, stream);
         case kSkinny32x32: return w16 ? launch_cfg<2, 2, 2, 1, 16>(p, plan, group, stream) : launch_cfg<2, 2, 2, 2, 8>(p, plan, group, stream);
         case kSkinny32x64: return launch_cfg<2, 4, 2, 2, 8>(p, plan, group, stream);
         case kSkinny64x32: return w16 ? hipErrorInvalidValue : launch_cfg<4, 2, 2, 2, 8>(p, plan, group, stream);
