@@ -119,9 +119,12 @@ TM_API int tm_packed_raw(const tm_packed_w4* packed, const void** weights, size_
 TM_API int tm_get_plan(const tm_packed_w4* packed, int M, int* variant, int* split_k, int* grid, int* block);
 TM_API int tm_set_variant(int variant, int split_k);
 /*
- * Two more launch parameters for sweeps, 0 = automatic: waves per CTA of the skinny (M <= 32) kernels, which split K
- * inside the CTA (8 or 16), and MFMA steps of 32 K-rows per pipeline stage of the tile kernels (2, 4 or 8; a request
- * the shape cannot honour falls back to the nearest valid depth).
+ * Two more launch parameters for sweeps, 0 = automatic.
+ *   waves        waves per CTA: 8 or 16 for the skinny (M <= 16/32/64) kernels, which split K inside the CTA; 4, 8 or
+ *                16 for the tile kernels, whose CTAs hold one, two or four sets of waves, each set multiplying its
+ *                own slice of every K stage (a value a variant is not built with falls back to its default);
+ *   stage_steps  MFMA steps of 32 K-rows per pipeline stage and wave set of the tile kernels: 2, 4 or 8 (a request
+ *                the shape or the variant's register budget cannot honour falls back to the nearest valid depth).
  */
 TM_API int tm_set_launch(int waves, int stage_steps);
 TM_API const char* tm_variant_name(int variant);
