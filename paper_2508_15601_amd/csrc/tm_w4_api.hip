@@ -144,10 +144,10 @@ Plan make_plan(const tm_packed_w4* h, int M, int num_cu)
                 if (ceil_div(NT, 8) * 4 <= num_cu) variant = kTile32x128;      // narrow: more CTAs, K split on top
                 else variant = cost(kTile64x96) < cost(kTile64x128) ? kTile64x96 : kTile64x128;
             } else {
-                // the tallest tile that still fills the chip: two CTAs per CU for the 128-row tiles (their register
-                // budget allows two per CU), one for the shorter ones, which hold several wave sets instead
-                if (ctas(kTile128x256) >= 2L * num_cu) variant = kTile128x256;
-                else if (ctas(kTile128x128) >= 2L * num_cu) variant = kTile128x128;
+                // the tallest tile that still gives every CU a CTA (measured at K = N = 8192: M = 1024 runs 131 us on
+                // 256 CTAs of 128 x 256 against 134-139 us on 512 CTAs of 128 x 128; M = 512 is within 5 % on all
+                // of 64 x 128, 64 x 256 and 128 x 128)
+                if (ctas(kTile128x256) >= num_cu) variant = kTile128x256;
                 else if (ctas(kTile64x128) >= num_cu) variant = kTile64x128;
                 else variant = kTile32x128;
             }

@@ -7,7 +7,8 @@
 //
 // Differences from the paper's design: packed weights go from HBM/L2 straight into registers in matrix-core operand
 // order (no shared-memory stage, no matrix-load instruction, hence nothing to swizzle); only X passes through LDS,
-// in a padded row-major layout in which the 128-bit fragment reads are bank-conflict-free.
+// loaded there directly from global memory, in a row-major layout whose 16-byte chunks are XOR-swizzled within a
+// row so that the 128-bit fragment reads are bank-conflict-free.
 // The four waves of a CTA split the tile along N only, so every weight fragment is converted exactly once per CTA
 // and feeds TM MFMAs.  The weight fragment is the A operand, so a lane ends up with four consecutive columns of
 // one output row and stores them as one 8-byte word.  CTAs are numbered so that the CTAs resident on one XCD
@@ -26,14 +27,6 @@ namespace tmw4 {
 namespace {
 
 constexpr int kPanelN = 8;                 // output tiles per panel row (XCD-local rasterisation)
-
-// LDS row pitch in halves for a stage of `bk` halves: 16 halves (32 bytes) of padding.  With 64-deep stages that is
-// 160 bytes, the pitch at which the profiler's SQ_LDS_BANK_CONFLICT reads zero for the 128-bit fragment reads
-// (144 and 176 bytes both show 4 conflict cycles per read).
-#ifndef TM_TILE_PAD
-#define TM_TILE_PAD 16
-#endif
-constexpr int tile_pitch(int bk) { return bk + TM_TILE_PAD; }
 
 typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
 
@@ -60,28 +53,29 @@ __device__ __forceinline__ void static_for(F&& f)
 // partial sums in global memory.
 // GPU = K-groups per 128-row unit, KW = MFMA steps per pipeline stage (2, 4 or 8).
 // An X fragment read from LDS (1 KiB per wave) feeds TN MFMAs.
-// PD = prefetch distance in stages (the memory pipeline depth of paper Sec. 4.3): global loads of stage s+PD are
-// issued while stage s is multiplied.  Register sets rotate by compile-time phase (the loop is unrolled PD*(PD+1)
-// times), never by copies, because a copy would wait for the load it renames.  Short tiles take PD = 2: their MFMA
-// time per stage is below the L2/HBM latency and too few of their CTAs fit a CU to cover it.
-template <int TM, int TN, int NW, int GPU, int KW, int PD = (TM <= 4 ? 2 : 1), int KG = 1>
+// PD = prefetch distance of the packed weights in stages (the memory pipeline depth of paper Sec. 4.3): the weight
+// loads of stage s+PD are issued while stage s is multiplied.  Register sets rotate by compile-time phase (the loop
+// is unrolled PD*(PD+1) times), never by copies, because a copy would wait for the load it renames.  PD = 2 wherever
+// the registers allow (tiles up to 128 rows): one stage of MFMAs is shorter than an HBM round trip.  X runs one
+// stage ahead, through the second LDS buffer.
+template <int TM, int TN, int NW, int GPU, int KW, int PD = (TM <= 8 ? 2 : 1), int KG = 1>
 __global__ __launch_bounds__(NW * KG * 64) void tile_kernel(GemmParams p)
 {
     constexpr int NT_ = NW * KG * 64;                      // threads per CTA
     constexpr int BM = TM * 16, BN = NW * TN * 16;
     constexpr int BK = 32 * KW;                            // halves of K per stage and wave set
     constexpr int BKS = BK * KG;                           // halves of K per stage
-    constexpr int kPitch = tile_pitch(BKS);
     constexpr int CPR = BKS / 8;                           // 16-byte chunks per X row and stage
     constexpr int CH = (BM * CPR + NT_ - 1) / NT_;         // chunks per thread and stage
     constexpr int SG = (KW * GPU) / 4 > 0 ? (KW * GPU) / 4 : 1;   // K-groups touched by one stage
     constexpr int UW = KW > 4 ? KW / 4 : 1;                // packed units touched by one stage
     constexpr int WPU = KW > 4 ? 4 : KW;                   // words of a unit used by one stage
-    // two X buffers; after the K loop the same memory carries the wave sets' partial tiles
-    constexpr size_t kXsBytes = 2 * (size_t)BM * kPitch * sizeof(uint16_t);
+    // two X buffers, separate objects so that the compiler can tell a write into one from a read of the other;
+    // after the K loop the first also carries the wave sets' partial tiles
+    constexpr size_t kXsBytes = (size_t)BM * BKS * sizeof(uint16_t);
     constexpr size_t kRedBytes = (size_t)(KG - 1) * NW * TM * TN * 64 * sizeof(f32x4);
-    __shared__ __attribute__((aligned(16))) unsigned char smem[kXsBytes > kRedBytes ? kXsBytes : kRedBytes];
-    uint16_t (*xs)[BM * kPitch] = (uint16_t (*)[BM * kPitch])smem;
+    __shared__ __attribute__((aligned(16))) unsigned char smem0[kXsBytes > kRedBytes ? kXsBytes : kRedBytes];
+    __shared__ __attribute__((aligned(16))) unsigned char smem1[kXsBytes];
     __shared__ uint32_t s_last;
 
     const int tid = threadIdx.x;
@@ -118,35 +112,52 @@ __global__ __launch_bounds__(NW * KG * 64) void tile_kernel(GemmParams p)
 #pragma unroll
         for (int j = 0; j < TN; ++j) acc[i][j] = f32x4{0.f, 0.f, 0.f, 0.f};
 
-    // global -> register staging of one X stage: chunk idx = i*NT_ + tid -> (row idx / CPR, 16-byte column idx % CPR)
-    // X of stage r (relative to st0) waits in register set r % PD until it is written to LDS one stage early
     // All global loads are buffer loads: a descriptor in scalar registers, a 32-bit per-lane byte offset that
     // never changes, and a scalar offset that advances along K.  That leaves no vector address arithmetic in the
     // K loop and no address register a later load could overwrite; reads past a descriptor's size return zero.
-    u32x4 xset[PD][CH];
+    //
+    // X goes from global memory straight into LDS (`buffer_load ... lds`): no staging registers, no LDS store
+    // instructions.  Such a load writes the 64 lanes' 16-byte chunks to consecutive LDS addresses, so the LDS image
+    // of a stage is simply chunk position idx = i*NT_ + tid <-> (row idx / CPR, slot idx % CPR), unpadded; what
+    // varies is which chunk of the row a lane fetches: slot s of row r holds chunk s ^ (r & 7).  With that XOR the
+    // 128-bit fragment reads of rows c = 0..7 fall into eight different 16-byte bank groups (SQ_LDS_BANK_CONFLICT
+    // reads zero), which padding achieved in the register-staged version of this kernel.
+    const __amdgpu_buffer_rsrc_t x_rsrc = make_rsrc(p.X, (uint32_t)p.M * (uint32_t)p.K * 2u);
     uint32_t x_off[CH];
 #pragma unroll
     for (int i = 0; i < CH; ++i) {
         const int idx = i * NT_ + tid;
         const int row = min(m0 + idx / CPR, p.M - 1);                  // rows past M repeat the last row
-        x_off[i] = (uint32_t)row * (uint32_t)p.K * 2u + (uint32_t)(idx % CPR) * 16u;
+        const int kc = (idx % CPR) ^ ((idx / CPR) & 7);
+        x_off[i] = (uint32_t)row * (uint32_t)p.K * 2u + (uint32_t)kc * 16u;
     }
-    const __amdgpu_buffer_rsrc_t x_rsrc = make_rsrc(p.X, (uint32_t)p.M * (uint32_t)p.K * 2u);
-    auto load_x = [&](u32x4 (&dst)[CH], int st) {
+    auto load_x = [&](int buf, int st) {
 #pragma unroll
         for (int i = 0; i < CH; ++i) {
-            const int idx = i * NT_ + tid;
-            if ((BM * CPR) % NT_ == 0 || idx < BM * CPR)
-                dst[i] = __builtin_amdgcn_raw_buffer_load_b128(x_rsrc, x_off[i], st * (BKS * 2), 0);
+            const int first = i * NT_ + wave_id * 64;      // wave-uniform: the wave's 64 chunks are contiguous in LDS
+            // (the host pass of the compiler only needs the kernel's signature; it cannot express the LDS pointer)
+#if defined(__HIP_DEVICE_COMPILE__)
+            if ((BM * CPR) % NT_ == 0 || first < BM * CPR)
+                __builtin_amdgcn_raw_ptr_buffer_load_lds(
+                    x_rsrc, (__attribute__((address_space(3))) void*)((buf ? smem1 : smem0) + (size_t)first * 16),
+                    16, x_off[i], st * (BKS * 2), 0, 0);
+#else
+            (void)first;
+            (void)buf;
+            (void)st;
+            (void)x_rsrc;
+#endif
         }
     };
-    auto store_x = [&](const u32x4 (&src)[CH], int buf) {
-#pragma unroll
-        for (int i = 0; i < CH; ++i) {
-            const int idx = i * NT_ + tid;
-            if ((BM * CPR) % NT_ == 0 || idx < BM * CPR)
-                *(u32x4*)(&xs[buf][(idx / CPR) * kPitch + (idx % CPR) * 8]) = src[i];
-        }
+    // Fragment of MFMA step tt, row tile i: lane (c, h) wants chunk 4q + h of row 16i + c, q = kg*KW + tt; it sits
+    // at byte (16i + c) * BKS*2 + (q ^ flip) * 64 + (h ^ (c & 3)) * 16 with flip = bit 2 of c.  kg*KW is even, so
+    // q ^ flip = kg*KW + (tt ^ flip), and tt ^ flip = tt + flip for even tt, tt - flip for odd tt: two lane bases,
+    // everything else an immediate offset.
+    const uint32_t xd_flip = (uint32_t)(c >> 2) & 1u;
+    const uint32_t xd_lane = (uint32_t)c * (BKS * 2) + (uint32_t)kg * (KW * 64) + (((uint32_t)h ^ ((uint32_t)c & 3u)) * 16u);
+    const uint32_t xd_even = xd_lane + xd_flip * 64u, xd_odd = xd_lane - xd_flip * 64u;
+    auto x_frag = [&](int buf, int tt, int i) -> const f16x8* {
+        return (const f16x8*)((buf ? smem1 : smem0) + ((tt & 1) ? xd_odd : xd_even) + tt * 64 + i * (16 * BKS * 2));
     };
 
     // packed weights of one stage: words [st*KW, st*KW + KW) of the lane's K sequence, for each n-tile
@@ -171,7 +182,7 @@ __global__ __launch_bounds__(NW * KG * 64) void tile_kernel(GemmParams p)
         const int wbyte = ((st * KW) / 4) * 1024 + ((st * KW) % 4) * 4;
         const int grp0 = (st * KW * GPU) / 4;              // first K-group of the slice
         // Issue order = order of first use one or two stages later (the load counter retires in order): the
-        // scale/zero words, then the weights; the callers issue the X loads last.
+        // scale/zero words, then the weights.  (The X loads of a stage are issued before this call.)
 #pragma unroll
         for (int j = 0; j < TN; ++j)
 #pragma unroll
@@ -204,15 +215,14 @@ __global__ __launch_bounds__(NW * KG * 64) void tile_kernel(GemmParams p)
     constexpr int PAIRS = TM / 2;
     auto step = [&](int buf, int tt, const f16x8 (&cur)[TN], f16x8 (&nxt)[TN], const uint32_t (&wsrc)[TN][KW],
                     const uint32_t (&ssrc)[TN][SG], int tt_next) {
-        const uint16_t* base = &xs[buf][c * kPitch + kg * BK + 32 * tt + 8 * h];
-        f16x8 x0 = *(const f16x8*)(base);
-        f16x8 x1 = *(const f16x8*)(base + 16 * kPitch);
+        f16x8 x0 = *x_frag(buf, tt, 0);
+        f16x8 x1 = *x_frag(buf, tt, 1);
 #pragma unroll
         for (int ip = 0; ip < PAIRS; ++ip) {
             f16x8 n0 = x0, n1 = x1;
             if (ip + 1 < PAIRS) {
-                n0 = *(const f16x8*)(base + (2 * ip + 2) * 16 * kPitch);
-                n1 = *(const f16x8*)(base + (2 * ip + 3) * 16 * kPitch);
+                n0 = *x_frag(buf, tt, 2 * ip + 2);
+                n1 = *x_frag(buf, tt, 2 * ip + 3);
             }
 #pragma unroll
             for (int j = 0; j < TN; ++j)
@@ -236,9 +246,8 @@ __global__ __launch_bounds__(NW * KG * 64) void tile_kernel(GemmParams p)
     constexpr int XF = XAHEAD ? TM : 1;
     f16x8 xfa[XF], xfb[XF];
     auto read_x = [&](f16x8 (&xf)[XF], int buf, int tt) {
-        const uint16_t* base = &xs[buf][c * kPitch + kg * BK + 32 * tt + 8 * h];
 #pragma unroll
-        for (int i = 0; i < XF; ++i) xf[i] = *(const f16x8*)(base + i * 16 * kPitch);
+        for (int i = 0; i < XF; ++i) xf[i] = *x_frag(buf, tt, i);
     };
     auto step_ahead = [&](const f16x8 (&xc)[XF], f16x8 (&xn)[XF], int buf, int tt_x_next, const f16x8 (&cur)[TN],
                           f16x8 (&nxt)[TN], const uint32_t (&wsrc)[TN][KW], const uint32_t (&ssrc)[TN][SG],
@@ -259,34 +268,47 @@ __global__ __launch_bounds__(NW * KG * 64) void tile_kernel(GemmParams p)
     if (st0 < st1) {
         f16x8 wfa[TN], wfb[TN];
         const int nst = st1 - st0, last = st1 - 1;
-        // prologue: stage 0 of X straight into LDS; stages 1..PD-1 of X and 0..PD-1 of W into their register sets
-        load_x(xset[0], st0);
+        // prologue: stage 0 of X into LDS buffer 0; stages 0..PD-1 of W into their register sets
+        // End of a stage.  The X loads are the first loads of every stage and each load_w call issues exactly
+        // kWLoads load instructions after them, so "at most NLOADS loads outstanding" (the load counter retires in
+        // order) means the X of the next stage has landed in LDS while the weight prefetch stays in flight across
+        // the barrier.  A plain barrier instruction, not __syncthreads(): the fence in the latter waits for every
+        // outstanding direct-to-LDS load, i.e. for everything younger in the queue as well.
+        constexpr int kWLoads = TN * SG + TN * UW;
+        auto stage_barrier = [&](auto NLOADS) {
+            // the counter field has 6 bits; a smaller bound only waits for a few weight loads more
+            constexpr int n = decltype(NLOADS)::value < 63 ? decltype(NLOADS)::value : 63;
+            // vmcnt = n, lgkmcnt = 0 (this wave's LDS reads are done), expcnt untouched
+            __builtin_amdgcn_s_waitcnt((n & 15) | ((n >> 4) << 14) | (7 << 4) | (0 << 8));
+            __builtin_amdgcn_s_barrier();
+        };
+        load_x(0, st0);
+        __builtin_amdgcn_sched_barrier(0);                 // nothing may be scheduled across: the count above is exact
         load_w(wset[0], sset[0], st0);
-        store_x(xset[0], 0);
         static_for<1, PD>([&](auto R) {
             constexpr int r = decltype(R)::value;
             load_w(wset[r % (PD + 1)], sset[r % (PD + 1)], min(st0 + r, last));
-            load_x(xset[r % PD], min(st0 + r, last));
         });
 #pragma unroll
         for (int j = 0; j < TN; ++j) wfa[j] = dequant8(wset[0][j][0], make_group_const(sset[0][j][0]), mg);
-        __syncthreads();
+        stage_barrier(std::integral_constant<int, PD * kWLoads>{});
         constexpr int PERIOD = PD * (PD + 1);
         for (int base = 0; base < nst; base += PERIOD) {
             static_for<0, PERIOD>([&](auto PH) {
                 constexpr int ph = decltype(PH)::value;
                 const int r = base + ph;               // stage relative to st0 (uniform)
                 if (r < nst) {
-                    constexpr int xi = ph % PD;                    // set that takes X(r + PD); it held X(r), now in LDS
-                    constexpr int xn = (ph + 1) % PD;              // set holding X(r + 1)
                     constexpr int wi = ph % (PD + 1);              // W(r)
                     constexpr int wn = (ph + 1) % (PD + 1);        // W(r + 1)
                     constexpr int wf = (ph + PD) % (PD + 1);       // set that takes W(r + PD)
-                    const int buf = r & 1;
+                    constexpr int buf = ph & 1;                    // = r & 1: PERIOD is even
                     if constexpr (XAHEAD) read_x(xfa, buf, 0);
                     // stages past the end re-fetch the last one instead of branching; that data is never used
+                    // X of the next stage goes straight into the other LDS buffer, which every wave finished
+                    // reading before the barrier that ended the previous stage; these loads come first
+                    load_x(buf ^ 1, min(st0 + r + 1, last));
+                    __builtin_amdgcn_sched_barrier(0);
                     load_w(wset[wf], sset[wf], min(st0 + r + PD, last));
-                    load_x(xset[xi], min(st0 + r + PD, last));
                     // The group constants derive from the scale/zero words alone, so the compiler would compute
                     // them right after the load that fetches those words, i.e. wait for loads just issued.  The
                     // words of the NEXT stage are therefore made opaque right before the stage's last step, the
@@ -317,8 +339,7 @@ __global__ __launch_bounds__(NW * KG * 64) void tile_kernel(GemmParams p)
                             }
                         }
                     }
-                    store_x(xset[xn], buf ^ 1);
-                    __syncthreads();
+                    stage_barrier(std::integral_constant<int, kWLoads>{});
                 }
             });
         }
@@ -328,7 +349,7 @@ __global__ __launch_bounds__(NW * KG * 64) void tile_kernel(GemmParams p)
     // them in a fixed order and alone runs the epilogue.
     bool writer = true;
     if constexpr (KG > 1) {
-        f32x4* red = (f32x4*)smem;
+        f32x4* red = (f32x4*)smem0;
         if (kg > 0) {
 #pragma unroll
             for (int i = 0; i < TM; ++i)
@@ -420,7 +441,7 @@ __global__ __launch_bounds__(NW * KG * 64) void tile_kernel(GemmParams p)
 template <int TM, int TN, int NW, int KW, int KG = 1>
 hipError_t launch_shape(const GemmParams& p, const Plan& plan, int group, hipStream_t stream)
 {
-    constexpr int PD = TM <= 4 ? 2 : 1;
+    constexpr int PD = TM <= 8 ? 2 : 1;                // the 192- and 256-row tiles have no registers for more
     dim3 grid(plan.grid), block(NW * KG * 64);
     // the kernel assumes whole stages: every K split is a multiple of the stage depth, and so is K
     if (plan.block != NW * KG * 64 || plan.stage_steps != KW || plan.kgroups != KG) return hipErrorInvalidValue;
