@@ -119,16 +119,18 @@ __global__ __launch_bounds__(NW * KG * 64) void tile_kernel(GemmParams p)
     // X goes from global memory straight into LDS (`buffer_load ... lds`): no staging registers, no LDS store
     // instructions.  Such a load writes the 64 lanes' 16-byte chunks to consecutive LDS addresses, so the LDS image
     // of a stage is simply chunk position idx = i*NT_ + tid <-> (row idx / CPR, slot idx % CPR), unpadded; what
-    // varies is which chunk of the row a lane fetches: slot s of row r holds chunk s ^ (r & 7).  With that XOR the
-    // 128-bit fragment reads of rows c = 0..7 fall into eight different 16-byte bank groups (SQ_LDS_BANK_CONFLICT
-    // reads zero), which padding achieved in the register-staged version of this kernel.
+    // varies is which chunk of the row a lane fetches: slot s of row r holds chunk s ^ (r & kSwz), kSwz = 15 (7 for
+    // 64-deep stages, whose rows have only eight chunks).  With that XOR the 128-bit fragment reads of rows
+    // c = 0..15 fall into different 16-byte bank groups (SQ_LDS_BANK_CONFLICT reads zero), which padding achieved
+    // in the register-staged version of this kernel.
+    constexpr int kSwz = CPR >= 16 ? 15 : 7;
     const __amdgpu_buffer_rsrc_t x_rsrc = make_rsrc(p.X, (uint32_t)p.M * (uint32_t)p.K * 2u);
     uint32_t x_off[CH];
 #pragma unroll
     for (int i = 0; i < CH; ++i) {
         const int idx = i * NT_ + tid;
         const int row = min(m0 + idx / CPR, p.M - 1);                  // rows past M repeat the last row
-        const int kc = (idx % CPR) ^ ((idx / CPR) & 7);
+        const int kc = (idx % CPR) ^ ((idx / CPR) & kSwz);
         x_off[i] = (uint32_t)row * (uint32_t)p.K * 2u + (uint32_t)kc * 16u;
     }
     auto load_x = [&](int buf, int st) {
@@ -150,14 +152,19 @@ __global__ __launch_bounds__(NW * KG * 64) void tile_kernel(GemmParams p)
         }
     };
     // Fragment of MFMA step tt, row tile i: lane (c, h) wants chunk 4q + h of row 16i + c, q = kg*KW + tt; it sits
-    // at byte (16i + c) * BKS*2 + (q ^ flip) * 64 + (h ^ (c & 3)) * 16 with flip = bit 2 of c.  kg*KW is even, so
-    // q ^ flip = kg*KW + (tt ^ flip), and tt ^ flip = tt + flip for even tt, tt - flip for odd tt: two lane bases,
-    // everything else an immediate offset.
-    const uint32_t xd_flip = (uint32_t)(c >> 2) & 1u;
-    const uint32_t xd_lane = (uint32_t)c * (BKS * 2) + (uint32_t)kg * (KW * 64) + (((uint32_t)h ^ ((uint32_t)c & 3u)) * 16u);
-    const uint32_t xd_even = xd_lane + xd_flip * 64u, xd_odd = xd_lane - xd_flip * 64u;
+    // at byte (16i + c) * BKS*2 + (q ^ f) * 64 + (h ^ (c & 3)) * 16 with f = the swizzle bits of c above its low
+    // two.  (q + 4) ^ f = (q ^ f) + 4, so one lane base per tt mod 4 serves all steps and everything else is an
+    // immediate offset.
+    constexpr int NXB = KW < 4 ? KW : 4;
+    uint32_t xd_base[NXB];
+#pragma unroll
+    for (int t = 0; t < NXB; ++t) {
+        const uint32_t f = ((uint32_t)c & kSwz) >> 2;
+        const uint32_t q = (uint32_t)kg * KW + t;
+        xd_base[t] = (uint32_t)c * (BKS * 2) + (q ^ f) * 64u + (((uint32_t)h ^ ((uint32_t)c & 3u)) * 16u) - t * 64u;
+    }
     auto x_frag = [&](int buf, int tt, int i) -> const f16x8* {
-        return (const f16x8*)((buf ? smem1 : smem0) + ((tt & 1) ? xd_odd : xd_even) + tt * 64 + i * (16 * BKS * 2));
+        return (const f16x8*)((buf ? smem1 : smem0) + xd_base[tt % NXB] + tt * 64 + i * (16 * BKS * 2));
     };
 
     // packed weights of one stage: words [st*KW, st*KW + KW) of the lane's K sequence, for each n-tile
