@@ -214,6 +214,8 @@ def main():
     ap.add_argument("--sweep-out", default=None, help="with --workload sweep: write the per-shape table here (JSON)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-prefill", action="store_true", help="skip the prefill companion measurement")
+    ap.add_argument("--companion-workloads", default="decode,mlp_decode,sweep5,prefill",
+                    help="workloads the fp16 x fp16 companion covers (comma-separated; one of them makes a short profiler run)")
     ap.add_argument("--eager", action="store_true", help="launch every kernel from the host instead of replaying HIP graphs")
     ap.add_argument("--only", default=None, help="restrict the workload to one 'layer:M' pair, e.g. cfg3_gate_up:1 (profiling)")
     ap.add_argument("--waves", type=int, default=0)
@@ -247,7 +249,7 @@ def main():
 
     if args.workload == "companion":
         table = []
-        for name in ("decode", "mlp_decode", "sweep5", "prefill"):
+        for name in args.companion_workloads.split(","):
             layers = [Layer(tm, torch, wl, cn, Ms) for cn, Ms in WORKLOADS[name]]
             rows = dense_companion(tm, torch, wl, layers)
             for r in rows:
