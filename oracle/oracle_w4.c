@@ -12,6 +12,11 @@
  *   - orc_pack_canonical / orc_unpack_canonical:
  *                     "eight INT4 values per 32-bit word" (paper Sec. 3.2, challenge M2): the interchange
  *                     layout handed to the library, u32 [K][N/8], nibble t of word (k,j) = q[k][8j+t].
+ *   - orc_pack_n8i / orc_unpack_n8i, orc_pack_k8 / orc_unpack_k8:
+ *                     the two other word orders in which 4-bit checkpoints of the families the paper names
+ *                     (Sec. 4.1: one pack routine serves several weight formats) keep the same integers:
+ *                     N-major words whose nibbles walk the eight columns in the order 0,2,4,6,1,3,5,7, and
+ *                     K-major words u32 [K/8][N] holding eight consecutive rows of one column.
  *   - orc_unpack_packed:
  *                     inverse index map of the library's MFMA-fragment-ordered buffer (the gfx950 analogue
  *                     of the packed fragment store of paper Sec. 4.1 steps (iii)-(iv)); written from the
@@ -138,6 +143,56 @@ ORC_API int orc_unpack_canonical(const uint32_t* in, int K, int N, uint8_t* q)
     for (int k = 0; k < K; ++k)
         for (int n = 0; n < N; ++n)
             q[(size_t)k * N + n] = (uint8_t)((in[(size_t)k * (N / 8) + n / 8] >> (4 * (n % 8))) & 0xF);
+    return 0;
+}
+
+/* N-major, interleaved nibbles: u32 [K][N/8]; nibble p of word (k,j) is q[k][8j + ord(p)] with
+ * ord = 0,2,4,6,1,3,5,7 (even columns fill the low half of the word, odd columns the high half) */
+static const int orc_n8i_order[8] = {0, 2, 4, 6, 1, 3, 5, 7};
+
+ORC_API int orc_pack_n8i(const uint8_t* q, int K, int N, uint32_t* out)
+{
+    if (!q || !out || K <= 0 || N <= 0 || N % 8) return -1;
+    for (int k = 0; k < K; ++k)
+        for (int j = 0; j < N / 8; ++j) {
+            uint32_t w = 0;
+            for (int p = 0; p < 8; ++p)
+                w |= (uint32_t)(q[(size_t)k * N + 8 * j + orc_n8i_order[p]] & 0xF) << (4 * p);
+            out[(size_t)k * (N / 8) + j] = w;
+        }
+    return 0;
+}
+
+ORC_API int orc_unpack_n8i(const uint32_t* in, int K, int N, uint8_t* q)
+{
+    if (!q || !in || K <= 0 || N <= 0 || N % 8) return -1;
+    for (int k = 0; k < K; ++k)
+        for (int j = 0; j < N / 8; ++j)
+            for (int p = 0; p < 8; ++p)
+                q[(size_t)k * N + 8 * j + orc_n8i_order[p]] =
+                    (uint8_t)((in[(size_t)k * (N / 8) + j] >> (4 * p)) & 0xF);
+    return 0;
+}
+
+/* K-major: u32 [K/8][N]; nibble t of word (i,n) is q[8i+t][n] */
+ORC_API int orc_pack_k8(const uint8_t* q, int K, int N, uint32_t* out)
+{
+    if (!q || !out || K <= 0 || N <= 0 || K % 8) return -1;
+    for (int i = 0; i < K / 8; ++i)
+        for (int n = 0; n < N; ++n) {
+            uint32_t w = 0;
+            for (int t = 0; t < 8; ++t) w |= (uint32_t)(q[(size_t)(8 * i + t) * N + n] & 0xF) << (4 * t);
+            out[(size_t)i * N + n] = w;
+        }
+    return 0;
+}
+
+ORC_API int orc_unpack_k8(const uint32_t* in, int K, int N, uint8_t* q)
+{
+    if (!q || !in || K <= 0 || N <= 0 || K % 8) return -1;
+    for (int k = 0; k < K; ++k)
+        for (int n = 0; n < N; ++n)
+            q[(size_t)k * N + n] = (uint8_t)((in[(size_t)(k / 8) * N + n] >> (4 * (k % 8))) & 0xF);
     return 0;
 }
 

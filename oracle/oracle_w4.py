@@ -43,6 +43,8 @@ def _load():
         lib.orc_quantise.argtypes = [vp, c.c_int, c.c_int, c.c_int, vp, vp, vp]
         lib.orc_pack_canonical.argtypes = [vp, c.c_int, c.c_int, vp]
         lib.orc_unpack_canonical.argtypes = [vp, c.c_int, c.c_int, vp]
+        for f in (lib.orc_pack_n8i, lib.orc_unpack_n8i, lib.orc_pack_k8, lib.orc_unpack_k8):
+            f.argtypes = [vp, c.c_int, c.c_int, vp]
         lib.orc_unpack_packed.argtypes = [vp, vp, c.c_int, c.c_int, c.c_int, vp, vp, vp]
         lib.orc_dequant.argtypes = [vp, vp, vp, c.c_int, c.c_int, c.c_int, vp]
         lib.orc_gemm.argtypes = [vp, c.c_int, vp, vp, vp, c.c_int, c.c_int, c.c_int, vp, vp]
@@ -107,6 +109,40 @@ def unpack_canonical(words: np.ndarray, N: int) -> np.ndarray:
     K = words.shape[0]
     q = np.empty((K, N), np.uint8)
     _check(_load().orc_unpack_canonical(_ptr(words), K, N, _ptr(q)), "unpack_canonical")
+    return q
+
+
+def pack_n8i(q: np.ndarray) -> np.ndarray:
+    """q u8 [K,N] -> u32 [K,N/8], nibble p of word (k,j) = q[k][8j + (0,2,4,6,1,3,5,7)[p]]."""
+    q = _as(q, np.uint8)
+    K, N = q.shape
+    out = np.empty((K, N // 8), np.uint32)
+    _check(_load().orc_pack_n8i(_ptr(q), K, N, _ptr(out)), "pack_n8i")
+    return out
+
+
+def unpack_n8i(words: np.ndarray, N: int) -> np.ndarray:
+    words = _as(words, np.uint32)
+    K = words.shape[0]
+    q = np.empty((K, N), np.uint8)
+    _check(_load().orc_unpack_n8i(_ptr(words), K, N, _ptr(q)), "unpack_n8i")
+    return q
+
+
+def pack_k8(q: np.ndarray) -> np.ndarray:
+    """q u8 [K,N] -> u32 [K/8,N], nibble t of word (i,n) = q[8i+t][n]."""
+    q = _as(q, np.uint8)
+    K, N = q.shape
+    out = np.empty((K // 8, N), np.uint32)
+    _check(_load().orc_pack_k8(_ptr(q), K, N, _ptr(out)), "pack_k8")
+    return out
+
+
+def unpack_k8(words: np.ndarray, K: int) -> np.ndarray:
+    words = _as(words, np.uint32)
+    N = words.shape[1]
+    q = np.empty((K, N), np.uint8)
+    _check(_load().orc_unpack_k8(_ptr(words), K, N, _ptr(q)), "unpack_k8")
     return q
 
 

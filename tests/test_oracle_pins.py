@@ -143,6 +143,52 @@ def test_pack_canonical_roundtrip_and_agrees_with_generator(oracle):
         assert np.array_equal(w, wl.pack_interchange(q))
 
 
+def test_alternative_layout_word_fixture(oracle):
+    n = 0
+    for line in open(os.path.join(GOLD, "interchange_word_orders.txt")):
+        line = line.split("#")[0].split()
+        if not line:
+            continue
+        vals, want = np.array([int(v) for v in line[1:9]], np.uint8), int(line[9], 16)
+        if line[0] == "n8i":
+            got = oracle.pack_n8i(vals.reshape(1, 8))
+        else:
+            got = oracle.pack_k8(vals.reshape(8, 1))
+        assert got.shape == (1, 1) and int(got[0, 0]) == want, line
+        n += 1
+    assert n >= 10
+
+
+def test_alternative_layouts_roundtrip_bruteforce_and_generator(oracle):
+    rng = np.random.default_rng(6)
+    order = [0, 2, 4, 6, 1, 3, 5, 7]
+    for K, N in [(8, 8), (16, 24), (128, 64)]:
+        q = rng.integers(0, 16, (K, N), dtype=np.uint8)
+        z = rng.integers(0, 16, (K // 8, N)).astype(np.float16)
+        wi, wk = oracle.pack_n8i(q), oracle.pack_k8(q)
+        assert np.array_equal(oracle.unpack_n8i(wi, N), q) and np.array_equal(oracle.unpack_k8(wk, K), q)
+        if K * N <= 512:                                   # every nibble, one by one
+            for k in range(K):
+                for n in range(N):
+                    assert (int(wi[k, n // 8]) >> (4 * order.index(n % 8))) & 15 == q[k, n]
+                    assert (int(wk[k // 8, n]) >> (4 * (k % 8))) & 15 == q[k, n]
+        # the same integers in a different order: interleaving permutes nibbles inside each canonical word
+        wc = oracle.pack_canonical(q)
+        assert np.array_equal(np.sort(np.stack([(wc >> (4 * t)) & 15 for t in range(8)]), axis=0),
+                              np.sort(np.stack([(wi >> (4 * t)) & 15 for t in range(8)]), axis=0))
+        # the input generator's encoders write the same words
+        for layout, wq in ((wl.LAYOUT_N8, wc), (wl.LAYOUT_N8_INTERLEAVED, wi), (wl.LAYOUT_K8, wk)):
+            gq, gz = wl.encode_layout(q, z, layout)
+            assert np.array_equal(gq, wq)
+            zi = z.astype(np.uint8)
+            if layout == wl.LAYOUT_N8:
+                assert gz is z
+            elif layout == wl.LAYOUT_N8_INTERLEAVED:
+                assert np.array_equal(gz, oracle.pack_n8i(zi))
+            else:
+                assert np.array_equal(gz, oracle.pack_canonical(zi))
+
+
 # ------------------------------------------------------------------ fragment-ordered layout (inverse map)
 
 def _pack_fragment_order_numpy(q, s, z, g):

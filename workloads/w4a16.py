@@ -61,6 +61,36 @@ def pack_interchange(q: np.ndarray) -> np.ndarray:
     return np.bitwise_or.reduce(q32 << shifts, axis=2).astype(np.uint32)
 
 
+# Interchange layouts tm_pack_w4_layout accepts (values of its ``layout`` argument).
+LAYOUT_N8, LAYOUT_N8_INTERLEAVED, LAYOUT_K8 = 0, 1, 2
+_N8I_ORDER = (0, 2, 4, 6, 1, 3, 5, 7)
+
+
+def encode_layout(q: np.ndarray, z: np.ndarray, layout: int):
+    """(q uint8 [K,N], z float16 [K/g,N] integer-valued) -> (qweight, zeros) as a checkpoint of that layout stores them.
+
+    LAYOUT_N8              qweight u32 [K,N/8] nibble t = column 8j+t;                    zeros fp16 [K/g,N]
+    LAYOUT_N8_INTERLEAVED  qweight u32 [K,N/8] nibble p = column 8j+(0,2,4,6,1,3,5,7)[p]; zeros u32 [K/g,N/8], same order
+    LAYOUT_K8              qweight u32 [K/8,N] nibble t = row 8i+t;                       zeros u32 [K/g,N/8] nibble t = column 8j+t
+    Only a storage format: no arithmetic of the method."""
+    shifts = 4 * np.arange(8, dtype=np.uint32)
+    zi = z.astype(np.float32).astype(np.uint8)
+    if layout == LAYOUT_N8:
+        return pack_interchange(q), z
+    if layout == LAYOUT_N8_INTERLEAVED:
+        def rows(a):
+            R, N = a.shape
+            a = a.astype(np.uint32).reshape(R, N // 8, 8)[:, :, list(_N8I_ORDER)]
+            return np.bitwise_or.reduce(a << shifts[None, None, :], axis=2).astype(np.uint32)
+        return rows(q), rows(zi)
+    if layout == LAYOUT_K8:
+        K, N = q.shape
+        a = q.astype(np.uint32).reshape(K // 8, 8, N)
+        qw = np.bitwise_or.reduce(a << shifts[None, :, None], axis=1).astype(np.uint32)
+        return qw, pack_interchange(zi)
+    raise ValueError(f"unknown layout {layout}")
+
+
 def draw_weights(case: Case, rng: np.random.Generator) -> np.ndarray:
     W = (case.sigma * rng.standard_normal((case.K, case.N), dtype=np.float32)).astype(np.float32)
     if case.outlier_frac > 0:
