@@ -71,6 +71,27 @@ TM_API tm_packed_w4* tm_pack_w4_on(const uint32_t* qweight, const uint16_t* scal
                                    int K, int N, int group, tm_stream stream);
 
 /*
+ * The same packing from the other word orders in which 4-bit checkpoints keep (q, s, z) (paper Sec. 4.1: one offline
+ * pack step absorbs the format differences, so the online GEMM sees a single layout).  The result is bit-identical to
+ * tm_pack_w4 of the same integers; only the reading side differs.
+ *
+ *   TM_LAYOUT_N8              qweight u32 [K][N/8], nibble t of word (k, j) = q[k][8j + t];  zeros fp16 [K/group][N]
+ *                             (exactly tm_pack_w4_on)
+ *   TM_LAYOUT_N8_INTERLEAVED  qweight u32 [K][N/8], nibble p of word (k, j) = q[k][8j + o(p)], o = 0,2,4,6,1,3,5,7
+ *                             (even columns in the low half-word, odd columns in the high half-word);
+ *                             zeros u32 [K/group][N/8], integers 0..15 packed in the same nibble order
+ *   TM_LAYOUT_K8              qweight u32 [K/8][N], nibble t of word (i, n) = q[8i + t][n];
+ *                             zeros u32 [K/group][N/8], nibble t of word (G, j) = z[G][8j + t]
+ *
+ * scales is fp16 [K/group][N] in every layout.  The zero integers are used as stored (a checkpoint convention that
+ * keeps z - 1 must be undone by the caller).  Shapes, alignment (4 bytes for u32 buffers), ownership and errors are
+ * those of tm_pack_w4_on; an unknown layout is TM_EINVAL (NULL return).
+ */
+typedef enum tm_layout { TM_LAYOUT_N8 = 0, TM_LAYOUT_N8_INTERLEAVED = 1, TM_LAYOUT_K8 = 2 } tm_layout;
+TM_API tm_packed_w4* tm_pack_w4_layout(const void* qweight, const uint16_t* scales, const void* zeros, int K, int N,
+                                       int group, int layout, tm_stream stream);
+
+/*
  * Online mixed-precision GEMM (paper Sec. 3.1 steps (i)-(iv) and Sec. 4.3): Y = X * dequant(packed).
  *
  *   X  fp16 [M][K] row-major, 16-byte aligned        Y  fp16 [M][N] row-major, 16-byte aligned;  M*K < 2^31

@@ -42,6 +42,8 @@ def load_library():
     lib.tm_pack_w4.argtypes = [vp, vp, vp, i, i, i]
     lib.tm_pack_w4_on.restype = vp
     lib.tm_pack_w4_on.argtypes = [vp, vp, vp, i, i, i, vp]
+    lib.tm_pack_w4_layout.restype = vp
+    lib.tm_pack_w4_layout.argtypes = [vp, vp, vp, i, i, i, i, vp]
     lib.tm_gemm_w4a16.restype = i
     lib.tm_gemm_w4a16.argtypes = [vp, vp, vp, i, vp]
     lib.tm_gemm_w4a16_ws.restype = i
@@ -142,6 +144,25 @@ def tm_pack_w4(qweight, scales, zeros, K: int, N: int, group: int, stream=None) 
         raise ValueError("tensor shapes do not match K, N, group")
     h = lib.tm_pack_w4_on(_dev_ptr(qweight, torch.int32, "qweight"), _dev_ptr(scales, torch.float16, "scales"),
                           _dev_ptr(zeros, torch.float16, "zeros"), K, N, group, _stream_ptr(stream))
+    if not h:
+        raise TmError(-1, tm_last_error())
+    return PackedW4(h, K, N, group)
+
+
+TM_LAYOUT_N8, TM_LAYOUT_N8_INTERLEAVED, TM_LAYOUT_K8 = 0, 1, 2
+
+
+def tm_pack_w4_layout(qweight, scales, zeros, K: int, N: int, group: int, layout: int, stream=None) -> PackedW4:
+    """Pack from one of the interchange layouts of tm_layout: qweight int32 [K, N/8] (layouts 0, 1) or [K/8, N]
+    (layout 2); zeros float16 [K/group, N] (layout 0) or int32 [K/group, N/8] (layouts 1, 2)."""
+    import torch
+    lib = load_library()
+    qshape = (K // 8, N) if layout == TM_LAYOUT_K8 else (K, N // 8)
+    zshape, zdtype = ((K // group, N), torch.float16) if layout == TM_LAYOUT_N8 else ((K // group, N // 8), torch.int32)
+    if tuple(qweight.shape) != qshape or tuple(scales.shape) != (K // group, N) or tuple(zeros.shape) != zshape:
+        raise ValueError("tensor shapes do not match K, N, group, layout")
+    h = lib.tm_pack_w4_layout(_dev_ptr(qweight, torch.int32, "qweight"), _dev_ptr(scales, torch.float16, "scales"),
+                              _dev_ptr(zeros, zdtype, "zeros"), K, N, group, layout, _stream_ptr(stream))
     if not h:
         raise TmError(-1, tm_last_error())
     return PackedW4(h, K, N, group)

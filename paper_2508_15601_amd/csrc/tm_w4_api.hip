@@ -309,9 +309,13 @@ using namespace tmw4;
 
 extern "C" {
 
-tm_packed_w4* tm_pack_w4_on(const uint32_t* qweight, const uint16_t* scales, const uint16_t* zeros, int K, int N,
-                            int group, tm_stream stream)
+tm_packed_w4* tm_pack_w4_layout(const void* qweight, const uint16_t* scales, const void* zeros, int K, int N,
+                                int group, int layout, tm_stream stream)
 {
+    if (layout != TM_LAYOUT_N8 && layout != TM_LAYOUT_N8_INTERLEAVED && layout != TM_LAYOUT_K8) {
+        fail(TM_EINVAL, "unknown layout %d", layout);
+        return nullptr;
+    }
     if (!qweight || !scales || !zeros) {
         fail(TM_EINVAL, "qweight, scales or zeros is null");
         return nullptr;
@@ -328,7 +332,7 @@ tm_packed_w4* tm_pack_w4_on(const uint32_t* qweight, const uint16_t* scales, con
         fail(TM_EINVAL, "K*N too large");
         return nullptr;
     }
-    if (((uintptr_t)qweight & 3) || ((uintptr_t)scales & 1) || ((uintptr_t)zeros & 1)) {
+    if (((uintptr_t)qweight & 3) || ((uintptr_t)scales & 1) || ((uintptr_t)zeros & (layout == TM_LAYOUT_N8 ? 1 : 3))) {
         fail(TM_EINVAL, "misaligned input");
         return nullptr;
     }
@@ -357,7 +361,8 @@ tm_packed_w4* tm_pack_w4_on(const uint32_t* qweight, const uint16_t* scales, con
         delete h;
         return nullptr;
     }
-    e = launch_repack(qweight, scales, zeros, h->w, h->sz, K, N, group, (hipStream_t)stream);
+    e = launch_repack((const uint32_t*)qweight, scales, zeros, h->w, h->sz, K, N, group, layout,
+                      (hipStream_t)stream);
     if (e != hipSuccess) {
         fail_hip(e, "repack launch");
         (void)hipFree(h->w);
@@ -366,6 +371,12 @@ tm_packed_w4* tm_pack_w4_on(const uint32_t* qweight, const uint16_t* scales, con
         return nullptr;
     }
     return h;
+}
+
+tm_packed_w4* tm_pack_w4_on(const uint32_t* qweight, const uint16_t* scales, const uint16_t* zeros, int K, int N,
+                            int group, tm_stream stream)
+{
+    return tm_pack_w4_layout(qweight, scales, zeros, K, N, group, TM_LAYOUT_N8, stream);
 }
 
 tm_packed_w4* tm_pack_w4(const uint32_t* qweight, const uint16_t* scales, const uint16_t* zeros, int K, int N,

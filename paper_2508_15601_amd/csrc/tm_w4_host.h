@@ -71,8 +71,8 @@ struct Plan {
     size_t ws_bytes;      // counters + partial sums
 };
 
-hipError_t launch_repack(const uint32_t* qweight, const uint16_t* scales, const uint16_t* zeros, uint32_t* w_out,
-                         uint32_t* sz_out, int K, int N, int group, hipStream_t stream);
+hipError_t launch_repack(const uint32_t* qweight, const uint16_t* scales, const void* zeros, uint32_t* w_out,
+                         uint32_t* sz_out, int K, int N, int group, int layout, hipStream_t stream);
 hipError_t launch_unpack(const uint32_t* w, const uint32_t* sz, uint32_t* qweight_out, uint16_t* scales_out,
                          uint16_t* zeros_out, int K, int N, int group, hipStream_t stream);
 hipError_t launch_copy(void* dst, const void* src, size_t bytes, hipStream_t stream);

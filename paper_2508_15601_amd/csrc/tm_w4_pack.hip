@@ -9,19 +9,39 @@
 
 namespace tmw4 {
 
+// LAYOUT selects how the interchange words are read (values of tm_layout):
+//   0  u32 [K][N/8], nibble t = column 8j+t          1  same shape, nibble p = column 8j + (0,2,4,6,1,3,5,7)[p]
+//   2  u32 [K/8][N], nibble t = row 8i+t
+// Layouts 0 and 1 stage the block as 128 rows x 16 words; layout 2 as 16 row-words x 128 columns, where the eight
+// rows one output word needs (32t + 8h + e, e = 0..7) are exactly one staged word.
+template <int LAYOUT>
 __global__ __launch_bounds__(256) void repack_w4_kernel(const uint32_t* __restrict__ qweight,
                                                         uint32_t* __restrict__ out, int K, int N)
 {
-    __shared__ uint32_t tile[128][17];             // 128 rows x 16 words (128 columns), padded
+    constexpr int kRows = LAYOUT == 2 ? 16 : 128, kPitch = LAYOUT == 2 ? 132 : 17;
+    __shared__ uint32_t tile[kRows][kPitch];
     const int KU = K / kUnitK, NT = N / kUnitN, NW = N / 8;
     const int ku = blockIdx.y;
     const int nt0 = blockIdx.x * 8;
     const int tid = threadIdx.x;
     for (int i = 0; i < 8; ++i) {
         int idx = i * 256 + tid;
-        int row = idx >> 4, wc = idx & 15;
-        int gw = nt0 * 2 + wc;
-        tile[row][wc] = gw < NW ? qweight[(size_t)(ku * kUnitK + row) * NW + gw] : 0u;
+        if constexpr (LAYOUT == 2) {
+            int row = idx >> 7, col = idx & 127;
+            int gc = nt0 * 16 + col;
+            tile[row][col] = gc < N ? qweight[(size_t)(ku * 16 + row) * N + gc] : 0u;
+        } else {
+            int row = idx >> 4, wc = idx & 15;
+            int gw = nt0 * 2 + wc;
+            uint32_t v = gw < NW ? qweight[(size_t)(ku * kUnitK + row) * NW + gw] : 0u;
+            if constexpr (LAYOUT == 1) {
+                uint32_t u = 0;                      // nibble p -> nibble o(p) = 2*(p&3) + (p>>2)
+#pragma unroll
+                for (int p = 0; p < 8; ++p) u |= ((v >> (4 * p)) & 0xFu) << (4 * (2 * (p & 3) + (p >> 2)));
+                v = u;
+            }
+            tile[row][wc] = v;
+        }
     }
     __syncthreads();
     const int lane = tid >> 2, t = tid & 3;
@@ -30,19 +50,28 @@ __global__ __launch_bounds__(256) void repack_w4_kernel(const uint32_t* __restri
         int nt = nt0 + j;
         if (nt >= NT) break;
         int col = 16 * j + c;
-        int wc = col >> 3, sh = 4 * (col & 7);
         uint32_t w = 0;
+        if constexpr (LAYOUT == 2) {
+            uint32_t v = tile[4 * t + h][col];
 #pragma unroll
-        for (int e = 0; e < 8; ++e) {
-            uint32_t nib = (tile[32 * t + 8 * h + e][wc] >> sh) & 0xFu;
-            w |= nib << (4 * (4 * (e & 1) + (e >> 1)));
+            for (int e = 0; e < 8; ++e) w |= ((v >> (4 * e)) & 0xFu) << (4 * (4 * (e & 1) + (e >> 1)));
+        } else {
+            int wc = col >> 3, sh = 4 * (col & 7);
+#pragma unroll
+            for (int e = 0; e < 8; ++e) {
+                uint32_t nib = (tile[32 * t + 8 * h + e][wc] >> sh) & 0xFu;
+                w |= nib << (4 * (4 * (e & 1) + (e >> 1)));
+            }
         }
         out[((size_t)nt * KU + ku) * kUnitWords + tid] = w;
     }
 }
 
+// ZFMT: 0 zeros are fp16 [G][N]; 1 u32 [G][N/8], nibble t = column 8j+t; 2 u32 [G][N/8], nibble p = column
+// 8j + (0,2,4,6,1,3,5,7)[p].  Packed integers are widened to the fp16 pattern the GEMM kernels expect.
+template <int ZFMT>
 __global__ __launch_bounds__(256) void repack_sz_kernel(const uint16_t* __restrict__ scales,
-                                                        const uint16_t* __restrict__ zeros,
+                                                        const void* __restrict__ zeros,
                                                         uint32_t* __restrict__ out, int G, int N)
 {
     size_t idx = (size_t)blockIdx.x * 256 + threadIdx.x;
@@ -52,8 +81,19 @@ __global__ __launch_bounds__(256) void repack_sz_kernel(const uint16_t* __restri
     size_t r = idx >> 4;
     int g = (int)(r % G);
     int nt = (int)(r / G);
-    size_t src = (size_t)g * N + 16 * nt + c;
-    out[idx] = (uint32_t)scales[src] | ((uint32_t)zeros[src] << 16);
+    int n = 16 * nt + c;
+    size_t src = (size_t)g * N + n;
+    uint32_t zb;
+    if constexpr (ZFMT == 0) {
+        zb = ((const uint16_t*)zeros)[src];
+    } else {
+        int t = n & 7;
+        int pos = ZFMT == 1 ? t : (t >> 1) + 4 * (t & 1);
+        uint32_t zi = (((const uint32_t*)zeros)[(size_t)g * (N / 8) + (n >> 3)] >> (4 * pos)) & 0xFu;
+        _Float16 zf = (_Float16)(int)zi;
+        zb = __builtin_bit_cast(unsigned short, zf);
+    }
+    out[idx] = (uint32_t)scales[src] | (zb << 16);
 }
 
 // Inverse permutation (test hook): one thread per interchange word (k, j).
@@ -106,15 +146,29 @@ __global__ __launch_bounds__(256) void read16_kernel(const u32x4* __restrict__ s
 
 // ------------------------------------------------------------------------------------------ host launchers
 
-hipError_t launch_repack(const uint32_t* qweight, const uint16_t* scales, const uint16_t* zeros, uint32_t* w_out,
-                         uint32_t* sz_out, int K, int N, int group, hipStream_t stream)
+hipError_t launch_repack(const uint32_t* qweight, const uint16_t* scales, const void* zeros, uint32_t* w_out,
+                         uint32_t* sz_out, int K, int N, int group, int layout, hipStream_t stream)
 {
     const int KU = K / kUnitK, NT = N / kUnitN, G = K / group;
     dim3 grid((NT + 7) / 8, KU);
-    hipLaunchKernelGGL(repack_w4_kernel, grid, dim3(256), 0, stream, qweight, w_out, K, N);
     size_t total = (size_t)G * N;
-    hipLaunchKernelGGL(repack_sz_kernel, dim3((unsigned)((total + 255) / 256)), dim3(256), 0, stream, scales, zeros,
-                       sz_out, G, N);
+    dim3 szgrid((unsigned)((total + 255) / 256));
+    switch (layout) {
+    case 0:
+        hipLaunchKernelGGL(repack_w4_kernel<0>, grid, dim3(256), 0, stream, qweight, w_out, K, N);
+        hipLaunchKernelGGL(repack_sz_kernel<0>, szgrid, dim3(256), 0, stream, scales, zeros, sz_out, G, N);
+        break;
+    case 1:
+        hipLaunchKernelGGL(repack_w4_kernel<1>, grid, dim3(256), 0, stream, qweight, w_out, K, N);
+        hipLaunchKernelGGL(repack_sz_kernel<2>, szgrid, dim3(256), 0, stream, scales, zeros, sz_out, G, N);
+        break;
+    case 2:
+        hipLaunchKernelGGL(repack_w4_kernel<2>, grid, dim3(256), 0, stream, qweight, w_out, K, N);
+        hipLaunchKernelGGL(repack_sz_kernel<1>, szgrid, dim3(256), 0, stream, scales, zeros, sz_out, G, N);
+        break;
+    default:
+        return hipErrorInvalidValue;
+    }
     return hipGetLastError();
 }
 

@@ -33,7 +33,7 @@ def test_header_symbols_are_exported(lib):
 
 def test_binding_uses_same_names():
     import paper_2508_15601_amd as tm
-    for n in ("tm_pack_w4", "tm_gemm_w4a16", "tm_gemm_w4a16_ws", "tm_unpack_w4", "tm_packed_raw", "tm_get_plan",
+    for n in ("tm_pack_w4", "tm_pack_w4_layout", "tm_gemm_w4a16", "tm_gemm_w4a16_ws", "tm_unpack_w4", "tm_packed_raw", "tm_get_plan",
               "tm_set_variant", "tm_gemm_workspace_bytes", "tm_last_error", "tm_version"):
         assert callable(getattr(tm, n))
 
@@ -47,6 +47,14 @@ def test_argument_validation_without_gpu(lib):
         assert lib.tm_pack_w4(fake, fake, fake, K, N, g) is None
         assert tm.tm_last_error()
     assert lib.tm_pack_w4(ctypes.c_void_p(4097), fake, fake, 128, 16, 128) is None
+    assert "misaligned" in tm.tm_last_error()
+    lib.tm_pack_w4_layout.restype = ctypes.c_void_p
+    lib.tm_pack_w4_layout.argtypes = [ctypes.c_void_p] * 3 + [ctypes.c_int] * 4 + [ctypes.c_void_p]
+    assert lib.tm_pack_w4_layout(fake, fake, fake, 128, 16, 128, 3, None) is None
+    assert "layout" in tm.tm_last_error()
+    assert lib.tm_pack_w4_layout(fake, fake, None, 128, 16, 128, 2, None) is None
+    assert "null" in tm.tm_last_error()
+    assert lib.tm_pack_w4_layout(fake, fake, ctypes.c_void_p(4098), 128, 16, 128, 1, None) is None    # u32 zeros
     assert "misaligned" in tm.tm_last_error()
     assert lib.tm_gemm_w4a16(fake, None, fake, 1, None) == -1
     assert lib.tm_gemm_workspace_bytes(None, 4) == 0

@@ -66,6 +66,53 @@ def test_pack_bit_exact_against_oracle_unpack(tm, oracle, K, N, g):
         packed.close()
 
 
+@pytest.mark.parametrize("layout", [0, 1, 2])
+@pytest.mark.parametrize("K,N,g", [(128, 16, 128), (256, 48, 32), (384, 2064, 64), (1024, 272, 128)])
+def test_pack_layouts_bit_exact(tm, oracle, K, N, g, layout):
+    """Every interchange layout packs to the same fragment-ordered buffer: checked through the oracle's inverse
+    map (paper Sec. 4.1) and against the canonical-layout pack, bit for bit."""
+    import torch
+    _say(f"pack layout={layout} K={K} N={N} g={g}")
+    rng = np.random.default_rng(K * 11 + N + layout)
+    kk, nn = np.meshgrid(np.arange(K), np.arange(N), indexing="ij")
+    for qq in (rng.integers(0, 16, (K, N), dtype=np.uint8),
+               ((kk * 5 + nn * 3 + (kk >> 3) + (nn >> 4)) & 15).astype(np.uint8)):
+        s = rng.uniform(0.001, 0.02, (K // g, N)).astype(np.float16)
+        z = rng.integers(0, 16, (K // g, N)).astype(np.float16)
+        qw, zs = wl.encode_layout(qq, z, layout)
+        zt = gu.to_dev(zs) if layout == 0 else torch.from_numpy(zs.view(np.int32)).cuda()
+        packed = tm.tm_pack_w4_layout(torch.from_numpy(qw.view(np.int32)).cuda(), gu.to_dev(s), zt, K, N, g, layout)
+        wbuf, szbuf = tm.tm_packed_raw(packed)
+        q2, s2, z2 = oracle.unpack_packed(wbuf, szbuf, K, N, g)
+        assert np.array_equal(q2, qq)
+        assert np.array_equal(s2.view(np.uint16), s.view(np.uint16))
+        assert np.array_equal(z2.view(np.uint16), z.view(np.uint16))
+        ref = gu.pack({"q": qq, "qweight": wl.pack_interchange(qq), "s": s, "z": z}, g)
+        wref, szref = tm.tm_packed_raw(ref)
+        assert np.array_equal(wbuf, wref) and np.array_equal(szbuf, szref)
+        packed.close(); ref.close()
+
+
+@pytest.mark.parametrize("layout", [1, 2])
+def test_gemm_from_layouts(tm, oracle, layout):
+    """End to end from a non-canonical checkpoint layout: pack, multiply, compare with the oracle GEMM."""
+    import torch
+    case = wl.Case("layout", 24, 1024, 528, 64, seed=77 + layout)
+    _say(f"gemm layout={layout} {case}")
+    d = wl.make(case)
+    qw, zs = wl.encode_layout(d["q"], d["z"], layout)
+    packed = tm.tm_pack_w4_layout(torch.from_numpy(qw.view(np.int32)).cuda(), gu.to_dev(d["s"]),
+                                  torch.from_numpy(zs.view(np.int32)).cuda(), case.K, case.N, case.group, layout)
+    X = gu.to_dev(d["X"])
+    Y = torch.empty((case.M, case.N), dtype=torch.float16, device="cuda")
+    tm.tm_gemm_w4a16(X, packed, Y)
+    torch.cuda.synchronize()
+    Yref = oracle.gemm(d["X"], d["q"], d["s"], d["z"], case.group)
+    ok, worst, fro = acceptance(Y.cpu().numpy(), Yref)
+    assert ok, (layout, worst, fro)
+    packed.close()
+
+
 # ------------------------------------------------------------------ GEMM: exact special cases
 
 @pytest.mark.parametrize("variant", [-1] + list(range(22)))
