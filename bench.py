@@ -1,7 +1,7 @@
 #!/usr/bin/env python3
 """Benchmark of the W4A16 GEMM hot path on one MI355X.
 
-    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload decode|mlp_decode|prefill|sweep]
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload decode|mlp_decode|prefill|sweep|companion|pack|copy]
                     [--sweep-out FILE] [--no-cpu-baseline] [--no-prefill]
 
 A "step" is one pass of the fused GEMM over every (layer, M) pair of the workload, weights already packed
@@ -210,7 +210,7 @@ def main():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=200)
     ap.add_argument("--warmup", type=int, default=20)
-    ap.add_argument("--workload", default="decode", choices=sorted(WORKLOADS) + ["sweep", "copy", "companion"])
+    ap.add_argument("--workload", default="decode", choices=sorted(WORKLOADS) + ["sweep", "copy", "companion", "pack"])
     ap.add_argument("--sweep-out", default=None, help="with --workload sweep: write the per-shape table here (JSON)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-prefill", action="store_true", help="skip the prefill companion measurement")
@@ -245,6 +245,33 @@ def main():
         print(json.dumps({"metric": "plain copy (counter calibration)", "bytes_read": n, "bytes_written": n,
                           "steps": args.steps, "ms_per_step": ev_ms / args.steps,
                           "GBps_read_plus_write": 2 * n / (ev_ms / args.steps * 1e-3) / 1e9}))
+        return
+
+    if args.workload == "pack":
+        # offline packing of one gate/up-shaped matrix from every interchange layout (wall time per call includes
+        # the handle's two device allocations; kernel times come from a profiler run of this same command)
+        import numpy as np
+        K, N, g = 4096, 22016, 128
+        rng = np.random.default_rng(0)
+        q = rng.integers(0, 16, (K, N), dtype=np.uint8)
+        s = torch.from_numpy(rng.uniform(0.001, 0.02, (K // g, N)).astype(np.float16)).cuda()
+        z = rng.integers(0, 16, (K // g, N)).astype(np.float16)
+        rows = []
+        for layout in (tm.TM_LAYOUT_N8, tm.TM_LAYOUT_N8_INTERLEAVED, tm.TM_LAYOUT_K8):
+            qw, zs = wl.encode_layout(q, z, layout)
+            qd = torch.from_numpy(qw.view(np.int32)).cuda()
+            zd = torch.from_numpy(zs if layout == tm.TM_LAYOUT_N8 else zs.view(np.int32)).cuda()
+            def once():
+                tm.tm_pack_w4_layout(qd, s, zd, K, N, g, layout).close()       # close() synchronises
+            for _ in range(args.warmup):
+                once()
+            t0 = time.perf_counter()
+            for _ in range(args.steps):
+                once()
+            ms = (time.perf_counter() - t0) * 1e3 / args.steps
+            rows.append({"layout": layout, "ms_per_pack_call": ms})
+            log(f"layout {layout}: {ms:.3f} ms per pack call (allocation + two kernels + free)")
+        print(json.dumps({"metric": "offline pack", "K": K, "N": N, "group": g, "steps": args.steps, "rows": rows}))
         return
 
     if args.workload == "companion":

@@ -51,8 +51,8 @@ typedef void* tm_stream;                   /* a hipStream_t */
  *
  *   qweight  u32 [K][N/8]       interchange layout "eight INT4 values per 32-bit word" (Sec. 3.2, M2):
  *                               nibble t (bits 4t..4t+3) of word (k, j) is q[k][8j + t], values 0..15
- *   scales   fp16 [K/group][N]  s, finite and positive
- *   zeros    fp16 [K/group][N]  z, integer-valued in [0, 15]
+ *   scales   fp16 [K/group][N]  s, finite and positive; group = 32, 64 or a multiple of 128 dividing K
+ *   zeros    fp16 [K/group][N]  z, integer-valued in [0, 15] (NULL: z = 8 everywhere, see tm_pack_w4_layout)
  *
  * Allocates the handle's device buffers (K*N/2 bytes of weights, 4*K*N/group bytes of scale/zero pairs), makes sure
  * the device-wide split-K workspace is large enough for this shape, and enqueues the repack kernels on `stream`.
@@ -83,7 +83,12 @@ TM_API tm_packed_w4* tm_pack_w4_on(const uint32_t* qweight, const uint16_t* scal
  *   TM_LAYOUT_K8              qweight u32 [K/8][N], nibble t of word (i, n) = q[8i + t][n];
  *                             zeros u32 [K/group][N/8], nibble t of word (G, j) = z[G][8j + t]
  *
- * scales is fp16 [K/group][N] in every layout.  The zero integers are used as stored (a checkpoint convention that
+ * scales is fp16 [K/group][N] in every layout.  Two further conventions are read here (and by tm_pack_w4 / _on):
+ *   - group may also be any multiple of 128 that divides K (group == K: one scale per output channel); such weights
+ *     are stored with their scale/zero rows repeated at the kernels' group of 128, which is what tm_packed_info then
+ *     reports;
+ *   - zeros == NULL means symmetric quantisation: every zero-point is 8 (q - 8 in [-8, 7]).
+ * The zero integers are used as stored (a checkpoint convention that
  * keeps z - 1 must be undone by the caller).  Shapes, alignment (4 bytes for u32 buffers), ownership and errors are
  * those of tm_pack_w4_on; an unknown layout is TM_EINVAL (NULL return).
  */

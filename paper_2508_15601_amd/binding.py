@@ -137,16 +137,9 @@ class PackedW4:
 
 
 def tm_pack_w4(qweight, scales, zeros, K: int, N: int, group: int, stream=None) -> PackedW4:
-    """qweight int32 [K, N/8] (interchange nibble order), scales/zeros float16 [K/group, N] -> PackedW4."""
-    import torch
-    lib = load_library()
-    if tuple(qweight.shape) != (K, N // 8) or tuple(scales.shape) != (K // group, N) or tuple(zeros.shape) != (K // group, N):
-        raise ValueError("tensor shapes do not match K, N, group")
-    h = lib.tm_pack_w4_on(_dev_ptr(qweight, torch.int32, "qweight"), _dev_ptr(scales, torch.float16, "scales"),
-                          _dev_ptr(zeros, torch.float16, "zeros"), K, N, group, _stream_ptr(stream))
-    if not h:
-        raise TmError(-1, tm_last_error())
-    return PackedW4(h, K, N, group)
+    """qweight int32 [K, N/8] (interchange nibble order), scales/zeros float16 [K/group, N] -> PackedW4.
+    zeros=None packs symmetric weights (zero-point 8); group may be 32, 64 or a multiple of 128 dividing K."""
+    return tm_pack_w4_layout(qweight, scales, zeros, K, N, group, TM_LAYOUT_N8, stream)
 
 
 TM_LAYOUT_N8, TM_LAYOUT_N8_INTERLEAVED, TM_LAYOUT_K8 = 0, 1, 2
@@ -159,13 +152,15 @@ def tm_pack_w4_layout(qweight, scales, zeros, K: int, N: int, group: int, layout
     lib = load_library()
     qshape = (K // 8, N) if layout == TM_LAYOUT_K8 else (K, N // 8)
     zshape, zdtype = ((K // group, N), torch.float16) if layout == TM_LAYOUT_N8 else ((K // group, N // 8), torch.int32)
-    if tuple(qweight.shape) != qshape or tuple(scales.shape) != (K // group, N) or tuple(zeros.shape) != zshape:
+    if tuple(qweight.shape) != qshape or tuple(scales.shape) != (K // group, N) or \
+            (zeros is not None and tuple(zeros.shape) != zshape):
         raise ValueError("tensor shapes do not match K, N, group, layout")
+    zptr = None if zeros is None else _dev_ptr(zeros, zdtype, "zeros")
     h = lib.tm_pack_w4_layout(_dev_ptr(qweight, torch.int32, "qweight"), _dev_ptr(scales, torch.float16, "scales"),
-                              _dev_ptr(zeros, zdtype, "zeros"), K, N, group, layout, _stream_ptr(stream))
+                              zptr, K, N, group, layout, _stream_ptr(stream))
     if not h:
         raise TmError(-1, tm_last_error())
-    return PackedW4(h, K, N, group)
+    return PackedW4(h, K, N, min(group, 128))
 
 
 def tm_gemm_w4a16(X, packed: PackedW4, Y, stream=None):

@@ -316,16 +316,16 @@ tm_packed_w4* tm_pack_w4_layout(const void* qweight, const uint16_t* scales, con
         fail(TM_EINVAL, "unknown layout %d", layout);
         return nullptr;
     }
-    if (!qweight || !scales || !zeros) {
-        fail(TM_EINVAL, "qweight, scales or zeros is null");
+    if (!qweight || !scales) {
+        fail(TM_EINVAL, "qweight or scales is null");
         return nullptr;
     }
     if (K <= 0 || N <= 0 || K % kUnitK || N % kUnitN) {
         fail(TM_EINVAL, "need K %% 128 == 0 and N %% 16 == 0 (K = %d, N = %d)", K, N);
         return nullptr;
     }
-    if (group != 32 && group != 64 && group != 128) {
-        fail(TM_EINVAL, "group must be 32, 64 or 128 (got %d)", group);
+    if (group != 32 && group != 64 && !(group >= 128 && group % 128 == 0 && K % group == 0)) {
+        fail(TM_EINVAL, "group must be 32, 64 or a multiple of 128 that divides K (got %d)", group);
         return nullptr;
     }
     if ((double)K * (double)N >= 1099511627776.0) {
@@ -336,6 +336,8 @@ tm_packed_w4* tm_pack_w4_layout(const void* qweight, const uint16_t* scales, con
         fail(TM_EINVAL, "misaligned input");
         return nullptr;
     }
+    const int caller_group = group;
+    if (group > 128) group = 128;                  // coarser groups are stored replicated at the kernels' 128 rows
     int dev;
     if (check_device(&dev) != TM_OK) return nullptr;
     if (ensure_workspace(dev) != TM_OK) return nullptr;
@@ -361,7 +363,7 @@ tm_packed_w4* tm_pack_w4_layout(const void* qweight, const uint16_t* scales, con
         delete h;
         return nullptr;
     }
-    e = launch_repack((const uint32_t*)qweight, scales, zeros, h->w, h->sz, K, N, group, layout,
+    e = launch_repack((const uint32_t*)qweight, scales, zeros, h->w, h->sz, K, N, caller_group, layout,
                       (hipStream_t)stream);
     if (e != hipSuccess) {
         fail_hip(e, "repack launch");

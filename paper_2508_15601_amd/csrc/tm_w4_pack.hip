@@ -69,22 +69,26 @@ __global__ __launch_bounds__(256) void repack_w4_kernel(const uint32_t* __restri
 
 // ZFMT: 0 zeros are fp16 [G][N]; 1 u32 [G][N/8], nibble t = column 8j+t; 2 u32 [G][N/8], nibble p = column
 // 8j + (0,2,4,6,1,3,5,7)[p].  Packed integers are widened to the fp16 pattern the GEMM kernels expect.
+// G counts the stored groups; source row g / rep feeds stored group g (rep > 1 when the caller's groups are coarser
+// than the 128 rows the kernels work with).  zeros == nullptr stands for the symmetric zero-point 8.
 template <int ZFMT>
 __global__ __launch_bounds__(256) void repack_sz_kernel(const uint16_t* __restrict__ scales,
                                                         const void* __restrict__ zeros,
-                                                        uint32_t* __restrict__ out, int G, int N)
+                                                        uint32_t* __restrict__ out, int G, int N, int rep)
 {
     size_t idx = (size_t)blockIdx.x * 256 + threadIdx.x;
     size_t total = (size_t)G * N;
     if (idx >= total) return;
     int c = idx & 15;
     size_t r = idx >> 4;
-    int g = (int)(r % G);
+    int g = (int)(r % G) / rep;
     int nt = (int)(r / G);
     int n = 16 * nt + c;
     size_t src = (size_t)g * N + n;
     uint32_t zb;
-    if constexpr (ZFMT == 0) {
+    if (!zeros) {
+        zb = 0x4800u;                              // fp16 8.0
+    } else if constexpr (ZFMT == 0) {
         zb = ((const uint16_t*)zeros)[src];
     } else {
         int t = n & 7;
@@ -149,22 +153,24 @@ __global__ __launch_bounds__(256) void read16_kernel(const u32x4* __restrict__ s
 hipError_t launch_repack(const uint32_t* qweight, const uint16_t* scales, const void* zeros, uint32_t* w_out,
                          uint32_t* sz_out, int K, int N, int group, int layout, hipStream_t stream)
 {
-    const int KU = K / kUnitK, NT = N / kUnitN, G = K / group;
+    // group is what the caller's scales are laid out for; coarser groups than 128 rows are stored as 128
+    const int stored = group > 128 ? 128 : group, rep = group / stored;
+    const int KU = K / kUnitK, NT = N / kUnitN, G = K / stored;
     dim3 grid((NT + 7) / 8, KU);
     size_t total = (size_t)G * N;
     dim3 szgrid((unsigned)((total + 255) / 256));
     switch (layout) {
     case 0:
         hipLaunchKernelGGL(repack_w4_kernel<0>, grid, dim3(256), 0, stream, qweight, w_out, K, N);
-        hipLaunchKernelGGL(repack_sz_kernel<0>, szgrid, dim3(256), 0, stream, scales, zeros, sz_out, G, N);
+        hipLaunchKernelGGL(repack_sz_kernel<0>, szgrid, dim3(256), 0, stream, scales, zeros, sz_out, G, N, rep);
         break;
     case 1:
         hipLaunchKernelGGL(repack_w4_kernel<1>, grid, dim3(256), 0, stream, qweight, w_out, K, N);
-        hipLaunchKernelGGL(repack_sz_kernel<2>, szgrid, dim3(256), 0, stream, scales, zeros, sz_out, G, N);
+        hipLaunchKernelGGL(repack_sz_kernel<2>, szgrid, dim3(256), 0, stream, scales, zeros, sz_out, G, N, rep);
         break;
     case 2:
         hipLaunchKernelGGL(repack_w4_kernel<2>, grid, dim3(256), 0, stream, qweight, w_out, K, N);
-        hipLaunchKernelGGL(repack_sz_kernel<1>, szgrid, dim3(256), 0, stream, scales, zeros, sz_out, G, N);
+        hipLaunchKernelGGL(repack_sz_kernel<1>, szgrid, dim3(256), 0, stream, scales, zeros, sz_out, G, N, rep);
         break;
     default:
         return hipErrorInvalidValue;

@@ -52,8 +52,12 @@ def test_argument_validation_without_gpu(lib):
     lib.tm_pack_w4_layout.argtypes = [ctypes.c_void_p] * 3 + [ctypes.c_int] * 4 + [ctypes.c_void_p]
     assert lib.tm_pack_w4_layout(fake, fake, fake, 128, 16, 128, 3, None) is None
     assert "layout" in tm.tm_last_error()
-    assert lib.tm_pack_w4_layout(fake, fake, None, 128, 16, 128, 2, None) is None
+    assert lib.tm_pack_w4_layout(fake, None, fake, 128, 16, 128, 2, None) is None
     assert "null" in tm.tm_last_error()
+    assert lib.tm_pack_w4_layout(fake, fake, None, 256, 16, 192, 0, None) is None       # 192 is no multiple of 128
+    assert "group" in tm.tm_last_error()
+    assert lib.tm_pack_w4_layout(fake, fake, None, 384, 16, 256, 0, None) is None       # 256 does not divide 384
+    assert "group" in tm.tm_last_error()
     assert lib.tm_pack_w4_layout(fake, fake, ctypes.c_void_p(4098), 128, 16, 128, 1, None) is None    # u32 zeros
     assert "misaligned" in tm.tm_last_error()
     assert lib.tm_gemm_w4a16(fake, None, fake, 1, None) == -1

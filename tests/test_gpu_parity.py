@@ -93,6 +93,32 @@ def test_pack_layouts_bit_exact(tm, oracle, K, N, g, layout):
         packed.close(); ref.close()
 
 
+@pytest.mark.parametrize("K,N,g,M", [(512, 48, 256, 5), (1024, 272, 1024, 3), (768, 528, 384, 40), (2048, 1040, 2048, 300)])
+@pytest.mark.parametrize("symmetric", [False, True])
+def test_coarse_groups_and_symmetric(tm, oracle, K, N, g, M, symmetric):
+    """Groups coarser than 128 rows (up to one scale per channel) and symmetric weights (zero-point 8, passed as
+    no zeros at all): the stored buffer holds the repeated rows, and the GEMM matches the oracle run with the
+    caller's own group size."""
+    import torch
+    _say(f"coarse group K={K} N={N} g={g} M={M} symmetric={symmetric}")
+    rng = np.random.default_rng(K + N + g)
+    q = rng.integers(0, 16, (K, N), dtype=np.uint8)
+    s = rng.uniform(0.001, 0.02, (K // g, N)).astype(np.float16)
+    z = np.full((K // g, N), 8, np.float16) if symmetric else rng.integers(0, 16, (K // g, N)).astype(np.float16)
+    X = rng.standard_normal((M, K)).astype(np.float16)
+    packed = tm.tm_pack_w4(gu.to_dev(wl.pack_interchange(q)), gu.to_dev(s), None if symmetric else gu.to_dev(z), K, N, g)
+    assert packed.group == 128
+    wbuf, szbuf = tm.tm_packed_raw(packed)
+    q2, s2, z2 = oracle.unpack_packed(wbuf, szbuf, K, N, 128)
+    assert np.array_equal(q2, q)
+    assert np.array_equal(s2.view(np.uint16), np.repeat(s, g // 128, axis=0).view(np.uint16))
+    assert np.array_equal(z2.view(np.uint16), np.repeat(z, g // 128, axis=0).view(np.uint16))
+    Y = gu.gemm(packed, X)
+    ok, worst, fro = acceptance(Y, oracle.gemm(X, q, s, z, g))
+    assert ok, (worst, fro)
+    packed.close()
+
+
 @pytest.mark.parametrize("layout", [1, 2])
 def test_gemm_from_layouts(tm, oracle, layout):
     """End to end from a non-canonical checkpoint layout: pack, multiply, compare with the oracle GEMM."""
