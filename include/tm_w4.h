@@ -122,6 +122,34 @@ TM_API size_t tm_gemm_workspace_bytes(const tm_packed_w4* packed, int M);
 /* Releases the handle and its device buffers.  NULL is ignored.  The caller makes sure no enqueued work still uses it. */
 TM_API void tm_free_packed(tm_packed_w4* packed);
 
+/*
+ * Grouped GEMM for mixture-of-experts layers.  The paper's evaluation includes MoE models (Sec. 5.1, Sec. 5.3) and
+ * describes no separate kernel for them: an expert layer is the same mixed-precision GEMM (Sec. 3.1) once per expert,
+ * each on the rows routed to it.  With the rows of X sorted by expert,
+ *
+ *     Y[r][:] = X[r][:] * dequant(expert e),   offsets[e] <= r < offsets[e+1],   e = 0 .. num_experts-1
+ *
+ * tm_group_experts (offline, once per layer): `experts` is a HOST array of num_experts handles (1..65535) with equal
+ * K, N, group and device; it allocates a small device table of their buffer addresses (synchronous copy).  The group
+ * borrows the handles: they must outlive it.  Returns NULL on error.  tm_free_expert_group releases the table only.
+ *
+ * tm_gemm_w4a16_grouped (online): X fp16 [total_rows][K], Y fp16 [total_rows][N], both 16-byte aligned; offsets is a
+ * DEVICE array of num_experts + 1 ascending int32 row indices, so routing results never pass through the host.  One
+ * launch covers all experts; an expert without rows costs one read of its offsets.  Rows outside
+ * [offsets[0], offsets[num_experts]) are left untouched; offsets are clamped to [0, total_rows].  Never allocates,
+ * uses no workspace (K is not split across CTAs), results are bit-identical from run to run.  The kernels are the
+ * decode (M <= 64 per pass) kernels: an expert with more rows is processed 16-64 rows at a time and re-reads its
+ * weights for each pass, which is correct for any load but only efficient for decode-sized batches.
+ * total_rows == 0 is a successful no-op; total_rows < 2^24.
+ */
+typedef struct tm_expert_group tm_expert_group;
+TM_API tm_expert_group* tm_group_experts(const tm_packed_w4* const* experts, int num_experts);
+TM_API void tm_free_expert_group(tm_expert_group* group);
+TM_API int tm_gemm_w4a16_grouped(const uint16_t* X, const tm_expert_group* group, const int32_t* offsets, uint16_t* Y,
+                                 int total_rows, tm_stream stream);
+/* Kernel variant and strips per expert the grouped launch would use (host out-pointers, may be NULL). */
+TM_API int tm_get_grouped_plan(const tm_expert_group* group, int total_rows, int* variant, int* strips);
+
 /* Shape of a handle; any out-pointer (host) may be NULL.  `bytes` = device bytes held (weights + scale/zero pairs). */
 TM_API int tm_packed_info(const tm_packed_w4* packed, int* K, int* N, int* group, size_t* bytes);
 

@@ -187,6 +187,20 @@ def gemm(X: np.ndarray, q: np.ndarray, s: np.ndarray, z: np.ndarray, group: int,
     return (Y.view(np.float16), Yd) if want_fp64 else Y.view(np.float16)
 
 
+def gemm_grouped(X: np.ndarray, experts, offsets, group: int) -> np.ndarray:
+    """Mixture-of-experts layer with rows sorted by expert (the MoE models of paper Sec. 5.1 run the GEMM of Sec. 3.1
+    once per expert): rows offsets[e] <= r < offsets[e+1] of X go through expert e = (q, s, z).  Rows no expert
+    claims come back as NaN so that a test can see they were left alone.  One gemm() call per expert, nothing else."""
+    X = np.asarray(X)
+    N = experts[0][0].shape[1]
+    Y = np.full((X.shape[0], N), np.nan, np.float16)
+    for e, (q, s, z) in enumerate(experts):
+        r0, r1 = int(offsets[e]), int(offsets[e + 1])
+        if r1 > r0:
+            Y[r0:r1] = gemm(X[r0:r1], q, s, z, group)
+    return Y
+
+
 def gemm_sampled(X, q, s, z, group: int, ms, ns, want_fp64: bool = False):
     """The plain triple loop evaluated only at the listed (m, n) pairs."""
     X = _as(X, np.uint16)

@@ -42,6 +42,14 @@ def load_library():
     lib.tm_pack_w4.argtypes = [vp, vp, vp, i, i, i]
     lib.tm_pack_w4_on.restype = vp
     lib.tm_pack_w4_on.argtypes = [vp, vp, vp, i, i, i, vp]
+    lib.tm_group_experts.restype = vp
+    lib.tm_group_experts.argtypes = [vp, i]
+    lib.tm_free_expert_group.restype = None
+    lib.tm_free_expert_group.argtypes = [vp]
+    lib.tm_gemm_w4a16_grouped.restype = i
+    lib.tm_gemm_w4a16_grouped.argtypes = [vp, vp, vp, vp, i, vp]
+    lib.tm_get_grouped_plan.restype = i
+    lib.tm_get_grouped_plan.argtypes = [vp, i, vp, vp]
     lib.tm_pack_w4_layout.restype = vp
     lib.tm_pack_w4_layout.argtypes = [vp, vp, vp, i, i, i, i, vp]
     lib.tm_gemm_w4a16.restype = i
@@ -161,6 +169,64 @@ def tm_pack_w4_layout(qweight, scales, zeros, K: int, N: int, group: int, layout
     if not h:
         raise TmError(-1, tm_last_error())
     return PackedW4(h, K, N, min(group, 128))
+
+
+class ExpertGroup:
+    """Owner of a tm_expert_group handle; keeps its PackedW4 experts alive."""
+
+    def __init__(self, handle: int, experts):
+        self._h = handle
+        self.experts = list(experts)
+        self.K, self.N, self.group = experts[0].K, experts[0].N, experts[0].group
+
+    @property
+    def handle(self):
+        if not self._h:
+            raise ValueError("expert group already freed")
+        return ctypes.c_void_p(self._h)
+
+    def close(self):
+        if self._h:
+            import torch
+            torch.cuda.synchronize()
+            load_library().tm_free_expert_group(ctypes.c_void_p(self._h))
+            self._h = 0
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass
+
+
+def tm_group_experts(experts) -> ExpertGroup:
+    """experts: sequence of PackedW4 with equal K, N, group -> ExpertGroup."""
+    lib = load_library()
+    arr = (ctypes.c_void_p * len(experts))(*[p.handle for p in experts])
+    h = lib.tm_group_experts(arr, len(experts))
+    if not h:
+        raise TmError(-1, tm_last_error())
+    return ExpertGroup(h, experts)
+
+
+def tm_gemm_w4a16_grouped(X, group: ExpertGroup, offsets, Y, stream=None):
+    """Rows offsets[e]..offsets[e+1] of X [R,K] times expert e -> the same rows of Y [R,N]; offsets int32 on the device."""
+    import torch
+    R = X.shape[0]
+    if X.dim() != 2 or X.shape[1] != group.K or tuple(Y.shape) != (R, group.N) or offsets.numel() != len(group.experts) + 1:
+        raise ValueError("X/Y/offsets shapes do not match the expert group")
+    if R == 0:
+        return Y
+    _check(load_library().tm_gemm_w4a16_grouped(_dev_ptr(X, torch.float16, "X"), group.handle,
+                                                _dev_ptr(offsets, torch.int32, "offsets"),
+                                                _dev_ptr(Y, torch.float16, "Y"), R, _stream_ptr(stream)))
+    return Y
+
+
+def tm_get_grouped_plan(group: ExpertGroup, total_rows: int):
+    v, st = ctypes.c_int(), ctypes.c_int()
+    _check(load_library().tm_get_grouped_plan(group.handle, total_rows, ctypes.byref(v), ctypes.byref(st)))
+    return v.value, st.value
 
 
 def tm_gemm_w4a16(X, packed: PackedW4, Y, stream=None):

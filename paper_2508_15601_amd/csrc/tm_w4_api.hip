@@ -5,6 +5,7 @@
 
 #include <mutex>
 #include <new>
+#include <vector>
 
 #include "tm_w4.h"
 #include "tm_w4_host.h"
@@ -98,11 +99,43 @@ struct tm_packed_w4 {
     size_t w_bytes, sz_bytes;
 };
 
+struct tm_expert_group {
+    uint32_t magic;
+    int experts, K, N, group, device;
+    uint64_t* table;   // device: per expert, address of the packed weights and of the scale/zero words
+};
+
 namespace tmw4 {
 
 namespace {
 
+constexpr uint32_t kGroupMagic = 0x746D4547u;
+
 bool valid(const tm_packed_w4* p) { return p && p->magic == kMagic; }
+bool valid(const tm_expert_group* g) { return g && g->magic == kGroupMagic; }
+int ceil_div(int a, int b);
+
+// Kernel choice for the grouped launch.  The rows per expert live on the device, so the row-tile height comes from
+// the average load (total_rows / experts) and the strip width from how many strips the experts that can be active
+// need to cover the chip; wide strips reuse each activation fragment for more weights.
+void grouped_plan(const tm_expert_group* g, int total_rows, int num_cu, int* variant, int* strips)
+{
+    const int NT = g->N / kUnitN;
+    const int avg = ceil_div(total_rows, g->experts);
+    const int active = total_rows < g->experts ? total_rows : g->experts;
+    const int want = ceil_div(2 * num_cu, active > 0 ? active : 1);         // strips per expert for two CTAs per CU
+    int per = NT / (want > NT ? NT : want);                                  // tiles per strip, at least one
+    int v;
+    if (g_force_variant >= 0) v = g_force_variant;
+    else if (avg > 32) v = kSkinny64x64;
+    else if (avg > 16) v = kSkinny32x64;
+    else v = per >= 8 ? kSkinny16x128 : per >= 4 ? kSkinny16x64 : per >= 2 ? kSkinny16x32 : kSkinny16x16;
+    const int ntw = skinny_ntw(v);
+    if (per > ntw) per = ntw;
+    int st = ceil_div(NT, per);
+    *variant = v;
+    *strips = st;
+}
 
 int ceil_div(int a, int b) { return (a + b - 1) / b; }
 
@@ -390,6 +423,111 @@ tm_packed_w4* tm_pack_w4(const uint32_t* qweight, const uint16_t* scales, const 
 int tm_gemm_w4a16(const uint16_t* X, const tm_packed_w4* packed, uint16_t* Y, int M, tm_stream stream)
 {
     return run_gemm(X, packed, Y, M, nullptr, 0, true, (hipStream_t)stream);
+}
+
+tm_expert_group* tm_group_experts(const tm_packed_w4* const* experts, int num_experts)
+{
+    if (!experts || num_experts <= 0 || num_experts > 65535) {
+        fail(TM_EINVAL, "experts is null or num_experts = %d out of range (1..65535)", num_experts);
+        return nullptr;
+    }
+    for (int e = 0; e < num_experts; ++e) {
+        if (!valid(experts[e])) {
+            fail(TM_EINVAL, "expert %d: handle is null or invalid", e);
+            return nullptr;
+        }
+        if (experts[e]->K != experts[0]->K || experts[e]->N != experts[0]->N ||
+            experts[e]->group != experts[0]->group || experts[e]->device != experts[0]->device) {
+            fail(TM_EINVAL, "expert %d differs from expert 0 in K, N, group or device", e);
+            return nullptr;
+        }
+    }
+    int dev;
+    if (check_device(&dev) != TM_OK) return nullptr;
+    if (dev != experts[0]->device) {
+        fail(TM_EINVAL, "experts live on device %d, current device is %d", experts[0]->device, dev);
+        return nullptr;
+    }
+    std::vector<uint64_t> host(2 * (size_t)num_experts);
+    for (int e = 0; e < num_experts; ++e) {
+        host[2 * e] = (uint64_t)(uintptr_t)experts[e]->w;
+        host[2 * e + 1] = (uint64_t)(uintptr_t)experts[e]->sz;
+    }
+    tm_expert_group* g = new (std::nothrow) tm_expert_group();
+    if (!g) {
+        fail(TM_ENOMEM, "host allocation failed");
+        return nullptr;
+    }
+    hipError_t e = hipMalloc((void**)&g->table, host.size() * sizeof(uint64_t));
+    if (e == hipSuccess) {
+        e = hipMemcpy(g->table, host.data(), host.size() * sizeof(uint64_t), hipMemcpyHostToDevice);
+        if (e != hipSuccess) (void)hipFree(g->table);
+    }
+    if (e != hipSuccess) {
+        fail_hip(e, "expert table");
+        delete g;
+        return nullptr;
+    }
+    g->magic = kGroupMagic;
+    g->experts = num_experts;
+    g->K = experts[0]->K;
+    g->N = experts[0]->N;
+    g->group = experts[0]->group;
+    g->device = dev;
+    return g;
+}
+
+void tm_free_expert_group(tm_expert_group* group)
+{
+    if (!valid(group)) return;
+    group->magic = 0;
+    (void)hipFree(group->table);
+    delete group;
+}
+
+int tm_gemm_w4a16_grouped(const uint16_t* X, const tm_expert_group* group, const int32_t* offsets, uint16_t* Y,
+                          int total_rows, tm_stream stream)
+{
+    if (!valid(group)) return fail(TM_EINVAL, "expert group is null or invalid");
+    if (total_rows == 0) return TM_OK;
+    if (!X || !Y || !offsets) return fail(TM_EINVAL, "X, Y or offsets is null");
+    if (total_rows < 0 || total_rows >= (1 << 24))
+        return fail(TM_EINVAL, "total_rows = %d out of range", total_rows);
+    if (((uintptr_t)X & 15) || ((uintptr_t)Y & 15) || ((uintptr_t)offsets & 3)) return fail(TM_EINVAL, "misaligned X, Y or offsets");
+    int dev;
+    int rc = check_device(&dev);
+    if (rc != TM_OK) return rc;
+    if (dev != group->device) return fail(TM_EINVAL, "experts live on device %d, current device is %d", group->device, dev);
+    int variant, strips;
+    grouped_plan(group, total_rows, g_dev[dev].num_cu, &variant, &strips);
+    GroupedParams gp{};
+    gp.X = X;
+    gp.Y = Y;
+    gp.table = group->table;
+    gp.offsets = offsets;
+    gp.K = group->K;
+    gp.N = group->N;
+    gp.KU = group->K / kUnitK;
+    gp.NT = group->N / kUnitN;
+    gp.G = group->K / group->group;
+    gp.strips = strips;
+    gp.total_rows = total_rows;
+    hipError_t e = launch_skinny_grouped(gp, variant, group->experts, group->group, (hipStream_t)stream);
+    if (e != hipSuccess) return fail_hip(e, "grouped kernel launch");
+    return TM_OK;
+}
+
+int tm_get_grouped_plan(const tm_expert_group* group, int total_rows, int* variant, int* strips)
+{
+    if (!valid(group)) return fail(TM_EINVAL, "expert group is null or invalid");
+    if (total_rows <= 0) return fail(TM_EINVAL, "total_rows = %d out of range", total_rows);
+    int dev = group->device;
+    int cu = (dev >= 0 && dev < kMaxDevices && g_dev[dev].checked) ? g_dev[dev].num_cu : 256;
+    int v, st;
+    grouped_plan(group, total_rows, cu, &v, &st);
+    if (variant) *variant = v;
+    if (strips) *strips = st;
+    return TM_OK;
 }
 
 int tm_gemm_w4a16_ws(const uint16_t* X, const tm_packed_w4* packed, uint16_t* Y, int M, void* workspace,

@@ -35,6 +35,15 @@ struct GemmParams {
     int strips;               // skinny kernel only: strip s owns tiles [s*NT/strips, (s+1)*NT/strips)
 };
 
+// Grouped (mixture-of-experts) launch: rows [offsets[e], offsets[e+1]) of X and Y belong to expert e.
+struct GroupedParams {
+    const uint16_t* X;
+    uint16_t* Y;
+    const uint64_t* table;      // per expert: address of the packed weights, address of the scale/zero words
+    const int32_t* offsets;     // [experts + 1], ascending
+    int K, N, KU, NT, G, strips, total_rows;
+};
+
 __device__ __forceinline__ f16x2 as_f16x2(uint32_t u) { return __builtin_bit_cast(f16x2, u); }
 
 // Per-(column, K-group) constants of the conversion: the scale in both halves, and the two exact offsets that

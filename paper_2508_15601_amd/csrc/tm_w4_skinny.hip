@@ -137,20 +137,21 @@ __device__ __forceinline__ void compute_stage(const Stage<TM, NTW, GPU>& st, f32
 
 // TM 16-row tiles, NTW 16-column tiles per wave, GPU K-groups per 128-row unit, D register stages per wave,
 // MAXW the largest CTA (in waves) this instantiation is launched with.
-template <int TM, int NTW, int GPU, int D, int MAXW>
-__global__ __launch_bounds__(MAXW * 64) void skinny_kernel(GemmParams p)
+//
+// One CTA's work on one GEMM: strip and K slice follow from `bx`, the CTA's index among p.strips * p.split.
+// red is [waves][NTW*4][64] floats of LDS (one 16 x 16*NTW fp32 tile per wave), s_last one LDS word.
+template <int TM, int NTW, int GPU, int D>
+__device__ __forceinline__ void skinny_body(const GemmParams& p, const int bx, float* __restrict__ red,
+                                            uint32_t& s_last)
 {
-    extern __shared__ float red[];                 // [waves][NTW*4][64]: one 16 x 16*NTW fp32 tile per wave
-    __shared__ uint32_t s_last;
-
     const int tid = threadIdx.x;
     const int lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);     // wave-uniform by construction
     const int waves = blockDim.x >> 6;
     // The NT column tiles are dealt evenly into p.strips strips (widths differ by at most one tile), so that a
     // shape whose tile count is not a multiple of the CU count still loads every CU almost equally.
-    const int strip = blockIdx.x % p.strips;
-    const int sk = blockIdx.x / p.strips;
+    const int strip = bx % p.strips;
+    const int sk = bx / p.strips;
     const int nt0 = (int)(((long)strip * p.NT) / p.strips);
     const int ntw = (int)(((long)(strip + 1) * p.NT) / p.strips) - nt0;     // <= NTW (host guarantees)
     const int ku0 = sk * p.ku_per_split;
@@ -264,6 +265,56 @@ __global__ __launch_bounds__(MAXW * 64) void skinny_kernel(GemmParams p)
     }
 }
 
+template <int TM, int NTW, int GPU, int D, int MAXW>
+__global__ __launch_bounds__(MAXW * 64) void skinny_kernel(GemmParams p)
+{
+    extern __shared__ float red[];
+    __shared__ uint32_t s_last;
+    skinny_body<TM, NTW, GPU, D>(p, blockIdx.x, red, s_last);
+}
+
+// Grouped form for mixture-of-experts layers (the paper's evaluation covers MoE models, Sec. 5.1; their expert GEMMs
+// are this same GEMM once per expert): rows [offsets[e], offsets[e+1]) of X and Y belong to expert e, whose packed
+// weights the pointer table names.  blockIdx.y is the expert, blockIdx.x the strip; an expert without rows costs
+// one offsets read.  Experts with more than 16*TM rows are taken 16*TM rows at a time.
+__device__ __forceinline__ uint64_t uniform64(uint64_t v)
+{
+    uint32_t lo = __builtin_amdgcn_readfirstlane((uint32_t)v), hi = __builtin_amdgcn_readfirstlane((uint32_t)(v >> 32));
+    return ((uint64_t)hi << 32) | lo;
+}
+
+template <int TM, int NTW, int GPU, int D, int MAXW>
+__global__ __launch_bounds__(MAXW * 64) void skinny_grouped_kernel(GroupedParams gp)
+{
+    extern __shared__ float red[];
+    __shared__ uint32_t s_last;
+    const int e = blockIdx.y;
+    // rows are clamped to the buffers whatever the offsets hold
+    int r0 = __builtin_amdgcn_readfirstlane(gp.offsets[e]);
+    int r1 = __builtin_amdgcn_readfirstlane(gp.offsets[e + 1]);
+    r0 = min(max(r0, 0), gp.total_rows);
+    r1 = min(r1, gp.total_rows);
+    if (r1 <= r0) return;
+    GemmParams p{};
+    p.W = (const u32x4*)uniform64(gp.table[2 * e]);
+    p.SZ = (const uint32_t*)uniform64(gp.table[2 * e + 1]);
+    p.K = gp.K;
+    p.N = gp.N;
+    p.KU = gp.KU;
+    p.NT = gp.NT;
+    p.G = gp.G;
+    p.split = 1;
+    p.ku_per_split = gp.KU;
+    p.strips = gp.strips;
+    for (int m0 = r0; m0 < r1; m0 += 16 * TM) {
+        if (m0 != r0) __syncthreads();             // the previous chunk's reads of red are done
+        p.X = gp.X + (size_t)m0 * gp.K;
+        p.Y = gp.Y + (size_t)m0 * gp.N;
+        p.M = min(16 * TM, r1 - m0);
+        skinny_body<TM, NTW, GPU, D>(p, blockIdx.x, red, s_last);
+    }
+}
+
 // D128 / DSMALL: register stages per wave for group 128 and for the smaller groups (which carry more scale/zero
 // words per unit and would spill with the deeper ring).
 template <int TM, int NTW, int D128, int DSMALL, int MAXW>
@@ -281,7 +332,36 @@ hipError_t launch_cfg(const GemmParams& p, const Plan& plan, int group, hipStrea
     return hipGetLastError();
 }
 
+template <int TM, int NTW, int D128, int DSMALL>
+hipError_t launch_grouped_cfg(const GroupedParams& gp, int experts, int group, hipStream_t stream)
+{
+    dim3 grid(gp.strips, experts), block(512);
+    size_t lds = (size_t)8 * NTW * 4 * 64 * sizeof(float);
+    switch (group) {
+        case 128: hipLaunchKernelGGL((skinny_grouped_kernel<TM, NTW, 1, D128, 8>), grid, block, lds, stream, gp); break;
+        case 64: hipLaunchKernelGGL((skinny_grouped_kernel<TM, NTW, 2, DSMALL, 8>), grid, block, lds, stream, gp); break;
+        case 32: hipLaunchKernelGGL((skinny_grouped_kernel<TM, NTW, 4, DSMALL, 8>), grid, block, lds, stream, gp); break;
+        default: return hipErrorInvalidValue;
+    }
+    return hipGetLastError();
+}
+
 }  // namespace
+
+// Eight-wave CTAs only: with one grid row per expert there are several CTAs per CU to overlap.
+hipError_t launch_skinny_grouped(const GroupedParams& gp, int variant, int experts, int group, hipStream_t stream)
+{
+    if (experts <= 0 || experts > 65535 || gp.strips <= 0) return hipErrorInvalidValue;
+    switch (variant) {
+        case kSkinny16x16: return launch_grouped_cfg<1, 1, 4, 4>(gp, experts, group, stream);
+        case kSkinny16x32: return launch_grouped_cfg<1, 2, 4, 4>(gp, experts, group, stream);
+        case kSkinny16x64: return launch_grouped_cfg<1, 4, 2, 2>(gp, experts, group, stream);
+        case kSkinny16x128: return launch_grouped_cfg<1, 8, 2, 1>(gp, experts, group, stream);
+        case kSkinny32x64: return launch_grouped_cfg<2, 4, 2, 2>(gp, experts, group, stream);
+        case kSkinny64x64: return launch_grouped_cfg<4, 4, 1, 1>(gp, experts, group, stream);
+        default: return hipErrorInvalidValue;
+    }
+}
 
 hipError_t launch_skinny(const GemmParams& p, const Plan& plan, int group, hipStream_t stream)
 {

@@ -425,3 +425,88 @@ def test_hip_graph_replay_matches_eager(tm, oracle):
         torch.cuda.synchronize()
         assert torch.equal(Y2.view(torch.int16), Y_eager.view(torch.int16))
     tm.tm_set_variant(-1, 0)
+
+
+# ------------------------------------------------------------------ grouped (mixture-of-experts) GEMM
+
+def _make_experts(tm, rng, E, K, N, g):
+    host, dev = [], []
+    for e in range(E):
+        q = rng.integers(0, 16, (K, N), dtype=np.uint8)
+        s = rng.uniform(0.001, 0.02, (K // g, N)).astype(np.float16)
+        z = rng.integers(0, 16, (K // g, N)).astype(np.float16)
+        host.append((q, s, z))
+        dev.append(gu.pack({"q": q, "qweight": wl.pack_interchange(q), "s": s, "z": z}, g))
+    return host, dev
+
+
+GROUPED_CASES = [
+    # E, K, N, g, rows per expert, rows before the first / after the last expert, forced variant (-1: library's choice)
+    (4, 512, 272, 128, [0, 1, 17, 5], 0, 0, -1),
+    (8, 1024, 2064, 64, [3, 0, 16, 2, 0, 0, 9, 1], 2, 3, -1),
+    (3, 256, 48, 32, [40, 0, 70], 0, 1, -1),            # average load picks the 64-row kernels; 70 rows = two passes
+    (3, 256, 48, 32, [40, 0, 70], 1, 0, 0),             # 16-row kernel: five passes for the last expert
+    (3, 384, 336, 128, [33, 2, 18], 0, 0, 1),
+    (2, 512, 1040, 64, [16, 15], 0, 0, 2),
+    (2, 512, 1040, 128, [7, 31], 0, 0, 16),
+    (5, 256, 528, 128, [20, 0, 0, 45, 1], 0, 0, 4),
+    (64, 256, 96, 128, [0] * 20 + [2] + [0] * 30 + [1, 5] + [0] * 11, 0, 0, -1),
+    (6, 2048, 512, 128, [1, 1, 1, 1, 1, 1], 0, 0, -1),
+]
+
+
+@pytest.mark.parametrize("E,K,N,g,counts,lead,trail,variant", GROUPED_CASES)
+def test_grouped_gemm_against_oracle(tm, oracle, E, K, N, g, counts, lead, trail, variant):
+    import torch
+    _say(f"grouped E={E} K={K} N={N} g={g} counts={counts} lead={lead} trail={trail} variant={variant}")
+    assert len(counts) == E
+    rng = np.random.default_rng(E * 1000 + K + N)
+    host, dev = _make_experts(tm, rng, E, K, N, g)
+    offsets = (lead + np.concatenate([[0], np.cumsum(counts)])).astype(np.int32)
+    R = int(offsets[-1]) + trail
+    X = rng.standard_normal((R, K)).astype(np.float16)
+    group = tm.tm_group_experts(dev)
+    Xd, od = gu.to_dev(X), torch.from_numpy(offsets).cuda()
+    tm.tm_set_variant(variant, 0)
+    try:
+        outs = []
+        for _ in range(2):
+            Y = torch.full((R, N), float("nan"), dtype=torch.float16, device="cuda")
+            tm.tm_gemm_w4a16_grouped(Xd, group, od, Y)
+            torch.cuda.synchronize()
+            outs.append(Y.cpu().numpy())
+    finally:
+        tm.tm_set_variant(-1, 0)
+    assert np.array_equal(outs[0].view(np.uint16), outs[1].view(np.uint16))        # run-to-run identical
+    Yref = oracle.gemm_grouped(X, host, offsets, g)
+    owned = ~np.isnan(Yref[:, 0])
+    assert owned.sum() == sum(counts)
+    assert np.isnan(outs[0][~owned]).all()                                          # unowned rows untouched
+    ok, worst, fro = acceptance(outs[0][owned], Yref[owned])
+    assert ok, (worst, fro)
+    group.close()
+    for p in dev:
+        p.close()
+
+
+def test_grouped_gemm_clamps_offsets_and_rejects_mismatched_experts(tm, oracle):
+    import torch
+    _say("grouped: offsets beyond the buffers, mismatched experts")
+    rng = np.random.default_rng(3)
+    host, dev = _make_experts(tm, rng, 2, 256, 32, 128)
+    other = _make_experts(tm, rng, 1, 256, 48, 128)[1]
+    with pytest.raises(tm.TmError):
+        tm.tm_group_experts(dev + other)
+    group = tm.tm_group_experts(dev)
+    R = 6
+    X = rng.standard_normal((R, 256)).astype(np.float16)
+    offsets = np.array([-4, 2, 50], np.int32)             # reads as [0, 2, 6]
+    Y = torch.full((R, 32), float("nan"), dtype=torch.float16, device="cuda")
+    tm.tm_gemm_w4a16_grouped(gu.to_dev(X), group, torch.from_numpy(offsets).cuda(), Y)
+    torch.cuda.synchronize()
+    Yref = oracle.gemm_grouped(X, host, np.array([0, 2, 6]), 128)
+    ok, worst, fro = acceptance(Y.cpu().numpy(), Yref)
+    assert ok, (worst, fro)
+    group.close()
+    for p in dev + other:
+        p.close()

@@ -379,3 +379,35 @@ def test_acceptance_rule_itself():
     assert not acceptance(y, r)[0]                 # absolute part: 1e-2
     y = r.copy(); y[0, 1] = np.float16(-2.0 - 0.03)
     assert not acceptance(y, r)[0]                 # 1e-2 + 5e-3*2 = 0.02 < 0.03
+
+
+# ------------------------------------------------------------------ grouped (mixture-of-experts) form
+
+def test_gemm_grouped_equals_masked_sum_of_dense_products(oracle):
+    """Row r of the grouped result is row r of X times the matrix of the one expert that owns r: written here as a
+    sum over experts of (row mask) * (X @ W_e) with numpy, which shares nothing with the slice-and-call loop."""
+    rng = np.random.default_rng(21)
+    K, N, g, E = 64, 16, 32, 4
+    experts, What = [], []
+    for e in range(E):
+        q = rng.integers(0, 16, (K, N), dtype=np.uint8)
+        s = rng.uniform(0.01, 0.05, (K // g, N)).astype(np.float16)
+        z = rng.integers(0, 16, (K // g, N)).astype(np.float16)
+        experts.append((q, s, z))
+        What.append((q.astype(np.float64) - np.repeat(z.astype(np.float64), g, 0)) * np.repeat(s.astype(np.float64), g, 0))
+    offsets = np.array([0, 3, 3, 8, 9], np.int32)           # expert 1 has no rows; row 9 belongs to nobody
+    X = rng.standard_normal((10, K)).astype(np.float16)
+    Y = oracle.gemm_grouped(X, experts, offsets, g)
+    owner = np.full(10, -1)
+    for e in range(E):
+        owner[offsets[e]:offsets[e + 1]] = e
+    want = sum((owner == e)[:, None] * (X.astype(np.float64) @ What[e]) for e in range(E))
+    assert np.isnan(Y[9]).all() and not np.isnan(Y[:9]).any()
+    assert np.allclose(Y[:9].astype(np.float64), want[:9], rtol=2e-3, atol=1e-3)
+    # one-hot rows pick single dequantised weights, which fp16 holds after one rounding
+    X1 = np.zeros((10, K), np.float16)
+    for r in range(10):
+        X1[r, (7 * r) % K] = 1.0
+    Y1 = oracle.gemm_grouped(X1, experts, offsets, g)
+    for r in range(9):
+        assert np.array_equal(Y1[r], What[owner[r]][(7 * r) % K].astype(np.float16))
