@@ -1,7 +1,7 @@
 #!/usr/bin/env python3
 """Benchmark of the W4A16 GEMM hot path on one MI355X.
 
-    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload decode|mlp_decode|prefill|sweep|companion|pack|copy]
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload decode|mlp_decode|prefill|sweep|companion|moe|pack|copy]
                     [--sweep-out FILE] [--no-cpu-baseline] [--no-prefill]
 
 A "step" is one pass of the fused GEMM over every (layer, M) pair of the workload, weights already packed
@@ -175,6 +175,83 @@ def dense_companion(tm, torch, wl, layers, iters=50):
     return rows
 
 
+# Mixture-of-experts decode layers in the shapes of the MoE models the paper evaluates (Sec. 5.1): (experts, experts
+# per token, K, N); gate and up projections fused along N.  Weights are random int4 words (timing does not depend on
+# their values); routing is uniform, seeded, k distinct experts per token, a new draw for every timed step.
+MOE_LAYERS = {
+    "moe8_gate_up": (8, 2, 4096, 28672),
+    "moe8_down": (8, 2, 14336, 4096),
+    "moe128_gate_up": (128, 8, 4096, 3072),
+    "moe128_down": (128, 8, 1536, 4096),
+}
+
+
+def moe_table(tm, torch, names, tokens=(1, 4, 16, 64), iters=40, group=128, only=None, use_graph=True):
+    import numpy as np
+    rows = []
+    for name in names:
+        E, topk, K, N = MOE_LAYERS[name]
+        G = K // group
+        experts = []
+        for e in range(E):
+            qw = torch.randint(-2 ** 31, 2 ** 31 - 1, (K, N // 8), dtype=torch.int32, device="cuda")
+            s = (torch.rand((G, N), device="cuda") * 0.02 + 0.001).to(torch.float16)
+            z = torch.randint(0, 16, (G, N), device="cuda").to(torch.float16)
+            experts.append(tm.tm_pack_w4(qw, s, z, K, N, group))
+        del qw, s, z
+        grp = tm.tm_group_experts(experts)
+        ebytes = K * N // 2 + 4 * G * N
+        rng = np.random.default_rng(E * 7 + K)
+        for T in tokens:
+            if only is not None and (name, T) != only:
+                continue
+            R = T * topk
+            X = (torch.randn((R, K), device="cuda")).to(torch.float16)
+            Y = torch.empty((R, N), dtype=torch.float16, device="cuda")
+            offs, counts_all, active = [], [], 0
+            for _ in range(iters):
+                picks = np.concatenate([rng.choice(E, topk, replace=False) for _ in range(T)])
+                counts = np.bincount(picks, minlength=E)
+                active += int((counts > 0).sum())
+                counts_all.append(counts)
+                offs.append(np.concatenate([[0], np.cumsum(counts)]).astype(np.int32))
+            od = torch.from_numpy(np.stack(offs)).cuda()
+            turn = [0]
+
+            def grouped_step():
+                tm.tm_gemm_w4a16_grouped(X, grp, od[turn[0] % iters], Y)
+                turn[0] += 1
+
+            def looped_step():                          # one ordinary GEMM per expert that has rows (host-side counts)
+                i = turn[0] % iters
+                turn[0] += 1
+                for e in range(E):
+                    r0, r1 = int(offs[i][e]), int(offs[i][e + 1])
+                    if r1 > r0:
+                        tm.tm_gemm_w4a16(X[r0:r1], experts[e], Y[r0:r1])
+
+            turn[0] = 0
+            g_ms, _ = time_steps(torch, grouped_step, iters, 0, graph_steps=iters if use_graph else 0)
+            turn[0] = 0
+            l_ms, _ = time_steps(torch, looped_step, iters, 0, graph_steps=iters) if use_graph else (float("nan"), 0)
+            t = g_ms / iters * 1e-3
+            B = active / iters * ebytes + R * K * 2 + R * N * 2
+            v, st = tm.tm_get_grouped_plan(grp, R)
+            rows.append({"layer": name, "experts": E, "top_k": topk, "K": K, "N": N, "tokens": T, "rows": R,
+                         "active_experts_avg": active / iters, "us": t * 1e6, "GBps": B / t / 1e9,
+                         "hbm_frac": B / t / 1e9 / HBM_PEAK_GBPS, "looped_us": l_ms / iters * 1e3,
+                         "variant": tm.tm_variant_name(v), "strips": st})
+            log(f"{name:15s} E={E:3d} top{topk} tokens={T:3d} rows={R:4d} active={active / iters:6.1f}  grouped {t * 1e6:8.2f} us "
+                f"({B / t / 1e9:6.0f} GB/s, {100 * B / t / 1e9 / HBM_PEAK_GBPS:4.1f} % HBM)   one launch per expert "
+                f"{l_ms / iters * 1e3:8.2f} us   {tm.tm_variant_name(v)} x{st}")
+        grp.close()
+        for p in experts:
+            p.close()
+        del experts
+        torch.cuda.empty_cache()
+    return rows
+
+
 def cpu_baseline(wl, layers, min_s=5.0, budget_s=25.0):
     """The oracle as it stands, timed on this host's cores over the same workload: whole passes over every
     (layer, M) pair are repeated until at least `min_s` seconds have been spent; a single GEMM too large for
@@ -210,7 +287,7 @@ def main():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=200)
     ap.add_argument("--warmup", type=int, default=20)
-    ap.add_argument("--workload", default="decode", choices=sorted(WORKLOADS) + ["sweep", "copy", "companion", "pack"])
+    ap.add_argument("--workload", default="decode", choices=sorted(WORKLOADS) + ["sweep", "copy", "companion", "pack", "moe"])
     ap.add_argument("--sweep-out", default=None, help="with --workload sweep: write the per-shape table here (JSON)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-prefill", action="store_true", help="skip the prefill companion measurement")
@@ -272,6 +349,19 @@ def main():
             rows.append({"layout": layout, "ms_per_pack_call": ms})
             log(f"layout {layout}: {ms:.3f} ms per pack call (allocation + two kernels + free)")
         print(json.dumps({"metric": "offline pack", "K": K, "N": N, "group": g, "steps": args.steps, "rows": rows}))
+        return
+
+    if args.workload == "moe":
+        only = None
+        if args.only:
+            nm, T = args.only.split(":")
+            only = (nm, int(T))
+        names = [n for n in MOE_LAYERS if only is None or n == only[0]]
+        table = moe_table(tm, torch, names, iters=args.steps if args.steps <= 40 else 40, only=only, use_graph=not args.eager)
+        if args.sweep_out:
+            os.makedirs(os.path.dirname(os.path.abspath(args.sweep_out)), exist_ok=True)
+            json.dump(table, open(args.sweep_out, "w"), indent=1)
+        print(json.dumps({"metric": "grouped W4A16 GEMM, MoE decode: effective HBM GB/s", "workload": "moe", "rows": table}))
         return
 
     if args.workload == "companion":

@@ -121,7 +121,11 @@ int ceil_div(int a, int b);
 void grouped_plan(const tm_expert_group* g, int total_rows, int num_cu, int* variant, int* strips)
 {
     const int NT = g->N / kUnitN;
-    const int avg = ceil_div(total_rows, g->experts);
+    // row tiles sized for the busiest expert of a balanced routing: mean load plus three standard deviations
+    const int mean = ceil_div(total_rows, g->experts);
+    int dev3 = 0;
+    while ((dev3 + 1) * (dev3 + 1) <= 9 * mean) ++dev3;
+    const int avg = total_rows < mean + dev3 ? total_rows : mean + dev3;
     const int active = total_rows < g->experts ? total_rows : g->experts;
     const int want = ceil_div(2 * num_cu, active > 0 ? active : 1);         // strips per expert for two CTAs per CU
     int per = NT / (want > NT ? NT : want);                                  // tiles per strip, at least one
@@ -512,6 +516,7 @@ int tm_gemm_w4a16_grouped(const uint16_t* X, const tm_expert_group* group, const
     gp.G = group->K / group->group;
     gp.strips = strips;
     gp.total_rows = total_rows;
+    gp.experts = group->experts;
     hipError_t e = launch_skinny_grouped(gp, variant, group->experts, group->group, (hipStream_t)stream);
     if (e != hipSuccess) return fail_hip(e, "grouped kernel launch");
     return TM_OK;

@@ -275,29 +275,56 @@ __global__ __launch_bounds__(MAXW * 64) void skinny_kernel(GemmParams p)
 
 // Grouped form for mixture-of-experts layers (the paper's evaluation covers MoE models, Sec. 5.1; their expert GEMMs
 // are this same GEMM once per expert): rows [offsets[e], offsets[e+1]) of X and Y belong to expert e, whose packed
-// weights the pointer table names.  blockIdx.y is the expert, blockIdx.x the strip; an expert without rows costs
-// one offsets read.  Experts with more than 16*TM rows are taken 16*TM rows at a time.
-__device__ __forceinline__ uint64_t uniform64(uint64_t v)
-{
-    uint32_t lo = __builtin_amdgcn_readfirstlane((uint32_t)v), hi = __builtin_amdgcn_readfirstlane((uint32_t)(v >> 32));
-    return ((uint64_t)hi << 32) | lo;
-}
-
+// weights the pointer table names.  blockIdx.x is the strip, blockIdx.y selects among the experts that have rows.
+// Experts with more than 16*TM rows are taken 16*TM rows at a time.
 template <int TM, int NTW, int GPU, int D, int MAXW>
 __global__ __launch_bounds__(MAXW * 64) void skinny_grouped_kernel(GroupedParams gp)
 {
     extern __shared__ float red[];
     __shared__ uint32_t s_last;
-    const int e = blockIdx.y;
-    // rows are clamped to the buffers whatever the offsets hold
-    int r0 = __builtin_amdgcn_readfirstlane(gp.offsets[e]);
-    int r1 = __builtin_amdgcn_readfirstlane(gp.offsets[e + 1]);
-    r0 = min(max(r0, 0), gp.total_rows);
-    r1 = min(r1, gp.total_rows);
-    if (r1 <= r0) return;
+    // blockIdx.y counts experts that have rows, not experts: the grid is only as tall as the number of experts that
+    // can be active (min(experts, rows)), and every wave finds "its" expert by scanning the offsets 64 experts at a
+    // time.  Each lane also fetches its candidate's two table entries, so that the scan, the row range and the
+    // buffer addresses cost a single round trip to memory.
+    const int lane = threadIdx.x & 63;
+    int want = blockIdx.y;                          // index among the experts with rows that is still to be skipped
+    int r0 = 0, r1 = 0;
+    uint64_t wptr = 0, szptr = 0;
+    bool found = false;
+    for (int base = 0; base < gp.experts; base += 64) {
+        const int e = base + lane;
+        int a = 0, b = 0;
+        uint64_t tw = 0, ts = 0;
+        if (e < gp.experts) {
+            a = gp.offsets[e];
+            b = gp.offsets[e + 1];
+            tw = gp.table[2 * e];
+            ts = gp.table[2 * e + 1];
+        }
+        a = min(max(a, 0), gp.total_rows);          // rows are clamped to the buffers whatever the offsets hold
+        b = min(b, gp.total_rows);
+        const bool has_rows = b > a;
+        const uint64_t mask = __ballot(has_rows);
+        const int count = __popcll(mask);
+        if (want < count) {
+            const int before = __popcll(mask & ((1ull << lane) - 1ull));
+            const uint64_t hit = __ballot(has_rows && before == want);
+            const int src = __builtin_ctzll(hit);   // exactly one lane
+            r0 = __builtin_amdgcn_readlane(a, src);
+            r1 = __builtin_amdgcn_readlane(b, src);
+            wptr = ((uint64_t)(uint32_t)__builtin_amdgcn_readlane((int)(tw >> 32), src) << 32) |
+                   (uint32_t)__builtin_amdgcn_readlane((int)(uint32_t)tw, src);
+            szptr = ((uint64_t)(uint32_t)__builtin_amdgcn_readlane((int)(ts >> 32), src) << 32) |
+                    (uint32_t)__builtin_amdgcn_readlane((int)(uint32_t)ts, src);
+            found = true;
+            break;
+        }
+        want -= count;
+    }
+    if (!found) return;                             // fewer experts have rows than the grid is tall
     GemmParams p{};
-    p.W = (const u32x4*)uniform64(gp.table[2 * e]);
-    p.SZ = (const uint32_t*)uniform64(gp.table[2 * e + 1]);
+    p.W = (const u32x4*)wptr;
+    p.SZ = (const uint32_t*)szptr;
     p.K = gp.K;
     p.N = gp.N;
     p.KU = gp.KU;
@@ -335,7 +362,7 @@ hipError_t launch_cfg(const GemmParams& p, const Plan& plan, int group, hipStrea
 template <int TM, int NTW, int D128, int DSMALL>
 hipError_t launch_grouped_cfg(const GroupedParams& gp, int experts, int group, hipStream_t stream)
 {
-    dim3 grid(gp.strips, experts), block(512);
+    dim3 grid(gp.strips, gp.total_rows < experts ? gp.total_rows : experts), block(512);
     size_t lds = (size_t)8 * NTW * 4 * 64 * sizeof(float);
     switch (group) {
         case 128: hipLaunchKernelGGL((skinny_grouped_kernel<TM, NTW, 1, D128, 8>), grid, block, lds, stream, gp); break;
