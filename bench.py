@@ -237,12 +237,14 @@ def moe_table(tm, torch, names, tokens=(1, 4, 16, 64), iters=40, group=128, only
             t = g_ms / iters * 1e-3
             B = active / iters * ebytes + R * K * 2 + R * N * 2
             v, st = tm.tm_get_grouped_plan(grp, R)
+            F = 2.0 * R * K * N
             rows.append({"layer": name, "experts": E, "top_k": topk, "K": K, "N": N, "tokens": T, "rows": R,
                          "active_experts_avg": active / iters, "us": t * 1e6, "GBps": B / t / 1e9,
+                         "TFLOPs": F / t / 1e12, "mfma_frac": F / t / 1e12 / MFMA_F16_PEAK_TFLOPS,
                          "hbm_frac": B / t / 1e9 / HBM_PEAK_GBPS, "looped_us": l_ms / iters * 1e3,
                          "variant": tm.tm_variant_name(v), "strips": st})
             log(f"{name:15s} E={E:3d} top{topk} tokens={T:3d} rows={R:4d} active={active / iters:6.1f}  grouped {t * 1e6:8.2f} us "
-                f"({B / t / 1e9:6.0f} GB/s, {100 * B / t / 1e9 / HBM_PEAK_GBPS:4.1f} % HBM)   one launch per expert "
+                f"({B / t / 1e9:6.0f} GB/s, {100 * B / t / 1e9 / HBM_PEAK_GBPS:4.1f} % HBM; {F / t / 1e12:7.1f} TF)   one launch per expert "
                 f"{l_ms / iters * 1e3:8.2f} us   {tm.tm_variant_name(v)} x{st}")
         grp.close()
         for p in experts:
@@ -294,6 +296,7 @@ def main():
     ap.add_argument("--companion-workloads", default="decode,mlp_decode,sweep5,prefill",
                     help="workloads the fp16 x fp16 companion covers (comma-separated; one of them makes a short profiler run)")
     ap.add_argument("--eager", action="store_true", help="launch every kernel from the host instead of replaying HIP graphs")
+    ap.add_argument("--moe-tokens", default="1,4,16,64", help="with --workload moe: tokens per step (comma-separated)")
     ap.add_argument("--only", default=None, help="restrict the workload to one 'layer:M' pair, e.g. cfg3_gate_up:1 (profiling)")
     ap.add_argument("--waves", type=int, default=0)
     ap.add_argument("--stage-steps", type=int, default=0)
@@ -357,7 +360,7 @@ def main():
             nm, T = args.only.split(":")
             only = (nm, int(T))
         names = [n for n in MOE_LAYERS if only is None or n == only[0]]
-        table = moe_table(tm, torch, names, iters=args.steps if args.steps <= 40 else 40, only=only, use_graph=not args.eager)
+        table = moe_table(tm, torch, names, tokens=tuple(int(t) for t in args.moe_tokens.split(",")), iters=args.steps if args.steps <= 40 else 40, only=only, use_graph=not args.eager)
         if args.sweep_out:
             os.makedirs(os.path.dirname(os.path.abspath(args.sweep_out)), exist_ok=True)
             json.dump(table, open(args.sweep_out, "w"), indent=1)

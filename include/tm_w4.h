@@ -135,11 +135,12 @@ TM_API void tm_free_packed(tm_packed_w4* packed);
  *
  * tm_gemm_w4a16_grouped (online): X fp16 [total_rows][K], Y fp16 [total_rows][N], both 16-byte aligned; offsets is a
  * DEVICE array of num_experts + 1 ascending int32 row indices, so routing results never pass through the host.  One
- * launch covers all experts; an expert without rows costs one read of its offsets.  Rows outside
+ * launch covers all experts, and only experts with rows occupy CTAs.  Rows outside
  * [offsets[0], offsets[num_experts]) are left untouched; offsets are clamped to [0, total_rows].  Never allocates,
- * uses no workspace (K is not split across CTAs), results are bit-identical from run to run.  The kernels are the
- * decode (M <= 64 per pass) kernels: an expert with more rows is processed 16-64 rows at a time and re-reads its
- * weights for each pass, which is correct for any load but only efficient for decode-sized batches.
+ * uses no workspace (K is not split across CTAs), results are bit-identical from run to run.  The kernel is chosen
+ * from total_rows / num_experts (the per-expert counts are not known on the host): decode-sized loads run the decode
+ * kernels (an expert with more rows than one pass takes, 16-64, is processed in several passes), prefill-sized
+ * loads (about 64 rows per expert and more) run the CTA-tile kernels, which need total_rows * K < 2^31.
  * total_rows == 0 is a successful no-op; total_rows < 2^24.
  */
 typedef struct tm_expert_group tm_expert_group;

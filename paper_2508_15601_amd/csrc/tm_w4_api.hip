@@ -131,10 +131,12 @@ void grouped_plan(const tm_expert_group* g, int total_rows, int num_cu, int* var
     int per = NT / (want > NT ? NT : want);                                  // tiles per strip, at least one
     int v;
     if (g_force_variant >= 0) v = g_force_variant;
+    else if (avg > 192) v = kTile128x256;            // prefill-sized loads: CTA tiles, weights read once per row tile
+    else if (avg > 64) v = kTile64x128;
     else if (avg > 32) v = kSkinny64x64;
     else if (avg > 16) v = kSkinny32x64;
     else v = per >= 8 ? kSkinny16x128 : per >= 4 ? kSkinny16x64 : per >= 2 ? kSkinny16x32 : kSkinny16x16;
-    const int ntw = skinny_ntw(v);
+    const int ntw = is_skinny(v) ? skinny_ntw(v) : 1;
     if (per > ntw) per = ntw;
     int st = ceil_div(NT, per);
     *variant = v;
@@ -517,7 +519,11 @@ int tm_gemm_w4a16_grouped(const uint16_t* X, const tm_expert_group* group, const
     gp.strips = strips;
     gp.total_rows = total_rows;
     gp.experts = group->experts;
-    hipError_t e = launch_skinny_grouped(gp, variant, group->experts, group->group, (hipStream_t)stream);
+    if (!is_skinny(variant) && (uint64_t)total_rows * (uint64_t)group->K >= (1ull << 31))
+        return fail(TM_EINVAL, "total_rows*K must be below 2^31 for prefill-sized expert loads");
+    hipError_t e = is_skinny(variant)
+                       ? launch_skinny_grouped(gp, variant, group->experts, group->group, (hipStream_t)stream)
+                       : launch_tile_grouped(gp, variant, group->experts, group->group, (hipStream_t)stream);
     if (e != hipSuccess) return fail_hip(e, "grouped kernel launch");
     return TM_OK;
 }

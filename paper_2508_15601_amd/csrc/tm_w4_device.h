@@ -42,6 +42,7 @@ struct GroupedParams {
     const uint64_t* table;      // per expert: address of the packed weights, address of the scale/zero words
     const int32_t* offsets;     // [experts + 1], ascending
     int K, N, KU, NT, G, strips, total_rows, experts;
+    int tiles_n, mtiles;        // tile kernels: column tiles, and the upper bound of row tiles over all experts
 };
 
 __device__ __forceinline__ f16x2 as_f16x2(uint32_t u) { return __builtin_bit_cast(f16x2, u); }

@@ -80,6 +80,7 @@ hipError_t launch_read(const void* src, size_t bytes, void* sink, hipStream_t st
 
 hipError_t launch_skinny(const GemmParams& p, const Plan& plan, int group, hipStream_t stream);
 hipError_t launch_skinny_grouped(const GroupedParams& gp, int variant, int experts, int group, hipStream_t stream);
+hipError_t launch_tile_grouped(const GroupedParams& gp, int variant, int experts, int group, hipStream_t stream);
 hipError_t launch_tile(const GemmParams& p, const Plan& plan, int group, hipStream_t stream);
 hipError_t launch_tile_small(const GemmParams& p, const Plan& plan, int group, hipStream_t stream);
 hipError_t launch_tile_large(const GemmParams& p, const Plan& plan, int group, hipStream_t stream);

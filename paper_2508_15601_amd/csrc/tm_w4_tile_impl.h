@@ -58,8 +58,10 @@ __device__ __forceinline__ void static_for(F&& f)
 // is unrolled PD*(PD+1) times), never by copies, because a copy would wait for the load it renames.  PD = 2 wherever
 // the registers allow (tiles up to 128 rows): one stage of MFMAs is shorter than an HBM round trip.  X runs one
 // stage ahead, through the second LDS buffer.
-template <int TM, int TN, int NW, int GPU, int KW, int PD = (TM <= 8 ? 2 : 1), int KG = 1>
-__global__ __launch_bounds__(NW * KG * 64) void tile_kernel(GemmParams p)
+//
+// tile_body is one CTA's work on output tile (tile_m, tile_n) and K split sk of one GEMM.
+template <int TM, int TN, int NW, int GPU, int KW, int PD, int KG>
+__device__ __forceinline__ void tile_body(const GemmParams& p, const int tile_m, const int tile_n, const int sk)
 {
     constexpr int NT_ = NW * KG * 64;                      // threads per CTA
     constexpr int BM = TM * 16, BN = NW * TN * 16;
@@ -84,20 +86,6 @@ __global__ __launch_bounds__(NW * KG * 64) void tile_kernel(GemmParams p)
     const int wave = wave_id % NW, kg = wave_id / NW;       // column slot and K slice of this wave
     const int c = lane & 15, h = lane >> 4;
     const Magic mg = make_magic();
-
-    // XCD-aware numbering: consecutive block ids go to different XCDs, so the ids congruent mod 8 (one XCD) are
-    // mapped to consecutive logical tiles, and logical tiles walk panels of kPanelN tiles along N.
-    const int tiles = p.tiles_m * p.tiles_n;
-    const int chunk = (tiles + 7) / 8;
-    const int sk = blockIdx.x / (chunk * 8);
-    const int b = blockIdx.x % (chunk * 8);
-    const int logical = (b % 8) * chunk + b / 8;
-    if (logical >= tiles) return;
-    const int panel_tiles = kPanelN * p.tiles_m;
-    const int panel = logical / panel_tiles;
-    const int within = logical % panel_tiles;
-    const int pw = min(kPanelN, p.tiles_n - panel * kPanelN);      // width of this panel
-    const int tile_m = within / pw, tile_n = panel * kPanelN + within % pw;
 
     const int m0 = tile_m * BM;
     const int nt_end = min(p.NT, (tile_n + 1) * (BN / 16));    // 16-column tiles of this CTA end here
@@ -441,6 +429,25 @@ __global__ __launch_bounds__(NW * KG * 64) void tile_kernel(GemmParams p)
         }
     }
     if (tid == 0) __hip_atomic_store(&p.counters[tile], 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+
+template <int TM, int TN, int NW, int GPU, int KW, int PD = (TM <= 8 ? 2 : 1), int KG = 1>
+__global__ __launch_bounds__(NW * KG * 64) void tile_kernel(GemmParams p)
+{
+    // XCD-aware numbering: consecutive block ids go to different XCDs, so the ids congruent mod 8 (one XCD) are
+    // mapped to consecutive logical tiles, and logical tiles walk panels of kPanelN tiles along N.
+    const int tiles = p.tiles_m * p.tiles_n;
+    const int chunk = (tiles + 7) / 8;
+    const int sk = blockIdx.x / (chunk * 8);
+    const int b = blockIdx.x % (chunk * 8);
+    const int logical = (b % 8) * chunk + b / 8;
+    if (logical >= tiles) return;
+    const int panel_tiles = kPanelN * p.tiles_m;
+    const int panel = logical / panel_tiles;
+    const int within = logical % panel_tiles;
+    const int pw = min(kPanelN, p.tiles_n - panel * kPanelN);      // width of this panel
+    const int tile_m = within / pw, tile_n = panel * kPanelN + within % pw;
+    tile_body<TM, TN, NW, GPU, KW, PD, KG>(p, tile_m, tile_n, sk);
 }
 
 // KW8: stages two packed units deep (needs an even number of units per K split, which the host checks);

@@ -452,6 +452,13 @@ GROUPED_CASES = [
     (5, 256, 528, 128, [20, 0, 0, 45, 1], 0, 0, 4),
     (64, 256, 96, 128, [0] * 20 + [2] + [0] * 30 + [1, 5] + [0] * 11, 0, 0, -1),
     (6, 2048, 512, 128, [1, 1, 1, 1, 1, 1], 0, 0, -1),
+    # prefill-sized loads go through the CTA-tile kernels (64x128, 128x256), also forced on small loads
+    (3, 512, 528, 128, [200, 0, 70], 0, 0, -1),
+    (2, 256, 272, 64, [300, 260], 3, 2, -1),
+    (4, 384, 144, 32, [130, 1, 0, 129], 0, 5, 9),
+    (5, 256, 528, 128, [20, 0, 0, 45, 1], 1, 0, 7),
+    (70, 256, 96, 128, [0] * 30 + [65] + [0] * 34 + [3, 0, 64, 0, 130], 0, 0, 9),
+    (3, 1024, 1040, 64, [257, 128, 1], 0, 0, 7),
 ]
 
 
