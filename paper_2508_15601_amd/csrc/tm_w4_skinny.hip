@@ -195,10 +195,12 @@ __device__ __forceinline__ void skinny_body(const GemmParams& p, const int bx, f
         }
     }
 
-    // Reduce the waves' tiles through LDS, one 16-row tile at a time; every (row, two adjacent columns) slot of
-    // the 16 x 16*NTW tile is owned by one thread (threads take several slots when the CTA has fewer than 128*NTW).
-    constexpr int kPairs = 8 * NTW;                // column pairs per row
-    constexpr int kSlots = 16 * kPairs;
+    // Reduce the waves' tiles through LDS, one 16-row tile at a time.  A wave stores its accumulator registers as
+    // they are (register-major, 64 lanes contiguous), and the readers keep that shape: reader thread e owns
+    // accumulator element (register e / 64, lane e % 64), so the 64 lanes of a reading wave fetch 64 consecutive
+    // floats per source wave, free of bank conflicts.  In the accumulator layout lane l holds column l % 16 of rows
+    // 4*(l / 16) + r; even lanes fetch their right-hand neighbour's sum and store two fp16 columns at once.
+    constexpr int kElems = NTW * 4 * 64;
     const int nthreads = blockDim.x;
 #pragma unroll
     for (int mt = 0; mt < TM; ++mt) {
@@ -208,25 +210,22 @@ __device__ __forceinline__ void skinny_body(const GemmParams& p, const int bx, f
 #pragma unroll
             for (int r = 0; r < 4; ++r) red[(wave * NTW * 4 + j * 4 + r) * 64 + lane] = acc[mt][j][r];
         __syncthreads();
-        for (int slot = tid; slot < kSlots; slot += nthreads) {
-            const int row = slot / kPairs;
-            const int col = (slot % kPairs) * 2;
-            const int m = mt * 16 + row;
-            if (m >= p.M || col >= ntw * 16) continue;
-            const int src_reg = (col >> 4) * 4 + (row & 3);
-            const int src_lane = 16 * (row >> 2) + (col & 15);
-            const int n = nt0 * 16 + col;
-            float v0 = 0.f, v1 = 0.f;
-            for (int w = 0; w < waves; ++w) {
-                float2 t = *(const float2*)&red[(w * NTW * 4 + src_reg) * 64 + src_lane];
-                v0 += t.x;
-                v1 += t.y;
-            }
+        for (int e = tid; e < kElems; e += nthreads) {      // whole waves enter or skip an iteration
+            const int reg = e >> 6;
+            const int j = reg >> 2;
+            const int m = mt * 16 + 4 * (lane >> 4) + (reg & 3);
+            const bool mine = m < p.M && j < ntw;
+            float v = 0.f;
+            if (mine)
+                for (int w = 0; w < waves; ++w) v += red[(w * NTW * 4 + reg) * 64 + lane];
+            const float vr = __shfl_xor(v, 1);
+            if (!mine || (lane & 1)) continue;
+            const int n = (nt0 + j) * 16 + (lane & 15);
             if (p.split == 1) {
-                uint32_t o = (uint32_t)f32_to_f16_bits(v0) | ((uint32_t)f32_to_f16_bits(v1) << 16);
+                uint32_t o = (uint32_t)f32_to_f16_bits(v) | ((uint32_t)f32_to_f16_bits(vr) << 16);
                 *(uint32_t*)(p.Y + (size_t)m * p.N + n) = o;
             } else {
-                st_partial2(p.partial + ((size_t)sk * p.M + m) * p.N + n, v0, v1);
+                st_partial2(p.partial + ((size_t)sk * p.M + m) * p.N + n, v, vr);
             }
         }
     }
@@ -241,6 +240,8 @@ __device__ __forceinline__ void skinny_body(const GemmParams& p, const int bx, f
         }
         __syncthreads();
         if (s_last) {
+            constexpr int kPairs = 8 * NTW;        // column pairs per row of the 16 x 16*NTW tile
+            constexpr int kSlots = 16 * kPairs;
 #pragma unroll
             for (int mt = 0; mt < TM; ++mt) {
                 for (int slot = tid; slot < kSlots; slot += nthreads) {

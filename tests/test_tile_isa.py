@@ -19,6 +19,7 @@ CSRC = os.path.join(ROOT, "paper_2508_15601_amd", "csrc")
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 UNITS = {"tm_w4_tile_small": ["-mllvm", "-amdgpu-mfma-vgpr-form=1"],
          "tm_w4_tile_kgroup": ["-mllvm", "-amdgpu-mfma-vgpr-form=1"],
+         "tm_w4_tile_grouped": ["-mllvm", "-amdgpu-mfma-vgpr-form=1"],
          "tm_w4_tile_large": []}
 VMCNT_MAX = 63          # six-bit counter: a wave cannot have more loads outstanding, so a larger bound is no wait at all
 
