@@ -18,20 +18,24 @@ template <int LAYOUT>
 __global__ __launch_bounds__(256) void repack_w4_kernel(const uint32_t* __restrict__ qweight,
                                                         uint32_t* __restrict__ out, int K, int N)
 {
-    constexpr int kRows = LAYOUT == 2 ? 16 : 128, kPitch = LAYOUT == 2 ? 132 : 17;
+    // A CTA covers 128 rows x kTiles 16-column tiles.  The N-major layouts take 16 tiles so that a row segment is
+    // 32 words = 128 contiguous bytes (with 64-byte segments the memory system fetched twice the bytes read).
+    constexpr int kTiles = LAYOUT == 2 ? 8 : 16;
+    constexpr int kRows = LAYOUT == 2 ? 16 : 128, kPitch = LAYOUT == 2 ? 132 : 33;
     __shared__ uint32_t tile[kRows][kPitch];
     const int KU = K / kUnitK, NT = N / kUnitN, NW = N / 8;
     const int ku = blockIdx.y;
-    const int nt0 = blockIdx.x * 8;
+    const int nt0 = blockIdx.x * kTiles;
     const int tid = threadIdx.x;
-    for (int i = 0; i < 8; ++i) {
+    constexpr int kWords = LAYOUT == 2 ? 16 * 128 : 128 * 32;      // staged words per CTA
+    for (int i = 0; i < kWords / 256; ++i) {
         int idx = i * 256 + tid;
         if constexpr (LAYOUT == 2) {
             int row = idx >> 7, col = idx & 127;
             int gc = nt0 * 16 + col;
             tile[row][col] = gc < N ? qweight[(size_t)(ku * 16 + row) * N + gc] : 0u;
         } else {
-            int row = idx >> 4, wc = idx & 15;
+            int row = idx >> 5, wc = idx & 31;
             int gw = nt0 * 2 + wc;
             uint32_t v = gw < NW ? qweight[(size_t)(ku * kUnitK + row) * NW + gw] : 0u;
             if constexpr (LAYOUT == 1) {
@@ -46,7 +50,7 @@ __global__ __launch_bounds__(256) void repack_w4_kernel(const uint32_t* __restri
     __syncthreads();
     const int lane = tid >> 2, t = tid & 3;
     const int c = lane & 15, h = lane >> 4;
-    for (int j = 0; j < 8; ++j) {
+    for (int j = 0; j < kTiles; ++j) {
         int nt = nt0 + j;
         if (nt >= NT) break;
         int col = 16 * j + c;
@@ -156,7 +160,8 @@ hipError_t launch_repack(const uint32_t* qweight, const uint16_t* scales, const 
     // group is what the caller's scales are laid out for; coarser groups than 128 rows are stored as 128
     const int stored = group > 128 ? 128 : group, rep = group / stored;
     const int KU = K / kUnitK, NT = N / kUnitN, G = K / stored;
-    dim3 grid((NT + 7) / 8, KU);
+    const int tiles_per_cta = layout == 2 ? 8 : 16;     // as in repack_w4_kernel
+    dim3 grid((NT + tiles_per_cta - 1) / tiles_per_cta, KU);
     size_t total = (size_t)G * N;
     dim3 szgrid((unsigned)((total + 255) / 256));
     switch (layout) {
