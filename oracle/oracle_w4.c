@@ -17,6 +17,9 @@
  *                     (Sec. 4.1: one pack routine serves several weight formats) keep the same integers:
  *                     N-major words whose nibbles walk the eight columns in the order 0,2,4,6,1,3,5,7, and
  *                     K-major words u32 [K/8][N] holding eight consecutive rows of one column.
+ *   - orc_quantise_bits, orc_pack_canonical8 / orc_unpack_canonical8, orc_unpack_packed8:
+ *                     the same pipeline for 8-bit weights (paper Sec. 4.1/Sec. 3.3 present packing and the fused
+ *                     GEMM as independent of the weight width): codes 0..255, four per 32-bit word.
  *   - orc_unpack_packed:
  *                     inverse index map of the library's MFMA-fragment-ordered buffer (the gfx950 analogue
  *                     of the packed fragment store of paper Sec. 4.1 steps (iii)-(iv)); written from the
@@ -93,9 +96,10 @@ static float clampf(float v, float lo, float hi) { return v < lo ? lo : (v > hi 
  * s is rounded to fp16 first; z and q are computed in fp32 with that rounded s.
  * A group whose fp16 scale would be zero (constant group, or range below fp16 resolution) gets s = 1.
  */
-ORC_API int orc_quantise(const float* W, int K, int N, int g, uint8_t* q, uint16_t* s, uint16_t* z)
+ORC_API int orc_quantise_bits(const float* W, int K, int N, int g, int bits, uint8_t* q, uint16_t* s, uint16_t* z)
 {
-    if (!W || !q || !s || !z || K <= 0 || N <= 0 || g <= 0 || K % g) return -1;
+    if (!W || !q || !s || !z || K <= 0 || N <= 0 || g <= 0 || K % g || (bits != 4 && bits != 8)) return -1;
+    const float qmax = (float)((1 << bits) - 1);           /* 15 or 255 */
     int G = K / g;
     for (int gi = 0; gi < G; ++gi) {
         for (int n = 0; n < N; ++n) {
@@ -105,21 +109,27 @@ ORC_API int orc_quantise(const float* W, int K, int N, int g, uint8_t* q, uint16
                 if (w < mn) mn = w;
                 if (w > mx) mx = w;
             }
-            float s32 = (mx - mn) / 15.0f;
+            float s32 = (mx - mn) / qmax;
             uint16_t sh = orc_double_to_fp16((double)s32);
             float sf = (float)orc_fp16_to_double(sh);
             if (!(sf > 0.0f) || isinf(sf)) { sf = 1.0f; sh = 0x3C00u; }
-            float zf = clampf(rintf(-mn / sf), 0.0f, 15.0f);
+            float zf = clampf(rintf(-mn / sf), 0.0f, qmax);
             s[(size_t)gi * N + n] = sh;
             z[(size_t)gi * N + n] = orc_double_to_fp16((double)zf);
             for (int k = gi * g; k < gi * g + g; ++k) {
                 float w = W[(size_t)k * N + n];
-                float qf = clampf(rintf(w / sf) + zf, 0.0f, 15.0f);
+                float qf = clampf(rintf(w / sf) + zf, 0.0f, qmax);
                 q[(size_t)k * N + n] = (uint8_t)qf;
             }
         }
     }
     return 0;
+}
+
+/* the 4-bit recipe of the benchmark configurations */
+ORC_API int orc_quantise(const float* W, int K, int N, int g, uint8_t* q, uint16_t* s, uint16_t* z)
+{
+    return orc_quantise_bits(W, K, N, g, 4, q, s, z);
 }
 
 /* ---------------------------------------------------------------- canonical interchange layout */
@@ -143,6 +153,28 @@ ORC_API int orc_unpack_canonical(const uint32_t* in, int K, int N, uint8_t* q)
     for (int k = 0; k < K; ++k)
         for (int n = 0; n < N; ++n)
             q[(size_t)k * N + n] = (uint8_t)((in[(size_t)k * (N / 8) + n / 8] >> (4 * (n % 8))) & 0xF);
+    return 0;
+}
+
+/* 8-bit codes: q u8 [K][N] -> u32 [K][N/4]; byte t (bits 8t..8t+7) of word (k,j) is q[k][4j+t] */
+ORC_API int orc_pack_canonical8(const uint8_t* q, int K, int N, uint32_t* out)
+{
+    if (!q || !out || K <= 0 || N <= 0 || N % 4) return -1;
+    for (int k = 0; k < K; ++k)
+        for (int j = 0; j < N / 4; ++j) {
+            uint32_t w = 0;
+            for (int t = 0; t < 4; ++t) w |= (uint32_t)q[(size_t)k * N + 4 * j + t] << (8 * t);
+            out[(size_t)k * (N / 4) + j] = w;
+        }
+    return 0;
+}
+
+ORC_API int orc_unpack_canonical8(const uint32_t* in, int K, int N, uint8_t* q)
+{
+    if (!q || !in || K <= 0 || N <= 0 || N % 4) return -1;
+    for (int k = 0; k < K; ++k)
+        for (int n = 0; n < N; ++n)
+            q[(size_t)k * N + n] = (uint8_t)((in[(size_t)k * (N / 4) + n / 4] >> (8 * (n % 4))) & 0xFF);
     return 0;
 }
 
@@ -234,9 +266,41 @@ ORC_API int orc_unpack_packed(const uint32_t* wbuf, const uint32_t* szbuf, int K
     return 0;
 }
 
+/*
+ * 8-bit weights.  Units of 16 columns x 64 rows (again 256 words = 1 KiB); unit (nt, ks) covers columns
+ * 16*nt .. 16*nt+15 and rows 64*ks .. 64*ks+63 and starts at word ((nt * (K/64)) + ks) * 256.  Word index =
+ * 4*lane + 2*tt + hf with lane = 16*h + c (c = 0..15, h = 0..3), tt = 0..1, hf = 0..1; it holds, for column
+ * 16*nt + c, rows 64*ks + 32*tt + 8*h + 4*hf + b (b = 0..3), code b in byte b (bits [8b, 8b+7]).
+ * The scale/zero buffer is that of the 4-bit layout.
+ */
+ORC_API int orc_unpack_packed8(const uint32_t* wbuf, const uint32_t* szbuf, int K, int N, int g,
+                               uint8_t* q, uint16_t* s, uint16_t* z)
+{
+    if (!wbuf || !szbuf || !q || !s || !z) return -1;
+    if (K <= 0 || N <= 0 || g <= 0 || K % 128 || N % 16 || K % g) return -1;
+    int KS = K / 64, G = K / g;
+    for (int k = 0; k < K; ++k) {
+        for (int n = 0; n < N; ++n) {
+            int nt = n / 16, c = n % 16;
+            int ks = k / 64, kk = k % 64;
+            int tt = kk / 32, h = (kk % 32) / 8, hf = (kk % 8) / 4, b = kk % 4;
+            int lane = 16 * h + c;
+            uint32_t w = wbuf[((size_t)nt * KS + ks) * 256 + 4 * lane + 2 * tt + hf];
+            q[(size_t)k * N + n] = (uint8_t)((w >> (8 * b)) & 0xFF);
+        }
+    }
+    for (int gi = 0; gi < G; ++gi)
+        for (int n = 0; n < N; ++n) {
+            uint32_t w = szbuf[((size_t)(n / 16) * G + gi) * 16 + (n % 16)];
+            s[(size_t)gi * N + n] = (uint16_t)(w & 0xFFFFu);
+            z[(size_t)gi * N + n] = (uint16_t)(w >> 16);
+        }
+    return 0;
+}
+
 /* ---------------------------------------------------------------- dequantise and multiply */
 
-/* What[k][n] = (q - z) * s in fp64 (exact: a 5-bit integer times an 11-bit significand) */
+/* What[k][n] = (q - z) * s in fp64 (exact: an integer of at most 9 bits times an 11-bit significand) */
 ORC_API int orc_dequant(const uint8_t* q, const uint16_t* s, const uint16_t* z, int K, int N, int g, double* What)
 {
     if (!q || !s || !z || !What || K <= 0 || N <= 0 || g <= 0 || K % g) return -1;

@@ -45,6 +45,10 @@ def _load():
         lib.orc_unpack_canonical.argtypes = [vp, c.c_int, c.c_int, vp]
         for f in (lib.orc_pack_n8i, lib.orc_unpack_n8i, lib.orc_pack_k8, lib.orc_unpack_k8):
             f.argtypes = [vp, c.c_int, c.c_int, vp]
+        lib.orc_quantise_bits.argtypes = [vp, c.c_int, c.c_int, c.c_int, c.c_int, vp, vp, vp]
+        lib.orc_pack_canonical8.argtypes = [vp, c.c_int, c.c_int, vp]
+        lib.orc_unpack_canonical8.argtypes = [vp, c.c_int, c.c_int, vp]
+        lib.orc_unpack_packed8.argtypes = [vp, vp, c.c_int, c.c_int, c.c_int, vp, vp, vp]
         lib.orc_unpack_packed.argtypes = [vp, vp, c.c_int, c.c_int, c.c_int, vp, vp, vp]
         lib.orc_dequant.argtypes = [vp, vp, vp, c.c_int, c.c_int, c.c_int, vp]
         lib.orc_gemm.argtypes = [vp, c.c_int, vp, vp, vp, c.c_int, c.c_int, c.c_int, vp, vp]
@@ -85,15 +89,32 @@ def double_to_fp16(x: float) -> int:
     return int(_load().orc_double_to_fp16(float(x)))
 
 
-def quantise(W: np.ndarray, group: int):
-    """W fp32 [K,N] -> (q uint8 [K,N], s float16 [K/g,N], z float16 [K/g,N])."""
+def quantise(W: np.ndarray, group: int, bits: int = 4):
+    """W fp32 [K,N] -> (q uint8 [K,N] codes 0..2^bits-1, s float16 [K/g,N], z float16 [K/g,N])."""
     W = _as(W, np.float32)
     K, N = W.shape
     q = np.empty((K, N), np.uint8)
     s = np.empty((K // group, N), np.uint16)
     z = np.empty((K // group, N), np.uint16)
-    _check(_load().orc_quantise(_ptr(W), K, N, group, _ptr(q), _ptr(s), _ptr(z)), "quantise")
+    _check(_load().orc_quantise_bits(_ptr(W), K, N, group, bits, _ptr(q), _ptr(s), _ptr(z)), "quantise")
     return q, s.view(np.float16), z.view(np.float16)
+
+
+def pack_canonical8(q: np.ndarray) -> np.ndarray:
+    """8-bit codes q u8 [K,N] -> u32 [K,N/4], byte t of word (k,j) = q[k][4j+t]."""
+    q = _as(q, np.uint8)
+    K, N = q.shape
+    out = np.empty((K, N // 4), np.uint32)
+    _check(_load().orc_pack_canonical8(_ptr(q), K, N, _ptr(out)), "pack_canonical8")
+    return out
+
+
+def unpack_canonical8(words: np.ndarray, N: int) -> np.ndarray:
+    words = _as(words, np.uint32)
+    K = words.shape[0]
+    q = np.empty((K, N), np.uint8)
+    _check(_load().orc_unpack_canonical8(_ptr(words), K, N, _ptr(q)), "unpack_canonical8")
+    return q
 
 
 def pack_canonical(q: np.ndarray) -> np.ndarray:
@@ -146,17 +167,19 @@ def unpack_k8(words: np.ndarray, K: int) -> np.ndarray:
     return q
 
 
-def unpack_packed(wbuf: np.ndarray, szbuf: np.ndarray, K: int, N: int, group: int):
+def unpack_packed(wbuf: np.ndarray, szbuf: np.ndarray, K: int, N: int, group: int, bits: int = 4):
     """Invert the library's fragment-ordered buffers -> (q, s, z) in the plain [K,N] / [K/g,N] layouts."""
     wbuf = _as(wbuf, np.uint32).reshape(-1)
     szbuf = _as(szbuf, np.uint32).reshape(-1)
-    if wbuf.size != K * N // 8 or szbuf.size != (K // group) * N:
-        raise ValueError("packed buffer sizes do not match K, N, group")
+    if bits not in (4, 8):
+        raise ValueError("bits must be 4 or 8")
+    if wbuf.size != K * N * bits // 32 or szbuf.size != (K // group) * N:
+        raise ValueError("packed buffer sizes do not match K, N, group, bits")
     q = np.empty((K, N), np.uint8)
     s = np.empty((K // group, N), np.uint16)
     z = np.empty((K // group, N), np.uint16)
-    _check(_load().orc_unpack_packed(_ptr(wbuf), _ptr(szbuf), K, N, group, _ptr(q), _ptr(s), _ptr(z)),
-           "unpack_packed")
+    fn = _load().orc_unpack_packed if bits == 4 else _load().orc_unpack_packed8
+    _check(fn(_ptr(wbuf), _ptr(szbuf), K, N, group, _ptr(q), _ptr(s), _ptr(z)), "unpack_packed")
     return q, s.view(np.float16), z.view(np.float16)
 
 

@@ -80,6 +80,23 @@ def test_quantise_hand_worked_group(oracle):
     assert deq[:, 0].tolist() == [r[2] for r in rows]
 
 
+def test_quantise_8bit_hand_worked_group(oracle):
+    rows = _read_quant_fixture("quant_group_8bit.txt")
+    W = np.array([[r[0]] for r in rows], np.float32)
+    q, s, z = oracle.quantise(W, len(rows), bits=8)
+    assert float(s[0, 0]) == 0.015625 and float(z[0, 0]) == 64.0
+    assert q[:, 0].tolist() == [r[1] for r in rows]
+    assert oracle.dequant(q, s, z, len(rows))[:, 0].tolist() == [r[2] for r in rows]
+    # and the independent vectorised recipe agrees bit for bit on random data
+    rng = np.random.default_rng(8)
+    Wr = (0.02 * rng.standard_normal((256, 24))).astype(np.float32)
+    for g in (32, 128):
+        q1, s1, z1 = oracle.quantise(Wr, g, bits=8)
+        q2, s2, z2 = wl.quantise_recipe(Wr, g, bits=8)
+        assert np.array_equal(q1, q2) and np.array_equal(s1.view(np.uint16), s2.view(np.uint16))
+        assert np.array_equal(z1.view(np.uint16), z2.view(np.uint16)) and q1.max() > 200
+
+
 def test_quantise_zero_point_tie_fixture(oracle):
     rows = _read_quant_fixture("quant_group_ztie.txt")
     W = np.array([[r[0]] for r in rows], np.float32)
@@ -152,6 +169,8 @@ def test_alternative_layout_word_fixture(oracle):
         vals, want = np.array([int(v) for v in line[1:9]], np.uint8), int(line[9], 16)
         if line[0] == "n8i":
             got = oracle.pack_n8i(vals.reshape(1, 8))
+        elif line[0] == "q8":
+            got = oracle.pack_canonical8(vals[:4].reshape(1, 4))
         else:
             got = oracle.pack_k8(vals.reshape(8, 1))
         assert got.shape == (1, 1) and int(got[0, 0]) == want, line
@@ -244,6 +263,54 @@ def test_unpack_packed_position_codes(oracle):
     idx = ((nn // 16) * G + gi) * 16 + nn % 16
     assert np.array_equal(s.view(np.uint16), (idx * 3 + 1).astype(np.uint16))
     assert np.array_equal(z.view(np.uint16), (idx * 5 + 2).astype(np.uint16))
+
+
+def test_8bit_canonical_and_packed_layout(oracle):
+    """8-bit words: round trip and generator agreement for the interchange layout; the fragment-ordered layout
+    against hand-worked words, position codes and an independent forward statement written with reshapes."""
+    rng = np.random.default_rng(9)
+    for K, N in [(1, 4), (5, 12), (128, 32)]:
+        q = rng.integers(0, 256, (K, N), dtype=np.uint8)
+        w = oracle.pack_canonical8(q)
+        assert np.array_equal(oracle.unpack_canonical8(w, N), q) and np.array_equal(w, wl.pack_interchange8(q))
+    # hand-worked fragment words: every lane's word pair (2*tt, 2*tt+1) set to the fixture's pair
+    K, N, g = 128, 16, 128
+    sz = np.zeros(N, np.uint32)
+    for line in open(os.path.join(GOLD, "fragment_word_orders_8bit.txt")):
+        line = line.split("#")[0].split()
+        if not line:
+            continue
+        es, w0, w1 = [int(e) for e in line[:8]], int(line[8], 16), int(line[9], 16)
+        wbuf = np.tile(np.array([w0, w1], np.uint32), K * N // 8)
+        q, _, _ = oracle.unpack_packed(wbuf, sz, K, N, g, bits=8)
+        assert np.array_equal(q, np.repeat(np.tile(np.array(es, np.uint8), K // 8)[:, None], N, axis=1))
+    # position codes: a buffer filled with one layout coordinate unpacks to that coordinate's closed form
+    K, N, g = 256, 32, 64
+    KS, NT = K // 64, N // 16
+    nt, ks, h, c, tt, hf = np.meshgrid(np.arange(NT), np.arange(KS), np.arange(4), np.arange(16), np.arange(2),
+                                       np.arange(2), indexing="ij")        # buffer order [nt, ks, lane=16h+c, 2tt+hf]
+    k = np.arange(K)[:, None] * np.ones((1, N), int)
+    n = np.ones((K, 1), int) * np.arange(N)[None, :]
+    sz = np.zeros((K // g) * N, np.uint32)
+    for code, want in [(h, (k % 32) // 8), (tt, (k % 64) // 32), (hf, (k % 8) // 4), (c, n % 16),
+                       (nt * KS + ks, (n // 16) * KS + k // 64)]:
+        wbuf = (code.astype(np.uint32) * np.uint32(0x01010101)).reshape(-1)
+        q, _, _ = oracle.unpack_packed(wbuf, sz, K, N, g, bits=8)
+        assert np.array_equal(q, want.astype(np.uint8))
+    wbuf = np.tile(np.array([0x03020100], np.uint32), K * N // 4)           # byte index b = k % 4
+    q, _, _ = oracle.unpack_packed(wbuf, sz, K, N, g, bits=8)
+    assert np.array_equal(q, (k % 4).astype(np.uint8))
+    # forward statement with reshapes: [ks, tt, h, hf, b, nt, c] -> [nt, ks, h, c, tt, hf] words of bytes b
+    q = rng.integers(0, 256, (K, N), dtype=np.uint8)
+    s = rng.uniform(0.001, 0.02, (K // g, N)).astype(np.float16)
+    z = rng.integers(0, 256, (K // g, N)).astype(np.float16)
+    a = q.reshape(KS, 2, 4, 2, 4, NT, 16).transpose(5, 0, 2, 6, 1, 3, 4).astype(np.uint32)
+    words = np.bitwise_or.reduce(a << (8 * np.arange(4, dtype=np.uint32)), axis=-1).reshape(-1)
+    szw = (s.view(np.uint16).astype(np.uint32) | (z.view(np.uint16).astype(np.uint32) << 16))
+    szw = np.ascontiguousarray(szw.reshape(K // g, NT, 16).transpose(1, 0, 2)).reshape(-1)
+    q2, s2, z2 = oracle.unpack_packed(words, szw, K, N, g, bits=8)
+    assert np.array_equal(q2, q) and np.array_equal(s2.view(np.uint16), s.view(np.uint16))
+    assert np.array_equal(z2.view(np.uint16), z.view(np.uint16))
 
 
 @pytest.mark.parametrize("K,N,g", [(128, 16, 128), (384, 80, 64), (256, 48, 32)])

@@ -35,21 +35,23 @@ class Case:
     seed: int = 0
 
 
-def quantise_recipe(W: np.ndarray, group: int):
-    """Vectorised statement of the quantiser recipe: W fp32 [K,N] -> q uint8 [K,N], s,z float16 [K/g,N]."""
+def quantise_recipe(W: np.ndarray, group: int, bits: int = 4):
+    """Vectorised statement of the quantiser recipe: W fp32 [K,N] -> q uint8 [K,N], s,z float16 [K/g,N].
+    bits = 8 is the same recipe with 255 levels (codes 0..255) for the 8-bit weight format."""
+    qmax = np.float32((1 << bits) - 1)
     W = np.ascontiguousarray(W, dtype=np.float32)
     K, N = W.shape
     Wg = W.reshape(K // group, group, N)
     mn = Wg.min(axis=1)
     mx = Wg.max(axis=1)
-    s32 = (mx - mn) / np.float32(15.0)
+    s32 = (mx - mn) / qmax
     s16 = s32.astype(np.float16)
     sf = s16.astype(np.float32)
     bad = ~(sf > 0) | np.isinf(sf)
     sf = np.where(bad, np.float32(1.0), sf).astype(np.float32)
     s16 = np.where(bad, np.float16(1.0), s16).astype(np.float16)
-    z = np.clip(np.rint(-mn / sf), 0, 15).astype(np.float32)
-    q = np.clip(np.rint(Wg / sf[:, None, :]) + z[:, None, :], 0, 15)
+    z = np.clip(np.rint(-mn / sf), 0, qmax).astype(np.float32)
+    q = np.clip(np.rint(Wg / sf[:, None, :]) + z[:, None, :], 0, qmax)
     return q.reshape(K, N).astype(np.uint8), s16, z.astype(np.float16)
 
 
@@ -89,6 +91,14 @@ def encode_layout(q: np.ndarray, z: np.ndarray, layout: int):
         qw = np.bitwise_or.reduce(a << shifts[None, :, None], axis=1).astype(np.uint32)
         return qw, pack_interchange(zi)
     raise ValueError(f"unknown layout {layout}")
+
+
+def pack_interchange8(q: np.ndarray) -> np.ndarray:
+    """8-bit codes q uint8 [K,N] -> uint32 [K,N/4], byte t of word (k,j) = q[k][4j+t] (the layout tm_pack_w8 accepts)."""
+    K, N = q.shape
+    q32 = q.astype(np.uint32).reshape(K, N // 4, 4)
+    shifts = (8 * np.arange(4, dtype=np.uint32))[None, None, :]
+    return np.bitwise_or.reduce(q32 << shifts, axis=2).astype(np.uint32)
 
 
 def draw_weights(case: Case, rng: np.random.Generator) -> np.ndarray:
