@@ -97,6 +97,24 @@ TM_API tm_packed_w4* tm_pack_w4_layout(const void* qweight, const uint16_t* scal
                                        int group, int layout, tm_stream stream);
 
 /*
+ * 8-bit weight codes (W8A16) through the same two stages; the paper presents packing and the fused GEMM as independent
+ * of the weight width (Sec. 3.3, Sec. 4.1).  qweight is u32 [K][N/4], byte t (bits 8t..8t+7) of word (k, j) =
+ * q[k][4j + t], codes 0..255; scales fp16 [K/group][N]; zeros fp16 [K/group][N], integer-valued in [0, 255], or NULL for
+ * the symmetric zero-point 128.  Shapes, groups, alignment, ownership and errors as for tm_pack_w4_on.  The handle works
+ * with tm_gemm_w4a16 / tm_gemm_w4a16_ws, tm_packed_info, tm_packed_raw, tm_get_plan and tm_free_packed; tm_unpack_w4 and
+ * tm_group_experts take 4-bit handles only (TM_EUNSUPPORTED).  Only the decode kernels exist for this format: a GEMM with
+ * M > 64 is run 64 rows at a time and re-reads the weights for each slice.
+ *
+ * Packed layout: units of 16 columns x 64 rows (1 KiB); unit (nt, ks) is the 256 words from ((nt*(K/64))+ks)*256;
+ * word 4*lane + 2*tt + hf (lane = 16*h + c, tt, hf in 0..1) holds column 16*nt + c, rows 64*ks + 32*tt + 8*h + 4*hf + b
+ * in byte b.  Scale/zero words as for 4-bit weights.
+ */
+TM_API tm_packed_w4* tm_pack_w8(const uint32_t* qweight, const uint16_t* scales, const uint16_t* zeros, int K, int N,
+                                int group, tm_stream stream);
+/* Width of the handle's weight codes: 4 or 8 (negative status on error). */
+TM_API int tm_packed_bits(const tm_packed_w4* packed);
+
+/*
  * Online mixed-precision GEMM (paper Sec. 3.1 steps (i)-(iv) and Sec. 4.3): Y = X * dequant(packed).
  *
  *   X  fp16 [M][K] row-major, 16-byte aligned        Y  fp16 [M][N] row-major, 16-byte aligned;  M*K < 2^31

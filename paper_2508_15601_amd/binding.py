@@ -42,6 +42,10 @@ def load_library():
     lib.tm_pack_w4.argtypes = [vp, vp, vp, i, i, i]
     lib.tm_pack_w4_on.restype = vp
     lib.tm_pack_w4_on.argtypes = [vp, vp, vp, i, i, i, vp]
+    lib.tm_pack_w8.restype = vp
+    lib.tm_pack_w8.argtypes = [vp, vp, vp, i, i, i, vp]
+    lib.tm_packed_bits.restype = i
+    lib.tm_packed_bits.argtypes = [vp]
     lib.tm_group_experts.restype = vp
     lib.tm_group_experts.argtypes = [vp, i]
     lib.tm_free_expert_group.restype = None
@@ -123,6 +127,7 @@ class PackedW4:
     def __init__(self, handle: int, K: int, N: int, group: int):
         self._h = handle
         self.K, self.N, self.group = K, N, group
+        self.bits = 4
 
     @property
     def handle(self):
@@ -148,6 +153,24 @@ def tm_pack_w4(qweight, scales, zeros, K: int, N: int, group: int, stream=None) 
     """qweight int32 [K, N/8] (interchange nibble order), scales/zeros float16 [K/group, N] -> PackedW4.
     zeros=None packs symmetric weights (zero-point 8); group may be 32, 64 or a multiple of 128 dividing K."""
     return tm_pack_w4_layout(qweight, scales, zeros, K, N, group, TM_LAYOUT_N8, stream)
+
+
+def tm_pack_w8(qweight, scales, zeros, K: int, N: int, group: int, stream=None) -> PackedW4:
+    """8-bit codes: qweight int32 [K, N/4] (byte t = column 4j+t), scales float16 [K/group, N], zeros float16 of the
+    same shape or None (symmetric, zero-point 128) -> PackedW4 usable with tm_gemm_w4a16."""
+    import torch
+    lib = load_library()
+    if tuple(qweight.shape) != (K, N // 4) or tuple(scales.shape) != (K // group, N) or \
+            (zeros is not None and tuple(zeros.shape) != (K // group, N)):
+        raise ValueError("tensor shapes do not match K, N, group")
+    zptr = None if zeros is None else _dev_ptr(zeros, torch.float16, "zeros")
+    h = lib.tm_pack_w8(_dev_ptr(qweight, torch.int32, "qweight"), _dev_ptr(scales, torch.float16, "scales"), zptr,
+                       K, N, group, _stream_ptr(stream))
+    if not h:
+        raise TmError(-1, tm_last_error())
+    p = PackedW4(h, K, N, min(group, 128))
+    p.bits = 8
+    return p
 
 
 TM_LAYOUT_N8, TM_LAYOUT_N8_INTERLEAVED, TM_LAYOUT_K8 = 0, 1, 2

@@ -94,6 +94,7 @@ int ensure_workspace(int dev)
 struct tm_packed_w4 {
     uint32_t magic;
     int K, N, group, device;
+    int bits;          // width of the weight codes: 4, or 8 (tm_pack_w8)
     uint32_t* w;       // K*N/8 words
     uint32_t* sz;      // (K/group)*N words
     size_t w_bytes, sz_bytes;
@@ -153,10 +154,19 @@ int ceil_div(int a, int b) { return (a + b - 1) / b; }
 // Split factors are bounded so that every wave keeps at least one unit and the partial sums fit the workspace.
 Plan make_plan(const tm_packed_w4* h, int M, int num_cu)
 {
-    const int KU = h->K / kUnitK, NT = h->N / kUnitN;
+    // packed units along K: 128 rows of 4-bit codes or 64 rows of 8-bit codes (1 KiB per 16 columns either way)
+    const int KU = h->bits == 8 ? h->K / 64 : h->K / kUnitK, NT = h->N / kUnitN;
     Plan pl{};
     int variant = g_force_variant;
-    if (variant < 0) {
+    // 8-bit codes run the decode kernels only (run_gemm hands them at most 64 rows at a time)
+    const bool w8 = h->bits == 8;
+    if (w8 && variant >= 0 && !(variant == kSkinny16x16 || variant == kSkinny16x32 || variant == kSkinny16x48 ||
+                                variant == kSkinny16x64 || variant == kSkinny16x96 || variant == kSkinny16x128 ||
+                                variant == kSkinny32x64 || variant == kSkinny64x64))
+        variant = -1;
+    if (variant < 0 && w8 && M > 16) {
+        variant = M <= 32 ? kSkinny32x64 : kSkinny64x64;
+    } else if (variant < 0) {
         if (M <= 16) {
             // One CTA per CU: the column tiles are dealt evenly over min(NT, #CU) strips (widths differ by at most
             // one tile), because a CU sustains only ~25 GB/s of weight traffic and the slowest CU sets the time.
@@ -166,7 +176,7 @@ Plan make_plan(const tm_packed_w4* h, int M, int num_cu)
             // Deep-and-narrow layers with many rows: every strip re-reads all M*K activations, which then outweighs
             // the weights; 64-column strips with K split over four CTAs read a quarter of X each (measured
             // 11.2 vs 14.2 us at K=11008, N=4096, M=16; not a gain at K=4096).
-            if (per_cu <= 1 && M > 8 && KU >= 64 && NT >= num_cu) variant = kSkinny16x64;
+            if (per_cu <= 1 && M > 8 && h->K >= 8192 && NT >= num_cu) variant = kSkinny16x64;
         } else if (M <= 32 && ceil_div(NT, 4) * 2 <= num_cu) {
             // narrow outputs (N <= 8192 on 256 CUs): 64-column strips with K split across CTAs so that every
             // CU gets one CTA; each CTA then re-reads only its K slice of X
@@ -193,7 +203,7 @@ Plan make_plan(const tm_packed_w4* h, int M, int num_cu)
         }
     }
     if (is_skinny(variant) && M > skinny_rows(variant))        // a forced skinny variant must still cover M
-        variant = M <= 32 ? kSkinny32x64 : (M <= 64 ? kSkinny64x64 : kTile64x256);
+        variant = M <= 32 ? kSkinny32x64 : (M <= 64 || w8 ? kSkinny64x64 : kTile64x256);
     pl.variant = variant;
     const size_t out_bytes = (size_t)M * h->N * sizeof(float);
     int max_split_ws = (int)(kPartialBudget / (out_bytes ? out_bytes : 1));
@@ -304,6 +314,16 @@ int run_gemm(const uint16_t* X, const tm_packed_w4* h, uint16_t* Y, int M, void*
     int rc = check_device(&dev);
     if (rc != TM_OK) return rc;
     if (dev != h->device) return fail(TM_EINVAL, "handle belongs to device %d, current device is %d", h->device, dev);
+    if (h->bits == 8 && M > 64) {
+        // 8-bit codes have decode kernels only: larger batches go through them 64 rows at a time (stream order
+        // keeps the shared workspace safe), re-reading the weights for every slice
+        for (int m0 = 0; m0 < M; m0 += 64) {
+            rc = run_gemm(X + (size_t)m0 * h->K, h, Y + (size_t)m0 * h->N, M - m0 < 64 ? M - m0 : 64, ws, ws_bytes,
+                          own_ws, stream);
+            if (rc != TM_OK) return rc;
+        }
+        return TM_OK;
+    }
     Plan pl = make_plan(h, M, g_dev[dev].num_cu);
     if (own_ws) {
         ws = g_dev[dev].workspace;
@@ -326,7 +346,7 @@ int run_gemm(const uint16_t* X, const tm_packed_w4* h, uint16_t* Y, int M, void*
     p.M = M;
     p.K = h->K;
     p.N = h->N;
-    p.KU = h->K / kUnitK;
+    p.KU = h->bits == 8 ? h->K / 64 : h->K / kUnitK;
     p.NT = h->N / kUnitN;
     p.G = h->K / h->group;
     p.split = pl.split;
@@ -334,8 +354,9 @@ int run_gemm(const uint16_t* X, const tm_packed_w4* h, uint16_t* Y, int M, void*
     p.tiles_m = pl.tiles_m;
     p.tiles_n = pl.tiles_n;
     p.strips = pl.strips;
-    hipError_t e = is_skinny(pl.variant) ? launch_skinny(p, pl, h->group, stream)
-                                         : launch_tile(p, pl, h->group, stream);
+    hipError_t e = h->bits == 8 ? launch_skinny_w8(p, pl, h->group, stream)
+                   : is_skinny(pl.variant) ? launch_skinny(p, pl, h->group, stream)
+                                           : launch_tile(p, pl, h->group, stream);
     if (e != hipSuccess) return fail_hip(e, "kernel launch");
     return TM_OK;
 }
@@ -348,8 +369,8 @@ using namespace tmw4;
 
 extern "C" {
 
-tm_packed_w4* tm_pack_w4_layout(const void* qweight, const uint16_t* scales, const void* zeros, int K, int N,
-                                int group, int layout, tm_stream stream)
+static tm_packed_w4* pack_impl(const void* qweight, const uint16_t* scales, const void* zeros, int K, int N, int group,
+                        int layout, int bits, tm_stream stream)
 {
     if (layout != TM_LAYOUT_N8 && layout != TM_LAYOUT_N8_INTERLEAVED && layout != TM_LAYOUT_K8) {
         fail(TM_EINVAL, "unknown layout %d", layout);
@@ -390,7 +411,8 @@ tm_packed_w4* tm_pack_w4_layout(const void* qweight, const uint16_t* scales, con
     h->N = N;
     h->group = group;
     h->device = dev;
-    h->w_bytes = (size_t)K * N / 2;
+    h->bits = bits;
+    h->w_bytes = (size_t)K * N * bits / 8;
     h->sz_bytes = (size_t)(K / group) * N * 4;
     hipError_t e = hipMalloc((void**)&h->w, h->w_bytes);
     if (e == hipSuccess) {
@@ -402,8 +424,10 @@ tm_packed_w4* tm_pack_w4_layout(const void* qweight, const uint16_t* scales, con
         delete h;
         return nullptr;
     }
-    e = launch_repack((const uint32_t*)qweight, scales, zeros, h->w, h->sz, K, N, caller_group, layout,
-                      (hipStream_t)stream);
+    e = bits == 4 ? launch_repack((const uint32_t*)qweight, scales, zeros, h->w, h->sz, K, N, caller_group, layout,
+                                  (hipStream_t)stream)
+                  : launch_repack8((const uint32_t*)qweight, scales, (const uint16_t*)zeros, h->w, h->sz, K, N,
+                                   caller_group, (hipStream_t)stream);
     if (e != hipSuccess) {
         fail_hip(e, "repack launch");
         (void)hipFree(h->w);
@@ -412,6 +436,18 @@ tm_packed_w4* tm_pack_w4_layout(const void* qweight, const uint16_t* scales, con
         return nullptr;
     }
     return h;
+}
+
+tm_packed_w4* tm_pack_w4_layout(const void* qweight, const uint16_t* scales, const void* zeros, int K, int N,
+                                int group, int layout, tm_stream stream)
+{
+    return pack_impl(qweight, scales, zeros, K, N, group, layout, 4, stream);
+}
+
+tm_packed_w4* tm_pack_w8(const uint32_t* qweight, const uint16_t* scales, const uint16_t* zeros, int K, int N,
+                         int group, tm_stream stream)
+{
+    return pack_impl(qweight, scales, zeros, K, N, group, TM_LAYOUT_N8, 8, stream);
 }
 
 tm_packed_w4* tm_pack_w4_on(const uint32_t* qweight, const uint16_t* scales, const uint16_t* zeros, int K, int N,
@@ -440,6 +476,10 @@ tm_expert_group* tm_group_experts(const tm_packed_w4* const* experts, int num_ex
     for (int e = 0; e < num_experts; ++e) {
         if (!valid(experts[e])) {
             fail(TM_EINVAL, "expert %d: handle is null or invalid", e);
+            return nullptr;
+        }
+        if (experts[e]->bits != 4) {
+            fail(TM_EUNSUPPORTED, "expert %d: grouped GEMM takes 4-bit weights only", e);
             return nullptr;
         }
         if (experts[e]->K != experts[0]->K || experts[e]->N != experts[0]->N ||
@@ -555,7 +595,7 @@ size_t tm_gemm_workspace_bytes(const tm_packed_w4* packed, int M)
     }
     int dev = packed->device;
     int cu = (dev >= 0 && dev < kMaxDevices && g_dev[dev].checked) ? g_dev[dev].num_cu : 256;
-    return make_plan(packed, M, cu).ws_bytes;
+    return make_plan(packed, packed->bits == 8 && M > 64 ? 64 : M, cu).ws_bytes;
 }
 
 void tm_free_packed(tm_packed_w4* packed)
@@ -577,10 +617,17 @@ int tm_packed_info(const tm_packed_w4* packed, int* K, int* N, int* group, size_
     return TM_OK;
 }
 
+int tm_packed_bits(const tm_packed_w4* packed)
+{
+    if (!valid(packed)) return fail(TM_EINVAL, "packed handle is null or invalid");
+    return packed->bits;
+}
+
 int tm_unpack_w4(const tm_packed_w4* packed, uint32_t* qweight_out, uint16_t* scales_out, uint16_t* zeros_out,
                  tm_stream stream)
 {
     if (!valid(packed)) return fail(TM_EINVAL, "packed handle is null or invalid");
+    if (packed->bits != 4) return fail(TM_EUNSUPPORTED, "tm_unpack_w4 handles 4-bit weights only");
     hipError_t e = launch_unpack(packed->w, packed->sz, qweight_out, scales_out, zeros_out, packed->K, packed->N,
                                  packed->group, (hipStream_t)stream);
     if (e != hipSuccess) return fail_hip(e, "unpack launch");
@@ -604,7 +651,7 @@ int tm_get_plan(const tm_packed_w4* packed, int M, int* variant, int* split_k, i
     if (M <= 0 || M >= (1 << 24)) return fail(TM_EINVAL, "M = %d out of range", M);
     int dev = packed->device;
     int cu = (dev >= 0 && dev < kMaxDevices && g_dev[dev].checked) ? g_dev[dev].num_cu : 256;
-    Plan pl = make_plan(packed, M, cu);
+    Plan pl = make_plan(packed, packed->bits == 8 && M > 64 ? 64 : M, cu);      // 8-bit: plan of one 64-row slice
     if (variant) *variant = pl.variant;
     if (split_k) *split_k = pl.split;
     if (grid) *grid = (int)pl.grid;

@@ -61,7 +61,7 @@ __device__ __forceinline__ GroupConst make_group_const(uint32_t sz)
     _Float16 s = p.x, z = p.y;
     GroupConst g;
     g.s2 = f16x2{s, s};
-    _Float16 a = (_Float16)(-1024.0f) - z;   // exact: 1024 + z <= 1039 is an fp16 integer
+    _Float16 a = (_Float16)(-1024.0f) - z;   // exact: 1024 + z is an fp16 integer (z <= 15, or <= 255 for 8-bit codes)
     _Float16 b = (_Float16)(-64.0f) - z;
     g.off1024 = f16x2{a, a};
     g.off64 = f16x2{b, b};
@@ -124,6 +124,39 @@ __device__ __forceinline__ f16x8 bias_cancel8(_Float16 z)
     _Float16 a = (_Float16)(-1024.0f) - z;   // exact: 1024 + z <= 1039 is an fp16 integer
     _Float16 b = (_Float16)(-64.0f) - z;
     return f16x8{a, a, b, b, a, a, b, b};
+}
+
+// 8-bit codes.  A byte b placed under the exponent byte 0x64 is the fp16 number 1024 + b (b fills the low eight
+// mantissa bits), so one byte permute (v_perm_b32 against the constant 0x64646464) turns two codes into two fp16
+// values: four permutes per eight weights.  w0 holds the codes e0..e3 in bytes 0..3, w1 holds e4..e7.
+__device__ __forceinline__ f16x8 biased8_w8(uint32_t w0, uint32_t w1)
+{
+    const uint32_t hi = 0x64646464u;               // selector bytes 4..7 pick from here, 0..3 from the weight word
+    u32x4 r;
+    r.x = __builtin_amdgcn_perm(hi, w0, 0x04010400u);
+    r.y = __builtin_amdgcn_perm(hi, w0, 0x04030402u);
+    r.z = __builtin_amdgcn_perm(hi, w1, 0x04010400u);
+    r.w = __builtin_amdgcn_perm(hi, w1, 0x04030402u);
+    return __builtin_bit_cast(f16x8, r);
+}
+
+// -(1024 + z) in all eight places: exact, because 1024 + z <= 1279 is an fp16 integer.
+__device__ __forceinline__ f16x8 bias_cancel8_w8(_Float16 z)
+{
+    _Float16 a = (_Float16)(-1024.0f) - z;
+    return f16x8{a, a, a, a, a, a, a, a};
+}
+
+// (1024 + q) - (1024 + z) = q - z exactly (|q - z| <= 255), then one rounded multiply by the scale:
+// 12 vector instructions per 8 weights.
+__device__ __forceinline__ f16x8 dequant8_w8(uint32_t w0, uint32_t w1, const GroupConst& g)
+{
+    const uint32_t hi = 0x64646464u;
+    f16x2 r0 = (as_f16x2(__builtin_amdgcn_perm(hi, w0, 0x04010400u)) + g.off1024) * g.s2;
+    f16x2 r1 = (as_f16x2(__builtin_amdgcn_perm(hi, w0, 0x04030402u)) + g.off1024) * g.s2;
+    f16x2 r2 = (as_f16x2(__builtin_amdgcn_perm(hi, w1, 0x04010400u)) + g.off1024) * g.s2;
+    f16x2 r3 = (as_f16x2(__builtin_amdgcn_perm(hi, w1, 0x04030402u)) + g.off1024) * g.s2;
+    return f16x8{r0.x, r0.y, r1.x, r1.y, r2.x, r2.y, r3.x, r3.y};
 }
 
 // D = A(16x32) * B(32x16) + C on the matrix cores.  Lane l supplies row l%16 of A and column l%16 of B, each

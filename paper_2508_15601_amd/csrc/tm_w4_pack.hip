@@ -71,6 +71,42 @@ __global__ __launch_bounds__(256) void repack_w4_kernel(const uint32_t* __restri
     }
 }
 
+// 8-bit codes: interchange words u32 [K][N/4] (byte t = column 4j+t) -> units of 16 columns x 64 rows, word
+// 4*lane + 2*tt + hf = rows 64*ks + 32*tt + 8*h + 4*hf + b in byte b (lane = 16*h + c).  A CTA stages 128 rows x 128
+// columns (128-byte row segments) and writes the 8 x 2 units they make.
+__global__ __launch_bounds__(256) void repack_w8_kernel(const uint32_t* __restrict__ qweight,
+                                                        uint32_t* __restrict__ out, int K, int N)
+{
+    __shared__ uint32_t tile[128][33];
+    const int KS = K / 64, NT = N / kUnitN, NW = N / 4;
+    const int ku = blockIdx.y;
+    const int nt0 = blockIdx.x * 8;
+    const int tid = threadIdx.x;
+    for (int i = 0; i < 16; ++i) {
+        int idx = i * 256 + tid;
+        int row = idx >> 5, wc = idx & 31;
+        int gw = nt0 * 4 + wc;
+        tile[row][wc] = gw < NW ? qweight[(size_t)(ku * 128 + row) * NW + gw] : 0u;
+    }
+    __syncthreads();
+    const int lane = tid >> 2, wi = tid & 3;
+    const int c = lane & 15, h = lane >> 4;
+    const int r0 = 32 * (wi >> 1) + 8 * h + 4 * (wi & 1);
+    for (int j = 0; j < 8; ++j) {
+        int nt = nt0 + j;
+        if (nt >= NT) break;
+        int col = 16 * j + c;
+        int wc = col >> 2, sh = 8 * (col & 3);
+#pragma unroll
+        for (int su = 0; su < 2; ++su) {
+            uint32_t w = 0;
+#pragma unroll
+            for (int b = 0; b < 4; ++b) w |= ((tile[64 * su + r0 + b][wc] >> sh) & 0xFFu) << (8 * b);
+            out[((size_t)nt * KS + 2 * ku + su) * kUnitWords + tid] = w;
+        }
+    }
+}
+
 // ZFMT: 0 zeros are fp16 [G][N]; 1 u32 [G][N/8], nibble t = column 8j+t; 2 u32 [G][N/8], nibble p = column
 // 8j + (0,2,4,6,1,3,5,7)[p].  Packed integers are widened to the fp16 pattern the GEMM kernels expect.
 // G counts the stored groups; source row g / rep feeds stored group g (rep > 1 when the caller's groups are coarser
@@ -78,7 +114,7 @@ __global__ __launch_bounds__(256) void repack_w4_kernel(const uint32_t* __restri
 template <int ZFMT>
 __global__ __launch_bounds__(256) void repack_sz_kernel(const uint16_t* __restrict__ scales,
                                                         const void* __restrict__ zeros,
-                                                        uint32_t* __restrict__ out, int G, int N, int rep)
+                                                        uint32_t* __restrict__ out, int G, int N, int rep, uint32_t sym_zero)
 {
     size_t idx = (size_t)blockIdx.x * 256 + threadIdx.x;
     size_t total = (size_t)G * N;
@@ -91,7 +127,7 @@ __global__ __launch_bounds__(256) void repack_sz_kernel(const uint16_t* __restri
     size_t src = (size_t)g * N + n;
     uint32_t zb;
     if (!zeros) {
-        zb = 0x4800u;                              // fp16 8.0
+        zb = sym_zero;                             // fp16 8.0 (4-bit codes) or 128.0 (8-bit codes)
     } else if constexpr (ZFMT == 0) {
         zb = ((const uint16_t*)zeros)[src];
     } else {
@@ -167,19 +203,32 @@ hipError_t launch_repack(const uint32_t* qweight, const uint16_t* scales, const 
     switch (layout) {
     case 0:
         hipLaunchKernelGGL(repack_w4_kernel<0>, grid, dim3(256), 0, stream, qweight, w_out, K, N);
-        hipLaunchKernelGGL(repack_sz_kernel<0>, szgrid, dim3(256), 0, stream, scales, zeros, sz_out, G, N, rep);
+        hipLaunchKernelGGL(repack_sz_kernel<0>, szgrid, dim3(256), 0, stream, scales, zeros, sz_out, G, N, rep, 0x4800u);
         break;
     case 1:
         hipLaunchKernelGGL(repack_w4_kernel<1>, grid, dim3(256), 0, stream, qweight, w_out, K, N);
-        hipLaunchKernelGGL(repack_sz_kernel<2>, szgrid, dim3(256), 0, stream, scales, zeros, sz_out, G, N, rep);
+        hipLaunchKernelGGL(repack_sz_kernel<2>, szgrid, dim3(256), 0, stream, scales, zeros, sz_out, G, N, rep, 0x4800u);
         break;
     case 2:
         hipLaunchKernelGGL(repack_w4_kernel<2>, grid, dim3(256), 0, stream, qweight, w_out, K, N);
-        hipLaunchKernelGGL(repack_sz_kernel<1>, szgrid, dim3(256), 0, stream, scales, zeros, sz_out, G, N, rep);
+        hipLaunchKernelGGL(repack_sz_kernel<1>, szgrid, dim3(256), 0, stream, scales, zeros, sz_out, G, N, rep, 0x4800u);
         break;
     default:
         return hipErrorInvalidValue;
     }
+    return hipGetLastError();
+}
+
+hipError_t launch_repack8(const uint32_t* qweight, const uint16_t* scales, const uint16_t* zeros, uint32_t* w_out,
+                          uint32_t* sz_out, int K, int N, int group, hipStream_t stream)
+{
+    const int stored = group > 128 ? 128 : group, rep = group / stored;
+    const int NT = N / kUnitN, G = K / stored;
+    dim3 grid((NT + 7) / 8, K / 128);
+    hipLaunchKernelGGL(repack_w8_kernel, grid, dim3(256), 0, stream, qweight, w_out, K, N);
+    size_t total = (size_t)G * N;
+    hipLaunchKernelGGL(repack_sz_kernel<0>, dim3((unsigned)((total + 255) / 256)), dim3(256), 0, stream, scales,
+                       (const void*)zeros, sz_out, G, N, rep, 0x5800u);
     return hipGetLastError();
 }
 

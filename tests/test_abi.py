@@ -33,7 +33,7 @@ def test_header_symbols_are_exported(lib):
 
 def test_binding_uses_same_names():
     import paper_2508_15601_amd as tm
-    for n in ("tm_pack_w4", "tm_pack_w4_layout", "tm_group_experts", "tm_gemm_w4a16_grouped", "tm_gemm_w4a16", "tm_gemm_w4a16_ws", "tm_unpack_w4", "tm_packed_raw", "tm_get_plan",
+    for n in ("tm_pack_w4", "tm_pack_w4_layout", "tm_pack_w8", "tm_group_experts", "tm_gemm_w4a16_grouped", "tm_gemm_w4a16", "tm_gemm_w4a16_ws", "tm_unpack_w4", "tm_packed_raw", "tm_get_plan",
               "tm_set_variant", "tm_gemm_workspace_bytes", "tm_last_error", "tm_version"):
         assert callable(getattr(tm, n))
 
@@ -61,6 +61,9 @@ def test_argument_validation_without_gpu(lib):
     assert lib.tm_pack_w4_layout(fake, fake, ctypes.c_void_p(4098), 128, 16, 128, 1, None) is None    # u32 zeros
     assert "misaligned" in tm.tm_last_error()
     assert lib.tm_gemm_w4a16(fake, None, fake, 1, None) == -1
+    assert lib.tm_pack_w8(fake, None, fake, 128, 16, 128, None) is None and "null" in tm.tm_last_error()
+    assert lib.tm_pack_w8(fake, fake, None, 128, 16, 96, None) is None and "group" in tm.tm_last_error()
+    assert lib.tm_packed_bits(None) == -1
     assert lib.tm_group_experts(None, 2) is None and lib.tm_group_experts(fake, 0) is None
     assert lib.tm_gemm_w4a16_grouped(fake, None, fake, fake, 4, None) == -1
     assert lib.tm_get_grouped_plan(None, 4, None, None) == -1

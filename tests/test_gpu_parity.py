@@ -517,3 +517,113 @@ def test_grouped_gemm_clamps_offsets_and_rejects_mismatched_experts(tm, oracle):
     group.close()
     for p in dev + other:
         p.close()
+
+
+# ------------------------------------------------------------------ 8-bit weight codes (W8A16)
+
+def _w8_case(rng, K, N, g, symmetric=False):
+    q = rng.integers(0, 256, (K, N), dtype=np.uint8)
+    s = rng.uniform(0.0001, 0.002, (K // g, N)).astype(np.float16)
+    z = np.full((K // g, N), 128, np.float16) if symmetric else rng.integers(0, 256, (K // g, N)).astype(np.float16)
+    return q, s, z
+
+
+def _pack_w8(tm, q, s, z, g, symmetric=False):
+    K, N = q.shape
+    return tm.tm_pack_w8(gu.to_dev(wl.pack_interchange8(q)), gu.to_dev(s), None if symmetric else gu.to_dev(z), K, N, g)
+
+
+@pytest.mark.parametrize("K,N,g", [(128, 16, 128), (256, 48, 32), (384, 2064, 64), (1024, 272, 128), (512, 32, 512)])
+def test_w8_pack_bit_exact(tm, oracle, K, N, g):
+    _say(f"w8 pack K={K} N={N} g={g}")
+    rng = np.random.default_rng(K * 13 + N)
+    kk, nn = np.meshgrid(np.arange(K), np.arange(N), indexing="ij")
+    for q in (rng.integers(0, 256, (K, N), dtype=np.uint8), ((kk * 37 + nn * 11 + (kk >> 2) + (nn >> 4)) & 255).astype(np.uint8)):
+        _, s, z = _w8_case(rng, K, N, g)
+        packed = _pack_w8(tm, q, s, z, g)
+        assert packed.bits == 8 and tm.load_library().tm_packed_bits(packed.handle) == 8
+        wbuf, szbuf = tm.tm_packed_raw(packed)
+        gs = min(g, 128)
+        q2, s2, z2 = oracle.unpack_packed(wbuf, szbuf, K, N, gs, bits=8)
+        assert np.array_equal(q2, q)
+        assert np.array_equal(s2.view(np.uint16), np.repeat(s, g // gs, axis=0).view(np.uint16))
+        assert np.array_equal(z2.view(np.uint16), np.repeat(z, g // gs, axis=0).view(np.uint16))
+        packed.close()
+
+
+W8_VARIANTS = [-1, 0, 1, 14, 2, 15, 16, 4, 19]
+
+
+@pytest.mark.parametrize("variant", W8_VARIANTS)
+def test_w8_one_hot_rows_return_dequantised_weights_bit_exactly(tm, oracle, variant):
+    """X = one-hot rows: Y[m] must equal row k_m of (q - z) * s rounded once to fp16, whatever the kernel."""
+    _say(f"w8 one-hot variant={variant}")
+    K, N, g, M = 512, 272, 64, 16
+    rng = np.random.default_rng(31 + variant)
+    q, s, z = _w8_case(rng, K, N, g)
+    packed = _pack_w8(tm, q, s, z, g)
+    X = np.zeros((M, K), np.float16)
+    ks = rng.integers(0, K, M)
+    X[np.arange(M), ks] = 1.0
+    tm.tm_set_variant(variant, 0)
+    try:
+        Y = gu.gemm(packed, X)
+    finally:
+        tm.tm_set_variant(-1, 0)
+    What = oracle.dequant(q, s, z, g)
+    assert np.array_equal(Y.view(np.uint16), What[ks].astype(np.float16).view(np.uint16))
+    packed.close()
+
+
+@pytest.mark.parametrize("g", [32, 64, 128])
+@pytest.mark.parametrize("M,K,N,variant,split", [
+    (1, 1024, 528, -1, 0), (7, 768, 4112, -1, 0), (16, 2048, 1040, -1, 0), (16, 512, 48, 0, 0), (9, 1280, 336, 1, 2),
+    (13, 1024, 1552, 14, 0), (16, 1024, 1040, 2, 3), (5, 896, 1552, 15, 0), (16, 640, 2064, 16, 0),
+    (23, 1024, 1040, -1, 0), (32, 1536, 528, 4, 2), (33, 1024, 272, -1, 0), (64, 768, 1040, 19, 0),
+    (100, 512, 272, -1, 0), (300, 1024, 528, -1, 0)])
+def test_w8_gemm_against_oracle(tm, oracle, M, K, N, variant, split, g):
+    _say(f"w8 gemm M={M} K={K} N={N} g={g} variant={variant} split={split}")
+    rng = np.random.default_rng(M + K + N + g)
+    q, s, z = _w8_case(rng, K, N, g)
+    X = rng.standard_normal((M, K)).astype(np.float16)
+    packed = _pack_w8(tm, q, s, z, g)
+    tm.tm_set_variant(variant, split)
+    try:
+        for waves in ((0, 8, 16) if M <= 16 else (0,)):
+            tm.tm_set_launch(waves, 0)
+            Y = gu.gemm(packed, X)
+            ok, worst, fro = acceptance(Y, oracle.gemm(X, q, s, z, g))
+            assert ok, (waves, worst, fro)
+    finally:
+        tm.tm_set_variant(-1, 0)
+        tm.tm_set_launch(0, 0)
+    packed.close()
+
+
+def test_w8_quantised_weights_symmetric_and_per_channel(tm, oracle):
+    """End to end from fp32 weights through the 8-bit recipe; symmetric packing without a zeros tensor; one scale per
+    output channel; and the handle kinds that take 4-bit weights only."""
+    _say("w8 recipe / symmetric / per-channel")
+    rng = np.random.default_rng(77)
+    K, N, M = 1024, 528, 12
+    W = (0.02 * rng.standard_normal((K, N))).astype(np.float32)
+    X = rng.standard_normal((M, K)).astype(np.float16)
+    for g in (128, K):
+        q, s, z = wl.quantise_recipe(W, g, bits=8)
+        packed = _pack_w8(tm, q, s, z, g)
+        Yref = oracle.gemm(X, q, s, z, g)
+        ok, worst, fro = acceptance(gu.gemm(packed, X), Yref)
+        assert ok, (g, worst, fro)
+        # the 8-bit codes reproduce the fp32 product far better than the tolerance of the 4-bit path
+        exact = X.astype(np.float64) @ W.astype(np.float64)
+        assert np.linalg.norm(Yref.astype(np.float64) - exact) / np.linalg.norm(exact) < (2e-2 if g == K else 1e-2)
+        packed.close()
+    q, s, _ = _w8_case(rng, K, N, 128)
+    packed = _pack_w8(tm, q, s, None, 128, symmetric=True)
+    ok, worst, fro = acceptance(gu.gemm(packed, X), oracle.gemm(X, q, s, np.full((K // 128, N), 128, np.float16), 128))
+    assert ok, (worst, fro)
+    with pytest.raises(tm.TmError):
+        tm.tm_unpack_w4(packed)
+    with pytest.raises(tm.TmError):
+        tm.tm_group_experts([packed])
+    packed.close()
