@@ -1,7 +1,7 @@
 #!/usr/bin/env python3
 """Benchmark of the W4A16 GEMM hot path on one MI355X.
 
-    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload decode|mlp_decode|prefill|sweep|companion|moe|pack|copy]
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload decode|mlp_decode|prefill|sweep|companion|moe|w8|pack|copy]
                     [--sweep-out FILE] [--no-cpu-baseline] [--no-prefill]
 
 A "step" is one pass of the fused GEMM over every (layer, M) pair of the workload, weights already packed
@@ -254,6 +254,48 @@ def moe_table(tm, torch, names, tokens=(1, 4, 16, 64), iters=40, group=128, only
     return rows
 
 
+def w8_table(tm, torch, wl, iters=100):
+    """W8A16 decode: the decode and MLP-decode layer shapes with 8-bit weight codes (random codes; timing does not
+    depend on their values), same timing method as the 4-bit sweep."""
+    rows = []
+    for name, Ms in WORKLOADS["decode"] + WORKLOADS["mlp_decode"]:
+        c = wl.case_by_name(name)
+        G = c.K // c.group
+        wbytes = c.K * c.N + 4 * G * c.N
+        copies = max(2, -(-ROTATE_BYTES // wbytes))
+        packed = []
+        for _ in range(copies):
+            qw = torch.randint(-2 ** 31, 2 ** 31 - 1, (c.K, c.N // 4), dtype=torch.int32, device="cuda")
+            s = (torch.rand((G, c.N), device="cuda") * 0.002 + 0.0001).to(torch.float16)
+            z = torch.randint(0, 256, (G, c.N), device="cuda").to(torch.float16)
+            packed.append(tm.tm_pack_w8(qw, s, z, c.K, c.N, c.group))
+        del qw, s, z
+        for M in Ms:
+            X = [torch.randn((M, c.K), device="cuda").to(torch.float16) for _ in range(4)]
+            Y = [torch.empty((M, c.N), dtype=torch.float16, device="cuda") for _ in range(4)]
+            turn = [0]
+
+            def step():
+                i = turn[0]
+                turn[0] += 1
+                tm.tm_gemm_w4a16(X[i % 4], packed[i % copies], Y[i % 4])
+
+            ev_ms, _ = time_steps(torch, step, iters, 10, graph_steps=iters)
+            t = ev_ms / iters * 1e-3
+            B = wl.algorithmic_bytes(M, c.K, c.N, c.group, bits=8)
+            plan = tm.tm_get_plan(packed[0], M)
+            rows.append({"layer": c.name.rsplit("_M", 1)[0], "M": M, "K": c.K, "N": c.N, "group": c.group, "bits": 8,
+                         "us": t * 1e6, "GBps": B / t / 1e9, "hbm_frac": B / t / 1e9 / HBM_PEAK_GBPS,
+                         "variant": plan["name"], "split_k": plan["split_k"], "grid": plan["grid"], "block": plan["block"]})
+            log(f"W8A16 {rows[-1]['layer']:14s} M={M:3d} K={c.K:6d} N={c.N:6d} {t * 1e6:8.2f} us {B / t / 1e9:7.0f} GB/s "
+                f"({100 * B / t / 1e9 / HBM_PEAK_GBPS:4.1f} % HBM)  {plan['name']} split {plan['split_k']} block {plan['block']}")
+        for p in packed:
+            p.close()
+        del packed
+        torch.cuda.empty_cache()
+    return rows
+
+
 def cpu_baseline(wl, layers, min_s=5.0, budget_s=25.0):
     """The oracle as it stands, timed on this host's cores over the same workload: whole passes over every
     (layer, M) pair are repeated until at least `min_s` seconds have been spent; a single GEMM too large for
@@ -289,7 +331,7 @@ def main():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=200)
     ap.add_argument("--warmup", type=int, default=20)
-    ap.add_argument("--workload", default="decode", choices=sorted(WORKLOADS) + ["sweep", "copy", "companion", "pack", "moe"])
+    ap.add_argument("--workload", default="decode", choices=sorted(WORKLOADS) + ["sweep", "copy", "companion", "pack", "moe", "w8"])
     ap.add_argument("--sweep-out", default=None, help="with --workload sweep: write the per-shape table here (JSON)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-prefill", action="store_true", help="skip the prefill companion measurement")
@@ -352,6 +394,14 @@ def main():
             rows.append({"layout": layout, "ms_per_pack_call": ms})
             log(f"layout {layout}: {ms:.3f} ms per pack call (allocation + two kernels + free)")
         print(json.dumps({"metric": "offline pack", "K": K, "N": N, "group": g, "steps": args.steps, "rows": rows}))
+        return
+
+    if args.workload == "w8":
+        table = w8_table(tm, torch, wl, iters=min(args.steps, 100))
+        if args.sweep_out:
+            os.makedirs(os.path.dirname(os.path.abspath(args.sweep_out)), exist_ok=True)
+            json.dump(table, open(args.sweep_out, "w"), indent=1)
+        print(json.dumps({"metric": "W8A16 GEMM, decode: effective HBM GB/s", "workload": "w8", "rows": table}))
         return
 
     if args.workload == "moe":

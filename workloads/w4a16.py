@@ -162,9 +162,9 @@ def case_by_name(name: str) -> Case:
     raise KeyError(name)
 
 
-def algorithmic_bytes(M: int, K: int, N: int, group: int) -> int:
-    """Bytes the method itself must move: int4 weights + fp16 scale and zero per group + X + Y."""
-    return K * N // 2 + 4 * K * N // group + 2 * M * K + 2 * M * N
+def algorithmic_bytes(M: int, K: int, N: int, group: int, bits: int = 4) -> int:
+    """Bytes the method itself must move: int4 (or int8) weights + fp16 scale and zero per group + X + Y."""
+    return K * N * bits // 8 + 4 * K * N // group + 2 * M * K + 2 * M * N
 
 
 def flops(M: int, K: int, N: int) -> int:
