@@ -20,6 +20,10 @@
  *   - orc_quantise_bits, orc_pack_canonical8 / orc_unpack_canonical8, orc_unpack_packed8:
  *                     the same pipeline for 8-bit weights (paper Sec. 4.1/Sec. 3.3 present packing and the fused
  *                     GEMM as independent of the weight width): codes 0..255, four per 32-bit word.
+ *   - orc_fp8e4m3_decode_table, orc_quantise_fp8, orc_dequant_fp8, orc_gemm_fp8:
+ *                     FP8 (E4M3) weight codes through the same GEMM (the paper's evaluation includes an FP8 model,
+ *                     Sec. 5.3): W^[k][n] = fp8(q[k][n]) * s[k/g][n], no zero-point; the format is the published
+ *                     OCP 8-bit floating point E4M3 (finite-only: bias 7, no infinities, S.1111.111 = NaN).
  *   - orc_unpack_packed:
  *                     inverse index map of the library's MFMA-fragment-ordered buffer (the gfx950 analogue
  *                     of the packed fragment store of paper Sec. 4.1 steps (iii)-(iv)); written from the
@@ -299,6 +303,89 @@ ORC_API int orc_unpack_packed8(const uint32_t* wbuf, const uint32_t* szbuf, int 
 }
 
 /* ---------------------------------------------------------------- dequantise and multiply */
+
+/* OCP FP8 E4M3, finite-only: sign(1) exponent(4, bias 7) mantissa(3); exponent 0 is subnormal (m/8 * 2^-6);
+ * exponent 15 is an ordinary binade except mantissa 7, which is NaN.  Largest finite value 1.75 * 2^8 = 448. */
+static double fp8e4m3_to_double(uint8_t c)
+{
+    int sign = c >> 7, e = (c >> 3) & 0xF, m = c & 7;
+    double v;
+    if (e == 15 && m == 7) return NAN;
+    if (e == 0) v = ldexp((double)m / 8.0, -6);
+    else v = ldexp(1.0 + (double)m / 8.0, e - 7);
+    return sign ? -v : v;
+}
+
+ORC_API void orc_fp8e4m3_decode_table(double* out256)
+{
+    for (int c = 0; c < 256; ++c) out256[c] = fp8e4m3_to_double((uint8_t)c);
+}
+
+/* nearest finite code to v (|v| <= 448 after clamping); ties go to the code with an even mantissa bit.
+ * Brute force over the 127 non-negative finite codes: slow and obviously right. */
+static uint8_t fp8e4m3_from_float(float v)
+{
+    double a = fabs((double)v);
+    if (a > 448.0) a = 448.0;
+    int best = 0;
+    double bestd = a;                                   /* distance to code 0 */
+    for (int c = 1; c < 127; ++c) {
+        double d = fabs(fp8e4m3_to_double((uint8_t)c) - a);
+        if (d < bestd || (d == bestd && (c & 1) == 0)) { best = c; bestd = d; }
+    }
+    return (uint8_t)(best | ((v < 0.0f || (v == 0.0f && signbit(v))) ? 0x80 : 0));
+}
+
+/* recipe: per column and K-group s = fp16(max|w| / 448) (1 if that is 0 or not finite), q = fp8(w / s), fp32 arithmetic */
+ORC_API int orc_quantise_fp8(const float* W, int K, int N, int g, uint8_t* q, uint16_t* s)
+{
+    if (!W || !q || !s || K <= 0 || N <= 0 || g <= 0 || K % g) return -1;
+    for (int gi = 0; gi < K / g; ++gi)
+        for (int n = 0; n < N; ++n) {
+            float amax = 0.0f;
+            for (int k = gi * g; k < gi * g + g; ++k) {
+                float a = fabsf(W[(size_t)k * N + n]);
+                if (a > amax) amax = a;
+            }
+            uint16_t sh = orc_double_to_fp16((double)(amax / 448.0f));
+            float sf = (float)orc_fp16_to_double(sh);
+            if (!(sf > 0.0f) || isinf(sf)) { sf = 1.0f; sh = 0x3C00u; }
+            s[(size_t)gi * N + n] = sh;
+            for (int k = gi * g; k < gi * g + g; ++k)
+                q[(size_t)k * N + n] = fp8e4m3_from_float(W[(size_t)k * N + n] / sf);
+        }
+    return 0;
+}
+
+ORC_API int orc_dequant_fp8(const uint8_t* q, const uint16_t* s, int K, int N, int g, double* What)
+{
+    if (!q || !s || !What || K <= 0 || N <= 0 || g <= 0 || K % g) return -1;
+    for (int k = 0; k < K; ++k)
+        for (int n = 0; n < N; ++n)
+            What[(size_t)k * N + n] = fp8e4m3_to_double(q[(size_t)k * N + n]) * orc_fp16_to_double(s[(size_t)(k / g) * N + n]);
+    return 0;
+}
+
+/* Y[m][n] = fp16( sum_k X[m][k] * fp8(q[k][n]) * s[k/g][n] ), k ascending in fp64, one rounding */
+ORC_API int orc_gemm_fp8(const uint16_t* X, int M, const uint8_t* q, const uint16_t* s, int K, int N, int g,
+                         uint16_t* Y, double* Yd)
+{
+    if (!X || !q || !s || !Y || M < 0 || K <= 0 || N <= 0 || g <= 0 || K % g) return -1;
+#ifdef _OPENMP
+#pragma omp parallel for schedule(static)
+#endif
+    for (int n = 0; n < N; ++n)
+        for (int m = 0; m < M; ++m) {
+            double acc = 0.0;
+            for (int k = 0; k < K; ++k)
+                acc += orc_fp16_to_double(X[(size_t)m * K + k]) *
+                       (fp8e4m3_to_double(q[(size_t)k * N + n]) * orc_fp16_to_double(s[(size_t)(k / g) * N + n]));
+            if (Yd) Yd[(size_t)m * N + n] = acc;
+            Y[(size_t)m * N + n] = orc_double_to_fp16(acc);
+        }
+    return 0;
+}
+
 
 /* What[k][n] = (q - z) * s in fp64 (exact: an integer of at most 9 bits times an 11-bit significand) */
 ORC_API int orc_dequant(const uint8_t* q, const uint16_t* s, const uint16_t* z, int K, int N, int g, double* What)

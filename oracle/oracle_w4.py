@@ -49,6 +49,11 @@ def _load():
         lib.orc_pack_canonical8.argtypes = [vp, c.c_int, c.c_int, vp]
         lib.orc_unpack_canonical8.argtypes = [vp, c.c_int, c.c_int, vp]
         lib.orc_unpack_packed8.argtypes = [vp, vp, c.c_int, c.c_int, c.c_int, vp, vp, vp]
+        lib.orc_fp8e4m3_decode_table.argtypes = [vp]
+        lib.orc_fp8e4m3_decode_table.restype = None
+        lib.orc_quantise_fp8.argtypes = [vp, c.c_int, c.c_int, c.c_int, vp, vp]
+        lib.orc_dequant_fp8.argtypes = [vp, vp, c.c_int, c.c_int, c.c_int, vp]
+        lib.orc_gemm_fp8.argtypes = [vp, c.c_int, vp, vp, c.c_int, c.c_int, c.c_int, vp, vp]
         lib.orc_unpack_packed.argtypes = [vp, vp, c.c_int, c.c_int, c.c_int, vp, vp, vp]
         lib.orc_dequant.argtypes = [vp, vp, vp, c.c_int, c.c_int, c.c_int, vp]
         lib.orc_gemm.argtypes = [vp, c.c_int, vp, vp, vp, c.c_int, c.c_int, c.c_int, vp, vp]
@@ -208,6 +213,44 @@ def gemm(X: np.ndarray, q: np.ndarray, s: np.ndarray, z: np.ndarray, group: int,
     _check(_load().orc_gemm(_ptr(X), M, _ptr(q), _ptr(s), _ptr(z), K, N, group, _ptr(Y),
                             _ptr(Yd) if want_fp64 else None), "gemm")
     return (Y.view(np.float16), Yd) if want_fp64 else Y.view(np.float16)
+
+
+def fp8e4m3_table() -> np.ndarray:
+    """The 256 values of the OCP FP8 E4M3 (finite-only) codes as float64 (NaN at 0x7F and 0xFF)."""
+    out = np.empty(256, np.float64)
+    _load().orc_fp8e4m3_decode_table(_ptr(out))
+    return out
+
+
+def quantise_fp8(W: np.ndarray, group: int):
+    """W fp32 [K,N] -> (q uint8 [K,N] FP8 E4M3 codes, s float16 [K/g,N]), s = fp16(max|w|/448) per group."""
+    W = _as(W, np.float32)
+    K, N = W.shape
+    q = np.empty((K, N), np.uint8)
+    s = np.empty((K // group, N), np.uint16)
+    _check(_load().orc_quantise_fp8(_ptr(W), K, N, group, _ptr(q), _ptr(s)), "quantise_fp8")
+    return q, s.view(np.float16)
+
+
+def dequant_fp8(q: np.ndarray, s: np.ndarray, group: int) -> np.ndarray:
+    q = _as(q, np.uint8)
+    s = _as(s, np.uint16)
+    K, N = q.shape
+    out = np.empty((K, N), np.float64)
+    _check(_load().orc_dequant_fp8(_ptr(q), _ptr(s), K, N, group, _ptr(out)), "dequant_fp8")
+    return out
+
+
+def gemm_fp8(X: np.ndarray, q: np.ndarray, s: np.ndarray, group: int) -> np.ndarray:
+    """Y = fp16(X @ (fp8(q) * s)) with fp64 accumulation, k ascending."""
+    X = _as(X, np.uint16)
+    q = _as(q, np.uint8)
+    s = _as(s, np.uint16)
+    M, K = X.shape
+    N = q.shape[1]
+    Y = np.empty((M, N), np.uint16)
+    _check(_load().orc_gemm_fp8(_ptr(X), M, _ptr(q), _ptr(s), K, N, group, _ptr(Y), None), "gemm_fp8")
+    return Y.view(np.float16)
 
 
 def gemm_grouped(X: np.ndarray, experts, offsets, group: int) -> np.ndarray:

@@ -478,3 +478,53 @@ def test_gemm_grouped_equals_masked_sum_of_dense_products(oracle):
     Y1 = oracle.gemm_grouped(X1, experts, offsets, g)
     for r in range(9):
         assert np.array_equal(Y1[r], What[owner[r]][(7 * r) % K].astype(np.float16))
+
+
+# ------------------------------------------------------------------ FP8 (E4M3) weight codes
+
+def test_fp8_decode_table_against_closed_forms_and_torch(oracle):
+    import torch
+    t = oracle.fp8e4m3_table()
+    # closed forms of the format: zero, smallest subnormal 2^-9, smallest normal 2^-6, 1.0 = code 0x38, largest 448
+    assert t[0] == 0.0 and t[1] == 2.0 ** -9 and t[8] == 2.0 ** -6 and t[0x38] == 1.0 and t[0x7E] == 448.0
+    assert np.isnan(t[0x7F]) and np.isnan(t[0xFF]) and t[0x80] == 0.0 and np.signbit(t[0x80])
+    assert np.array_equal(t[128:255], -t[0:127])
+    assert np.all(np.diff(t[:127]) > 0)                                   # codes are ordered like their values
+    ref = torch.arange(256, dtype=torch.uint8).view(torch.float8_e4m3fn).to(torch.float64).numpy()
+    assert np.array_equal(np.isnan(t), np.isnan(ref)) and np.array_equal(t[~np.isnan(t)], ref[~np.isnan(ref)])
+
+
+def test_fp8_quantiser_against_torch_and_generator(oracle):
+    import torch
+    rng = np.random.default_rng(12)
+    W = (0.02 * rng.standard_normal((256, 24))).astype(np.float32)
+    W[0, 0] = 0.0
+    W[5, 1] = -0.0
+    for g in (32, 128):
+        q, s = oracle.quantise_fp8(W, g)
+        q2, s2 = wl.quantise_fp8_recipe(W, g)
+        assert np.array_equal(s.view(np.uint16), s2.view(np.uint16)) and np.array_equal(q, q2)
+        assert (q & 0x7F).max() == 0x7E                                   # every group's maximum lands on 448
+    # exact ties between neighbouring codes go to the even mantissa: 17 -> 16 (0x58), 19 -> 20 (0x5A), 18 stays (0x59)
+    Wt = np.array([[448.0], [17.0], [18.0], [19.0], [-17.0], [0.0009765625]], np.float32)    # s = 1 exactly
+    qt, st = oracle.quantise_fp8(Wt, 6)
+    assert float(st[0, 0]) == 1.0 and qt[:, 0].tolist() == [0x7E, 0x58, 0x59, 0x5A, 0xD8, 0x00]
+    assert qt[:, 0].tolist() == torch.from_numpy(Wt[:, 0]).to(torch.float8_e4m3fn).view(torch.uint8).tolist()
+
+
+def test_fp8_gemm_against_numpy(oracle):
+    rng = np.random.default_rng(13)
+    K, N, g, M = 128, 24, 32, 5
+    q = rng.integers(0, 256, (K, N), dtype=np.uint8)
+    q[(q & 0x7F) == 0x7F] = 0x3C                                          # no NaN codes
+    s = rng.uniform(0.001, 0.01, (K // g, N)).astype(np.float16)
+    X = rng.standard_normal((M, K)).astype(np.float16)
+    What = oracle.fp8e4m3_table()[q] * np.repeat(s.astype(np.float64), g, axis=0)
+    assert np.array_equal(oracle.dequant_fp8(q, s, g), What)
+    want = X.astype(np.float64) @ What
+    Y = oracle.gemm_fp8(X, q, s, g)
+    assert np.allclose(Y.astype(np.float64), want, rtol=1e-3, atol=1e-6)
+    # one-hot rows pick single dequantised weights, rounded once
+    X1 = np.zeros((M, K), np.float16)
+    X1[np.arange(M), [3, 40, 77, 100, 127]] = 1.0
+    assert np.array_equal(oracle.gemm_fp8(X1, q, s, g), What[[3, 40, 77, 100, 127]].astype(np.float16))

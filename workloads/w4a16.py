@@ -93,6 +93,25 @@ def encode_layout(q: np.ndarray, z: np.ndarray, layout: int):
     raise ValueError(f"unknown layout {layout}")
 
 
+def quantise_fp8_recipe(W: np.ndarray, group: int):
+    """FP8 (E4M3, finite-only) weight recipe: per column and K-group s = fp16(max|w| / 448) (1.0 if that is 0),
+    q = nearest FP8 code of w / s (fp32 division, round-to-nearest-even), written with PyTorch's CPU float8 type.
+    -> (q uint8 [K,N] codes, s float16 [K/g,N])."""
+    import torch
+    W = np.ascontiguousarray(W, dtype=np.float32)
+    K, N = W.shape
+    Wg = W.reshape(K // group, group, N)
+    s32 = np.abs(Wg).max(axis=1) / np.float32(448.0)
+    s16 = s32.astype(np.float16)
+    sf = s16.astype(np.float32)
+    bad = ~(sf > 0) | np.isinf(sf)
+    sf = np.where(bad, np.float32(1.0), sf).astype(np.float32)
+    s16 = np.where(bad, np.float16(1.0), s16).astype(np.float16)
+    r = np.clip(Wg / sf[:, None, :], -448.0, 448.0).astype(np.float32)
+    q = torch.from_numpy(r).to(torch.float8_e4m3fn).view(torch.uint8).numpy()
+    return q.reshape(K, N), s16
+
+
 def pack_interchange8(q: np.ndarray) -> np.ndarray:
     """8-bit codes q uint8 [K,N] -> uint32 [K,N/4], byte t of word (k,j) = q[k][4j+t] (the layout tm_pack_w8 accepts)."""
     K, N = q.shape
