@@ -111,6 +111,15 @@ TM_API tm_packed_w4* tm_pack_w4_layout(const void* qweight, const uint16_t* scal
  */
 TM_API tm_packed_w4* tm_pack_w8(const uint32_t* qweight, const uint16_t* scales, const uint16_t* zeros, int K, int N,
                                 int group, tm_stream stream);
+/*
+ * FP8 weights (the paper's evaluation includes an FP8 model, Sec. 5.3): the 8-bit codes are numbers of the OCP FP8 E4M3
+ * format (finite-only: bias 7, largest value 448, S.1111.111 = NaN) and
+ *     dequant(Wq)[k][n] = fp8(q[k][n]) * s[k/group][n]          (no zero-point).
+ * qweight u32 [K][N/4] as for tm_pack_w8, scales fp16 [K/group][N].  Same packed layout, same kernels restriction
+ * (decode kernels; M > 64 in slices of 64 rows), same supporting calls as tm_pack_w8.  NaN codes propagate.
+ */
+TM_API tm_packed_w4* tm_pack_w8_fp8(const uint32_t* qweight, const uint16_t* scales, int K, int N, int group,
+                                    tm_stream stream);
 /* Width of the handle's weight codes: 4 or 8 (negative status on error). */
 TM_API int tm_packed_bits(const tm_packed_w4* packed);
 

@@ -44,6 +44,8 @@ def load_library():
     lib.tm_pack_w4_on.argtypes = [vp, vp, vp, i, i, i, vp]
     lib.tm_pack_w8.restype = vp
     lib.tm_pack_w8.argtypes = [vp, vp, vp, i, i, i, vp]
+    lib.tm_pack_w8_fp8.restype = vp
+    lib.tm_pack_w8_fp8.argtypes = [vp, vp, i, i, i, vp]
     lib.tm_packed_bits.restype = i
     lib.tm_packed_bits.argtypes = [vp]
     lib.tm_group_experts.restype = vp
@@ -166,6 +168,21 @@ def tm_pack_w8(qweight, scales, zeros, K: int, N: int, group: int, stream=None) 
     zptr = None if zeros is None else _dev_ptr(zeros, torch.float16, "zeros")
     h = lib.tm_pack_w8(_dev_ptr(qweight, torch.int32, "qweight"), _dev_ptr(scales, torch.float16, "scales"), zptr,
                        K, N, group, _stream_ptr(stream))
+    if not h:
+        raise TmError(-1, tm_last_error())
+    p = PackedW4(h, K, N, min(group, 128))
+    p.bits = 8
+    return p
+
+
+def tm_pack_w8_fp8(qweight, scales, K: int, N: int, group: int, stream=None) -> PackedW4:
+    """FP8 E4M3 codes: qweight int32 [K, N/4] (byte t = column 4j+t), scales float16 [K/group, N] -> PackedW4."""
+    import torch
+    lib = load_library()
+    if tuple(qweight.shape) != (K, N // 4) or tuple(scales.shape) != (K // group, N):
+        raise ValueError("tensor shapes do not match K, N, group")
+    h = lib.tm_pack_w8_fp8(_dev_ptr(qweight, torch.int32, "qweight"), _dev_ptr(scales, torch.float16, "scales"),
+                           K, N, group, _stream_ptr(stream))
     if not h:
         raise TmError(-1, tm_last_error())
     p = PackedW4(h, K, N, min(group, 128))

@@ -94,7 +94,8 @@ int ensure_workspace(int dev)
 struct tm_packed_w4 {
     uint32_t magic;
     int K, N, group, device;
-    int bits;          // width of the weight codes: 4, or 8 (tm_pack_w8)
+    int bits;          // width of the weight codes: 4, or 8 (tm_pack_w8, tm_pack_w8_fp8)
+    bool fp8;          // the 8-bit codes are FP8 E4M3 numbers, not integers
     uint32_t* w;       // K*N/8 words
     uint32_t* sz;      // (K/group)*N words
     size_t w_bytes, sz_bytes;
@@ -354,7 +355,7 @@ int run_gemm(const uint16_t* X, const tm_packed_w4* h, uint16_t* Y, int M, void*
     p.tiles_m = pl.tiles_m;
     p.tiles_n = pl.tiles_n;
     p.strips = pl.strips;
-    hipError_t e = h->bits == 8 ? launch_skinny_w8(p, pl, h->group, stream)
+    hipError_t e = h->bits == 8 ? (h->fp8 ? launch_skinny_f8(p, pl, h->group, stream) : launch_skinny_w8(p, pl, h->group, stream))
                    : is_skinny(pl.variant) ? launch_skinny(p, pl, h->group, stream)
                                            : launch_tile(p, pl, h->group, stream);
     if (e != hipSuccess) return fail_hip(e, "kernel launch");
@@ -370,7 +371,7 @@ using namespace tmw4;
 extern "C" {
 
 static tm_packed_w4* pack_impl(const void* qweight, const uint16_t* scales, const void* zeros, int K, int N, int group,
-                        int layout, int bits, tm_stream stream)
+                               int layout, int bits, bool fp8, tm_stream stream)
 {
     if (layout != TM_LAYOUT_N8 && layout != TM_LAYOUT_N8_INTERLEAVED && layout != TM_LAYOUT_K8) {
         fail(TM_EINVAL, "unknown layout %d", layout);
@@ -412,6 +413,7 @@ static tm_packed_w4* pack_impl(const void* qweight, const uint16_t* scales, cons
     h->group = group;
     h->device = dev;
     h->bits = bits;
+    h->fp8 = fp8;
     h->w_bytes = (size_t)K * N * bits / 8;
     h->sz_bytes = (size_t)(K / group) * N * 4;
     hipError_t e = hipMalloc((void**)&h->w, h->w_bytes);
@@ -427,7 +429,7 @@ static tm_packed_w4* pack_impl(const void* qweight, const uint16_t* scales, cons
     e = bits == 4 ? launch_repack((const uint32_t*)qweight, scales, zeros, h->w, h->sz, K, N, caller_group, layout,
                                   (hipStream_t)stream)
                   : launch_repack8((const uint32_t*)qweight, scales, (const uint16_t*)zeros, h->w, h->sz, K, N,
-                                   caller_group, (hipStream_t)stream);
+                                   caller_group, fp8, (hipStream_t)stream);
     if (e != hipSuccess) {
         fail_hip(e, "repack launch");
         (void)hipFree(h->w);
@@ -441,13 +443,18 @@ static tm_packed_w4* pack_impl(const void* qweight, const uint16_t* scales, cons
 tm_packed_w4* tm_pack_w4_layout(const void* qweight, const uint16_t* scales, const void* zeros, int K, int N,
                                 int group, int layout, tm_stream stream)
 {
-    return pack_impl(qweight, scales, zeros, K, N, group, layout, 4, stream);
+    return pack_impl(qweight, scales, zeros, K, N, group, layout, 4, false, stream);
 }
 
 tm_packed_w4* tm_pack_w8(const uint32_t* qweight, const uint16_t* scales, const uint16_t* zeros, int K, int N,
                          int group, tm_stream stream)
 {
-    return pack_impl(qweight, scales, zeros, K, N, group, TM_LAYOUT_N8, 8, stream);
+    return pack_impl(qweight, scales, zeros, K, N, group, TM_LAYOUT_N8, 8, false, stream);
+}
+
+tm_packed_w4* tm_pack_w8_fp8(const uint32_t* qweight, const uint16_t* scales, int K, int N, int group, tm_stream stream)
+{
+    return pack_impl(qweight, scales, nullptr, K, N, group, TM_LAYOUT_N8, 8, true, stream);
 }
 
 tm_packed_w4* tm_pack_w4_on(const uint32_t* qweight, const uint16_t* scales, const uint16_t* zeros, int K, int N,

@@ -159,6 +159,21 @@ __device__ __forceinline__ f16x8 dequant8_w8(uint32_t w0, uint32_t w1, const Gro
     return f16x8{r0.x, r0.y, r1.x, r1.y, r2.x, r2.y, r3.x, r3.y};
 }
 
+// Weight formats of the decode kernels' BITS parameter: 4-bit and 8-bit integer codes, and FP8 (OCP E4M3) codes,
+// which share the 8-bit packed layout and need neither a conversion bias nor a zero-point.
+constexpr int kFmtInt4 = 4, kFmtInt8 = 8, kFmtFp8 = 18;
+
+// Eight FP8 E4M3 codes -> eight fp16 values (every E4M3 value is an fp16 value, so the conversion is exact):
+// gfx950 converts two codes per instruction (v_cvt_scalef32_pk_f16_fp8 with scale 1).
+__device__ __forceinline__ f16x8 cvt8_fp8(uint32_t w0, uint32_t w1)
+{
+    f16x2 r0 = __builtin_amdgcn_cvt_scalef32_pk_f16_fp8(w0, 1.0f, false);
+    f16x2 r1 = __builtin_amdgcn_cvt_scalef32_pk_f16_fp8(w0, 1.0f, true);
+    f16x2 r2 = __builtin_amdgcn_cvt_scalef32_pk_f16_fp8(w1, 1.0f, false);
+    f16x2 r3 = __builtin_amdgcn_cvt_scalef32_pk_f16_fp8(w1, 1.0f, true);
+    return f16x8{r0.x, r0.y, r1.x, r1.y, r2.x, r2.y, r3.x, r3.y};
+}
+
 // D = A(16x32) * B(32x16) + C on the matrix cores.  Lane l supplies row l%16 of A and column l%16 of B, each
 // with the eight k-values 8*(l/16) .. 8*(l/16)+7; it receives D[4*(l/16) + r][l%16] in c[r].
 __device__ __forceinline__ f32x4 mfma16x16x32(f16x8 a, f16x8 b, f32x4 c)

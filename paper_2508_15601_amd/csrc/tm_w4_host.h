@@ -74,7 +74,7 @@ struct Plan {
 hipError_t launch_repack(const uint32_t* qweight, const uint16_t* scales, const void* zeros, uint32_t* w_out,
                          uint32_t* sz_out, int K, int N, int group, int layout, hipStream_t stream);
 hipError_t launch_repack8(const uint32_t* qweight, const uint16_t* scales, const uint16_t* zeros, uint32_t* w_out,
-                          uint32_t* sz_out, int K, int N, int group, hipStream_t stream);
+                          uint32_t* sz_out, int K, int N, int group, bool fp8, hipStream_t stream);
 hipError_t launch_unpack(const uint32_t* w, const uint32_t* sz, uint32_t* qweight_out, uint16_t* scales_out,
                          uint16_t* zeros_out, int K, int N, int group, hipStream_t stream);
 hipError_t launch_copy(void* dst, const void* src, size_t bytes, hipStream_t stream);
@@ -82,6 +82,7 @@ hipError_t launch_read(const void* src, size_t bytes, void* sink, hipStream_t st
 
 hipError_t launch_skinny(const GemmParams& p, const Plan& plan, int group, hipStream_t stream);
 hipError_t launch_skinny_w8(const GemmParams& p, const Plan& plan, int group, hipStream_t stream);
+hipError_t launch_skinny_f8(const GemmParams& p, const Plan& plan, int group, hipStream_t stream);
 hipError_t launch_skinny_grouped(const GroupedParams& gp, int variant, int experts, int group, hipStream_t stream);
 hipError_t launch_tile_grouped(const GroupedParams& gp, int variant, int experts, int group, hipStream_t stream);
 hipError_t launch_tile(const GemmParams& p, const Plan& plan, int group, hipStream_t stream);

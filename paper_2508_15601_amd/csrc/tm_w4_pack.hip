@@ -220,7 +220,7 @@ hipError_t launch_repack(const uint32_t* qweight, const uint16_t* scales, const 
 }
 
 hipError_t launch_repack8(const uint32_t* qweight, const uint16_t* scales, const uint16_t* zeros, uint32_t* w_out,
-                          uint32_t* sz_out, int K, int N, int group, hipStream_t stream)
+                          uint32_t* sz_out, int K, int N, int group, bool fp8, hipStream_t stream)
 {
     const int stored = group > 128 ? 128 : group, rep = group / stored;
     const int NT = N / kUnitN, G = K / stored;
@@ -228,7 +228,7 @@ hipError_t launch_repack8(const uint32_t* qweight, const uint16_t* scales, const
     hipLaunchKernelGGL(repack_w8_kernel, grid, dim3(256), 0, stream, qweight, w_out, K, N);
     size_t total = (size_t)G * N;
     hipLaunchKernelGGL(repack_sz_kernel<0>, dim3((unsigned)((total + 255) / 256)), dim3(256), 0, stream, scales,
-                       (const void*)zeros, sz_out, G, N, rep, 0x5800u);
+                       (const void*)zeros, sz_out, G, N, rep, fp8 ? 0u : 0x5800u);   // FP8 codes carry no zero-point
     return hipGetLastError();
 }
 

@@ -14,7 +14,7 @@ template <int BITS, int GPU>
 struct UnitShape {
     static constexpr int T = BITS == 4 ? 4 : 2;
     static constexpr int GU = BITS == 4 ? GPU : (GPU >= 2 ? GPU / 2 : 1);
-    static constexpr int SZDIV = (BITS == 8 && GPU == 1) ? 2 : 1;
+    static constexpr int SZDIV = (BITS != 4 && GPU == 1) ? 2 : 1;
 };
 
 template <int TM, int NTW, int GU, int T>
@@ -105,8 +105,15 @@ __device__ __forceinline__ void compute_stage(const Stage<TM, NTW, GU, T>& st, f
 #pragma unroll
             for (int t = 0; t < T; ++t) {
                 f16x8 b;
-                if constexpr (BITS == 4) b = dequant8(st.wq[j][t], gc[t / TG], mg);
-                else b = dequant8_w8(st.wq[j][2 * t], st.wq[j][2 * t + 1], gc[t / TG]);
+                if constexpr (BITS == kFmtInt4) {
+                    b = dequant8(st.wq[j][t], gc[t / TG], mg);
+                } else if constexpr (BITS == kFmtInt8) {
+                    b = dequant8_w8(st.wq[j][2 * t], st.wq[j][2 * t + 1], gc[t / TG]);
+                } else {                           // FP8: exact conversion, one rounded multiply by the scale
+                    const f16x8 v = cvt8_fp8(st.wq[j][2 * t], st.wq[j][2 * t + 1]);
+                    const _Float16 sc = gc[t / TG].s2.x;
+                    b = v * f16x8{sc, sc, sc, sc, sc, sc, sc, sc};
+                }
 #pragma unroll
                 for (int mt = 0; mt < TM; ++mt)
                     acc[mt][j] = mfma16x16x32(__builtin_bit_cast(f16x8, st.xf[mt][t]), b, acc[mt][j]);
@@ -119,7 +126,7 @@ __device__ __forceinline__ void compute_stage(const Stage<TM, NTW, GU, T>& st, f
 #pragma unroll
         for (int g = 0; g < GU; ++g) {
             const f16x2 szp = as_f16x2(st.sz[j][g]);
-            const f16x8 cancel = BITS == 4 ? bias_cancel8(szp.y) : bias_cancel8_w8(szp.y);
+            const f16x8 cancel = BITS == kFmtInt4 ? bias_cancel8(szp.y) : bias_cancel8_w8(szp.y);   // unused for FP8
             const float scale = (float)szp.x;
             f32x4 part[TM];
 #pragma unroll
@@ -128,13 +135,14 @@ __device__ __forceinline__ void compute_stage(const Stage<TM, NTW, GU, T>& st, f
             for (int tt = 0; tt < TG; ++tt) {
                 const int t = g * TG + tt;
                 f16x8 b;
-                if constexpr (BITS == 4) b = biased8(st.wq[j][t], mg);
-                else b = biased8_w8(st.wq[j][2 * t], st.wq[j][2 * t + 1]);
+                if constexpr (BITS == kFmtInt4) b = biased8(st.wq[j][t], mg);
+                else if constexpr (BITS == kFmtInt8) b = biased8_w8(st.wq[j][2 * t], st.wq[j][2 * t + 1]);
+                else b = cvt8_fp8(st.wq[j][2 * t], st.wq[j][2 * t + 1]);
 #pragma unroll
                 for (int mt = 0; mt < TM; ++mt) {
                     const f16x8 a = __builtin_bit_cast(f16x8, st.xf[mt][t]);
                     part[mt] = mfma16x16x32(a, b, part[mt]);
-                    part[mt] = mfma16x16x32(a, cancel, part[mt]);
+                    if constexpr (BITS != kFmtFp8) part[mt] = mfma16x16x32(a, cancel, part[mt]);
                 }
             }
 #pragma unroll
@@ -367,6 +375,24 @@ hipError_t launch_cfg(const GemmParams& p, const Plan& plan, int group, hipStrea
         default: return hipErrorInvalidValue;
     }
     return hipGetLastError();
+}
+
+// The strip widths the dispatcher uses for the 8-bit formats (BITS = kFmtInt8 or kFmtFp8).
+template <int BITS>
+hipError_t launch_skinny_8bit(const GemmParams& p, const Plan& plan, int group, hipStream_t stream)
+{
+    const bool w16 = plan.block > 512;
+    switch (plan.variant) {
+        case kSkinny16x16: return w16 ? launch_cfg<1, 1, 3, 2, 16, BITS>(p, plan, group, stream) : launch_cfg<1, 1, 4, 4, 8, BITS>(p, plan, group, stream);
+        case kSkinny16x32: return w16 ? launch_cfg<1, 2, 2, 2, 16, BITS>(p, plan, group, stream) : launch_cfg<1, 2, 4, 4, 8, BITS>(p, plan, group, stream);
+        case kSkinny16x48: return w16 ? launch_cfg<1, 3, 2, 2, 16, BITS>(p, plan, group, stream) : launch_cfg<1, 3, 3, 3, 8, BITS>(p, plan, group, stream);
+        case kSkinny16x64: return w16 ? launch_cfg<1, 4, 2, 1, 16, BITS>(p, plan, group, stream) : launch_cfg<1, 4, 2, 2, 8, BITS>(p, plan, group, stream);
+        case kSkinny16x96: return w16 ? launch_cfg<1, 6, 1, 1, 16, BITS>(p, plan, group, stream) : launch_cfg<1, 6, 3, 2, 8, BITS>(p, plan, group, stream);
+        case kSkinny16x128: return w16 ? launch_cfg<1, 8, 1, 1, 16, BITS>(p, plan, group, stream) : launch_cfg<1, 8, 2, 2, 8, BITS>(p, plan, group, stream);
+        case kSkinny32x64: return w16 ? hipErrorInvalidValue : launch_cfg<2, 4, 2, 2, 8, BITS>(p, plan, group, stream);
+        case kSkinny64x64: return w16 ? hipErrorInvalidValue : launch_cfg<4, 4, 2, 1, 8, BITS>(p, plan, group, stream);
+        default: return hipErrorInvalidValue;
+    }
 }
 
 }  // namespace

@@ -627,3 +627,80 @@ def test_w8_quantised_weights_symmetric_and_per_channel(tm, oracle):
     with pytest.raises(tm.TmError):
         tm.tm_group_experts([packed])
     packed.close()
+
+
+# ------------------------------------------------------------------ FP8 (E4M3) weight codes
+
+def _fp8_case(rng, K, N, g):
+    q = rng.integers(0, 256, (K, N), dtype=np.uint8)
+    q[(q & 0x7F) == 0x7F] = 0x30                                          # no NaN codes
+    s = rng.uniform(0.0005, 0.005, (K // g, N)).astype(np.float16)
+    return q, s
+
+
+def test_fp8_every_code_converts_exactly(tm, oracle):
+    """One-hot rows against a weight matrix that holds all 254 finite codes: Y must be fp16(fp8(q) * s), bit for bit,
+    for the bias-free MFMA route (16- and 32-row kernels) and the ALU route (64-row kernel)."""
+    _say("fp8 all codes")
+    K, N, g = 256, 16, 128
+    codes = np.array([c for c in range(256) if (c & 0x7F) != 0x7F], np.uint8)
+    q = np.zeros((K, N), np.uint8)
+    q[:len(codes), :] = codes[:, None]
+    s = np.array([[1.0, 0.5, 0.25, 3.0, 0.0078125, 1.5, 0.001, 0.37] * 2] * (K // g), np.float16)
+    packed = tm.tm_pack_w8_fp8(gu.to_dev(wl.pack_interchange8(q)), gu.to_dev(s), K, N, g)
+    wbuf, szbuf = tm.tm_packed_raw(packed)
+    q2, s2, z2 = oracle.unpack_packed(wbuf, szbuf, K, N, g, bits=8)
+    assert np.array_equal(q2, q) and np.array_equal(s2.view(np.uint16), s.view(np.uint16)) and not z2.view(np.uint16).any()
+    What = oracle.dequant_fp8(q, s, g)
+    for variant in (0, 1, 2, 4, 19):
+        tm.tm_set_variant(variant, 0)
+        try:
+            for k0 in range(0, K, 16):
+                X = np.zeros((16, K), np.float16)
+                X[np.arange(16), k0 + np.arange(16)] = 1.0
+                Y = gu.gemm(packed, X)
+                # numeric equality: a sum that starts at +0 returns +0 for the code -0, on both sides
+                assert np.array_equal(Y, What[k0:k0 + 16].astype(np.float16)), (variant, k0)
+        finally:
+            tm.tm_set_variant(-1, 0)
+    packed.close()
+
+
+@pytest.mark.parametrize("g", [32, 64, 128])
+@pytest.mark.parametrize("M,K,N,variant,split", [
+    (1, 1024, 528, -1, 0), (8, 768, 4112, -1, 0), (16, 2048, 1040, -1, 0), (11, 1280, 336, 1, 2), (16, 1024, 1552, 14, 0),
+    (6, 896, 1552, 15, 0), (16, 640, 2064, 16, 0), (29, 1024, 1040, -1, 0), (64, 768, 1040, 19, 3), (150, 512, 272, -1, 0)])
+def test_fp8_gemm_against_oracle(tm, oracle, M, K, N, variant, split, g):
+    _say(f"fp8 gemm M={M} K={K} N={N} g={g} variant={variant} split={split}")
+    rng = np.random.default_rng(M + K + N + g + 1)
+    q, s = _fp8_case(rng, K, N, g)
+    # codes are uniform over the exponent range, so a few huge weights dominate: scale X down to keep fp16 outputs finite
+    X = (rng.standard_normal((M, K)) * 0.25).astype(np.float16)
+    packed = tm.tm_pack_w8_fp8(gu.to_dev(wl.pack_interchange8(q)), gu.to_dev(s), K, N, g)
+    tm.tm_set_variant(variant, split)
+    try:
+        for waves in ((0, 8, 16) if M <= 16 else (0,)):
+            tm.tm_set_launch(waves, 0)
+            ok, worst, fro = acceptance(gu.gemm(packed, X), oracle.gemm_fp8(X, q, s, g))
+            assert ok, (waves, worst, fro)
+    finally:
+        tm.tm_set_variant(-1, 0)
+        tm.tm_set_launch(0, 0)
+    packed.close()
+
+
+def test_fp8_quantised_weights_end_to_end(tm, oracle):
+    _say("fp8 recipe end to end")
+    rng = np.random.default_rng(99)
+    K, N, M = 1024, 528, 12
+    W = (0.02 * rng.standard_normal((K, N))).astype(np.float32)
+    X = rng.standard_normal((M, K)).astype(np.float16)
+    for g in (128, K):
+        q, s = wl.quantise_fp8_recipe(W, g)
+        packed = tm.tm_pack_w8_fp8(gu.to_dev(wl.pack_interchange8(q)), gu.to_dev(s), K, N, g)
+        Yref = oracle.gemm_fp8(X, q, s, g)
+        ok, worst, fro = acceptance(gu.gemm(packed, X), Yref)
+        assert ok, (g, worst, fro)
+        exact = X.astype(np.float64) @ W.astype(np.float64)
+        assert np.linalg.norm(Yref.astype(np.float64) - exact) / np.linalg.norm(exact) < 5e-2     # 3 mantissa bits
+        packed.close()
