@@ -255,10 +255,10 @@ def moe_table(tm, torch, names, tokens=(1, 4, 16, 64), iters=40, group=128, only
 
 
 def w8_table(tm, torch, wl, iters=100):
-    """W8A16 decode: the decode and MLP-decode layer shapes with 8-bit weight codes (random codes; timing does not
-    depend on their values), same timing method as the 4-bit sweep."""
+    """8-bit weights at decode sizes: the decode and MLP-decode layer shapes with int8 codes (W8A16) and with FP8 E4M3
+    codes (random codes; timing does not depend on their values), same timing method as the 4-bit sweep."""
     rows = []
-    for name, Ms in WORKLOADS["decode"] + WORKLOADS["mlp_decode"]:
+    for fmt, (name, Ms) in [(f, l) for f in ("int8", "fp8") for l in WORKLOADS["decode"] + WORKLOADS["mlp_decode"]]:
         c = wl.case_by_name(name)
         G = c.K // c.group
         wbytes = c.K * c.N + 4 * G * c.N
@@ -268,7 +268,11 @@ def w8_table(tm, torch, wl, iters=100):
             qw = torch.randint(-2 ** 31, 2 ** 31 - 1, (c.K, c.N // 4), dtype=torch.int32, device="cuda")
             s = (torch.rand((G, c.N), device="cuda") * 0.002 + 0.0001).to(torch.float16)
             z = torch.randint(0, 256, (G, c.N), device="cuda").to(torch.float16)
-            packed.append(tm.tm_pack_w8(qw, s, z, c.K, c.N, c.group))
+            if fmt == "int8":
+                packed.append(tm.tm_pack_w8(qw, s, z, c.K, c.N, c.group))
+            else:
+                qw &= -16843010                      # 0xFEFEFEFE: no byte is a NaN code
+                packed.append(tm.tm_pack_w8_fp8(qw, s, c.K, c.N, c.group))
         del qw, s, z
         for M in Ms:
             X = [torch.randn((M, c.K), device="cuda").to(torch.float16) for _ in range(4)]
@@ -284,10 +288,10 @@ def w8_table(tm, torch, wl, iters=100):
             t = ev_ms / iters * 1e-3
             B = wl.algorithmic_bytes(M, c.K, c.N, c.group, bits=8)
             plan = tm.tm_get_plan(packed[0], M)
-            rows.append({"layer": c.name.rsplit("_M", 1)[0], "M": M, "K": c.K, "N": c.N, "group": c.group, "bits": 8,
+            rows.append({"layer": c.name.rsplit("_M", 1)[0], "M": M, "K": c.K, "N": c.N, "group": c.group, "bits": 8, "format": fmt,
                          "us": t * 1e6, "GBps": B / t / 1e9, "hbm_frac": B / t / 1e9 / HBM_PEAK_GBPS,
                          "variant": plan["name"], "split_k": plan["split_k"], "grid": plan["grid"], "block": plan["block"]})
-            log(f"W8A16 {rows[-1]['layer']:14s} M={M:3d} K={c.K:6d} N={c.N:6d} {t * 1e6:8.2f} us {B / t / 1e9:7.0f} GB/s "
+            log(f"{fmt:4s} {rows[-1]['layer']:14s} M={M:3d} K={c.K:6d} N={c.N:6d} {t * 1e6:8.2f} us {B / t / 1e9:7.0f} GB/s "
                 f"({100 * B / t / 1e9 / HBM_PEAK_GBPS:4.1f} % HBM)  {plan['name']} split {plan['split_k']} block {plan['block']}")
         for p in packed:
             p.close()
