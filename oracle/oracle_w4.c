@@ -24,6 +24,9 @@
  *                     FP8 (E4M3) weight codes through the same GEMM (the paper's evaluation includes an FP8 model,
  *                     Sec. 5.3): W^[k][n] = fp8(q[k][n]) * s[k/g][n], no zero-point; the format is the published
  *                     OCP 8-bit floating point E4M3 (finite-only: bias 7, no infinities, S.1111.111 = NaN).
+ *   - orc_dequant_gidx, orc_gemm_gidx:
+ *                     the same GEMM when the K-group of a row is given by an index array instead of k / g
+ *                     (checkpoints quantised in activation order): W^[k][n] = (q[k][n] - z[gidx[k]][n]) * s[gidx[k]][n].
  *   - orc_unpack_packed:
  *                     inverse index map of the library's MFMA-fragment-ordered buffer (the gfx950 analogue
  *                     of the packed fragment store of paper Sec. 4.1 steps (iii)-(iv)); written from the
@@ -303,6 +306,43 @@ ORC_API int orc_unpack_packed8(const uint32_t* wbuf, const uint32_t* szbuf, int 
 }
 
 /* ---------------------------------------------------------------- dequantise and multiply */
+
+/* rows carry their group index explicitly: gidx[k] in [0, G) */
+ORC_API int orc_dequant_gidx(const uint8_t* q, const uint16_t* s, const uint16_t* z, const int32_t* gidx, int K, int N,
+                             int G, double* What)
+{
+    if (!q || !s || !z || !gidx || !What || K <= 0 || N <= 0 || G <= 0) return -1;
+    for (int k = 0; k < K; ++k) {
+        if (gidx[k] < 0 || gidx[k] >= G) return -2;
+        for (int n = 0; n < N; ++n) {
+            size_t gi = (size_t)gidx[k] * N + n;
+            What[(size_t)k * N + n] = ((double)q[(size_t)k * N + n] - orc_fp16_to_double(z[gi])) * orc_fp16_to_double(s[gi]);
+        }
+    }
+    return 0;
+}
+
+ORC_API int orc_gemm_gidx(const uint16_t* X, int M, const uint8_t* q, const uint16_t* s, const uint16_t* z,
+                          const int32_t* gidx, int K, int N, int G, uint16_t* Y)
+{
+    if (!X || !q || !s || !z || !gidx || !Y || M < 0 || K <= 0 || N <= 0 || G <= 0) return -1;
+    for (int k = 0; k < K; ++k)
+        if (gidx[k] < 0 || gidx[k] >= G) return -2;
+#ifdef _OPENMP
+#pragma omp parallel for schedule(static)
+#endif
+    for (int n = 0; n < N; ++n)
+        for (int m = 0; m < M; ++m) {
+            double acc = 0.0;
+            for (int k = 0; k < K; ++k) {
+                size_t gi = (size_t)gidx[k] * N + n;
+                double w = ((double)q[(size_t)k * N + n] - orc_fp16_to_double(z[gi])) * orc_fp16_to_double(s[gi]);
+                acc += orc_fp16_to_double(X[(size_t)m * K + k]) * w;
+            }
+            Y[(size_t)m * N + n] = orc_double_to_fp16(acc);
+        }
+    return 0;
+}
 
 /* OCP FP8 E4M3, finite-only: sign(1) exponent(4, bias 7) mantissa(3); exponent 0 is subnormal (m/8 * 2^-6);
  * exponent 15 is an ordinary binade except mantissa 7, which is NaN.  Largest finite value 1.75 * 2^8 = 448. */

@@ -54,6 +54,8 @@ def _load():
         lib.orc_quantise_fp8.argtypes = [vp, c.c_int, c.c_int, c.c_int, vp, vp]
         lib.orc_dequant_fp8.argtypes = [vp, vp, c.c_int, c.c_int, c.c_int, vp]
         lib.orc_gemm_fp8.argtypes = [vp, c.c_int, vp, vp, c.c_int, c.c_int, c.c_int, vp, vp]
+        lib.orc_dequant_gidx.argtypes = [vp, vp, vp, vp, c.c_int, c.c_int, c.c_int, vp]
+        lib.orc_gemm_gidx.argtypes = [vp, c.c_int, vp, vp, vp, vp, c.c_int, c.c_int, c.c_int, vp]
         lib.orc_unpack_packed.argtypes = [vp, vp, c.c_int, c.c_int, c.c_int, vp, vp, vp]
         lib.orc_dequant.argtypes = [vp, vp, vp, c.c_int, c.c_int, c.c_int, vp]
         lib.orc_gemm.argtypes = [vp, c.c_int, vp, vp, vp, c.c_int, c.c_int, c.c_int, vp, vp]
@@ -213,6 +215,27 @@ def gemm(X: np.ndarray, q: np.ndarray, s: np.ndarray, z: np.ndarray, group: int,
     _check(_load().orc_gemm(_ptr(X), M, _ptr(q), _ptr(s), _ptr(z), K, N, group, _ptr(Y),
                             _ptr(Yd) if want_fp64 else None), "gemm")
     return (Y.view(np.float16), Yd) if want_fp64 else Y.view(np.float16)
+
+
+def dequant_gidx(q: np.ndarray, s: np.ndarray, z: np.ndarray, g_idx: np.ndarray) -> np.ndarray:
+    """(q - z[g_idx[k]]) * s[g_idx[k]]: the K-group of row k is g_idx[k] (activation-order checkpoints)."""
+    q = _as(q, np.uint8); s = _as(s, np.uint16); z = _as(z, np.uint16); g_idx = _as(g_idx, np.int32)
+    K, N = q.shape
+    out = np.empty((K, N), np.float64)
+    _check(_load().orc_dequant_gidx(_ptr(q), _ptr(s), _ptr(z), _ptr(g_idx), K, N, s.shape[0], _ptr(out)), "dequant_gidx")
+    return out
+
+
+def gemm_gidx(X: np.ndarray, q: np.ndarray, s: np.ndarray, z: np.ndarray, g_idx: np.ndarray) -> np.ndarray:
+    """Y = fp16(X @ dequant_gidx(q, s, z, g_idx)), fp64 accumulation with k ascending in the checkpoint's row order."""
+    X = _as(X, np.uint16); q = _as(q, np.uint8); s = _as(s, np.uint16); z = _as(z, np.uint16)
+    g_idx = _as(g_idx, np.int32)
+    M, K = X.shape
+    N = q.shape[1]
+    Y = np.empty((M, N), np.uint16)
+    _check(_load().orc_gemm_gidx(_ptr(X), M, _ptr(q), _ptr(s), _ptr(z), _ptr(g_idx), K, N, s.shape[0], _ptr(Y)),
+           "gemm_gidx")
+    return Y.view(np.float16)
 
 
 def fp8e4m3_table() -> np.ndarray:

@@ -528,3 +528,29 @@ def test_fp8_gemm_against_numpy(oracle):
     X1 = np.zeros((M, K), np.float16)
     X1[np.arange(M), [3, 40, 77, 100, 127]] = 1.0
     assert np.array_equal(oracle.gemm_fp8(X1, q, s, g), What[[3, 40, 77, 100, 127]].astype(np.float16))
+
+
+# ------------------------------------------------------------------ explicit group index (activation order)
+
+def test_gidx_forms_against_plain_forms_and_numpy(oracle):
+    rng = np.random.default_rng(14)
+    K, N, g, M = 96, 16, 32, 4
+    q = rng.integers(0, 16, (K, N), dtype=np.uint8)
+    s = rng.uniform(0.01, 0.05, (K // g, N)).astype(np.float16)
+    z = rng.integers(0, 16, (K // g, N)).astype(np.float16)
+    X = rng.standard_normal((M, K)).astype(np.float16)
+    plain = (np.arange(K) // g).astype(np.int32)
+    assert np.array_equal(oracle.dequant_gidx(q, s, z, plain), oracle.dequant(q, s, z, g))
+    assert np.array_equal(oracle.gemm_gidx(X, q, s, z, plain), oracle.gemm(X, q, s, z, g))
+    gi = wl.draw_act_order(K, g, rng)
+    assert sorted(np.bincount(gi).tolist()) == [g] * (K // g) and not np.array_equal(gi, plain)
+    What = (q.astype(np.float64) - z.astype(np.float64)[gi]) * s.astype(np.float64)[gi]          # numpy gather
+    assert np.array_equal(oracle.dequant_gidx(q, s, z, gi), What)
+    assert np.allclose(oracle.gemm_gidx(X, q, s, z, gi).astype(np.float64), X.astype(np.float64) @ What, rtol=2e-3, atol=1e-3)
+    # sorting the rows by group (and the columns of X the same way) gives the plain grouped problem with the same Y
+    perm = np.argsort(gi, kind="stable")
+    Y1 = oracle.gemm_gidx(X, q, s, z, gi).astype(np.float64)
+    Y2 = oracle.gemm(np.ascontiguousarray(X[:, perm]), np.ascontiguousarray(q[perm]), s, z, g).astype(np.float64)
+    assert np.allclose(Y1, Y2, rtol=2e-3, atol=2e-3)
+    with pytest.raises(ValueError):
+        oracle.gemm_gidx(X, q, s, z, np.full(K, K // g, np.int32))                                # index out of range

@@ -120,6 +120,14 @@ def pack_interchange8(q: np.ndarray) -> np.ndarray:
     return np.bitwise_or.reduce(q32 << shifts, axis=2).astype(np.uint32)
 
 
+def draw_act_order(K: int, group: int, rng: np.random.Generator) -> np.ndarray:
+    """Group index per row as an activation-order (act-order) checkpoint stores it: a random permutation of the rows is
+    cut into consecutive groups, so every group has exactly ``group`` rows scattered over K.  int32 [K]."""
+    g_idx = np.empty(K, np.int32)
+    g_idx[rng.permutation(K)] = np.arange(K, dtype=np.int32) // group
+    return g_idx
+
+
 def draw_weights(case: Case, rng: np.random.Generator) -> np.ndarray:
     W = (case.sigma * rng.standard_normal((case.K, case.N), dtype=np.float32)).astype(np.float32)
     if case.outlier_frac > 0:
