@@ -97,6 +97,21 @@ TM_API tm_packed_w4* tm_pack_w4_layout(const void* qweight, const uint16_t* scal
                                        int group, int layout, tm_stream stream);
 
 /*
+ * Activation-order checkpoints: the K-group of row k is g_idx[k] instead of k / group, i.e.
+ *     dequant(Wq)[k][n] = (q[k][n] - z[g_idx[k]][n]) * s[g_idx[k]][n].
+ * g_idx is a DEVICE array of K int32 in which every group 0 .. K/group-1 occurs exactly `group` times (anything else is
+ * TM_EINVAL).  The pack sorts the rows by group once (stable), so the online GEMM sees the ordinary layout; the row order
+ * is kept in the handle and tm_gemm_w4a16 gathers the columns of X accordingly before it multiplies (one small extra
+ * kernel).  qweight / scales / zeros / layout as for tm_pack_w4_layout.  Unlike the other pack calls this one
+ * synchronises `stream` (it reads g_idx on the host and frees a temporary) and allocates, per device, a 32 MiB buffer
+ * for the regrouped activations; a GEMM whose M*K*2 bytes exceed it runs in several passes.  With tm_gemm_w4a16_ws the
+ * regrouped activations live in the caller's workspace instead (tm_gemm_workspace_bytes includes them).  tm_unpack_w4
+ * returns the rows in packed (group-sorted) order; tm_group_experts does not take such handles.
+ */
+TM_API tm_packed_w4* tm_pack_w4_actorder(const void* qweight, const uint16_t* scales, const void* zeros,
+                                         const int32_t* g_idx, int K, int N, int group, int layout, tm_stream stream);
+
+/*
  * 8-bit weight codes (W8A16) through the same two stages; the paper presents packing and the fused GEMM as independent
  * of the weight width (Sec. 3.3, Sec. 4.1).  qweight is u32 [K][N/4], byte t (bits 8t..8t+7) of word (k, j) =
  * q[k][4j + t], codes 0..255; scales fp16 [K/group][N]; zeros fp16 [K/group][N], integer-valued in [0, 255], or NULL for

@@ -42,6 +42,8 @@ def load_library():
     lib.tm_pack_w4.argtypes = [vp, vp, vp, i, i, i]
     lib.tm_pack_w4_on.restype = vp
     lib.tm_pack_w4_on.argtypes = [vp, vp, vp, i, i, i, vp]
+    lib.tm_pack_w4_actorder.restype = vp
+    lib.tm_pack_w4_actorder.argtypes = [vp, vp, vp, vp, i, i, i, i, vp]
     lib.tm_pack_w8.restype = vp
     lib.tm_pack_w8.argtypes = [vp, vp, vp, i, i, i, vp]
     lib.tm_pack_w8_fp8.restype = vp
@@ -155,6 +157,23 @@ def tm_pack_w4(qweight, scales, zeros, K: int, N: int, group: int, stream=None) 
     """qweight int32 [K, N/8] (interchange nibble order), scales/zeros float16 [K/group, N] -> PackedW4.
     zeros=None packs symmetric weights (zero-point 8); group may be 32, 64 or a multiple of 128 dividing K."""
     return tm_pack_w4_layout(qweight, scales, zeros, K, N, group, TM_LAYOUT_N8, stream)
+
+
+def tm_pack_w4_actorder(qweight, scales, zeros, g_idx, K: int, N: int, group: int, layout: int = 2, stream=None) -> PackedW4:
+    """Activation-order checkpoint: as tm_pack_w4_layout plus g_idx int32 [K] (device), the K-group of every row."""
+    import torch
+    lib = load_library()
+    qshape = (K // 8, N) if layout == TM_LAYOUT_K8 else (K, N // 8)
+    zshape, zdtype = ((K // group, N), torch.float16) if layout == TM_LAYOUT_N8 else ((K // group, N // 8), torch.int32)
+    if tuple(qweight.shape) != qshape or tuple(scales.shape) != (K // group, N) or g_idx.numel() != K or \
+            (zeros is not None and tuple(zeros.shape) != zshape):
+        raise ValueError("tensor shapes do not match K, N, group, layout")
+    zptr = None if zeros is None else _dev_ptr(zeros, zdtype, "zeros")
+    h = lib.tm_pack_w4_actorder(_dev_ptr(qweight, torch.int32, "qweight"), _dev_ptr(scales, torch.float16, "scales"), zptr,
+                                _dev_ptr(g_idx, torch.int32, "g_idx"), K, N, group, layout, _stream_ptr(stream))
+    if not h:
+        raise TmError(-1, tm_last_error())
+    return PackedW4(h, K, N, min(group, 128))
 
 
 def tm_pack_w8(qweight, scales, zeros, K: int, N: int, group: int, stream=None) -> PackedW4:

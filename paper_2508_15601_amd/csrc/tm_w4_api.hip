@@ -17,6 +17,7 @@ namespace {
 constexpr uint32_t kMagic = 0x74573461u;              // "tW4a"
 constexpr size_t kPartialBudget = 32u << 20;          // bytes of fp32 partial sums a plan may use
 constexpr size_t kWorkspaceBytes = kCounterBytes + kPartialBudget;
+constexpr size_t kXpermBytes = 32u << 20;             // activations regrouped for activation-order handles
 constexpr int kMaxDevices = 16;
 
 thread_local char g_error[512] = "";
@@ -39,6 +40,7 @@ struct DeviceState {
     bool checked = false;
     bool supported = false;
     void* workspace = nullptr;
+    void* xperm = nullptr;     // kXpermBytes, allocated with the first activation-order handle
     int num_cu = 256;
 };
 DeviceState g_dev[kMaxDevices];
@@ -96,6 +98,7 @@ struct tm_packed_w4 {
     int K, N, group, device;
     int bits;          // width of the weight codes: 4, or 8 (tm_pack_w8, tm_pack_w8_fp8)
     bool fp8;          // the 8-bit codes are FP8 E4M3 numbers, not integers
+    int32_t* perm;     // activation-order handles: packed row i is checkpoint row perm[i] (device, K entries); else null
     uint32_t* w;       // K*N/8 words
     uint32_t* sz;      // (K/group)*N words
     size_t w_bytes, sz_bytes;
@@ -302,8 +305,11 @@ Plan make_plan(const tm_packed_w4* h, int M, int num_cu)
     return pl;
 }
 
+size_t align256(size_t v) { return (v + 255) & ~(size_t)255; }
+
+// x_regrouped: X already follows the packed row order of an activation-order handle
 int run_gemm(const uint16_t* X, const tm_packed_w4* h, uint16_t* Y, int M, void* ws, size_t ws_bytes, bool own_ws,
-             hipStream_t stream)
+             hipStream_t stream, bool x_regrouped = false)
 {
     if (!valid(h)) return fail(TM_EINVAL, "packed handle is null or invalid");
     if (M < 0 || M >= (1 << 24)) return fail(TM_EINVAL, "M = %d out of range", M);
@@ -315,12 +321,40 @@ int run_gemm(const uint16_t* X, const tm_packed_w4* h, uint16_t* Y, int M, void*
     int rc = check_device(&dev);
     if (rc != TM_OK) return rc;
     if (dev != h->device) return fail(TM_EINVAL, "handle belongs to device %d, current device is %d", h->device, dev);
+    if (h->perm && !x_regrouped) {
+        // activation-order handle: gather the columns of X into the packed row order, then multiply.  With the
+        // library's buffers the rows go through in passes that fit the regroup buffer; a caller workspace carries
+        // its own regroup area behind the split-K area of the full-size plan.
+        if (own_ws) {
+            uint16_t* xb = (uint16_t*)g_dev[dev].xperm;
+            if (!xb) return fail(TM_EINVAL, "library regroup buffer missing");
+            const int rows_max = (int)(kXpermBytes / ((size_t)h->K * 2)) > 0 ? (int)(kXpermBytes / ((size_t)h->K * 2)) : 0;
+            if (rows_max < 1) return fail(TM_EINVAL, "K = %d too large for the regroup buffer", h->K);
+            for (int m0 = 0; m0 < M; m0 += rows_max) {
+                const int rows = M - m0 < rows_max ? M - m0 : rows_max;
+                hipError_t e = launch_permute_x(X + (size_t)m0 * h->K, h->perm, xb, rows, h->K, stream);
+                if (e != hipSuccess) return fail_hip(e, "regroup launch");
+                rc = run_gemm(xb, h, Y + (size_t)m0 * h->N, rows, ws, ws_bytes, own_ws, stream, true);
+                if (rc != TM_OK) return rc;
+            }
+            return TM_OK;
+        }
+        if (!ws) return fail(TM_EINVAL, "workspace is null");
+        if ((uintptr_t)ws & 255) return fail(TM_EINVAL, "workspace must be 256-byte aligned");
+        const size_t plan_bytes = align256(make_plan(h, M, g_dev[dev].num_cu).ws_bytes);
+        const size_t need = plan_bytes + (size_t)M * h->K * 2;
+        if (ws_bytes < need) return fail(TM_EINVAL, "workspace too small: %zu < %zu", ws_bytes, need);
+        uint16_t* xb = (uint16_t*)((char*)ws + plan_bytes);
+        hipError_t e = launch_permute_x(X, h->perm, xb, M, h->K, stream);
+        if (e != hipSuccess) return fail_hip(e, "regroup launch");
+        return run_gemm(xb, h, Y, M, ws, plan_bytes, own_ws, stream, true);
+    }
     if (h->bits == 8 && M > 64) {
         // 8-bit codes have decode kernels only: larger batches go through them 64 rows at a time (stream order
         // keeps the shared workspace safe), re-reading the weights for every slice
         for (int m0 = 0; m0 < M; m0 += 64) {
             rc = run_gemm(X + (size_t)m0 * h->K, h, Y + (size_t)m0 * h->N, M - m0 < 64 ? M - m0 : 64, ws, ws_bytes,
-                          own_ws, stream);
+                          own_ws, stream, x_regrouped);
             if (rc != TM_OK) return rc;
         }
         return TM_OK;
@@ -414,6 +448,7 @@ static tm_packed_w4* pack_impl(const void* qweight, const uint16_t* scales, cons
     h->device = dev;
     h->bits = bits;
     h->fp8 = fp8;
+    h->perm = nullptr;
     h->w_bytes = (size_t)K * N * bits / 8;
     h->sz_bytes = (size_t)(K / group) * N * 4;
     hipError_t e = hipMalloc((void**)&h->w, h->w_bytes);
@@ -444,6 +479,75 @@ tm_packed_w4* tm_pack_w4_layout(const void* qweight, const uint16_t* scales, con
                                 int group, int layout, tm_stream stream)
 {
     return pack_impl(qweight, scales, zeros, K, N, group, layout, 4, false, stream);
+}
+
+tm_packed_w4* tm_pack_w4_actorder(const void* qweight, const uint16_t* scales, const void* zeros, const int32_t* g_idx,
+                                  int K, int N, int group, int layout, tm_stream stream)
+{
+    if (!g_idx || ((uintptr_t)g_idx & 3)) {
+        fail(TM_EINVAL, "g_idx is null or misaligned");
+        return nullptr;
+    }
+    if (!qweight || K <= 0 || N <= 0 || K % kUnitK || N % kUnitN || group <= 0 || K % group ||
+        (layout != TM_LAYOUT_N8 && layout != TM_LAYOUT_N8_INTERLEAVED && layout != TM_LAYOUT_K8)) {
+        fail(TM_EINVAL, "bad shape, group or layout (K = %d, N = %d, group = %d, layout = %d)", K, N, group, layout);
+        return nullptr;
+    }
+    int dev;
+    if (check_device(&dev) != TM_OK) return nullptr;
+    hipStream_t st = (hipStream_t)stream;
+    // the group indices come to the host once: the row order is fixed here, offline
+    std::vector<int32_t> gi((size_t)K), perm((size_t)K);
+    hipError_t e = hipStreamSynchronize(st);
+    if (e == hipSuccess) e = hipMemcpy(gi.data(), g_idx, (size_t)K * sizeof(int32_t), hipMemcpyDeviceToHost);
+    if (e != hipSuccess) {
+        fail_hip(e, "reading g_idx");
+        return nullptr;
+    }
+    const int G = K / group;
+    std::vector<int> fill((size_t)G, 0);
+    for (int k = 0; k < K; ++k) {
+        if (gi[k] < 0 || gi[k] >= G || fill[gi[k]] >= group) {
+            fail(TM_EINVAL, "g_idx must name each of the %d groups exactly %d times (row %d)", G, group, k);
+            return nullptr;
+        }
+        perm[(size_t)gi[k] * group + fill[gi[k]]++] = k;       // stable: rows of a group keep their order
+    }
+    {
+        std::lock_guard<std::mutex> lock(g_mutex);
+        if (!g_dev[dev].xperm) {
+            e = hipMalloc(&g_dev[dev].xperm, kXpermBytes);
+            if (e != hipSuccess) {
+                g_dev[dev].xperm = nullptr;
+                fail_hip(e, "hipMalloc(regroup buffer)");
+                return nullptr;
+            }
+        }
+    }
+    int32_t* dperm = nullptr;
+    uint32_t* tmp = nullptr;
+    e = hipMalloc((void**)&dperm, (size_t)K * sizeof(int32_t));
+    if (e == hipSuccess) e = hipMalloc((void**)&tmp, (size_t)K * N / 2);
+    if (e == hipSuccess) e = hipMemcpy(dperm, perm.data(), (size_t)K * sizeof(int32_t), hipMemcpyHostToDevice);
+    if (e == hipSuccess) e = launch_permute_rows((const uint32_t*)qweight, dperm, tmp, K, N, layout == TM_LAYOUT_K8, st);
+    tm_packed_w4* h = nullptr;
+    if (e == hipSuccess) {
+        h = pack_impl(tmp, scales, zeros, K, N, group, layout, 4, false, stream);
+        if (h) e = hipStreamSynchronize(st);               // tmp is released below
+    } else {
+        fail_hip(e, "activation-order regrouping");
+    }
+    if (tmp) (void)hipFree(tmp);
+    if (!h || e != hipSuccess) {
+        if (h) {
+            fail_hip(e, "activation-order pack");
+            tm_free_packed(h);
+        }
+        if (dperm) (void)hipFree(dperm);
+        return nullptr;
+    }
+    h->perm = dperm;
+    return h;
 }
 
 tm_packed_w4* tm_pack_w8(const uint32_t* qweight, const uint16_t* scales, const uint16_t* zeros, int K, int N,
@@ -485,8 +589,8 @@ tm_expert_group* tm_group_experts(const tm_packed_w4* const* experts, int num_ex
             fail(TM_EINVAL, "expert %d: handle is null or invalid", e);
             return nullptr;
         }
-        if (experts[e]->bits != 4) {
-            fail(TM_EUNSUPPORTED, "expert %d: grouped GEMM takes 4-bit weights only", e);
+        if (experts[e]->bits != 4 || experts[e]->perm) {
+            fail(TM_EUNSUPPORTED, "expert %d: grouped GEMM takes 4-bit weights in plain row order only", e);
             return nullptr;
         }
         if (experts[e]->K != experts[0]->K || experts[e]->N != experts[0]->N ||
@@ -602,7 +706,8 @@ size_t tm_gemm_workspace_bytes(const tm_packed_w4* packed, int M)
     }
     int dev = packed->device;
     int cu = (dev >= 0 && dev < kMaxDevices && g_dev[dev].checked) ? g_dev[dev].num_cu : 256;
-    return make_plan(packed, packed->bits == 8 && M > 64 ? 64 : M, cu).ws_bytes;
+    const size_t plan_bytes = make_plan(packed, packed->bits == 8 && M > 64 ? 64 : M, cu).ws_bytes;
+    return packed->perm ? align256(plan_bytes) + (size_t)M * packed->K * 2 : plan_bytes;
 }
 
 void tm_free_packed(tm_packed_w4* packed)
@@ -611,6 +716,7 @@ void tm_free_packed(tm_packed_w4* packed)
     packed->magic = 0;
     (void)hipFree(packed->w);
     (void)hipFree(packed->sz);
+    if (packed->perm) (void)hipFree(packed->perm);
     delete packed;
 }
 

@@ -75,6 +75,9 @@ hipError_t launch_repack(const uint32_t* qweight, const uint16_t* scales, const 
                          uint32_t* sz_out, int K, int N, int group, int layout, hipStream_t stream);
 hipError_t launch_repack8(const uint32_t* qweight, const uint16_t* scales, const uint16_t* zeros, uint32_t* w_out,
                           uint32_t* sz_out, int K, int N, int group, bool fp8, hipStream_t stream);
+hipError_t launch_permute_rows(const uint32_t* in, const int32_t* perm, uint32_t* out, int K, int N, int k_major,
+                               hipStream_t stream);
+hipError_t launch_permute_x(const uint16_t* X, const int32_t* perm, uint16_t* out, int M, int K, hipStream_t stream);
 hipError_t launch_unpack(const uint32_t* w, const uint32_t* sz, uint32_t* qweight_out, uint16_t* scales_out,
                          uint16_t* zeros_out, int K, int N, int group, hipStream_t stream);
 hipError_t launch_copy(void* dst, const void* src, size_t bytes, hipStream_t stream);

@@ -188,7 +188,68 @@ __global__ __launch_bounds__(256) void read16_kernel(const u32x4* __restrict__ s
     if (v == 0x9E3779B9u) *sink = v;               // practically never taken; keeps the loads alive
 }
 
+// Activation-order checkpoints: row i of the matrix that gets packed is row perm[i] of the checkpoint, so that the
+// rows of one K-group become consecutive.  N-major words move whole; a K-major word is rebuilt from eight rows.
+__global__ __launch_bounds__(256) void permute_rows_kernel(const uint32_t* __restrict__ in, const int32_t* __restrict__ perm,
+                                                           uint32_t* __restrict__ out, int K, int N, int k_major)
+{
+    size_t idx = (size_t)blockIdx.x * 256 + threadIdx.x;
+    if (k_major) {
+        if (idx >= (size_t)(K / 8) * N) return;
+        int i = (int)(idx / N), n = (int)(idx % N);
+        uint32_t w = 0;
+#pragma unroll
+        for (int t = 0; t < 8; ++t) {
+            int src = perm[8 * i + t];
+            w |= ((in[(size_t)(src >> 3) * N + n] >> (4 * (src & 7))) & 0xFu) << (4 * t);
+        }
+        out[idx] = w;
+    } else {
+        const int NW = N / 8;
+        if (idx >= (size_t)K * NW) return;
+        int r = (int)(idx / NW), j = (int)(idx % NW);
+        out[idx] = in[(size_t)perm[r] * NW + j];
+    }
+}
+
+// X'[m][i] = X[m][perm[i]]: the activations follow the rows of the packed matrix.  One thread per 16-byte chunk.
+__global__ __launch_bounds__(256) void permute_x_kernel(const uint16_t* __restrict__ X, const int32_t* __restrict__ perm,
+                                                        uint16_t* __restrict__ out, int M, int K)
+{
+    size_t idx = (size_t)blockIdx.x * 256 + threadIdx.x;
+    const int KC = K / 8;
+    if (idx >= (size_t)M * KC) return;
+    int m = (int)(idx / KC), c = (int)(idx % KC);
+    const uint16_t* row = X + (size_t)m * K;
+    u32x4 v;
+    uint32_t h[8];
+#pragma unroll
+    for (int e = 0; e < 8; ++e) h[e] = row[perm[8 * c + e]];
+    v.x = h[0] | (h[1] << 16);
+    v.y = h[2] | (h[3] << 16);
+    v.z = h[4] | (h[5] << 16);
+    v.w = h[6] | (h[7] << 16);
+    *(u32x4*)(out + (size_t)m * K + 8 * c) = v;
+}
+
 // ------------------------------------------------------------------------------------------ host launchers
+
+hipError_t launch_permute_rows(const uint32_t* in, const int32_t* perm, uint32_t* out, int K, int N, int k_major,
+                               hipStream_t stream)
+{
+    size_t total = (size_t)K * N / 8;
+    hipLaunchKernelGGL(permute_rows_kernel, dim3((unsigned)((total + 255) / 256)), dim3(256), 0, stream, in, perm, out, K,
+                       N, k_major);
+    return hipGetLastError();
+}
+
+hipError_t launch_permute_x(const uint16_t* X, const int32_t* perm, uint16_t* out, int M, int K, hipStream_t stream)
+{
+    size_t total = (size_t)M * (K / 8);
+    hipLaunchKernelGGL(permute_x_kernel, dim3((unsigned)((total + 255) / 256)), dim3(256), 0, stream, X, perm, out, M, K);
+    return hipGetLastError();
+}
+
 
 hipError_t launch_repack(const uint32_t* qweight, const uint16_t* scales, const void* zeros, uint32_t* w_out,
                          uint32_t* sz_out, int K, int N, int group, int layout, hipStream_t stream)

@@ -64,6 +64,10 @@ def test_argument_validation_without_gpu(lib):
     assert lib.tm_pack_w8(fake, None, fake, 128, 16, 128, None) is None and "null" in tm.tm_last_error()
     assert lib.tm_pack_w8(fake, fake, None, 128, 16, 96, None) is None and "group" in tm.tm_last_error()
     assert lib.tm_pack_w8_fp8(fake, None, 128, 16, 128, None) is None and "null" in tm.tm_last_error()
+    lib.tm_pack_w4_actorder.restype = ctypes.c_void_p
+    lib.tm_pack_w4_actorder.argtypes = [ctypes.c_void_p] * 4 + [ctypes.c_int] * 4 + [ctypes.c_void_p]
+    assert lib.tm_pack_w4_actorder(fake, fake, fake, None, 128, 16, 128, 2, None) is None and "g_idx" in tm.tm_last_error()
+    assert lib.tm_pack_w4_actorder(fake, fake, fake, fake, 128, 16, 100, 2, None) is None and "group" in tm.tm_last_error()
     assert lib.tm_packed_bits(None) == -1
     assert lib.tm_group_experts(None, 2) is None and lib.tm_group_experts(fake, 0) is None
     assert lib.tm_gemm_w4a16_grouped(fake, None, fake, fake, 4, None) == -1

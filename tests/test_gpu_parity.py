@@ -704,3 +704,57 @@ def test_fp8_quantised_weights_end_to_end(tm, oracle):
         exact = X.astype(np.float64) @ W.astype(np.float64)
         assert np.linalg.norm(Yref.astype(np.float64) - exact) / np.linalg.norm(exact) < 5e-2     # 3 mantissa bits
         packed.close()
+
+
+# ------------------------------------------------------------------ activation-order checkpoints
+
+@pytest.mark.parametrize("layout", [0, 1, 2])
+@pytest.mark.parametrize("M,K,N,g", [(1, 512, 272, 128), (16, 1024, 528, 64), (40, 768, 1040, 32), (300, 1024, 272, 128),
+                                     (5, 512, 48, 256)])
+def test_act_order_checkpoints(tm, oracle, M, K, N, g, layout):
+    """Rows carry their group in g_idx: the pack sorts rows by group, the GEMM regroups X; Y must match the oracle that
+    reads the checkpoint as it is."""
+    import torch
+    _say(f"act-order M={M} K={K} N={N} g={g} layout={layout}")
+    rng = np.random.default_rng(M + K + N + g + layout)
+    q = rng.integers(0, 16, (K, N), dtype=np.uint8)
+    s = rng.uniform(0.001, 0.02, (K // g, N)).astype(np.float16)
+    z = rng.integers(0, 16, (K // g, N)).astype(np.float16)
+    gi = wl.draw_act_order(K, g, rng)
+    X = rng.standard_normal((M, K)).astype(np.float16)
+    qw, zs = wl.encode_layout(q, z, layout)
+    zt = gu.to_dev(zs) if layout == 0 else torch.from_numpy(zs.view(np.int32)).cuda()
+    packed = tm.tm_pack_w4_actorder(torch.from_numpy(qw.view(np.int32)).cuda(), gu.to_dev(s), zt,
+                                    torch.from_numpy(gi).cuda(), K, N, g, layout)
+    # the packed buffer holds the rows sorted by group (stable)
+    perm = np.argsort(gi, kind="stable")
+    wbuf, szbuf = tm.tm_packed_raw(packed)
+    gs = min(g, 128)
+    q2, s2, z2 = oracle.unpack_packed(wbuf, szbuf, K, N, gs)
+    assert np.array_equal(q2, q[perm])
+    assert np.array_equal(s2.view(np.uint16), np.repeat(s, g // gs, axis=0).view(np.uint16))
+    Yref = oracle.gemm_gidx(X, q, s, z, gi)
+    ok, worst, fro = acceptance(gu.gemm(packed, X), Yref)
+    assert ok, (worst, fro)
+    # caller-workspace entry point: regroup area inside the workspace
+    nbytes = tm.tm_gemm_workspace_bytes(packed, M)
+    assert nbytes >= M * K * 2
+    ws = torch.zeros(nbytes, dtype=torch.uint8, device="cuda")
+    Y = torch.full((M, N), float("nan"), dtype=torch.float16, device="cuda")
+    tm.tm_gemm_w4a16_ws(gu.to_dev(X), packed, Y, ws)
+    torch.cuda.synchronize()
+    ok, worst, fro = acceptance(Y.cpu().numpy(), Yref)
+    assert ok, (worst, fro)
+    packed.close()
+
+
+def test_act_order_rejects_bad_group_index(tm):
+    import torch
+    _say("act-order bad g_idx")
+    K, N, g = 256, 16, 128
+    qw = torch.zeros((K // 8, N), dtype=torch.int32, device="cuda")
+    s = torch.ones((K // g, N), dtype=torch.float16, device="cuda")
+    zq = torch.zeros((K // g, N // 8), dtype=torch.int32, device="cuda")
+    for bad in (np.zeros(K, np.int32), np.full(K, 2, np.int32), np.concatenate([np.zeros(129), np.ones(127)]).astype(np.int32)):
+        with pytest.raises(tm.TmError):
+            tm.tm_pack_w4_actorder(qw, s, zq, torch.from_numpy(bad).cuda(), K, N, g, 2)
