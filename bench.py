@@ -258,7 +258,8 @@ def w8_table(tm, torch, wl, iters=100):
     """8-bit weights at decode sizes: the decode and MLP-decode layer shapes with int8 codes (W8A16) and with FP8 E4M3
     codes (random codes; timing does not depend on their values), same timing method as the 4-bit sweep."""
     rows = []
-    for fmt, (name, Ms) in [(f, l) for f in ("int8", "fp8") for l in WORKLOADS["decode"] + WORKLOADS["mlp_decode"]]:
+    shapes = WORKLOADS["decode"] + WORKLOADS["mlp_decode"] + WORKLOADS["sweep5"] + WORKLOADS["prefill"]
+    for fmt, (name, Ms) in [(f, l) for f in ("int8", "fp8") for l in shapes]:
         c = wl.case_by_name(name)
         G = c.K // c.group
         wbytes = c.K * c.N + 4 * G * c.N
@@ -284,15 +285,18 @@ def w8_table(tm, torch, wl, iters=100):
                 turn[0] += 1
                 tm.tm_gemm_w4a16(X[i % 4], packed[i % copies], Y[i % 4])
 
-            ev_ms, _ = time_steps(torch, step, iters, 10, graph_steps=iters)
-            t = ev_ms / iters * 1e-3
+            it = iters if M < 1024 else 10
+            ev_ms, _ = time_steps(torch, step, it, 3, graph_steps=it)
+            t = ev_ms / it * 1e-3
             B = wl.algorithmic_bytes(M, c.K, c.N, c.group, bits=8)
             plan = tm.tm_get_plan(packed[0], M)
             rows.append({"layer": c.name.rsplit("_M", 1)[0], "M": M, "K": c.K, "N": c.N, "group": c.group, "bits": 8, "format": fmt,
                          "us": t * 1e6, "GBps": B / t / 1e9, "hbm_frac": B / t / 1e9 / HBM_PEAK_GBPS,
+                         "TFLOPs": wl.flops(M, c.K, c.N) / t / 1e12,
                          "variant": plan["name"], "split_k": plan["split_k"], "grid": plan["grid"], "block": plan["block"]})
-            log(f"{fmt:4s} {rows[-1]['layer']:14s} M={M:3d} K={c.K:6d} N={c.N:6d} {t * 1e6:8.2f} us {B / t / 1e9:7.0f} GB/s "
-                f"({100 * B / t / 1e9 / HBM_PEAK_GBPS:4.1f} % HBM)  {plan['name']} split {plan['split_k']} block {plan['block']}")
+            log(f"{fmt:4s} {rows[-1]['layer']:14s} M={M:4d} K={c.K:6d} N={c.N:6d} {t * 1e6:8.2f} us {B / t / 1e9:7.0f} GB/s "
+                f"({100 * B / t / 1e9 / HBM_PEAK_GBPS:4.1f} % HBM) {wl.flops(M, c.K, c.N) / t / 1e12:7.1f} TF  "
+                f"{plan['name']} split {plan['split_k']} block {plan['block']}")
         for p in packed:
             p.close()
         del packed

@@ -117,8 +117,7 @@ TM_API tm_packed_w4* tm_pack_w4_actorder(const void* qweight, const uint16_t* sc
  * q[k][4j + t], codes 0..255; scales fp16 [K/group][N]; zeros fp16 [K/group][N], integer-valued in [0, 255], or NULL for
  * the symmetric zero-point 128.  Shapes, groups, alignment, ownership and errors as for tm_pack_w4_on.  The handle works
  * with tm_gemm_w4a16 / tm_gemm_w4a16_ws, tm_packed_info, tm_packed_raw, tm_get_plan and tm_free_packed; tm_unpack_w4 and
- * tm_group_experts take 4-bit handles only (TM_EUNSUPPORTED).  Only the decode kernels exist for this format: a GEMM with
- * M > 64 is run 64 rows at a time and re-reads the weights for each slice.
+ * tm_group_experts take 4-bit handles only (TM_EUNSUPPORTED).
  *
  * Packed layout: units of 16 columns x 64 rows (1 KiB); unit (nt, ks) is the 256 words from ((nt*(K/64))+ks)*256;
  * word 4*lane + 2*tt + hf (lane = 16*h + c, tt, hf in 0..1) holds column 16*nt + c, rows 64*ks + 32*tt + 8*h + 4*hf + b
@@ -130,8 +129,8 @@ TM_API tm_packed_w4* tm_pack_w8(const uint32_t* qweight, const uint16_t* scales,
  * FP8 weights (the paper's evaluation includes an FP8 model, Sec. 5.3): the 8-bit codes are numbers of the OCP FP8 E4M3
  * format (finite-only: bias 7, largest value 448, S.1111.111 = NaN) and
  *     dequant(Wq)[k][n] = fp8(q[k][n]) * s[k/group][n]          (no zero-point).
- * qweight u32 [K][N/4] as for tm_pack_w8, scales fp16 [K/group][N].  Same packed layout, same kernels restriction
- * (decode kernels; M > 64 in slices of 64 rows), same supporting calls as tm_pack_w8.  NaN codes propagate.
+ * qweight u32 [K][N/4] as for tm_pack_w8, scales fp16 [K/group][N].  Same packed layout and the same
+ * supporting calls as tm_pack_w8.  NaN codes propagate.
  */
 TM_API tm_packed_w4* tm_pack_w8_fp8(const uint32_t* qweight, const uint16_t* scales, int K, int N, int group,
                                     tm_stream stream);

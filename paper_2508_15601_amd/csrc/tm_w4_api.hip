@@ -162,14 +162,23 @@ Plan make_plan(const tm_packed_w4* h, int M, int num_cu)
     const int KU = h->bits == 8 ? h->K / 64 : h->K / kUnitK, NT = h->N / kUnitN;
     Plan pl{};
     int variant = g_force_variant;
-    // 8-bit codes run the decode kernels only (run_gemm hands them at most 64 rows at a time)
+    // 8-bit formats: the decode kernels up to 64 rows, three CTA-tile shapes above
     const bool w8 = h->bits == 8;
     if (w8 && variant >= 0 && !(variant == kSkinny16x16 || variant == kSkinny16x32 || variant == kSkinny16x48 ||
                                 variant == kSkinny16x64 || variant == kSkinny16x96 || variant == kSkinny16x128 ||
-                                variant == kSkinny32x64 || variant == kSkinny64x64))
+                                variant == kSkinny32x64 || variant == kSkinny64x64 || variant == kTile32x128 ||
+                                variant == kTile64x128 || variant == kTile128x256))
         variant = -1;
     if (variant < 0 && w8 && M > 16) {
-        variant = M <= 32 ? kSkinny32x64 : kSkinny64x64;
+        auto ctas = [&](int v) { return (long)ceil_div(M, tile_bm(v)) * ceil_div(h->N, tile_bn(v)); };
+        // up to 64 rows: narrow outputs (N <= 8192 on 256 CUs) stay with the decode kernels and split K, wide ones take
+        // the short tiles (measured at N = 22016: 24.4 vs 32.3 us at M = 32, 28.8 vs 47.6 us at M = 64)
+        const bool narrow = ceil_div(NT, 4) * 2 <= num_cu;
+        if (M <= 32) variant = narrow ? kSkinny32x64 : kTile32x128;
+        else if (M <= 64) variant = narrow ? kSkinny64x64 : kTile64x128;
+        else if (ctas(kTile128x256) >= num_cu) variant = kTile128x256;
+        else if (ctas(kTile64x128) >= num_cu) variant = kTile64x128;
+        else variant = kTile32x128;
     } else if (variant < 0) {
         if (M <= 16) {
             // One CTA per CU: the column tiles are dealt evenly over min(NT, #CU) strips (widths differ by at most
@@ -207,7 +216,7 @@ Plan make_plan(const tm_packed_w4* h, int M, int num_cu)
         }
     }
     if (is_skinny(variant) && M > skinny_rows(variant))        // a forced skinny variant must still cover M
-        variant = M <= 32 ? kSkinny32x64 : (M <= 64 || w8 ? kSkinny64x64 : kTile64x256);
+        variant = M <= 32 ? kSkinny32x64 : (M <= 64 ? kSkinny64x64 : (w8 ? kTile64x128 : kTile64x256));
     pl.variant = variant;
     const size_t out_bytes = (size_t)M * h->N * sizeof(float);
     int max_split_ws = (int)(kPartialBudget / (out_bytes ? out_bytes : 1));
@@ -273,6 +282,10 @@ Plan make_plan(const tm_packed_w4* h, int M, int num_cu)
         if (bm <= 64 && kg > 1 && g_force_stage == 0) steps = 4;
         if (g_force_waves >= 4) kg = g_force_waves * 64 / tile_threads(variant);
         if (!tile_has_kgroups(variant, kg)) kg = tile_has_kgroups(variant, 1) ? 1 : 4;
+        if (w8) {                                  // the 8-bit tiles are built in one depth each, one wave set
+            steps = variant == kTile128x256 ? 2 : 4;
+            kg = 1;
+        }
         // both X buffers (bm rows x (32*steps*kg + 16) halves each) must fit the 160 KiB of LDS
         while (kg > 1 && 2L * bm * (32 * steps * kg + 16) * 2 > 160 * 1024) {
             if (steps > 2) steps /= 2; else kg /= 2;
@@ -287,7 +300,7 @@ Plan make_plan(const tm_packed_w4* h, int M, int num_cu)
         while (steps * kg > 4 && KU % (steps * kg / 4)) {
             if (steps > 2) steps /= 2; else kg /= 2;
         }
-        const int ups = steps * kg / 4;
+        const int ups = steps * kg / (w8 ? 2 : 4);  // packed units per stage
         if (ups > 1 && pl.ku_per_split % ups) pl.ku_per_split += ups - pl.ku_per_split % ups;
         pl.stage_steps = steps;
         pl.kgroups = kg;
@@ -349,16 +362,6 @@ int run_gemm(const uint16_t* X, const tm_packed_w4* h, uint16_t* Y, int M, void*
         if (e != hipSuccess) return fail_hip(e, "regroup launch");
         return run_gemm(xb, h, Y, M, ws, plan_bytes, own_ws, stream, true);
     }
-    if (h->bits == 8 && M > 64) {
-        // 8-bit codes have decode kernels only: larger batches go through them 64 rows at a time (stream order
-        // keeps the shared workspace safe), re-reading the weights for every slice
-        for (int m0 = 0; m0 < M; m0 += 64) {
-            rc = run_gemm(X + (size_t)m0 * h->K, h, Y + (size_t)m0 * h->N, M - m0 < 64 ? M - m0 : 64, ws, ws_bytes,
-                          own_ws, stream, x_regrouped);
-            if (rc != TM_OK) return rc;
-        }
-        return TM_OK;
-    }
     Plan pl = make_plan(h, M, g_dev[dev].num_cu);
     if (own_ws) {
         ws = g_dev[dev].workspace;
@@ -389,7 +392,9 @@ int run_gemm(const uint16_t* X, const tm_packed_w4* h, uint16_t* Y, int M, void*
     p.tiles_m = pl.tiles_m;
     p.tiles_n = pl.tiles_n;
     p.strips = pl.strips;
-    hipError_t e = h->bits == 8 ? (h->fp8 ? launch_skinny_f8(p, pl, h->group, stream) : launch_skinny_w8(p, pl, h->group, stream))
+    hipError_t e = h->bits == 8 ? (!is_skinny(pl.variant) ? launch_tile_8bit(p, pl, h->group, h->fp8, stream)
+                                   : h->fp8 ? launch_skinny_f8(p, pl, h->group, stream)
+                                            : launch_skinny_w8(p, pl, h->group, stream))
                    : is_skinny(pl.variant) ? launch_skinny(p, pl, h->group, stream)
                                            : launch_tile(p, pl, h->group, stream);
     if (e != hipSuccess) return fail_hip(e, "kernel launch");
@@ -706,7 +711,7 @@ size_t tm_gemm_workspace_bytes(const tm_packed_w4* packed, int M)
     }
     int dev = packed->device;
     int cu = (dev >= 0 && dev < kMaxDevices && g_dev[dev].checked) ? g_dev[dev].num_cu : 256;
-    const size_t plan_bytes = make_plan(packed, packed->bits == 8 && M > 64 ? 64 : M, cu).ws_bytes;
+    const size_t plan_bytes = make_plan(packed, M, cu).ws_bytes;
     return packed->perm ? align256(plan_bytes) + (size_t)M * packed->K * 2 : plan_bytes;
 }
 
@@ -764,7 +769,7 @@ int tm_get_plan(const tm_packed_w4* packed, int M, int* variant, int* split_k, i
     if (M <= 0 || M >= (1 << 24)) return fail(TM_EINVAL, "M = %d out of range", M);
     int dev = packed->device;
     int cu = (dev >= 0 && dev < kMaxDevices && g_dev[dev].checked) ? g_dev[dev].num_cu : 256;
-    Plan pl = make_plan(packed, packed->bits == 8 && M > 64 ? 64 : M, cu);      // 8-bit: plan of one 64-row slice
+    Plan pl = make_plan(packed, M, cu);
     if (variant) *variant = pl.variant;
     if (split_k) *split_k = pl.split;
     if (grid) *grid = (int)pl.grid;

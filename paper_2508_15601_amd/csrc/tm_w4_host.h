@@ -87,6 +87,7 @@ hipError_t launch_skinny(const GemmParams& p, const Plan& plan, int group, hipSt
 hipError_t launch_skinny_w8(const GemmParams& p, const Plan& plan, int group, hipStream_t stream);
 hipError_t launch_skinny_f8(const GemmParams& p, const Plan& plan, int group, hipStream_t stream);
 hipError_t launch_skinny_grouped(const GroupedParams& gp, int variant, int experts, int group, hipStream_t stream);
+hipError_t launch_tile_8bit(const GemmParams& p, const Plan& plan, int group, bool fp8, hipStream_t stream);
 hipError_t launch_tile_grouped(const GroupedParams& gp, int variant, int experts, int group, hipStream_t stream);
 hipError_t launch_tile(const GemmParams& p, const Plan& plan, int group, hipStream_t stream);
 hipError_t launch_tile_small(const GemmParams& p, const Plan& plan, int group, hipStream_t stream);

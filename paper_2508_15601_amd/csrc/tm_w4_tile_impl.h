@@ -60,9 +60,13 @@ __device__ __forceinline__ void static_for(F&& f)
 // stage ahead, through the second LDS buffer.
 //
 // tile_body is one CTA's work on output tile (tile_m, tile_n) and K split sk of one GEMM.
-template <int TM, int TN, int NW, int GPU, int KW, int PD, int KG>
+// FMT is the weight format (kFmtInt4, kFmtInt8, kFmtFp8): 8-bit codes take two words per MFMA step and their packed
+// units hold two steps (64 rows) instead of four.
+template <int TM, int TN, int NW, int GPU, int KW, int PD, int KG, int FMT = kFmtInt4>
 __device__ __forceinline__ void tile_body(const GemmParams& p, const int tile_m, const int tile_n, const int sk)
 {
+    constexpr int WPS = FMT == kFmtInt4 ? 1 : 2;           // packed words per lane and MFMA step
+    constexpr int SPU = FMT == kFmtInt4 ? 4 : 2;           // MFMA steps per packed unit
     constexpr int NT_ = NW * KG * 64;                      // threads per CTA
     constexpr int BM = TM * 16, BN = NW * TN * 16;
     constexpr int BK = 32 * KW;                            // halves of K per stage and wave set
@@ -70,8 +74,8 @@ __device__ __forceinline__ void tile_body(const GemmParams& p, const int tile_m,
     constexpr int CPR = BKS / 8;                           // 16-byte chunks per X row and stage
     constexpr int CH = (BM * CPR + NT_ - 1) / NT_;         // chunks per thread and stage
     constexpr int SG = (KW * GPU) / 4 > 0 ? (KW * GPU) / 4 : 1;   // K-groups touched by one stage
-    constexpr int UW = KW > 4 ? KW / 4 : 1;                // packed units touched by one stage
-    constexpr int WPU = KW > 4 ? 4 : KW;                   // words of a unit used by one stage
+    constexpr int UW = KW > SPU ? KW / SPU : 1;            // packed units touched by one stage
+    constexpr int WPU = (KW > SPU ? SPU : KW) * WPS;       // words of a unit used by one stage
     // two X buffers, separate objects so that the compiler can tell a write into one from a read of the other;
     // after the K loop the first also carries the wave sets' partial tiles
     constexpr size_t kXsBytes = (size_t)BM * BKS * sizeof(uint16_t);
@@ -91,8 +95,8 @@ __device__ __forceinline__ void tile_body(const GemmParams& p, const int tile_m,
     const int nt_end = min(p.NT, (tile_n + 1) * (BN / 16));    // 16-column tiles of this CTA end here
     const int nt0 = (tile_n * BN) / 16 + wave * TN;        // first 16-column tile of this wave
     // stages of this CTA's K range (the host makes ku_per_split a multiple of UW when KW > 4)
-    const int st0 = (sk * p.ku_per_split * 4) / (KW * KG);
-    const int st1 = (min(p.KU, (sk + 1) * p.ku_per_split) * 4) / (KW * KG);
+    const int st0 = (sk * p.ku_per_split * SPU) / (KW * KG);
+    const int st1 = (min(p.KU, (sk + 1) * p.ku_per_split) * SPU) / (KW * KG);
 
     f32x4 acc[TM][TN];
 #pragma unroll
@@ -158,7 +162,7 @@ __device__ __forceinline__ void tile_body(const GemmParams& p, const int tile_m,
     // packed weights of one stage: words [st*KW, st*KW + KW) of the lane's K sequence, for each n-tile
     // packed weights and scale/zero words of stage r live in register set r % (PD + 1)
     const uint32_t w_lane = (uint32_t)lane * 16u, sz_lane = (uint32_t)c * 4u;
-    uint32_t wset[PD + 1][TN][KW];
+    uint32_t wset[PD + 1][TN][KW * WPS];
     uint32_t sset[PD + 1][TN][SG];
     // one descriptor per 16-column tile of this wave: its K/128 packed units, and its K/group scale/zero rows.
     // A tile past the edge of the strip gets empty descriptors: its loads return zero without touching memory
@@ -171,10 +175,10 @@ __device__ __forceinline__ void tile_body(const GemmParams& p, const int tile_m,
         w_rsrc[j] = make_rsrc((const char*)p.W + (size_t)nt * p.KU * 1024, live ? (uint32_t)p.KU * 1024u : 0u);
         s_rsrc[j] = make_rsrc((const char*)p.SZ + (size_t)nt * p.G * 64, live ? (uint32_t)p.G * 64u : 0u);
     }
-    auto load_w = [&](uint32_t (&w)[TN][KW], uint32_t (&s)[TN][SG], int stage) {
+    auto load_w = [&](uint32_t (&w)[TN][KW * WPS], uint32_t (&s)[TN][SG], int stage) {
         const int st = stage * KG + kg;                    // this wave set's slice of the stage
         // packed unit of the slice, and the first of the lane's four words in it (non-zero only for KW == 2)
-        const int wbyte = ((st * KW) / 4) * 1024 + ((st * KW) % 4) * 4;
+        const int wbyte = ((st * KW) / SPU) * 1024 + ((st * KW) % SPU) * 4 * WPS;
         const int grp0 = (st * KW * GPU) / 4;              // first K-group of the slice
         // Issue order = order of first use one or two stages later (the load counter retires in order): the
         // scale/zero words, then the weights.  (The X loads of a stage are issued before this call.)
@@ -207,8 +211,21 @@ __device__ __forceinline__ void tile_body(const GemmParams& p, const int tile_m,
     // into `nxt`, a few at a time between groups of MFMAs, and LDS reads run one row-pair ahead of their use.
     // The scheduling barriers keep the compiler from hoisting all LDS reads and conversions to the top, which
     // would both starve the matrix cores and blow the register budget.
+    // The fp16 operand of MFMA step tt from the stage's packed words (paper Sec. 3.1 step (iii)).
+    auto convert = [&](const uint32_t (&wj)[KW * WPS], int tt, uint32_t szw) -> f16x8 {
+        const GroupConst gc = make_group_const(szw);
+        if constexpr (FMT == kFmtInt4) {
+            return dequant8(wj[tt], gc, mg);
+        } else if constexpr (FMT == kFmtInt8) {
+            return dequant8_w8(wj[2 * tt], wj[2 * tt + 1], gc);
+        } else {
+            const f16x8 v = cvt8_fp8(wj[2 * tt], wj[2 * tt + 1]);
+            const _Float16 sc = gc.s2.x;
+            return v * f16x8{sc, sc, sc, sc, sc, sc, sc, sc};
+        }
+    };
     constexpr int PAIRS = TM / 2;
-    auto step = [&](int buf, int tt, const f16x8 (&cur)[TN], f16x8 (&nxt)[TN], const uint32_t (&wsrc)[TN][KW],
+    auto step = [&](int buf, int tt, const f16x8 (&cur)[TN], f16x8 (&nxt)[TN], const uint32_t (&wsrc)[TN][KW * WPS],
                     const uint32_t (&ssrc)[TN][SG], int tt_next) {
         f16x8 x0 = *x_frag(buf, tt, 0);
         f16x8 x1 = *x_frag(buf, tt, 1);
@@ -222,7 +239,7 @@ __device__ __forceinline__ void tile_body(const GemmParams& p, const int tile_m,
 #pragma unroll
             for (int j = 0; j < TN; ++j)
                 if (j * PAIRS / TN == ip)          // spread the TN conversions over the row pairs
-                    nxt[j] = dequant8(wsrc[j][tt_next], make_group_const(ssrc[j][(tt_next * GPU) / 4 % SG]), mg);
+                    nxt[j] = convert(wsrc[j], tt_next, ssrc[j][(tt_next * GPU) / 4 % SG]);
 #pragma unroll
             for (int j = 0; j < TN; ++j) acc[2 * ip][j] = mfma16x16x32(cur[j], x0, acc[2 * ip][j]);
 #pragma unroll
@@ -245,7 +262,7 @@ __device__ __forceinline__ void tile_body(const GemmParams& p, const int tile_m,
         for (int i = 0; i < XF; ++i) xf[i] = *x_frag(buf, tt, i);
     };
     auto step_ahead = [&](const f16x8 (&xc)[XF], f16x8 (&xn)[XF], int buf, int tt_x_next, const f16x8 (&cur)[TN],
-                          f16x8 (&nxt)[TN], const uint32_t (&wsrc)[TN][KW], const uint32_t (&ssrc)[TN][SG],
+                          f16x8 (&nxt)[TN], const uint32_t (&wsrc)[TN][KW * WPS], const uint32_t (&ssrc)[TN][SG],
                           int tt_next) {
         if (tt_x_next >= 0) read_x(xn, buf, tt_x_next);
 #pragma unroll
@@ -253,7 +270,7 @@ __device__ __forceinline__ void tile_body(const GemmParams& p, const int tile_m,
 #pragma unroll
             for (int j = 0; j < TN; ++j)
                 if (j * XF / TN == i)              // spread the TN conversions over the rows
-                    nxt[j] = dequant8(wsrc[j][tt_next], make_group_const(ssrc[j][(tt_next * GPU) / 4 % SG]), mg);
+                    nxt[j] = convert(wsrc[j], tt_next, ssrc[j][(tt_next * GPU) / 4 % SG]);
 #pragma unroll
             for (int j = 0; j < TN; ++j) acc[i][j] = mfma16x16x32(cur[j], xc[i], acc[i][j]);
         }
@@ -285,7 +302,7 @@ __device__ __forceinline__ void tile_body(const GemmParams& p, const int tile_m,
             load_w(wset[r % (PD + 1)], sset[r % (PD + 1)], min(st0 + r, last));
         });
 #pragma unroll
-        for (int j = 0; j < TN; ++j) wfa[j] = dequant8(wset[0][j][0], make_group_const(sset[0][j][0]), mg);
+        for (int j = 0; j < TN; ++j) wfa[j] = convert(wset[0][j], 0, sset[0][j][0]);
         stage_barrier(std::integral_constant<int, PD * kWLoads>{});
         constexpr int PERIOD = PD * (PD + 1);
         for (int base = 0; base < nst; base += PERIOD) {
@@ -431,7 +448,7 @@ __device__ __forceinline__ void tile_body(const GemmParams& p, const int tile_m,
     if (tid == 0) __hip_atomic_store(&p.counters[tile], 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
 }
 
-template <int TM, int TN, int NW, int GPU, int KW, int PD = (TM <= 8 ? 2 : 1), int KG = 1>
+template <int TM, int TN, int NW, int GPU, int KW, int PD = (TM <= 8 ? 2 : 1), int KG = 1, int FMT = kFmtInt4>
 __global__ __launch_bounds__(NW * KG * 64) void tile_kernel(GemmParams p)
 {
     // XCD-aware numbering: consecutive block ids go to different XCDs, so the ids congruent mod 8 (one XCD) are
@@ -447,23 +464,24 @@ __global__ __launch_bounds__(NW * KG * 64) void tile_kernel(GemmParams p)
     const int within = logical % panel_tiles;
     const int pw = min(kPanelN, p.tiles_n - panel * kPanelN);      // width of this panel
     const int tile_m = within / pw, tile_n = panel * kPanelN + within % pw;
-    tile_body<TM, TN, NW, GPU, KW, PD, KG>(p, tile_m, tile_n, sk);
+    tile_body<TM, TN, NW, GPU, KW, PD, KG, FMT>(p, tile_m, tile_n, sk);
 }
 
 // KW8: stages two packed units deep (needs an even number of units per K split, which the host checks);
 // otherwise one unit deep for short tiles and half a unit for tall ones.
-template <int TM, int TN, int NW, int KW, int KG = 1>
+template <int TM, int TN, int NW, int KW, int KG = 1, int FMT = kFmtInt4>
 hipError_t launch_shape(const GemmParams& p, const Plan& plan, int group, hipStream_t stream)
 {
     constexpr int PD = TM <= 8 ? 2 : 1;                // the 192- and 256-row tiles have no registers for more
+    constexpr int SPU = FMT == kFmtInt4 ? 4 : 2;       // MFMA steps per packed unit
     dim3 grid(plan.grid), block(NW * KG * 64);
     // the kernel assumes whole stages: every K split is a multiple of the stage depth, and so is K
     if (plan.block != NW * KG * 64 || plan.stage_steps != KW || plan.kgroups != KG) return hipErrorInvalidValue;
-    if ((plan.ku_per_split * 4) % (KW * KG) || (p.KU * 4) % (KW * KG)) return hipErrorInvalidValue;
+    if ((plan.ku_per_split * SPU) % (KW * KG) || (p.KU * SPU) % (KW * KG)) return hipErrorInvalidValue;
     switch (group) {
-        case 128: hipLaunchKernelGGL((tile_kernel<TM, TN, NW, 1, KW, PD, KG>), grid, block, 0, stream, p); break;
-        case 64: hipLaunchKernelGGL((tile_kernel<TM, TN, NW, 2, KW, PD, KG>), grid, block, 0, stream, p); break;
-        case 32: hipLaunchKernelGGL((tile_kernel<TM, TN, NW, 4, KW, PD, KG>), grid, block, 0, stream, p); break;
+        case 128: hipLaunchKernelGGL((tile_kernel<TM, TN, NW, 1, KW, PD, KG, FMT>), grid, block, 0, stream, p); break;
+        case 64: hipLaunchKernelGGL((tile_kernel<TM, TN, NW, 2, KW, PD, KG, FMT>), grid, block, 0, stream, p); break;
+        case 32: hipLaunchKernelGGL((tile_kernel<TM, TN, NW, 4, KW, PD, KG, FMT>), grid, block, 0, stream, p); break;
         default: return hipErrorInvalidValue;
     }
     return hipGetLastError();

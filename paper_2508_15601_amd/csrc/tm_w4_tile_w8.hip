@@ -1,0 +1,27 @@
+// CTA-tile kernels instantiated for the 8-bit weight formats (integer codes and FP8 E4M3): the same body with two packed
+// words per MFMA step and packed units of 64 rows.  Three tile shapes, one wave set, built like the small 4-bit tiles.
+#include "tm_w4_tile_impl.h"
+
+namespace tmw4 {
+
+namespace {
+
+template <int FMT>
+hipError_t launch_fmt(const GemmParams& p, const Plan& plan, int group, hipStream_t stream)
+{
+    switch (plan.variant) {
+        case kTile32x128: return launch_shape<2, 2, 4, 4, 1, FMT>(p, plan, group, stream);
+        case kTile64x128: return launch_shape<4, 2, 4, 4, 1, FMT>(p, plan, group, stream);
+        case kTile128x256: return launch_shape<8, 4, 4, 2, 1, FMT>(p, plan, group, stream);
+        default: return hipErrorInvalidValue;
+    }
+}
+
+}  // namespace
+
+hipError_t launch_tile_8bit(const GemmParams& p, const Plan& plan, int group, bool fp8, hipStream_t stream)
+{
+    return fp8 ? launch_fmt<kFmtFp8>(p, plan, group, stream) : launch_fmt<kFmtInt8>(p, plan, group, stream);
+}
+
+}  // namespace tmw4

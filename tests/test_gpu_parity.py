@@ -551,7 +551,7 @@ def test_w8_pack_bit_exact(tm, oracle, K, N, g):
         packed.close()
 
 
-W8_VARIANTS = [-1, 0, 1, 14, 2, 15, 16, 4, 19]
+W8_VARIANTS = [-1, 0, 1, 14, 2, 15, 16, 4, 19, 13, 9, 7]
 
 
 @pytest.mark.parametrize("variant", W8_VARIANTS)
@@ -580,7 +580,9 @@ def test_w8_one_hot_rows_return_dequantised_weights_bit_exactly(tm, oracle, vari
     (1, 1024, 528, -1, 0), (7, 768, 4112, -1, 0), (16, 2048, 1040, -1, 0), (16, 512, 48, 0, 0), (9, 1280, 336, 1, 2),
     (13, 1024, 1552, 14, 0), (16, 1024, 1040, 2, 3), (5, 896, 1552, 15, 0), (16, 640, 2064, 16, 0),
     (23, 1024, 1040, -1, 0), (32, 1536, 528, 4, 2), (33, 1024, 272, -1, 0), (64, 768, 1040, 19, 0),
-    (100, 512, 272, -1, 0), (300, 1024, 528, -1, 0)])
+    (100, 512, 272, -1, 0), (300, 1024, 528, -1, 0),
+    # CTA-tile kernels of the 8-bit formats: forced shapes, ragged M and N, split-K
+    (200, 1024, 1040, 7, 0), (70, 768, 528, 9, 2), (130, 512, 272, 13, 3), (257, 1536, 2064, 7, 2), (96, 2048, 336, 9, 0)])
 def test_w8_gemm_against_oracle(tm, oracle, M, K, N, variant, split, g):
     _say(f"w8 gemm M={M} K={K} N={N} g={g} variant={variant} split={split}")
     rng = np.random.default_rng(M + K + N + g)
@@ -652,7 +654,7 @@ def test_fp8_every_code_converts_exactly(tm, oracle):
     q2, s2, z2 = oracle.unpack_packed(wbuf, szbuf, K, N, g, bits=8)
     assert np.array_equal(q2, q) and np.array_equal(s2.view(np.uint16), s.view(np.uint16)) and not z2.view(np.uint16).any()
     What = oracle.dequant_fp8(q, s, g)
-    for variant in (0, 1, 2, 4, 19):
+    for variant in (0, 1, 2, 4, 19, 13, 7):
         tm.tm_set_variant(variant, 0)
         try:
             for k0 in range(0, K, 16):
@@ -669,7 +671,8 @@ def test_fp8_every_code_converts_exactly(tm, oracle):
 @pytest.mark.parametrize("g", [32, 64, 128])
 @pytest.mark.parametrize("M,K,N,variant,split", [
     (1, 1024, 528, -1, 0), (8, 768, 4112, -1, 0), (16, 2048, 1040, -1, 0), (11, 1280, 336, 1, 2), (16, 1024, 1552, 14, 0),
-    (6, 896, 1552, 15, 0), (16, 640, 2064, 16, 0), (29, 1024, 1040, -1, 0), (64, 768, 1040, 19, 3), (150, 512, 272, -1, 0)])
+    (6, 896, 1552, 15, 0), (16, 640, 2064, 16, 0), (29, 1024, 1040, -1, 0), (64, 768, 1040, 19, 3), (150, 512, 272, -1, 0),
+    (200, 1024, 1040, 7, 0), (70, 768, 528, 9, 2), (130, 512, 272, 13, 3), (300, 1024, 528, -1, 0)])
 def test_fp8_gemm_against_oracle(tm, oracle, M, K, N, variant, split, g):
     _say(f"fp8 gemm M={M} K={K} N={N} g={g} variant={variant} split={split}")
     rng = np.random.default_rng(M + K + N + g + 1)
