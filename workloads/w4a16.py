@@ -166,7 +166,7 @@ def make(case: Case, keep_W: bool = False, chunk_rows: int = 1024):
 
 
 # ---------------------------------------------------------------------------------------------
-# The five benchmark configurations (shapes and distributions as listed in BASELINE.json:configs).
+# The five benchmark configurations (layer shapes, group sizes and value distributions of the headline metric).
 
 def config_cases():
     cases = [Case("cfg1_tiny_M1", 1, 512, 512, 128)]
