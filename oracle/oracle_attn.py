@@ -1,0 +1,94 @@
+"""Reference (oracle) for decode attention over a quantised KV cache.  TEST INFRASTRUCTURE ONLY: imported by tests/,
+__graft_entry__.smoke() and bench.py's cpu_baseline leg, never by the GPU library or its binding.
+
+Plain numpy, fp64 throughout, one loop per (sequence, head); no blocking, no online softmax, no fused dequantisation.
+
+What it follows (paper Sec. 3.3 "attention pipeline design", Sec. 4.2, Sec. 4.4): at a decoding step every query head
+attends over the keys and values cached for its sequence; the cache holds low-bit integer codes that are dequantised to
+floating point before S = Q K^T and O = P V.  The paper does not state the granularity of the cache quantisation; the
+reading taken here is the usual one for such caches: one asymmetric scale / zero-point pair per token and KV head over the
+head dimension, x^ = (q - z) * s, with the same rounding rules as the weight recipe (s rounded to fp16 first, round half
+to even, clamp to the code range).
+
+Parity status: every function is pinned in tests/test_oracle_attn_pins.py (hand-worked quantiser group, softmax closed
+forms, PyTorch's CPU scaled_dot_product_attention in fp64, brute-force layout inverse).  Nothing is "parity unpinned".
+"""
+from __future__ import annotations
+
+import numpy as np
+
+HEAD_DIM = 128
+
+
+def kv_quantise(x: np.ndarray, bits: int = 8):
+    """x [..., D] (fp16 or fp32 values) -> (q uint8 [..., D], s float16 [...], z float16 [...]).
+    Per last axis: s = fp16((max - min) / (2^bits - 1)) (1 if that is 0 or not finite), z = clip(rint(-min / s), 0, qmax),
+    q = clip(rint(x / s) + z, 0, qmax); fp32 arithmetic with the rounded s."""
+    qmax = np.float32((1 << bits) - 1)
+    x = np.asarray(x, dtype=np.float32)
+    mn = x.min(axis=-1)
+    mx = x.max(axis=-1)
+    s16 = ((mx - mn) / qmax).astype(np.float32).astype(np.float16)
+    sf = s16.astype(np.float32)
+    bad = ~(sf > 0) | np.isinf(sf)
+    sf = np.where(bad, np.float32(1.0), sf).astype(np.float32)
+    s16 = np.where(bad, np.float16(1.0), s16).astype(np.float16)
+    z = np.clip(np.rint(-mn / sf), 0, qmax).astype(np.float32)
+    q = np.clip(np.rint(x / sf[..., None]) + z[..., None], 0, qmax)
+    return q.astype(np.uint8), s16, z.astype(np.float16)
+
+
+def kv_dequant(q: np.ndarray, s: np.ndarray, z: np.ndarray) -> np.ndarray:
+    """(q - z) * s in fp64, exact."""
+    return (q.astype(np.float64) - z.astype(np.float64)[..., None]) * s.astype(np.float64)[..., None]
+
+
+def attn_decode(Q, Kq, Ks, Kz, Vq, Vs, Vz, lens, scale: float) -> np.ndarray:
+    """One decoding step.  Q float16 [B, Hq, D]; K/V codes uint8 [B, Hkv, T, D] with scale / zero float16 [B, Hkv, T];
+    lens int [B] (tokens cached per sequence, 1..T); query head h uses KV head h // (Hq / Hkv).
+    O[b, h] = softmax(scale * K^ q) V^ over the first lens[b] tokens, computed in fp64, rounded once to float16."""
+    Q = np.asarray(Q)
+    B, Hq, D = Q.shape
+    Hkv = Kq.shape[1]
+    G = Hq // Hkv
+    O = np.zeros((B, Hq, D), np.float16)
+    for b in range(B):
+        L = int(lens[b])
+        for h in range(Hq):
+            kv = h // G
+            K = kv_dequant(Kq[b, kv, :L], Ks[b, kv, :L], Kz[b, kv, :L])          # [L, D]
+            V = kv_dequant(Vq[b, kv, :L], Vs[b, kv, :L], Vz[b, kv, :L])
+            sc = (K @ Q[b, h].astype(np.float64)) * float(scale)                # [L]
+            e = np.exp(sc - sc.max())
+            p = e / e.sum()
+            O[b, h] = (p @ V).astype(np.float16)
+    return O
+
+
+def kv_cache_unpack(kbuf, vbuf, szbuf, B: int, Hkv: int, cap: int, bits: int = 8):
+    """Inverse of the library's cache layout (8-bit codes), written from its specification:
+      K codes:  byte ((b*Hkv + h)*cap + t)*128 + d                                   (row-major, one 128-byte row per token)
+      V codes:  blocks of 32 tokens, 4096 bytes each, block ((b*Hkv + h)*(cap/32) + t/32); inside a block the byte of
+                token u = t % 32 and dimension d sits at ((c*4 + hh)*8 + i)*8 + e with c = d % 16, i = d / 16,
+                hh = (u % 16) / 4, e = u % 4 + 4*(u / 16)
+      scale/zero: u32 words, K pairs then V pairs: word ((b*Hkv + h)*cap + t)*2 + {0: K, 1: V} = scale bits | zero bits << 16
+    -> (Kq, Ks, Kz, Vq, Vs, Vz) in the plain [B, Hkv, cap, (D)] arrangement."""
+    assert bits == 8 and cap % 32 == 0
+    D = HEAD_DIM
+    kbuf = np.asarray(kbuf, np.uint8).reshape(-1)
+    vbuf = np.asarray(vbuf, np.uint8).reshape(-1)
+    szbuf = np.asarray(szbuf, np.uint32).reshape(-1)
+    Kq = kbuf.reshape(B, Hkv, cap, D).copy()
+    Vq = np.empty((B, Hkv, cap, D), np.uint8)
+    for t in range(cap):
+        u = t % 32
+        hh, e = (u % 16) // 4, u % 4 + 4 * (u // 16)
+        for d in range(D):
+            c, i = d % 16, d // 16
+            off = ((c * 4 + hh) * 8 + i) * 8 + e
+            blk = (np.arange(B)[:, None] * Hkv + np.arange(Hkv)[None, :]) * (cap // 32) + t // 32
+            Vq[:, :, t, d] = vbuf[blk * 4096 + off]
+    sz = szbuf.reshape(B, Hkv, cap, 2)
+    s = (sz & 0xFFFF).astype(np.uint16).view(np.float16)
+    z = (sz >> 16).astype(np.uint16).view(np.float16)
+    return Kq, s[..., 0], z[..., 0], Vq, s[..., 1], z[..., 1]

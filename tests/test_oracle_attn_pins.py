@@ -1,0 +1,96 @@
+"""Pins for the attention oracle (CPU only): quantiser fixture, softmax closed forms, PyTorch's fp64 attention."""
+import os
+
+import numpy as np
+import pytest
+
+from oracle import oracle_attn as oa
+from workloads import attn as wa
+
+GOLD = os.path.join(os.path.dirname(os.path.abspath(__file__)), "golden")
+
+
+def test_kv_quantise_hand_worked_row():
+    rows = []
+    for line in open(os.path.join(GOLD, "quant_group_8bit.txt")):
+        line = line.split("#")[0].split()
+        if line:
+            rows.append((float(line[0]), int(line[1]), float(line[2])))
+    x = np.array([r[0] for r in rows], np.float32)[None, :]                 # one token-head of 12 values
+    q, s, z = oa.kv_quantise(x)
+    assert float(s[0]) == 0.015625 and float(z[0]) == 64.0
+    assert q[0].tolist() == [r[1] for r in rows]
+    assert oa.kv_dequant(q, s, z)[0].tolist() == [r[2] for r in rows]
+    # constant row: scale falls back to 1, zero-point clamps
+    q, s, z = oa.kv_quantise(np.full((1, 8), 3.0, np.float32))
+    assert float(s[0]) == 1.0 and np.all(oa.kv_dequant(q, s, z) == 3.0)
+
+
+def _random_cache(rng, B, Hkv, T, D=128):
+    K = rng.standard_normal((B, Hkv, T, D)).astype(np.float16)
+    V = rng.standard_normal((B, Hkv, T, D)).astype(np.float16)
+    return oa.kv_quantise(K) + oa.kv_quantise(V)
+
+
+def test_attn_decode_closed_forms():
+    rng = np.random.default_rng(1)
+    B, Hq, Hkv, T, D = 2, 4, 2, 9, 128
+    Kq, Ks, Kz, Vq, Vs, Vz = _random_cache(rng, B, Hkv, T)
+    lens = np.array([9, 5])
+    V = oa.kv_dequant(Vq, Vs, Vz)
+    # zero query: uniform weights -> mean of the cached values
+    O = oa.attn_decode(np.zeros((B, Hq, D), np.float16), Kq, Ks, Kz, Vq, Vs, Vz, lens, 0.1)
+    for b in range(B):
+        for h in range(Hq):
+            assert np.allclose(O[b, h].astype(np.float64), V[b, h // 2, :lens[b]].mean(axis=0), rtol=2e-3, atol=2e-3)
+    # one cached token: the output is that token's value, whatever the query
+    Q = rng.standard_normal((B, Hq, D)).astype(np.float16)
+    O = oa.attn_decode(Q, Kq, Ks, Kz, Vq, Vs, Vz, np.array([1, 1]), 0.1)
+    assert np.array_equal(O[1, 3], V[1, 1, 0].astype(np.float16))
+    # a query aligned with one key and a huge scale: the output is that token's value
+    K = oa.kv_dequant(Kq, Ks, Kz)
+    Q2 = np.zeros((B, Hq, D), np.float16)
+    Q2[0, 0] = K[0, 0, 4].astype(np.float16)
+    O = oa.attn_decode(Q2, Kq, Ks, Kz, Vq, Vs, Vz, lens, 50.0)
+    assert np.allclose(O[0, 0].astype(np.float64), V[0, 0, 4], rtol=2e-3, atol=2e-3)
+    # tokens past lens are ignored
+    Kq2 = Kq.copy(); Kq2[:, :, 5:] = 255
+    assert np.array_equal(oa.attn_decode(Q, Kq2, Ks, Kz, Vq, Vs, Vz, lens, 0.1)[1], oa.attn_decode(Q, Kq, Ks, Kz, Vq, Vs, Vz, lens, 0.1)[1])
+
+
+def test_attn_decode_against_torch_sdpa():
+    import torch
+    rng = np.random.default_rng(2)
+    B, Hq, Hkv, T, D = 2, 8, 2, 37, 128
+    Kq, Ks, Kz, Vq, Vs, Vz = _random_cache(rng, B, Hkv, T)
+    Q = rng.standard_normal((B, Hq, D)).astype(np.float16)
+    lens = np.array([37, 20])
+    scale = 1.0 / np.sqrt(D)
+    O = oa.attn_decode(Q, Kq, Ks, Kz, Vq, Vs, Vz, lens, scale).astype(np.float64)
+    K = torch.from_numpy(oa.kv_dequant(Kq, Ks, Kz)).repeat_interleave(Hq // Hkv, dim=1)     # [B, Hq, T, D]
+    V = torch.from_numpy(oa.kv_dequant(Vq, Vs, Vz)).repeat_interleave(Hq // Hkv, dim=1)
+    for b in range(B):
+        L = int(lens[b])
+        ref = torch.nn.functional.scaled_dot_product_attention(
+            torch.from_numpy(Q[b].astype(np.float64))[:, None, :], K[b, :, :L], V[b, :, :L], scale=scale)[:, 0].numpy()
+        assert np.allclose(O[b], ref, rtol=1e-3, atol=1e-3)
+
+
+def test_cache_layout_inverse_against_generator_encoder():
+    """The oracle's inverse of the library's cache layout undoes the input generator's independent encoder, and single
+    position codes land where the layout rule says."""
+    rng = np.random.default_rng(3)
+    B, Hkv, cap = 2, 3, 64
+    Kq = rng.integers(0, 256, (B, Hkv, cap, 128), dtype=np.uint8)
+    Vq = rng.integers(0, 256, (B, Hkv, cap, 128), dtype=np.uint8)
+    s = [rng.uniform(0.001, 0.1, (B, Hkv, cap)).astype(np.float16) for _ in range(2)]
+    z = [rng.integers(0, 256, (B, Hkv, cap)).astype(np.float16) for _ in range(2)]
+    kbuf, vbuf, szbuf = wa.encode_cache(Kq, s[0], z[0], Vq, s[1], z[1])
+    out = oa.kv_cache_unpack(kbuf, vbuf, szbuf, B, Hkv, cap)
+    for a, b in zip(out, (Kq, s[0], z[0], Vq, s[1], z[1])):
+        assert np.array_equal(a.view(np.uint16) if a.dtype == np.float16 else a, b.view(np.uint16) if b.dtype == np.float16 else b)
+    # hand-placed bytes: token 21 (u = 21: hh = 1, e = 1 + 4 = 5), dimension 35 (c = 3, i = 2) of block 0
+    vb = np.zeros(B * Hkv * cap * 128, np.uint8)
+    vb[((3 * 4 + 1) * 8 + 2) * 8 + 5] = 77
+    _, _, _, Vu, _, _ = oa.kv_cache_unpack(np.zeros_like(vb), vb, np.zeros(B * Hkv * cap * 2, np.uint32), B, Hkv, cap)
+    assert Vu[0, 0, 21, 35] == 77 and Vu.sum() == 77

@@ -1,0 +1,39 @@
+"""Seeded synthetic inputs for decode attention over a quantised KV cache: Gaussian queries, keys and values in the
+shapes of the grouped-query-attention models the paper evaluates (head dimension 128), per-sequence context lengths, and
+the byte-level encoder of the cache layout the library reads (an input *format*, no arithmetic of the method).
+
+The cache layout (8-bit codes), per sequence b and KV head h, capacity cap tokens (a multiple of 32):
+  K codes   row-major: byte ((b*Hkv + h)*cap + t)*128 + d
+  V codes   blocks of 32 tokens x 128 dimensions (4096 bytes); inside a block, token u = t % 32 and dimension d sit at
+            ((c*4 + hh)*8 + i)*8 + e  with  c = d % 16, i = d / 16, hh = (u % 16) / 4, e = u % 4 + 4*(u / 16)
+  scale/zero words  u32 [(b*Hkv + h)*cap + t][2]: K pair, V pair; scale bits | zero bits << 16
+"""
+from __future__ import annotations
+
+import numpy as np
+
+
+def draw(B: int, Hq: int, Hkv: int, T: int, seed: int, D: int = 128, min_len: int = 1):
+    """-> Q float16 [B,Hq,D], K, V float16 [B,Hkv,T,D], lens int32 [B] (uniform in [min_len, T], the first one = T)."""
+    rng = np.random.default_rng(seed)
+    Q = rng.standard_normal((B, Hq, D)).astype(np.float16)
+    K = rng.standard_normal((B, Hkv, T, D)).astype(np.float16)
+    V = rng.standard_normal((B, Hkv, T, D)).astype(np.float16)
+    lens = rng.integers(min_len, T + 1, B).astype(np.int32)
+    lens[0] = T
+    return Q, K, V, lens
+
+
+def encode_cache(Kq, Ks, Kz, Vq, Vs, Vz):
+    """Plain arrays ([B,Hkv,cap,128] codes, [B,Hkv,cap] float16 scale / zero) -> (kbuf, vbuf uint8, szbuf uint32) in
+    the library's cache layout, written with reshapes."""
+    B, Hkv, cap, D = Kq.shape
+    assert D == 128 and cap % 32 == 0
+    kbuf = np.ascontiguousarray(Kq).reshape(-1)
+    # token u = 16*e_hi + 4*hh + e_lo ; e = e_lo + 4*e_hi ; d = 16*i + c  ->  [blk][c][hh][i][e_hi][e_lo]
+    v = Vq.reshape(B, Hkv, cap // 32, 2, 4, 4, 8, 16)            # [b,h,blk,e_hi,hh,e_lo,i,c]
+    vbuf = np.ascontiguousarray(v.transpose(0, 1, 2, 7, 4, 6, 3, 5)).reshape(-1)
+    def words(s, z):
+        return s.view(np.uint16).astype(np.uint32) | (z.view(np.uint16).astype(np.uint32) << 16)
+    szbuf = np.ascontiguousarray(np.stack([words(Ks, Kz), words(Vs, Vz)], axis=-1)).reshape(-1)
+    return kbuf, vbuf, szbuf
