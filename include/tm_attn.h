@@ -1,0 +1,74 @@
+/*
+ * tm_attn — decode attention over a quantised KV cache for AMD Instinct MI355X (gfx950); part of libtm_w4.
+ *
+ * The attention pipeline of the paper (Sec. 3.3 "attention pipeline design"): at a decoding step each query head
+ * attends over the keys and values cached for its sequence,
+ *
+ *     O[b][h] = softmax(scale * K^[b][h/G] q[b][h]) V^[b][h/G],      K^ = (Kq - zK) * sK,   V^ = (Vq - zV) * sV,
+ *
+ * with the cache kept as low-bit integer codes (Sec. 3.1: the same workflow with INT4/INT8 KV caches).  The paper does
+ * not state the cache's quantisation granularity; here every token and KV head has one asymmetric 8-bit scale /
+ * zero-point pair over the 128 values of the head (x^ = (q - z) * s, s = fp16((max - min)/255), z = round(-min/s)).
+ *
+ *   Q branch (Sec. 4.2, adaptive head alignment): the query fragments are arranged once per call so that their
+ *     per-lane dimension order equals the order in which a lane receives the low-bit key bytes; no key is reshuffled.
+ *   KV branch (Sec. 4.4, KV memory loading pipeline; Sec. 4.3): key and value codes are loaded straight into matrix-core
+ *     operand order, one block ahead of the block being multiplied, converted by bit manipulation; scale and zero-point
+ *     are applied to the scores and probabilities (per token), never to the 128 values of a token.
+ *
+ * Conventions as in tm_w4.h: plain C ABI, DEVICE pointers unless marked host, fp16 as uint16_t bit patterns, nothing
+ * synchronises, work is enqueued on the given stream, negative tm_status codes with tm_last_error().
+ * Head dimension is 128.  Grouped-query attention: q_heads = G * kv_heads, 1 <= G <= 16.
+ */
+#ifndef TM_ATTN_H
+#define TM_ATTN_H
+
+#include "tm_w4.h"
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef struct tm_kv_cache tm_kv_cache;   /* opaque; owns its device buffers */
+
+/*
+ * A cache for `batch` sequences x `kv_heads` heads x `capacity` tokens (rounded up to a multiple of 32) of 8-bit codes
+ * (bits must be 8).  Allocates 2 * batch*kv_heads*capacity*128 bytes of codes, 8 bytes of scale/zero pairs per token and
+ * head, and the split workspace of tm_attn_decode (a few MiB).  Contents start undefined.  NULL on error.
+ *
+ * Layout (also what tm_kv_raw exposes); bh = b*kv_heads + h:
+ *   K codes   byte (bh*capacity + t)*128 + d
+ *   V codes   blocks of 32 tokens (4096 bytes), block bh*(capacity/32) + t/32; token u = t % 32, dimension d at byte
+ *             ((c*4 + hh)*8 + i)*8 + e,  c = d % 16, i = d / 16, hh = (u % 16) / 4, e = u % 4 + 4*(u / 16)
+ *             (a lane's 64 consecutive bytes are its operand of the P*V product for all eight 16-row tiles)
+ *   pairs     u32 word (bh*capacity + t)*2 + {0: K, 1: V} = scale bits | zero bits << 16
+ */
+TM_API tm_kv_cache* tm_kv_create(int batch, int kv_heads, int capacity, int bits);
+TM_API void tm_kv_free(tm_kv_cache* cache);
+
+/*
+ * Quantise and store `count` new tokens per sequence: K_new, V_new fp16 [batch][count][kv_heads][128]; sequence b's
+ * tokens go to positions[b] .. positions[b] + count - 1 (positions: int32 [batch]; tokens that would fall outside
+ * [0, capacity) are dropped).  Codes are decided in fp32 with the fp16-rounded scale, round half to even.
+ */
+TM_API int tm_kv_append(tm_kv_cache* cache, const uint16_t* K_new, const uint16_t* V_new, const int32_t* positions,
+                        int count, tm_stream stream);
+
+/*
+ * One decoding step.  Q fp16 [batch][q_heads][128], O fp16 [batch][q_heads][128], both 16-byte aligned; lens int32
+ * [batch] = tokens cached per sequence (clamped to [0, capacity]; a sequence with 0 tokens gets O = 0).  max_len (host)
+ * bounds lens and only steers how the context is split across CTAs; pass the capacity if unknown.  Never allocates.
+ * Partial results of split contexts go through the cache's own workspace: calls on one cache must be ordered on one
+ * stream.  Results are bit-identical from run to run.
+ */
+TM_API int tm_attn_decode(const uint16_t* Q, const tm_kv_cache* cache, const int32_t* lens, uint16_t* O, int q_heads,
+                          float scale, int max_len, tm_stream stream);
+
+/* Test hook: the cache's device buffers and sizes (host out-pointers, any may be NULL); memory stays owned by the cache. */
+TM_API int tm_kv_raw(const tm_kv_cache* cache, void** k_codes, void** v_codes, void** pairs, size_t* code_bytes,
+                     size_t* pair_bytes);
+
+#ifdef __cplusplus
+}
+#endif
+#endif

@@ -42,6 +42,16 @@ def load_library():
     lib.tm_pack_w4.argtypes = [vp, vp, vp, i, i, i]
     lib.tm_pack_w4_on.restype = vp
     lib.tm_pack_w4_on.argtypes = [vp, vp, vp, i, i, i, vp]
+    lib.tm_kv_create.restype = vp
+    lib.tm_kv_create.argtypes = [i, i, i, i]
+    lib.tm_kv_free.restype = None
+    lib.tm_kv_free.argtypes = [vp]
+    lib.tm_kv_append.restype = i
+    lib.tm_kv_append.argtypes = [vp, vp, vp, vp, i, vp]
+    lib.tm_attn_decode.restype = i
+    lib.tm_attn_decode.argtypes = [vp, vp, vp, vp, i, ctypes.c_float, i, vp]
+    lib.tm_kv_raw.restype = i
+    lib.tm_kv_raw.argtypes = [vp, vp, vp, vp, vp, vp]
     lib.tm_pack_w4_actorder.restype = vp
     lib.tm_pack_w4_actorder.argtypes = [vp, vp, vp, vp, i, i, i, i, vp]
     lib.tm_pack_w8.restype = vp
@@ -378,3 +388,100 @@ def tm_bench_read(src, sink, stream=None):
     nbytes = src.numel() * src.element_size()
     _check(load_library().tm_bench_read(ctypes.c_void_p(src.data_ptr()), nbytes, ctypes.c_void_p(sink.data_ptr()),
                                         _stream_ptr(stream)))
+
+
+# ------------------------------------------------------------------ attention over a quantised KV cache (tm_attn.h)
+
+class KvCache:
+    """Owner of a tm_kv_cache handle (8-bit codes, head dimension 128)."""
+
+    def __init__(self, batch: int, kv_heads: int, capacity: int, bits: int = 8):
+        h = load_library().tm_kv_create(batch, kv_heads, capacity, bits)
+        if not h:
+            raise TmError(-1, tm_last_error())
+        self._h = h
+        self.batch, self.kv_heads, self.capacity = batch, kv_heads, (capacity + 31) // 32 * 32
+
+    @property
+    def handle(self):
+        if not self._h:
+            raise ValueError("cache already freed")
+        return ctypes.c_void_p(self._h)
+
+    def close(self):
+        if self._h:
+            import torch
+            torch.cuda.synchronize()
+            load_library().tm_kv_free(ctypes.c_void_p(self._h))
+            self._h = 0
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass
+
+
+def tm_kv_create(batch: int, kv_heads: int, capacity: int, bits: int = 8) -> KvCache:
+    return KvCache(batch, kv_heads, capacity, bits)
+
+
+def tm_kv_append(cache: KvCache, K_new, V_new, positions, stream=None):
+    """K_new, V_new float16 [batch, count, kv_heads, 128]; positions int32 [batch] (device)."""
+    import torch
+    if K_new.dim() != 4 or tuple(K_new.shape) != tuple(V_new.shape) or K_new.shape[0] != cache.batch or \
+            K_new.shape[2] != cache.kv_heads or K_new.shape[3] != 128 or positions.numel() != cache.batch:
+        raise ValueError("K_new / V_new / positions shapes do not match the cache")
+    _check(load_library().tm_kv_append(cache.handle, _dev_ptr(K_new, torch.float16, "K_new"),
+                                       _dev_ptr(V_new, torch.float16, "V_new"), _dev_ptr(positions, torch.int32, "positions"),
+                                       K_new.shape[1], _stream_ptr(stream)))
+
+
+def tm_attn_decode(Q, cache: KvCache, lens, O, scale: float, max_len: int = 0, stream=None):
+    """Q, O float16 [batch, q_heads, 128]; lens int32 [batch] (device)."""
+    import torch
+    if Q.dim() != 3 or Q.shape[0] != cache.batch or Q.shape[2] != 128 or tuple(O.shape) != tuple(Q.shape) or \
+            lens.numel() != cache.batch:
+        raise ValueError("Q / O / lens shapes do not match the cache")
+    _check(load_library().tm_attn_decode(_dev_ptr(Q, torch.float16, "Q"), cache.handle, _dev_ptr(lens, torch.int32, "lens"),
+                                         _dev_ptr(O, torch.float16, "O"), Q.shape[1], float(scale), int(max_len),
+                                         _stream_ptr(stream)))
+    return O
+
+
+def tm_kv_raw(cache: KvCache):
+    """Device pointers and sizes of the cache's buffers: (k_ptr, v_ptr, pair_ptr, code_bytes, pair_bytes)."""
+    k, v, p = ctypes.c_void_p(), ctypes.c_void_p(), ctypes.c_void_p()
+    cb, pb = ctypes.c_size_t(), ctypes.c_size_t()
+    _check(load_library().tm_kv_raw(cache.handle, ctypes.byref(k), ctypes.byref(v), ctypes.byref(p), ctypes.byref(cb),
+                                    ctypes.byref(pb)))
+    return k.value, v.value, p.value, cb.value, pb.value
+
+
+def tm_kv_download(cache: KvCache):
+    """Host copies of the cache's buffers: (K codes uint8, V codes uint8, pairs uint32), flat."""
+    import numpy as np
+    import torch
+    lib = load_library()
+    k, v, p, cb, pb = tm_kv_raw(cache)
+    torch.cuda.synchronize()
+    outs = []
+    for ptr, nbytes in ((k, cb), (v, cb), (p, pb)):
+        tmp = torch.empty(nbytes, dtype=torch.uint8, device="cuda")
+        _check(lib.tm_bench_copy(ctypes.c_void_p(tmp.data_ptr()), ctypes.c_void_p(ptr), nbytes, _stream_ptr(None)))
+        outs.append(tmp.cpu().numpy())
+    return outs[0], outs[1], outs[2].view(np.uint32)
+
+
+def tm_kv_upload(cache: KvCache, kbuf, vbuf, szbuf):
+    """Overwrite the cache's buffers with host arrays in the cache layout (tests and benchmarks)."""
+    import numpy as np
+    import torch
+    lib = load_library()
+    k, v, p, cb, pb = tm_kv_raw(cache)
+    for ptr, nbytes, host in ((k, cb, kbuf), (v, cb, vbuf), (p, pb, szbuf)):
+        t = torch.from_numpy(np.ascontiguousarray(host).view(np.uint8).reshape(-1)).cuda()
+        if t.numel() != nbytes:
+            raise ValueError("buffer size does not match the cache")
+        _check(lib.tm_bench_copy(ctypes.c_void_p(ptr), ctypes.c_void_p(t.data_ptr()), nbytes, _stream_ptr(None)))
+    torch.cuda.synchronize()

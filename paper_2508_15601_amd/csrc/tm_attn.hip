@@ -1,0 +1,349 @@
+// Decode attention over an 8-bit KV cache (paper Sec. 3.3 attention pipeline; Sec. 4.2, 4.3, 4.4), and the kernel that
+// quantises new keys / values into the cache.
+//
+// What differs from the paper's design, which rearranges Q in shared memory so that a 32-lane fragment load of the
+// low-bit K tile lines up with it, and stages K/V tiles through shared memory:
+//   - The matrix-core operand layout of gfx950 is an explicit index map, and a dot product does not care in which
+//     order its 128 dimensions are visited.  Lane (c, h) of a wave therefore simply takes the 32 consecutive key bytes
+//     32h .. 32h+31 of "its" token as the k-values of the four MFMA steps, and the query operand is loaded once in that
+//     same order.  That is the whole of the head alignment: no LDS, no shuffle, for any code width.
+//   - Scores are computed transposed (S^T = K Q^T, tokens as rows).  The MFMA result layout then hands every lane the
+//     probabilities of exactly the tokens whose value bytes it needs as the k-values of O^T = V^T P^T, so P never
+//     leaves its registers either; the cache stores V in blocks of 32 tokens in that operand order.
+//   - Scale and zero-point are per token, i.e. per row of S^T and per k-index of the second product: they are applied
+//     to four scores and eight probabilities per lane and block instead of to 2 x 128 code values per token.  The codes
+//     enter the matrix cores as 1024 + q (one byte permute per two codes); the bias and the zero-point leave through
+//     one fp32 term per query head.
+//   - K, V and their scale/zero pairs of the next 32-token block are in flight (registers) while the current block is
+//     multiplied; a CTA's waves take blocks round-robin and meet in LDS at the end; long contexts are split across
+//     CTAs and merged by a second, tiny kernel.
+#include "tm_w4_host.h"
+
+namespace tmw4 {
+
+namespace {
+
+typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
+
+constexpr int kHeadDim = 128;
+constexpr float kNegBig = -1.0e30f;     // "minus infinity" that stays finite under subtraction
+
+__device__ __forceinline__ float xor_max(float v, int mask) { return fmaxf(v, __shfl_xor(v, mask)); }
+__device__ __forceinline__ float xor_add(float v, int mask) { return v + __shfl_xor(v, mask); }
+
+// ------------------------------------------------------------------------------------------------ quantise + store
+// One wave per (sequence, new token, KV head); lane l owns dimensions l and l + 64 of the key and of the value.
+__global__ __launch_bounds__(64) void kv_append_kernel(AttnCache kv, const uint16_t* __restrict__ Kn,
+                                                       const uint16_t* __restrict__ Vn,
+                                                       const int32_t* __restrict__ positions, int count)
+{
+    const int lane = threadIdx.x;
+    const int h = blockIdx.x % kv.heads;
+    const int j = (blockIdx.x / kv.heads) % count;
+    const int b = blockIdx.x / (kv.heads * count);
+    const int t = positions[b] + j;
+    if (t < 0 || t >= kv.cap) return;                       // wave-uniform
+    const size_t src = (((size_t)b * count + j) * kv.heads + h) * kHeadDim;
+    const size_t bh = (size_t)b * kv.heads + h;
+#pragma unroll
+    for (int which = 0; which < 2; ++which) {
+        const uint16_t* x = (which ? Vn : Kn) + src;
+        const float x0 = (float)__builtin_bit_cast(_Float16, x[lane]);
+        const float x1 = (float)__builtin_bit_cast(_Float16, x[lane + 64]);
+        float mn = fminf(x0, x1), mx = fmaxf(x0, x1);
+#pragma unroll
+        for (int m = 1; m < 64; m <<= 1) {
+            mn = fminf(mn, __shfl_xor(mn, m));
+            mx = fmaxf(mx, __shfl_xor(mx, m));
+        }
+        _Float16 s16 = (_Float16)((mx - mn) / 255.0f);
+        float sf = (float)s16;
+        if (!(sf > 0.0f) || __builtin_isinf(sf)) {
+            sf = 1.0f;
+            s16 = (_Float16)1.0f;
+        }
+        const float zf = fminf(fmaxf(rintf(-mn / sf), 0.0f), 255.0f);
+        const uint32_t q0 = (uint32_t)fminf(fmaxf(rintf(x0 / sf) + zf, 0.0f), 255.0f);
+        const uint32_t q1 = (uint32_t)fminf(fmaxf(rintf(x1 / sf) + zf, 0.0f), 255.0f);
+        if (which == 0) {
+            uint8_t* row = kv.k + (bh * kv.cap + t) * kHeadDim;
+            row[lane] = (uint8_t)q0;
+            row[lane + 64] = (uint8_t)q1;
+        } else {
+            const int u = t & 31;
+            const int hh = (u & 15) >> 2, e = (u & 3) + 4 * (u >> 4);
+            uint8_t* blk = kv.v + (bh * (kv.cap / 32) + (t >> 5)) * 4096;
+            // dimension d = 16*i + c  ->  byte ((c*4 + hh)*8 + i)*8 + e
+            const int c = lane & 15, i0 = lane >> 4;        // d = lane: i = lane / 16; d = lane + 64: i + 4
+            blk[((c * 4 + hh) * 8 + i0) * 8 + e] = (uint8_t)q0;
+            blk[((c * 4 + hh) * 8 + i0 + 4) * 8 + e] = (uint8_t)q1;
+        }
+        if (lane == 0) {
+            const _Float16 z16 = (_Float16)zf;
+            kv.sz[(bh * kv.cap + t) * 2 + which] =
+                (uint32_t)__builtin_bit_cast(unsigned short, s16) | ((uint32_t)__builtin_bit_cast(unsigned short, z16) << 16);
+        }
+    }
+}
+
+// ------------------------------------------------------------------------------------------------ decode attention
+struct BlockRegs {
+    u32x4 k[2][2];      // two 16-token tiles: 32 key bytes of the lane's token (dimensions 32h .. 32h+31)
+    u32x4 sz[2][2];     // per tile: (K pair, V pair) of the lane's four tokens 4h .. 4h+3
+    u32x4 v[4];         // 64 value bytes: eight 16-row tiles x the lane's eight tokens
+};
+
+__device__ __forceinline__ void load_block(BlockRegs& r, const AttnCache& kv, size_t bh, int blk, int lane)
+{
+    const int c = lane & 15, h = lane >> 4;
+    const int t0 = blk * 32;
+#pragma unroll
+    for (int j = 0; j < 2; ++j) {
+        const uint8_t* kp = kv.k + (bh * kv.cap + t0 + 16 * j + c) * kHeadDim + 32 * h;
+        r.k[j][0] = __builtin_nontemporal_load((const u32x4*)kp);
+        r.k[j][1] = __builtin_nontemporal_load((const u32x4*)(kp + 16));
+        const uint32_t* sp = kv.sz + (bh * kv.cap + t0 + 16 * j + 4 * h) * 2;
+        r.sz[j][0] = *(const u32x4*)sp;
+        r.sz[j][1] = *(const u32x4*)(sp + 4);
+    }
+    const uint8_t* vp = kv.v + (bh * (kv.cap / 32) + blk) * 4096 + (c * 4 + h) * 64;
+#pragma unroll
+    for (int i = 0; i < 4; ++i) r.v[i] = __builtin_nontemporal_load((const u32x4*)(vp + 16 * i));
+}
+
+// Running state of one wave (per query head m = lane % 16; m_run is equal in the four lanes that share an m, l_run and
+// corr are per-lane partial sums over the lane's own tokens).
+struct SoftmaxState {
+    float m_run, l_run, corr;
+};
+
+__device__ __forceinline__ void process_block(const BlockRegs& r, const f16x8 (&qf)[4], float qsum, int t0, int len,
+                                              int lane, SoftmaxState& st, f32x4 (&acc)[8])
+{
+    const int h = lane >> 4;
+    // S^T for the two 16-token tiles: rows = tokens, columns = query heads
+    float s[2][4];
+    float vs[2][4], vzb[2][4];
+#pragma unroll
+    for (int j = 0; j < 2; ++j) {
+        f32x4 d = {0.f, 0.f, 0.f, 0.f};
+        d = mfma16x16x32(biased8_w8(r.k[j][0].x, r.k[j][0].y), qf[0], d);
+        d = mfma16x16x32(biased8_w8(r.k[j][0].z, r.k[j][0].w), qf[1], d);
+        d = mfma16x16x32(biased8_w8(r.k[j][1].x, r.k[j][1].y), qf[2], d);
+        d = mfma16x16x32(biased8_w8(r.k[j][1].z, r.k[j][1].w), qf[3], d);
+#pragma unroll
+        for (int rr = 0; rr < 4; ++rr) {
+            const uint32_t kw = rr < 2 ? r.sz[j][0][2 * rr] : r.sz[j][1][2 * (rr - 2)];
+            const uint32_t vw = rr < 2 ? r.sz[j][0][2 * rr + 1] : r.sz[j][1][2 * (rr - 2) + 1];
+            const f16x2 kp = as_f16x2(kw), vp = as_f16x2(vw);
+            const bool live = t0 + 16 * j + 4 * h + rr < len;
+            // sum_d (1024 + q_d) Q_d  -  (1024 + z) sum_d Q_d  =  sum_d (q_d - z) Q_d ; times the token's scale
+            const float sc = (float)kp.x * (d[rr] - (1024.0f + (float)kp.y) * qsum);
+            s[j][rr] = live ? sc : kNegBig;
+            vs[j][rr] = live ? (float)vp.x : 0.0f;          // a dead token contributes nothing, whatever its pair holds
+            vzb[j][rr] = live ? 1024.0f + (float)vp.y : 0.0f;
+        }
+    }
+    // online softmax in base 2 (the query carries scale * log2(e))
+    float mx = fmaxf(fmaxf(fmaxf(s[0][0], s[0][1]), fmaxf(s[0][2], s[0][3])), fmaxf(fmaxf(s[1][0], s[1][1]), fmaxf(s[1][2], s[1][3])));
+    mx = xor_max(xor_max(mx, 16), 32);
+    const float m_new = fmaxf(st.m_run, mx);
+    const float alpha = exp2f(st.m_run - m_new);
+    st.m_run = m_new;
+    float psum = 0.f, csum = 0.f;
+    f16x8 pb;
+#pragma unroll
+    for (int j = 0; j < 2; ++j)
+#pragma unroll
+        for (int rr = 0; rr < 4; ++rr) {
+            const float p = exp2f(s[j][rr] - m_new);        // 0 for masked tokens
+            psum += p;
+            const _Float16 pv = (_Float16)(p * vs[j][rr]);  // probability times the value scale of that token
+            pb[4 * j + rr] = pv;
+            csum += vzb[j][rr] * (float)pv;
+        }
+    st.l_run = st.l_run * alpha + psum;
+    st.corr = st.corr * alpha + csum;
+    // O^T += V^T P'^T : rows = dimensions (eight 16-row tiles), k = the 32 tokens of the block
+#pragma unroll
+    for (int i = 0; i < 8; ++i) {
+        const u32x4 w = r.v[i >> 1];
+        const f16x8 a = (i & 1) ? biased8_w8(w.z, w.w) : biased8_w8(w.x, w.y);
+        acc[i] = mfma16x16x32(a, pb, acc[i] * alpha);
+    }
+}
+
+// grid (kv heads, batch, splits); 256 threads.  Partial layout per (b, h, split): m[16], l[16], out[128][16] floats.
+constexpr int kPartialFloats = 32 + kHeadDim * 16;
+
+__global__ __launch_bounds__(256) void attn_decode_kernel(AttnCache kv, const uint16_t* __restrict__ Q,
+                                                          const int32_t* __restrict__ lens, uint16_t* __restrict__ O,
+                                                          int q_heads, float scale_log2e, int blocks_per_split,
+                                                          int splits)
+{
+    __shared__ float sm_ml[4][2][16];
+    __shared__ float sm_out[4][8][4][64];
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int c = lane & 15, h = lane >> 4;
+    const int hk = blockIdx.x, b = blockIdx.y, split = blockIdx.z;
+    const int G = q_heads / kv.heads;
+    const size_t bh = (size_t)b * kv.heads + hk;
+    const int len = min(max(lens[b], 0), kv.cap);
+    const int nblk = (len + 31) >> 5;
+    const int blk0 = split * blocks_per_split;
+    const int blk1 = min(nblk, blk0 + blocks_per_split);
+
+    // Query operand (adaptive head alignment): column m = c, k-values of step tt = dimensions 32h + 8tt .. +7, the
+    // order in which the lane's key bytes arrive; scaled once by scale * log2(e).
+    f16x8 qf[4];
+    float qsum = 0.f;
+    {
+        const bool real = c < G;
+        const uint16_t* qp = Q + ((size_t)b * q_heads + (size_t)hk * G + (real ? c : 0)) * kHeadDim + 32 * h;
+#pragma unroll
+        for (int tt = 0; tt < 4; ++tt) {
+            const f16x8 raw = *(const f16x8*)(qp + 8 * tt);
+#pragma unroll
+            for (int e = 0; e < 8; ++e) {
+                const _Float16 v = real ? (_Float16)((float)raw[e] * scale_log2e) : (_Float16)0.0f;
+                qf[tt][e] = v;
+                qsum += (float)v;
+            }
+        }
+        qsum = xor_add(xor_add(qsum, 16), 32);
+    }
+
+    SoftmaxState st{kNegBig, 0.f, 0.f};
+    f32x4 acc[8];
+#pragma unroll
+    for (int i = 0; i < 8; ++i) acc[i] = f32x4{0.f, 0.f, 0.f, 0.f};
+
+    // KV memory loading pipeline: the next block of this wave is in flight while the current one is multiplied
+    BlockRegs ra, rb;
+    int blk = blk0 + wave;
+    if (blk < blk1) load_block(ra, kv, bh, blk, lane);
+    while (blk < blk1) {
+        if (blk + 4 < blk1) load_block(rb, kv, bh, blk + 4, lane);
+        process_block(ra, qf, qsum, blk * 32, len, lane, st, acc);
+        blk += 4;
+        if (blk >= blk1) break;
+        if (blk + 4 < blk1) load_block(ra, kv, bh, blk + 4, lane);
+        process_block(rb, qf, qsum, blk * 32, len, lane, st, acc);
+        blk += 4;
+    }
+
+    // the four lanes of a query head add their partial sums; the waves meet in LDS
+    const float l_w = xor_add(xor_add(st.l_run, 16), 32);
+    const float corr_w = xor_add(xor_add(st.corr, 16), 32);
+    if (h == 0) {
+        sm_ml[wave][0][c] = st.m_run;
+        sm_ml[wave][1][c] = l_w;
+    }
+#pragma unroll
+    for (int i = 0; i < 8; ++i)
+#pragma unroll
+        for (int rr = 0; rr < 4; ++rr) sm_out[wave][i][rr][lane] = acc[i][rr] - corr_w;   // bias and zero-point leave here
+    __syncthreads();
+    // thread (wave w, lane) finalises row tiles 2w and 2w+1 of its column
+    float M = kNegBig;
+#pragma unroll
+    for (int w = 0; w < 4; ++w) M = fmaxf(M, sm_ml[w][0][c]);
+    float L = 0.f, f[4];
+#pragma unroll
+    for (int w = 0; w < 4; ++w) {
+        f[w] = exp2f(sm_ml[w][0][c] - M);
+        L += sm_ml[w][1][c] * f[w];
+    }
+    float* part = nullptr;
+    if (splits > 1) {
+        part = kv.partial + (((size_t)bh * splits) + split) * kPartialFloats;
+        if (wave == 0 && h == 0) {
+            part[c] = M;
+            part[16 + c] = L;
+        }
+    }
+    const float inv = L > 0.f ? 1.0f / L : 0.f;
+#pragma unroll
+    for (int ii = 0; ii < 2; ++ii) {
+        const int i = 2 * wave + ii;
+        float o[4];
+#pragma unroll
+        for (int rr = 0; rr < 4; ++rr) {
+            float v = 0.f;
+#pragma unroll
+            for (int w = 0; w < 4; ++w) v += sm_out[w][i][rr][lane] * f[w];
+            o[rr] = v;
+        }
+        const int d0 = 16 * i + 4 * h;                      // this lane's four consecutive dimensions
+        if (splits > 1) {
+#pragma unroll
+            for (int rr = 0; rr < 4; ++rr) part[32 + (d0 + rr) * 16 + c] = o[rr];
+        } else if (c < G) {
+            u32x2 out;
+            out.x = (uint32_t)f32_to_f16_bits(o[0] * inv) | ((uint32_t)f32_to_f16_bits(o[1] * inv) << 16);
+            out.y = (uint32_t)f32_to_f16_bits(o[2] * inv) | ((uint32_t)f32_to_f16_bits(o[3] * inv) << 16);
+            *(u32x2*)(O + ((size_t)b * q_heads + (size_t)hk * G + c) * kHeadDim + d0) = out;
+        }
+    }
+}
+
+// Merge of the context splits: grid (kv heads, batch), 256 threads; thread -> (dimension pair, query head).
+__global__ __launch_bounds__(256) void attn_merge_kernel(AttnCache kv, uint16_t* __restrict__ O, int q_heads, int splits)
+{
+    const int hk = blockIdx.x, b = blockIdx.y;
+    const int G = q_heads / kv.heads;
+    const size_t bh = (size_t)b * kv.heads + hk;
+    const float* base = kv.partial + (size_t)bh * splits * kPartialFloats;
+    const int m = threadIdx.x & 15;
+    float M = kNegBig;
+    for (int s = 0; s < splits; ++s) M = fmaxf(M, base[(size_t)s * kPartialFloats + m]);
+    float L = 0.f;
+    for (int s = 0; s < splits; ++s) L += base[(size_t)s * kPartialFloats + 16 + m] * exp2f(base[(size_t)s * kPartialFloats + m] - M);
+    const float inv = L > 0.f ? 1.0f / L : 0.f;
+    if (m >= G) return;
+    for (int d = threadIdx.x >> 4; d < kHeadDim; d += 16) {
+        float v = 0.f;
+        for (int s = 0; s < splits; ++s) {
+            const float* p = base + (size_t)s * kPartialFloats;
+            v += p[32 + d * 16 + m] * exp2f(p[m] - M);
+        }
+        O[((size_t)b * q_heads + (size_t)hk * G + m) * kHeadDim + d] = f32_to_f16_bits(v * inv);
+    }
+}
+
+}  // namespace
+
+hipError_t launch_kv_append(const AttnCache& kv, const uint16_t* Kn, const uint16_t* Vn, const int32_t* positions,
+                            int count, hipStream_t stream)
+{
+    const long waves = (long)kv.batch * count * kv.heads;
+    if (waves <= 0 || waves > 0x7fffffffL) return hipErrorInvalidValue;
+    hipLaunchKernelGGL(kv_append_kernel, dim3((unsigned)waves), dim3(64), 0, stream, kv, Kn, Vn, positions, count);
+    return hipGetLastError();
+}
+
+hipError_t launch_attn_decode(const AttnCache& kv, const uint16_t* Q, const int32_t* lens, uint16_t* O, int q_heads,
+                              float scale, int max_len, int num_cu, hipStream_t stream)
+{
+    const int nblk = (max_len + 31) / 32;
+    // enough CTAs for about three per CU, at least four blocks per wave and split, and no more partial results than
+    // the cache's workspace holds
+    int splits = (3 * num_cu + kv.batch * kv.heads - 1) / (kv.batch * kv.heads);
+    const int by_work = nblk / 16 > 0 ? nblk / 16 : 1;
+    if (splits > by_work) splits = by_work;
+    if (splits > kv.max_splits) splits = kv.max_splits;
+    if (splits < 1) splits = 1;
+    const int bps = (nblk + splits - 1) / splits;
+    splits = (nblk + bps - 1) / bps > 0 ? (nblk + bps - 1) / bps : 1;
+    if (kv.heads > 65535 || kv.batch > 65535) return hipErrorInvalidValue;
+    const float scale_log2e = scale * 1.4426950408889634f;
+    hipLaunchKernelGGL(attn_decode_kernel, dim3(kv.heads, kv.batch, splits), dim3(256), 0, stream, kv, Q, lens, O, q_heads,
+                       scale_log2e, bps, splits);
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess || splits == 1) return e;
+    hipLaunchKernelGGL(attn_merge_kernel, dim3(kv.heads, kv.batch), dim3(256), 0, stream, kv, O, q_heads, splits);
+    return hipGetLastError();
+}
+
+}  // namespace tmw4

@@ -7,6 +7,7 @@
 #include <new>
 #include <vector>
 
+#include "tm_attn.h"
 #include "tm_w4.h"
 #include "tm_w4_host.h"
 
@@ -102,6 +103,13 @@ struct tm_packed_w4 {
     uint32_t* w;       // K*N/8 words
     uint32_t* sz;      // (K/group)*N words
     size_t w_bytes, sz_bytes;
+};
+
+struct tm_kv_cache {
+    uint32_t magic;
+    int device;
+    tmw4::AttnCache kv;
+    size_t code_bytes, pair_bytes;
 };
 
 struct tm_expert_group {
@@ -846,5 +854,115 @@ int tm_bench_read(const void* src, size_t bytes, void* sink, tm_stream stream)
 const char* tm_last_error(void) { return g_error; }
 
 const char* tm_version(void) { return "tm_w4 0.1 (gfx950)"; }
+
+
+// ---------------------------------------------------------------------------------------- attention over a KV cache
+
+static bool valid_kv(const tm_kv_cache* c) { return c && c->magic == 0x746D4B56u; }
+
+tm_kv_cache* tm_kv_create(int batch, int kv_heads, int capacity, int bits)
+{
+    if (batch <= 0 || kv_heads <= 0 || capacity <= 0 || batch > 65535 || kv_heads > 65535 || bits != 8) {
+        fail(TM_EINVAL, "need 1 <= batch, kv_heads <= 65535, capacity > 0, bits == 8 (got %d, %d, %d, %d)", batch, kv_heads,
+             capacity, bits);
+        return nullptr;
+    }
+    const long cap = ((long)capacity + 31) / 32 * 32;
+    const double codes = (double)batch * kv_heads * (double)cap * 128.0;
+    if (cap >= (1L << 24) || codes >= 1.0e12) {
+        fail(TM_EINVAL, "cache too large");
+        return nullptr;
+    }
+    int dev;
+    if (check_device(&dev) != TM_OK) return nullptr;
+    tm_kv_cache* c = new (std::nothrow) tm_kv_cache();
+    if (!c) {
+        fail(TM_ENOMEM, "host allocation failed");
+        return nullptr;
+    }
+    c->device = dev;
+    c->kv.batch = batch;
+    c->kv.heads = kv_heads;
+    c->kv.cap = (int)cap;
+    // partial results of split contexts: at most 1024 (sequence, head, split) slots of 8.3 KiB, at most 64 splits
+    int ms = 1024 / (batch * kv_heads);
+    c->kv.max_splits = ms < 1 ? 1 : (ms > 64 ? 64 : ms);
+    c->code_bytes = (size_t)batch * kv_heads * cap * 128;
+    c->pair_bytes = (size_t)batch * kv_heads * cap * 8;
+    const size_t part_bytes = (size_t)batch * kv_heads * c->kv.max_splits * (32 + 128 * 16) * sizeof(float);
+    hipError_t e = hipMalloc((void**)&c->kv.k, c->code_bytes);
+    if (e == hipSuccess) e = hipMalloc((void**)&c->kv.v, c->code_bytes);
+    if (e == hipSuccess) e = hipMalloc((void**)&c->kv.sz, c->pair_bytes);
+    if (e == hipSuccess) e = hipMalloc((void**)&c->kv.partial, part_bytes);
+    if (e != hipSuccess) {
+        fail_hip(e, "hipMalloc(kv cache)");
+        if (c->kv.k) (void)hipFree(c->kv.k);
+        if (c->kv.v) (void)hipFree(c->kv.v);
+        if (c->kv.sz) (void)hipFree(c->kv.sz);
+        delete c;
+        return nullptr;
+    }
+    c->magic = 0x746D4B56u;
+    return c;
+}
+
+void tm_kv_free(tm_kv_cache* cache)
+{
+    if (!valid_kv(cache)) return;
+    cache->magic = 0;
+    (void)hipFree(cache->kv.k);
+    (void)hipFree(cache->kv.v);
+    (void)hipFree(cache->kv.sz);
+    (void)hipFree(cache->kv.partial);
+    delete cache;
+}
+
+int tm_kv_append(tm_kv_cache* cache, const uint16_t* K_new, const uint16_t* V_new, const int32_t* positions, int count,
+                 tm_stream stream)
+{
+    if (!valid_kv(cache)) return fail(TM_EINVAL, "cache handle is null or invalid");
+    if (count == 0) return TM_OK;
+    if (!K_new || !V_new || !positions) return fail(TM_EINVAL, "K_new, V_new or positions is null");
+    if (count < 0 || count > cache->kv.cap) return fail(TM_EINVAL, "count = %d out of range", count);
+    if (((uintptr_t)K_new & 1) || ((uintptr_t)V_new & 1) || ((uintptr_t)positions & 3)) return fail(TM_EINVAL, "misaligned input");
+    int dev;
+    int rc = check_device(&dev);
+    if (rc != TM_OK) return rc;
+    if (dev != cache->device) return fail(TM_EINVAL, "cache lives on device %d, current device is %d", cache->device, dev);
+    hipError_t e = launch_kv_append(cache->kv, K_new, V_new, positions, count, (hipStream_t)stream);
+    if (e != hipSuccess) return fail_hip(e, "kv append launch");
+    return TM_OK;
+}
+
+int tm_attn_decode(const uint16_t* Q, const tm_kv_cache* cache, const int32_t* lens, uint16_t* O, int q_heads, float scale,
+                   int max_len, tm_stream stream)
+{
+    if (!valid_kv(cache)) return fail(TM_EINVAL, "cache handle is null or invalid");
+    if (!Q || !O || !lens) return fail(TM_EINVAL, "Q, O or lens is null");
+    if (((uintptr_t)Q & 15) || ((uintptr_t)O & 15) || ((uintptr_t)lens & 3)) return fail(TM_EINVAL, "misaligned Q, O or lens");
+    const int hk = cache->kv.heads;
+    if (q_heads <= 0 || q_heads % hk || q_heads / hk > 16)
+        return fail(TM_EINVAL, "q_heads = %d must be 1..16 times the cache's %d heads", q_heads, hk);
+    if (!(scale > 0.0f) || !(scale < 1.0e6f)) return fail(TM_EINVAL, "scale out of range");
+    if (max_len <= 0 || max_len > cache->kv.cap) max_len = cache->kv.cap;
+    int dev;
+    int rc = check_device(&dev);
+    if (rc != TM_OK) return rc;
+    if (dev != cache->device) return fail(TM_EINVAL, "cache lives on device %d, current device is %d", cache->device, dev);
+    hipError_t e = launch_attn_decode(cache->kv, Q, lens, O, q_heads, scale, max_len, g_dev[dev].num_cu, (hipStream_t)stream);
+    if (e != hipSuccess) return fail_hip(e, "attention launch");
+    return TM_OK;
+}
+
+int tm_kv_raw(const tm_kv_cache* cache, void** k_codes, void** v_codes, void** pairs, size_t* code_bytes, size_t* pair_bytes)
+{
+    if (!valid_kv(cache)) return fail(TM_EINVAL, "cache handle is null or invalid");
+    if (k_codes) *k_codes = cache->kv.k;
+    if (v_codes) *v_codes = cache->kv.v;
+    if (pairs) *pairs = cache->kv.sz;
+    if (code_bytes) *code_bytes = cache->code_bytes;
+    if (pair_bytes) *pair_bytes = cache->pair_bytes;
+    return TM_OK;
+}
 
 }  // extern "C"

@@ -45,6 +45,15 @@ struct GroupedParams {
     int tiles_n, mtiles;        // tile kernels: column tiles, and the upper bound of row tiles over all experts
 };
 
+// Quantised KV cache of the attention kernels: 8-bit codes, one scale/zero pair per token and head.
+struct AttnCache {
+    uint8_t* k;          // [batch*heads][cap][128] codes, row-major
+    uint8_t* v;          // [batch*heads][cap/32] blocks of 4096 bytes in P*V operand order
+    uint32_t* sz;        // [batch*heads][cap][2] scale | zero << 16: K pair, V pair
+    float* partial;      // split workspace: [batch*heads][max_splits] x (m[16], l[16], out[128][16])
+    int batch, heads, cap, max_splits;
+};
+
 __device__ __forceinline__ f16x2 as_f16x2(uint32_t u) { return __builtin_bit_cast(f16x2, u); }
 
 // Per-(column, K-group) constants of the conversion: the scale in both halves, and the two exact offsets that

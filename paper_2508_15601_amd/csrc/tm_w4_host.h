@@ -83,6 +83,10 @@ hipError_t launch_unpack(const uint32_t* w, const uint32_t* sz, uint32_t* qweigh
 hipError_t launch_copy(void* dst, const void* src, size_t bytes, hipStream_t stream);
 hipError_t launch_read(const void* src, size_t bytes, void* sink, hipStream_t stream);
 
+hipError_t launch_kv_append(const AttnCache& kv, const uint16_t* Kn, const uint16_t* Vn, const int32_t* positions,
+                            int count, hipStream_t stream);
+hipError_t launch_attn_decode(const AttnCache& kv, const uint16_t* Q, const int32_t* lens, uint16_t* O, int q_heads,
+                              float scale, int max_len, int num_cu, hipStream_t stream);
 hipError_t launch_skinny(const GemmParams& p, const Plan& plan, int group, hipStream_t stream);
 hipError_t launch_skinny_w8(const GemmParams& p, const Plan& plan, int group, hipStream_t stream);
 hipError_t launch_skinny_f8(const GemmParams& p, const Plan& plan, int group, hipStream_t stream);

@@ -10,7 +10,8 @@ ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
 
 
 def _declared_symbols():
-    text = open(os.path.join(ROOT, "include", "tm_w4.h")).read()
+    text = "".join(open(os.path.join(ROOT, "include", f)).read() for f in sorted(os.listdir(os.path.join(ROOT, "include")))
+                   if f.endswith(".h"))
     text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
     return sorted(set(re.findall(r"\b(tm_[a-z0-9_]+)\s*\(", text)))
 
@@ -69,6 +70,11 @@ def test_argument_validation_without_gpu(lib):
     assert lib.tm_pack_w4_actorder(fake, fake, fake, None, 128, 16, 128, 2, None) is None and "g_idx" in tm.tm_last_error()
     assert lib.tm_pack_w4_actorder(fake, fake, fake, fake, 128, 16, 100, 2, None) is None and "group" in tm.tm_last_error()
     assert lib.tm_packed_bits(None) == -1
+    assert lib.tm_kv_create(0, 1, 32, 8) is None and lib.tm_kv_create(1, 1, 32, 4) is None
+    assert lib.tm_kv_append(None, fake, fake, fake, 1, None) == -1
+    assert lib.tm_attn_decode(fake, None, fake, fake, 8, 0.1, 0, None) == -1
+    assert lib.tm_kv_raw(None, None, None, None, None, None) == -1
+    lib.tm_kv_free(None)
     assert lib.tm_group_experts(None, 2) is None and lib.tm_group_experts(fake, 0) is None
     assert lib.tm_gemm_w4a16_grouped(fake, None, fake, fake, 4, None) == -1
     assert lib.tm_get_grouped_plan(None, 4, None, None) == -1

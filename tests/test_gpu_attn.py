@@ -1,0 +1,144 @@
+"""GPU parity of the attention path (tm_attn.h) against the oracle: the quantise-and-store kernel bit for bit, the decode
+attention within  |O - Oref| <= 2e-3 + 5e-3*|Oref|  and relative Frobenius error <= 2e-3  (the probabilities enter the
+second matrix product as fp16, and O is rounded to fp16 once)."""
+import sys
+
+import numpy as np
+import pytest
+
+from oracle import oracle_attn as oa
+from workloads import attn as wa
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def tm():
+    import torch
+    if not torch.cuda.is_available():
+        pytest.skip("needs a GPU")
+    import paper_2508_15601_amd as tm
+    tm.load_library()
+    return tm
+
+
+def _say(msg):
+    print(msg, file=sys.stderr, flush=True)
+
+
+def _close(O, Oref):
+    o, r = O.astype(np.float64), Oref.astype(np.float64)
+    worst = float((np.abs(o - r) / (2e-3 + 5e-3 * np.abs(r))).max())
+    fro = float(np.linalg.norm(o - r) / max(np.linalg.norm(r), 1e-30))
+    return worst <= 1.0 and fro <= 2e-3, worst, fro
+
+
+def _dev(a):
+    import torch
+    return torch.from_numpy(np.ascontiguousarray(a)).cuda()
+
+
+@pytest.mark.parametrize("B,Hkv,T,chunks", [(1, 1, 32, [32]), (2, 3, 70, [40, 1, 1, 28]), (3, 2, 97, [97]), (2, 1, 33, [1] * 33)])
+def test_kv_append_bit_exact(tm, B, Hkv, T, chunks):
+    """Keys and values appended in chunks land in the cache layout with exactly the oracle's codes and pairs."""
+    import torch
+    _say(f"kv append B={B} Hkv={Hkv} T={T} chunks={chunks[:4]}")
+    _, K, V, _ = wa.draw(B, Hkv, Hkv, T, seed=T)
+    K[0, 0, 0, :] = 1.5                                   # a constant row: scale falls back to 1
+    V[-1, -1, -1, :64] = 0.0
+    cache = tm.tm_kv_create(B, Hkv, T)
+    cap = cache.capacity
+    tm.tm_kv_upload(cache, np.zeros(B * Hkv * cap * 128, np.uint8), np.zeros(B * Hkv * cap * 128, np.uint8),
+                    np.zeros(B * Hkv * cap * 2, np.uint32))
+    pos = 0
+    for n in chunks:
+        Kn = np.ascontiguousarray(K[:, :, pos:pos + n].transpose(0, 2, 1, 3))      # [B, n, Hkv, 128]
+        Vn = np.ascontiguousarray(V[:, :, pos:pos + n].transpose(0, 2, 1, 3))
+        tm.tm_kv_append(cache, _dev(Kn), _dev(Vn), torch.full((B,), pos, dtype=torch.int32, device="cuda"))
+        pos += n
+    kbuf, vbuf, szbuf = tm.tm_kv_download(cache)
+    Kq, Ks, Kz, Vq, Vs, Vz = oa.kv_cache_unpack(kbuf, vbuf, szbuf, B, Hkv, cap)
+    for got, want in zip((Kq, Ks, Kz), oa.kv_quantise(K)):
+        g, w = got[:, :, :T], want
+        assert np.array_equal(g.view(np.uint16) if g.dtype == np.float16 else g, w.view(np.uint16) if w.dtype == np.float16 else w)
+    for got, want in zip((Vq, Vs, Vz), oa.kv_quantise(V)):
+        g, w = got[:, :, :T], want
+        assert np.array_equal(g.view(np.uint16) if g.dtype == np.float16 else g, w.view(np.uint16) if w.dtype == np.float16 else w)
+    assert not Kq[:, :, T:].any() and not Vq[:, :, T:].any()                       # nothing written past the tokens
+    # tokens that would fall outside the cache are dropped
+    tm.tm_kv_append(cache, _dev(Kn), _dev(Vn), torch.full((B,), cap, dtype=torch.int32, device="cuda"))
+    k2, v2, s2 = tm.tm_kv_download(cache)
+    assert np.array_equal(k2, kbuf) and np.array_equal(v2, vbuf) and np.array_equal(s2, szbuf)
+    cache.close()
+
+
+ATTN_CASES = [
+    # B, Hq, Hkv, T, lens (None: drawn)
+    (1, 1, 1, 1, [1]),
+    (2, 4, 4, 31, None),
+    (2, 8, 2, 32, [32, 17]),
+    (3, 8, 1, 33, None),
+    (2, 16, 1, 100, None),
+    (1, 32, 8, 257, None),
+    (4, 12, 3, 1000, None),                # several blocks per wave
+    (1, 8, 2, 5000, [5000]),               # split context, merged by the second kernel
+    (2, 8, 8, 4100, [4100, 1300]),         # splits of which some are empty for the short sequence
+    (1, 64, 8, 640, None),
+]
+
+
+@pytest.mark.parametrize("B,Hq,Hkv,T,lens", ATTN_CASES)
+def test_attn_decode_against_oracle(tm, B, Hq, Hkv, T, lens):
+    import torch
+    _say(f"attn decode B={B} Hq={Hq} Hkv={Hkv} T={T} lens={lens}")
+    Q, K, V, drawn = wa.draw(B, Hq, Hkv, T, seed=B * 100 + Hq + T)
+    lens = np.array(lens, np.int32) if lens is not None else drawn
+    Kq, Ks, Kz = oa.kv_quantise(K)
+    Vq, Vs, Vz = oa.kv_quantise(V)
+    cache = tm.tm_kv_create(B, Hkv, T)
+    cap = cache.capacity
+    # the cache is filled by the library's own kernel; positions past T keep whatever the allocation held
+    tm.tm_kv_append(cache, _dev(np.ascontiguousarray(K.transpose(0, 2, 1, 3))), _dev(np.ascontiguousarray(V.transpose(0, 2, 1, 3))),
+                    torch.zeros(B, dtype=torch.int32, device="cuda"))
+    scale = 1.0 / np.sqrt(128.0)
+    outs = []
+    for _ in range(2):
+        O = torch.full((B, Hq, 128), float("nan"), dtype=torch.float16, device="cuda")
+        tm.tm_attn_decode(_dev(Q), cache, _dev(lens), O, scale, max_len=int(lens.max()))
+        torch.cuda.synchronize()
+        outs.append(O.cpu().numpy())
+    assert np.array_equal(outs[0].view(np.uint16), outs[1].view(np.uint16))        # run-to-run identical
+    Oref = oa.attn_decode(Q, Kq, Ks, Kz, Vq, Vs, Vz, lens, scale)
+    ok, worst, fro = _close(outs[0], Oref)
+    assert ok, (worst, fro)
+    cache.close()
+
+
+def test_attn_decode_special_cases(tm):
+    """Sharp softmax (one token takes all the weight), a sequence without tokens, cache bytes past the context that hold
+    NaN pairs, and max_len left at 0."""
+    import torch
+    _say("attn special cases")
+    B, Hq, Hkv, T = 2, 8, 2, 96
+    Q, K, V, _ = wa.draw(B, Hq, Hkv, T, seed=5)
+    Kq, Ks, Kz = oa.kv_quantise(K)
+    Vq, Vs, Vz = oa.kv_quantise(V)
+    Kd = oa.kv_dequant(Kq, Ks, Kz)
+    Q[0, :4] = (Kd[0, 0, 70] * 1.0).astype(np.float16)     # heads 0..3 (KV head 0) point at token 70
+    lens = np.array([80, 0], np.int32)
+    cache = tm.tm_kv_create(B, Hkv, T)
+    cap = cache.capacity
+    kbuf, vbuf, szbuf = wa.encode_cache(*[np.ascontiguousarray(a) for a in (Kq, Ks, Kz, Vq, Vs, Vz)])
+    sz = szbuf.reshape(B, Hkv, cap, 2).copy()
+    sz[:, :, 80:] = 0x7E007E00                              # NaN scale and zero-point past the context
+    tm.tm_kv_upload(cache, kbuf, vbuf, sz.reshape(-1))
+    O = torch.full((B, Hq, 128), float("nan"), dtype=torch.float16, device="cuda")
+    tm.tm_attn_decode(_dev(Q), cache, _dev(lens), O, 4.0)   # max_len = 0: the capacity
+    torch.cuda.synchronize()
+    O = O.cpu().numpy()
+    assert not O[1].any()                                   # no tokens: zeros
+    Oref = oa.attn_decode(Q[:1], Kq[:1], Ks[:1], Kz[:1], Vq[:1], Vs[:1], Vz[:1], lens[:1], 4.0)
+    ok, worst, fro = _close(O[:1], Oref)
+    assert ok, (worst, fro)
+    assert np.allclose(O[0, 0].astype(np.float64), oa.kv_dequant(Vq, Vs, Vz)[0, 0, 70], rtol=1e-2, atol=2e-3)
+    cache.close()
