@@ -1,7 +1,7 @@
 #!/usr/bin/env python3
 """Benchmark of the W4A16 GEMM hot path on one MI355X.
 
-    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload decode|mlp_decode|prefill|sweep|companion|moe|w8|pack|copy]
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload decode|mlp_decode|prefill|sweep|companion|moe|w8|attn|pack|copy]
                     [--sweep-out FILE] [--no-cpu-baseline] [--no-prefill]
 
 A "step" is one pass of the fused GEMM over every (layer, M) pair of the workload, weights already packed
@@ -304,6 +304,60 @@ def w8_table(tm, torch, wl, iters=100):
     return rows
 
 
+# Decode attention over an 8-bit KV cache in the head geometry of the 8B model of the paper's kernel benchmark (32 query
+# heads, 8 KV heads, head dimension 128): (batch, context length).  Cache contents are random codes with valid pairs.
+ATTN_SHAPES = [(1, 2048), (1, 8192), (1, 32768), (8, 2048), (8, 8192), (32, 2048), (32, 8192), (64, 4096), (128, 2048)]
+
+
+args_eager = [False]
+
+
+def attn_table(tm, torch, iters=50, q_heads=32, kv_heads=8, only=None):
+    import numpy as np
+    rows = []
+    rng = np.random.default_rng(0)
+    for B, T in ATTN_SHAPES:
+        if only is not None and (B, T) != only:
+            continue
+        per_cache = B * kv_heads * T * (2 * 128 + 8)
+        copies = max(2, -(-ROTATE_BYTES // per_cache))
+        caches = []
+        for _ in range(copies):
+            c = tm.tm_kv_create(B, kv_heads, T)
+            n = B * kv_heads * c.capacity
+            pairs = (rng.uniform(0.005, 0.05, 2 * n).astype(np.float16).view(np.uint16).astype(np.uint32)
+                     | (rng.integers(0, 256, 2 * n).astype(np.float16).view(np.uint16).astype(np.uint32) << 16))
+            k, v, p, cb, pb = tm.tm_kv_raw(c)
+            for ptr in (k, v):                          # random codes generated on the device
+                t = torch.randint(0, 256, (cb,), dtype=torch.uint8, device="cuda")
+                tm.tm_bench_copy_raw(ptr, t.data_ptr(), cb)
+            t = torch.from_numpy(pairs.view(np.uint8)).cuda()
+            tm.tm_bench_copy_raw(p, t.data_ptr(), pb)
+            torch.cuda.synchronize()
+            caches.append(c)
+        Q = torch.randn((B, q_heads, 128), device="cuda").to(torch.float16)
+        O = torch.empty_like(Q)
+        lens = torch.full((B,), T, dtype=torch.int32, device="cuda")
+        turn = [0]
+
+        def step():
+            tm.tm_attn_decode(Q, caches[turn[0] % copies], lens, O, 0.08838834764831845, max_len=T)
+            turn[0] += 1
+
+        ev_ms, _ = time_steps(torch, step, iters, 5, graph_steps=0 if args_eager[0] else iters)
+        t = ev_ms / iters * 1e-3
+        bytes_ = per_cache + 2 * B * q_heads * 128 * 2
+        rows.append({"batch": B, "context": T, "q_heads": q_heads, "kv_heads": kv_heads, "kv_bits": 8, "us": t * 1e6,
+                     "GBps": bytes_ / t / 1e9, "hbm_frac": bytes_ / t / 1e9 / HBM_PEAK_GBPS, "cache_copies": copies})
+        log(f"attn decode KV8  batch {B:4d} context {T:6d}  {t * 1e6:9.2f} us  {bytes_ / t / 1e9:7.0f} GB/s "
+            f"({100 * bytes_ / t / 1e9 / HBM_PEAK_GBPS:4.1f} % of HBM peak)  {bytes_ / 1e6:8.1f} MB per call")
+        for c in caches:
+            c.close()
+        del caches
+        torch.cuda.empty_cache()
+    return rows
+
+
 def cpu_baseline(wl, layers, min_s=5.0, budget_s=25.0):
     """The oracle as it stands, timed on this host's cores over the same workload: whole passes over every
     (layer, M) pair are repeated until at least `min_s` seconds have been spent; a single GEMM too large for
@@ -339,7 +393,7 @@ def main():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=200)
     ap.add_argument("--warmup", type=int, default=20)
-    ap.add_argument("--workload", default="decode", choices=sorted(WORKLOADS) + ["sweep", "copy", "companion", "pack", "moe", "w8"])
+    ap.add_argument("--workload", default="decode", choices=sorted(WORKLOADS) + ["sweep", "copy", "companion", "pack", "moe", "w8", "attn"])
     ap.add_argument("--sweep-out", default=None, help="with --workload sweep: write the per-shape table here (JSON)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-prefill", action="store_true", help="skip the prefill companion measurement")
@@ -402,6 +456,17 @@ def main():
             rows.append({"layout": layout, "ms_per_pack_call": ms})
             log(f"layout {layout}: {ms:.3f} ms per pack call (allocation + two kernels + free)")
         print(json.dumps({"metric": "offline pack", "K": K, "N": N, "group": g, "steps": args.steps, "rows": rows}))
+        return
+
+    if args.workload == "attn":
+        only = tuple(int(v) for v in args.only.split(":")) if args.only else None
+        args_eager[0] = args.eager
+        table = attn_table(tm, torch, iters=min(args.steps, 50), only=only)
+        if args.sweep_out:
+            os.makedirs(os.path.dirname(os.path.abspath(args.sweep_out)), exist_ok=True)
+            json.dump(table, open(args.sweep_out, "w"), indent=1)
+        print(json.dumps({"metric": "decode attention over an 8-bit KV cache: effective HBM GB/s", "workload": "attn",
+                          "rows": table}))
         return
 
     if args.workload == "w8":

@@ -13,7 +13,7 @@
  *   Q branch (Sec. 4.2, adaptive head alignment): the query fragments are arranged once per call so that their
  *     per-lane dimension order equals the order in which a lane receives the low-bit key bytes; no key is reshuffled.
  *   KV branch (Sec. 4.4, KV memory loading pipeline; Sec. 4.3): key and value codes are loaded straight into matrix-core
- *     operand order, one block ahead of the block being multiplied, converted by bit manipulation; scale and zero-point
+ *     operand order, two blocks ahead of the block being multiplied, converted by bit manipulation; scale and zero-point
  *     are applied to the scores and probabilities (per token), never to the 128 values of a token.
  *
  * Conventions as in tm_w4.h: plain C ABI, DEVICE pointers unless marked host, fp16 as uint16_t bit patterns, nothing
@@ -36,11 +36,14 @@ typedef struct tm_kv_cache tm_kv_cache;   /* opaque; owns its device buffers */
  * (bits must be 8).  Allocates 2 * batch*kv_heads*capacity*128 bytes of codes, 8 bytes of scale/zero pairs per token and
  * head, and the split workspace of tm_attn_decode (a few MiB).  Contents start undefined.  NULL on error.
  *
- * Layout (also what tm_kv_raw exposes); bh = b*kv_heads + h:
- *   K codes   byte (bh*capacity + t)*128 + d
- *   V codes   blocks of 32 tokens (4096 bytes), block bh*(capacity/32) + t/32; token u = t % 32, dimension d at byte
- *             ((c*4 + hh)*8 + i)*8 + e,  c = d % 16, i = d / 16, hh = (u % 16) / 4, e = u % 4 + 4*(u / 16)
- *             (a lane's 64 consecutive bytes are its operand of the P*V product for all eight 16-row tiles)
+ * Layout (also what tm_kv_raw exposes); bh = b*kv_heads + h.  The cache is kept in matrix-core operand order (the
+ * hardware-aware packing of Sec. 4.1 applied to the cache): codes in blocks of 32 tokens x 128 dimensions (4096 bytes),
+ * block bh*(capacity/32) + t/32, token u = t % 32, such that every load instruction of a wave reads 1 KiB of consecutive
+ * bytes and each lane receives exactly its operand bytes:
+ *   K block   dimension d at byte ((j*2 + half)*64 + 16*hh + c)*16 + x,  j = u / 16, c = u % 16, hh = d / 32,
+ *             half = (d % 32) / 16, x = d % 16
+ *   V block   dimension d at byte ((i/2)*64 + 16*hh + c)*16 + (i % 2)*8 + e,  c = d % 16, i = d / 16,
+ *             hh = (u % 16) / 4, e = u % 4 + 4*(u / 16)
  *   pairs     u32 word (bh*capacity + t)*2 + {0: K, 1: V} = scale bits | zero bits << 16
  */
 TM_API tm_kv_cache* tm_kv_create(int batch, int kv_heads, int capacity, int bits);

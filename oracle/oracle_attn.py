@@ -66,28 +66,32 @@ def attn_decode(Q, Kq, Ks, Kz, Vq, Vs, Vz, lens, scale: float) -> np.ndarray:
 
 
 def kv_cache_unpack(kbuf, vbuf, szbuf, B: int, Hkv: int, cap: int, bits: int = 8):
-    """Inverse of the library's cache layout (8-bit codes), written from its specification:
-      K codes:  byte ((b*Hkv + h)*cap + t)*128 + d                                   (row-major, one 128-byte row per token)
-      V codes:  blocks of 32 tokens, 4096 bytes each, block ((b*Hkv + h)*(cap/32) + t/32); inside a block the byte of
-                token u = t % 32 and dimension d sits at ((c*4 + hh)*8 + i)*8 + e with c = d % 16, i = d / 16,
+    """Inverse of the library's cache layout (8-bit codes), written from its specification.  Codes live in blocks of
+    32 tokens x 128 dimensions (4096 bytes), block index (b*Hkv + h)*(cap/32) + t/32, token u = t % 32 inside it:
+      K block:  byte ((j*2 + half)*64 + 16*hh + c)*16 + x   for dimension d,  j = u / 16, c = u % 16, hh = d / 32,
+                half = (d % 32) / 16, x = d % 16
+      V block:  byte ((i/2)*64 + 16*hh + c)*16 + (i % 2)*8 + e   for dimension d,  c = d % 16, i = d / 16,
                 hh = (u % 16) / 4, e = u % 4 + 4*(u / 16)
-      scale/zero: u32 words, K pairs then V pairs: word ((b*Hkv + h)*cap + t)*2 + {0: K, 1: V} = scale bits | zero bits << 16
+      scale/zero: u32 words, word ((b*Hkv + h)*cap + t)*2 + {0: K, 1: V} = scale bits | zero bits << 16
     -> (Kq, Ks, Kz, Vq, Vs, Vz) in the plain [B, Hkv, cap, (D)] arrangement."""
     assert bits == 8 and cap % 32 == 0
     D = HEAD_DIM
     kbuf = np.asarray(kbuf, np.uint8).reshape(-1)
     vbuf = np.asarray(vbuf, np.uint8).reshape(-1)
     szbuf = np.asarray(szbuf, np.uint32).reshape(-1)
-    Kq = kbuf.reshape(B, Hkv, cap, D).copy()
+    Kq = np.empty((B, Hkv, cap, D), np.uint8)
     Vq = np.empty((B, Hkv, cap, D), np.uint8)
+    bh = np.arange(B)[:, None] * Hkv + np.arange(Hkv)[None, :]
     for t in range(cap):
         u = t % 32
-        hh, e = (u % 16) // 4, u % 4 + 4 * (u // 16)
+        blk = bh * (cap // 32) + t // 32
         for d in range(D):
-            c, i = d % 16, d // 16
-            off = ((c * 4 + hh) * 8 + i) * 8 + e
-            blk = (np.arange(B)[:, None] * Hkv + np.arange(Hkv)[None, :]) * (cap // 32) + t // 32
-            Vq[:, :, t, d] = vbuf[blk * 4096 + off]
+            koff = (((u // 16) * 2 + (d % 32) // 16) * 64 + 16 * (d // 32) + u % 16) * 16 + d % 16
+            Kq[:, :, t, d] = kbuf[blk * 4096 + koff]
+            i, c = d // 16, d % 16
+            hh, e = (u % 16) // 4, u % 4 + 4 * (u // 16)
+            voff = ((i // 2) * 64 + 16 * hh + c) * 16 + (i % 2) * 8 + e
+            Vq[:, :, t, d] = vbuf[blk * 4096 + voff]
     sz = szbuf.reshape(B, Hkv, cap, 2)
     s = (sz & 0xFFFF).astype(np.uint16).view(np.float16)
     z = (sz >> 16).astype(np.uint16).view(np.float16)

@@ -458,6 +458,11 @@ def tm_kv_raw(cache: KvCache):
     return k.value, v.value, p.value, cb.value, pb.value
 
 
+def tm_bench_copy_raw(dst_ptr: int, src_ptr: int, nbytes: int, stream=None):
+    """Plain device copy between raw device addresses (multiples of 16 bytes)."""
+    _check(load_library().tm_bench_copy(ctypes.c_void_p(dst_ptr), ctypes.c_void_p(src_ptr), nbytes, _stream_ptr(stream)))
+
+
 def tm_kv_download(cache: KvCache):
     """Host copies of the cache's buffers: (K codes uint8, V codes uint8, pairs uint32), flat."""
     import numpy as np

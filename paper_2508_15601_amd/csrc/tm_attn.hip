@@ -14,9 +14,12 @@
 //     to four scores and eight probabilities per lane and block instead of to 2 x 128 code values per token.  The codes
 //     enter the matrix cores as 1024 + q (one byte permute per two codes); the bias and the zero-point leave through
 //     one fp32 term per query head.
-//   - K, V and their scale/zero pairs of the next 32-token block are in flight (registers) while the current block is
-//     multiplied; a CTA's waves take blocks round-robin and meet in LDS at the end; long contexts are split across
-//     CTAs and merged by a second, tiny kernel.
+//   - The cache itself is stored in operand order (blocks of 32 tokens x 128 dimensions), the hardware-aware packing of
+//     the weights applied to K and V: every load instruction of a wave reads 1 KiB of consecutive bytes (row-major keys
+//     had every instruction touch half of sixteen 128-byte rows: 4.1 instead of 5.7 TB/s).
+//   - The codes of the next two 32-token blocks are in flight in registers while the current block is multiplied; the
+//     blocks' scale/zero words go through a small per-wave LDS ring (direct-to-LDS loads); a CTA's waves take blocks
+//     round-robin and meet in LDS at the end; long contexts are split across CTAs and merged by a second, tiny kernel.
 #include "tm_w4_host.h"
 
 namespace tmw4 {
@@ -65,18 +68,25 @@ __global__ __launch_bounds__(64) void kv_append_kernel(AttnCache kv, const uint1
         const float zf = fminf(fmaxf(rintf(-mn / sf), 0.0f), 255.0f);
         const uint32_t q0 = (uint32_t)fminf(fmaxf(rintf(x0 / sf) + zf, 0.0f), 255.0f);
         const uint32_t q1 = (uint32_t)fminf(fmaxf(rintf(x1 / sf) + zf, 0.0f), 255.0f);
+        const int u = t & 31;
+        uint8_t* blk = (which ? kv.v : kv.k) + (bh * (kv.cap / 32) + (t >> 5)) * 4096;
         if (which == 0) {
-            uint8_t* row = kv.k + (bh * kv.cap + t) * kHeadDim;
-            row[lane] = (uint8_t)q0;
-            row[lane + 64] = (uint8_t)q1;
+            // dimension d -> byte ((j*2 + half)*64 + 16*hh + c)*16 + x, j = u/16, c = u%16, hh = d/32, half = (d%32)/16
+            const int j = u >> 4, c = u & 15;
+#pragma unroll
+            for (int k = 0; k < 2; ++k) {
+                const int d = lane + 64 * k;
+                blk[((j * 2 + ((d & 31) >> 4)) * 64 + 16 * (d >> 5) + c) * 16 + (d & 15)] = (uint8_t)(k ? q1 : q0);
+            }
         } else {
-            const int u = t & 31;
+            // dimension d = 16*i + c -> byte ((i/2)*64 + 16*hh + c)*16 + (i%2)*8 + e, hh = (u%16)/4, e = u%4 + 4*(u/16)
             const int hh = (u & 15) >> 2, e = (u & 3) + 4 * (u >> 4);
-            uint8_t* blk = kv.v + (bh * (kv.cap / 32) + (t >> 5)) * 4096;
-            // dimension d = 16*i + c  ->  byte ((c*4 + hh)*8 + i)*8 + e
-            const int c = lane & 15, i0 = lane >> 4;        // d = lane: i = lane / 16; d = lane + 64: i + 4
-            blk[((c * 4 + hh) * 8 + i0) * 8 + e] = (uint8_t)q0;
-            blk[((c * 4 + hh) * 8 + i0 + 4) * 8 + e] = (uint8_t)q1;
+            const int c = lane & 15;
+#pragma unroll
+            for (int k = 0; k < 2; ++k) {
+                const int i = (lane >> 4) + 4 * k;
+                blk[((i >> 1) * 64 + 16 * hh + c) * 16 + (i & 1) * 8 + e] = (uint8_t)(k ? q1 : q0);
+            }
         }
         if (lane == 0) {
             const _Float16 z16 = (_Float16)zf;
@@ -87,28 +97,42 @@ __global__ __launch_bounds__(64) void kv_append_kernel(AttnCache kv, const uint1
 }
 
 // ------------------------------------------------------------------------------------------------ decode attention
+// The codes of a block travel in registers (they are the in-flight memory of the pipeline: two blocks ahead).  The 64
+// scale/zero words of a block would cost as many registers per lane as its 8 KiB of codes, so they go through LDS
+// instead: one direct-to-LDS load per block and wave (lane l fetches word l) into a slot private to the wave.
 struct BlockRegs {
     u32x4 k[2][2];      // two 16-token tiles: 32 key bytes of the lane's token (dimensions 32h .. 32h+31)
-    u32x4 sz[2][2];     // per tile: (K pair, V pair) of the lane's four tokens 4h .. 4h+3
     u32x4 v[4];         // 64 value bytes: eight 16-row tiles x the lane's eight tokens
 };
 
-__device__ __forceinline__ void load_block(BlockRegs& r, const AttnCache& kv, size_t bh, int blk, int lane)
+__device__ __forceinline__ __amdgpu_buffer_rsrc_t make_rsrc(const void* p, uint32_t bytes)
 {
-    const int c = lane & 15, h = lane >> 4;
+    return __builtin_amdgcn_make_buffer_rsrc(const_cast<void*>(p), 0, (int)bytes, 0x00020000);
+}
+
+__device__ __forceinline__ void load_block(BlockRegs& r, uint32_t* sz_slot, const __amdgpu_buffer_rsrc_t& sz_rsrc,
+                                           const AttnCache& kv, size_t bh, int blk, int lane)
+{
     const int t0 = blk * 32;
+    // (the host pass of the compiler only needs the kernel's signature; it cannot express the LDS pointer)
+#if defined(__HIP_DEVICE_COMPILE__)
+    __builtin_amdgcn_raw_ptr_buffer_load_lds(sz_rsrc, (__attribute__((address_space(3))) void*)sz_slot, 4, lane * 4,
+                                             t0 * 8, 0, 0);
+#else
+    (void)sz_slot;
+    (void)sz_rsrc;
+    (void)t0;
+#endif
+    // every load instruction of the wave reads 1 KiB of consecutive bytes: the blocks are stored in operand order
+    const uint8_t* kp = kv.k + (bh * (kv.cap / 32) + blk) * 4096 + lane * 16;
 #pragma unroll
     for (int j = 0; j < 2; ++j) {
-        const uint8_t* kp = kv.k + (bh * kv.cap + t0 + 16 * j + c) * kHeadDim + 32 * h;
-        r.k[j][0] = __builtin_nontemporal_load((const u32x4*)kp);
-        r.k[j][1] = __builtin_nontemporal_load((const u32x4*)(kp + 16));
-        const uint32_t* sp = kv.sz + (bh * kv.cap + t0 + 16 * j + 4 * h) * 2;
-        r.sz[j][0] = *(const u32x4*)sp;
-        r.sz[j][1] = *(const u32x4*)(sp + 4);
+        r.k[j][0] = __builtin_nontemporal_load((const u32x4*)(kp + (j * 2 + 0) * 1024));
+        r.k[j][1] = __builtin_nontemporal_load((const u32x4*)(kp + (j * 2 + 1) * 1024));
     }
-    const uint8_t* vp = kv.v + (bh * (kv.cap / 32) + blk) * 4096 + (c * 4 + h) * 64;
+    const uint8_t* vp = kv.v + (bh * (kv.cap / 32) + blk) * 4096 + lane * 16;
 #pragma unroll
-    for (int i = 0; i < 4; ++i) r.v[i] = __builtin_nontemporal_load((const u32x4*)(vp + 16 * i));
+    for (int i = 0; i < 4; ++i) r.v[i] = __builtin_nontemporal_load((const u32x4*)(vp + i * 1024));
 }
 
 // Running state of one wave (per query head m = lane % 16; m_run is equal in the four lanes that share an m, l_run and
@@ -117,8 +141,8 @@ struct SoftmaxState {
     float m_run, l_run, corr;
 };
 
-__device__ __forceinline__ void process_block(const BlockRegs& r, const f16x8 (&qf)[4], float qsum, int t0, int len,
-                                              int lane, SoftmaxState& st, f32x4 (&acc)[8])
+__device__ __forceinline__ void process_block(const BlockRegs& r, const uint32_t* sz_slot, const f16x8 (&qf)[4],
+                                              float qsum, int t0, int len, int lane, SoftmaxState& st, f32x4 (&acc)[8])
 {
     const int h = lane >> 4;
     // S^T for the two 16-token tiles: rows = tokens, columns = query heads
@@ -131,10 +155,13 @@ __device__ __forceinline__ void process_block(const BlockRegs& r, const f16x8 (&
         d = mfma16x16x32(biased8_w8(r.k[j][0].z, r.k[j][0].w), qf[1], d);
         d = mfma16x16x32(biased8_w8(r.k[j][1].x, r.k[j][1].y), qf[2], d);
         d = mfma16x16x32(biased8_w8(r.k[j][1].z, r.k[j][1].w), qf[3], d);
+        // (K pair, V pair) of the lane's four tokens 16j + 4h .. +3: eight consecutive words of the slot
+        const u32x4 p0 = *(const u32x4*)(sz_slot + 32 * j + 8 * h);
+        const u32x4 p1 = *(const u32x4*)(sz_slot + 32 * j + 8 * h + 4);
 #pragma unroll
         for (int rr = 0; rr < 4; ++rr) {
-            const uint32_t kw = rr < 2 ? r.sz[j][0][2 * rr] : r.sz[j][1][2 * (rr - 2)];
-            const uint32_t vw = rr < 2 ? r.sz[j][0][2 * rr + 1] : r.sz[j][1][2 * (rr - 2) + 1];
+            const uint32_t kw = rr < 2 ? p0[2 * rr] : p1[2 * (rr - 2)];
+            const uint32_t vw = rr < 2 ? p0[2 * rr + 1] : p1[2 * (rr - 2) + 1];
             const f16x2 kp = as_f16x2(kw), vp = as_f16x2(vw);
             const bool live = t0 + 16 * j + 4 * h + rr < len;
             // sum_d (1024 + q_d) Q_d  -  (1024 + z) sum_d Q_d  =  sum_d (q_d - z) Q_d ; times the token's scale
@@ -164,25 +191,35 @@ __device__ __forceinline__ void process_block(const BlockRegs& r, const f16x8 (&
         }
     st.l_run = st.l_run * alpha + psum;
     st.corr = st.corr * alpha + csum;
+    // the running maximum seldom moves after the first blocks: rescale only when some query head needs it
+    if (__any(alpha != 1.0f)) {
+#pragma unroll
+        for (int i = 0; i < 8; ++i) acc[i] *= alpha;
+    }
     // O^T += V^T P'^T : rows = dimensions (eight 16-row tiles), k = the 32 tokens of the block
 #pragma unroll
     for (int i = 0; i < 8; ++i) {
         const u32x4 w = r.v[i >> 1];
         const f16x8 a = (i & 1) ? biased8_w8(w.z, w.w) : biased8_w8(w.x, w.y);
-        acc[i] = mfma16x16x32(a, pb, acc[i] * alpha);
+        acc[i] = mfma16x16x32(a, pb, acc[i]);
     }
 }
 
 // grid (kv heads, batch, splits); 256 threads.  Partial layout per (b, h, split): m[16], l[16], out[128][16] floats.
 constexpr int kPartialFloats = 32 + kHeadDim * 16;
 
-__global__ __launch_bounds__(256) void attn_decode_kernel(AttnCache kv, const uint16_t* __restrict__ Q,
+__global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))) void attn_decode_kernel(AttnCache kv, const uint16_t* __restrict__ Q,
                                                           const int32_t* __restrict__ lens, uint16_t* __restrict__ O,
                                                           int q_heads, float scale_log2e, int blocks_per_split,
                                                           int splits)
 {
     __shared__ float sm_ml[4][2][16];
     __shared__ float sm_out[4][8][4][64];
+    // scale/zero words of the blocks in flight: [wave][64 words]; one array per ring slot so that the compiler can tell
+    // which direct-to-LDS load a read depends on
+    __shared__ __attribute__((aligned(16))) uint32_t sz_ring0[4][64];
+    __shared__ __attribute__((aligned(16))) uint32_t sz_ring1[4][64];
+    __shared__ __attribute__((aligned(16))) uint32_t sz_ring2[4][64];
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int c = lane & 15, h = lane >> 4;
@@ -219,18 +256,34 @@ __global__ __launch_bounds__(256) void attn_decode_kernel(AttnCache kv, const ui
 #pragma unroll
     for (int i = 0; i < 8; ++i) acc[i] = f32x4{0.f, 0.f, 0.f, 0.f};
 
-    // KV memory loading pipeline: the next block of this wave is in flight while the current one is multiplied
-    BlockRegs ra, rb;
+    // KV memory loading pipeline: the next two blocks of this wave are in flight while the current one is multiplied
+    // (three register sets and three LDS slots, rotated by unrolling; with one block ahead the waves spent half their
+    // time waiting for memory).  Loads are unconditional - past the end of the wave's range they re-fetch its last
+    // block - so that the loop body is straight-line code with a known number of loads in flight.
+    const __amdgpu_buffer_rsrc_t sz_rsrc = make_rsrc(kv.sz + bh * kv.cap * 2, (uint32_t)kv.cap * 8u);
+    uint32_t* const z0 = sz_ring0[wave];
+    uint32_t* const z1 = sz_ring1[wave];
+    uint32_t* const z2 = sz_ring2[wave];
+    BlockRegs r0, r1, r2;
     int blk = blk0 + wave;
-    if (blk < blk1) load_block(ra, kv, bh, blk, lane);
-    while (blk < blk1) {
-        if (blk + 4 < blk1) load_block(rb, kv, bh, blk + 4, lane);
-        process_block(ra, qf, qsum, blk * 32, len, lane, st, acc);
-        blk += 4;
-        if (blk >= blk1) break;
-        if (blk + 4 < blk1) load_block(ra, kv, bh, blk + 4, lane);
-        process_block(rb, qf, qsum, blk * 32, len, lane, st, acc);
-        blk += 4;
+    if (blk < blk1) {
+        const int last = blk + ((blk1 - 1 - blk) / 4) * 4;      // this wave's last block
+        load_block(r0, z0, sz_rsrc, kv, bh, blk, lane);
+        load_block(r1, z1, sz_rsrc, kv, bh, min(blk + 4, last), lane);
+        while (true) {
+            load_block(r2, z2, sz_rsrc, kv, bh, min(blk + 8, last), lane);
+            process_block(r0, z0, qf, qsum, blk * 32, len, lane, st, acc);
+            blk += 4;
+            if (blk > last) break;
+            load_block(r0, z0, sz_rsrc, kv, bh, min(blk + 8, last), lane);
+            process_block(r1, z1, qf, qsum, blk * 32, len, lane, st, acc);
+            blk += 4;
+            if (blk > last) break;
+            load_block(r1, z1, sz_rsrc, kv, bh, min(blk + 8, last), lane);
+            process_block(r2, z2, qf, qsum, blk * 32, len, lane, st, acc);
+            blk += 4;
+            if (blk > last) break;
+        }
     }
 
     // the four lanes of a query head add their partial sums; the waves meet in LDS
@@ -288,28 +341,53 @@ __global__ __launch_bounds__(256) void attn_decode_kernel(AttnCache kv, const ui
     }
 }
 
-// Merge of the context splits: grid (kv heads, batch), 256 threads; thread -> (dimension pair, query head).
+// Merge of the context splits: grid (kv heads, batch, 8 chunks of 16 dimensions), 256 threads = 16 query heads x 16.
+// Phase 1 (every CTA, all threads): running maximum and denominator over the splits, four splits per thread, reduced
+// through LDS; the per-split factors exp2(m_s - M) / L stay in LDS.  Phase 2: thread (m, dd) sums dimension
+// 16*chunk + dd of query head m over the splits.
 __global__ __launch_bounds__(256) void attn_merge_kernel(AttnCache kv, uint16_t* __restrict__ O, int q_heads, int splits)
 {
-    const int hk = blockIdx.x, b = blockIdx.y;
+    __shared__ float red[16][16];
+    __shared__ float fac[64][16];                  // splits <= 64
+    const int hk = blockIdx.x, b = blockIdx.y, chunk = blockIdx.z;
     const int G = q_heads / kv.heads;
     const size_t bh = (size_t)b * kv.heads + hk;
     const float* base = kv.partial + (size_t)bh * splits * kPartialFloats;
-    const int m = threadIdx.x & 15;
+    const int m = threadIdx.x & 15, g = threadIdx.x >> 4;
+    float ms[4], ls[4];
+    float mx = kNegBig;
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+        const int s = g + 16 * i;
+        ms[i] = s < splits ? base[(size_t)s * kPartialFloats + m] : kNegBig;
+        ls[i] = s < splits ? base[(size_t)s * kPartialFloats + 16 + m] : 0.f;
+        mx = fmaxf(mx, ms[i]);
+    }
+    red[g][m] = mx;
+    __syncthreads();
     float M = kNegBig;
-    for (int s = 0; s < splits; ++s) M = fmaxf(M, base[(size_t)s * kPartialFloats + m]);
+#pragma unroll
+    for (int i = 0; i < 16; ++i) M = fmaxf(M, red[i][m]);
+    __syncthreads();
+    float part = 0.f;
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+        const float f = exp2f(ms[i] - M);
+        part += ls[i] * f;
+        if (g + 16 * i < splits) fac[g + 16 * i][m] = f;
+    }
+    red[g][m] = part;
+    __syncthreads();
     float L = 0.f;
-    for (int s = 0; s < splits; ++s) L += base[(size_t)s * kPartialFloats + 16 + m] * exp2f(base[(size_t)s * kPartialFloats + m] - M);
+#pragma unroll
+    for (int i = 0; i < 16; ++i) L += red[i][m];
     const float inv = L > 0.f ? 1.0f / L : 0.f;
     if (m >= G) return;
-    for (int d = threadIdx.x >> 4; d < kHeadDim; d += 16) {
-        float v = 0.f;
-        for (int s = 0; s < splits; ++s) {
-            const float* p = base + (size_t)s * kPartialFloats;
-            v += p[32 + d * 16 + m] * exp2f(p[m] - M);
-        }
-        O[((size_t)b * q_heads + (size_t)hk * G + m) * kHeadDim + d] = f32_to_f16_bits(v * inv);
-    }
+    const int d = 16 * chunk + g;
+    float v = 0.f;
+#pragma unroll 8
+    for (int s = 0; s < splits; ++s) v += base[(size_t)s * kPartialFloats + 32 + d * 16 + m] * fac[s][m];
+    O[((size_t)b * q_heads + (size_t)hk * G + m) * kHeadDim + d] = f32_to_f16_bits(v * inv);
 }
 
 }  // namespace
@@ -342,7 +420,7 @@ hipError_t launch_attn_decode(const AttnCache& kv, const uint16_t* Q, const int3
                        scale_log2e, bps, splits);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess || splits == 1) return e;
-    hipLaunchKernelGGL(attn_merge_kernel, dim3(kv.heads, kv.batch), dim3(256), 0, stream, kv, O, q_heads, splits);
+    hipLaunchKernelGGL(attn_merge_kernel, dim3(kv.heads, kv.batch, 8), dim3(256), 0, stream, kv, O, q_heads, splits);
     return hipGetLastError();
 }
 

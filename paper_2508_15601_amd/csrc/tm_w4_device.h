@@ -47,8 +47,8 @@ struct GroupedParams {
 
 // Quantised KV cache of the attention kernels: 8-bit codes, one scale/zero pair per token and head.
 struct AttnCache {
-    uint8_t* k;          // [batch*heads][cap][128] codes, row-major
-    uint8_t* v;          // [batch*heads][cap/32] blocks of 4096 bytes in P*V operand order
+    uint8_t* k;          // [batch*heads][cap/32] blocks of 4096 bytes in K*Q^T operand order
+    uint8_t* v;          // [batch*heads][cap/32] blocks of 4096 bytes in V^T*P^T operand order
     uint32_t* sz;        // [batch*heads][cap][2] scale | zero << 16: K pair, V pair
     float* partial;      // split workspace: [batch*heads][max_splits] x (m[16], l[16], out[128][16])
     int batch, heads, cap, max_splits;

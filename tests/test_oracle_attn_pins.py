@@ -89,8 +89,14 @@ def test_cache_layout_inverse_against_generator_encoder():
     out = oa.kv_cache_unpack(kbuf, vbuf, szbuf, B, Hkv, cap)
     for a, b in zip(out, (Kq, s[0], z[0], Vq, s[1], z[1])):
         assert np.array_equal(a.view(np.uint16) if a.dtype == np.float16 else a, b.view(np.uint16) if b.dtype == np.float16 else b)
-    # hand-placed bytes: token 21 (u = 21: hh = 1, e = 1 + 4 = 5), dimension 35 (c = 3, i = 2) of block 0
-    vb = np.zeros(B * Hkv * cap * 128, np.uint8)
-    vb[((3 * 4 + 1) * 8 + 2) * 8 + 5] = 77
-    _, _, _, Vu, _, _ = oa.kv_cache_unpack(np.zeros_like(vb), vb, np.zeros(B * Hkv * cap * 2, np.uint32), B, Hkv, cap)
+    # hand-placed bytes in block 0: value of token 21 (u = 21: hh = 1, e = 1 + 4 = 5), dimension 35 (c = 3, i = 2):
+    # ((2/2)*64 + 16*1 + 3)*16 + 0*8 + 5; key of token 21 (j = 1, c = 5), dimension 83 (hh = 2, half = 1, x = 3):
+    # ((1*2 + 1)*64 + 16*2 + 5)*16 + 3
+    n = B * Hkv * cap * 128
+    vb = np.zeros(n, np.uint8)
+    vb[(64 + 16 + 3) * 16 + 5] = 77
+    kb = np.zeros(n, np.uint8)
+    kb[(3 * 64 + 32 + 5) * 16 + 3] = 99
+    Ku, _, _, Vu, _, _ = oa.kv_cache_unpack(kb, vb, np.zeros(B * Hkv * cap * 2, np.uint32), B, Hkv, cap)
     assert Vu[0, 0, 21, 35] == 77 and Vu.sum() == 77
+    assert Ku[0, 0, 21, 83] == 99 and Ku.sum() == 99

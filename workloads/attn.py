@@ -2,10 +2,10 @@
 shapes of the grouped-query-attention models the paper evaluates (head dimension 128), per-sequence context lengths, and
 the byte-level encoder of the cache layout the library reads (an input *format*, no arithmetic of the method).
 
-The cache layout (8-bit codes), per sequence b and KV head h, capacity cap tokens (a multiple of 32):
-  K codes   row-major: byte ((b*Hkv + h)*cap + t)*128 + d
-  V codes   blocks of 32 tokens x 128 dimensions (4096 bytes); inside a block, token u = t % 32 and dimension d sit at
-            ((c*4 + hh)*8 + i)*8 + e  with  c = d % 16, i = d / 16, hh = (u % 16) / 4, e = u % 4 + 4*(u / 16)
+The cache layout (8-bit codes), per sequence b and KV head h, capacity cap tokens (a multiple of 32): codes in blocks of
+32 tokens x 128 dimensions (4096 bytes each, block (b*Hkv + h)*(cap/32) + t/32), token u = t % 32:
+  K block   byte ((j*2 + half)*64 + 16*hh + c)*16 + x,  j = u / 16, c = u % 16, hh = d / 32, half = (d % 32) / 16, x = d % 16
+  V block   byte ((i/2)*64 + 16*hh + c)*16 + (i % 2)*8 + e,  c = d % 16, i = d / 16, hh = (u % 16) / 4, e = u % 4 + 4*(u / 16)
   scale/zero words  u32 [(b*Hkv + h)*cap + t][2]: K pair, V pair; scale bits | zero bits << 16
 """
 from __future__ import annotations
@@ -29,10 +29,12 @@ def encode_cache(Kq, Ks, Kz, Vq, Vs, Vz):
     the library's cache layout, written with reshapes."""
     B, Hkv, cap, D = Kq.shape
     assert D == 128 and cap % 32 == 0
-    kbuf = np.ascontiguousarray(Kq).reshape(-1)
-    # token u = 16*e_hi + 4*hh + e_lo ; e = e_lo + 4*e_hi ; d = 16*i + c  ->  [blk][c][hh][i][e_hi][e_lo]
-    v = Vq.reshape(B, Hkv, cap // 32, 2, 4, 4, 8, 16)            # [b,h,blk,e_hi,hh,e_lo,i,c]
-    vbuf = np.ascontiguousarray(v.transpose(0, 1, 2, 7, 4, 6, 3, 5)).reshape(-1)
+    # K: token u = 16*j + c ; d = 32*hh + 16*half + x  ->  [blk][j][half][hh][c][x]
+    k = Kq.reshape(B, Hkv, cap // 32, 2, 16, 4, 2, 16)           # [b,h,blk,j,c,hh,half,x]
+    kbuf = np.ascontiguousarray(k.transpose(0, 1, 2, 3, 6, 5, 4, 7)).reshape(-1)
+    # V: token u = 16*e_hi + 4*hh + e_lo ; e = e_lo + 4*e_hi ; d = 16*(2*i2 + i_lo) + c  ->  [blk][i2][hh][c][i_lo][e_hi][e_lo]
+    v = Vq.reshape(B, Hkv, cap // 32, 2, 4, 4, 4, 2, 16)         # [b,h,blk,e_hi,hh,e_lo,i2,i_lo,c]
+    vbuf = np.ascontiguousarray(v.transpose(0, 1, 2, 6, 4, 8, 7, 3, 5)).reshape(-1)
     def words(s, z):
         return s.view(np.uint16).astype(np.uint32) | (z.view(np.uint16).astype(np.uint32) << 16)
     szbuf = np.ascontiguousarray(np.stack([words(Ks, Kz), words(Vs, Vz)], axis=-1)).reshape(-1)
