@@ -30,6 +30,7 @@ typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
 
 constexpr int kHeadDim = 128;
 constexpr float kNegBig = -1.0e30f;     // "minus infinity" that stays finite under subtraction
+constexpr int kNonTemporal = 2;         // cache-policy bit of a buffer load: streamed once, do not keep
 
 __device__ __forceinline__ float xor_max(float v, int mask) { return fmaxf(v, __shfl_xor(v, mask)); }
 __device__ __forceinline__ float xor_add(float v, int mask) { return v + __shfl_xor(v, mask); }
@@ -110,29 +111,32 @@ __device__ __forceinline__ __amdgpu_buffer_rsrc_t make_rsrc(const void* p, uint3
     return __builtin_amdgcn_make_buffer_rsrc(const_cast<void*>(p), 0, (int)bytes, 0x00020000);
 }
 
-__device__ __forceinline__ void load_block(BlockRegs& r, uint32_t* sz_slot, const __amdgpu_buffer_rsrc_t& sz_rsrc,
-                                           const AttnCache& kv, size_t bh, int blk, int lane)
+// Descriptors of one (sequence, head): its K blocks, V blocks and scale/zero words, each cut off after the last block
+// of the context.  A load past that end returns zeros without touching memory, which lets the pipeline issue its loads
+// unconditionally (the surplus ones at the end of a wave's range cost nothing).
+struct HeadRsrc {
+    __amdgpu_buffer_rsrc_t k, v, sz;
+};
+
+__device__ __forceinline__ void load_block(BlockRegs& r, uint32_t* sz_slot, const HeadRsrc& rs, int blk, int lane)
 {
-    const int t0 = blk * 32;
     // (the host pass of the compiler only needs the kernel's signature; it cannot express the LDS pointer)
 #if defined(__HIP_DEVICE_COMPILE__)
-    __builtin_amdgcn_raw_ptr_buffer_load_lds(sz_rsrc, (__attribute__((address_space(3))) void*)sz_slot, 4, lane * 4,
-                                             t0 * 8, 0, 0);
+    __builtin_amdgcn_raw_ptr_buffer_load_lds(rs.sz, (__attribute__((address_space(3))) void*)sz_slot, 4,
+                                             lane * 4 + blk * 256, 0, 0, 0);
 #else
     (void)sz_slot;
-    (void)sz_rsrc;
-    (void)t0;
 #endif
-    // every load instruction of the wave reads 1 KiB of consecutive bytes: the blocks are stored in operand order
-    const uint8_t* kp = kv.k + (bh * (kv.cap / 32) + blk) * 4096 + lane * 16;
+    // every load instruction of the wave reads 1 KiB of consecutive bytes: the blocks are stored in operand order.
+    // The block offset sits in the per-lane offset, which the descriptor's range check covers.
+    const int off = lane * 16 + blk * 4096;
 #pragma unroll
     for (int j = 0; j < 2; ++j) {
-        r.k[j][0] = __builtin_nontemporal_load((const u32x4*)(kp + (j * 2 + 0) * 1024));
-        r.k[j][1] = __builtin_nontemporal_load((const u32x4*)(kp + (j * 2 + 1) * 1024));
+        r.k[j][0] = __builtin_amdgcn_raw_buffer_load_b128(rs.k, off + (j * 2 + 0) * 1024, 0, kNonTemporal);
+        r.k[j][1] = __builtin_amdgcn_raw_buffer_load_b128(rs.k, off + (j * 2 + 1) * 1024, 0, kNonTemporal);
     }
-    const uint8_t* vp = kv.v + (bh * (kv.cap / 32) + blk) * 4096 + lane * 16;
 #pragma unroll
-    for (int i = 0; i < 4; ++i) r.v[i] = __builtin_nontemporal_load((const u32x4*)(vp + i * 1024));
+    for (int i = 0; i < 4; ++i) r.v[i] = __builtin_amdgcn_raw_buffer_load_b128(rs.v, off + i * 1024, 0, kNonTemporal);
 }
 
 // Running state of one wave (per query head m = lane % 16; m_run is equal in the four lanes that share an m, l_run and
@@ -258,31 +262,34 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))) voi
 
     // KV memory loading pipeline: the next two blocks of this wave are in flight while the current one is multiplied
     // (three register sets and three LDS slots, rotated by unrolling; with one block ahead the waves spent half their
-    // time waiting for memory).  Loads are unconditional - past the end of the wave's range they re-fetch its last
-    // block - so that the loop body is straight-line code with a known number of loads in flight.
-    const __amdgpu_buffer_rsrc_t sz_rsrc = make_rsrc(kv.sz + bh * kv.cap * 2, (uint32_t)kv.cap * 8u);
+    // time waiting for memory).  Loads are unconditional - past the end of the wave's range they point behind the
+    // descriptors' ranges and return zeros without memory traffic - so that the loop body is straight-line code with a
+    // known number of loads in flight.
+    HeadRsrc rs;
+    rs.k = make_rsrc(kv.k + bh * kv.cap * kHeadDim, (uint32_t)nblk * 4096u);
+    rs.v = make_rsrc(kv.v + bh * kv.cap * kHeadDim, (uint32_t)nblk * 4096u);
+    rs.sz = make_rsrc(kv.sz + bh * kv.cap * 2, (uint32_t)nblk * 256u);
     uint32_t* const z0 = sz_ring0[wave];
     uint32_t* const z1 = sz_ring1[wave];
     uint32_t* const z2 = sz_ring2[wave];
     BlockRegs r0, r1, r2;
     int blk = blk0 + wave;
     if (blk < blk1) {
-        const int last = blk + ((blk1 - 1 - blk) / 4) * 4;      // this wave's last block
-        load_block(r0, z0, sz_rsrc, kv, bh, blk, lane);
-        load_block(r1, z1, sz_rsrc, kv, bh, min(blk + 4, last), lane);
+        load_block(r0, z0, rs, blk, lane);
+        load_block(r1, z1, rs, blk + 4 < blk1 ? blk + 4 : nblk, lane);
         while (true) {
-            load_block(r2, z2, sz_rsrc, kv, bh, min(blk + 8, last), lane);
+            load_block(r2, z2, rs, blk + 8 < blk1 ? blk + 8 : nblk, lane);
             process_block(r0, z0, qf, qsum, blk * 32, len, lane, st, acc);
             blk += 4;
-            if (blk > last) break;
-            load_block(r0, z0, sz_rsrc, kv, bh, min(blk + 8, last), lane);
+            if (blk >= blk1) break;
+            load_block(r0, z0, rs, blk + 8 < blk1 ? blk + 8 : nblk, lane);
             process_block(r1, z1, qf, qsum, blk * 32, len, lane, st, acc);
             blk += 4;
-            if (blk > last) break;
-            load_block(r1, z1, sz_rsrc, kv, bh, min(blk + 8, last), lane);
+            if (blk >= blk1) break;
+            load_block(r1, z1, rs, blk + 8 < blk1 ? blk + 8 : nblk, lane);
             process_block(r2, z2, qf, qsum, blk * 32, len, lane, st, acc);
             blk += 4;
-            if (blk > last) break;
+            if (blk >= blk1) break;
         }
     }
 
