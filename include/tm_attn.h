@@ -53,6 +53,8 @@ TM_API void tm_kv_free(tm_kv_cache* cache);
  * Quantise and store `count` new tokens per sequence: K_new, V_new fp16 [batch][count][kv_heads][128]; sequence b's
  * tokens go to positions[b] .. positions[b] + count - 1 (positions: int32 [batch]; tokens that would fall outside
  * [0, capacity) are dropped).  Codes are decided in fp32 with the fp16-rounded scale, round half to even.
+ * Runs of 16 or more tokens with 16-byte aligned K_new and V_new take a block-wise kernel that writes whole 4 KiB cache
+ * blocks; the stored bytes are the same either way.  Appends to one cache must be ordered on one stream.
  */
 TM_API int tm_kv_append(tm_kv_cache* cache, const uint16_t* K_new, const uint16_t* V_new, const int32_t* positions,
                         int count, tm_stream stream);

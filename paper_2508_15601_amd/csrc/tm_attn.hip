@@ -97,6 +97,123 @@ __global__ __launch_bounds__(64) void kv_append_kernel(AttnCache kv, const uint1
     }
 }
 
+// Prompt-sized appends: one CTA of 256 threads per (KV head, 32-token block touched, sequence).  Sixteen lanes share a
+// token (eight dimensions = one 16-byte load each), so a wave quantises four tokens at a time; codes are assembled in
+// LDS in cache order and leave as 16-byte stores: a fully covered block is written as 2 x 4 KiB of consecutive bytes.
+// A partly covered block keeps its other tokens: key chunks belong to one token each (stored or skipped), value chunks
+// hold eight tokens and are merged bytewise with what the cache holds (calls on one cache are ordered on one stream).
+// Same arithmetic, operation for operation, as kv_append_kernel.
+__global__ __launch_bounds__(256) void kv_append_block_kernel(AttnCache kv, const uint16_t* __restrict__ Kn,
+                                                              const uint16_t* __restrict__ Vn,
+                                                              const int32_t* __restrict__ positions, int count)
+{
+    __shared__ __align__(16) uint8_t lds[2][4096];
+    const int h = blockIdx.x, b = blockIdx.z;
+    const int pos = positions[b];
+    long first = pos < 0 ? 0 : pos, last = (long)pos + count;         // tokens [first, last) of the cache are new
+    if (last > kv.cap) last = kv.cap;
+    if (first >= last) return;
+    const int tb = (int)(first >> 5) + (int)blockIdx.y;                // this CTA's block of 32 tokens
+    const long t0 = first > (long)tb * 32 ? first : (long)tb * 32;
+    const long t1 = last < (long)(tb + 1) * 32 ? last : (long)(tb + 1) * 32;
+    if (t0 >= t1) return;                                              // CTA-uniform
+    const int u0 = (int)(t0 - (long)tb * 32), u1 = (int)(t1 - (long)tb * 32);
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int sub = lane & 15;                                         // dimensions 8*sub .. 8*sub + 7
+    const size_t bh = (size_t)b * kv.heads + h;
+#pragma unroll
+    for (int it = 0; it < 4; ++it) {
+        const int which = it >> 1;                                     // 0: keys, 1: values
+        const int u = wave * 8 + (it & 1) * 4 + (lane >> 4);           // token of the block
+        const bool live = u >= u0 && u < u1;
+        const long t = (long)tb * 32 + u;
+        float x[8];
+        if (live) {
+            const size_t src = (((size_t)b * count + (size_t)(t - pos)) * kv.heads + h) * kHeadDim + 8 * sub;
+            const u32x4 raw = *reinterpret_cast<const u32x4*>((which ? Vn : Kn) + src);
+#pragma unroll
+            for (int k = 0; k < 4; ++k) {
+                x[2 * k] = (float)__builtin_bit_cast(_Float16, (unsigned short)(raw[k] & 0xffffu));
+                x[2 * k + 1] = (float)__builtin_bit_cast(_Float16, (unsigned short)(raw[k] >> 16));
+            }
+        } else {
+#pragma unroll
+            for (int k = 0; k < 8; ++k) x[k] = 0.f;
+        }
+        float mn = x[0], mx = x[0];
+#pragma unroll
+        for (int k = 1; k < 8; ++k) {
+            mn = fminf(mn, x[k]);
+            mx = fmaxf(mx, x[k]);
+        }
+#pragma unroll
+        for (int m = 1; m < 16; m <<= 1) {
+            mn = fminf(mn, __shfl_xor(mn, m));
+            mx = fmaxf(mx, __shfl_xor(mx, m));
+        }
+        _Float16 s16 = (_Float16)((mx - mn) / 255.0f);
+        float sf = (float)s16;
+        if (!(sf > 0.0f) || __builtin_isinf(sf)) {
+            sf = 1.0f;
+            s16 = (_Float16)1.0f;
+        }
+        const float zf = fminf(fmaxf(rintf(-mn / sf), 0.0f), 255.0f);
+        uint32_t q[8];
+#pragma unroll
+        for (int k = 0; k < 8; ++k) q[k] = (uint32_t)fminf(fmaxf(rintf(x[k] / sf) + zf, 0.0f), 255.0f);
+        if (which == 0) {
+            // dimensions 8*sub .. +7 of token u: eight consecutive bytes of chunk (j*2 + half)*64 + 16*hh + c
+            const int d = 8 * sub;
+            const int chunk = ((u >> 4) * 2 + ((d & 31) >> 4)) * 64 + 16 * (d >> 5) + (u & 15);
+            u32x2 w;
+            w[0] = q[0] | (q[1] << 8) | (q[2] << 16) | (q[3] << 24);
+            w[1] = q[4] | (q[5] << 8) | (q[6] << 16) | (q[7] << 24);
+            *reinterpret_cast<u32x2*>(&lds[0][chunk * 16 + (d & 15)]) = w;
+        } else {
+            const int hh = (u & 15) >> 2, e = (u & 3) + 4 * (u >> 4);
+#pragma unroll
+            for (int k = 0; k < 8; ++k) {
+                const int d = 8 * sub + k, i = d >> 4;
+                lds[1][((i >> 1) * 64 + 16 * hh + (d & 15)) * 16 + (i & 1) * 8 + e] = (uint8_t)q[k];
+            }
+        }
+        if (live && sub == 0) {
+            const _Float16 z16 = (_Float16)zf;
+            kv.sz[(bh * kv.cap + t) * 2 + which] =
+                (uint32_t)__builtin_bit_cast(unsigned short, s16) | ((uint32_t)__builtin_bit_cast(unsigned short, z16) << 16);
+        }
+    }
+    __syncthreads();
+    const size_t blk = (bh * (kv.cap / 32) + tb) * 4096;
+    const int chunk = threadIdx.x;                                     // 256 chunks of 16 bytes per block
+    const u32x4 kc = *reinterpret_cast<const u32x4*>(&lds[0][chunk * 16]);
+    u32x4 vc = *reinterpret_cast<const u32x4*>(&lds[1][chunk * 16]);
+    u32x4* kdst = reinterpret_cast<u32x4*>(kv.k + blk) + chunk;
+    u32x4* vdst = reinterpret_cast<u32x4*>(kv.v + blk) + chunk;
+    if (u0 == 0 && u1 == 32) {
+        *kdst = kc;
+        *vdst = vc;
+        return;
+    }
+    const int ku = (chunk >> 7) * 16 + (chunk & 15);                   // the token of this key chunk
+    if (ku >= u0 && ku < u1) *kdst = kc;
+    // value chunk: byte e of either half belongs to token (e % 4) + 4*hh + 16*(e / 4), hh = (chunk % 64) / 16
+    const int hh = (chunk & 63) >> 4;
+    uint32_t keep_lo = 0, keep_hi = 0;                                 // byte masks of tokens e = 0..3 and e = 4..7
+#pragma unroll
+    for (int e = 0; e < 4; ++e) {
+        const int ua = e + 4 * hh, ub = ua + 16;
+        if (ua >= u0 && ua < u1) keep_lo |= 0xffu << (8 * e);
+        if (ub >= u0 && ub < u1) keep_hi |= 0xffu << (8 * e);
+    }
+    const u32x4 old = *vdst;
+    vc[0] = (vc[0] & keep_lo) | (old[0] & ~keep_lo);
+    vc[1] = (vc[1] & keep_hi) | (old[1] & ~keep_hi);
+    vc[2] = (vc[2] & keep_lo) | (old[2] & ~keep_lo);
+    vc[3] = (vc[3] & keep_hi) | (old[3] & ~keep_hi);
+    *vdst = vc;
+}
+
 // ------------------------------------------------------------------------------------------------ decode attention
 // The codes of a block travel in registers (they are the in-flight memory of the pipeline: two blocks ahead).  The 64
 // scale/zero words of a block would cost as many registers per lane as its 8 KiB of codes, so they go through LDS
@@ -404,6 +521,13 @@ hipError_t launch_kv_append(const AttnCache& kv, const uint16_t* Kn, const uint1
 {
     const long waves = (long)kv.batch * count * kv.heads;
     if (waves <= 0 || waves > 0x7fffffffL) return hipErrorInvalidValue;
+    if (count >= 16 && kv.heads <= 65535 && kv.batch <= 65535 && !(((uintptr_t)Kn | (uintptr_t)Vn) & 15)) {
+        // blocks a run of `count` tokens can touch: one more than it fills when it starts inside a block
+        const unsigned blocks = (unsigned)((count + 31) / 32 + 1);
+        hipLaunchKernelGGL(kv_append_block_kernel, dim3(kv.heads, blocks, kv.batch), dim3(256), 0, stream, kv, Kn, Vn,
+                           positions, count);
+        return hipGetLastError();
+    }
     hipLaunchKernelGGL(kv_append_kernel, dim3((unsigned)waves), dim3(64), 0, stream, kv, Kn, Vn, positions, count);
     return hipGetLastError();
 }

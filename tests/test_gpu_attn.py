@@ -38,7 +38,8 @@ def _dev(a):
     return torch.from_numpy(np.ascontiguousarray(a)).cuda()
 
 
-@pytest.mark.parametrize("B,Hkv,T,chunks", [(1, 1, 32, [32]), (2, 3, 70, [40, 1, 1, 28]), (3, 2, 97, [97]), (2, 1, 33, [1] * 33)])
+@pytest.mark.parametrize("B,Hkv,T,chunks", [(1, 1, 32, [32]), (2, 3, 70, [40, 1, 1, 28]), (3, 2, 97, [97]), (2, 1, 33, [1] * 33),
+                                             (2, 2, 300, [5, 200, 15, 80])])
 def test_kv_append_bit_exact(tm, B, Hkv, T, chunks):
     """Keys and values appended in chunks land in the cache layout with exactly the oracle's codes and pairs."""
     import torch
@@ -69,6 +70,45 @@ def test_kv_append_bit_exact(tm, B, Hkv, T, chunks):
     tm.tm_kv_append(cache, _dev(Kn), _dev(Vn), torch.full((B,), cap, dtype=torch.int32, device="cuda"))
     k2, v2, s2 = tm.tm_kv_download(cache)
     assert np.array_equal(k2, kbuf) and np.array_equal(v2, vbuf) and np.array_equal(s2, szbuf)
+    cache.close()
+
+
+def test_kv_append_ragged_positions(tm):
+    """Sequences at different positions, runs that start and end inside a 32-token block (the block-wise kernel merges with
+    what the cache holds), a run cut off by the capacity, and a run that starts before position 0."""
+    import torch
+    B, Hkv, cap = 3, 2, 160
+    _say("kv append ragged positions")
+    _, K, V, _ = wa.draw(B, Hkv, Hkv, cap, seed=11)
+    cache = tm.tm_kv_create(B, Hkv, cap)
+    assert cache.capacity == cap
+    tm.tm_kv_upload(cache, np.zeros(B * Hkv * cap * 128, np.uint8), np.zeros(B * Hkv * cap * 128, np.uint8),
+                    np.zeros(B * Hkv * cap * 2, np.uint32))
+    filled = np.zeros((B, cap), bool)
+    # (count, positions per sequence): first lays single tokens and short runs, then long runs over and between them
+    for n, pos in [(3, [0, 30, 157]), (20, [5, 40, 100]), (70, [25, 64, 120]), (33, [-7, 129, 10]), (17, [95, 0, 143])]:
+        Kn = np.zeros((B, n, Hkv, 128), np.float16)
+        Vn = np.zeros((B, n, Hkv, 128), np.float16)
+        for b in range(B):
+            for j in range(n):
+                t = pos[b] + j
+                if 0 <= t < cap:
+                    Kn[b, j], Vn[b, j] = K[b, :, t], V[b, :, t]
+                    filled[b, t] = True
+                else:
+                    Kn[b, j], Vn[b, j] = 7.0, -3.0              # must never reach the cache
+        tm.tm_kv_append(cache, _dev(Kn), _dev(Vn), torch.tensor(pos, dtype=torch.int32, device="cuda"))
+    kbuf, vbuf, szbuf = tm.tm_kv_download(cache)
+    got = oa.kv_cache_unpack(kbuf, vbuf, szbuf, B, Hkv, cap)
+    want = oa.kv_quantise(K) + oa.kv_quantise(V)
+    m = filled[:, None, :]
+    assert filled.any() and not filled.all()
+    for g, w in zip(got, want):
+        g = g.view(np.uint16) if g.dtype == np.float16 else g
+        w = w.view(np.uint16) if w.dtype == np.float16 else w
+        mm = np.broadcast_to(m[..., None] if g.ndim == 4 else m, g.shape)
+        assert np.array_equal(g[mm], w[mm])
+        assert not g[~mm].any()                                  # untouched tokens still hold the zeros uploaded
     cache.close()
 
 
