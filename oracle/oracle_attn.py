@@ -66,14 +66,22 @@ def attn_decode(Q, Kq, Ks, Kz, Vq, Vs, Vz, lens, scale: float) -> np.ndarray:
 
 
 def kv_cache_unpack(kbuf, vbuf, szbuf, B: int, Hkv: int, cap: int, bits: int = 8):
-    """Inverse of the library's cache layout (8-bit codes), written from its specification.  Codes live in blocks of
-    32 tokens x 128 dimensions (4096 bytes), block index (b*Hkv + h)*(cap/32) + t/32, token u = t % 32 inside it:
+    """Inverse of the library's cache layout, written from its specification.  Codes live in blocks of 32 tokens x 128
+    dimensions, block index (b*Hkv + h)*(cap/32) + t/32, token u = t % 32 inside it.
+    8-bit codes (4096-byte blocks):
       K block:  byte ((j*2 + half)*64 + 16*hh + c)*16 + x   for dimension d,  j = u / 16, c = u % 16, hh = d / 32,
                 half = (d % 32) / 16, x = d % 16
       V block:  byte ((i/2)*64 + 16*hh + c)*16 + (i % 2)*8 + e   for dimension d,  c = d % 16, i = d / 16,
                 hh = (u % 16) / 4, e = u % 4 + 4*(u / 16)
-      scale/zero: u32 words, word ((b*Hkv + h)*cap + t)*2 + {0: K, 1: V} = scale bits | zero bits << 16
+    4-bit codes (2048-byte blocks of little-endian 32-bit words; the code of operand element e sits in bits 4p .. 4p+3
+    with p = e/2 + 4*(e % 2)):
+      K block:  word ((u/16)*64 + 16*(d/32) + u%16)*4 + (d%32)/8,  element e = d % 8
+      V block:  word ((i/4)*64 + 16*hh + c)*4 + i%4,  i = d / 16, c = d % 16, hh = (u % 16) / 4,
+                element e = u % 4 + 4*(u / 16)
+    scale/zero: u32 words, word ((b*Hkv + h)*cap + t)*2 + {0: K, 1: V} = scale bits | zero bits << 16
     -> (Kq, Ks, Kz, Vq, Vs, Vz) in the plain [B, Hkv, cap, (D)] arrangement."""
+    if bits == 4:
+        return _kv_cache_unpack4(kbuf, vbuf, szbuf, B, Hkv, cap)
     assert bits == 8 and cap % 32 == 0
     D = HEAD_DIM
     kbuf = np.asarray(kbuf, np.uint8).reshape(-1)
@@ -92,6 +100,32 @@ def kv_cache_unpack(kbuf, vbuf, szbuf, B: int, Hkv: int, cap: int, bits: int = 8
             hh, e = (u % 16) // 4, u % 4 + 4 * (u // 16)
             voff = ((i // 2) * 64 + 16 * hh + c) * 16 + (i % 2) * 8 + e
             Vq[:, :, t, d] = vbuf[blk * 4096 + voff]
+    sz = szbuf.reshape(B, Hkv, cap, 2)
+    s = (sz & 0xFFFF).astype(np.uint16).view(np.float16)
+    z = (sz >> 16).astype(np.uint16).view(np.float16)
+    return Kq, s[..., 0], z[..., 0], Vq, s[..., 1], z[..., 1]
+
+
+def _kv_cache_unpack4(kbuf, vbuf, szbuf, B: int, Hkv: int, cap: int):
+    assert cap % 32 == 0
+    D = HEAD_DIM
+    kw = np.asarray(kbuf, np.uint8).reshape(-1).view("<u4")
+    vw = np.asarray(vbuf, np.uint8).reshape(-1).view("<u4")
+    szbuf = np.asarray(szbuf, np.uint32).reshape(-1)
+    Kq = np.empty((B, Hkv, cap, D), np.uint8)
+    Vq = np.empty((B, Hkv, cap, D), np.uint8)
+    bh = np.arange(B)[:, None] * Hkv + np.arange(Hkv)[None, :]
+    for t in range(cap):
+        u = t % 32
+        blk = bh * (cap // 32) + t // 32                       # 512 words per block
+        for d in range(D):
+            e = d % 8
+            word = ((u // 16) * 64 + 16 * (d // 32) + u % 16) * 4 + (d % 32) // 8
+            Kq[:, :, t, d] = (kw[blk * 512 + word] >> (4 * (e // 2 + 4 * (e % 2)))) & 15
+            i, c = d // 16, d % 16
+            hh, e = (u % 16) // 4, u % 4 + 4 * (u // 16)
+            word = ((i // 4) * 64 + 16 * hh + c) * 4 + i % 4
+            Vq[:, :, t, d] = (vw[blk * 512 + word] >> (4 * (e // 2 + 4 * (e % 2)))) & 15
     sz = szbuf.reshape(B, Hkv, cap, 2)
     s = (sz & 0xFFFF).astype(np.uint16).view(np.float16)
     z = (sz >> 16).astype(np.uint16).view(np.float16)

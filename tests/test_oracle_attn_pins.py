@@ -100,3 +100,63 @@ def test_cache_layout_inverse_against_generator_encoder():
     Ku, _, _, Vu, _, _ = oa.kv_cache_unpack(kb, vb, np.zeros(B * Hkv * cap * 2, np.uint32), B, Hkv, cap)
     assert Vu[0, 0, 21, 35] == 77 and Vu.sum() == 77
     assert Ku[0, 0, 21, 83] == 99 and Ku.sum() == 99
+
+
+def test_kv_quantise_hand_worked_row_4bit():
+    rows = []
+    for line in open(os.path.join(GOLD, "kv_quant_row_4bit.txt")):
+        line = line.split("#")[0].split()
+        if line:
+            rows.append((float(line[0]), int(line[1]), float(line[2])))
+    x = np.array([r[0] for r in rows], np.float32)[None, :]
+    q, s, z = oa.kv_quantise(x, bits=4)
+    assert float(s[0]) == 0.125 and float(z[0]) == 8.0
+    assert q[0].tolist() == [r[1] for r in rows]
+    assert oa.kv_dequant(q, s, z)[0].tolist() == [r[2] for r in rows]
+    # codes never leave [0, 15], also where the rounded scale makes the largest value overshoot
+    q, s, z = oa.kv_quantise(np.random.default_rng(0).standard_normal((50, 128)).astype(np.float16), bits=4)
+    assert q.max() == 15 and q.min() == 0 and z.max() <= 15
+
+
+def test_cache_layout_inverse_4bit():
+    """4-bit codes: the oracle's inverse undoes the generator's reshape-based encoder, and single hand-placed codes land
+    where the layout rule says."""
+    rng = np.random.default_rng(4)
+    B, Hkv, cap = 2, 2, 96
+    Kq = rng.integers(0, 16, (B, Hkv, cap, 128), dtype=np.uint8)
+    Vq = rng.integers(0, 16, (B, Hkv, cap, 128), dtype=np.uint8)
+    s = [rng.uniform(0.01, 0.5, (B, Hkv, cap)).astype(np.float16) for _ in range(2)]
+    z = [rng.integers(0, 16, (B, Hkv, cap)).astype(np.float16) for _ in range(2)]
+    kbuf, vbuf, szbuf = wa.encode_cache(Kq, s[0], z[0], Vq, s[1], z[1], bits=4)
+    assert kbuf.size == vbuf.size == B * Hkv * cap * 64
+    out = oa.kv_cache_unpack(kbuf, vbuf, szbuf, B, Hkv, cap, bits=4)
+    for a, b in zip(out, (Kq, s[0], z[0], Vq, s[1], z[1])):
+        assert np.array_equal(a.view(np.uint16) if a.dtype == np.float16 else a, b.view(np.uint16) if b.dtype == np.float16 else b)
+    # key of token 21 (tile 1, row 5), dimension 83 = 32*2 + 8*2 + 3: word ((1*64 + 16*2 + 5)*4 + 2), element 3 ->
+    # nibble 3/2 + 4*1 = 5, i.e. the high half of byte 2 of that word
+    n = B * Hkv * cap * 64
+    kb = np.zeros(n, np.uint8)
+    kb[((64 + 32 + 5) * 4 + 2) * 4 + 2] = 0xB0
+    # value of token 21 (hh = 1, element 1 + 4 = 5 -> nibble 5/2 + 4 = 6), dimension 99 = 16*6 + 3: word
+    # ((6/4)*64 + 16*1 + 3)*4 + 6%4, low half of byte 3
+    vb = np.zeros(n, np.uint8)
+    vb[((64 + 16 + 3) * 4 + 2) * 4 + 3] = 0x0D
+    Ku, _, _, Vu, _, _ = oa.kv_cache_unpack(kb, vb, np.zeros(B * Hkv * cap * 2, np.uint32), B, Hkv, cap, bits=4)
+    assert Ku[0, 0, 21, 83] == 11 and Ku.sum() == 11
+    assert Vu[0, 0, 21, 99] == 13 and Vu.sum() == 13
+
+
+def test_attn_decode_4bit_codes_against_torch_sdpa():
+    """The decode oracle on a 4-bit cache equals PyTorch's CPU attention on the dequantised keys and values."""
+    import torch
+    rng = np.random.default_rng(5)
+    B, Hq, Hkv, T = 2, 8, 2, 40
+    K = rng.standard_normal((B, Hkv, T, 128)).astype(np.float16)
+    V = rng.standard_normal((B, Hkv, T, 128)).astype(np.float16)
+    Q = rng.standard_normal((B, Hq, 128)).astype(np.float16)
+    kq, vq = oa.kv_quantise(K, bits=4), oa.kv_quantise(V, bits=4)
+    O = oa.attn_decode(Q, *kq, *vq, np.array([T, T]), 0.1)
+    Kd = torch.from_numpy(oa.kv_dequant(*kq)).double().repeat_interleave(Hq // Hkv, dim=1)
+    Vd = torch.from_numpy(oa.kv_dequant(*vq)).double().repeat_interleave(Hq // Hkv, dim=1)
+    ref = torch.nn.functional.scaled_dot_product_attention(torch.from_numpy(Q).double()[:, :, None, :], Kd, Vd, scale=0.1)
+    assert np.allclose(O.astype(np.float64), ref[:, :, 0].numpy(), rtol=2e-3, atol=1e-3)

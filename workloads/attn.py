@@ -24,18 +24,41 @@ def draw(B: int, Hq: int, Hkv: int, T: int, seed: int, D: int = 128, min_len: in
     return Q, K, V, lens
 
 
-def encode_cache(Kq, Ks, Kz, Vq, Vs, Vz):
+_NIBBLE_ELEMENT = [0, 2, 4, 6, 1, 3, 5, 7]      # operand element held by nibble p = 0..7 of a 32-bit word (4-bit codes)
+
+
+def _nibbles_to_bytes(x):
+    """[..., 8] codes in nibble order p -> [..., 4] bytes of the little-endian word."""
+    x = x.astype(np.uint8)
+    return x[..., 0::2] | (x[..., 1::2] << 4)
+
+
+def encode_cache(Kq, Ks, Kz, Vq, Vs, Vz, bits: int = 8):
     """Plain arrays ([B,Hkv,cap,128] codes, [B,Hkv,cap] float16 scale / zero) -> (kbuf, vbuf uint8, szbuf uint32) in
     the library's cache layout, written with reshapes."""
     B, Hkv, cap, D = Kq.shape
     assert D == 128 and cap % 32 == 0
+    if bits == 4:
+        # K: token u = 16*j + c ; d = 32*hh + 8*tt + e  ->  [blk][j][hh][c][tt][nibble p]
+        k = Kq.reshape(B, Hkv, cap // 32, 2, 16, 4, 4, 8)        # [b,h,blk,j,c,hh,tt,e]
+        k = k.transpose(0, 1, 2, 3, 5, 4, 6, 7)[..., _NIBBLE_ELEMENT]
+        kbuf = np.ascontiguousarray(_nibbles_to_bytes(k)).reshape(-1)
+        # V: token u = 16*e_hi + 4*hh + e_lo ; e = e_lo + 4*e_hi ; d = 16*(4*i_hi + i_lo) + c
+        #    ->  [blk][i_hi][hh][c][i_lo][nibble p]
+        v = Vq.reshape(B, Hkv, cap // 32, 2, 4, 4, 2, 4, 16)     # [b,h,blk,e_hi,hh,e_lo,i_hi,i_lo,c]
+        v = v.transpose(0, 1, 2, 6, 4, 8, 7, 3, 5).reshape(B, Hkv, cap // 32, 2, 4, 16, 4, 8)[..., _NIBBLE_ELEMENT]
+        vbuf = np.ascontiguousarray(_nibbles_to_bytes(v)).reshape(-1)
+        szbuf = np.ascontiguousarray(np.stack([_words(Ks, Kz), _words(Vs, Vz)], axis=-1)).reshape(-1)
+        return kbuf, vbuf, szbuf
     # K: token u = 16*j + c ; d = 32*hh + 16*half + x  ->  [blk][j][half][hh][c][x]
     k = Kq.reshape(B, Hkv, cap // 32, 2, 16, 4, 2, 16)           # [b,h,blk,j,c,hh,half,x]
     kbuf = np.ascontiguousarray(k.transpose(0, 1, 2, 3, 6, 5, 4, 7)).reshape(-1)
     # V: token u = 16*e_hi + 4*hh + e_lo ; e = e_lo + 4*e_hi ; d = 16*(2*i2 + i_lo) + c  ->  [blk][i2][hh][c][i_lo][e_hi][e_lo]
     v = Vq.reshape(B, Hkv, cap // 32, 2, 4, 4, 4, 2, 16)         # [b,h,blk,e_hi,hh,e_lo,i2,i_lo,c]
     vbuf = np.ascontiguousarray(v.transpose(0, 1, 2, 6, 4, 8, 7, 3, 5)).reshape(-1)
-    def words(s, z):
-        return s.view(np.uint16).astype(np.uint32) | (z.view(np.uint16).astype(np.uint32) << 16)
-    szbuf = np.ascontiguousarray(np.stack([words(Ks, Kz), words(Vs, Vz)], axis=-1)).reshape(-1)
+    szbuf = np.ascontiguousarray(np.stack([_words(Ks, Kz), _words(Vs, Vz)], axis=-1)).reshape(-1)
     return kbuf, vbuf, szbuf
+
+
+def _words(s, z):
+    return s.view(np.uint16).astype(np.uint32) | (z.view(np.uint16).astype(np.uint32) << 16)
