@@ -312,18 +312,18 @@ ATTN_SHAPES = [(1, 2048), (1, 8192), (1, 32768), (8, 2048), (8, 8192), (32, 2048
 args_eager = [False]
 
 
-def attn_table(tm, torch, iters=50, q_heads=32, kv_heads=8, only=None):
+def attn_table(tm, torch, iters=50, q_heads=32, kv_heads=8, only=None, bits=8):
     import numpy as np
     rows = []
     rng = np.random.default_rng(0)
     for B, T in ATTN_SHAPES:
         if only is not None and (B, T) != only:
             continue
-        per_cache = B * kv_heads * T * (2 * 128 + 8)
+        per_cache = B * kv_heads * T * (2 * 128 * bits // 8 + 8)
         copies = max(2, -(-ROTATE_BYTES // per_cache))
         caches = []
         for _ in range(copies):
-            c = tm.tm_kv_create(B, kv_heads, T)
+            c = tm.tm_kv_create(B, kv_heads, T, bits)
             n = B * kv_heads * c.capacity
             pairs = (rng.uniform(0.005, 0.05, 2 * n).astype(np.float16).view(np.uint16).astype(np.uint32)
                      | (rng.integers(0, 256, 2 * n).astype(np.float16).view(np.uint16).astype(np.uint32) << 16))
@@ -358,10 +358,10 @@ def attn_table(tm, torch, iters=50, q_heads=32, kv_heads=8, only=None):
         ev_ms, _ = time_steps(torch, store, iters, 5, graph_steps=0 if args_eager[0] else iters)
         t_store = ev_ms / iters * 1e-3
         bytes_ = per_cache + 2 * B * q_heads * 128 * 2
-        rows.append({"batch": B, "context": T, "q_heads": q_heads, "kv_heads": kv_heads, "kv_bits": 8, "us": t * 1e6,
+        rows.append({"batch": B, "context": T, "q_heads": q_heads, "kv_heads": kv_heads, "kv_bits": bits, "us": t * 1e6,
                      "GBps": bytes_ / t / 1e9, "hbm_frac": bytes_ / t / 1e9 / HBM_PEAK_GBPS, "cache_copies": copies,
                      "append_us": t_store * 1e6})
-        log(f"attn decode KV8  batch {B:4d} context {T:6d}  {t * 1e6:9.2f} us  {bytes_ / t / 1e9:7.0f} GB/s "
+        log(f"attn decode KV{bits}  batch {B:4d} context {T:6d}  {t * 1e6:9.2f} us  {bytes_ / t / 1e9:7.0f} GB/s "
             f"({100 * bytes_ / t / 1e9 / HBM_PEAK_GBPS:4.1f} % of HBM peak)  {bytes_ / 1e6:8.1f} MB per call; "
             f"append of one token per sequence {t_store * 1e6:6.2f} us")
         for c in caches:
@@ -371,18 +371,18 @@ def attn_table(tm, torch, iters=50, q_heads=32, kv_heads=8, only=None):
     return rows
 
 
-def attn_store_row(tm, torch, iters=20, B=16, T=2048, kv_heads=8):
+def attn_store_row(tm, torch, iters=20, B=16, T=2048, kv_heads=8, bits=8):
     """Quantise-and-store of a whole prompt (the prefill side of the cache): reads 2 fp16 tensors, writes codes + pairs."""
-    c = tm.tm_kv_create(B, kv_heads, T)
+    c = tm.tm_kv_create(B, kv_heads, T, bits)
     knew = torch.randn((B, T, kv_heads, 128), device="cuda").to(torch.float16)
     vnew = torch.randn((B, T, kv_heads, 128), device="cuda").to(torch.float16)
     pos = torch.zeros((B,), dtype=torch.int32, device="cuda")
     ev_ms, _ = time_steps(torch, lambda: tm.tm_kv_append(c, knew, vnew, pos), iters, 3, graph_steps=0 if args_eager[0] else iters)
     t = ev_ms / iters * 1e-3
-    bytes_ = B * T * kv_heads * (2 * 128 * 2 + 2 * 128 + 8)
+    bytes_ = B * T * kv_heads * (2 * 128 * 2 + 2 * 128 * bits // 8 + 8)
     c.close()
-    log(f"kv append (prompt) batch {B} tokens {T}: {t * 1e6:9.2f} us  {bytes_ / t / 1e9:7.0f} GB/s read+written")
-    return {"batch": B, "tokens": T, "kv_heads": kv_heads, "us": t * 1e6, "GBps": bytes_ / t / 1e9,
+    log(f"kv append (prompt) KV{bits} batch {B} tokens {T}: {t * 1e6:9.2f} us  {bytes_ / t / 1e9:7.0f} GB/s read+written")
+    return {"batch": B, "tokens": T, "kv_heads": kv_heads, "kv_bits": bits, "us": t * 1e6, "GBps": bytes_ / t / 1e9,
             "hbm_frac": bytes_ / t / 1e9 / HBM_PEAK_GBPS}
 
 
@@ -506,20 +506,24 @@ def main():
     if args.workload == "attn":
         only = tuple(int(v) for v in args.only.split(":")) if args.only else None
         args_eager[0] = args.eager
-        table = attn_table(tm, torch, iters=min(args.steps, 50), only=only)
+        if only is not None and len(only) == 3:                 # --only batch:context:bits
+            table = attn_table(tm, torch, iters=min(args.steps, 50), only=only[:2], bits=only[2])
+        else:
+            table = attn_table(tm, torch, iters=min(args.steps, 50), only=only)
+            table += attn_table(tm, torch, iters=min(args.steps, 50), only=only, bits=4)
         if args.sweep_out:
             os.makedirs(os.path.dirname(os.path.abspath(args.sweep_out)), exist_ok=True)
             json.dump(table, open(args.sweep_out, "w"), indent=1)
         best = max(table, key=lambda r: r["GBps"])
-        print(json.dumps({"metric": "decode attention over an 8-bit KV cache: effective HBM GB/s", "workload": "attn",
-                          "value": best["GBps"], "unit": "GB/s", "n_gpus": 1, "dtype": "u8 codes, f16 activations, f32 accumulation",
-                          "data": "synthetic", "config": {"workload": f"batch {best['batch']} x context {best['context']}, "
+        print(json.dumps({"metric": "decode attention over a quantised KV cache: effective HBM GB/s", "workload": "attn",
+                          "value": best["GBps"], "unit": "GB/s", "n_gpus": 1, "dtype": "u8 / u4 codes, f16 activations, f32 accumulation",
+                          "data": "synthetic", "config": {"workload": f"KV{best['kv_bits']}, batch {best['batch']} x context {best['context']}, "
                                                                       f"{best['q_heads']} query / {best['kv_heads']} KV heads, head dimension 128"},
                           "roofline": {"bound": "hbm", "achieved": best["GBps"], "peak": HBM_PEAK_GBPS, "unit": "GB/s",
-                                       "frac": best["hbm_frac"], "traffic": None, "kernel": "attn_decode_kernel",
+                                       "frac": best["hbm_frac"], "traffic": None, "kernel": f"attn_decode_kernel<{best['kv_bits']}>",
                                        "avg_launch_us": best["us"]},
                           "cpu_baseline": None if args.no_cpu_baseline else attn_cpu_baseline(),
-                          "store": None if only is not None else attn_store_row(tm, torch),
+                          "store": None if only is not None else [attn_store_row(tm, torch), attn_store_row(tm, torch, bits=4)],
                           "rows": table}))
         return
 

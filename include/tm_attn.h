@@ -7,8 +7,9 @@
  *     O[b][h] = softmax(scale * K^[b][h/G] q[b][h]) V^[b][h/G],      K^ = (Kq - zK) * sK,   V^ = (Vq - zV) * sV,
  *
  * with the cache kept as low-bit integer codes (Sec. 3.1: the same workflow with INT4/INT8 KV caches).  The paper does
- * not state the cache's quantisation granularity; here every token and KV head has one asymmetric 8-bit scale /
- * zero-point pair over the 128 values of the head (x^ = (q - z) * s, s = fp16((max - min)/255), z = round(-min/s)).
+ * not state the cache's quantisation granularity; here every token and KV head has one asymmetric scale / zero-point
+ * pair over the 128 values of the head, for 8-bit or 4-bit codes (x^ = (q - z) * s, s = fp16((max - min)/qmax),
+ * z = round(-min/s), qmax = 255 or 15).
  *
  *   Q branch (Sec. 4.2, adaptive head alignment): the query fragments are arranged once per call so that their
  *     per-lane dimension order equals the order in which a lane receives the low-bit key bytes; no key is reshuffled.
@@ -32,9 +33,10 @@ extern "C" {
 typedef struct tm_kv_cache tm_kv_cache;   /* opaque; owns its device buffers */
 
 /*
- * A cache for `batch` sequences x `kv_heads` heads x `capacity` tokens (rounded up to a multiple of 32) of 8-bit codes
- * (bits must be 8).  Allocates 2 * batch*kv_heads*capacity*128 bytes of codes, 8 bytes of scale/zero pairs per token and
- * head, and the split workspace of tm_attn_decode (a few MiB).  Contents start undefined.  NULL on error.
+ * A cache for `batch` sequences x `kv_heads` heads x `capacity` tokens of `bits`-bit codes (bits 8 or 4; the capacity is
+ * rounded up to a multiple of 256 / bits tokens).  Allocates 2 * batch*kv_heads*capacity*128*bits/8 bytes of codes,
+ * 8 bytes of scale/zero pairs per token and head, and the split workspace of tm_attn_decode (a few MiB).  Contents start
+ * undefined.  NULL on error.
  *
  * Layout (also what tm_kv_raw exposes); bh = b*kv_heads + h.  The cache is kept in matrix-core operand order (the
  * hardware-aware packing of Sec. 4.1 applied to the cache): codes in blocks of 32 tokens x 128 dimensions (4096 bytes),
@@ -45,6 +47,10 @@ typedef struct tm_kv_cache tm_kv_cache;   /* opaque; owns its device buffers */
  *   V block   dimension d at byte ((i/2)*64 + 16*hh + c)*16 + (i % 2)*8 + e,  c = d % 16, i = d / 16,
  *             hh = (u % 16) / 4, e = u % 4 + 4*(u / 16)
  *   pairs     u32 word (bh*capacity + t)*2 + {0: K, 1: V} = scale bits | zero bits << 16
+ * 4-bit codes: blocks of 32 tokens are 2048 bytes of little-endian 32-bit words, eight codes per word; the code of
+ * operand element e sits in bits 4p .. 4p+3, p = e/2 + 4*(e % 2) (the order the bit-manipulation conversion emits):
+ *   K block   word ((u/16)*64 + 16*(d/32) + u%16)*4 + (d%32)/8, element e = d % 8
+ *   V block   word ((i/4)*64 + 16*hh + c)*4 + i%4, i = d / 16, c = d % 16, hh = (u % 16) / 4, element e = u%4 + 4*(u/16)
  */
 TM_API tm_kv_cache* tm_kv_create(int batch, int kv_heads, int capacity, int bits);
 TM_API void tm_kv_free(tm_kv_cache* cache);
@@ -54,7 +60,8 @@ TM_API void tm_kv_free(tm_kv_cache* cache);
  * tokens go to positions[b] .. positions[b] + count - 1 (positions: int32 [batch]; tokens that would fall outside
  * [0, capacity) are dropped).  Codes are decided in fp32 with the fp16-rounded scale, round half to even.
  * Runs of 16 or more tokens with 16-byte aligned K_new and V_new take a block-wise kernel that writes whole 4 KiB cache
- * blocks; the stored bytes are the same either way.  Appends to one cache must be ordered on one stream.
+ * blocks; the stored bytes are the same either way.  A 4-bit cache needs 16-byte aligned K_new and V_new.  Appends to
+ * one cache must be ordered on one stream.
  */
 TM_API int tm_kv_append(tm_kv_cache* cache, const uint16_t* K_new, const uint16_t* V_new, const int32_t* positions,
                         int count, tm_stream stream);

@@ -400,7 +400,8 @@ class KvCache:
         if not h:
             raise TmError(-1, tm_last_error())
         self._h = h
-        self.batch, self.kv_heads, self.capacity = batch, kv_heads, (capacity + 31) // 32 * 32
+        tok = 256 // bits                           # the library rounds the capacity up to whole 4 KiB blocks of codes
+        self.batch, self.kv_heads, self.capacity, self.bits = batch, kv_heads, (capacity + tok - 1) // tok * tok, bits
 
     @property
     def handle(self):

@@ -214,6 +214,121 @@ __global__ __launch_bounds__(256) void kv_append_block_kernel(AttnCache kv, cons
     *vdst = vc;
 }
 
+// 4-bit codes: one CTA of 256 threads per (KV head, 32-token half block touched, sequence), for runs of any length (two
+// tokens share bytes of the value block, so tokens are never written by independent waves).  Quantisation as above
+// with 15 levels; key codes leave a lane as one whole operand word, value codes are staged as bytes in LDS and gathered
+// into operand words (eight tokens per word).  A partly covered half block is merged with what the cache holds: key
+// chunks belong to one token each, value words are merged nibble by nibble.
+__global__ __launch_bounds__(256) void kv4_append_block_kernel(AttnCache kv, const uint16_t* __restrict__ Kn,
+                                                               const uint16_t* __restrict__ Vn,
+                                                               const int32_t* __restrict__ positions, int count)
+{
+    __shared__ __align__(16) uint32_t kwords[512];                     // the key half block in cache order
+    __shared__ __align__(8) uint8_t vcodes[32][136];                   // value codes [token][dimension], padded rows
+    const int h = blockIdx.x, b = blockIdx.z;
+    const int pos = positions[b];
+    long first = pos < 0 ? 0 : pos, last = (long)pos + count;
+    if (last > kv.cap) last = kv.cap;
+    if (first >= last) return;
+    const int tb = (int)(first >> 5) + (int)blockIdx.y;
+    const long t0 = first > (long)tb * 32 ? first : (long)tb * 32;
+    const long t1 = last < (long)(tb + 1) * 32 ? last : (long)(tb + 1) * 32;
+    if (t0 >= t1) return;                                              // CTA-uniform
+    const int u0 = (int)(t0 - (long)tb * 32), u1 = (int)(t1 - (long)tb * 32);
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int sub = lane & 15;                                         // dimensions 8*sub .. 8*sub + 7
+    const size_t bh = (size_t)b * kv.heads + h;
+#pragma unroll
+    for (int it = 0; it < 4; ++it) {
+        const int which = it >> 1;
+        const int u = wave * 8 + (it & 1) * 4 + (lane >> 4);
+        const bool live = u >= u0 && u < u1;
+        const long t = (long)tb * 32 + u;
+        float x[8];
+        if (live) {
+            const size_t src = (((size_t)b * count + (size_t)(t - pos)) * kv.heads + h) * kHeadDim + 8 * sub;
+            const u32x4 raw = *reinterpret_cast<const u32x4*>((which ? Vn : Kn) + src);
+#pragma unroll
+            for (int k = 0; k < 4; ++k) {
+                x[2 * k] = (float)__builtin_bit_cast(_Float16, (unsigned short)(raw[k] & 0xffffu));
+                x[2 * k + 1] = (float)__builtin_bit_cast(_Float16, (unsigned short)(raw[k] >> 16));
+            }
+        } else {
+#pragma unroll
+            for (int k = 0; k < 8; ++k) x[k] = 0.f;
+        }
+        float mn = x[0], mx = x[0];
+#pragma unroll
+        for (int k = 1; k < 8; ++k) {
+            mn = fminf(mn, x[k]);
+            mx = fmaxf(mx, x[k]);
+        }
+#pragma unroll
+        for (int m = 1; m < 16; m <<= 1) {
+            mn = fminf(mn, __shfl_xor(mn, m));
+            mx = fmaxf(mx, __shfl_xor(mx, m));
+        }
+        _Float16 s16 = (_Float16)((mx - mn) / 15.0f);
+        float sf = (float)s16;
+        if (!(sf > 0.0f) || __builtin_isinf(sf)) {
+            sf = 1.0f;
+            s16 = (_Float16)1.0f;
+        }
+        const float zf = fminf(fmaxf(rintf(-mn / sf), 0.0f), 15.0f);
+        uint32_t q[8];
+#pragma unroll
+        for (int k = 0; k < 8; ++k) q[k] = (uint32_t)fminf(fmaxf(rintf(x[k] / sf) + zf, 0.0f), 15.0f);
+        if (which == 0) {
+            // dimensions 32*hh + 8*tt + e, e = 0..7: word tt of chunk (u/16)*64 + 16*hh + u%16; element e at nibble
+            // e/2 + 4*(e % 2)
+            const int chunk = (u >> 4) * 64 + 16 * (sub >> 2) + (u & 15);
+            uint32_t w = 0;
+#pragma unroll
+            for (int e = 0; e < 8; ++e) w |= q[e] << (4 * ((e >> 1) + 4 * (e & 1)));
+            kwords[chunk * 4 + (sub & 3)] = w;
+        } else {
+            u32x2 w;
+            w[0] = q[0] | (q[1] << 8) | (q[2] << 16) | (q[3] << 24);
+            w[1] = q[4] | (q[5] << 8) | (q[6] << 16) | (q[7] << 24);
+            *reinterpret_cast<u32x2*>(&vcodes[u][8 * sub]) = w;
+        }
+        if (live && sub == 0) {
+            const _Float16 z16 = (_Float16)zf;
+            kv.sz[(bh * kv.cap + t) * 2 + which] =
+                (uint32_t)__builtin_bit_cast(unsigned short, s16) | ((uint32_t)__builtin_bit_cast(unsigned short, z16) << 16);
+        }
+    }
+    __syncthreads();
+    const size_t blk = (bh * (kv.cap / 32) + tb) * 2048;
+    const bool whole = u0 == 0 && u1 == 32;
+    const int chunk = threadIdx.x & 127;                               // 128 chunks of 16 bytes per half block
+    if (threadIdx.x < 128) {
+        const int ku = (chunk >> 6) * 16 + (chunk & 15);               // the token of this key chunk
+        if (whole || (ku >= u0 && ku < u1))
+            reinterpret_cast<u32x4*>(kv.k + blk)[chunk] = *reinterpret_cast<const u32x4*>(&kwords[chunk * 4]);
+        return;
+    }
+    // value chunk (i/4)*64 + 16*hh + c: word i % 4 holds dimension 16*i + c of the tokens (e % 4) + 4*hh + 16*(e / 4)
+    const int ii = chunk >> 6, hh = (chunk & 63) >> 4, c = chunk & 15;
+    u32x4 vc = {0u, 0u, 0u, 0u};
+    uint32_t keep = 0;
+#pragma unroll
+    for (int e = 0; e < 8; ++e) {
+        const int u = (e & 3) + 4 * hh + 16 * (e >> 2);
+        const int sh = 4 * ((e >> 1) + 4 * (e & 1));
+        if (u >= u0 && u < u1) keep |= 0xfu << sh;
+#pragma unroll
+        for (int w = 0; w < 4; ++w) vc[w] |= (uint32_t)vcodes[u][16 * (4 * ii + w) + c] << sh;
+    }
+    u32x4* vdst = reinterpret_cast<u32x4*>(kv.v + blk) + chunk;
+    if (!whole) {
+        const u32x4 old = *vdst;
+#pragma unroll
+        for (int w = 0; w < 4; ++w) vc[w] = (vc[w] & keep) | (old[w] & ~keep);
+    }
+    *vdst = vc;
+}
+
 // ------------------------------------------------------------------------------------------------ decode attention
 // The codes of a block travel in registers (they are the in-flight memory of the pipeline: two blocks ahead).  The 64
 // scale/zero words of a block would cost as many registers per lane as its 8 KiB of codes, so they go through LDS
@@ -235,12 +350,22 @@ struct HeadRsrc {
     __amdgpu_buffer_rsrc_t k, v, sz;
 };
 
+// A block is 4096 bytes of key codes and as many of value codes: 32 tokens of 8-bit codes, or 64 tokens of 4-bit codes
+// (two 32-token halves of 2048 bytes each, r.k[half][tile], r.v[2*half + i/4]); the load instructions are the same.
+template <int BITS>
 __device__ __forceinline__ void load_block(BlockRegs& r, uint32_t* sz_slot, const HeadRsrc& rs, int blk, int lane)
 {
     // (the host pass of the compiler only needs the kernel's signature; it cannot express the LDS pointer)
 #if defined(__HIP_DEVICE_COMPILE__)
-    __builtin_amdgcn_raw_ptr_buffer_load_lds(rs.sz, (__attribute__((address_space(3))) void*)sz_slot, 4,
-                                             lane * 4 + blk * 256, 0, 0, 0);
+    if constexpr (BITS == 8) {
+        __builtin_amdgcn_raw_ptr_buffer_load_lds(rs.sz, (__attribute__((address_space(3))) void*)sz_slot, 4,
+                                                 lane * 4 + blk * 256, 0, 0, 0);
+    } else {
+        __builtin_amdgcn_raw_ptr_buffer_load_lds(rs.sz, (__attribute__((address_space(3))) void*)sz_slot, 4,
+                                                 lane * 4 + blk * 512, 0, 0, 0);
+        __builtin_amdgcn_raw_ptr_buffer_load_lds(rs.sz, (__attribute__((address_space(3))) void*)(sz_slot + 64), 4,
+                                                 lane * 4 + blk * 512 + 256, 0, 0, 0);
+    }
 #else
     (void)sz_slot;
 #endif
@@ -262,8 +387,12 @@ struct SoftmaxState {
     float m_run, l_run, corr;
 };
 
-__device__ __forceinline__ void process_block(const BlockRegs& r, const uint32_t* sz_slot, const f16x8 (&qf)[4],
-                                              float qsum, int t0, int len, int lane, SoftmaxState& st, f32x4 (&acc)[8])
+// Thirty-two tokens (a whole 8-bit block, or half `sb` of a 4-bit block) starting at token t0.  qsum = sum of the
+// query's 128 values, qbias = sum of the conversion bias of each code position times the query value it meets.
+template <int BITS>
+__device__ __forceinline__ void process_tokens(const BlockRegs& r, int sb, const uint32_t* sz_slot, const f16x8 (&qf)[4],
+                                               float qsum, float qbias, const Magic& mg, int t0, int len, int lane,
+                                               SoftmaxState& st, f32x4 (&acc)[8])
 {
     const int h = lane >> 4;
     // S^T for the two 16-token tiles: rows = tokens, columns = query heads
@@ -272,10 +401,18 @@ __device__ __forceinline__ void process_block(const BlockRegs& r, const uint32_t
 #pragma unroll
     for (int j = 0; j < 2; ++j) {
         f32x4 d = {0.f, 0.f, 0.f, 0.f};
-        d = mfma16x16x32(biased8_w8(r.k[j][0].x, r.k[j][0].y), qf[0], d);
-        d = mfma16x16x32(biased8_w8(r.k[j][0].z, r.k[j][0].w), qf[1], d);
-        d = mfma16x16x32(biased8_w8(r.k[j][1].x, r.k[j][1].y), qf[2], d);
-        d = mfma16x16x32(biased8_w8(r.k[j][1].z, r.k[j][1].w), qf[3], d);
+        if constexpr (BITS == 8) {
+            d = mfma16x16x32(biased8_w8(r.k[j][0].x, r.k[j][0].y), qf[0], d);
+            d = mfma16x16x32(biased8_w8(r.k[j][0].z, r.k[j][0].w), qf[1], d);
+            d = mfma16x16x32(biased8_w8(r.k[j][1].x, r.k[j][1].y), qf[2], d);
+            d = mfma16x16x32(biased8_w8(r.k[j][1].z, r.k[j][1].w), qf[3], d);
+        } else {
+            const u32x4 w = r.k[sb][j];
+            d = mfma16x16x32(biased8(w.x, mg), qf[0], d);
+            d = mfma16x16x32(biased8(w.y, mg), qf[1], d);
+            d = mfma16x16x32(biased8(w.z, mg), qf[2], d);
+            d = mfma16x16x32(biased8(w.w, mg), qf[3], d);
+        }
         // (K pair, V pair) of the lane's four tokens 16j + 4h .. +3: eight consecutive words of the slot
         const u32x4 p0 = *(const u32x4*)(sz_slot + 32 * j + 8 * h);
         const u32x4 p1 = *(const u32x4*)(sz_slot + 32 * j + 8 * h + 4);
@@ -285,11 +422,16 @@ __device__ __forceinline__ void process_block(const BlockRegs& r, const uint32_t
             const uint32_t vw = rr < 2 ? p0[2 * rr + 1] : p1[2 * (rr - 2) + 1];
             const f16x2 kp = as_f16x2(kw), vp = as_f16x2(vw);
             const bool live = t0 + 16 * j + 4 * h + rr < len;
-            // sum_d (1024 + q_d) Q_d  -  (1024 + z) sum_d Q_d  =  sum_d (q_d - z) Q_d ; times the token's scale
-            const float sc = (float)kp.x * (d[rr] - (1024.0f + (float)kp.y) * qsum);
+            // sum_d (bias_d + q_d) Q_d  -  sum_d bias_d Q_d  -  z sum_d Q_d  =  sum_d (q_d - z) Q_d ; times the token's
+            // scale.  8-bit codes all carry the bias 1024; 4-bit codes carry 1024 or 64 by position.
+            float sc;
+            if constexpr (BITS == 8) sc = (float)kp.x * (d[rr] - (1024.0f + (float)kp.y) * qsum);
+            else sc = (float)kp.x * ((d[rr] - qbias) - (float)kp.y * qsum);
             s[j][rr] = live ? sc : kNegBig;
             vs[j][rr] = live ? (float)vp.x : 0.0f;          // a dead token contributes nothing, whatever its pair holds
-            vzb[j][rr] = live ? 1024.0f + (float)vp.y : 0.0f;
+            // the value code of this token is the k-value 4j + rr of the second product: bias 64 at positions 2, 3, 6, 7
+            const float vbias = (BITS == 8 || rr < 2) ? 1024.0f : 64.0f;
+            vzb[j][rr] = live ? vbias + (float)vp.y : 0.0f;
         }
     }
     // online softmax in base 2 (the query carries scale * log2(e))
@@ -306,10 +448,22 @@ __device__ __forceinline__ void process_block(const BlockRegs& r, const uint32_t
         for (int rr = 0; rr < 4; ++rr) {
             const float p = exp2f(s[j][rr] - m_new);        // 0 for masked tokens
             psum += p;
-            const _Float16 pv = (_Float16)(p * vs[j][rr]);  // probability times the value scale of that token
-            pb[4 * j + rr] = pv;
-            csum += vzb[j][rr] * (float)pv;
+            pb[4 * j + rr] = (_Float16)(p * vs[j][rr]);     // probability times the value scale of that token
         }
+    // The correction term must be built from the very fp16 values the matrix core multiplies: the bias is about a
+    // thousand times the payload, so one fp16 ulp of disagreement on a single probability shifts a whole output row by
+    // several per cent.  Left to itself the compiler rounds p * vs once for the operand (fused multiply-and-convert)
+    // and once more, through fp32, for the sum below; the two differ when the fp32 product lands on an fp16 tie.
+    // Pinning the packed operand makes it the only copy.
+    {
+        u32x4 bits = __builtin_bit_cast(u32x4, pb);
+        asm volatile("" : "+v"(bits.x), "+v"(bits.y), "+v"(bits.z), "+v"(bits.w));
+        pb = __builtin_bit_cast(f16x8, bits);
+    }
+#pragma unroll
+    for (int j = 0; j < 2; ++j)
+#pragma unroll
+        for (int rr = 0; rr < 4; ++rr) csum += vzb[j][rr] * (float)pb[4 * j + rr];
     st.l_run = st.l_run * alpha + psum;
     st.corr = st.corr * alpha + csum;
     // the running maximum seldom moves after the first blocks: rescale only when some query head needs it
@@ -320,15 +474,35 @@ __device__ __forceinline__ void process_block(const BlockRegs& r, const uint32_t
     // O^T += V^T P'^T : rows = dimensions (eight 16-row tiles), k = the 32 tokens of the block
 #pragma unroll
     for (int i = 0; i < 8; ++i) {
-        const u32x4 w = r.v[i >> 1];
-        const f16x8 a = (i & 1) ? biased8_w8(w.z, w.w) : biased8_w8(w.x, w.y);
+        f16x8 a;
+        if constexpr (BITS == 8) {
+            const u32x4 w = r.v[i >> 1];
+            a = (i & 1) ? biased8_w8(w.z, w.w) : biased8_w8(w.x, w.y);
+        } else {
+            a = biased8(r.v[2 * sb + (i >> 2)][i & 3], mg);
+        }
         acc[i] = mfma16x16x32(a, pb, acc[i]);
+    }
+}
+
+template <int BITS>
+__device__ __forceinline__ void process_block(const BlockRegs& r, const uint32_t* sz_slot, const f16x8 (&qf)[4],
+                                              float qsum, float qbias, const Magic& mg, int blk, int len, int lane,
+                                              SoftmaxState& st, f32x4 (&acc)[8])
+{
+    if constexpr (BITS == 8) {
+        process_tokens<8>(r, 0, sz_slot, qf, qsum, qbias, mg, blk * 32, len, lane, st, acc);
+    } else {
+        // the first half always holds a live token; the second half may lie wholly behind the context (wave-uniform)
+        process_tokens<4>(r, 0, sz_slot, qf, qsum, qbias, mg, blk * 64, len, lane, st, acc);
+        if (blk * 64 + 32 < len) process_tokens<4>(r, 1, sz_slot + 64, qf, qsum, qbias, mg, blk * 64 + 32, len, lane, st, acc);
     }
 }
 
 // grid (kv heads, batch, splits); 256 threads.  Partial layout per (b, h, split): m[16], l[16], out[128][16] floats.
 constexpr int kPartialFloats = 32 + kHeadDim * 16;
 
+template <int BITS>
 __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))) void attn_decode_kernel(AttnCache kv, const uint16_t* __restrict__ Q,
                                                           const int32_t* __restrict__ lens, uint16_t* __restrict__ O,
                                                           int q_heads, float scale_log2e, int blocks_per_split,
@@ -338,9 +512,10 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))) voi
     __shared__ float sm_out[4][8][4][64];
     // scale/zero words of the blocks in flight: [wave][64 words]; one array per ring slot so that the compiler can tell
     // which direct-to-LDS load a read depends on
-    __shared__ __attribute__((aligned(16))) uint32_t sz_ring0[4][64];
-    __shared__ __attribute__((aligned(16))) uint32_t sz_ring1[4][64];
-    __shared__ __attribute__((aligned(16))) uint32_t sz_ring2[4][64];
+    constexpr int TOK = 256 / BITS;                 // tokens per block
+    __shared__ __attribute__((aligned(16))) uint32_t sz_ring0[4][2 * TOK];
+    __shared__ __attribute__((aligned(16))) uint32_t sz_ring1[4][2 * TOK];
+    __shared__ __attribute__((aligned(16))) uint32_t sz_ring2[4][2 * TOK];
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int c = lane & 15, h = lane >> 4;
@@ -348,14 +523,15 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))) voi
     const int G = q_heads / kv.heads;
     const size_t bh = (size_t)b * kv.heads + hk;
     const int len = min(max(lens[b], 0), kv.cap);
-    const int nblk = (len + 31) >> 5;
+    const int nblk = (len + TOK - 1) / TOK;
     const int blk0 = split * blocks_per_split;
     const int blk1 = min(nblk, blk0 + blocks_per_split);
 
     // Query operand (adaptive head alignment): column m = c, k-values of step tt = dimensions 32h + 8tt .. +7, the
     // order in which the lane's key bytes arrive; scaled once by scale * log2(e).
     f16x8 qf[4];
-    float qsum = 0.f;
+    float qsum = 0.f, qbias = 0.f;
+    const Magic mg = make_magic();
     {
         const bool real = c < G;
         const uint16_t* qp = Q + ((size_t)b * q_heads + (size_t)hk * G + (real ? c : 0)) * kHeadDim + 32 * h;
@@ -367,9 +543,11 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))) voi
                 const _Float16 v = real ? (_Float16)((float)raw[e] * scale_log2e) : (_Float16)0.0f;
                 qf[tt][e] = v;
                 qsum += (float)v;
+                qbias += ((e & 2) ? 64.0f : 1024.0f) * (float)v;     // bias of a 4-bit code at operand position e
             }
         }
         qsum = xor_add(xor_add(qsum, 16), 32);
+        qbias = xor_add(xor_add(qbias, 16), 32);
     }
 
     SoftmaxState st{kNegBig, 0.f, 0.f};
@@ -383,28 +561,28 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))) voi
     // descriptors' ranges and return zeros without memory traffic - so that the loop body is straight-line code with a
     // known number of loads in flight.
     HeadRsrc rs;
-    rs.k = make_rsrc(kv.k + bh * kv.cap * kHeadDim, (uint32_t)nblk * 4096u);
-    rs.v = make_rsrc(kv.v + bh * kv.cap * kHeadDim, (uint32_t)nblk * 4096u);
-    rs.sz = make_rsrc(kv.sz + bh * kv.cap * 2, (uint32_t)nblk * 256u);
+    rs.k = make_rsrc(kv.k + bh * (kv.cap / TOK) * 4096, (uint32_t)nblk * 4096u);
+    rs.v = make_rsrc(kv.v + bh * (kv.cap / TOK) * 4096, (uint32_t)nblk * 4096u);
+    rs.sz = make_rsrc(kv.sz + bh * kv.cap * 2, (uint32_t)nblk * (8u * TOK));
     uint32_t* const z0 = sz_ring0[wave];
     uint32_t* const z1 = sz_ring1[wave];
     uint32_t* const z2 = sz_ring2[wave];
     BlockRegs r0, r1, r2;
     int blk = blk0 + wave;
     if (blk < blk1) {
-        load_block(r0, z0, rs, blk, lane);
-        load_block(r1, z1, rs, blk + 4 < blk1 ? blk + 4 : nblk, lane);
+        load_block<BITS>(r0, z0, rs, blk, lane);
+        load_block<BITS>(r1, z1, rs, blk + 4 < blk1 ? blk + 4 : nblk, lane);
         while (true) {
-            load_block(r2, z2, rs, blk + 8 < blk1 ? blk + 8 : nblk, lane);
-            process_block(r0, z0, qf, qsum, blk * 32, len, lane, st, acc);
+            load_block<BITS>(r2, z2, rs, blk + 8 < blk1 ? blk + 8 : nblk, lane);
+            process_block<BITS>(r0, z0, qf, qsum, qbias, mg, blk, len, lane, st, acc);
             blk += 4;
             if (blk >= blk1) break;
-            load_block(r0, z0, rs, blk + 8 < blk1 ? blk + 8 : nblk, lane);
-            process_block(r1, z1, qf, qsum, blk * 32, len, lane, st, acc);
+            load_block<BITS>(r0, z0, rs, blk + 8 < blk1 ? blk + 8 : nblk, lane);
+            process_block<BITS>(r1, z1, qf, qsum, qbias, mg, blk, len, lane, st, acc);
             blk += 4;
             if (blk >= blk1) break;
-            load_block(r1, z1, rs, blk + 8 < blk1 ? blk + 8 : nblk, lane);
-            process_block(r2, z2, qf, qsum, blk * 32, len, lane, st, acc);
+            load_block<BITS>(r1, z1, rs, blk + 8 < blk1 ? blk + 8 : nblk, lane);
+            process_block<BITS>(r2, z2, qf, qsum, qbias, mg, blk, len, lane, st, acc);
             blk += 4;
             if (blk >= blk1) break;
         }
@@ -521,6 +699,13 @@ hipError_t launch_kv_append(const AttnCache& kv, const uint16_t* Kn, const uint1
 {
     const long waves = (long)kv.batch * count * kv.heads;
     if (waves <= 0 || waves > 0x7fffffffL) return hipErrorInvalidValue;
+    if (kv.bits == 4) {
+        if (kv.heads > 65535 || kv.batch > 65535 || ((((uintptr_t)Kn | (uintptr_t)Vn) & 15))) return hipErrorInvalidValue;
+        const unsigned blocks = (unsigned)((count + 31) / 32 + 1);
+        hipLaunchKernelGGL(kv4_append_block_kernel, dim3(kv.heads, blocks, kv.batch), dim3(256), 0, stream, kv, Kn, Vn,
+                           positions, count);
+        return hipGetLastError();
+    }
     if (count >= 16 && kv.heads <= 65535 && kv.batch <= 65535 && !(((uintptr_t)Kn | (uintptr_t)Vn) & 15)) {
         // blocks a run of `count` tokens can touch: one more than it fills when it starts inside a block
         const unsigned blocks = (unsigned)((count + 31) / 32 + 1);
@@ -535,7 +720,8 @@ hipError_t launch_kv_append(const AttnCache& kv, const uint16_t* Kn, const uint1
 hipError_t launch_attn_decode(const AttnCache& kv, const uint16_t* Q, const int32_t* lens, uint16_t* O, int q_heads,
                               float scale, int max_len, int num_cu, hipStream_t stream)
 {
-    const int nblk = (max_len + 31) / 32;
+    const int tok = 256 / kv.bits;                                   // tokens per 4 KiB block
+    const int nblk = (max_len + tok - 1) / tok;
     // enough CTAs for about three per CU, at least four blocks per wave and split, and no more partial results than
     // the cache's workspace holds
     int splits = (3 * num_cu + kv.batch * kv.heads - 1) / (kv.batch * kv.heads);
@@ -547,8 +733,12 @@ hipError_t launch_attn_decode(const AttnCache& kv, const uint16_t* Q, const int3
     splits = (nblk + bps - 1) / bps > 0 ? (nblk + bps - 1) / bps : 1;
     if (kv.heads > 65535 || kv.batch > 65535) return hipErrorInvalidValue;
     const float scale_log2e = scale * 1.4426950408889634f;
-    hipLaunchKernelGGL(attn_decode_kernel, dim3(kv.heads, kv.batch, splits), dim3(256), 0, stream, kv, Q, lens, O, q_heads,
-                       scale_log2e, bps, splits);
+    if (kv.bits == 8)
+        hipLaunchKernelGGL(attn_decode_kernel<8>, dim3(kv.heads, kv.batch, splits), dim3(256), 0, stream, kv, Q, lens, O,
+                           q_heads, scale_log2e, bps, splits);
+    else
+        hipLaunchKernelGGL(attn_decode_kernel<4>, dim3(kv.heads, kv.batch, splits), dim3(256), 0, stream, kv, Q, lens, O,
+                           q_heads, scale_log2e, bps, splits);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess || splits == 1) return e;
     hipLaunchKernelGGL(attn_merge_kernel, dim3(kv.heads, kv.batch, 8), dim3(256), 0, stream, kv, O, q_heads, splits);

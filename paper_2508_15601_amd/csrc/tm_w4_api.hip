@@ -862,12 +862,13 @@ static bool valid_kv(const tm_kv_cache* c) { return c && c->magic == 0x746D4B56u
 
 tm_kv_cache* tm_kv_create(int batch, int kv_heads, int capacity, int bits)
 {
-    if (batch <= 0 || kv_heads <= 0 || capacity <= 0 || batch > 65535 || kv_heads > 65535 || bits != 8) {
-        fail(TM_EINVAL, "need 1 <= batch, kv_heads <= 65535, capacity > 0, bits == 8 (got %d, %d, %d, %d)", batch, kv_heads,
+    if (batch <= 0 || kv_heads <= 0 || capacity <= 0 || batch > 65535 || kv_heads > 65535 || (bits != 8 && bits != 4)) {
+        fail(TM_EINVAL, "need 1 <= batch, kv_heads <= 65535, capacity > 0, bits 8 or 4 (got %d, %d, %d, %d)", batch, kv_heads,
              capacity, bits);
         return nullptr;
     }
-    const long cap = ((long)capacity + 31) / 32 * 32;
+    const long tok = 256 / bits;                          // tokens per 4 KiB block of codes
+    const long cap = ((long)capacity + tok - 1) / tok * tok;
     const double codes = (double)batch * kv_heads * (double)cap * 128.0;
     if (cap >= (1L << 24) || codes >= 1.0e12) {
         fail(TM_EINVAL, "cache too large");
@@ -884,10 +885,11 @@ tm_kv_cache* tm_kv_create(int batch, int kv_heads, int capacity, int bits)
     c->kv.batch = batch;
     c->kv.heads = kv_heads;
     c->kv.cap = (int)cap;
+    c->kv.bits = bits;
     // partial results of split contexts: at most 1024 (sequence, head, split) slots of 8.3 KiB, at most 64 splits
     int ms = 1024 / (batch * kv_heads);
     c->kv.max_splits = ms < 1 ? 1 : (ms > 64 ? 64 : ms);
-    c->code_bytes = (size_t)batch * kv_heads * cap * 128;
+    c->code_bytes = (size_t)batch * kv_heads * cap * 128 * bits / 8;
     c->pair_bytes = (size_t)batch * kv_heads * cap * 8;
     const size_t part_bytes = (size_t)batch * kv_heads * c->kv.max_splits * (32 + 128 * 16) * sizeof(float);
     hipError_t e = hipMalloc((void**)&c->kv.k, c->code_bytes);
@@ -925,6 +927,8 @@ int tm_kv_append(tm_kv_cache* cache, const uint16_t* K_new, const uint16_t* V_ne
     if (!K_new || !V_new || !positions) return fail(TM_EINVAL, "K_new, V_new or positions is null");
     if (count < 0 || count > cache->kv.cap) return fail(TM_EINVAL, "count = %d out of range", count);
     if (((uintptr_t)K_new & 1) || ((uintptr_t)V_new & 1) || ((uintptr_t)positions & 3)) return fail(TM_EINVAL, "misaligned input");
+    if (cache->kv.bits == 4 && ((((uintptr_t)K_new | (uintptr_t)V_new) & 15)))
+        return fail(TM_EINVAL, "a 4-bit cache needs 16-byte aligned K_new and V_new");
     int dev;
     int rc = check_device(&dev);
     if (rc != TM_OK) return rc;

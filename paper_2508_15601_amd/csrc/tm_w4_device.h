@@ -47,11 +47,12 @@ struct GroupedParams {
 
 // Quantised KV cache of the attention kernels: 8-bit codes, one scale/zero pair per token and head.
 struct AttnCache {
-    uint8_t* k;          // [batch*heads][cap/32] blocks of 4096 bytes in K*Q^T operand order
-    uint8_t* v;          // [batch*heads][cap/32] blocks of 4096 bytes in V^T*P^T operand order
+    uint8_t* k;          // [batch*heads][cap/32] blocks of 32 tokens (4096 or 2048 bytes) in K*Q^T operand order
+    uint8_t* v;          // [batch*heads][cap/32] blocks of 32 tokens in V^T*P^T operand order
     uint32_t* sz;        // [batch*heads][cap][2] scale | zero << 16: K pair, V pair
     float* partial;      // split workspace: [batch*heads][max_splits] x (m[16], l[16], out[128][16])
     int batch, heads, cap, max_splits;
+    int bits;            // 8 or 4 bits per code; cap is a multiple of 256 / bits
 };
 
 __device__ __forceinline__ f16x2 as_f16x2(uint32_t u) { return __builtin_bit_cast(f16x2, u); }

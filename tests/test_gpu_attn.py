@@ -40,16 +40,18 @@ def _dev(a):
 
 @pytest.mark.parametrize("B,Hkv,T,chunks", [(1, 1, 32, [32]), (2, 3, 70, [40, 1, 1, 28]), (3, 2, 97, [97]), (2, 1, 33, [1] * 33),
                                              (2, 2, 300, [5, 200, 15, 80])])
-def test_kv_append_bit_exact(tm, B, Hkv, T, chunks):
+@pytest.mark.parametrize("bits", [8, 4])
+def test_kv_append_bit_exact(tm, B, Hkv, T, chunks, bits):
     """Keys and values appended in chunks land in the cache layout with exactly the oracle's codes and pairs."""
     import torch
-    _say(f"kv append B={B} Hkv={Hkv} T={T} chunks={chunks[:4]}")
+    _say(f"kv append B={B} Hkv={Hkv} T={T} chunks={chunks[:4]} bits={bits}")
+    cbytes = 128 * bits // 8
     _, K, V, _ = wa.draw(B, Hkv, Hkv, T, seed=T)
     K[0, 0, 0, :] = 1.5                                   # a constant row: scale falls back to 1
     V[-1, -1, -1, :64] = 0.0
-    cache = tm.tm_kv_create(B, Hkv, T)
+    cache = tm.tm_kv_create(B, Hkv, T, bits)
     cap = cache.capacity
-    tm.tm_kv_upload(cache, np.zeros(B * Hkv * cap * 128, np.uint8), np.zeros(B * Hkv * cap * 128, np.uint8),
+    tm.tm_kv_upload(cache, np.zeros(B * Hkv * cap * cbytes, np.uint8), np.zeros(B * Hkv * cap * cbytes, np.uint8),
                     np.zeros(B * Hkv * cap * 2, np.uint32))
     pos = 0
     for n in chunks:
@@ -58,11 +60,11 @@ def test_kv_append_bit_exact(tm, B, Hkv, T, chunks):
         tm.tm_kv_append(cache, _dev(Kn), _dev(Vn), torch.full((B,), pos, dtype=torch.int32, device="cuda"))
         pos += n
     kbuf, vbuf, szbuf = tm.tm_kv_download(cache)
-    Kq, Ks, Kz, Vq, Vs, Vz = oa.kv_cache_unpack(kbuf, vbuf, szbuf, B, Hkv, cap)
-    for got, want in zip((Kq, Ks, Kz), oa.kv_quantise(K)):
+    Kq, Ks, Kz, Vq, Vs, Vz = oa.kv_cache_unpack(kbuf, vbuf, szbuf, B, Hkv, cap, bits)
+    for got, want in zip((Kq, Ks, Kz), oa.kv_quantise(K, bits)):
         g, w = got[:, :, :T], want
         assert np.array_equal(g.view(np.uint16) if g.dtype == np.float16 else g, w.view(np.uint16) if w.dtype == np.float16 else w)
-    for got, want in zip((Vq, Vs, Vz), oa.kv_quantise(V)):
+    for got, want in zip((Vq, Vs, Vz), oa.kv_quantise(V, bits)):
         g, w = got[:, :, :T], want
         assert np.array_equal(g.view(np.uint16) if g.dtype == np.float16 else g, w.view(np.uint16) if w.dtype == np.float16 else w)
     assert not Kq[:, :, T:].any() and not Vq[:, :, T:].any()                       # nothing written past the tokens
@@ -73,20 +75,22 @@ def test_kv_append_bit_exact(tm, B, Hkv, T, chunks):
     cache.close()
 
 
-def test_kv_append_ragged_positions(tm):
+@pytest.mark.parametrize("bits", [8, 4])
+def test_kv_append_ragged_positions(tm, bits):
     """Sequences at different positions, runs that start and end inside a 32-token block (the block-wise kernel merges with
     what the cache holds), a run cut off by the capacity, and a run that starts before position 0."""
     import torch
-    B, Hkv, cap = 3, 2, 160
-    _say("kv append ragged positions")
+    B, Hkv, cap = 3, 2, 192
+    _say(f"kv append ragged positions bits={bits}")
+    cbytes = 128 * bits // 8
     _, K, V, _ = wa.draw(B, Hkv, Hkv, cap, seed=11)
-    cache = tm.tm_kv_create(B, Hkv, cap)
+    cache = tm.tm_kv_create(B, Hkv, cap, bits)
     assert cache.capacity == cap
-    tm.tm_kv_upload(cache, np.zeros(B * Hkv * cap * 128, np.uint8), np.zeros(B * Hkv * cap * 128, np.uint8),
+    tm.tm_kv_upload(cache, np.zeros(B * Hkv * cap * cbytes, np.uint8), np.zeros(B * Hkv * cap * cbytes, np.uint8),
                     np.zeros(B * Hkv * cap * 2, np.uint32))
     filled = np.zeros((B, cap), bool)
     # (count, positions per sequence): first lays single tokens and short runs, then long runs over and between them
-    for n, pos in [(3, [0, 30, 157]), (20, [5, 40, 100]), (70, [25, 64, 120]), (33, [-7, 129, 10]), (17, [95, 0, 143])]:
+    for n, pos in [(3, [0, 30, 189]), (20, [5, 40, 100]), (70, [25, 64, 150]), (33, [-7, 129, 10]), (17, [95, 0, 175])]:
         Kn = np.zeros((B, n, Hkv, 128), np.float16)
         Vn = np.zeros((B, n, Hkv, 128), np.float16)
         for b in range(B):
@@ -99,8 +103,8 @@ def test_kv_append_ragged_positions(tm):
                     Kn[b, j], Vn[b, j] = 7.0, -3.0              # must never reach the cache
         tm.tm_kv_append(cache, _dev(Kn), _dev(Vn), torch.tensor(pos, dtype=torch.int32, device="cuda"))
     kbuf, vbuf, szbuf = tm.tm_kv_download(cache)
-    got = oa.kv_cache_unpack(kbuf, vbuf, szbuf, B, Hkv, cap)
-    want = oa.kv_quantise(K) + oa.kv_quantise(V)
+    got = oa.kv_cache_unpack(kbuf, vbuf, szbuf, B, Hkv, cap, bits)
+    want = oa.kv_quantise(K, bits) + oa.kv_quantise(V, bits)
     m = filled[:, None, :]
     assert filled.any() and not filled.all()
     for g, w in zip(got, want):
@@ -124,18 +128,21 @@ ATTN_CASES = [
     (1, 8, 2, 5000, [5000]),               # split context, merged by the second kernel
     (2, 8, 8, 4100, [4100, 1300]),         # splits of which some are empty for the short sequence
     (1, 64, 8, 640, None),
+    (2, 4, 2, 64, [33, 64]),               # a 4-bit block whose second half holds one token / is full
+    (1, 8, 2, 8200, [8161]),               # split context ending in the first half of a 64-token block
 ]
 
 
 @pytest.mark.parametrize("B,Hq,Hkv,T,lens", ATTN_CASES)
-def test_attn_decode_against_oracle(tm, B, Hq, Hkv, T, lens):
+@pytest.mark.parametrize("bits", [8, 4])
+def test_attn_decode_against_oracle(tm, B, Hq, Hkv, T, lens, bits):
     import torch
-    _say(f"attn decode B={B} Hq={Hq} Hkv={Hkv} T={T} lens={lens}")
+    _say(f"attn decode B={B} Hq={Hq} Hkv={Hkv} T={T} lens={lens} bits={bits}")
     Q, K, V, drawn = wa.draw(B, Hq, Hkv, T, seed=B * 100 + Hq + T)
     lens = np.array(lens, np.int32) if lens is not None else drawn
-    Kq, Ks, Kz = oa.kv_quantise(K)
-    Vq, Vs, Vz = oa.kv_quantise(V)
-    cache = tm.tm_kv_create(B, Hkv, T)
+    Kq, Ks, Kz = oa.kv_quantise(K, bits)
+    Vq, Vs, Vz = oa.kv_quantise(V, bits)
+    cache = tm.tm_kv_create(B, Hkv, T, bits)
     cap = cache.capacity
     # the cache is filled by the library's own kernel; positions past T keep whatever the allocation held
     tm.tm_kv_append(cache, _dev(np.ascontiguousarray(K.transpose(0, 2, 1, 3))), _dev(np.ascontiguousarray(V.transpose(0, 2, 1, 3))),
@@ -154,21 +161,23 @@ def test_attn_decode_against_oracle(tm, B, Hq, Hkv, T, lens):
     cache.close()
 
 
-def test_attn_decode_special_cases(tm):
+@pytest.mark.parametrize("bits", [8, 4])
+def test_attn_decode_special_cases(tm, bits):
     """Sharp softmax (one token takes all the weight), a sequence without tokens, cache bytes past the context that hold
     NaN pairs, and max_len left at 0."""
     import torch
-    _say("attn special cases")
-    B, Hq, Hkv, T = 2, 8, 2, 96
+    _say(f"attn special cases bits={bits}")
+    B, Hq, Hkv, T = 2, 8, 2, 128
     Q, K, V, _ = wa.draw(B, Hq, Hkv, T, seed=5)
-    Kq, Ks, Kz = oa.kv_quantise(K)
-    Vq, Vs, Vz = oa.kv_quantise(V)
+    Kq, Ks, Kz = oa.kv_quantise(K, bits)
+    Vq, Vs, Vz = oa.kv_quantise(V, bits)
     Kd = oa.kv_dequant(Kq, Ks, Kz)
     Q[0, :4] = (Kd[0, 0, 70] * 1.0).astype(np.float16)     # heads 0..3 (KV head 0) point at token 70
     lens = np.array([80, 0], np.int32)
-    cache = tm.tm_kv_create(B, Hkv, T)
+    cache = tm.tm_kv_create(B, Hkv, T, bits)
     cap = cache.capacity
-    kbuf, vbuf, szbuf = wa.encode_cache(*[np.ascontiguousarray(a) for a in (Kq, Ks, Kz, Vq, Vs, Vz)])
+    assert cap == T
+    kbuf, vbuf, szbuf = wa.encode_cache(*[np.ascontiguousarray(a) for a in (Kq, Ks, Kz, Vq, Vs, Vz)], bits=bits)
     sz = szbuf.reshape(B, Hkv, cap, 2).copy()
     sz[:, :, 80:] = 0x7E007E00                              # NaN scale and zero-point past the context
     tm.tm_kv_upload(cache, kbuf, vbuf, sz.reshape(-1))
