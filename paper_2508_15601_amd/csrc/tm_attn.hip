@@ -32,6 +32,10 @@ constexpr int kHeadDim = 128;
 constexpr float kNegBig = -1.0e30f;     // "minus infinity" that stays finite under subtraction
 constexpr int kNonTemporal = 2;         // cache-policy bit of a buffer load: streamed once, do not keep
 
+// 2^x by the hardware instruction alone: arguments here are <= 0 and a result below the smallest normal number may
+// flush to zero (the library function spends four more instructions per call on that range).
+__device__ __forceinline__ float fast_exp2(float x) { return __builtin_amdgcn_exp2f(x); }
+
 __device__ __forceinline__ float xor_max(float v, int mask) { return fmaxf(v, __shfl_xor(v, mask)); }
 __device__ __forceinline__ float xor_add(float v, int mask) { return v + __shfl_xor(v, mask); }
 
@@ -329,6 +333,80 @@ __global__ __launch_bounds__(256) void kv4_append_block_kernel(AttnCache kv, con
     *vdst = vc;
 }
 
+// 4-bit codes, one new token per sequence (the append of a decoding step): one wave per (sequence, KV head); lane l owns
+// dimensions l and l + 64.  Key codes: the eight lanes of an operand word OR their nibbles together and one of them
+// stores the word.  Value codes: every dimension has its own word, shared with seven other tokens, so each lane replaces
+// one nibble in each of its two words (no other wave of the launch touches this sequence and head).
+__global__ __launch_bounds__(64) void kv4_append_token_kernel(AttnCache kv, const uint16_t* __restrict__ Kn,
+                                                              const uint16_t* __restrict__ Vn,
+                                                              const int32_t* __restrict__ positions)
+{
+    const int lane = threadIdx.x;
+    const int h = blockIdx.x % kv.heads, b = blockIdx.x / kv.heads;
+    const int t = positions[b];
+    if (t < 0 || t >= kv.cap) return;                       // wave-uniform
+    const size_t bh = (size_t)b * kv.heads + h;
+    const size_t src = bh * kHeadDim;
+    const int u = t & 31;
+    const size_t blk = (bh * (kv.cap / 32) + (t >> 5)) * 512;      // in words
+#pragma unroll
+    for (int which = 0; which < 2; ++which) {
+        const uint16_t* x = (which ? Vn : Kn) + src;
+        const float x0 = (float)__builtin_bit_cast(_Float16, x[lane]);
+        const float x1 = (float)__builtin_bit_cast(_Float16, x[lane + 64]);
+        float mn = fminf(x0, x1), mx = fmaxf(x0, x1);
+#pragma unroll
+        for (int m = 1; m < 64; m <<= 1) {
+            mn = fminf(mn, __shfl_xor(mn, m));
+            mx = fmaxf(mx, __shfl_xor(mx, m));
+        }
+        _Float16 s16 = (_Float16)((mx - mn) / 15.0f);
+        float sf = (float)s16;
+        if (!(sf > 0.0f) || __builtin_isinf(sf)) {
+            sf = 1.0f;
+            s16 = (_Float16)1.0f;
+        }
+        const float zf = fminf(fmaxf(rintf(-mn / sf), 0.0f), 15.0f);
+        const uint32_t q0 = (uint32_t)fminf(fmaxf(rintf(x0 / sf) + zf, 0.0f), 15.0f);
+        const uint32_t q1 = (uint32_t)fminf(fmaxf(rintf(x1 / sf) + zf, 0.0f), 15.0f);
+        if (which == 0) {
+            // dimension d = 32*hh + 8*tt + e: word ((u/16)*64 + 16*hh + u%16)*4 + tt, nibble e/2 + 4*(e % 2)
+            const int e = lane & 7;
+            const int sh = 4 * ((e >> 1) + 4 * (e & 1));
+            uint32_t w0 = q0 << sh, w1 = q1 << sh;
+#pragma unroll
+            for (int m = 1; m < 8; m <<= 1) {
+                w0 |= (uint32_t)__shfl_xor((int)w0, m);
+                w1 |= (uint32_t)__shfl_xor((int)w1, m);
+            }
+            if (e == 0) {
+                uint32_t* kw = reinterpret_cast<uint32_t*>(kv.k) + blk;
+                const int d = lane;                          // and d + 64: two more 32-dimension groups up
+                const int word = ((u >> 4) * 64 + 16 * (d >> 5) + (u & 15)) * 4 + ((d & 31) >> 3);
+                kw[word] = w0;
+                kw[word + 2 * 16 * 4] = w1;
+            }
+        } else {
+            // dimension d = 16*i + c: word ((i/4)*64 + 16*hh + c)*4 + i%4, hh = (u%16)/4; this token is operand element
+            // e = u%4 + 4*(u/16) of the word
+            const int e = (u & 3) + 4 * (u >> 4), hh = (u & 15) >> 2;
+            const int sh = 4 * ((e >> 1) + 4 * (e & 1));
+            uint32_t* vw = reinterpret_cast<uint32_t*>(kv.v) + blk;
+#pragma unroll
+            for (int k = 0; k < 2; ++k) {
+                const int d = lane + 64 * k, i = d >> 4;
+                uint32_t* wp = vw + ((i >> 2) * 64 + 16 * hh + (d & 15)) * 4 + (i & 3);
+                *wp = (*wp & ~(0xfu << sh)) | ((k ? q1 : q0) << sh);
+            }
+        }
+        if (lane == 0) {
+            const _Float16 z16 = (_Float16)zf;
+            kv.sz[(bh * kv.cap + t) * 2 + which] =
+                (uint32_t)__builtin_bit_cast(unsigned short, s16) | ((uint32_t)__builtin_bit_cast(unsigned short, z16) << 16);
+        }
+    }
+}
+
 // ------------------------------------------------------------------------------------------------ decode attention
 // The codes of a block travel in registers (they are the in-flight memory of the pipeline: two blocks ahead).  The 64
 // scale/zero words of a block would cost as many registers per lane as its 8 KiB of codes, so they go through LDS
@@ -389,7 +467,7 @@ struct SoftmaxState {
 
 // Thirty-two tokens (a whole 8-bit block, or half `sb` of a 4-bit block) starting at token t0.  qsum = sum of the
 // query's 128 values, qbias = sum of the conversion bias of each code position times the query value it meets.
-template <int BITS>
+template <int BITS, bool MASKED>
 __device__ __forceinline__ void process_tokens(const BlockRegs& r, int sb, const uint32_t* sz_slot, const f16x8 (&qf)[4],
                                                float qsum, float qbias, const Magic& mg, int t0, int len, int lane,
                                                SoftmaxState& st, f32x4 (&acc)[8])
@@ -400,7 +478,8 @@ __device__ __forceinline__ void process_tokens(const BlockRegs& r, int sb, const
     float vs[2][4], vzb[2][4];
 #pragma unroll
     for (int j = 0; j < 2; ++j) {
-        f32x4 d = {0.f, 0.f, 0.f, 0.f};
+        // the accumulator starts at minus the bias term: sum_d (bias_d + q_d) Q_d - sum_d bias_d Q_d = sum_d q_d Q_d
+        f32x4 d = {-qbias, -qbias, -qbias, -qbias};
         if constexpr (BITS == 8) {
             d = mfma16x16x32(biased8_w8(r.k[j][0].x, r.k[j][0].y), qf[0], d);
             d = mfma16x16x32(biased8_w8(r.k[j][0].z, r.k[j][0].w), qf[1], d);
@@ -418,27 +497,25 @@ __device__ __forceinline__ void process_tokens(const BlockRegs& r, int sb, const
         const u32x4 p1 = *(const u32x4*)(sz_slot + 32 * j + 8 * h + 4);
 #pragma unroll
         for (int rr = 0; rr < 4; ++rr) {
+            const bool live = !MASKED || t0 + 16 * j + 4 * h + rr < len;
             const uint32_t kw = rr < 2 ? p0[2 * rr] : p1[2 * (rr - 2)];
-            const uint32_t vw = rr < 2 ? p0[2 * rr + 1] : p1[2 * (rr - 2) + 1];
+            // a dead token contributes nothing, whatever its pair holds: scale 0 and zero-point 0 for its values
+            const uint32_t vw = live ? (rr < 2 ? p0[2 * rr + 1] : p1[2 * (rr - 2) + 1]) : 0u;
             const f16x2 kp = as_f16x2(kw), vp = as_f16x2(vw);
-            const bool live = t0 + 16 * j + 4 * h + rr < len;
-            // sum_d (bias_d + q_d) Q_d  -  sum_d bias_d Q_d  -  z sum_d Q_d  =  sum_d (q_d - z) Q_d ; times the token's
-            // scale.  8-bit codes all carry the bias 1024; 4-bit codes carry 1024 or 64 by position.
-            float sc;
-            if constexpr (BITS == 8) sc = (float)kp.x * (d[rr] - (1024.0f + (float)kp.y) * qsum);
-            else sc = (float)kp.x * ((d[rr] - qbias) - (float)kp.y * qsum);
+            // sum_d q_d Q_d  -  z sum_d Q_d  =  sum_d (q_d - z) Q_d ; times the token's scale
+            const float sc = (float)kp.x * (d[rr] - (float)kp.y * qsum);
             s[j][rr] = live ? sc : kNegBig;
-            vs[j][rr] = live ? (float)vp.x : 0.0f;          // a dead token contributes nothing, whatever its pair holds
+            vs[j][rr] = (float)vp.x;
             // the value code of this token is the k-value 4j + rr of the second product: bias 64 at positions 2, 3, 6, 7
             const float vbias = (BITS == 8 || rr < 2) ? 1024.0f : 64.0f;
-            vzb[j][rr] = live ? vbias + (float)vp.y : 0.0f;
+            vzb[j][rr] = vbias + (float)vp.y;
         }
     }
     // online softmax in base 2 (the query carries scale * log2(e))
     float mx = fmaxf(fmaxf(fmaxf(s[0][0], s[0][1]), fmaxf(s[0][2], s[0][3])), fmaxf(fmaxf(s[1][0], s[1][1]), fmaxf(s[1][2], s[1][3])));
     mx = xor_max(xor_max(mx, 16), 32);
     const float m_new = fmaxf(st.m_run, mx);
-    const float alpha = exp2f(st.m_run - m_new);
+    const float alpha = fast_exp2(st.m_run - m_new);
     st.m_run = m_new;
     float psum = 0.f, csum = 0.f;
     f16x8 pb;
@@ -446,7 +523,7 @@ __device__ __forceinline__ void process_tokens(const BlockRegs& r, int sb, const
     for (int j = 0; j < 2; ++j)
 #pragma unroll
         for (int rr = 0; rr < 4; ++rr) {
-            const float p = exp2f(s[j][rr] - m_new);        // 0 for masked tokens
+            const float p = fast_exp2(s[j][rr] - m_new);    // 0 for masked tokens
             psum += p;
             pb[4 * j + rr] = (_Float16)(p * vs[j][rr]);     // probability times the value scale of that token
         }
@@ -490,12 +567,14 @@ __device__ __forceinline__ void process_block(const BlockRegs& r, const uint32_t
                                               float qsum, float qbias, const Magic& mg, int blk, int len, int lane,
                                               SoftmaxState& st, f32x4 (&acc)[8])
 {
-    if constexpr (BITS == 8) {
-        process_tokens<8>(r, 0, sz_slot, qf, qsum, qbias, mg, blk * 32, len, lane, st, acc);
-    } else {
-        // the first half always holds a live token; the second half may lie wholly behind the context (wave-uniform)
-        process_tokens<4>(r, 0, sz_slot, qf, qsum, qbias, mg, blk * 64, len, lane, st, acc);
-        if (blk * 64 + 32 < len) process_tokens<4>(r, 1, sz_slot + 64, qf, qsum, qbias, mg, blk * 64 + 32, len, lane, st, acc);
+    constexpr int TOK = 256 / BITS;
+    const int t0 = blk * TOK;
+    // the first 32 tokens always hold a live one; the second half of a 4-bit block may lie wholly behind the context
+    // (wave-uniform).  (A second, unmasked copy of the code for blocks inside the context costs more registers than the
+    // kernel has: it spills.)
+    process_tokens<BITS, true>(r, 0, sz_slot, qf, qsum, qbias, mg, t0, len, lane, st, acc);
+    if constexpr (BITS == 4) {
+        if (t0 + 32 < len) process_tokens<4, true>(r, 1, sz_slot + 64, qf, qsum, qbias, mg, t0 + 32, len, lane, st, acc);
     }
 }
 
@@ -547,7 +626,7 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))) voi
             }
         }
         qsum = xor_add(xor_add(qsum, 16), 32);
-        qbias = xor_add(xor_add(qbias, 16), 32);
+        qbias = BITS == 8 ? 1024.0f * qsum : xor_add(xor_add(qbias, 16), 32);   // every 8-bit code carries the bias 1024
     }
 
     SoftmaxState st{kNegBig, 0.f, 0.f};
@@ -701,6 +780,10 @@ hipError_t launch_kv_append(const AttnCache& kv, const uint16_t* Kn, const uint1
     if (waves <= 0 || waves > 0x7fffffffL) return hipErrorInvalidValue;
     if (kv.bits == 4) {
         if (kv.heads > 65535 || kv.batch > 65535 || ((((uintptr_t)Kn | (uintptr_t)Vn) & 15))) return hipErrorInvalidValue;
+        if (count == 1) {
+            hipLaunchKernelGGL(kv4_append_token_kernel, dim3((unsigned)waves), dim3(64), 0, stream, kv, Kn, Vn, positions);
+            return hipGetLastError();
+        }
         const unsigned blocks = (unsigned)((count + 31) / 32 + 1);
         hipLaunchKernelGGL(kv4_append_block_kernel, dim3(kv.heads, blocks, kv.batch), dim3(256), 0, stream, kv, Kn, Vn,
                            positions, count);
