@@ -371,6 +371,44 @@ def attn_table(tm, torch, iters=50, q_heads=32, kv_heads=8, only=None, bits=8):
     return rows
 
 
+def attn_companion(torch, iters=20, q_heads=32, kv_heads=8, only=None):
+    """The companion measurement of the attention rows: the same decode step over an unquantised fp16 cache through the
+    framework's own fused attention (`scaled_dot_product_attention`, grouped-query mode) - what a serving stack without
+    the quantised cache runs.  Same rotation over > 512 MB; HIP-graph replay when the library call can be captured."""
+    import torch.nn.functional as F
+    rows = []
+    for B, T in ATTN_SHAPES:
+        if only is not None and (B, T) != only:
+            continue
+        per_cache = B * kv_heads * T * 2 * 128 * 2
+        copies = max(2, -(-ROTATE_BYTES // per_cache))
+        Ks = [torch.randn((B, kv_heads, T, 128), device="cuda").to(torch.float16) for _ in range(copies)]
+        Vs = [torch.randn((B, kv_heads, T, 128), device="cuda").to(torch.float16) for _ in range(copies)]
+        Q = torch.randn((B, q_heads, 1, 128), device="cuda").to(torch.float16)
+        out = [None]
+        turn = [0]
+
+        def step():
+            i = turn[0] % copies
+            out[0] = F.scaled_dot_product_attention(Q, Ks[i], Vs[i], enable_gqa=True)
+            turn[0] += 1
+
+        try:
+            ev_ms, _ = time_steps(torch, step, iters, 3, graph_steps=iters)
+            how = "graph"
+        except Exception:
+            torch.cuda.synchronize()
+            ev_ms, _ = time_steps(torch, step, iters, 3, graph_steps=0)
+            how = "eager"
+        t = ev_ms / iters * 1e-3
+        bytes_ = per_cache + 2 * B * q_heads * 128 * 2
+        rows.append({"batch": B, "context": T, "us": t * 1e6, "GBps": bytes_ / t / 1e9, "timed": how})
+        log(f"attn decode fp16 cache (library)  batch {B:4d} context {T:6d}  {t * 1e6:9.2f} us  {bytes_ / t / 1e9:7.0f} GB/s  ({how})")
+        del Ks, Vs
+        torch.cuda.empty_cache()
+    return rows
+
+
 def attn_store_row(tm, torch, iters=20, B=16, T=2048, kv_heads=8, bits=8):
     """Quantise-and-store of a whole prompt (the prefill side of the cache): reads 2 fp16 tensors, writes codes + pairs."""
     c = tm.tm_kv_create(B, kv_heads, T, bits)
@@ -441,6 +479,8 @@ def main():
     ap.add_argument("--workload", default="decode", choices=sorted(WORKLOADS) + ["sweep", "copy", "companion", "pack", "moe", "w8", "attn"])
     ap.add_argument("--sweep-out", default=None, help="with --workload sweep: write the per-shape table here (JSON)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--attn-companion", action="store_true",
+                    help="attn workload: also time the framework's fused attention over an fp16 cache on the same shapes")
     ap.add_argument("--no-prefill", action="store_true", help="skip the prefill companion measurement")
     ap.add_argument("--companion-workloads", default="decode,mlp_decode,sweep5,prefill",
                     help="workloads the fp16 x fp16 companion covers (comma-separated; one of them makes a short profiler run)")
@@ -515,15 +555,20 @@ def main():
             os.makedirs(os.path.dirname(os.path.abspath(args.sweep_out)), exist_ok=True)
             json.dump(table, open(args.sweep_out, "w"), indent=1)
         best = max(table, key=lambda r: r["GBps"])
+        traffic = None                      # HBM bytes per launch from the committed profile of that shape and code width
+        traffic_file = os.path.join(ROOT, "profiles", "traffic.json")
+        if os.path.exists(traffic_file) and (best["batch"], best["context"]) == (128, 2048):
+            traffic = json.load(open(traffic_file)).get(f"attn_kv{best['kv_bits']}")
         print(json.dumps({"metric": "decode attention over a quantised KV cache: effective HBM GB/s", "workload": "attn",
                           "value": best["GBps"], "unit": "GB/s", "n_gpus": 1, "dtype": "u8 / u4 codes, f16 activations, f32 accumulation",
                           "data": "synthetic", "config": {"workload": f"KV{best['kv_bits']}, batch {best['batch']} x context {best['context']}, "
                                                                       f"{best['q_heads']} query / {best['kv_heads']} KV heads, head dimension 128"},
                           "roofline": {"bound": "hbm", "achieved": best["GBps"], "peak": HBM_PEAK_GBPS, "unit": "GB/s",
-                                       "frac": best["hbm_frac"], "traffic": None, "kernel": f"attn_decode_kernel<{best['kv_bits']}>",
+                                       "frac": best["hbm_frac"], "traffic": traffic, "kernel": f"attn_decode_kernel<{best['kv_bits']}>",
                                        "avg_launch_us": best["us"]},
                           "cpu_baseline": None if args.no_cpu_baseline else attn_cpu_baseline(),
                           "store": None if only is not None else [attn_store_row(tm, torch), attn_store_row(tm, torch, bits=4)],
+                          "fp16_cache_library": attn_companion(torch, iters=min(args.steps, 20)) if args.attn_companion else None,
                           "rows": table}))
         return
 

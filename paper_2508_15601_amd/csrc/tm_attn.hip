@@ -619,10 +619,16 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))) voi
             const f16x8 raw = *(const f16x8*)(qp + 8 * tt);
 #pragma unroll
             for (int e = 0; e < 8; ++e) {
-                const _Float16 v = real ? (_Float16)((float)raw[e] * scale_log2e) : (_Float16)0.0f;
-                qf[tt][e] = v;
-                qsum += (float)v;
-                qbias += ((e & 2) ? 64.0f : 1024.0f) * (float)v;     // bias of a 4-bit code at operand position e
+                qf[tt][e] = real ? (_Float16)((float)raw[e] * scale_log2e) : (_Float16)0.0f;
+            }
+            // the sums below must see the very fp16 values the matrix core multiplies (one rounding, one copy)
+            u32x4 bits = __builtin_bit_cast(u32x4, qf[tt]);
+            asm volatile("" : "+v"(bits.x), "+v"(bits.y), "+v"(bits.z), "+v"(bits.w));
+            qf[tt] = __builtin_bit_cast(f16x8, bits);
+#pragma unroll
+            for (int e = 0; e < 8; ++e) {
+                qsum += (float)qf[tt][e];
+                qbias += ((e & 2) ? 64.0f : 1024.0f) * (float)qf[tt][e];     // bias of a 4-bit code at operand position e
             }
         }
         qsum = xor_add(xor_add(qsum, 16), 32);

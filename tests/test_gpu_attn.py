@@ -191,3 +191,35 @@ def test_attn_decode_special_cases(tm, bits):
     assert ok, (worst, fro)
     assert np.allclose(O[0, 0].astype(np.float64), oa.kv_dequant(Vq, Vs, Vz)[0, 0, 70], rtol=1e-2, atol=2e-3)
     cache.close()
+
+
+@pytest.mark.parametrize("bits", [8, 4])
+def test_attn_decode_full_size_sampled(tm, bits):
+    """The benchmark's largest shape in its own launch configuration (batch 128 x context 2048, 32 query / 8 KV heads, the
+    prompt stored by one block-wise append, one decode launch without splits); the oracle recomputes a sample of the
+    sequences from the same keys and values."""
+    import torch
+    B, Hq, Hkv, T = 128, 32, 8, 2048
+    _say(f"attn full size B={B} T={T} bits={bits}")
+    g = torch.Generator(device="cuda").manual_seed(1234 + bits)
+    K = torch.randn((B, T, Hkv, 128), generator=g, device="cuda").to(torch.float16)
+    V = torch.randn((B, T, Hkv, 128), generator=g, device="cuda").to(torch.float16)
+    Q = torch.randn((B, Hq, 128), generator=g, device="cuda").to(torch.float16)
+    lens = torch.randint(1, T + 1, (B,), generator=g, device="cuda").to(torch.int32)
+    lens[0] = T
+    lens[5] = 1
+    cache = tm.tm_kv_create(B, Hkv, T, bits)
+    tm.tm_kv_append(cache, K, V, torch.zeros(B, dtype=torch.int32, device="cuda"))
+    O = torch.full((B, Hq, 128), float("nan"), dtype=torch.float16, device="cuda")
+    scale = 1.0 / np.sqrt(128.0)
+    tm.tm_attn_decode(Q, cache, lens, O, scale, max_len=T)
+    torch.cuda.synchronize()
+    assert not torch.isnan(O).any()
+    sample = [0, 5, 17, 64, 127]
+    Ks = K[sample].permute(0, 2, 1, 3).contiguous().cpu().numpy()           # [n, Hkv, T, 128]
+    Vs = V[sample].permute(0, 2, 1, 3).contiguous().cpu().numpy()
+    Oref = oa.attn_decode(Q[sample].cpu().numpy(), *oa.kv_quantise(Ks, bits), *oa.kv_quantise(Vs, bits),
+                          lens[sample].cpu().numpy(), scale)
+    ok, worst, fro = _close(O[sample].cpu().numpy(), Oref)
+    assert ok, (worst, fro)
+    cache.close()
