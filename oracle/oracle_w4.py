@@ -305,3 +305,24 @@ def gemm_sampled(X, q, s, z, group: int, ms, ns, want_fp64: bool = False):
     _check(_load().orc_gemm_sampled(_ptr(X), M, _ptr(q), _ptr(s), _ptr(z), K, N, group, _ptr(ms), _ptr(ns),
                                     ms.size, _ptr(Y), _ptr(Yd) if want_fp64 else None), "gemm_sampled")
     return (Y.view(np.float16), Yd) if want_fp64 else Y.view(np.float16)
+
+
+def epilogue(Yd: np.ndarray, bias=None, residual=None, act: str = "none") -> np.ndarray:
+    """What surrounds the matrix product in a transformer block, written out in fp64 (not in the paper: the widened
+    "fused epilogue" row): Yd [M, N] unrounded sums -> fp16.
+      bias      [N]: added to every row
+      act       "none", or "silu_mul": the columns are [gate | up] halves and the result is silu(gate) * up, [M, N/2],
+                silu(x) = x / (1 + exp(-x))
+      residual  [M, N_out]: added last."""
+    Y = np.asarray(Yd, np.float64)
+    if bias is not None:
+        Y = Y + np.asarray(bias).astype(np.float64)[None, :]
+    if act == "silu_mul":
+        half = Y.shape[1] // 2
+        g, u = Y[:, :half], Y[:, half:]
+        Y = g / (1.0 + np.exp(-g)) * u
+    elif act != "none":
+        raise ValueError(act)
+    if residual is not None:
+        Y = Y + np.asarray(residual).astype(np.float64)
+    return Y.astype(np.float16)

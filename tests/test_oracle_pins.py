@@ -554,3 +554,27 @@ def test_gidx_forms_against_plain_forms_and_numpy(oracle):
     assert np.allclose(Y1, Y2, rtol=2e-3, atol=2e-3)
     with pytest.raises(ValueError):
         oracle.gemm_gidx(X, q, s, z, np.full(K, K // g, np.int32))                                # index out of range
+
+
+def test_epilogue_closed_forms_and_torch_silu(oracle):
+    """The epilogue oracle against values fixed by the definition and against PyTorch's CPU silu."""
+    import torch
+    Y = np.array([[0.0, 1.0, -1.0, 20.0, 2.0, 3.0, 4.0, 0.5]], np.float64)          # gate = first four, up = last four
+    out = oracle.epilogue(Y, act="silu_mul").astype(np.float64)
+    want = [0.0, 1.0 / (1.0 + np.e ** -1.0) * 3.0, -1.0 / (1.0 + np.e) * 4.0, 20.0 * 0.5]
+    assert out.shape == (1, 4) and np.allclose(out[0], want, rtol=1e-3)
+    assert out[0, 0] == 0.0 and abs(out[0, 3] - 10.0) < 1e-2                           # silu(0) = 0, silu(x) -> x
+    # bias is added before the activation, the residual after it
+    b = np.array([1.0, 0, 0, 0, 0, 0, 0, 0])
+    r = np.full((1, 4), 0.25)
+    out2 = oracle.epilogue(Y, bias=b, residual=r, act="silu_mul").astype(np.float64)
+    assert abs(out2[0, 0] - (1.0 / (1.0 + np.e ** -1.0) * 2.0 + 0.25)) < 2e-3
+    assert np.allclose(out2[0, 1:], out[0, 1:] + 0.25, atol=4e-3)
+    # without activation: plain sums, rounded once
+    out3 = oracle.epilogue(Y, bias=b, residual=np.ones((1, 8)))
+    assert out3.dtype == np.float16 and out3[0].tolist() == [2.0, 2.0, 0.0, 21.0, 3.0, 4.0, 5.0, 1.5]
+    rng = np.random.default_rng(0)
+    G, U = rng.standard_normal((5, 64)) * 4, rng.standard_normal((5, 64)) * 4
+    ref = (torch.nn.functional.silu(torch.from_numpy(G)) * torch.from_numpy(U)).numpy()
+    got = oracle.epilogue(np.concatenate([G, U], axis=1), act="silu_mul").astype(np.float64)
+    assert np.allclose(got, ref, rtol=1e-3, atol=1e-3)
