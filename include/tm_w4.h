@@ -150,6 +150,37 @@ TM_API int tm_packed_bits(const tm_packed_w4* packed);
 TM_API int tm_gemm_w4a16(const uint16_t* X, const tm_packed_w4* packed, uint16_t* Y, int M, tm_stream stream);
 
 /*
+ * The same product with what surrounds it in a transformer block fused into the kernels' final store (not a technique
+ * of the paper; it removes the extra pass over Y that an unfused bias / activation / residual costs):
+ *
+ *     T = X * dequant(packed) + bias                                   bias fp16 [N], or NULL
+ *     U = T                        (TM_ACT_NONE)                       [M][N]
+ *       = silu(T_gate) * T_up      (TM_ACT_SILU_MUL)                   [M][N/2], silu(x) = x / (1 + exp(-x))
+ *     Y = fp16(U + residual)                                           residual fp16 [M][N or N/2], or NULL
+ *
+ * all in fp32 on the fp32 sums, rounded once.  TM_ACT_SILU_MUL takes the fused gate+up projection of a gated MLP: the
+ * weight's columns are [gate (N/2) | up (N/2)] and the handle must come from tm_pack_w4_gate_up, which stores gate
+ * column j and up column j side by side so that one thread holds both; such a handle is accepted by this call with
+ * TM_ACT_SILU_MUL only.  bias and residual follow the caller's column order and must be 16-byte aligned; Y as above.
+ * epilogue == NULL is tm_gemm_w4a16.  Works for every weight format a handle can hold.
+ */
+typedef enum tm_activation { TM_ACT_NONE = 0, TM_ACT_SILU_MUL = 1 } tm_activation;
+typedef struct tm_epilogue {
+    const uint16_t* bias;      /* device, fp16 [N], or NULL */
+    const uint16_t* residual;  /* device, fp16 [M][N] (TM_ACT_NONE) or [M][N/2] (TM_ACT_SILU_MUL), or NULL */
+    int act;                   /* tm_activation */
+} tm_epilogue;
+TM_API int tm_gemm_w4a16_ex(const uint16_t* X, const tm_packed_w4* packed, uint16_t* Y, int M, const tm_epilogue* epilogue,
+                            tm_stream stream);
+/*
+ * tm_pack_w4 for a fused [gate | up] weight (N = 2 * intermediate size, N % 32 == 0; inputs in the layout of
+ * tm_pack_w4, zeros may be NULL): the columns are interleaved as (gate j, up j) pairs before the packing.  Synchronises
+ * `stream` once (the interleaved copies are temporaries).  The handle serves tm_gemm_w4a16_ex with TM_ACT_SILU_MUL.
+ */
+TM_API tm_packed_w4* tm_pack_w4_gate_up(const uint32_t* qweight, const uint16_t* scales, const uint16_t* zeros, int K, int N,
+                                        int group, tm_stream stream);
+
+/*
  * Same multiply with a caller-owned workspace of at least tm_gemm_workspace_bytes(packed, M) bytes, 256-byte aligned.
  * The workspace must be zero-filled once before its first use; every call leaves it ready for the next one.
  * Distinct workspaces may be used concurrently on distinct streams.

@@ -25,6 +25,10 @@ def lib_path() -> str:
     return _LIB_PATH
 
 
+class TmEpilogue(ctypes.Structure):
+    _fields_ = [("bias", ctypes.c_void_p), ("residual", ctypes.c_void_p), ("act", ctypes.c_int)]
+
+
 def load_library():
     """dlopen libtm_w4.so (built by paper_2508_15601_amd/build.py) and declare every entry point."""
     global _lib
@@ -72,6 +76,10 @@ def load_library():
     lib.tm_pack_w4_layout.argtypes = [vp, vp, vp, i, i, i, i, vp]
     lib.tm_gemm_w4a16.restype = i
     lib.tm_gemm_w4a16.argtypes = [vp, vp, vp, i, vp]
+    lib.tm_gemm_w4a16_ex.restype = i
+    lib.tm_gemm_w4a16_ex.argtypes = [vp, vp, vp, i, c.POINTER(TmEpilogue), vp]
+    lib.tm_pack_w4_gate_up.restype = vp
+    lib.tm_pack_w4_gate_up.argtypes = [vp, vp, vp, i, i, i, vp]
     lib.tm_gemm_w4a16_ws.restype = i
     lib.tm_gemm_w4a16_ws.argtypes = [vp, vp, vp, i, vp, sz, vp]
     lib.tm_gemm_workspace_bytes.restype = sz
@@ -309,6 +317,41 @@ def tm_gemm_w4a16(X, packed: PackedW4, Y, stream=None):
     _check(load_library().tm_gemm_w4a16(_dev_ptr(X, torch.float16, "X"), packed.handle,
                                         _dev_ptr(Y, torch.float16, "Y"), M, _stream_ptr(stream)))
     return Y
+
+
+TM_ACT_NONE, TM_ACT_SILU_MUL = 0, 1
+
+
+def tm_gemm_w4a16_ex(X, packed: PackedW4, Y, bias=None, residual=None, act: int = TM_ACT_NONE, stream=None):
+    """Y = fp16(act(X * dequant(packed) + bias) + residual); with TM_ACT_SILU_MUL (handles of tm_pack_w4_gate_up) Y and
+    residual are [M, N/2].  All float16 device tensors."""
+    import torch
+    M = X.shape[0]
+    n_out = packed.N // 2 if act == TM_ACT_SILU_MUL else packed.N
+    if X.dim() != 2 or X.shape[1] != packed.K or tuple(Y.shape) != (M, n_out) or \
+            (bias is not None and tuple(bias.shape) != (packed.N,)) or (residual is not None and tuple(residual.shape) != (M, n_out)):
+        raise ValueError("X / Y / bias / residual shapes do not match the packed weight")
+    if M == 0:
+        return Y
+    epi = TmEpilogue(None if bias is None else _dev_ptr(bias, torch.float16, "bias"),
+                     None if residual is None else _dev_ptr(residual, torch.float16, "residual"), int(act))
+    _check(load_library().tm_gemm_w4a16_ex(_dev_ptr(X, torch.float16, "X"), packed.handle, _dev_ptr(Y, torch.float16, "Y"), M,
+                                           ctypes.byref(epi), _stream_ptr(stream)))
+    return Y
+
+
+def tm_pack_w4_gate_up(qweight, scales, zeros, K: int, N: int, group: int, stream=None) -> PackedW4:
+    """Fused [gate | up] weight in the layout of tm_pack_w4 -> handle for tm_gemm_w4a16_ex(..., act=TM_ACT_SILU_MUL)."""
+    import torch
+    if tuple(qweight.shape) != (K, N // 8) or tuple(scales.shape) != (K // group, N) or \
+            (zeros is not None and tuple(zeros.shape) != (K // group, N)):
+        raise ValueError("tensor shapes do not match K, N, group")
+    h = load_library().tm_pack_w4_gate_up(_dev_ptr(qweight, torch.int32, "qweight"), _dev_ptr(scales, torch.float16, "scales"),
+                                          None if zeros is None else _dev_ptr(zeros, torch.float16, "zeros"), K, N, group,
+                                          _stream_ptr(stream))
+    if not h:
+        raise TmError(-1, tm_last_error())
+    return PackedW4(h, K, N, min(group, 128))
 
 
 def tm_gemm_w4a16_ws(X, packed: PackedW4, Y, workspace, stream=None):

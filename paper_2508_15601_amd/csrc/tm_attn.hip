@@ -26,7 +26,6 @@ namespace tmw4 {
 
 namespace {
 
-typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
 
 constexpr int kHeadDim = 128;
 constexpr float kNegBig = -1.0e30f;     // "minus infinity" that stays finite under subtraction

@@ -99,6 +99,7 @@ struct tm_packed_w4 {
     int K, N, group, device;
     int bits;          // width of the weight codes: 4, or 8 (tm_pack_w8, tm_pack_w8_fp8)
     bool fp8;          // the 8-bit codes are FP8 E4M3 numbers, not integers
+    bool gate_up;      // columns interleaved as (gate j, up j) pairs (tm_pack_w4_gate_up)
     int32_t* perm;     // activation-order handles: packed row i is checkpoint row perm[i] (device, K entries); else null
     uint32_t* w;       // K*N/8 words
     uint32_t* sz;      // (K/group)*N words
@@ -330,7 +331,7 @@ size_t align256(size_t v) { return (v + 255) & ~(size_t)255; }
 
 // x_regrouped: X already follows the packed row order of an activation-order handle
 int run_gemm(const uint16_t* X, const tm_packed_w4* h, uint16_t* Y, int M, void* ws, size_t ws_bytes, bool own_ws,
-             hipStream_t stream, bool x_regrouped = false)
+             hipStream_t stream, bool x_regrouped = false, const tm_epilogue* epi = nullptr)
 {
     if (!valid(h)) return fail(TM_EINVAL, "packed handle is null or invalid");
     if (M < 0 || M >= (1 << 24)) return fail(TM_EINVAL, "M = %d out of range", M);
@@ -338,6 +339,15 @@ int run_gemm(const uint16_t* X, const tm_packed_w4* h, uint16_t* Y, int M, void*
     if (!X || !Y) return fail(TM_EINVAL, "X or Y is null");
     if (((uintptr_t)X & 15) || ((uintptr_t)Y & 15)) return fail(TM_EINVAL, "X and Y must be 16-byte aligned");
     if ((uint64_t)M * (uint64_t)h->K >= (1ull << 31)) return fail(TM_EINVAL, "M*K must be below 2^31");
+    const bool act = epi && epi->act != TM_ACT_NONE;
+    if (epi) {
+        if (epi->act != TM_ACT_NONE && epi->act != TM_ACT_SILU_MUL) return fail(TM_EINVAL, "unknown activation %d", epi->act);
+        if (act && !h->gate_up) return fail(TM_EINVAL, "silu(gate)*up needs a handle made by tm_pack_w4_gate_up");
+        if (((uintptr_t)epi->bias & 15) || ((uintptr_t)epi->residual & 15))
+            return fail(TM_EINVAL, "bias and residual must be 16-byte aligned");
+    }
+    if (h->gate_up && !act) return fail(TM_EINVAL, "a gate/up handle holds interleaved columns: call tm_gemm_w4a16_ex with TM_ACT_SILU_MUL");
+    const int ldy = act ? h->N / 2 : h->N;
     int dev;
     int rc = check_device(&dev);
     if (rc != TM_OK) return rc;
@@ -355,7 +365,12 @@ int run_gemm(const uint16_t* X, const tm_packed_w4* h, uint16_t* Y, int M, void*
                 const int rows = M - m0 < rows_max ? M - m0 : rows_max;
                 hipError_t e = launch_permute_x(X + (size_t)m0 * h->K, h->perm, xb, rows, h->K, stream);
                 if (e != hipSuccess) return fail_hip(e, "regroup launch");
-                rc = run_gemm(xb, h, Y + (size_t)m0 * h->N, rows, ws, ws_bytes, own_ws, stream, true);
+                tm_epilogue part{};
+                if (epi) {
+                    part = *epi;
+                    if (part.residual) part.residual += (size_t)m0 * ldy;
+                }
+                rc = run_gemm(xb, h, Y + (size_t)m0 * ldy, rows, ws, ws_bytes, own_ws, stream, true, epi ? &part : nullptr);
                 if (rc != TM_OK) return rc;
             }
             return TM_OK;
@@ -368,7 +383,7 @@ int run_gemm(const uint16_t* X, const tm_packed_w4* h, uint16_t* Y, int M, void*
         uint16_t* xb = (uint16_t*)((char*)ws + plan_bytes);
         hipError_t e = launch_permute_x(X, h->perm, xb, M, h->K, stream);
         if (e != hipSuccess) return fail_hip(e, "regroup launch");
-        return run_gemm(xb, h, Y, M, ws, plan_bytes, own_ws, stream, true);
+        return run_gemm(xb, h, Y, M, ws, plan_bytes, own_ws, stream, true, epi);
     }
     Plan pl = make_plan(h, M, g_dev[dev].num_cu);
     if (own_ws) {
@@ -400,6 +415,13 @@ int run_gemm(const uint16_t* X, const tm_packed_w4* h, uint16_t* Y, int M, void*
     p.tiles_m = pl.tiles_m;
     p.tiles_n = pl.tiles_n;
     p.strips = pl.strips;
+    p.ldy = ldy;
+    if (epi) {
+        p.bias = epi->bias;
+        p.residual = epi->residual;
+        p.act = act ? 1 : 0;
+        p.epi = (p.bias != nullptr) | (p.residual != nullptr) | p.act;
+    }
     hipError_t e = h->bits == 8 ? (!is_skinny(pl.variant) ? launch_tile_8bit(p, pl, h->group, h->fp8, stream)
                                    : h->fp8 ? launch_skinny_f8(p, pl, h->group, stream)
                                             : launch_skinny_w8(p, pl, h->group, stream))
@@ -591,6 +613,56 @@ int tm_gemm_w4a16(const uint16_t* X, const tm_packed_w4* packed, uint16_t* Y, in
     return run_gemm(X, packed, Y, M, nullptr, 0, true, (hipStream_t)stream);
 }
 
+int tm_gemm_w4a16_ex(const uint16_t* X, const tm_packed_w4* packed, uint16_t* Y, int M, const tm_epilogue* epilogue,
+                     tm_stream stream)
+{
+    return run_gemm(X, packed, Y, M, nullptr, 0, true, (hipStream_t)stream, false, epilogue);
+}
+
+tm_packed_w4* tm_pack_w4_gate_up(const uint32_t* qweight, const uint16_t* scales, const uint16_t* zeros, int K, int N,
+                                 int group, tm_stream stream)
+{
+    if (!qweight || !scales) {
+        fail(TM_EINVAL, "qweight or scales is null");
+        return nullptr;
+    }
+    if (K <= 0 || N <= 0 || K % kUnitK || N % 32) {
+        fail(TM_EINVAL, "need K %% 128 == 0 and N %% 32 == 0 (two halves of whole 16-column tiles; K = %d, N = %d)", K, N);
+        return nullptr;
+    }
+    if (group != 32 && group != 64 && !(group >= 128 && group % 128 == 0 && K % group == 0)) {
+        fail(TM_EINVAL, "group must be 32, 64 or a multiple of 128 that divides K (got %d)", group);
+        return nullptr;
+    }
+    int dev;
+    if (check_device(&dev) != TM_OK) return nullptr;
+    hipStream_t st = (hipStream_t)stream;
+    const int G = K / group;
+    uint32_t* q2 = nullptr;
+    uint16_t *s2 = nullptr, *z2 = nullptr;
+    hipError_t e = hipMalloc((void**)&q2, (size_t)K * N / 2);
+    if (e == hipSuccess) e = hipMalloc((void**)&s2, (size_t)G * N * 2);
+    if (e == hipSuccess && zeros) e = hipMalloc((void**)&z2, (size_t)G * N * 2);
+    if (e == hipSuccess) e = launch_interleave_gate_up(qweight, scales, zeros, q2, s2, z2, K, N, G, st);
+    tm_packed_w4* h = nullptr;
+    if (e == hipSuccess) {
+        h = pack_impl(q2, s2, zeros ? z2 : nullptr, K, N, group, TM_LAYOUT_N8, 4, false, stream);
+        if (h) e = hipStreamSynchronize(st);               // the temporaries are released below
+    } else {
+        fail_hip(e, "gate/up interleave");
+    }
+    if (q2) (void)hipFree(q2);
+    if (s2) (void)hipFree(s2);
+    if (z2) (void)hipFree(z2);
+    if (h && e != hipSuccess) {
+        fail_hip(e, "gate/up pack");
+        tm_free_packed(h);
+        return nullptr;
+    }
+    if (h) h->gate_up = true;
+    return h;
+}
+
 tm_expert_group* tm_group_experts(const tm_packed_w4* const* experts, int num_experts)
 {
     if (!experts || num_experts <= 0 || num_experts > 65535) {
@@ -602,7 +674,7 @@ tm_expert_group* tm_group_experts(const tm_packed_w4* const* experts, int num_ex
             fail(TM_EINVAL, "expert %d: handle is null or invalid", e);
             return nullptr;
         }
-        if (experts[e]->bits != 4 || experts[e]->perm) {
+        if (experts[e]->bits != 4 || experts[e]->perm || experts[e]->gate_up) {
             fail(TM_EUNSUPPORTED, "expert %d: grouped GEMM takes 4-bit weights in plain row order only", e);
             return nullptr;
         }

@@ -10,6 +10,7 @@ typedef _Float16 f16x2 __attribute__((ext_vector_type(2)));
 typedef _Float16 f16x8 __attribute__((ext_vector_type(8)));
 typedef float f32x4 __attribute__((ext_vector_type(4)));
 typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
 
 constexpr int kUnitK = 128;       // rows of one packed unit
 constexpr int kUnitN = 16;        // columns of one packed unit
@@ -33,6 +34,12 @@ struct GemmParams {
     int ku_per_split;         // k-units per split (ceil)
     int tiles_m, tiles_n;     // tile kernel only
     int strips;               // skinny kernel only: strip s owns tiles [s*NT/strips, (s+1)*NT/strips)
+    // Fused epilogue (all optional; 0 / null = plain Y = X * dequant(W)).
+    const uint16_t* bias;     // fp16 [N] in the caller's column order, added to the sums
+    const uint16_t* residual; // fp16 [M][ldy], added last
+    int act;                  // 1: columns are interleaved (gate, up) pairs and Y[m][n/2] = silu(gate) * up
+    int ldy;                  // row stride of Y and residual: N, or N/2 with act
+    int epi;                  // 0: none of the three is set (the stores take the plain path on one test)
 };
 
 // Grouped (mixture-of-experts) launch: rows [offsets[e], offsets[e+1]) of X and Y belong to expert e.
@@ -224,6 +231,99 @@ __device__ __forceinline__ uint16_t f32_to_f16_bits(float v)
 {
     _Float16 h = (_Float16)v;          // v_cvt_f16_f32, round-to-nearest-even
     return __builtin_bit_cast(uint16_t, h);
+}
+
+__device__ __forceinline__ float f16_bits_to_f32(uint16_t b) { return (float)__builtin_bit_cast(_Float16, b); }
+
+// silu(g) * u in fp32; exp2 of a large positive argument gives +inf and the quotient 0, as it should.
+__device__ __forceinline__ float silu_mul(float g, float u)
+{
+    return g / (1.0f + __builtin_amdgcn_exp2f(-1.4426950408889634f * g)) * u;
+}
+
+// The one place where sums become outputs.  v0, v1 are the fp32 sums of columns n, n + 1 (n even) of row m.  All
+// branches are uniform over the launch.  With act the packed weight's columns are interleaved - kernel column 2j is
+// gate column j, 2j + 1 is up column j of the caller's [gate | up] matrix - so every thread that holds a pair holds a
+// matching one, and the pair collapses into output column n / 2.
+__device__ __forceinline__ void store_pair(const GemmParams& p, int m, int n, float v0, float v1)
+{
+    if (p.epi == 0) {
+        *(uint32_t*)(p.Y + (size_t)m * p.N + n) = (uint32_t)f32_to_f16_bits(v0) | ((uint32_t)f32_to_f16_bits(v1) << 16);
+        return;
+    }
+    if (p.act) {
+        if (p.bias) {
+            v0 += f16_bits_to_f32(p.bias[n >> 1]);
+            v1 += f16_bits_to_f32(p.bias[(p.N >> 1) + (n >> 1)]);
+        }
+        float y = silu_mul(v0, v1);
+        const size_t at = (size_t)m * p.ldy + (n >> 1);
+        if (p.residual) y += f16_bits_to_f32(p.residual[at]);
+        p.Y[at] = f32_to_f16_bits(y);
+        return;
+    }
+    const size_t at = (size_t)m * p.ldy + n;
+    if (p.bias) {
+        const uint32_t b = *(const uint32_t*)(p.bias + n);
+        v0 += f16_bits_to_f32((uint16_t)b);
+        v1 += f16_bits_to_f32((uint16_t)(b >> 16));
+    }
+    if (p.residual) {
+        const uint32_t r = *(const uint32_t*)(p.residual + at);
+        v0 += f16_bits_to_f32((uint16_t)r);
+        v1 += f16_bits_to_f32((uint16_t)(r >> 16));
+    }
+    *(uint32_t*)(p.Y + at) = (uint32_t)f32_to_f16_bits(v0) | ((uint32_t)f32_to_f16_bits(v1) << 16);
+}
+
+// Four consecutive columns n .. n + 3 (n a multiple of 4) of row m.
+__device__ __forceinline__ void store_quad(const GemmParams& p, int m, int n, float v0, float v1, float v2, float v3)
+{
+    if (p.epi == 0) {
+        u32x2 o;
+        o.x = (uint32_t)f32_to_f16_bits(v0) | ((uint32_t)f32_to_f16_bits(v1) << 16);
+        o.y = (uint32_t)f32_to_f16_bits(v2) | ((uint32_t)f32_to_f16_bits(v3) << 16);
+        *(u32x2*)(p.Y + (size_t)m * p.N + n) = o;
+        return;
+    }
+    if (p.act) {
+        if (p.bias) {
+            const uint32_t bg = *(const uint32_t*)(p.bias + (n >> 1));
+            const uint32_t bu = *(const uint32_t*)(p.bias + (p.N >> 1) + (n >> 1));
+            v0 += f16_bits_to_f32((uint16_t)bg);
+            v1 += f16_bits_to_f32((uint16_t)bu);
+            v2 += f16_bits_to_f32((uint16_t)(bg >> 16));
+            v3 += f16_bits_to_f32((uint16_t)(bu >> 16));
+        }
+        float y0 = silu_mul(v0, v1), y1 = silu_mul(v2, v3);
+        const size_t at = (size_t)m * p.ldy + (n >> 1);
+        if (p.residual) {
+            const uint32_t r = *(const uint32_t*)(p.residual + at);
+            y0 += f16_bits_to_f32((uint16_t)r);
+            y1 += f16_bits_to_f32((uint16_t)(r >> 16));
+        }
+        *(uint32_t*)(p.Y + at) = (uint32_t)f32_to_f16_bits(y0) | ((uint32_t)f32_to_f16_bits(y1) << 16);
+        return;
+    }
+    const size_t at = (size_t)m * p.ldy + n;
+    if (p.bias) {
+        const u32x2 b = *(const u32x2*)(p.bias + n);
+        v0 += f16_bits_to_f32((uint16_t)b.x);
+        v1 += f16_bits_to_f32((uint16_t)(b.x >> 16));
+        v2 += f16_bits_to_f32((uint16_t)b.y);
+        v3 += f16_bits_to_f32((uint16_t)(b.y >> 16));
+    }
+    if (p.residual) {
+        const u32x2 r = *(const u32x2*)(p.residual + at);
+        v0 += f16_bits_to_f32((uint16_t)r.x);
+        v1 += f16_bits_to_f32((uint16_t)(r.x >> 16));
+        v2 += f16_bits_to_f32((uint16_t)r.y);
+        v3 += f16_bits_to_f32((uint16_t)(r.y >> 16));
+    }
+    u32x2 o;
+    o.x = (uint32_t)f32_to_f16_bits(v0) | ((uint32_t)f32_to_f16_bits(v1) << 16);
+    o.y = (uint32_t)f32_to_f16_bits(v2) | ((uint32_t)f32_to_f16_bits(v3) << 16);
+    *(u32x2*)(p.Y + at) = o;
 }
 
 }  // namespace tmw4

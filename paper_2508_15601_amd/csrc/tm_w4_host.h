@@ -78,6 +78,8 @@ hipError_t launch_repack8(const uint32_t* qweight, const uint16_t* scales, const
 hipError_t launch_permute_rows(const uint32_t* in, const int32_t* perm, uint32_t* out, int K, int N, int k_major,
                                hipStream_t stream);
 hipError_t launch_permute_x(const uint16_t* X, const int32_t* perm, uint16_t* out, int M, int K, hipStream_t stream);
+hipError_t launch_interleave_gate_up(const uint32_t* q, const uint16_t* s, const uint16_t* z, uint32_t* q_out, uint16_t* s_out,
+                                     uint16_t* z_out, int K, int N, int G, hipStream_t stream);
 hipError_t launch_unpack(const uint32_t* w, const uint32_t* sz, uint32_t* qweight_out, uint16_t* scales_out,
                          uint16_t* zeros_out, int K, int N, int group, hipStream_t stream);
 hipError_t launch_copy(void* dst, const void* src, size_t bytes, hipStream_t stream);

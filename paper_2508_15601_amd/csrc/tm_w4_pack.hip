@@ -232,6 +232,34 @@ __global__ __launch_bounds__(256) void permute_x_kernel(const uint16_t* __restri
     *(u32x4*)(out + (size_t)m * K + 8 * c) = v;
 }
 
+// Column interleave of a fused [gate | up] weight (N = 2*I columns): output column 2j is gate column j, 2j + 1 is up
+// column I + j, so that every thread of a GEMM epilogue that holds two neighbouring columns holds a matching pair.
+// Codes: output word (k, w) = columns 8w .. 8w+7 takes four nibbles of gate word w/2 and four of up word I/8 + w/2.
+__global__ __launch_bounds__(256) void interleave_gate_up_q_kernel(const uint32_t* __restrict__ in, uint32_t* __restrict__ out,
+                                                                   int K, int N)
+{
+    const size_t idx = (size_t)blockIdx.x * 256 + threadIdx.x;
+    const int words = N / 8;
+    if (idx >= (size_t)K * words) return;
+    const int w = (int)(idx % words);
+    const size_t row = idx / words * words;
+    const int sh = 16 * (w & 1);                                // nibbles 0..3 or 4..7 of the source words
+    const uint32_t g = in[row + (w >> 1)] >> sh, u = in[row + (N / 16) + (w >> 1)] >> sh;
+    uint32_t o = 0;
+#pragma unroll
+    for (int i = 0; i < 4; ++i) o |= (((g >> (4 * i)) & 15u) << (8 * i)) | (((u >> (4 * i)) & 15u) << (8 * i + 4));
+    out[idx] = o;
+}
+
+__global__ __launch_bounds__(256) void interleave_gate_up_f16_kernel(const uint16_t* __restrict__ in, uint16_t* __restrict__ out,
+                                                                     int G, int N)
+{
+    const size_t idx = (size_t)blockIdx.x * 256 + threadIdx.x;
+    if (idx >= (size_t)G * N) return;
+    const int c = (int)(idx % N);
+    out[idx] = in[idx - c + ((c & 1) ? N / 2 + (c >> 1) : (c >> 1))];
+}
+
 // ------------------------------------------------------------------------------------------ host launchers
 
 hipError_t launch_permute_rows(const uint32_t* in, const int32_t* perm, uint32_t* out, int K, int N, int k_major,
@@ -240,6 +268,16 @@ hipError_t launch_permute_rows(const uint32_t* in, const int32_t* perm, uint32_t
     size_t total = (size_t)K * N / 8;
     hipLaunchKernelGGL(permute_rows_kernel, dim3((unsigned)((total + 255) / 256)), dim3(256), 0, stream, in, perm, out, K,
                        N, k_major);
+    return hipGetLastError();
+}
+
+hipError_t launch_interleave_gate_up(const uint32_t* q, const uint16_t* s, const uint16_t* z, uint32_t* q_out, uint16_t* s_out,
+                                     uint16_t* z_out, int K, int N, int G, hipStream_t stream)
+{
+    const size_t nq = (size_t)K * N / 8, nf = (size_t)G * N;
+    hipLaunchKernelGGL(interleave_gate_up_q_kernel, dim3((unsigned)((nq + 255) / 256)), dim3(256), 0, stream, q, q_out, K, N);
+    hipLaunchKernelGGL(interleave_gate_up_f16_kernel, dim3((unsigned)((nf + 255) / 256)), dim3(256), 0, stream, s, s_out, G, N);
+    if (z) hipLaunchKernelGGL(interleave_gate_up_f16_kernel, dim3((unsigned)((nf + 255) / 256)), dim3(256), 0, stream, z, z_out, G, N);
     return hipGetLastError();
 }
 

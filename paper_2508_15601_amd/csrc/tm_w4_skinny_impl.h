@@ -239,8 +239,7 @@ __device__ __forceinline__ void skinny_body(const GemmParams& p, const int bx, f
             if (!mine || (lane & 1)) continue;
             const int n = (nt0 + j) * 16 + (lane & 15);
             if (p.split == 1) {
-                uint32_t o = (uint32_t)f32_to_f16_bits(v) | ((uint32_t)f32_to_f16_bits(vr) << 16);
-                *(uint32_t*)(p.Y + (size_t)m * p.N + n) = o;
+                store_pair(p, m, n, v, vr);
             } else {
                 st_partial2(p.partial + ((size_t)sk * p.M + m) * p.N + n, v, vr);
             }
@@ -274,8 +273,7 @@ __device__ __forceinline__ void skinny_body(const GemmParams& p, const int bx, f
                         v0 += a;
                         v1 += b;
                     }
-                    uint32_t o = (uint32_t)f32_to_f16_bits(v0) | ((uint32_t)f32_to_f16_bits(v1) << 16);
-                    *(uint32_t*)(p.Y + (size_t)m * p.N + n) = o;
+                    store_pair(p, m, n, v0, v1);
                 }
             }
             if (tid == 0) __hip_atomic_store(&p.counters[strip], 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
@@ -345,6 +343,7 @@ __global__ __launch_bounds__(MAXW * 64) void skinny_grouped_kernel(GroupedParams
     p.SZ = (const uint32_t*)szptr;
     p.K = gp.K;
     p.N = gp.N;
+    p.ldy = gp.N;
     p.KU = gp.KU;
     p.NT = gp.NT;
     p.G = gp.G;

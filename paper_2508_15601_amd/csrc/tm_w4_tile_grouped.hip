@@ -76,6 +76,7 @@ __global__ __launch_bounds__(NW * 64) void tile_grouped_kernel(GroupedParams gp)
     p.M = r1 - r0;
     p.K = gp.K;
     p.N = gp.N;
+    p.ldy = gp.N;
     p.KU = gp.KU;
     p.NT = gp.NT;
     p.G = gp.G;

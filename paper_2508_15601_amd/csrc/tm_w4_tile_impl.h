@@ -28,7 +28,6 @@ namespace {
 
 constexpr int kPanelN = 8;                 // output tiles per panel row (XCD-local rasterisation)
 
-typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
 
 // Raw buffer descriptor over `bytes` bytes at p (gfx9 layout: 32-bit data format, no swizzle, no stride).
 __device__ __forceinline__ __amdgpu_buffer_rsrc_t make_rsrc(const void* p, uint32_t bytes)
@@ -392,10 +391,7 @@ __device__ __forceinline__ void tile_body(const GemmParams& p, const int tile_m,
             for (int j = 0; j < TN; ++j) {
                 const int nt = nt0 + j;
                 if (nt >= nt_end) continue;
-                u32x2 o;
-                o.x = (uint32_t)f32_to_f16_bits(acc[i][j][0]) | ((uint32_t)f32_to_f16_bits(acc[i][j][1]) << 16);
-                o.y = (uint32_t)f32_to_f16_bits(acc[i][j][2]) | ((uint32_t)f32_to_f16_bits(acc[i][j][3]) << 16);
-                *(u32x2*)(p.Y + (size_t)m * p.N + nt * 16 + 4 * h) = o;
+                store_quad(p, m, nt * 16 + 4 * h, acc[i][j][0], acc[i][j][1], acc[i][j][2], acc[i][j][3]);
             }
         }
         return;
@@ -439,10 +435,7 @@ __device__ __forceinline__ void tile_body(const GemmParams& p, const int tile_m,
                 ld_partial2(src + 2, a2, a3);
                 v[0] += a0; v[1] += a1; v[2] += a2; v[3] += a3;
             }
-            u32x2 o;
-            o.x = (uint32_t)f32_to_f16_bits(v[0]) | ((uint32_t)f32_to_f16_bits(v[1]) << 16);
-            o.y = (uint32_t)f32_to_f16_bits(v[2]) | ((uint32_t)f32_to_f16_bits(v[3]) << 16);
-            *(u32x2*)(p.Y + (size_t)m * p.N + nt * 16 + 4 * h) = o;
+            store_quad(p, m, nt * 16 + 4 * h, v[0], v[1], v[2], v[3]);
         }
     }
     if (tid == 0) __hip_atomic_store(&p.counters[tile], 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);

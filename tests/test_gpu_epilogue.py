@@ -1,0 +1,122 @@
+"""GPU parity of the fused epilogue (bias, silu(gate)*up, residual) against the oracle, through the C ABI.
+
+Without activation the acceptance rule of the plain product applies (|Y - Yref| <= 1e-2 + 5e-3*|Yref|, relative Frobenius
+<= 2e-3).  silu(gate)*up multiplies two such sums, so each factor's relative error adds: 2e-2 + 1e-2*|Yref| and 4e-3."""
+import sys
+
+import numpy as np
+import pytest
+
+from workloads import w4a16 as wl
+from helpers import acceptance
+import gpu_util as gu
+
+pytestmark = pytest.mark.gpu
+
+
+def _say(msg):
+    print(msg, file=sys.stderr, flush=True)
+
+
+@pytest.fixture(scope="module")
+def tm():
+    import torch
+    import paper_2508_15601_amd as tm
+    assert torch.cuda.is_available(), "GPU tests need a device"
+    tm.load_library()
+    yield tm
+    tm.tm_set_variant(-1, 0)
+    tm.tm_set_launch(0, 0)
+
+
+def _accept_act(Y, Yref):
+    y, r = Y.astype(np.float64), Yref.astype(np.float64)
+    worst = float((np.abs(y - r) / (2e-2 + 1e-2 * np.abs(r))).max())
+    fro = float(np.linalg.norm(y - r) / np.linalg.norm(r))
+    return worst <= 1.0 and fro <= 4e-3, worst, fro
+
+
+def _run(tm, oracle, d, g, M, mode, variant=-1, split=0, waves=0, stage=0):
+    import torch
+    K, N = d["q"].shape
+    rng = np.random.default_rng(N + M)
+    act = "silu_mul" in mode
+    n_out = N // 2 if act else N
+    bias = rng.standard_normal(N).astype(np.float16) if "bias" in mode else None
+    res = rng.standard_normal((M, n_out)).astype(np.float16) if "residual" in mode else None
+    if act:
+        packed = tm.tm_pack_w4_gate_up(gu.to_dev(d["qweight"]), gu.to_dev(d["s"]), gu.to_dev(d["z"]), K, N, g)
+    else:
+        packed = gu.pack(d, g)
+    tm.tm_set_launch(waves, stage)
+    tm.tm_set_variant(variant, split)
+    plan = tm.tm_get_plan(packed, M)
+    _say(f"epilogue {mode} M={M} K={K} N={N} g={g} plan={plan}")
+    if variant >= 0:
+        assert plan["variant"] == variant
+    X = d["X"][:M]
+    outs = []
+    for _ in range(2):
+        Y = torch.full((M, n_out), float("nan"), dtype=torch.float16, device="cuda")
+        tm.tm_gemm_w4a16_ex(gu.to_dev(X), packed, Y, bias=None if bias is None else gu.to_dev(bias),
+                            residual=None if res is None else gu.to_dev(res),
+                            act=tm.TM_ACT_SILU_MUL if act else tm.TM_ACT_NONE)
+        torch.cuda.synchronize()
+        outs.append(Y.cpu().numpy())
+    tm.tm_set_variant(-1, 0)
+    tm.tm_set_launch(0, 0)
+    assert np.array_equal(outs[0].view(np.uint16), outs[1].view(np.uint16))
+    _, Yd = oracle.gemm(X, d["q"], d["s"], d["z"], g, want_fp64=True)
+    Yref = oracle.epilogue(Yd, bias, res, "silu_mul" if act else "none")
+    ok, worst, fro = _accept_act(outs[0], Yref) if act else acceptance(outs[0], Yref)
+    assert ok, (mode, worst, fro)
+    packed.close()
+
+
+MODES = ["bias", "residual", "bias+residual", "silu_mul", "silu_mul+bias+residual"]
+# (variant, split, waves, M): decode strips with and without split-K, CTA tiles with and without split-K and wave sets,
+# the 128-row tile; -1 = the library's own choice
+LAUNCHES = [(-1, 0, 0, 1), (-1, 0, 0, 16), (-1, 0, 0, 40), (-1, 0, 0, 300), (0, 1, 8, 13), (0, 3, 16, 13), (3, 1, 8, 29),
+            (4, 2, 8, 32), (5, 3, 0, 30), (8, 1, 0, 300), (9, 2, 0, 70), (11, 1, 0, 200), (13, 1, 8, 33), (20, 1, 4, 30)]
+
+
+@pytest.mark.parametrize("variant,split,waves,M", LAUNCHES)
+@pytest.mark.parametrize("mode", MODES)
+def test_epilogue_against_oracle(tm, oracle, variant, split, waves, M, mode):
+    K, N, g = 1152, 352, 128
+    d = wl.make(wl.Case(f"epi_{M}", max(M, 1), K, N, g, seed=(variant + 2) * 7 + split + M))
+    _run(tm, oracle, d, g, M, mode, variant, split, waves)
+
+
+@pytest.mark.parametrize("M", [4, 96])
+def test_epilogue_small_groups_and_real_shape(tm, oracle, M):
+    """Group 32 on a ragged shape, and the gated MLP's fused projection at a real width (sampled rows keep the oracle
+    within seconds)."""
+    d = wl.make(wl.Case("epi_g32", M, 640, 416, 32, seed=5))
+    _run(tm, oracle, d, 32, M, "silu_mul+bias+residual")
+    d = wl.make(wl.Case("epi_mlp", min(M, 8), 4096, 2 * 11008, 128, seed=6))
+    _run(tm, oracle, d, 128, min(M, 8), "silu_mul+residual")
+
+
+def test_epilogue_argument_checks(tm, oracle):
+    import torch
+    d = wl.make(wl.Case("epi_args", 4, 256, 64, 128, seed=1))
+    plain = gu.pack(d, 128)
+    fused = tm.tm_pack_w4_gate_up(gu.to_dev(d["qweight"]), gu.to_dev(d["s"]), gu.to_dev(d["z"]), 256, 64, 128)
+    X = gu.to_dev(d["X"])
+    Yh = torch.empty((4, 32), dtype=torch.float16, device="cuda")
+    Yf = torch.empty((4, 64), dtype=torch.float16, device="cuda")
+    with pytest.raises(tm.TmError):                       # a plain handle has no interleaved columns
+        tm.tm_gemm_w4a16_ex(X, plain, Yh, act=tm.TM_ACT_SILU_MUL)
+    with pytest.raises(tm.TmError):                       # an interleaved handle only serves the activation
+        tm.tm_gemm_w4a16(X, fused, Yf)
+    with pytest.raises(tm.TmError):
+        tm.tm_pack_w4_gate_up(gu.to_dev(d["qweight"][:, :6]), gu.to_dev(d["s"][:, :48]), None, 256, 48, 128)   # N % 32
+    # no epilogue fields set: identical to the plain call
+    tm.tm_gemm_w4a16_ex(X, plain, Yf)
+    Y0 = torch.empty_like(Yf)
+    tm.tm_gemm_w4a16(X, plain, Y0)
+    torch.cuda.synchronize()
+    assert torch.equal(Yf, Y0)
+    plain.close()
+    fused.close()
