@@ -1,7 +1,7 @@
 #!/usr/bin/env python3
 """Benchmark of the W4A16 GEMM hot path on one MI355X.
 
-    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload decode|mlp_decode|prefill|sweep|companion|moe|w8|attn|pack|copy]
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload decode|mlp_decode|prefill|sweep|companion|moe|w8|attn|epilogue|pack|copy]
                     [--sweep-out FILE] [--no-cpu-baseline] [--no-prefill]
 
 A "step" is one pass of the fused GEMM over every (layer, M) pair of the workload, weights already packed
@@ -371,6 +371,60 @@ def attn_table(tm, torch, iters=50, q_heads=32, kv_heads=8, only=None, bits=8):
     return rows
 
 
+def epilogue_table(tm, torch, wl, iters=100):
+    """Fused epilogue against the same work done as a second pass over Y (PyTorch elementwise kernels, same HIP graph):
+    the gated MLP's fused gate+up projection with silu(gate)*up, and its down projection with the residual add."""
+    import numpy as np
+    import torch.nn.functional as F
+    rows = []
+    dev = lambda a: torch.from_numpy(np.ascontiguousarray(a.view(np.int32) if a.dtype == np.uint32 else a)).cuda()
+    for case_name, mode in (("cfg3_gate_up_M64", "silu_mul"), ("cfg3_down_M64", "residual")):
+        c = wl.case_by_name(case_name)
+        d = wl.make(c)
+        qw, sc, z = dev(d["qweight"]), dev(d["s"]), dev(d["z"])
+        wbytes = c.K * c.N // 2 + 4 * c.K * c.N // c.group
+        copies = max(2, -(-ROTATE_BYTES // wbytes))
+        act = mode == "silu_mul"
+        plain = [tm.tm_pack_w4(qw, sc, z, c.K, c.N, c.group) for _ in range(copies)]
+        fused = [tm.tm_pack_w4_gate_up(qw, sc, z, c.K, c.N, c.group) for _ in range(copies)] if act else plain
+        n_out = c.N // 2 if act else c.N
+        for M in (1, 16, 64, 512, 4096):
+            X = torch.randn((M, c.K), device="cuda").to(torch.float16)
+            Y = torch.empty((M, c.N), dtype=torch.float16, device="cuda")
+            Z = torch.empty((M, n_out), dtype=torch.float16, device="cuda")
+            R = torch.randn((M, n_out), device="cuda").to(torch.float16)
+            turn = [0]
+
+            def step_fused():
+                i = turn[0] % copies
+                turn[0] += 1
+                if act:
+                    tm.tm_gemm_w4a16_ex(X, fused[i], Z, act=tm.TM_ACT_SILU_MUL)
+                else:
+                    tm.tm_gemm_w4a16_ex(X, fused[i], Z, residual=R)
+
+            def step_unfused():
+                i = turn[0] % copies
+                turn[0] += 1
+                tm.tm_gemm_w4a16(X, plain[i], Y)
+                if act:
+                    torch.mul(F.silu(Y[:, :n_out]), Y[:, n_out:], out=Z)
+                else:
+                    torch.add(Y, R, out=Z)
+
+            n = iters if M <= 512 else max(10, iters // 10)
+            tf = time_steps(torch, step_fused, n, 5, graph_steps=n)[0] / n * 1e3
+            tu = time_steps(torch, step_unfused, n, 5, graph_steps=n)[0] / n * 1e3
+            rows.append({"layer": case_name.split("_M")[0], "epilogue": mode, "M": M, "K": c.K, "N": c.N, "fused_us": tf,
+                         "unfused_us": tu, "speedup": tu / tf})
+            log(f"{case_name.split('_M')[0]:14s} {mode:9s} M={M:5d}  fused {tf:9.2f} us   GEMM + elementwise pass {tu:9.2f} us   x{tu / tf:.2f}")
+        for h in plain + (fused if act else []):
+            h.close()
+        del plain, fused
+        torch.cuda.empty_cache()
+    return rows
+
+
 def attn_companion(torch, iters=20, q_heads=32, kv_heads=8, only=None):
     """The companion measurement of the attention rows: the same decode step over an unquantised fp16 cache through the
     framework's own fused attention (`scaled_dot_product_attention`, grouped-query mode) - what a serving stack without
@@ -476,7 +530,7 @@ def main():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=200)
     ap.add_argument("--warmup", type=int, default=20)
-    ap.add_argument("--workload", default="decode", choices=sorted(WORKLOADS) + ["sweep", "copy", "companion", "pack", "moe", "w8", "attn"])
+    ap.add_argument("--workload", default="decode", choices=sorted(WORKLOADS) + ["sweep", "copy", "companion", "pack", "moe", "w8", "attn", "epilogue"])
     ap.add_argument("--sweep-out", default=None, help="with --workload sweep: write the per-shape table here (JSON)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--attn-companion", action="store_true",
@@ -541,6 +595,15 @@ def main():
             rows.append({"layout": layout, "ms_per_pack_call": ms})
             log(f"layout {layout}: {ms:.3f} ms per pack call (allocation + two kernels + free)")
         print(json.dumps({"metric": "offline pack", "K": K, "N": N, "group": g, "steps": args.steps, "rows": rows}))
+        return
+
+    if args.workload == "epilogue":
+        table = epilogue_table(tm, torch, wl, iters=min(args.steps, 100))
+        if args.sweep_out:
+            os.makedirs(os.path.dirname(os.path.abspath(args.sweep_out)), exist_ok=True)
+            json.dump(table, open(args.sweep_out, "w"), indent=1)
+        print(json.dumps({"metric": "fused epilogue vs a second pass over Y: microseconds per layer call", "workload": "epilogue",
+                          "n_gpus": 1, "data": "synthetic", "rows": table}))
         return
 
     if args.workload == "attn":
