@@ -220,6 +220,13 @@ TM_API tm_expert_group* tm_group_experts(const tm_packed_w4* const* experts, int
 TM_API void tm_free_expert_group(tm_expert_group* group);
 TM_API int tm_gemm_w4a16_grouped(const uint16_t* X, const tm_expert_group* group, const int32_t* offsets, uint16_t* Y,
                                  int total_rows, tm_stream stream);
+/*
+ * The grouped call with the gated MLP's activation fused (see tm_gemm_w4a16_ex): every expert of the group is a handle
+ * of tm_pack_w4_gate_up and Y is fp16 [total_rows][N/2], Y[r] = silu(T_gate) * T_up of T = X[r] * dequant(expert).
+ * act must be TM_ACT_SILU_MUL for such a group and TM_ACT_NONE (= tm_gemm_w4a16_grouped) for any other.
+ */
+TM_API int tm_gemm_w4a16_grouped_act(const uint16_t* X, const tm_expert_group* group, const int32_t* offsets, uint16_t* Y,
+                                     int total_rows, int act, tm_stream stream);
 /* Kernel variant and strips per expert the grouped launch would use (host out-pointers, may be NULL). */
 TM_API int tm_get_grouped_plan(const tm_expert_group* group, int total_rows, int* variant, int* strips);
 

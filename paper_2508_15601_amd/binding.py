@@ -70,6 +70,8 @@ def load_library():
     lib.tm_free_expert_group.argtypes = [vp]
     lib.tm_gemm_w4a16_grouped.restype = i
     lib.tm_gemm_w4a16_grouped.argtypes = [vp, vp, vp, vp, i, vp]
+    lib.tm_gemm_w4a16_grouped_act.restype = i
+    lib.tm_gemm_w4a16_grouped_act.argtypes = [vp, vp, vp, vp, i, i, vp]
     lib.tm_get_grouped_plan.restype = i
     lib.tm_get_grouped_plan.argtypes = [vp, i, vp, vp]
     lib.tm_pack_w4_layout.restype = vp
@@ -297,6 +299,21 @@ def tm_gemm_w4a16_grouped(X, group: ExpertGroup, offsets, Y, stream=None):
     _check(load_library().tm_gemm_w4a16_grouped(_dev_ptr(X, torch.float16, "X"), group.handle,
                                                 _dev_ptr(offsets, torch.int32, "offsets"),
                                                 _dev_ptr(Y, torch.float16, "Y"), R, _stream_ptr(stream)))
+    return Y
+
+
+def tm_gemm_w4a16_grouped_act(X, group: ExpertGroup, offsets, Y, act: int = 1, stream=None):
+    """The grouped call with silu(gate)*up fused: experts packed by tm_pack_w4_gate_up, Y [R, N/2]."""
+    import torch
+    R = X.shape[0]
+    n_out = group.N // 2 if act == 1 else group.N
+    if X.dim() != 2 or X.shape[1] != group.K or tuple(Y.shape) != (R, n_out) or offsets.numel() != len(group.experts) + 1:
+        raise ValueError("X/Y/offsets shapes do not match the expert group")
+    if R == 0:
+        return Y
+    _check(load_library().tm_gemm_w4a16_grouped_act(_dev_ptr(X, torch.float16, "X"), group.handle,
+                                                    _dev_ptr(offsets, torch.int32, "offsets"),
+                                                    _dev_ptr(Y, torch.float16, "Y"), R, int(act), _stream_ptr(stream)))
     return Y
 
 

@@ -116,6 +116,7 @@ struct tm_kv_cache {
 struct tm_expert_group {
     uint32_t magic;
     int experts, K, N, group, device;
+    bool gate_up;      // every expert is a gate/up handle with interleaved columns
     uint64_t* table;   // device: per expert, address of the packed weights and of the scale/zero words
 };
 
@@ -674,8 +675,12 @@ tm_expert_group* tm_group_experts(const tm_packed_w4* const* experts, int num_ex
             fail(TM_EINVAL, "expert %d: handle is null or invalid", e);
             return nullptr;
         }
-        if (experts[e]->bits != 4 || experts[e]->perm || experts[e]->gate_up) {
+        if (experts[e]->bits != 4 || experts[e]->perm) {
             fail(TM_EUNSUPPORTED, "expert %d: grouped GEMM takes 4-bit weights in plain row order only", e);
+            return nullptr;
+        }
+        if (experts[e]->gate_up != experts[0]->gate_up) {
+            fail(TM_EINVAL, "expert %d: gate/up handles and plain handles cannot share a group", e);
             return nullptr;
         }
         if (experts[e]->K != experts[0]->K || experts[e]->N != experts[0]->N ||
@@ -713,6 +718,7 @@ tm_expert_group* tm_group_experts(const tm_packed_w4* const* experts, int num_ex
     g->magic = kGroupMagic;
     g->experts = num_experts;
     g->K = experts[0]->K;
+    g->gate_up = experts[0]->gate_up;
     g->N = experts[0]->N;
     g->group = experts[0]->group;
     g->device = dev;
@@ -727,10 +733,13 @@ void tm_free_expert_group(tm_expert_group* group)
     delete group;
 }
 
-int tm_gemm_w4a16_grouped(const uint16_t* X, const tm_expert_group* group, const int32_t* offsets, uint16_t* Y,
-                          int total_rows, tm_stream stream)
+static int run_grouped(const uint16_t* X, const tm_expert_group* group, const int32_t* offsets, uint16_t* Y, int total_rows,
+                       int act, tm_stream stream)
 {
     if (!valid(group)) return fail(TM_EINVAL, "expert group is null or invalid");
+    if (act != TM_ACT_NONE && act != TM_ACT_SILU_MUL) return fail(TM_EINVAL, "unknown activation %d", act);
+    if ((act == TM_ACT_SILU_MUL) != group->gate_up)
+        return fail(TM_EINVAL, "silu(gate)*up takes experts packed by tm_pack_w4_gate_up, and such experts nothing else");
     if (total_rows == 0) return TM_OK;
     if (!X || !Y || !offsets) return fail(TM_EINVAL, "X, Y or offsets is null");
     if (total_rows < 0 || total_rows >= (1 << 24))
@@ -755,6 +764,7 @@ int tm_gemm_w4a16_grouped(const uint16_t* X, const tm_expert_group* group, const
     gp.strips = strips;
     gp.total_rows = total_rows;
     gp.experts = group->experts;
+    gp.act = act == TM_ACT_SILU_MUL ? 1 : 0;
     if (!is_skinny(variant) && (uint64_t)total_rows * (uint64_t)group->K >= (1ull << 31))
         return fail(TM_EINVAL, "total_rows*K must be below 2^31 for prefill-sized expert loads");
     hipError_t e = is_skinny(variant)
@@ -762,6 +772,18 @@ int tm_gemm_w4a16_grouped(const uint16_t* X, const tm_expert_group* group, const
                        : launch_tile_grouped(gp, variant, group->experts, group->group, (hipStream_t)stream);
     if (e != hipSuccess) return fail_hip(e, "grouped kernel launch");
     return TM_OK;
+}
+
+int tm_gemm_w4a16_grouped(const uint16_t* X, const tm_expert_group* group, const int32_t* offsets, uint16_t* Y,
+                          int total_rows, tm_stream stream)
+{
+    return run_grouped(X, group, offsets, Y, total_rows, TM_ACT_NONE, stream);
+}
+
+int tm_gemm_w4a16_grouped_act(const uint16_t* X, const tm_expert_group* group, const int32_t* offsets, uint16_t* Y,
+                              int total_rows, int act, tm_stream stream)
+{
+    return run_grouped(X, group, offsets, Y, total_rows, act, stream);
 }
 
 int tm_get_grouped_plan(const tm_expert_group* group, int total_rows, int* variant, int* strips)

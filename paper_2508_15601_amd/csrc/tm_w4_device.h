@@ -50,6 +50,7 @@ struct GroupedParams {
     const int32_t* offsets;     // [experts + 1], ascending
     int K, N, KU, NT, G, strips, total_rows, experts;
     int tiles_n, mtiles;        // tile kernels: column tiles, and the upper bound of row tiles over all experts
+    int act;                    // 1: gate/up experts, Y[r][n/2] = silu(gate) * up, row stride N/2
 };
 
 // Quantised KV cache of the attention kernels: 8-bit codes, one scale/zero pair per token and head.

@@ -343,7 +343,9 @@ __global__ __launch_bounds__(MAXW * 64) void skinny_grouped_kernel(GroupedParams
     p.SZ = (const uint32_t*)szptr;
     p.K = gp.K;
     p.N = gp.N;
-    p.ldy = gp.N;
+    p.ldy = gp.act ? gp.N / 2 : gp.N;
+    p.act = gp.act;
+    p.epi = gp.act;
     p.KU = gp.KU;
     p.NT = gp.NT;
     p.G = gp.G;
@@ -353,7 +355,7 @@ __global__ __launch_bounds__(MAXW * 64) void skinny_grouped_kernel(GroupedParams
     for (int m0 = r0; m0 < r1; m0 += 16 * TM) {
         if (m0 != r0) __syncthreads();             // the previous chunk's reads of red are done
         p.X = gp.X + (size_t)m0 * gp.K;
-        p.Y = gp.Y + (size_t)m0 * gp.N;
+        p.Y = gp.Y + (size_t)m0 * p.ldy;
         p.M = min(16 * TM, r1 - m0);
         skinny_body<TM, NTW, GPU, D, 4>(p, blockIdx.x, red, s_last);
     }

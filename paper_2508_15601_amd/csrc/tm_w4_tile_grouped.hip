@@ -70,13 +70,15 @@ __global__ __launch_bounds__(NW * 64) void tile_grouped_kernel(GroupedParams gp)
 
     GemmParams p{};
     p.X = gp.X + (size_t)r0 * gp.K;
-    p.Y = gp.Y + (size_t)r0 * gp.N;
+    p.ldy = gp.act ? gp.N / 2 : gp.N;
+    p.act = gp.act;
+    p.epi = gp.act;
+    p.Y = gp.Y + (size_t)r0 * p.ldy;
     p.W = (const u32x4*)wptr;
     p.SZ = (const uint32_t*)szptr;
     p.M = r1 - r0;
     p.K = gp.K;
     p.N = gp.N;
-    p.ldy = gp.N;
     p.KU = gp.KU;
     p.NT = gp.NT;
     p.G = gp.G;

@@ -120,3 +120,51 @@ def test_epilogue_argument_checks(tm, oracle):
     assert torch.equal(Yf, Y0)
     plain.close()
     fused.close()
+
+
+@pytest.mark.parametrize("E,K,N,g,counts,variant", [
+    (4, 512, 288, 128, [0, 1, 17, 5], -1),                  # decode-sized loads
+    (3, 256, 96, 32, [40, 0, 70], 0),                       # several passes per expert
+    (2, 512, 1056, 64, [16, 15], 2),
+    (3, 512, 544, 128, [200, 0, 70], -1),                   # CTA tiles
+    (4, 384, 160, 32, [130, 1, 0, 129], 9),
+])
+def test_grouped_gemm_with_fused_activation(tm, oracle, E, K, N, g, counts, variant):
+    """All experts of a mixture-of-experts layer in one launch, silu(gate)*up fused: per expert the oracle's product on
+    that expert's rows, then the oracle's epilogue."""
+    import torch
+    _say(f"grouped silu_mul E={E} K={K} N={N} g={g} counts={counts} variant={variant}")
+    rng = np.random.default_rng(E * 100 + N)
+    host, dev = [], []
+    for e in range(E):
+        q = rng.integers(0, 16, (K, N), dtype=np.uint8)
+        s = rng.uniform(0.001, 0.02, (K // g, N)).astype(np.float16)
+        z = rng.integers(0, 16, (K // g, N)).astype(np.float16)
+        host.append((q, s, z))
+        dev.append(tm.tm_pack_w4_gate_up(gu.to_dev(wl.pack_interchange(q)), gu.to_dev(s), gu.to_dev(z), K, N, g))
+    offsets = np.concatenate([[0], np.cumsum(counts)]).astype(np.int32)
+    R = int(offsets[-1]) + 2                                 # two rows no expert owns
+    X = rng.standard_normal((R, K)).astype(np.float16)
+    group = tm.tm_group_experts(dev)
+    Y = torch.full((R, N // 2), float("nan"), dtype=torch.float16, device="cuda")
+    tm.tm_set_variant(variant, 0)
+    try:
+        tm.tm_gemm_w4a16_grouped_act(gu.to_dev(X), group, torch.from_numpy(offsets).cuda(), Y, tm.TM_ACT_SILU_MUL)
+        torch.cuda.synchronize()
+        with pytest.raises(tm.TmError):                      # interleaved experts serve the activation only
+            tm.tm_gemm_w4a16_grouped(gu.to_dev(X), group, torch.from_numpy(offsets).cuda(),
+                                     torch.empty((R, N), dtype=torch.float16, device="cuda"))
+    finally:
+        tm.tm_set_variant(-1, 0)
+    Y = Y.cpu().numpy()
+    assert np.isnan(Y[offsets[-1]:]).all()
+    for e in range(E):
+        r0, r1 = offsets[e], offsets[e + 1]
+        if r1 == r0:
+            continue
+        _, Yd = oracle.gemm(X[r0:r1], *host[e], g, want_fp64=True)
+        ok, worst, fro = _accept_act(Y[r0:r1], oracle.epilogue(Yd, act="silu_mul"))
+        assert ok, (e, worst, fro)
+    group.close()
+    for p in dev:
+        p.close()
