@@ -468,25 +468,26 @@ struct SoftmaxState {
 // query's 128 values, qbias = sum of the conversion bias of each code position times the query value it meets.
 template <int BITS, bool MASKED>
 __device__ __forceinline__ void process_tokens(const BlockRegs& r, int sb, const uint32_t* sz_slot, const f16x8 (&qf)[4],
-                                               float qsum, float qbias, const Magic& mg, int t0, int len, int lane,
+                                               float qsum, const f32x4& neg_qbias, const Magic& mg, int t0, int len, int lane,
                                                SoftmaxState& st, f32x4 (&acc)[8])
 {
     const int h = lane >> 4;
+    const int rem = len - t0 - 4 * h;          // slot (j, rr) of this lane is a live token iff 16*j + rr < rem
     // S^T for the two 16-token tiles: rows = tokens, columns = query heads
     float s[2][4];
-    float vs[2][4], vzb[2][4];
+    uint32_t vw[2][4];                         // (scale, zero-point) of the slot's value row; 0 for a dead token
 #pragma unroll
     for (int j = 0; j < 2; ++j) {
         // the accumulator starts at minus the bias term: sum_d (bias_d + q_d) Q_d - sum_d bias_d Q_d = sum_d q_d Q_d
-        f32x4 d = {-qbias, -qbias, -qbias, -qbias};
+        f32x4 d;
         if constexpr (BITS == 8) {
-            d = mfma16x16x32(biased8_w8(r.k[j][0].x, r.k[j][0].y), qf[0], d);
+            d = mfma16x16x32(biased8_w8(r.k[j][0].x, r.k[j][0].y), qf[0], neg_qbias);
             d = mfma16x16x32(biased8_w8(r.k[j][0].z, r.k[j][0].w), qf[1], d);
             d = mfma16x16x32(biased8_w8(r.k[j][1].x, r.k[j][1].y), qf[2], d);
             d = mfma16x16x32(biased8_w8(r.k[j][1].z, r.k[j][1].w), qf[3], d);
         } else {
             const u32x4 w = r.k[sb][j];
-            d = mfma16x16x32(biased8(w.x, mg), qf[0], d);
+            d = mfma16x16x32(biased8(w.x, mg), qf[0], neg_qbias);
             d = mfma16x16x32(biased8(w.y, mg), qf[1], d);
             d = mfma16x16x32(biased8(w.z, mg), qf[2], d);
             d = mfma16x16x32(biased8(w.w, mg), qf[3], d);
@@ -496,18 +497,16 @@ __device__ __forceinline__ void process_tokens(const BlockRegs& r, int sb, const
         const u32x4 p1 = *(const u32x4*)(sz_slot + 32 * j + 8 * h + 4);
 #pragma unroll
         for (int rr = 0; rr < 4; ++rr) {
-            const bool live = !MASKED || t0 + 16 * j + 4 * h + rr < len;
-            const uint32_t kw = rr < 2 ? p0[2 * rr] : p1[2 * (rr - 2)];
+            const bool live = !MASKED || 16 * j + rr < rem;
+            const f16x2 kp = as_f16x2(rr < 2 ? p0[2 * rr] : p1[2 * (rr - 2)]);
             // a dead token contributes nothing, whatever its pair holds: scale 0 and zero-point 0 for its values
-            const uint32_t vw = live ? (rr < 2 ? p0[2 * rr + 1] : p1[2 * (rr - 2) + 1]) : 0u;
-            const f16x2 kp = as_f16x2(kw), vp = as_f16x2(vw);
-            // sum_d q_d Q_d  -  z sum_d Q_d  =  sum_d (q_d - z) Q_d ; times the token's scale
-            const float sc = (float)kp.x * (d[rr] - (float)kp.y * qsum);
+            vw[j][rr] = live ? (rr < 2 ? p0[2 * rr + 1] : p1[2 * (rr - 2) + 1]) : 0u;
+            // sum_d q_d Q_d  -  z sum_d Q_d  =  sum_d (q_d - z) Q_d ; times the token's scale.  Both steps are written
+            // as fused multiply-adds so that the fp16 pair enters the instruction directly (no separate conversion;
+            // an addend of +0 keeps the second one from being folded into a plain multiply).
+            const float t = __builtin_fmaf(-(float)kp.y, qsum, d[rr]);
+            const float sc = __builtin_fmaf((float)kp.x, t, 0.0f);
             s[j][rr] = live ? sc : kNegBig;
-            vs[j][rr] = (float)vp.x;
-            // the value code of this token is the k-value 4j + rr of the second product: bias 64 at positions 2, 3, 6, 7
-            const float vbias = (BITS == 8 || rr < 2) ? 1024.0f : 64.0f;
-            vzb[j][rr] = vbias + (float)vp.y;
         }
     }
     // online softmax in base 2 (the query carries scale * log2(e))
@@ -516,7 +515,7 @@ __device__ __forceinline__ void process_tokens(const BlockRegs& r, int sb, const
     const float m_new = fmaxf(st.m_run, mx);
     const float alpha = fast_exp2(st.m_run - m_new);
     st.m_run = m_new;
-    float psum = 0.f, csum = 0.f;
+    float psum = 0.f;
     f16x8 pb;
 #pragma unroll
     for (int j = 0; j < 2; ++j)
@@ -524,7 +523,8 @@ __device__ __forceinline__ void process_tokens(const BlockRegs& r, int sb, const
         for (int rr = 0; rr < 4; ++rr) {
             const float p = fast_exp2(s[j][rr] - m_new);    // 0 for masked tokens
             psum += p;
-            pb[4 * j + rr] = (_Float16)(p * vs[j][rr]);     // probability times the value scale of that token
+            // probability times the value scale of that token
+            pb[4 * j + rr] = (_Float16)__builtin_fmaf((float)as_f16x2(vw[j][rr]).x, p, 0.0f);
         }
     // The correction term must be built from the very fp16 values the matrix core multiplies: the bias is about a
     // thousand times the payload, so one fp16 ulp of disagreement on a single probability shifts a whole output row by
@@ -536,10 +536,19 @@ __device__ __forceinline__ void process_tokens(const BlockRegs& r, int sb, const
         asm volatile("" : "+v"(bits.x), "+v"(bits.y), "+v"(bits.z), "+v"(bits.w));
         pb = __builtin_bit_cast(f16x8, bits);
     }
+    // sum over the lane's tokens of (bias + z) * p': the value code of slot (j, rr) is the k-value 4j + rr of the
+    // second product and carries the bias 1024 - or 64 at positions 2, 3, 6, 7 of a 4-bit word
+    float sum_hi = 0.f, sum_lo = 0.f, zsum = 0.f;
 #pragma unroll
     for (int j = 0; j < 2; ++j)
 #pragma unroll
-        for (int rr = 0; rr < 4; ++rr) csum += vzb[j][rr] * (float)pb[4 * j + rr];
+        for (int rr = 0; rr < 4; ++rr) {
+            const float pv = (float)pb[4 * j + rr];
+            if (BITS == 8 || rr < 2) sum_hi = __builtin_fmaf(pv, 1.0f, sum_hi);
+            else sum_lo = __builtin_fmaf(pv, 1.0f, sum_lo);
+            zsum = __builtin_fmaf((float)as_f16x2(vw[j][rr]).y, pv, zsum);
+        }
+    const float csum = __builtin_fmaf(1024.0f, sum_hi, __builtin_fmaf(64.0f, sum_lo, zsum));
     st.l_run = st.l_run * alpha + psum;
     st.corr = st.corr * alpha + csum;
     // the running maximum seldom moves after the first blocks: rescale only when some query head needs it
@@ -563,7 +572,7 @@ __device__ __forceinline__ void process_tokens(const BlockRegs& r, int sb, const
 
 template <int BITS>
 __device__ __forceinline__ void process_block(const BlockRegs& r, const uint32_t* sz_slot, const f16x8 (&qf)[4],
-                                              float qsum, float qbias, const Magic& mg, int blk, int len, int lane,
+                                              float qsum, const f32x4& neg_qbias, const Magic& mg, int blk, int len, int lane,
                                               SoftmaxState& st, f32x4 (&acc)[8])
 {
     constexpr int TOK = 256 / BITS;
@@ -571,9 +580,9 @@ __device__ __forceinline__ void process_block(const BlockRegs& r, const uint32_t
     // the first 32 tokens always hold a live one; the second half of a 4-bit block may lie wholly behind the context
     // (wave-uniform).  (A second, unmasked copy of the code for blocks inside the context costs more registers than the
     // kernel has: it spills.)
-    process_tokens<BITS, true>(r, 0, sz_slot, qf, qsum, qbias, mg, t0, len, lane, st, acc);
+    process_tokens<BITS, true>(r, 0, sz_slot, qf, qsum, neg_qbias, mg, t0, len, lane, st, acc);
     if constexpr (BITS == 4) {
-        if (t0 + 32 < len) process_tokens<4, true>(r, 1, sz_slot + 64, qf, qsum, qbias, mg, t0 + 32, len, lane, st, acc);
+        if (t0 + 32 < len) process_tokens<4, true>(r, 1, sz_slot + 64, qf, qsum, neg_qbias, mg, t0 + 32, len, lane, st, acc);
     }
 }
 
@@ -633,6 +642,7 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))) voi
         qsum = xor_add(xor_add(qsum, 16), 32);
         qbias = BITS == 8 ? 1024.0f * qsum : xor_add(xor_add(qbias, 16), 32);   // every 8-bit code carries the bias 1024
     }
+    const f32x4 neg_qbias = {-qbias, -qbias, -qbias, -qbias};
 
     SoftmaxState st{kNegBig, 0.f, 0.f};
     f32x4 acc[8];
@@ -658,15 +668,15 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))) voi
         load_block<BITS>(r1, z1, rs, blk + 4 < blk1 ? blk + 4 : nblk, lane);
         while (true) {
             load_block<BITS>(r2, z2, rs, blk + 8 < blk1 ? blk + 8 : nblk, lane);
-            process_block<BITS>(r0, z0, qf, qsum, qbias, mg, blk, len, lane, st, acc);
+            process_block<BITS>(r0, z0, qf, qsum, neg_qbias, mg, blk, len, lane, st, acc);
             blk += 4;
             if (blk >= blk1) break;
             load_block<BITS>(r0, z0, rs, blk + 8 < blk1 ? blk + 8 : nblk, lane);
-            process_block<BITS>(r1, z1, qf, qsum, qbias, mg, blk, len, lane, st, acc);
+            process_block<BITS>(r1, z1, qf, qsum, neg_qbias, mg, blk, len, lane, st, acc);
             blk += 4;
             if (blk >= blk1) break;
             load_block<BITS>(r1, z1, rs, blk + 8 < blk1 ? blk + 8 : nblk, lane);
-            process_block<BITS>(r2, z2, qf, qsum, qbias, mg, blk, len, lane, st, acc);
+            process_block<BITS>(r2, z2, qf, qsum, neg_qbias, mg, blk, len, lane, st, acc);
             blk += 4;
             if (blk >= blk1) break;
         }
