@@ -614,20 +614,45 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))) voi
     const int blk0 = split * blocks_per_split;
     const int blk1 = min(nblk, blk0 + blocks_per_split);
 
+    // Order of the prologue: the query's raw loads, then at once the first two blocks of the KV memory loading pipeline,
+    // and only then the arithmetic on the query, which so runs under the blocks' latency (loads return in order, so the
+    // query must be requested first).
+    const bool real = c < G;
+    f16x8 qraw[4];
+    {
+        const uint16_t* qp = Q + ((size_t)b * q_heads + (size_t)hk * G + (real ? c : 0)) * kHeadDim + 32 * h;
+#pragma unroll
+        for (int tt = 0; tt < 4; ++tt) qraw[tt] = *(const f16x8*)(qp + 8 * tt);
+    }
+
+    // KV memory loading pipeline: the next two blocks of this wave are in flight while the current one is multiplied
+    // (three register sets and three LDS slots, rotated by unrolling; with one block ahead the waves spent half their
+    // time waiting for memory).  Loads are unconditional - past the end of the wave's range they point behind the
+    // descriptors' ranges and return zeros without memory traffic - so that the loop body is straight-line code with a
+    // known number of loads in flight.
+    HeadRsrc rs;
+    rs.k = make_rsrc(kv.k + bh * (kv.cap / TOK) * 4096, (uint32_t)nblk * 4096u);
+    rs.v = make_rsrc(kv.v + bh * (kv.cap / TOK) * 4096, (uint32_t)nblk * 4096u);
+    rs.sz = make_rsrc(kv.sz + bh * kv.cap * 2, (uint32_t)nblk * (8u * TOK));
+    uint32_t* const z0 = sz_ring0[wave];
+    uint32_t* const z1 = sz_ring1[wave];
+    uint32_t* const z2 = sz_ring2[wave];
+    BlockRegs r0, r1, r2;
+    int blk = blk0 + wave;
+    load_block<BITS>(r0, z0, rs, blk < blk1 ? blk : nblk, lane);
+    load_block<BITS>(r1, z1, rs, blk + 4 < blk1 ? blk + 4 : nblk, lane);
+
     // Query operand (adaptive head alignment): column m = c, k-values of step tt = dimensions 32h + 8tt .. +7, the
     // order in which the lane's key bytes arrive; scaled once by scale * log2(e).
     f16x8 qf[4];
     float qsum = 0.f, qbias = 0.f;
     const Magic mg = make_magic();
     {
-        const bool real = c < G;
-        const uint16_t* qp = Q + ((size_t)b * q_heads + (size_t)hk * G + (real ? c : 0)) * kHeadDim + 32 * h;
 #pragma unroll
         for (int tt = 0; tt < 4; ++tt) {
-            const f16x8 raw = *(const f16x8*)(qp + 8 * tt);
 #pragma unroll
             for (int e = 0; e < 8; ++e) {
-                qf[tt][e] = real ? (_Float16)((float)raw[e] * scale_log2e) : (_Float16)0.0f;
+                qf[tt][e] = real ? (_Float16)((float)qraw[tt][e] * scale_log2e) : (_Float16)0.0f;
             }
             // the sums below must see the very fp16 values the matrix core multiplies (one rounding, one copy)
             u32x4 bits = __builtin_bit_cast(u32x4, qf[tt]);
@@ -649,23 +674,7 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))) voi
 #pragma unroll
     for (int i = 0; i < 8; ++i) acc[i] = f32x4{0.f, 0.f, 0.f, 0.f};
 
-    // KV memory loading pipeline: the next two blocks of this wave are in flight while the current one is multiplied
-    // (three register sets and three LDS slots, rotated by unrolling; with one block ahead the waves spent half their
-    // time waiting for memory).  Loads are unconditional - past the end of the wave's range they point behind the
-    // descriptors' ranges and return zeros without memory traffic - so that the loop body is straight-line code with a
-    // known number of loads in flight.
-    HeadRsrc rs;
-    rs.k = make_rsrc(kv.k + bh * (kv.cap / TOK) * 4096, (uint32_t)nblk * 4096u);
-    rs.v = make_rsrc(kv.v + bh * (kv.cap / TOK) * 4096, (uint32_t)nblk * 4096u);
-    rs.sz = make_rsrc(kv.sz + bh * kv.cap * 2, (uint32_t)nblk * (8u * TOK));
-    uint32_t* const z0 = sz_ring0[wave];
-    uint32_t* const z1 = sz_ring1[wave];
-    uint32_t* const z2 = sz_ring2[wave];
-    BlockRegs r0, r1, r2;
-    int blk = blk0 + wave;
     if (blk < blk1) {
-        load_block<BITS>(r0, z0, rs, blk, lane);
-        load_block<BITS>(r1, z1, rs, blk + 4 < blk1 ? blk + 4 : nblk, lane);
         while (true) {
             load_block<BITS>(r2, z2, rs, blk + 8 < blk1 ? blk + 8 : nblk, lane);
             process_block<BITS>(r0, z0, qf, qsum, neg_qbias, mg, blk, len, lane, st, acc);
