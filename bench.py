@@ -1,7 +1,7 @@
 #!/usr/bin/env python3
 """Benchmark of the W4A16 GEMM hot path on one MI355X.
 
-    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload decode|mlp_decode|prefill|sweep|companion|moe|w8|attn|epilogue|pack|copy]
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload decode|mlp_decode|prefill|sweep|companion|moe|w8|attn|epilogue|layer|pack|copy]
                     [--sweep-out FILE] [--no-cpu-baseline] [--no-prefill]
 
 A "step" is one pass of the fused GEMM over every (layer, M) pair of the workload, weights already packed
@@ -309,10 +309,7 @@ def w8_table(tm, torch, wl, iters=100):
 ATTN_SHAPES = [(1, 2048), (1, 8192), (1, 32768), (8, 2048), (8, 8192), (32, 2048), (32, 8192), (64, 4096), (128, 2048)]
 
 
-args_eager = [False]
-
-
-def attn_table(tm, torch, iters=50, q_heads=32, kv_heads=8, only=None, bits=8):
+def attn_table(tm, torch, iters=50, q_heads=32, kv_heads=8, only=None, bits=8, eager=False):
     import numpy as np
     rows = []
     rng = np.random.default_rng(0)
@@ -344,7 +341,7 @@ def attn_table(tm, torch, iters=50, q_heads=32, kv_heads=8, only=None, bits=8):
             tm.tm_attn_decode(Q, caches[turn[0] % copies], lens, O, 0.08838834764831845, max_len=T)
             turn[0] += 1
 
-        ev_ms, _ = time_steps(torch, step, iters, 5, graph_steps=0 if args_eager[0] else iters)
+        ev_ms, _ = time_steps(torch, step, iters, 5, graph_steps=0 if eager else iters)
         t = ev_ms / iters * 1e-3
         # the step's other kernel: quantise and store the newest token of every sequence (position T - 1)
         knew = torch.randn((B, 1, kv_heads, 128), device="cuda").to(torch.float16)
@@ -355,7 +352,7 @@ def attn_table(tm, torch, iters=50, q_heads=32, kv_heads=8, only=None, bits=8):
             tm.tm_kv_append(caches[turn[0] % copies], knew, vnew, pos)
             turn[0] += 1
 
-        ev_ms, _ = time_steps(torch, store, iters, 5, graph_steps=0 if args_eager[0] else iters)
+        ev_ms, _ = time_steps(torch, store, iters, 5, graph_steps=0 if eager else iters)
         t_store = ev_ms / iters * 1e-3
         bytes_ = per_cache + 2 * B * q_heads * 128 * 2
         rows.append({"batch": B, "context": T, "q_heads": q_heads, "kv_heads": kv_heads, "kv_bits": bits, "us": t * 1e6,
@@ -425,6 +422,86 @@ def epilogue_table(tm, torch, wl, iters=100):
     return rows
 
 
+def layer_table(tm, torch, wl, iters=20, layers=8, context=2048, batches=(1, 8, 32, 64)):
+    """One decoding step through a stack of `layers` transformer layers built from the library's entry points only, in the
+    layer shapes of the benchmark configurations (hidden 4096, 32 heads of 128, gated MLP of 11008): fused QKV GEMM ->
+    quantise-and-store of the new key/value -> decode attention over the quantised cache -> output GEMM + residual ->
+    gate/up GEMM with silu(gate)*up -> down GEMM + residual.  Norms and rotary embedding are left out (elementwise, not
+    part of this library); the three slices of the QKV output are made contiguous by framework copies.  Every layer has
+    its own weights and cache, so a step streams `layers` x (101 MB of weights + the cache) and nothing is re-read from
+    the last-level cache.  Random codes; timing only."""
+    import numpy as np
+    H, NH, I = 4096, 32, 11008
+    rng = np.random.default_rng(0)
+    dev = lambda a: torch.from_numpy(np.ascontiguousarray(a)).cuda()
+
+    def weights(K, N):
+        q = rng.integers(0, 2 ** 31 - 1, (K, N // 8), dtype=np.int64).astype(np.int32)
+        sc = rng.uniform(0.001, 0.004, (K // 128, N)).astype(np.float16)
+        z = rng.integers(0, 16, (K // 128, N)).astype(np.float16)
+        return dev(q), dev(sc), dev(z)
+
+    stack = []
+    for _ in range(layers):
+        stack.append({"qkv": tm.tm_pack_w4(*weights(H, 3 * H), H, 3 * H, 128), "out": tm.tm_pack_w4(*weights(H, H), H, H, 128),
+                      "gate_up": tm.tm_pack_w4_gate_up(*weights(H, 2 * I), H, 2 * I, 128),
+                      "down": tm.tm_pack_w4(*weights(I, H), I, H, 128)})
+    rows = []
+    for bits in (8, 4):
+        for B in batches:
+            caches = []
+            for _ in range(layers):
+                c = tm.tm_kv_create(B, NH, context, bits)
+                k, v, p, cb, pb = tm.tm_kv_raw(c)
+                for ptr in (k, v):
+                    t = torch.randint(0, 256, (cb,), dtype=torch.uint8, device="cuda")
+                    tm.tm_bench_copy_raw(ptr, t.data_ptr(), cb)
+                n = B * NH * c.capacity
+                pairs = (rng.uniform(0.005, 0.05, 2 * n).astype(np.float16).view(np.uint16).astype(np.uint32)
+                         | (rng.integers(0, 16, 2 * n).astype(np.float16).view(np.uint16).astype(np.uint32) << 16))
+                t = torch.from_numpy(pairs.view(np.uint8)).cuda()
+                tm.tm_bench_copy_raw(p, t.data_ptr(), pb)
+                torch.cuda.synchronize()
+                caches.append(c)
+            f16 = lambda *shape: torch.empty(shape, dtype=torch.float16, device="cuda")
+            x0 = torch.randn((B, H), device="cuda").to(torch.float16) * 0.1
+            qkv, q, k, v = f16(B, 3 * H), f16(B, NH, 128), f16(B, 1, NH, 128), f16(B, 1, NH, 128)
+            att, h1, act, h2 = f16(B, NH, 128), f16(B, H), f16(B, I), f16(B, H)
+            pos = torch.full((B,), context - 1, dtype=torch.int32, device="cuda")
+            lens = torch.full((B,), context, dtype=torch.int32, device="cuda")
+
+            def step():
+                x = x0
+                for L, c in zip(stack, caches):
+                    tm.tm_gemm_w4a16(x, L["qkv"], qkv)
+                    q.copy_(qkv[:, :H].view(B, NH, 128))
+                    k.copy_(qkv[:, H:2 * H].view(B, 1, NH, 128))
+                    v.copy_(qkv[:, 2 * H:].view(B, 1, NH, 128))
+                    tm.tm_kv_append(c, k, v, pos)
+                    tm.tm_attn_decode(q, c, lens, att, 0.08838834764831845, max_len=context)
+                    tm.tm_gemm_w4a16_ex(att.view(B, H), L["out"], h1, residual=x)
+                    tm.tm_gemm_w4a16_ex(h1, L["gate_up"], act, act=tm.TM_ACT_SILU_MUL)
+                    tm.tm_gemm_w4a16_ex(act, L["down"], h2, residual=h1)
+                    x = h2
+
+            ev_ms, _ = time_steps(torch, step, iters, 2, graph_steps=iters)
+            us = ev_ms / iters / layers * 1e3
+            wbytes = sum((K * N // 2 + 4 * K * N // 128) for K, N in ((H, 3 * H), (H, H), (H, 2 * I), (I, H)))
+            cbytes = B * NH * context * (2 * 128 * bits // 8 + 8)
+            rows.append({"kv_bits": bits, "batch": B, "context": context, "layers": layers, "us_per_layer": us,
+                         "GBps": (wbytes + cbytes) / us / 1e3, "tokens_per_s_32_layers": B / (us * 32e-6)})
+            log(f"decode layer KV{bits} batch {B:3d} context {context}: {us:8.2f} us per layer  "
+                f"{(wbytes + cbytes) / us / 1e3:6.0f} GB/s of weights+cache  ({B / (us * 32e-6):8.0f} tokens/s at 32 layers)")
+            for c in caches:
+                c.close()
+            del caches
+            torch.cuda.empty_cache()
+    for L in stack:
+        for h in L.values():
+            h.close()
+    return rows
+
+
 def attn_companion(torch, iters=20, q_heads=32, kv_heads=8, only=None):
     """The companion measurement of the attention rows: the same decode step over an unquantised fp16 cache through the
     framework's own fused attention (`scaled_dot_product_attention`, grouped-query mode) - what a serving stack without
@@ -463,13 +540,13 @@ def attn_companion(torch, iters=20, q_heads=32, kv_heads=8, only=None):
     return rows
 
 
-def attn_store_row(tm, torch, iters=20, B=16, T=2048, kv_heads=8, bits=8):
+def attn_store_row(tm, torch, iters=20, B=16, T=2048, kv_heads=8, bits=8, eager=False):
     """Quantise-and-store of a whole prompt (the prefill side of the cache): reads 2 fp16 tensors, writes codes + pairs."""
     c = tm.tm_kv_create(B, kv_heads, T, bits)
     knew = torch.randn((B, T, kv_heads, 128), device="cuda").to(torch.float16)
     vnew = torch.randn((B, T, kv_heads, 128), device="cuda").to(torch.float16)
     pos = torch.zeros((B,), dtype=torch.int32, device="cuda")
-    ev_ms, _ = time_steps(torch, lambda: tm.tm_kv_append(c, knew, vnew, pos), iters, 3, graph_steps=0 if args_eager[0] else iters)
+    ev_ms, _ = time_steps(torch, lambda: tm.tm_kv_append(c, knew, vnew, pos), iters, 3, graph_steps=0 if eager else iters)
     t = ev_ms / iters * 1e-3
     bytes_ = B * T * kv_heads * (2 * 128 * 2 + 2 * 128 * bits // 8 + 8)
     c.close()
@@ -530,7 +607,7 @@ def main():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=200)
     ap.add_argument("--warmup", type=int, default=20)
-    ap.add_argument("--workload", default="decode", choices=sorted(WORKLOADS) + ["sweep", "copy", "companion", "pack", "moe", "w8", "attn", "epilogue"])
+    ap.add_argument("--workload", default="decode", choices=sorted(WORKLOADS) + ["sweep", "copy", "companion", "pack", "moe", "w8", "attn", "epilogue", "layer"])
     ap.add_argument("--sweep-out", default=None, help="with --workload sweep: write the per-shape table here (JSON)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--attn-companion", action="store_true",
@@ -597,6 +674,15 @@ def main():
         print(json.dumps({"metric": "offline pack", "K": K, "N": N, "group": g, "steps": args.steps, "rows": rows}))
         return
 
+    if args.workload == "layer":
+        table = layer_table(tm, torch, wl, iters=min(args.steps, 20))
+        if args.sweep_out:
+            os.makedirs(os.path.dirname(os.path.abspath(args.sweep_out)), exist_ok=True)
+            json.dump(table, open(args.sweep_out, "w"), indent=1)
+        print(json.dumps({"metric": "one decoding step of a transformer layer built from the library's entry points: microseconds per layer",
+                          "workload": "layer", "n_gpus": 1, "data": "synthetic", "rows": table}))
+        return
+
     if args.workload == "epilogue":
         table = epilogue_table(tm, torch, wl, iters=min(args.steps, 100))
         if args.sweep_out:
@@ -608,12 +694,11 @@ def main():
 
     if args.workload == "attn":
         only = tuple(int(v) for v in args.only.split(":")) if args.only else None
-        args_eager[0] = args.eager
         if only is not None and len(only) == 3:                 # --only batch:context:bits
-            table = attn_table(tm, torch, iters=min(args.steps, 50), only=only[:2], bits=only[2])
+            table = attn_table(tm, torch, iters=min(args.steps, 50), only=only[:2], bits=only[2], eager=args.eager)
         else:
-            table = attn_table(tm, torch, iters=min(args.steps, 50), only=only)
-            table += attn_table(tm, torch, iters=min(args.steps, 50), only=only, bits=4)
+            table = attn_table(tm, torch, iters=min(args.steps, 50), only=only, eager=args.eager)
+            table += attn_table(tm, torch, iters=min(args.steps, 50), only=only, bits=4, eager=args.eager)
         if args.sweep_out:
             os.makedirs(os.path.dirname(os.path.abspath(args.sweep_out)), exist_ok=True)
             json.dump(table, open(args.sweep_out, "w"), indent=1)
@@ -630,7 +715,7 @@ def main():
                                        "frac": best["hbm_frac"], "traffic": traffic, "kernel": f"attn_decode_kernel<{best['kv_bits']}>",
                                        "avg_launch_us": best["us"]},
                           "cpu_baseline": None if args.no_cpu_baseline else attn_cpu_baseline(),
-                          "store": None if only is not None else [attn_store_row(tm, torch), attn_store_row(tm, torch, bits=4)],
+                          "store": None if only is not None else [attn_store_row(tm, torch, eager=args.eager), attn_store_row(tm, torch, bits=4, eager=args.eager)],
                           "fp16_cache_library": attn_companion(torch, iters=min(args.steps, 20)) if args.attn_companion else None,
                           "rows": table}))
         return
