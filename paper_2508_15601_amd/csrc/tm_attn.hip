@@ -833,7 +833,10 @@ hipError_t launch_attn_decode(const AttnCache& kv, const uint16_t* Q, const int3
     // half-empty round (measured: 28.5 instead of 31.8 us at batch 8 x 8192) - at least four blocks per wave and split,
     // and no more partial results than the cache's workspace holds
     int splits = (2 * num_cu + kv.batch * kv.heads - 1) / (kv.batch * kv.heads);
-    const int by_work = nblk / 16 > 0 ? nblk / 16 : 1;
+    // (short contexts: up to eight splits of at least two blocks per wave - a 2048-token context is cut in four or
+    // eight instead of two or four pieces, which shortens each CTA's serial chain more than the merge costs)
+    const int few = nblk / 8 < 8 ? nblk / 8 : 8;
+    const int by_work = nblk / 16 > few ? nblk / 16 : (few > 0 ? few : 1);
     if (splits > by_work) splits = by_work;
     if (splits > kv.max_splits) splits = kv.max_splits;
     if (splits < 1) splits = 1;
