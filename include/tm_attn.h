@@ -69,7 +69,9 @@ TM_API int tm_kv_append(tm_kv_cache* cache, const uint16_t* K_new, const uint16_
 /*
  * One decoding step.  Q fp16 [batch][q_heads][128], O fp16 [batch][q_heads][128], both 16-byte aligned; lens int32
  * [batch] = tokens cached per sequence (clamped to [0, capacity]; a sequence with 0 tokens gets O = 0).  max_len (host)
- * bounds lens and only steers how the context is split across CTAs; pass the capacity if unknown.  Never allocates.
+ * is an upper bound of lens that steers how the context is split across CTAs; pass the capacity (or 0) if unknown.  A
+ * sequence longer than max_len rounded up to whole blocks and splits attends over that many leading tokens only.  Never
+ * allocates.
  * Partial results of split contexts go through the cache's own workspace: calls on one cache must be ordered on one
  * stream.  Results are bit-identical from run to run.
  */

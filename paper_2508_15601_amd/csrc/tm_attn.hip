@@ -609,7 +609,9 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))) voi
     const int hk = blockIdx.x, b = blockIdx.y, split = blockIdx.z;
     const int G = q_heads / kv.heads;
     const size_t bh = (size_t)b * kv.heads + hk;
-    const int len = min(max(lens[b], 0), kv.cap);
+    // the splits cover blocks_per_split * splits blocks (the host's max_len): a longer sequence is cut there, never read
+    // half-way
+    const int len = min(min(max(lens[b], 0), kv.cap), blocks_per_split * splits * TOK);
     const int nblk = (len + TOK - 1) / TOK;
     const int blk0 = split * blocks_per_split;
     const int blk1 = min(nblk, blk0 + blocks_per_split);

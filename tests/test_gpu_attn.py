@@ -190,6 +190,15 @@ def test_attn_decode_special_cases(tm, bits):
     ok, worst, fro = _close(O[:1], Oref)
     assert ok, (worst, fro)
     assert np.allclose(O[0, 0].astype(np.float64), oa.kv_dequant(Vq, Vs, Vz)[0, 0, 70], rtol=1e-2, atol=2e-3)
+    # a max_len below the sequence's length cuts the context at a block boundary instead of dropping blocks in the middle
+    tm.tm_kv_upload(cache, kbuf, vbuf, szbuf)
+    lens2 = np.array([128, 100], np.int32)
+    O2 = torch.full((B, Hq, 128), float("nan"), dtype=torch.float16, device="cuda")
+    tm.tm_attn_decode(_dev(Q), cache, _dev(lens2), O2, 0.1, max_len=64)
+    torch.cuda.synchronize()
+    Oref2 = oa.attn_decode(Q, Kq, Ks, Kz, Vq, Vs, Vz, np.array([64, 64], np.int32), 0.1)
+    ok, worst, fro = _close(O2.cpu().numpy(), Oref2)
+    assert ok, (worst, fro)
     cache.close()
 
 
