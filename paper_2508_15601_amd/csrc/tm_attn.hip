@@ -586,6 +586,15 @@ __device__ __forceinline__ void process_block(const BlockRegs& r, const uint32_t
     }
 }
 
+// Four consecutive dimensions d0 .. d0+3 of query head `head` of sequence b, rounded to fp16.
+__device__ __forceinline__ void store_out4(uint16_t* O, int b, int q_heads, int head, int d0, const float (&o)[4])
+{
+    u32x2 out;
+    out.x = (uint32_t)f32_to_f16_bits(o[0]) | ((uint32_t)f32_to_f16_bits(o[1]) << 16);
+    out.y = (uint32_t)f32_to_f16_bits(o[2]) | ((uint32_t)f32_to_f16_bits(o[3]) << 16);
+    *(u32x2*)(O + ((size_t)b * q_heads + head) * kHeadDim + d0) = out;
+}
+
 // grid (kv heads, batch, splits); 256 threads.  Partial layout per (b, h, split): m[16], l[16], out[128][16] floats.
 constexpr int kPartialFloats = 32 + kHeadDim * 16;
 
@@ -593,7 +602,7 @@ template <int BITS>
 __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))) void attn_decode_kernel(AttnCache kv, const uint16_t* __restrict__ Q,
                                                           const int32_t* __restrict__ lens, uint16_t* __restrict__ O,
                                                           int q_heads, float scale_log2e, int blocks_per_split,
-                                                          int splits)
+                                                          int splits, int merge_here)
 {
     __shared__ float sm_ml[4][2][16];
     __shared__ float sm_out[4][8][4][64];
@@ -715,37 +724,91 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))) voi
         f[w] = exp2f(sm_ml[w][0][c] - M);
         L += sm_ml[w][1][c] * f[w];
     }
-    float* part = nullptr;
-    if (splits > 1) {
-        part = kv.partial + (((size_t)bh * splits) + split) * kPartialFloats;
-        if (wave == 0 && h == 0) {
-            part[c] = M;
-            part[16 + c] = L;
+    if (splits == 1) {
+        const float inv = L > 0.f ? 1.0f / L : 0.f;
+#pragma unroll
+        for (int ii = 0; ii < 2; ++ii) {
+            const int i = 2 * wave + ii;
+            float o[4];
+#pragma unroll
+            for (int rr = 0; rr < 4; ++rr) {
+                float v = 0.f;
+#pragma unroll
+                for (int w = 0; w < 4; ++w) v += sm_out[w][i][rr][lane] * f[w];
+                o[rr] = v * inv;
+            }
+            if (c < G) store_out4(O, b, q_heads, hk * G + c, 16 * i + 4 * h, o);
         }
+        return;
     }
-    const float inv = L > 0.f ? 1.0f / L : 0.f;
+
+    // Split context: this CTA's maximum, denominator and unnormalised rows go to the workspace - values of row tile i,
+    // register rr at float 32 + (4*i + rr)*64 + lane, so that writer and reader touch whole 256-byte lines - as
+    // write-through stores that CTAs on other XCDs can read back without a device-wide fence.
+    float* part = kv.partial + (((size_t)bh * splits) + split) * kPartialFloats;
+    if (wave == 0 && h == 0) {
+        st_partial(part + c, M);
+        st_partial(part + 16 + c, L);
+    }
 #pragma unroll
     for (int ii = 0; ii < 2; ++ii) {
         const int i = 2 * wave + ii;
-        float o[4];
 #pragma unroll
         for (int rr = 0; rr < 4; ++rr) {
             float v = 0.f;
 #pragma unroll
             for (int w = 0; w < 4; ++w) v += sm_out[w][i][rr][lane] * f[w];
-            o[rr] = v;
-        }
-        const int d0 = 16 * i + 4 * h;                      // this lane's four consecutive dimensions
-        if (splits > 1) {
-#pragma unroll
-            for (int rr = 0; rr < 4; ++rr) part[32 + (d0 + rr) * 16 + c] = o[rr];
-        } else if (c < G) {
-            u32x2 out;
-            out.x = (uint32_t)f32_to_f16_bits(o[0] * inv) | ((uint32_t)f32_to_f16_bits(o[1] * inv) << 16);
-            out.y = (uint32_t)f32_to_f16_bits(o[2] * inv) | ((uint32_t)f32_to_f16_bits(o[3] * inv) << 16);
-            *(u32x2*)(O + ((size_t)b * q_heads + (size_t)hk * G + c) * kHeadDim + d0) = out;
+            st_partial(part + 32 + (4 * i + rr) * 64 + lane, v);
         }
     }
+    if (!merge_here) return;                                  // many splits: the merge kernel follows
+
+    // Few splits: the CTA that arrives last at this (sequence, head)'s counter merges them, in split order.
+    __shared__ uint32_t s_last;
+    wait_stores_done();
+    __syncthreads();
+    if (tid == 0) {
+        const uint32_t prev = atomicAdd(&kv.counters[bh], 1u);
+        s_last = (prev == (uint32_t)splits - 1u) ? 1u : 0u;
+    }
+    __syncthreads();
+    if (!s_last) return;
+    // at most four splits come here: all their loads are issued before the first use (the loop is unrolled and a
+    // missing split reads split 0 again with a factor of zero)
+    const float* base = kv.partial + (size_t)bh * splits * kPartialFloats;
+    float ms[4], ls[4], vals[4][2][4];
+#pragma unroll
+    for (int sp = 0; sp < 4; ++sp) {
+        const float* ps = base + (size_t)(sp < splits ? sp : 0) * kPartialFloats;
+        ms[sp] = ld_partial(ps + c);
+        ls[sp] = ld_partial(ps + 16 + c);
+#pragma unroll
+        for (int ii = 0; ii < 2; ++ii)
+#pragma unroll
+            for (int rr = 0; rr < 4; ++rr) vals[sp][ii][rr] = ld_partial(ps + 32 + (4 * (2 * wave + ii) + rr) * 64 + lane);
+    }
+    float Mg = kNegBig;
+#pragma unroll
+    for (int sp = 0; sp < 4; ++sp) Mg = fmaxf(Mg, sp < splits ? ms[sp] : kNegBig);
+    float Lg = 0.f;
+    float o[2][4] = {{0.f, 0.f, 0.f, 0.f}, {0.f, 0.f, 0.f, 0.f}};
+#pragma unroll
+    for (int sp = 0; sp < 4; ++sp) {
+        const float fs = sp < splits ? exp2f(ms[sp] - Mg) : 0.f;
+        Lg += ls[sp] * fs;
+#pragma unroll
+        for (int ii = 0; ii < 2; ++ii)
+#pragma unroll
+            for (int rr = 0; rr < 4; ++rr) o[ii][rr] += vals[sp][ii][rr] * fs;
+    }
+    const float invg = Lg > 0.f ? 1.0f / Lg : 0.f;
+#pragma unroll
+    for (int ii = 0; ii < 2; ++ii) {
+#pragma unroll
+        for (int rr = 0; rr < 4; ++rr) o[ii][rr] *= invg;
+        if (c < G) store_out4(O, b, q_heads, hk * G + c, 16 * (2 * wave + ii) + 4 * h, o[ii]);
+    }
+    if (tid == 0) __hip_atomic_store(&kv.counters[bh], 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
 }
 
 // Merge of the context splits: grid (kv heads, batch, 8 chunks of 16 dimensions), 256 threads = 16 query heads x 16.
@@ -766,8 +829,8 @@ __global__ __launch_bounds__(256) void attn_merge_kernel(AttnCache kv, uint16_t*
 #pragma unroll
     for (int i = 0; i < 4; ++i) {
         const int s = g + 16 * i;
-        ms[i] = s < splits ? base[(size_t)s * kPartialFloats + m] : kNegBig;
-        ls[i] = s < splits ? base[(size_t)s * kPartialFloats + 16 + m] : 0.f;
+        ms[i] = s < splits ? ld_partial(base + (size_t)s * kPartialFloats + m) : kNegBig;
+        ls[i] = s < splits ? ld_partial(base + (size_t)s * kPartialFloats + 16 + m) : 0.f;
         mx = fmaxf(mx, ms[i]);
     }
     red[g][m] = mx;
@@ -791,9 +854,11 @@ __global__ __launch_bounds__(256) void attn_merge_kernel(AttnCache kv, uint16_t*
     const float inv = L > 0.f ? 1.0f / L : 0.f;
     if (m >= G) return;
     const int d = 16 * chunk + g;
+    // dimension d = 16*chunk + 4*hh + rr of query head m sits at float 32 + (4*chunk + rr)*64 + 16*hh + m
+    const int at = 32 + (4 * chunk + (g & 3)) * 64 + 16 * (g >> 2) + m;
     float v = 0.f;
 #pragma unroll 8
-    for (int s = 0; s < splits; ++s) v += base[(size_t)s * kPartialFloats + 32 + d * 16 + m] * fac[s][m];
+    for (int s = 0; s < splits; ++s) v += ld_partial(base + (size_t)s * kPartialFloats + at) * fac[s][m];
     O[((size_t)b * q_heads + (size_t)hk * G + m) * kHeadDim + d] = f32_to_f16_bits(v * inv);
 }
 
@@ -846,14 +911,18 @@ hipError_t launch_attn_decode(const AttnCache& kv, const uint16_t* Q, const int3
     splits = (nblk + bps - 1) / bps > 0 ? (nblk + bps - 1) / bps : 1;
     if (kv.heads > 65535 || kv.batch > 65535) return hipErrorInvalidValue;
     const float scale_log2e = scale * 1.4426950408889634f;
+    // up to four splits are merged by the CTA that finishes last (measured at two splits: 27.6 instead of 29.7 us at
+    // batch 32 x 2048); with eight that one CTA's chain of loads became the bottleneck (11.5 instead of 8.5 us at batch
+    // 1 x 2048), so more splits go to the merge kernel, which spreads a (sequence, head) over eight CTAs
+    const int merge_here = splits > 1 && splits <= 4;
     if (kv.bits == 8)
         hipLaunchKernelGGL(attn_decode_kernel<8>, dim3(kv.heads, kv.batch, splits), dim3(256), 0, stream, kv, Q, lens, O,
-                           q_heads, scale_log2e, bps, splits);
+                           q_heads, scale_log2e, bps, splits, merge_here);
     else
         hipLaunchKernelGGL(attn_decode_kernel<4>, dim3(kv.heads, kv.batch, splits), dim3(256), 0, stream, kv, Q, lens, O,
-                           q_heads, scale_log2e, bps, splits);
+                           q_heads, scale_log2e, bps, splits, merge_here);
     hipError_t e = hipGetLastError();
-    if (e != hipSuccess || splits == 1) return e;
+    if (e != hipSuccess || splits == 1 || merge_here) return e;
     hipLaunchKernelGGL(attn_merge_kernel, dim3(kv.heads, kv.batch, 8), dim3(256), 0, stream, kv, O, q_heads, splits);
     return hipGetLastError();
 }

@@ -989,12 +989,17 @@ tm_kv_cache* tm_kv_create(int batch, int kv_heads, int capacity, int bits)
     hipError_t e = hipMalloc((void**)&c->kv.k, c->code_bytes);
     if (e == hipSuccess) e = hipMalloc((void**)&c->kv.v, c->code_bytes);
     if (e == hipSuccess) e = hipMalloc((void**)&c->kv.sz, c->pair_bytes);
-    if (e == hipSuccess) e = hipMalloc((void**)&c->kv.partial, part_bytes);
+    if (e == hipSuccess) e = hipMalloc((void**)&c->kv.partial, part_bytes + (size_t)batch * kv_heads * sizeof(uint32_t));
+    if (e == hipSuccess) {
+        c->kv.counters = (uint32_t*)((char*)c->kv.partial + part_bytes);
+        e = hipMemset(c->kv.counters, 0, (size_t)batch * kv_heads * sizeof(uint32_t));
+    }
     if (e != hipSuccess) {
         fail_hip(e, "hipMalloc(kv cache)");
         if (c->kv.k) (void)hipFree(c->kv.k);
         if (c->kv.v) (void)hipFree(c->kv.v);
         if (c->kv.sz) (void)hipFree(c->kv.sz);
+        if (c->kv.partial) (void)hipFree(c->kv.partial);
         delete c;
         return nullptr;
     }

@@ -58,7 +58,8 @@ struct AttnCache {
     uint8_t* k;          // [batch*heads][cap/32] blocks of 32 tokens (4096 or 2048 bytes) in K*Q^T operand order
     uint8_t* v;          // [batch*heads][cap/32] blocks of 32 tokens in V^T*P^T operand order
     uint32_t* sz;        // [batch*heads][cap][2] scale | zero << 16: K pair, V pair
-    float* partial;      // split workspace: [batch*heads][max_splits] x (m[16], l[16], out[128][16])
+    float* partial;      // split workspace: [batch*heads][max_splits] x (m[16], l[16], out[32 registers][64 lanes])
+    uint32_t* counters;  // [batch*heads] arrival counters of the split merge, zero between launches
     int batch, heads, cap, max_splits;
     int bits;            // 8 or 4 bits per code; cap is a multiple of 256 / bits
 };
