@@ -570,7 +570,110 @@ __device__ __forceinline__ void process_tokens(const BlockRegs& r, int sb, const
     }
 }
 
-template <int BITS>
+// The same 32 tokens when at most eight query heads share the KV head: the query operand then carries every head twice
+// (column c and c + 8 both hold head c % 8), so both score tiles come out with all 16 columns live, and a lane keeps
+// tile c / 8 only - four scores instead of eight, half the softmax arithmetic.  The probabilities of the other tile's
+// tokens reach the lane through one exchange with lane c ^ 8 before the second product; running sums are per lane over
+// its own tokens and meet at the end (xor 8, 16, 32).
+__device__ __forceinline__ uint32_t swap_half_rows(uint32_t v)
+{
+    return (uint32_t)__builtin_amdgcn_mov_dpp((int)v, 0x128, 0xf, 0xf, true);      // row_ror:8 = lane c <-> c ^ 8
+}
+
+template <int BITS, bool MASKED>
+__device__ __forceinline__ void process_tokens_packed(const BlockRegs& r, int sb, const uint32_t* sz_slot,
+                                                      const f16x8 (&qf)[4], float qsum, const f32x4& neg_qbias,
+                                                      const Magic& mg, int t0, int len, int lane, SoftmaxState& st,
+                                                      f32x4 (&acc)[8])
+{
+    const int h = lane >> 4, jl = (lane >> 3) & 1;           // jl: the 16-token tile this lane keeps
+    const int rem = len - t0 - 4 * h - 16 * jl;              // slot rr of this lane is a live token iff rr < rem
+    f32x4 d[2];
+#pragma unroll
+    for (int j = 0; j < 2; ++j) {
+        if constexpr (BITS == 8) {
+            d[j] = mfma16x16x32(biased8_w8(r.k[j][0].x, r.k[j][0].y), qf[0], neg_qbias);
+            d[j] = mfma16x16x32(biased8_w8(r.k[j][0].z, r.k[j][0].w), qf[1], d[j]);
+            d[j] = mfma16x16x32(biased8_w8(r.k[j][1].x, r.k[j][1].y), qf[2], d[j]);
+            d[j] = mfma16x16x32(biased8_w8(r.k[j][1].z, r.k[j][1].w), qf[3], d[j]);
+        } else {
+            const u32x4 w = r.k[sb][j];
+            d[j] = mfma16x16x32(biased8(w.x, mg), qf[0], neg_qbias);
+            d[j] = mfma16x16x32(biased8(w.y, mg), qf[1], d[j]);
+            d[j] = mfma16x16x32(biased8(w.z, mg), qf[2], d[j]);
+            d[j] = mfma16x16x32(biased8(w.w, mg), qf[3], d[j]);
+        }
+    }
+    // (K pair, V pair) of the lane's four tokens 16*jl + 4h .. +3
+    const u32x4 p0 = *(const u32x4*)(sz_slot + 32 * jl + 8 * h);
+    const u32x4 p1 = *(const u32x4*)(sz_slot + 32 * jl + 8 * h + 4);
+    float s[4];
+    uint32_t vw[4];
+#pragma unroll
+    for (int rr = 0; rr < 4; ++rr) {
+        const bool live = !MASKED || rr < rem;
+        const f16x2 kp = as_f16x2(rr < 2 ? p0[2 * rr] : p1[2 * (rr - 2)]);
+        vw[rr] = live ? (rr < 2 ? p0[2 * rr + 1] : p1[2 * (rr - 2) + 1]) : 0u;
+        const float dm = jl ? d[1][rr] : d[0][rr];
+        const float t = __builtin_fmaf(-(float)kp.y, qsum, dm);
+        const float sc = __builtin_fmaf((float)kp.x, t, 0.0f);
+        s[rr] = live ? sc : kNegBig;
+    }
+    float mx = fmaxf(fmaxf(s[0], s[1]), fmaxf(s[2], s[3]));
+    mx = fmaxf(mx, __builtin_bit_cast(float, swap_half_rows(__builtin_bit_cast(uint32_t, mx))));
+    mx = xor_max(xor_max(mx, 16), 32);
+    const float m_new = fmaxf(st.m_run, mx);
+    const float alpha = fast_exp2(st.m_run - m_new);
+    st.m_run = m_new;
+    float psum = 0.f;
+    _Float16 own[4];
+#pragma unroll
+    for (int rr = 0; rr < 4; ++rr) {
+        const float p = fast_exp2(s[rr] - m_new);            // 0 for masked tokens
+        psum += p;
+        own[rr] = (_Float16)__builtin_fmaf((float)as_f16x2(vw[rr]).x, p, 0.0f);
+    }
+    // the lane's four probabilities as two operand words, pinned (the correction below must see the very bits the
+    // matrix core multiplies), then the other tile's four from lane c ^ 8
+    uint32_t o0 = (uint32_t)__builtin_bit_cast(uint16_t, own[0]) | ((uint32_t)__builtin_bit_cast(uint16_t, own[1]) << 16);
+    uint32_t o1 = (uint32_t)__builtin_bit_cast(uint16_t, own[2]) | ((uint32_t)__builtin_bit_cast(uint16_t, own[3]) << 16);
+    asm volatile("" : "+v"(o0), "+v"(o1));
+    const uint32_t x0 = swap_half_rows(o0), x1 = swap_half_rows(o1);
+    u32x4 pbits;
+    pbits.x = jl ? x0 : o0;                                  // k-values 0..3: tile 0, 4..7: tile 1
+    pbits.y = jl ? x1 : o1;
+    pbits.z = jl ? o0 : x0;
+    pbits.w = jl ? o1 : x1;
+    const f16x8 pb = __builtin_bit_cast(f16x8, pbits);
+    float sum_hi = 0.f, sum_lo = 0.f, zsum = 0.f;
+#pragma unroll
+    for (int rr = 0; rr < 4; ++rr) {
+        const float pv = (float)(rr < 2 ? (rr == 0 ? as_f16x2(o0).x : as_f16x2(o0).y) : (rr == 2 ? as_f16x2(o1).x : as_f16x2(o1).y));
+        if (BITS == 8 || rr < 2) sum_hi = __builtin_fmaf(pv, 1.0f, sum_hi);
+        else sum_lo = __builtin_fmaf(pv, 1.0f, sum_lo);
+        zsum = __builtin_fmaf((float)as_f16x2(vw[rr]).y, pv, zsum);
+    }
+    const float csum = __builtin_fmaf(1024.0f, sum_hi, __builtin_fmaf(64.0f, sum_lo, zsum));
+    st.l_run = st.l_run * alpha + psum;
+    st.corr = st.corr * alpha + csum;
+    if (__any(alpha != 1.0f)) {
+#pragma unroll
+        for (int i = 0; i < 8; ++i) acc[i] *= alpha;
+    }
+#pragma unroll
+    for (int i = 0; i < 8; ++i) {
+        f16x8 a;
+        if constexpr (BITS == 8) {
+            const u32x4 w = r.v[i >> 1];
+            a = (i & 1) ? biased8_w8(w.z, w.w) : biased8_w8(w.x, w.y);
+        } else {
+            a = biased8(r.v[2 * sb + (i >> 2)][i & 3], mg);
+        }
+        acc[i] = mfma16x16x32(a, pb, acc[i]);
+    }
+}
+
+template <int BITS, bool PACK>
 __device__ __forceinline__ void process_block(const BlockRegs& r, const uint32_t* sz_slot, const f16x8 (&qf)[4],
                                               float qsum, const f32x4& neg_qbias, const Magic& mg, int blk, int len, int lane,
                                               SoftmaxState& st, f32x4 (&acc)[8])
@@ -580,9 +683,17 @@ __device__ __forceinline__ void process_block(const BlockRegs& r, const uint32_t
     // the first 32 tokens always hold a live one; the second half of a 4-bit block may lie wholly behind the context
     // (wave-uniform).  (A second, unmasked copy of the code for blocks inside the context costs more registers than the
     // kernel has: it spills.)
-    process_tokens<BITS, true>(r, 0, sz_slot, qf, qsum, neg_qbias, mg, t0, len, lane, st, acc);
-    if constexpr (BITS == 4) {
-        if (t0 + 32 < len) process_tokens<4, true>(r, 1, sz_slot + 64, qf, qsum, neg_qbias, mg, t0 + 32, len, lane, st, acc);
+    if constexpr (PACK) {
+        process_tokens_packed<BITS, true>(r, 0, sz_slot, qf, qsum, neg_qbias, mg, t0, len, lane, st, acc);
+        if constexpr (BITS == 4) {
+            if (t0 + 32 < len)
+                process_tokens_packed<4, true>(r, 1, sz_slot + 64, qf, qsum, neg_qbias, mg, t0 + 32, len, lane, st, acc);
+        }
+    } else {
+        process_tokens<BITS, true>(r, 0, sz_slot, qf, qsum, neg_qbias, mg, t0, len, lane, st, acc);
+        if constexpr (BITS == 4) {
+            if (t0 + 32 < len) process_tokens<4, true>(r, 1, sz_slot + 64, qf, qsum, neg_qbias, mg, t0 + 32, len, lane, st, acc);
+        }
     }
 }
 
@@ -598,7 +709,7 @@ __device__ __forceinline__ void store_out4(uint16_t* O, int b, int q_heads, int 
 // grid (kv heads, batch, splits); 256 threads.  Partial layout per (b, h, split): m[16], l[16], out[128][16] floats.
 constexpr int kPartialFloats = 32 + kHeadDim * 16;
 
-template <int BITS>
+template <int BITS, bool PACK>
 __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))) void attn_decode_kernel(AttnCache kv, const uint16_t* __restrict__ Q,
                                                           const int32_t* __restrict__ lens, uint16_t* __restrict__ O,
                                                           int q_heads, float scale_log2e, int blocks_per_split,
@@ -628,10 +739,11 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))) voi
     // Order of the prologue: the query's raw loads, then at once the first two blocks of the KV memory loading pipeline,
     // and only then the arithmetic on the query, which so runs under the blocks' latency (loads return in order, so the
     // query must be requested first).
-    const bool real = c < G;
+    const int qc = PACK ? (c & 7) : c;                       // the query head of operand column c
+    const bool real = qc < G;
     f16x8 qraw[4];
     {
-        const uint16_t* qp = Q + ((size_t)b * q_heads + (size_t)hk * G + (real ? c : 0)) * kHeadDim + 32 * h;
+        const uint16_t* qp = Q + ((size_t)b * q_heads + (size_t)hk * G + (real ? qc : 0)) * kHeadDim + 32 * h;
 #pragma unroll
         for (int tt = 0; tt < 4; ++tt) qraw[tt] = *(const f16x8*)(qp + 8 * tt);
     }
@@ -688,23 +800,27 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))) voi
     if (blk < blk1) {
         while (true) {
             load_block<BITS>(r2, z2, rs, blk + 8 < blk1 ? blk + 8 : nblk, lane);
-            process_block<BITS>(r0, z0, qf, qsum, neg_qbias, mg, blk, len, lane, st, acc);
+            process_block<BITS, PACK>(r0, z0, qf, qsum, neg_qbias, mg, blk, len, lane, st, acc);
             blk += 4;
             if (blk >= blk1) break;
             load_block<BITS>(r0, z0, rs, blk + 8 < blk1 ? blk + 8 : nblk, lane);
-            process_block<BITS>(r1, z1, qf, qsum, neg_qbias, mg, blk, len, lane, st, acc);
+            process_block<BITS, PACK>(r1, z1, qf, qsum, neg_qbias, mg, blk, len, lane, st, acc);
             blk += 4;
             if (blk >= blk1) break;
             load_block<BITS>(r1, z1, rs, blk + 8 < blk1 ? blk + 8 : nblk, lane);
-            process_block<BITS>(r2, z2, qf, qsum, neg_qbias, mg, blk, len, lane, st, acc);
+            process_block<BITS, PACK>(r2, z2, qf, qsum, neg_qbias, mg, blk, len, lane, st, acc);
             blk += 4;
             if (blk >= blk1) break;
         }
     }
 
     // the four lanes of a query head add their partial sums; the waves meet in LDS
-    const float l_w = xor_add(xor_add(st.l_run, 16), 32);
-    const float corr_w = xor_add(xor_add(st.corr, 16), 32);
+    float l_w = xor_add(xor_add(st.l_run, 16), 32);
+    float corr_w = xor_add(xor_add(st.corr, 16), 32);
+    if constexpr (PACK) {                                    // the two tiles' lanes of a query head
+        l_w = xor_add(l_w, 8);
+        corr_w = xor_add(corr_w, 8);
+    }
     if (h == 0) {
         sm_ml[wave][0][c] = st.m_run;
         sm_ml[wave][1][c] = l_w;
@@ -918,12 +1034,20 @@ hipError_t launch_attn_decode(const AttnCache& kv, const uint16_t* Q, const int3
     // batch 32 x 2048); with eight that one CTA's chain of loads became the bottleneck (11.5 instead of 8.5 us at batch
     // 1 x 2048), so more splits go to the merge kernel, which spreads a (sequence, head) over eight CTAs
     const int merge_here = splits > 1 && splits <= 4;
-    if (kv.bits == 8)
-        hipLaunchKernelGGL(attn_decode_kernel<8>, dim3(kv.heads, kv.batch, splits), dim3(256), 0, stream, kv, Q, lens, O,
-                           q_heads, scale_log2e, bps, splits, merge_here);
+    const dim3 grid(kv.heads, kv.batch, splits);
+    const bool pack = q_heads / kv.heads <= 8;               // both score tiles share one softmax pass
+    if (kv.bits == 8 && pack)
+        hipLaunchKernelGGL((attn_decode_kernel<8, true>), grid, dim3(256), 0, stream, kv, Q, lens, O, q_heads, scale_log2e, bps,
+                           splits, merge_here);
+    else if (kv.bits == 8)
+        hipLaunchKernelGGL((attn_decode_kernel<8, false>), grid, dim3(256), 0, stream, kv, Q, lens, O, q_heads, scale_log2e, bps,
+                           splits, merge_here);
+    else if (pack)
+        hipLaunchKernelGGL((attn_decode_kernel<4, true>), grid, dim3(256), 0, stream, kv, Q, lens, O, q_heads, scale_log2e, bps,
+                           splits, merge_here);
     else
-        hipLaunchKernelGGL(attn_decode_kernel<4>, dim3(kv.heads, kv.batch, splits), dim3(256), 0, stream, kv, Q, lens, O,
-                           q_heads, scale_log2e, bps, splits, merge_here);
+        hipLaunchKernelGGL((attn_decode_kernel<4, false>), grid, dim3(256), 0, stream, kv, Q, lens, O, q_heads, scale_log2e, bps,
+                           splits, merge_here);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess || splits == 1 || merge_here) return e;
     hipLaunchKernelGGL(attn_merge_kernel, dim3(kv.heads, kv.batch, 8), dim3(256), 0, stream, kv, O, q_heads, splits);
