@@ -712,7 +712,7 @@ def main():
                           "data": "synthetic", "config": {"workload": f"KV{best['kv_bits']}, batch {best['batch']} x context {best['context']}, "
                                                                       f"{best['q_heads']} query / {best['kv_heads']} KV heads, head dimension 128"},
                           "roofline": {"bound": "hbm", "achieved": best["GBps"], "peak": HBM_PEAK_GBPS, "unit": "GB/s",
-                                       "frac": best["hbm_frac"], "traffic": traffic, "kernel": f"attn_decode_kernel<{best['kv_bits']}>",
+                                       "frac": best["hbm_frac"], "traffic": traffic, "kernel": f"attn_decode_kernel<{best['kv_bits']}, true>",
                                        "avg_launch_us": best["us"]},
                           "cpu_baseline": None if args.no_cpu_baseline else attn_cpu_baseline(),
                           "store": None if only is not None else [attn_store_row(tm, torch, eager=args.eager), attn_store_row(tm, torch, bits=4, eager=args.eager)],
