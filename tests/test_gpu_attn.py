@@ -232,3 +232,41 @@ def test_attn_decode_full_size_sampled(tm, bits):
     ok, worst, fro = _close(O[sample].cpu().numpy(), Oref)
     assert ok, (worst, fro)
     cache.close()
+
+
+def _random_cases(n, seed):
+    rng = np.random.default_rng(seed)
+    cases = []
+    for i in range(n):
+        Hkv = int(rng.choice([1, 2, 3, 8]))
+        G = int(rng.choice([1, 2, 4, 5, 8, 9, 16]))
+        B = int(rng.choice([1, 2, 5, 9]))
+        T = int(rng.choice([1, 40, 64, 65, 130, 700, 2100, 6000]))
+        cases.append((i, B, Hkv * G, Hkv, T, int(rng.choice([4, 8]))))
+    return cases
+
+
+@pytest.mark.parametrize("i,B,Hq,Hkv,T,bits", _random_cases(24, 2024))
+def test_attn_decode_random_shapes(tm, i, B, Hq, Hkv, T, bits):
+    """Seeded random shapes: group sizes on both sides of the shared-pass limit (8), odd batch and head counts, contexts
+    from one token to several splits, ragged lengths (some sequences empty), both code widths."""
+    import torch
+    _say(f"attn random {i}: B={B} Hq={Hq} Hkv={Hkv} T={T} bits={bits}")
+    Q, K, V, lens = wa.draw(B, Hq, Hkv, T, seed=1000 + i, min_len=0)
+    if B > 2:
+        lens[1] = 0
+    cache = tm.tm_kv_create(B, Hkv, T, bits)
+    tm.tm_kv_append(cache, _dev(np.ascontiguousarray(K.transpose(0, 2, 1, 3))), _dev(np.ascontiguousarray(V.transpose(0, 2, 1, 3))),
+                    torch.zeros(B, dtype=torch.int32, device="cuda"))
+    O = torch.full((B, Hq, 128), float("nan"), dtype=torch.float16, device="cuda")
+    scale = 1.0 / np.sqrt(128.0)
+    tm.tm_attn_decode(_dev(Q), cache, _dev(lens), O, scale, max_len=int(max(lens.max(), 1)))
+    torch.cuda.synchronize()
+    O = O.cpu().numpy()
+    some = lens > 0                                          # the oracle defines attention over at least one token
+    assert not O[~some].any()                                # an empty sequence gets zeros
+    kq, vq = oa.kv_quantise(K[some], bits), oa.kv_quantise(V[some], bits)
+    Oref = oa.attn_decode(Q[some], *kq, *vq, lens[some], scale)
+    ok, worst, fro = _close(O[some], Oref)
+    assert ok, (worst, fro)
+    cache.close()
