@@ -708,6 +708,7 @@ __device__ __forceinline__ void store_out4(uint16_t* O, int b, int q_heads, int 
 
 // grid (kv heads, batch, splits); 256 threads.  Partial layout per (b, h, split): m[16], l[16], out[128][16] floats.
 constexpr int kPartialFloats = 32 + kHeadDim * 16;
+constexpr int kMergeHere = 8;            // splits the last-arriving CTA merges itself (all their loads in flight at once)
 
 template <int BITS, bool PACK>
 __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))) void attn_decode_kernel(AttnCache kv, const uint16_t* __restrict__ Q,
@@ -889,12 +890,12 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))) voi
     }
     __syncthreads();
     if (!s_last) return;
-    // at most four splits come here: all their loads are issued before the first use (the loop is unrolled and a
+    // at most kMergeHere splits come here: all their loads are issued before the first use (the loop is unrolled and a
     // missing split reads split 0 again with a factor of zero)
     const float* base = kv.partial + (size_t)bh * splits * kPartialFloats;
-    float ms[4], ls[4], vals[4][2][4];
+    float ms[kMergeHere], ls[kMergeHere], vals[kMergeHere][2][4];
 #pragma unroll
-    for (int sp = 0; sp < 4; ++sp) {
+    for (int sp = 0; sp < kMergeHere; ++sp) {
         const float* ps = base + (size_t)(sp < splits ? sp : 0) * kPartialFloats;
         ms[sp] = ld_partial(ps + c);
         ls[sp] = ld_partial(ps + 16 + c);
@@ -905,11 +906,11 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))) voi
     }
     float Mg = kNegBig;
 #pragma unroll
-    for (int sp = 0; sp < 4; ++sp) Mg = fmaxf(Mg, sp < splits ? ms[sp] : kNegBig);
+    for (int sp = 0; sp < kMergeHere; ++sp) Mg = fmaxf(Mg, sp < splits ? ms[sp] : kNegBig);
     float Lg = 0.f;
     float o[2][4] = {{0.f, 0.f, 0.f, 0.f}, {0.f, 0.f, 0.f, 0.f}};
 #pragma unroll
-    for (int sp = 0; sp < 4; ++sp) {
+    for (int sp = 0; sp < kMergeHere; ++sp) {
         const float fs = sp < splits ? exp2f(ms[sp] - Mg) : 0.f;
         Lg += ls[sp] * fs;
 #pragma unroll
@@ -1030,10 +1031,11 @@ hipError_t launch_attn_decode(const AttnCache& kv, const uint16_t* Q, const int3
     splits = (nblk + bps - 1) / bps > 0 ? (nblk + bps - 1) / bps : 1;
     if (kv.heads > 65535 || kv.batch > 65535) return hipErrorInvalidValue;
     const float scale_log2e = scale * 1.4426950408889634f;
-    // up to four splits are merged by the CTA that finishes last (measured at two splits: 27.6 instead of 29.7 us at
-    // batch 32 x 2048); with eight that one CTA's chain of loads became the bottleneck (11.5 instead of 8.5 us at batch
-    // 1 x 2048), so more splits go to the merge kernel, which spreads a (sequence, head) over eight CTAs
-    const int merge_here = splits > 1 && splits <= 4;
+    // up to eight splits are merged by the CTA that finishes last, with all its loads in flight at once (two splits:
+    // 27.6 instead of 29.7 us at batch 32 x 2048; a loop over the splits, one load chain after the other, cost 11.5
+    // instead of 8.5 us at batch 1 x 2048); more splits go to the merge kernel, which spreads a (sequence, head) over
+    // eight CTAs
+    const int merge_here = splits > 1 && splits <= kMergeHere;
     const dim3 grid(kv.heads, kv.batch, splits);
     const bool pack = q_heads / kv.heads <= 8;               // both score tiles share one softmax pass
     if (kv.bits == 8 && pack)
