@@ -270,3 +270,55 @@ def test_attn_decode_random_shapes(tm, i, B, Hq, Hkv, T, bits):
     ok, worst, fro = _close(O[some], Oref)
     assert ok, (worst, fro)
     cache.close()
+
+
+@pytest.mark.parametrize("bits,T", [(8, 3000), (4, 3000), (8, 40000)])
+def test_attn_hip_graph_replay_matches_eager(tm, bits, T):
+    """A decoding step - append of the newest token, then attention over split contexts (merged in the kernel through
+    the arrival counters at 3000 tokens, by the merge kernel at 40000) - allocates nothing and leaves its counters at
+    zero, so it can be captured into a HIP graph; every replay, with eager work between, reproduces the eager bits."""
+    import torch
+    B, Hq, Hkv = 2, 8, 2
+    _say(f"attn graph replay bits={bits} T={T}")
+    g = torch.Generator(device="cuda").manual_seed(7)
+    K = torch.randn((B, T, Hkv, 128), generator=g, device="cuda").to(torch.float16)
+    V = torch.randn((B, T, Hkv, 128), generator=g, device="cuda").to(torch.float16)
+    Q = torch.randn((B, Hq, 128), generator=g, device="cuda").to(torch.float16)
+    cache = tm.tm_kv_create(B, Hkv, T, bits)
+    zero = torch.zeros(B, dtype=torch.int32, device="cuda")
+    tm.tm_kv_append(cache, K[:, :T - 1].contiguous(), V[:, :T - 1].contiguous(), zero)
+    last_k, last_v = K[:, T - 1:].contiguous(), V[:, T - 1:].contiguous()
+    pos = torch.full((B,), T - 1, dtype=torch.int32, device="cuda")
+    lens = torch.tensor([T, T - 700], dtype=torch.int32, device="cuda")
+
+    def step(out):
+        tm.tm_kv_append(cache, last_k, last_v, pos)
+        tm.tm_attn_decode(Q, cache, lens, out, 0.09, max_len=T)
+
+    O_eager = torch.empty((B, Hq, 128), dtype=torch.float16, device="cuda")
+    step(O_eager)
+    torch.cuda.synchronize()
+    O_graph = torch.empty_like(O_eager)
+    stream = torch.cuda.Stream()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.stream(stream):
+        with torch.cuda.graph(graph, stream=stream):
+            step(O_graph)
+            step(O_graph)
+    for rep in range(3):
+        O_graph.fill_(float("nan"))
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        assert torch.equal(O_graph.view(torch.int16), O_eager.view(torch.int16)), f"replay {rep}"
+        O2 = torch.empty_like(O_eager)
+        step(O2)                                             # eager work between replays
+        torch.cuda.synchronize()
+        assert torch.equal(O2.view(torch.int16), O_eager.view(torch.int16))
+    # and the eager result is the right one (sampled against the oracle on the first sequence)
+    Ks = K[:1].permute(0, 2, 1, 3).contiguous().cpu().numpy()
+    Vs = V[:1].permute(0, 2, 1, 3).contiguous().cpu().numpy()
+    Oref = oa.attn_decode(Q[:1].cpu().numpy(), *oa.kv_quantise(Ks, bits), *oa.kv_quantise(Vs, bits), np.array([T]), 0.09)
+    ok, worst, fro = _close(O_eager[:1].cpu().numpy(), Oref)
+    assert ok, (worst, fro)
+    cache.close()
