@@ -168,3 +168,24 @@ def test_grouped_gemm_with_fused_activation(tm, oracle, E, K, N, g, counts, vari
     group.close()
     for p in dev:
         p.close()
+
+
+@pytest.mark.parametrize("K,N,g,symmetric", [(256, 64, 128, False), (384, 416, 32, False), (1024, 2080 * 2, 64, True)])
+def test_gate_up_pack_is_the_column_interleave_bit_for_bit(tm, oracle, K, N, g, symmetric):
+    """The packed buffer of a gate/up handle holds kernel column 2j = gate column j and 2j + 1 = up column N/2 + j:
+    undone by the oracle's inverse of the packed layout and compared with the input codes, scales and zero-points."""
+    rng = np.random.default_rng(K + N)
+    q = rng.integers(0, 16, (K, N), dtype=np.uint8)
+    s = rng.uniform(0.001, 0.02, (K // g, N)).astype(np.float16)
+    z = rng.integers(0, 16, (K // g, N)).astype(np.float16)
+    fused = tm.tm_pack_w4_gate_up(gu.to_dev(wl.pack_interchange(q)), gu.to_dev(s), None if symmetric else gu.to_dev(z), K, N, g)
+    wbuf, szbuf = tm.tm_packed_raw(fused)
+    q2, s2, z2 = oracle.unpack_packed(wbuf, szbuf, K, N, g)
+    src = np.empty(N, np.int64)
+    src[0::2] = np.arange(N // 2)
+    src[1::2] = N // 2 + np.arange(N // 2)
+    assert np.array_equal(q2, q[:, src])
+    assert np.array_equal(s2.view(np.uint16), s[:, src].view(np.uint16))
+    want_z = np.full_like(z, 8.0) if symmetric else z
+    assert np.array_equal(z2.view(np.uint16), want_z[:, src].view(np.uint16))
+    fused.close()
