@@ -37,8 +37,11 @@ def _random_problem(seed, M, K, N, g):
 
 # ------------------------------------------------------------------ packing: bit-exact
 
+# small and ragged shapes, then the weight matrix of every benchmark configuration (11008 rows = 86 packed units,
+# the one unit count that is not a power of two)
 PACK_SHAPES = [(128, 16, 128), (384, 80, 64), (256, 48, 32), (512, 512, 128), (1152, 272, 128),
-               (4096, 4096, 128), (8192, 8192, 64)]
+               (4096, 4096, 128), (4096, 12288, 128), (4096, 22016, 128), (11008, 4096, 128), (8192, 28672, 128),
+               (8192, 8192, 64)]
 
 
 @pytest.mark.parametrize("K,N,g", PACK_SHAPES)
@@ -47,7 +50,7 @@ def test_pack_bit_exact_against_oracle_unpack(tm, oracle, K, N, g):
     rng = np.random.default_rng(K * 7 + N)
     q = rng.integers(0, 16, (K, N), dtype=np.uint8)
     # position codes in a second pass so that every nibble slot is distinguished
-    kk, nn = np.meshgrid(np.arange(K), np.arange(N), indexing="ij")
+    kk, nn = np.arange(K, dtype=np.int32)[:, None], np.arange(N, dtype=np.int32)[None, :]
     for qq in (q, ((kk * 5 + nn * 3 + (kk >> 3) + (nn >> 4)) & 15).astype(np.uint8)):
         s = rng.uniform(0.001, 0.02, (K // g, N)).astype(np.float16)
         z = rng.integers(0, 16, (K // g, N)).astype(np.float16)
@@ -327,6 +330,14 @@ def test_edge_cases(tm, oracle):
 
 # ------------------------------------------------------------------ GEMM: the benchmark configurations
 
+def _plan_tile(plan):
+    """(rows, columns) of the output tile one CTA of the planned kernel owns, read from the variant's name
+    ("tile128x256", "skinny16x48"); a decode strip is dealt in 16-column tiles, so 16 columns is its granule."""
+    kind, dims = ("tile", plan["name"][4:]) if plan["name"].startswith("tile") else ("skinny", plan["name"][6:])
+    bm, bn = (int(v) for v in dims.split("x"))
+    return bm, (bn if kind == "tile" else 16)
+
+
 def _check_case(tm, oracle, case, d=None, packed=None, full_limit=2.5e10):
     d = d or wl.make(case)
     own = packed is None
@@ -336,19 +347,29 @@ def _check_case(tm, oracle, case, d=None, packed=None, full_limit=2.5e10):
     _say(f"{case.name}: M={case.M} K={case.K} N={case.N} g={case.group} plan={plan}")
     Y = gu.gemm(packed, X)
     assert not np.isnan(Y).any()
+    # same launch again: the reduction over K splits and wave sets has a fixed order, so the bits must repeat
+    Y_again = gu.gemm(packed, X)
+    assert np.array_equal(Y.view(np.uint16), Y_again.view(np.uint16)), (case.name, "not run-to-run identical")
     work = float(case.M) * case.K * case.N
     if work <= full_limit:
         Yref = oracle.gemm(X, d["q"], d["s"], d["z"], case.group)
         ok, worst, fro = acceptance(Y, Yref)
         assert ok, (case.name, worst, fro)
     else:
-        # sampled outputs: a few complete rows spread over the M tiles, and complete columns spread over N tiles
+        # Sampled outputs that still meet EVERY output tile of the planned kernel (and with it every K split, since
+        # an output sums over all of K): one complete row through each row of tiles and one complete column through
+        # each column of tiles, at a random place inside the tile, plus the four edges.  A tile written to the wrong
+        # place, or not at all, therefore fails whichever tile it is.
+        bm, bn = _plan_tile(plan)
         rng = np.random.default_rng(1)
-        rows = np.unique(np.concatenate([[0, case.M - 1], rng.integers(0, case.M, 6)]))
+        starts = np.arange(0, case.M, bm)
+        rows = np.unique(np.concatenate([[0, case.M - 1], starts + rng.integers(0, np.minimum(bm, case.M - starts))]))
         Yref_rows = oracle.gemm(X[rows], d["q"], d["s"], d["z"], case.group)
         ok, worst, fro = acceptance(Y[rows], Yref_rows)
         assert ok, (case.name, "rows", worst, fro)
-        cols = np.unique(np.concatenate([[0, case.N - 1], rng.integers(0, case.N, 6)]))
+        starts = np.arange(0, case.N, bn)
+        cols = np.unique(np.concatenate([[0, case.N - 1], starts + rng.integers(0, np.minimum(bn, case.N - starts))]))
+        _say(f"   sampled: {rows.size} rows (one per {bm}-row tile), {cols.size} columns (one per {bn}-column tile)")
         ms = np.repeat(np.arange(case.M), cols.size)
         ns = np.tile(cols, case.M)
         Yref_cols = oracle.gemm_sampled(X, d["q"], d["s"], d["z"], case.group, ms, ns)
