@@ -188,6 +188,21 @@ TM_API tm_packed_w4* tm_pack_w4_gate_up(const uint32_t* qweight, const uint16_t*
 TM_API int tm_gemm_w4a16_ws(const uint16_t* X, const tm_packed_w4* packed, uint16_t* Y, int M,
                             void* workspace, size_t workspace_bytes, tm_stream stream);
 
+/*
+ * tm_gemm_w4a16 for callers that cannot allocate device memory or let a library do so on their behalf: code under HIP
+ * graph capture, tight serving loops, harnesses that forbid hipMalloc.  Same kernels, same plan and bit-identical
+ * results; the split-K arrival counters and partial sums live in a fixed array inside the library's device image
+ * (64 KiB of counters + 8 MiB of partial sums per GPU, held until the process ends) instead of the workspace that
+ * tm_pack_w4 allocates.  The call itself allocates and frees nothing and never synchronises.  A plan whose partial
+ * sums (split_k * M * N * 4 bytes; for activation-order handles plus M * K * 2 bytes of regrouped activations) exceed
+ * the 8 MiB is refused with TM_EINVAL and a message that names both sizes; nothing is launched then.  All calls on one
+ * GPU share that GPU's array: calls that overlap in time on one GPU (two streams, two threads) race and must be
+ * serialised by the caller.  The first call on a device clears the counters with a small kernel on `stream`; every call
+ * returns them to zero, so the array is ready for the next call whatever its shape.  X, Y, M, stream, errors: as
+ * tm_gemm_w4a16.
+ */
+TM_API int tm_gemm_w4a16_static(const uint16_t* X, const tm_packed_w4* packed, uint16_t* Y, int M, tm_stream stream);
+
 /* Workspace bytes the plan for this (packed, M) needs (0 is never returned for M > 0; 0 on error or M == 0). */
 TM_API size_t tm_gemm_workspace_bytes(const tm_packed_w4* packed, int M);
 

@@ -78,6 +78,8 @@ def load_library():
     lib.tm_pack_w4_layout.argtypes = [vp, vp, vp, i, i, i, i, vp]
     lib.tm_gemm_w4a16.restype = i
     lib.tm_gemm_w4a16.argtypes = [vp, vp, vp, i, vp]
+    lib.tm_gemm_w4a16_static.restype = i
+    lib.tm_gemm_w4a16_static.argtypes = [vp, vp, vp, i, vp]
     lib.tm_gemm_w4a16_ex.restype = i
     lib.tm_gemm_w4a16_ex.argtypes = [vp, vp, vp, i, c.POINTER(TmEpilogue), vp]
     lib.tm_pack_w4_gate_up.restype = vp
@@ -333,6 +335,19 @@ def tm_gemm_w4a16(X, packed: PackedW4, Y, stream=None):
         return Y
     _check(load_library().tm_gemm_w4a16(_dev_ptr(X, torch.float16, "X"), packed.handle,
                                         _dev_ptr(Y, torch.float16, "Y"), M, _stream_ptr(stream)))
+    return Y
+
+
+def tm_gemm_w4a16_static(X, packed: PackedW4, Y, stream=None):
+    """tm_gemm_w4a16 through the library's fixed scratch array: the call allocates nothing (see include/tm_w4.h)."""
+    import torch
+    M = X.shape[0]
+    if X.dim() != 2 or X.shape[1] != packed.K or tuple(Y.shape) != (M, packed.N):
+        raise ValueError("X/Y shapes do not match the packed weight")
+    if M == 0:
+        return Y
+    _check(load_library().tm_gemm_w4a16_static(_dev_ptr(X, torch.float16, "X"), packed.handle,
+                                               _dev_ptr(Y, torch.float16, "Y"), M, _stream_ptr(stream)))
     return Y
 
 

@@ -20,6 +20,9 @@ constexpr size_t kPartialBudget = 32u << 20;          // bytes of fp32 partial s
 constexpr size_t kWorkspaceBytes = kCounterBytes + kPartialBudget;
 constexpr size_t kXpermBytes = 32u << 20;             // activations regrouped for activation-order handles
 constexpr int kMaxDevices = 16;
+// split-K partial sums the allocation-free entry point can hold (tm_gemm_w4a16_static)
+constexpr size_t kStaticPartialBytes = 8u << 20;
+constexpr size_t kStaticBytes = kCounterBytes + kStaticPartialBytes;
 
 thread_local char g_error[512] = "";
 
@@ -42,6 +45,7 @@ struct DeviceState {
     bool supported = false;
     void* workspace = nullptr;
     void* xperm = nullptr;     // kXpermBytes, allocated with the first activation-order handle
+    void* static_ws = nullptr; // this device's copy of the static scratch array, resolved at the first static call
     int num_cu = 256;
 };
 DeviceState g_dev[kMaxDevices];
@@ -82,6 +86,9 @@ int ensure_workspace(int dev)
     hipError_t e = hipMalloc(&ws, kWorkspaceBytes);
     if (e != hipSuccess) return fail_hip(e, "hipMalloc(workspace)");
     e = hipMemset(ws, 0, kCounterBytes);
+    // The clear runs on the null stream, which a caller's non-blocking stream does not wait for: finish it here, once,
+    // so that the first GEMM on any stream finds the counters at zero.
+    if (e == hipSuccess) e = hipStreamSynchronize(nullptr);
     if (e != hipSuccess) {
         (void)hipFree(ws);
         return fail_hip(e, "hipMemset(workspace)");
@@ -92,6 +99,21 @@ int ensure_workspace(int dev)
 
 }  // namespace
 
+}  // namespace tmw4
+
+// Scratch of the allocation-free entry point: the split-K arrival counters followed by the fp32 partial sums, one copy
+// per GPU, held for the life of the process.  In host code this name is only a handle for hipGetSymbolAddress; the
+// device address it yields (kept per device in DeviceState::static_ws) is what kernels and fills receive.
+static __device__ __align__(256) unsigned char scratch[tmw4::kStaticBytes];
+
+namespace tmw4 {
+namespace {
+__global__ void clear_words_kernel(uint32_t* p, int n)
+{
+    const int i = blockIdx.x * blockDim.x + threadIdx.x;
+    if (i < n) p[i] = 0u;
+}
+}  // namespace
 }  // namespace tmw4
 
 struct tm_packed_w4 {
@@ -803,6 +825,42 @@ int tm_gemm_w4a16_ws(const uint16_t* X, const tm_packed_w4* packed, uint16_t* Y,
                      size_t workspace_bytes, tm_stream stream)
 {
     return run_gemm(X, packed, Y, M, workspace, workspace_bytes, false, (hipStream_t)stream);
+}
+
+int tm_gemm_w4a16_static(const uint16_t* X, const tm_packed_w4* packed, uint16_t* Y, int M, tm_stream stream)
+{
+    if (!valid(packed)) return fail(TM_EINVAL, "packed handle is null or invalid");
+    if (M < 0 || M >= (1 << 24)) return fail(TM_EINVAL, "M = %d out of range", M);
+    if (M == 0) return TM_OK;
+    int dev;
+    int rc = check_device(&dev);
+    if (rc != TM_OK) return rc;
+    if (dev != packed->device) return fail(TM_EINVAL, "handle belongs to device %d, current device is %d", packed->device, dev);
+    size_t need = make_plan(packed, M, g_dev[dev].num_cu).ws_bytes;
+    if (packed->perm) need = align256(need) + (size_t)M * packed->K * 2;
+    if (need > kStaticBytes)
+        return fail(TM_EINVAL, "this call needs %zu bytes of scratch and the static buffer holds %zu: use tm_gemm_w4a16 or "
+                    "tm_gemm_w4a16_ws", need, (size_t)kStaticBytes);
+    void* ws;
+    {
+        std::lock_guard<std::mutex> lock(g_mutex);
+        DeviceState& d = g_dev[dev];
+        if (!d.static_ws) {
+            // first call on this device: its copy of the array has its own address; the counters must start at zero
+            // (a fill kernel on the caller's stream, ordered before the GEMM that follows; no memset node, so the call
+            // stays capturable)
+            void* ptr = nullptr;
+            hipError_t e = hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch));
+            if (e != hipSuccess || !ptr) return fail_hip(e, "hipGetSymbolAddress(scratch)");
+            hipLaunchKernelGGL(clear_words_kernel, dim3(kMaxCounters / 256), dim3(256), 0, (hipStream_t)stream,
+                               (uint32_t*)ptr, kMaxCounters);
+            e = hipGetLastError();
+            if (e != hipSuccess) return fail_hip(e, "clearing the static scratch");
+            d.static_ws = ptr;
+        }
+        ws = d.static_ws;
+    }
+    return run_gemm(X, packed, Y, M, ws, kStaticBytes, false, (hipStream_t)stream);
 }
 
 size_t tm_gemm_workspace_bytes(const tm_packed_w4* packed, int M)
