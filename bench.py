@@ -35,7 +35,10 @@ WORKLOADS = {
     "mlp_decode": [("cfg3_gate_up_M64", (1, 16, 32, 64)), ("cfg3_down_M64", (1, 16, 32, 64))],
     "prefill": [("cfg4_prefill_70b_mlp", (4096,))],
     "sweep5": [("cfg5_sweep_M1024", (1, 2, 4, 8, 32, 128, 256, 1024))],
+    "tiny": [("cfg1_tiny_M1", (1,))],
 }
+# the five configurations of the benchmark, in order, as workload names
+CONFIG_WORKLOADS = ("tiny", "decode", "mlp_decode", "prefill", "sweep5")
 
 
 def log(*a):
@@ -136,9 +139,13 @@ def per_shape_table(tm, torch, wl, layers, iters=100, warmup=10, use_graph=True)
             B = wl.algorithmic_bytes(M, c.K, c.N, c.group)
             F = wl.flops(M, c.K, c.N)
             plan = tm.tm_get_plan(L.packed[0], M)
+            hbm_frac, mfma_frac = B / t / 1e9 / HBM_PEAK_GBPS, F / t / 1e12 / MFMA_F16_PEAK_TFLOPS
+            # the roofline that binds: HBM while the ideal HBM time exceeds the ideal matrix-core time (M below about 84)
+            bound = "hbm" if B / (HBM_PEAK_GBPS * 1e9) >= F / (MFMA_F16_PEAK_TFLOPS * 1e12) else "mfma"
             rows.append({"layer": c.name.rsplit("_M", 1)[0], "M": M, "K": c.K, "N": c.N, "group": c.group,
                          "us": t * 1e6, "GBps": B / t / 1e9, "TFLOPs": F / t / 1e12,
-                         "hbm_frac": B / t / 1e9 / HBM_PEAK_GBPS, "mfma_frac": F / t / 1e12 / MFMA_F16_PEAK_TFLOPS,
+                         "hbm_frac": hbm_frac, "mfma_frac": mfma_frac, "bound": bound,
+                         "frac": hbm_frac if bound == "hbm" else mfma_frac,
                          "variant": plan["name"], "split_k": plan["split_k"], "grid": plan["grid"]})
     return rows
 
@@ -579,6 +586,82 @@ def attn_cpu_baseline(B=1, T=2048, q_heads=32, kv_heads=8):
             "sample": f"{n} decode steps of batch {B} x context {T}, {q_heads}/{kv_heads} heads (numpy fp64)"}
 
 
+# Launch shapes of the read-only stream tried for the ceiling: (CTAs per CU, threads per CTA, 128-bit loads in flight per
+# thread, flags: 1 = non-temporal, 2 = contiguous slice per CTA).  The short list holds the shapes that won at some byte
+# count in the full sweep (`--workload ceiling --ceiling-full`); grid 0 = one load per thread, the plain tm_bench_read shape.
+CEILING_SHORTLIST = [(0, 256, 1, 0), (1, 1024, 8, 1), (1, 1024, 4, 3), (2, 512, 4, 1), (2, 1024, 2, 1), (4, 256, 4, 1),
+                     (4, 512, 2, 1), (8, 256, 2, 1), (8, 256, 1, 1), (16, 256, 1, 1)]
+
+
+def ceiling_sizes(wl):
+    """(label, packed weight + scale/zero bytes) of every distinct weight matrix of the benchmark configurations."""
+    out, seen = [], set()
+    for name in ("decode", "mlp_decode", "sweep5", "prefill"):
+        for cn, _ in WORKLOADS[name]:
+            c = wl.case_by_name(cn)
+            b = c.K * c.N // 2 + 4 * c.K * c.N // c.group
+            if b not in seen:
+                seen.add(b)
+                out.append((cn.rsplit("_M", 1)[0], b))
+    return out
+
+
+def ceiling_table(tm, torch, sizes, iters=100, full=False, num_cu=256):
+    """Read-only streaming ceiling at given byte counts: the achievable HBM read rate of a kernel that does nothing but
+    load that many bytes once, timed exactly like the GEMM rows (HIP-graph replay, every launch on a different region of
+    a buffer of more than 512 MB, so nothing is found in L2 or the Infinity Cache).  Returns, per size, the best shape."""
+    total = ROTATE_BYTES + max(b for _, b in sizes) + (64 << 20)
+    pool = torch.empty(total, dtype=torch.uint8, device="cuda")
+    pool.random_(0, 256)
+    sink = torch.zeros(16, dtype=torch.int32, device="cuda")
+    base = pool.data_ptr()
+    if full:
+        shapes = [(0, 256, 1, 0)] + [(g, b, u, f) for g in (1, 2, 4, 8, 16, 32) for b in (256, 512, 1024) for u in (1, 2, 4, 8, 16)
+                                     for f in (0, 1, 2, 3) if g * b <= 8192 and g * b * u <= 32768]
+    else:
+        shapes = CEILING_SHORTLIST
+    rows = []
+    for label, nbytes in sizes:
+        nbytes = nbytes // 256 * 256
+        span = -(-nbytes // 4096) * 4096
+        slots = max(2, (total - span) // span)
+        best = None
+        for g, block, unroll, flags in shapes:
+            grid = g * num_cu if g else -(-nbytes // 16 // block)
+            turn = [0]
+
+            def step():
+                off = (turn[0] % slots) * span
+                turn[0] += 1
+                tm.tm_bench_read_shape(base + off, nbytes, sink, grid, block, unroll, flags)
+
+            ev_ms, _ = time_steps(torch, step, iters, 5, graph_steps=iters)
+            us = ev_ms / iters * 1e3
+            row = {"bytes": nbytes, "like": label, "grid": grid, "block": block, "unroll": unroll,
+                   "nontemporal": bool(flags & 1), "chunked": bool(flags & 2), "us": us, "GBps": nbytes / us / 1e3}
+            if full:
+                rows.append(row)
+            if best is None or us < best["us"]:
+                best = row
+            if g == 0:
+                plain = row
+        best = dict(best, plain_read_us=plain["us"], plain_read_GBps=plain["GBps"], best=True)
+        rows.append(best)
+        log(f"read ceiling at {nbytes / 1e6:7.2f} MB ({label:14s}): best {best['us']:7.2f} us = {best['GBps']:6.0f} GB/s "
+            f"({100 * best['GBps'] / HBM_PEAK_GBPS:4.1f} % of peak) with grid {best['grid']} x {best['block']}, {best['unroll']} in flight"
+            f"{', nt' if best['nontemporal'] else ''}{', chunked' if best['chunked'] else ''};  one load per thread: {plain['us']:7.2f} us")
+    del pool
+    torch.cuda.empty_cache()
+    return rows
+
+
+def empty_launch_us(tm, torch, iters=200):
+    """Cost of a kernel node that does no work (a 16-byte read), same graph-replay timing: the floor under every row."""
+    buf = torch.zeros(64, dtype=torch.int32, device="cuda")
+    ev_ms, _ = time_steps(torch, lambda: tm.tm_bench_read_shape(buf.data_ptr(), 16, buf, 1, 64, 1, 0), iters, 5, graph_steps=iters)
+    return ev_ms / iters * 1e3
+
+
 def cpu_baseline(wl, layers, min_s=5.0, budget_s=25.0):
     """The oracle as it stands, timed on this host's cores over the same workload: whole passes over every
     (layer, M) pair are repeated until at least `min_s` seconds have been spent; a single GEMM too large for
@@ -614,12 +697,15 @@ def main():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=200)
     ap.add_argument("--warmup", type=int, default=20)
-    ap.add_argument("--workload", default="decode", choices=sorted(WORKLOADS) + ["sweep", "copy", "companion", "pack", "moe", "w8", "attn", "epilogue", "layer"])
+    ap.add_argument("--workload", default="decode", choices=sorted(WORKLOADS) + ["sweep", "ceiling", "copy", "companion", "pack", "moe", "w8", "attn", "epilogue", "layer"])
     ap.add_argument("--sweep-out", default=None, help="with --workload sweep: write the per-shape table here (JSON)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--ceiling-full", action="store_true", help="with --workload ceiling: sweep every launch shape, not the short list")
     ap.add_argument("--attn-companion", action="store_true",
                     help="attn workload: also time the framework's fused attention over an fp16 cache on the same shapes")
     ap.add_argument("--no-prefill", action="store_true", help="skip the prefill companion measurement")
+    ap.add_argument("--no-per-config", action="store_true", help="skip the per-(configuration, M) rows of the default line")
+    ap.add_argument("--no-ceiling", action="store_true", help="skip the read-only streaming ceiling beside the roofline")
     ap.add_argument("--companion-workloads", default="decode,mlp_decode,sweep5,prefill",
                     help="workloads the fp16 x fp16 companion covers (comma-separated; one of them makes a short profiler run)")
     ap.add_argument("--eager", action="store_true", help="launch every kernel from the host instead of replaying HIP graphs")
@@ -652,6 +738,17 @@ def main():
         print(json.dumps({"metric": "plain copy (counter calibration)", "bytes_read": n, "bytes_written": n,
                           "steps": args.steps, "ms_per_step": ev_ms / args.steps,
                           "GBps_read_plus_write": 2 * n / (ev_ms / args.steps * 1e-3) / 1e9}))
+        return
+
+    if args.workload == "ceiling":
+        rows = ceiling_table(tm, torch, ceiling_sizes(wl), iters=min(args.steps, 100), full=args.ceiling_full)
+        empty = empty_launch_us(tm, torch)
+        log(f"empty kernel node: {empty:.2f} us")
+        if args.sweep_out:
+            os.makedirs(os.path.dirname(os.path.abspath(args.sweep_out)), exist_ok=True)
+            json.dump(rows, open(args.sweep_out, "w"), indent=1)
+        print(json.dumps({"metric": "read-only streaming ceiling at the byte counts of the benchmark's weight matrices", "workload": "ceiling",
+                          "n_gpus": 1, "empty_launch_us": empty, "rows": [r for r in rows if r.get("best")]}))
         return
 
     if args.workload == "pack":
@@ -843,6 +940,18 @@ def main():
     traffic_file = os.path.join(ROOT, "profiles", "traffic.json")
     if os.path.exists(traffic_file):
         roofline["traffic"] = json.load(open(traffic_file)).get(args.workload)
+        roofline["traffic_source"] = ("profiles/traffic.json: FETCH_SIZE x 2.0 + WRITE_SIZE from rocprofv3 --pmc runs of this command, "
+                                      "copied there by hand from the summaries under profiles/; a stored figure, not observed in this run")
+    if hbm_bound and not args.no_ceiling:
+        # the read-only stream at the dominant layer's byte count, timed the same way: what this chip's memory system
+        # delivers to a kernel that only loads those bytes, beside the 8 TB/s of the data sheet
+        c = dom.case
+        ceil = ceiling_table(tm, torch, [(c.name.rsplit("_M", 1)[0], c.K * c.N // 2 + 4 * c.K * c.N // c.group)], iters=100)[-1]
+        roofline["read_ceiling_GBps"] = ceil["GBps"]
+        roofline["read_ceiling_us"] = ceil["us"]
+        roofline["read_ceiling_shape"] = {k: ceil[k] for k in ("grid", "block", "unroll", "nontemporal", "chunked")}
+        roofline["frac_of_read_ceiling"] = ach / ceil["GBps"]
+        roofline["empty_launch_us"] = empty_launch_us(tm, torch)
 
     out = {
         "metric": METRIC, "value": gbps if hbm_bound else tflops, "unit": "GB/s" if hbm_bound else "TFLOP/s",
@@ -859,7 +968,25 @@ def main():
         "roofline": roofline,
     }
 
-    if args.workload == "decode" and not args.no_prefill:
+    if args.workload == "decode" and not args.no_per_config:
+        # one timed row per (configuration, M) of all five configurations, same timing method
+        table = []
+        for ci, name in enumerate(CONFIG_WORKLOADS):
+            ls = layers if name == "decode" else [Layer(tm, torch, wl, cn, Ms) for cn, Ms in WORKLOADS[name]]
+            rows = per_shape_table(tm, torch, wl, ls, iters=(20 if name == "prefill" else 100), warmup=3)
+            for r in rows:
+                r["config"] = ci + 1
+            table += rows
+            if name != "decode":
+                del ls
+                torch.cuda.empty_cache()
+        out["per_config"] = table
+        pr = [r for r in table if r["config"] == 4][0]
+        out["prefill"] = {"workload": "configs[3]: M=4096, K=8192, N=28672, group=128", "ms": pr["us"] * 1e-3, "TFLOPs": pr["TFLOPs"],
+                          "roofline": {"bound": "mfma", "achieved": pr["TFLOPs"], "peak": MFMA_F16_PEAK_TFLOPS,
+                                       "unit": "TFLOP/s", "frac": pr["mfma_frac"]},
+                          "kernel": pr["variant"]}
+    elif args.workload == "decode" and not args.no_prefill:
         PL = Layer(tm, torch, wl, *WORKLOADS["prefill"][0])
         pms, _ = time_steps(torch, lambda: PL.launch(tm, 4096), 20, 5, graph_steps=5)
         t = pms / 20 * 1e-3

@@ -285,6 +285,16 @@ TM_API const char* tm_variant_name(int variant);
  */
 TM_API int tm_bench_copy(void* dst, const void* src, size_t bytes, tm_stream stream);
 TM_API int tm_bench_read(const void* src, size_t bytes, void* sink, tm_stream stream);
+/*
+ * The same read-only stream in a chosen launch shape, to find the best streaming shape at a given byte count (the
+ * ceiling a weight-streaming kernel of that size can be held against): `grid` CTAs of `block` threads (a multiple of 64,
+ * at most 1024), `unroll` (1, 2, 4, 8 or 16) 128-bit loads in flight per thread; flags bit 0 = non-temporal loads,
+ * bit 1 = every CTA reads one contiguous slice of the buffer instead of interleaving with the others.
+ */
+#define TM_READ_NONTEMPORAL 1
+#define TM_READ_CHUNKED 2
+TM_API int tm_bench_read_shape(const void* src, size_t bytes, void* sink, int grid, int block, int unroll, int flags,
+                               tm_stream stream);
 
 TM_API const char* tm_last_error(void);
 TM_API const char* tm_version(void);

@@ -15,8 +15,10 @@ import subprocess
 import numpy as np
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
-_SRC = os.path.join(_HERE, "oracle_w4.c")
-_LIB = os.path.join(_HERE, "liboracle_w4.so")
+# ORACLE_W4_SRC names another copy of the C source to build and load instead (beside which its library is put): the
+# mutation and sanitizer tests run the pins against a deliberately damaged or an instrumented oracle that way.
+_SRC = os.environ.get("ORACLE_W4_SRC") or os.path.join(_HERE, "oracle_w4.c")
+_LIB = os.path.join(os.path.dirname(os.path.abspath(_SRC)), "liboracle_w4.so")
 _lib = None
 
 

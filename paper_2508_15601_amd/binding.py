@@ -8,8 +8,7 @@ import ctypes
 import os
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
-# TM_W4_LIB names another build of the same library (A/B comparisons of kernel variants); default: the in-tree build.
-_LIB_PATH = os.environ.get("TM_W4_LIB") or os.path.join(_HERE, "libtm_w4.so")
+_LIB_PATH = os.path.join(_HERE, "libtm_w4.so")
 _lib = None
 
 TM_OK = 0
@@ -108,6 +107,8 @@ def load_library():
     lib.tm_bench_copy.argtypes = [vp, vp, sz, vp]
     lib.tm_bench_read.restype = i
     lib.tm_bench_read.argtypes = [vp, sz, vp, vp]
+    lib.tm_bench_read_shape.restype = i
+    lib.tm_bench_read_shape.argtypes = [vp, sz, vp, i, i, i, i, vp]
     lib.tm_last_error.restype = c.c_char_p
     lib.tm_last_error.argtypes = []
     lib.tm_version.restype = c.c_char_p
@@ -463,6 +464,12 @@ def tm_bench_read(src, sink, stream=None):
     nbytes = src.numel() * src.element_size()
     _check(load_library().tm_bench_read(ctypes.c_void_p(src.data_ptr()), nbytes, ctypes.c_void_p(sink.data_ptr()),
                                         _stream_ptr(stream)))
+
+
+def tm_bench_read_shape(src_ptr: int, nbytes: int, sink, grid: int, block: int, unroll: int, flags: int = 0, stream=None):
+    """Read-only stream over nbytes at the raw device address src_ptr in the given launch shape (see include/tm_w4.h)."""
+    _check(load_library().tm_bench_read_shape(ctypes.c_void_p(src_ptr), nbytes, ctypes.c_void_p(sink.data_ptr()), grid, block,
+                                              unroll, flags, _stream_ptr(stream)))
 
 
 # ------------------------------------------------------------------ attention over a quantised KV cache (tm_attn.h)

@@ -21,18 +21,18 @@ FLAGS = ["-O3", "-std=c++17", "--offload-arch=gfx950", "-fPIC", "-fvisibility=hi
          "-Wall", "-Wno-unused-function", "-Wno-unused-command-line-argument"]
 
 
-def build(verbose: bool = False, jobs: int = 4, defines=(), out: str = LIB) -> str:
-    """Compile every translation unit and link the shared library.  Always rebuilds.
-    `defines` (e.g. ["-DTM_TILE_PITCH=88"]) and `out` build an experimental variant beside the default library."""
+def build(verbose: bool = False, jobs: int = 4) -> str:
+    """Compile every translation unit and link the shared library.  Always rebuilds."""
     hipcc = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
-    objdir = os.path.join(PKG, "_build") if out == LIB else os.path.join(PKG, "_build", "variant_" + os.path.basename(out))
+    out = LIB
+    objdir = os.path.join(PKG, "_build")
     os.makedirs(objdir, exist_ok=True)
     procs = []
     objs = []
     for src in SOURCES:
         obj = os.path.join(objdir, src.replace(".hip", ".o"))
         objs.append(obj)
-        cmd = [hipcc, *FLAGS, *defines, *EXTRA.get(src, []), "-I", os.path.join(ROOT, "include"), "-I", CSRC, "-c", os.path.join(CSRC, src), "-o", obj]
+        cmd = [hipcc, *FLAGS, *EXTRA.get(src, []), "-I", os.path.join(ROOT, "include"), "-I", CSRC, "-c", os.path.join(CSRC, src), "-o", obj]
         if verbose:
             print(" ".join(cmd), flush=True)
         procs.append((src, subprocess.Popen(cmd, stdout=subprocess.PIPE, stderr=subprocess.STDOUT, text=True)))
@@ -59,11 +59,4 @@ def _drain(procs):
 
 
 if __name__ == "__main__":
-    # python build.py [-DNAME=VALUE ...] [--out path/to/variant.so]
-    args = sys.argv[1:]
-    out = LIB
-    if "--out" in args:
-        i = args.index("--out")
-        out = os.path.abspath(args[i + 1])
-        del args[i:i + 2]
-    print(build(verbose=True, defines=args, out=out))
+    print(build(verbose=True))

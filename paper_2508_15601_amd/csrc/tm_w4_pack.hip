@@ -188,6 +188,40 @@ __global__ __launch_bounds__(256) void read16_kernel(const u32x4* __restrict__ s
     if (v == 0x9E3779B9u) *sink = v;               // practically never taken; keeps the loads alive
 }
 
+// The read-only stream in a chosen launch shape, for finding the best streaming shape of this chip at a given byte
+// count: every thread keeps U 128-bit loads in flight per round; CHUNKED gives each CTA one contiguous slice of the
+// buffer (as a weight-streaming CTA has) instead of interleaving the CTAs; NT uses the non-temporal load policy.
+template <int U, bool NT, bool CHUNKED>
+__global__ void read_shape_kernel(const u32x4* __restrict__ src, size_t n16, uint32_t* sink)
+{
+    const size_t threads = blockDim.x;
+    size_t begin, end, stride;
+    if (CHUNKED) {
+        const size_t per = (n16 + gridDim.x - 1) / gridDim.x;
+        begin = (size_t)blockIdx.x * per + threadIdx.x;
+        end = min(n16, (size_t)(blockIdx.x + 1) * per);
+        stride = threads;
+    } else {
+        begin = (size_t)blockIdx.x * threads + threadIdx.x;
+        end = n16;
+        stride = (size_t)gridDim.x * threads;
+    }
+    u32x4 acc = {0, 0, 0, 0};
+    for (size_t i = begin; i < end; i += stride * U) {
+        u32x4 v[U];
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+            const size_t at = i + u * stride;
+            v[u] = u32x4{0, 0, 0, 0};
+            if (at < end) v[u] = NT ? __builtin_nontemporal_load(src + at) : src[at];
+        }
+#pragma unroll
+        for (int u = 0; u < U; ++u) acc ^= v[u];
+    }
+    uint32_t x = acc.x ^ acc.y ^ acc.z ^ acc.w;
+    if (x == 0x9E3779B9u) *sink = x;               // practically never taken; keeps the loads alive
+}
+
 // Activation-order checkpoints: row i of the matrix that gets packed is row perm[i] of the checkpoint, so that the
 // rows of one K-group become consecutive.  N-major words move whole; a K-major word is rebuilt from eight rows.
 __global__ __launch_bounds__(256) void permute_rows_kernel(const uint32_t* __restrict__ in, const int32_t* __restrict__ perm,
@@ -363,6 +397,35 @@ hipError_t launch_read(const void* src, size_t bytes, void* sink, hipStream_t st
     unsigned blocks = (unsigned)((n16 + 255) / 256 < 8192 ? (n16 + 255) / 256 : 8192);
     if (blocks == 0) return hipSuccess;
     hipLaunchKernelGGL(read16_kernel, dim3(blocks), dim3(256), 0, stream, (const u32x4*)src, n16, (uint32_t*)sink);
+    return hipGetLastError();
+}
+
+template <int U>
+static void launch_read_u(const void* src, size_t n16, void* sink, unsigned grid, unsigned block, int flags, hipStream_t stream)
+{
+    const u32x4* p = (const u32x4*)src;
+    uint32_t* sk = (uint32_t*)sink;
+    switch (flags & 3) {
+        case 0: hipLaunchKernelGGL((read_shape_kernel<U, false, false>), dim3(grid), dim3(block), 0, stream, p, n16, sk); break;
+        case 1: hipLaunchKernelGGL((read_shape_kernel<U, true, false>), dim3(grid), dim3(block), 0, stream, p, n16, sk); break;
+        case 2: hipLaunchKernelGGL((read_shape_kernel<U, false, true>), dim3(grid), dim3(block), 0, stream, p, n16, sk); break;
+        default: hipLaunchKernelGGL((read_shape_kernel<U, true, true>), dim3(grid), dim3(block), 0, stream, p, n16, sk); break;
+    }
+}
+
+hipError_t launch_read_shape(const void* src, size_t bytes, void* sink, unsigned grid, unsigned block, int unroll, int flags,
+                             hipStream_t stream)
+{
+    const size_t n16 = bytes / 16;
+    if (n16 == 0) return hipSuccess;
+    switch (unroll) {
+        case 1: launch_read_u<1>(src, n16, sink, grid, block, flags, stream); break;
+        case 2: launch_read_u<2>(src, n16, sink, grid, block, flags, stream); break;
+        case 4: launch_read_u<4>(src, n16, sink, grid, block, flags, stream); break;
+        case 8: launch_read_u<8>(src, n16, sink, grid, block, flags, stream); break;
+        case 16: launch_read_u<16>(src, n16, sink, grid, block, flags, stream); break;
+        default: return hipErrorInvalidValue;
+    }
     return hipGetLastError();
 }
 
