@@ -438,6 +438,10 @@ int run_gemm(const uint16_t* X, const tm_packed_w4* h, uint16_t* Y, int M, void*
     p.tiles_m = pl.tiles_m;
     p.tiles_n = pl.tiles_n;
     p.strips = pl.strips;
+    if (pl.strips > 0) {
+        p.strip_base = p.NT / pl.strips;
+        p.strip_rem = p.NT % pl.strips;
+    }
     p.ldy = ldy;
     if (epi) {
         p.bias = epi->bias;
@@ -784,6 +788,8 @@ static int run_grouped(const uint16_t* X, const tm_expert_group* group, const in
     gp.NT = group->N / kUnitN;
     gp.G = group->K / group->group;
     gp.strips = strips;
+    gp.strip_base = gp.NT / strips;
+    gp.strip_rem = gp.NT % strips;
     gp.total_rows = total_rows;
     gp.experts = group->experts;
     gp.act = act == TM_ACT_SILU_MUL ? 1 : 0;

@@ -33,7 +33,9 @@ struct GemmParams {
     int split;                // split-K factor (>= 1)
     int ku_per_split;         // k-units per split (ceil)
     int tiles_m, tiles_n;     // tile kernel only
-    int strips;               // skinny kernel only: strip s owns tiles [s*NT/strips, (s+1)*NT/strips)
+    int strips;               // skinny kernel only: the NT column tiles are dealt into this many strips
+    int strip_base, strip_rem;  // NT / strips and NT % strips: strip s owns strip_base tiles (+1 if s < strip_rem),
+                                // starting at tile s * strip_base + min(s, strip_rem)
     // Fused epilogue (all optional; 0 / null = plain Y = X * dequant(W)).
     const uint16_t* bias;     // fp16 [N] in the caller's column order, added to the sums
     const uint16_t* residual; // fp16 [M][ldy], added last
@@ -49,6 +51,7 @@ struct GroupedParams {
     const uint64_t* table;      // per expert: address of the packed weights, address of the scale/zero words
     const int32_t* offsets;     // [experts + 1], ascending
     int K, N, KU, NT, G, strips, total_rows, experts;
+    int strip_base, strip_rem;  // as in GemmParams
     int tiles_n, mtiles;        // tile kernels: column tiles, and the upper bound of row tiles over all experts
     int act;                    // 1: gate/up experts, Y[r][n/2] = silu(gate) * up, row stride N/2
 };

@@ -154,10 +154,10 @@ __device__ __forceinline__ void compute_stage(const Stage<TM, NTW, GU, T>& st, f
 // TM 16-row tiles, NTW 16-column tiles per wave, GPU K-groups per 128-row unit, D register stages per wave,
 // MAXW the largest CTA (in waves) this instantiation is launched with.
 //
-// One CTA's work on one GEMM: strip and K slice follow from `bx`, the CTA's index among p.strips * p.split.
+// One CTA's work on one GEMM: column strip `strip` of p.strips, K slice `sk` of p.split.
 // red is [waves][NTW*4][64] floats of LDS (one 16 x 16*NTW fp32 tile per wave), s_last one LDS word.
 template <int TM, int NTW, int GPU, int D, int BITS>
-__device__ __forceinline__ void skinny_body(const GemmParams& p, const int bx, float* __restrict__ red,
+__device__ __forceinline__ void skinny_body(const GemmParams& p, const int strip, const int sk, float* __restrict__ red,
                                             uint32_t& s_last)
 {
     const int tid = threadIdx.x;
@@ -165,11 +165,10 @@ __device__ __forceinline__ void skinny_body(const GemmParams& p, const int bx, f
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);     // wave-uniform by construction
     const int waves = blockDim.x >> 6;
     // The NT column tiles are dealt evenly into p.strips strips (widths differ by at most one tile), so that a
-    // shape whose tile count is not a multiple of the CU count still loads every CU almost equally.
-    const int strip = bx % p.strips;
-    const int sk = bx / p.strips;
-    const int nt0 = (int)(((long)strip * p.NT) / p.strips);
-    const int ntw = (int)(((long)(strip + 1) * p.NT) / p.strips) - nt0;     // <= NTW (host guarantees)
+    // shape whose tile count is not a multiple of the CU count still loads every CU almost equally.  Quotient and
+    // remainder come from the host: a division here would stand between every wave and its first load.
+    const int nt0 = strip * p.strip_base + min(strip, p.strip_rem);
+    const int ntw = p.strip_base + (strip < p.strip_rem ? 1 : 0);          // <= NTW (host guarantees)
     const int ku0 = sk * p.ku_per_split;
     const int ku1 = min(p.KU, ku0 + p.ku_per_split);
 
@@ -286,7 +285,7 @@ __global__ __launch_bounds__(MAXW * 64) void skinny_kernel(GemmParams p)
 {
     extern __shared__ float red[];
     __shared__ uint32_t s_last;
-    skinny_body<TM, NTW, GPU, D, BITS>(p, blockIdx.x, red, s_last);
+    skinny_body<TM, NTW, GPU, D, BITS>(p, blockIdx.x, blockIdx.y, red, s_last);
 }
 
 // Grouped form for mixture-of-experts layers (the paper's evaluation covers MoE models, Sec. 5.1; their expert GEMMs
@@ -352,12 +351,14 @@ __global__ __launch_bounds__(MAXW * 64) void skinny_grouped_kernel(GroupedParams
     p.split = 1;
     p.ku_per_split = gp.KU;
     p.strips = gp.strips;
+    p.strip_base = gp.strip_base;
+    p.strip_rem = gp.strip_rem;
     for (int m0 = r0; m0 < r1; m0 += 16 * TM) {
         if (m0 != r0) __syncthreads();             // the previous chunk's reads of red are done
         p.X = gp.X + (size_t)m0 * gp.K;
         p.Y = gp.Y + (size_t)m0 * p.ldy;
         p.M = min(16 * TM, r1 - m0);
-        skinny_body<TM, NTW, GPU, D, 4>(p, blockIdx.x, red, s_last);
+        skinny_body<TM, NTW, GPU, D, 4>(p, blockIdx.x, 0, red, s_last);
     }
 }
 
@@ -366,8 +367,8 @@ __global__ __launch_bounds__(MAXW * 64) void skinny_grouped_kernel(GroupedParams
 template <int TM, int NTW, int D128, int DSMALL, int MAXW, int BITS = 4>
 hipError_t launch_cfg(const GemmParams& p, const Plan& plan, int group, hipStream_t stream)
 {
-    dim3 grid(plan.grid), block(plan.block);
-    if (plan.block > MAXW * 64) return hipErrorInvalidValue;
+    dim3 grid(plan.strips, plan.split), block(plan.block);           // x: column strip, y: K slice
+    if (plan.block > MAXW * 64 || plan.split > 65535) return hipErrorInvalidValue;
     size_t lds = (size_t)(plan.block / 64) * NTW * 4 * 64 * sizeof(float);
     switch (group) {
         case 128: hipLaunchKernelGGL((skinny_kernel<TM, NTW, 1, D128, MAXW, BITS>), grid, block, lds, stream, p); break;
