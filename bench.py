@@ -901,7 +901,7 @@ def main():
 
     # graph long enough that every layer walks through all of its packed copies at least once per replay
     want = max(-(-L.copies // len(L.Ms)) for L in layers)
-    graph_steps = 0 if args.eager else pick_graph_steps(args.steps, max(want, 1))
+    graph_steps = 0 if args.eager else pick_graph_steps(args.steps, max(want, 100 // launches_per_step, 1))
     ev_ms, wall_ms = time_steps(torch, step, args.steps, args.warmup, graph_steps=graph_steps)
     ms_per_step = ev_ms / args.steps
     B = sum(wl.algorithmic_bytes(M, L.case.K, L.case.N, L.case.group) for L in layers for M in L.Ms)
@@ -914,7 +914,8 @@ def main():
     # steps with the same launch mode, so that its average launch duration can be set against the profiler's.
     dom = max(layers, key=lambda L: L.case.K * L.case.N)
     dom_steps = args.steps
-    dom_graph = 0 if args.eager else pick_graph_steps(dom_steps, max(-(-dom.copies // len(dom.Ms)), 1))
+    # (graphs of about a hundred launches, so that the cost of starting a replay is spread as thinly as in the step above)
+    dom_graph = 0 if args.eager else pick_graph_steps(dom_steps, max(-(-dom.copies // len(dom.Ms)), 100 // len(dom.Ms), 1))
 
     def dom_step():
         for M in dom.Ms:

@@ -266,6 +266,13 @@ TM_API int tm_packed_raw(const tm_packed_w4* packed, const void** weights, size_
  * variant -1 / split_k 0 restore automatic selection.  tm_variant_name(-1..) returns "" past the last variant.
  */
 TM_API int tm_get_plan(const tm_packed_w4* packed, int M, int* variant, int* split_k, int* grid, int* block);
+/*
+ * The decode shapes (M <= 16, 4-bit codes) have two forms of their kernels: the one-shot form, in which a wave requests
+ * its whole share of the weight stream at once and keeps its rows of X in LDS (taken when the share fits the registers
+ * and the rows fit LDS), and the ring-buffered form.  Returns the packed units per wave of the one-shot form the plan for
+ * M rows uses, 0 if the plan uses the ring-buffered form or another kernel family, a negative status on error.
+ */
+TM_API int tm_get_plan_units_per_wave(const tm_packed_w4* packed, int M);
 TM_API int tm_set_variant(int variant, int split_k);
 /*
  * Two more launch parameters for sweeps, 0 = automatic.
@@ -273,7 +280,9 @@ TM_API int tm_set_variant(int variant, int split_k);
  *                16 for the tile kernels, whose CTAs hold one, two or four sets of waves, each set multiplying its
  *                own slice of every K stage (a value a variant is not built with falls back to its default);
  *   stage_steps  MFMA steps of 32 K-rows per pipeline stage and wave set of the tile kernels: 2, 4 or 8 (a request
- *                the shape or the variant's register budget cannot honour falls back to the nearest valid depth).
+ *                the shape or the variant's register budget cannot honour falls back to the nearest valid depth);
+ *                1 leaves the tile kernels alone and makes the decode shapes (M <= 16) take the ring-buffered form of
+ *                their kernels where they would take the one-shot form.
  */
 TM_API int tm_set_launch(int waves, int stage_steps);
 TM_API const char* tm_variant_name(int variant);

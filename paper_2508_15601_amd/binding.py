@@ -97,6 +97,8 @@ def load_library():
     lib.tm_packed_raw.argtypes = [vp, c.POINTER(vp), c.POINTER(sz), c.POINTER(vp), c.POINTER(sz)]
     lib.tm_get_plan.restype = i
     lib.tm_get_plan.argtypes = [vp, i, c.POINTER(i), c.POINTER(i), c.POINTER(i), c.POINTER(i)]
+    lib.tm_get_plan_units_per_wave.restype = i
+    lib.tm_get_plan_units_per_wave.argtypes = [vp, i]
     lib.tm_set_variant.restype = i
     lib.tm_set_variant.argtypes = [i, i]
     lib.tm_set_launch.restype = i
@@ -438,8 +440,11 @@ def tm_get_plan(packed: PackedW4, M: int) -> dict:
     lib = load_library()
     v, s, g, b = ctypes.c_int(), ctypes.c_int(), ctypes.c_int(), ctypes.c_int()
     _check(lib.tm_get_plan(packed.handle, M, ctypes.byref(v), ctypes.byref(s), ctypes.byref(g), ctypes.byref(b)))
+    upw = lib.tm_get_plan_units_per_wave(packed.handle, M)
+    if upw < 0:
+        raise TmError(upw, tm_last_error())
     return {"variant": v.value, "name": lib.tm_variant_name(v.value).decode(), "split_k": s.value,
-            "grid": g.value, "block": b.value}
+            "grid": g.value, "block": b.value, "one_shot_units_per_wave": upw}
 
 
 def tm_set_variant(variant: int = -1, split_k: int = 0):

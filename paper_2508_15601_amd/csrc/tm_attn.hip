@@ -415,11 +415,6 @@ struct BlockRegs {
     u32x4 v[4];         // 64 value bytes: eight 16-row tiles x the lane's eight tokens
 };
 
-__device__ __forceinline__ __amdgpu_buffer_rsrc_t make_rsrc(const void* p, uint32_t bytes)
-{
-    return __builtin_amdgcn_make_buffer_rsrc(const_cast<void*>(p), 0, (int)bytes, 0x00020000);
-}
-
 // Descriptors of one (sequence, head): its K blocks, V blocks and scale/zero words, each cut off after the last block
 // of the context.  A load past that end returns zeros without touching memory, which lets the pipeline issue its loads
 // unconditionally (the surplus ones at the end of a wave's range cost nothing).

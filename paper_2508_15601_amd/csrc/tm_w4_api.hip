@@ -89,9 +89,10 @@ int ensure_workspace(int dev)
     // The clear runs on the null stream, which a caller's non-blocking stream does not wait for: finish it here, once,
     // so that the first GEMM on any stream finds the counters at zero.
     if (e == hipSuccess) e = hipStreamSynchronize(nullptr);
+    if (e == hipSuccess) e = stream_setup();       // per-kernel LDS limits of the one-shot decode kernels
     if (e != hipSuccess) {
         (void)hipFree(ws);
-        return fail_hip(e, "hipMemset(workspace)");
+        return fail_hip(e, "workspace set-up");
     }
     d.workspace = ws;
     return TM_OK;
@@ -302,7 +303,7 @@ Plan make_plan(const tm_packed_w4* h, int M, int num_cu)
         // they take stages one or two packed units deep; tall tiles keep 64-deep stages (smaller LDS, two CTAs/CU).
         const int bm = tile_bm(variant);
         int steps = bm <= 64 ? 8 : (variant == kTile128x128 ? 4 : 2);
-        if (g_force_stage > 0) steps = g_force_stage;
+        if (g_force_stage > 1) steps = g_force_stage;
         if (bm > 128 || variant == kTile128x512) steps = 2;
         if (bm == 128 && steps == 8) steps = 4;
         if (variant == kTile128x256) steps = 2;      // register budget of the 128 x 256 tile
@@ -311,7 +312,7 @@ Plan make_plan(const tm_packed_w4* h, int M, int num_cu)
         int kg = 1;
         if (tile_bn(variant) == 96) kg = 2;
         else if (bm <= 64 && (long)pl.tiles_m * pl.tiles_n * split < 2L * num_cu) kg = 4;
-        if (bm <= 64 && kg > 1 && g_force_stage == 0) steps = 4;
+        if (bm <= 64 && kg > 1 && g_force_stage <= 1) steps = 4;
         if (g_force_waves >= 4) kg = g_force_waves * 64 / tile_threads(variant);
         if (!tile_has_kgroups(variant, kg)) kg = tile_has_kgroups(variant, 1) ? 1 : 4;
         if (w8) {                                  // the 8-bit tiles are built in one depth each, one wave set
@@ -340,6 +341,24 @@ Plan make_plan(const tm_packed_w4* h, int M, int num_cu)
     }
     split = ceil_div(KU, pl.ku_per_split);         // drop empty splits
     pl.split = split;
+    pl.stream_ni = 0;
+    if (is_skinny(variant) && skinny_rows(variant) == 16 && h->bits == 4 && g_force_stage != 1 && M <= 16) {
+        // The one-shot form of the decode kernels, where it is built for the strip width and the K slice and the
+        // slice of X fits into LDS: CTAs of 16 waves if a wave's share of the slice fits its registers, else 8.
+        const int widest = ceil_div(NT, pl.strips);
+        int mp_log = 0;
+        while ((1 << mp_log) < M) ++mp_log;
+        const int tries[2] = {g_force_waves >= 8 ? g_force_waves : 16, g_force_waves >= 8 ? g_force_waves : 8};
+        for (int w : tries) {
+            const int ni = stream_units_per_wave(widest, h->group, pl.ku_per_split, w);
+            int red_off;
+            if (ni > 0 && stream_lds(ni, mp_log, widest, w, &red_off) <= kStreamLdsBudget) {
+                pl.stream_ni = ni;
+                pl.block = (unsigned)w * 64;
+                break;
+            }
+        }
+    }
     if (is_skinny(variant)) {
         pl.grid = (unsigned)(pl.tiles_n * split);
     } else {
@@ -443,6 +462,7 @@ int run_gemm(const uint16_t* X, const tm_packed_w4* h, uint16_t* Y, int M, void*
         p.strip_rem = p.NT % pl.strips;
     }
     p.ldy = ldy;
+    while ((1 << p.mp_log) < M) ++p.mp_log;
     if (epi) {
         p.bias = epi->bias;
         p.residual = epi->residual;
@@ -452,6 +472,7 @@ int run_gemm(const uint16_t* X, const tm_packed_w4* h, uint16_t* Y, int M, void*
     hipError_t e = h->bits == 8 ? (!is_skinny(pl.variant) ? launch_tile_8bit(p, pl, h->group, h->fp8, stream)
                                    : h->fp8 ? launch_skinny_f8(p, pl, h->group, stream)
                                             : launch_skinny_w8(p, pl, h->group, stream))
+                   : pl.stream_ni > 0      ? launch_stream(p, pl, h->group, stream)
                    : is_skinny(pl.variant) ? launch_skinny(p, pl, h->group, stream)
                                            : launch_tile(p, pl, h->group, stream);
     if (e != hipSuccess) return fail_hip(e, "kernel launch");
@@ -943,6 +964,15 @@ int tm_get_plan(const tm_packed_w4* packed, int M, int* variant, int* split_k, i
     return TM_OK;
 }
 
+int tm_get_plan_units_per_wave(const tm_packed_w4* packed, int M)
+{
+    if (!valid(packed)) return fail(TM_EINVAL, "packed handle is null or invalid");
+    if (M <= 0 || M >= (1 << 24)) return fail(TM_EINVAL, "M = %d out of range", M);
+    int dev = packed->device;
+    int cu = (dev >= 0 && dev < kMaxDevices && g_dev[dev].checked) ? g_dev[dev].num_cu : 256;
+    return make_plan(packed, M, cu).stream_ni;
+}
+
 int tm_set_variant(int variant, int split_k)
 {
     if (variant < -1 || variant >= kNumVariants) return fail(TM_EINVAL, "unknown variant %d", variant);
@@ -955,8 +985,8 @@ int tm_set_variant(int variant, int split_k)
 int tm_set_launch(int waves, int stage_steps)
 {
     if (waves != 0 && waves != 4 && waves != 8 && waves != 16) return fail(TM_EINVAL, "waves must be 0 (auto), 4, 8 or 16");
-    if (stage_steps != 0 && stage_steps != 2 && stage_steps != 4 && stage_steps != 8)
-        return fail(TM_EINVAL, "stage_steps must be 0 (auto), 2, 4 or 8");
+    if (stage_steps != 0 && stage_steps != 1 && stage_steps != 2 && stage_steps != 4 && stage_steps != 8)
+        return fail(TM_EINVAL, "stage_steps must be 0 (auto), 1, 2, 4 or 8");
     g_force_waves = waves;
     g_force_stage = stage_steps;
     return TM_OK;

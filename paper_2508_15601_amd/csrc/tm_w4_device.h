@@ -42,6 +42,8 @@ struct GemmParams {
     int act;                  // 1: columns are interleaved (gate, up) pairs and Y[m][n/2] = silu(gate) * up
     int ldy;                  // row stride of Y and residual: N, or N/2 with act
     int epi;                  // 0: none of the three is set (the stores take the plain path on one test)
+    int mp_log;               // stream kernels: log2 of M rounded up to a power of two (rows of an X region in LDS)
+    int red_off;              // stream kernels: LDS byte offset of the reduction tiles; 0 = they reuse the X regions
 };
 
 // Grouped (mixture-of-experts) launch: rows [offsets[e], offsets[e+1]) of X and Y belong to expert e.
@@ -66,6 +68,15 @@ struct AttnCache {
     int batch, heads, cap, max_splits;
     int bits;            // 8 or 4 bits per code; cap is a multiple of 256 / bits
 };
+
+// Raw buffer descriptor over `bytes` bytes at p (gfx9 layout: 32-bit data format, no swizzle, no stride).  Loads
+// through it take a per-lane 32-bit byte offset plus a scalar one; lanes whose offset falls outside return zero
+// without touching memory.
+__device__ __forceinline__ __amdgpu_buffer_rsrc_t make_rsrc(const void* p, uint32_t bytes)
+{
+    return __builtin_amdgcn_make_buffer_rsrc(const_cast<void*>(p), 0, (int)bytes, 0x00020000);
+}
+constexpr int kNonTemporalLoad = 2;      // cache-policy bit of a buffer load: streamed once, do not keep
 
 __device__ __forceinline__ f16x2 as_f16x2(uint32_t u) { return __builtin_bit_cast(f16x2, u); }
 

@@ -65,6 +65,7 @@ struct Plan {
     int strips;           // skinny kernels: number of column strips the 16-column tiles are dealt into
     int stage_steps;      // tile kernels: MFMA steps (32 rows of K each) per pipeline stage and wave set: 2, 4 or 8
     int kgroups;          // tile kernels: sets of four waves per CTA, each taking its own slice of every stage
+    int stream_ni;        // decode kernels: > 0 = the one-shot kernel with this many packed units per wave
     int tiles_m, tiles_n;
     unsigned grid;
     unsigned block;
@@ -92,6 +93,11 @@ hipError_t launch_kv_append(const AttnCache& kv, const uint16_t* Kn, const uint1
 hipError_t launch_attn_decode(const AttnCache& kv, const uint16_t* Q, const int32_t* lens, uint16_t* O, int q_heads,
                               float scale, int max_len, int num_cu, hipStream_t stream);
 hipError_t launch_skinny(const GemmParams& p, const Plan& plan, int group, hipStream_t stream);
+hipError_t launch_stream(const GemmParams& p, const Plan& plan, int group, hipStream_t stream);
+hipError_t stream_setup();                                             // once per device, outside any capture
+int stream_units_per_wave(int ntw, int group, int kus, int waves);     // 0: no one-shot kernel is built for this shape
+constexpr size_t kStreamLdsBudget = 156 * 1024;                       // of the 160 KiB of a CU
+size_t stream_lds(int ni, int mp_log, int ntw, int waves, int* red_off);
 hipError_t launch_skinny_w8(const GemmParams& p, const Plan& plan, int group, hipStream_t stream);
 hipError_t launch_skinny_f8(const GemmParams& p, const Plan& plan, int group, hipStream_t stream);
 hipError_t launch_skinny_grouped(const GroupedParams& gp, int variant, int experts, int group, hipStream_t stream);

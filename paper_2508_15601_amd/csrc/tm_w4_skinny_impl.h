@@ -151,66 +151,17 @@ __device__ __forceinline__ void compute_stage(const Stage<TM, NTW, GU, T>& st, f
     }
 }
 
-// TM 16-row tiles, NTW 16-column tiles per wave, GPU K-groups per 128-row unit, D register stages per wave,
-// MAXW the largest CTA (in waves) this instantiation is launched with.
-//
-// One CTA's work on one GEMM: column strip `strip` of p.strips, K slice `sk` of p.split.
+// The waves of a CTA hold partial tiles of the same outputs (each wave multiplied its own units of K): add them through
+// LDS and store, or, when K is also split across CTAs, hand the CTA's sums to the split-K merge.
 // red is [waves][NTW*4][64] floats of LDS (one 16 x 16*NTW fp32 tile per wave), s_last one LDS word.
-template <int TM, int NTW, int GPU, int D, int BITS>
-__device__ __forceinline__ void skinny_body(const GemmParams& p, const int strip, const int sk, float* __restrict__ red,
-                                            uint32_t& s_last)
+template <int TM, int NTW>
+__device__ __forceinline__ void skinny_reduce(const GemmParams& p, f32x4 (&acc)[TM][NTW], const int strip, const int sk,
+                                              const int nt0, const int ntw, float* __restrict__ red, uint32_t& s_last)
 {
     const int tid = threadIdx.x;
     const int lane = tid & 63;
-    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);     // wave-uniform by construction
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int waves = blockDim.x >> 6;
-    // The NT column tiles are dealt evenly into p.strips strips (widths differ by at most one tile), so that a
-    // shape whose tile count is not a multiple of the CU count still loads every CU almost equally.  Quotient and
-    // remainder come from the host: a division here would stand between every wave and its first load.
-    const int nt0 = strip * p.strip_base + min(strip, p.strip_rem);
-    const int ntw = p.strip_base + (strip < p.strip_rem ? 1 : 0);          // <= NTW (host guarantees)
-    const int ku0 = sk * p.ku_per_split;
-    const int ku1 = min(p.KU, ku0 + p.ku_per_split);
-
-    const Magic mg = make_magic();
-    LaneOffsets<TM> lo;
-    lo.w = lane * 16;
-    lo.sz = (lane & 15) * 4;
-#pragma unroll
-    for (int mt = 0; mt < TM; ++mt) {
-        const int row = mt * 16 + (lane & 15);
-        lo.live[mt] = row < p.M;
-        lo.x[mt] = (uint32_t)row * (uint32_t)p.K * 2u + (lane >> 4) * 16;
-    }
-
-    f32x4 acc[TM][NTW];
-#pragma unroll
-    for (int mt = 0; mt < TM; ++mt)
-#pragma unroll
-        for (int j = 0; j < NTW; ++j) acc[mt][j] = f32x4{0.f, 0.f, 0.f, 0.f};
-
-    // Rolling prefetch (the memory pipeline of paper Sec. 4.3): a ring of D register stages; while the unit in
-    // stage r is converted and multiplied, the loads of the next D-1 units of this wave are in flight.
-    {
-        using US = UnitShape<BITS, GPU>;
-        Stage<TM, NTW, US::GU, US::T> st[D];
-        const int first = ku0 + wave;
-#pragma unroll
-        for (int r = 0; r < D - 1; ++r)
-            if (first + r * waves < ku1) load_stage<US::SZDIV>(st[r], p, lo, nt0, ntw, first + r * waves);
-        for (int base = first; base < ku1; base += D * waves) {
-#pragma unroll
-            for (int r = 0; r < D; ++r) {
-                const int cur = base + r * waves;
-                if (cur < ku1) {
-                    const int pre = cur + (D - 1) * waves;
-                    if (pre < ku1) load_stage<US::SZDIV>(st[(r + D - 1) % D], p, lo, nt0, ntw, pre);
-                    compute_stage<BITS>(st[r], acc, mg);
-                }
-            }
-        }
-    }
-
     // Reduce the waves' tiles through LDS, one 16-row tile at a time.  A wave stores its accumulator registers as
     // they are (register-major, 64 lanes contiguous), and the readers keep that shape: reader thread e owns
     // accumulator element (register e / 64, lane e % 64), so the 64 lanes of a reading wave fetch 64 consecutive
@@ -278,6 +229,69 @@ __device__ __forceinline__ void skinny_body(const GemmParams& p, const int strip
             if (tid == 0) __hip_atomic_store(&p.counters[strip], 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
         }
     }
+}
+
+// TM 16-row tiles, NTW 16-column tiles per wave, GPU K-groups per 128-row unit, D register stages per wave,
+// MAXW the largest CTA (in waves) this instantiation is launched with.
+//
+// One CTA's work on one GEMM: column strip `strip` of p.strips, K slice `sk` of p.split.
+// red is [waves][NTW*4][64] floats of LDS (one 16 x 16*NTW fp32 tile per wave), s_last one LDS word.
+template <int TM, int NTW, int GPU, int D, int BITS>
+__device__ __forceinline__ void skinny_body(const GemmParams& p, const int strip, const int sk, float* __restrict__ red,
+                                            uint32_t& s_last)
+{
+    const int tid = threadIdx.x;
+    const int lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);     // wave-uniform by construction
+    const int waves = blockDim.x >> 6;
+    // The NT column tiles are dealt evenly into p.strips strips (widths differ by at most one tile), so that a
+    // shape whose tile count is not a multiple of the CU count still loads every CU almost equally.  Quotient and
+    // remainder come from the host: a division here would stand between every wave and its first load.
+    const int nt0 = strip * p.strip_base + min(strip, p.strip_rem);
+    const int ntw = p.strip_base + (strip < p.strip_rem ? 1 : 0);          // <= NTW (host guarantees)
+    const int ku0 = sk * p.ku_per_split;
+    const int ku1 = min(p.KU, ku0 + p.ku_per_split);
+
+    const Magic mg = make_magic();
+    LaneOffsets<TM> lo;
+    lo.w = lane * 16;
+    lo.sz = (lane & 15) * 4;
+#pragma unroll
+    for (int mt = 0; mt < TM; ++mt) {
+        const int row = mt * 16 + (lane & 15);
+        lo.live[mt] = row < p.M;
+        lo.x[mt] = (uint32_t)row * (uint32_t)p.K * 2u + (lane >> 4) * 16;
+    }
+
+    f32x4 acc[TM][NTW];
+#pragma unroll
+    for (int mt = 0; mt < TM; ++mt)
+#pragma unroll
+        for (int j = 0; j < NTW; ++j) acc[mt][j] = f32x4{0.f, 0.f, 0.f, 0.f};
+
+    // Rolling prefetch (the memory pipeline of paper Sec. 4.3): a ring of D register stages; while the unit in
+    // stage r is converted and multiplied, the loads of the next D-1 units of this wave are in flight.
+    {
+        using US = UnitShape<BITS, GPU>;
+        Stage<TM, NTW, US::GU, US::T> st[D];
+        const int first = ku0 + wave;
+#pragma unroll
+        for (int r = 0; r < D - 1; ++r)
+            if (first + r * waves < ku1) load_stage<US::SZDIV>(st[r], p, lo, nt0, ntw, first + r * waves);
+        for (int base = first; base < ku1; base += D * waves) {
+#pragma unroll
+            for (int r = 0; r < D; ++r) {
+                const int cur = base + r * waves;
+                if (cur < ku1) {
+                    const int pre = cur + (D - 1) * waves;
+                    if (pre < ku1) load_stage<US::SZDIV>(st[(r + D - 1) % D], p, lo, nt0, ntw, pre);
+                    compute_stage<BITS>(st[r], acc, mg);
+                }
+            }
+        }
+    }
+
+    skinny_reduce<TM, NTW>(p, acc, strip, sk, nt0, ntw, red, s_last);
 }
 
 template <int TM, int NTW, int GPU, int D, int MAXW, int BITS = 4>

@@ -29,12 +29,6 @@ namespace {
 constexpr int kPanelN = 8;                 // output tiles per panel row (XCD-local rasterisation)
 
 
-// Raw buffer descriptor over `bytes` bytes at p (gfx9 layout: 32-bit data format, no swizzle, no stride).
-__device__ __forceinline__ __amdgpu_buffer_rsrc_t make_rsrc(const void* p, uint32_t bytes)
-{
-    return __builtin_amdgcn_make_buffer_rsrc(const_cast<void*>(p), 0, (int)bytes, 0x00020000);
-}
-
 // compile-time loop: f(std::integral_constant<int, I>{}) for I = B .. E-1
 template <int B, int E, class F>
 __device__ __forceinline__ void static_for(F&& f)

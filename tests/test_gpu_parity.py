@@ -235,6 +235,49 @@ def test_every_variant_and_split(tm, oracle, variant, split, waves, g, stage):
     assert np.array_equal(Y.view(np.uint16), Y2.view(np.uint16)), "split-K reduction must be run-to-run deterministic"
 
 
+# The decode shapes (M <= 16) have a one-shot and a ring-buffered form of their kernels: both forms of every strip width,
+# CTAs of 8 and 16 waves, K ranges that leave some waves a unit short, strips of two widths, K split across CTAs.
+@pytest.mark.parametrize("form", ["one_shot", "ring"])
+@pytest.mark.parametrize("variant", [0, 1, 14, 2, 15, 16])
+@pytest.mark.parametrize("M,K,N,g,waves,split", [(1, 1152, 336, 128, 16, 1), (5, 2048, 528, 64, 8, 1), (16, 1536, 1040, 32, 16, 2),
+                                                 (13, 4096, 272, 128, 16, 1), (8, 2560, 2064, 128, 8, 3), (16, 1024, 80, 64, 16, 1)])
+def test_decode_kernel_forms(tm, oracle, form, variant, M, K, N, g, waves, split):
+    d = _random_problem(variant * 31 + M + K, M, K, N, g)
+    packed = gu.pack(d, g)
+    tm.tm_set_variant(variant, split)
+    tm.tm_set_launch(waves, 1 if form == "ring" else 0)
+    try:
+        plan = tm.tm_get_plan(packed, M)
+        _say(f"decode form={form} variant={variant} M={M} K={K} N={N} g={g} waves={waves} split={split} plan={plan}")
+        assert plan["variant"] == variant
+        if form == "ring":
+            assert plan["one_shot_units_per_wave"] == 0
+        Y = gu.gemm(packed, d["X"])
+        Y2 = gu.gemm(packed, d["X"])
+    finally:
+        tm.tm_set_variant(-1, 0)
+        tm.tm_set_launch(0, 0)
+    ok, worst, fro = acceptance(Y, oracle.gemm(d["X"], d["q"], d["s"], d["z"], g))
+    assert ok, (plan, worst, fro)
+    assert np.array_equal(Y.view(np.uint16), Y2.view(np.uint16))
+    packed.close()
+
+
+def test_decode_configs_take_the_one_shot_form(tm):
+    """The benchmark's decode layers (M <= 16 at K = 4096 and 8192; K = 11008 at M = 1) run the one-shot kernels."""
+    import torch
+    for K, N, g, Ms in ((4096, 4096, 128, (1, 16)), (4096, 12288, 128, (1, 16)), (4096, 22016, 128, (1, 16)),
+                        (11008, 4096, 128, (1,)), (8192, 8192, 64, (1, 8))):
+        qw = torch.zeros((K, N // 8), dtype=torch.int32, device="cuda")
+        s = torch.ones((K // g, N), dtype=torch.float16, device="cuda")
+        packed = tm.tm_pack_w4(qw, s, None, K, N, g)
+        for M in Ms:
+            plan = tm.tm_get_plan(packed, M)
+            _say(f"decode plan K={K} N={N} M={M}: {plan}")
+            assert plan["one_shot_units_per_wave"] > 0, (K, N, M, plan)
+        packed.close()
+
+
 # (variant, waves per CTA): 128-column tiles with two or four sets of four waves, 96-column tiles with two or four
 # sets of two waves; the 128-row tile is built with two sets only
 WAVE_SETS = [(13, 8), (13, 16), (9, 8), (9, 16), (10, 8), (20, 4), (20, 8), (21, 4), (21, 8)]
