@@ -203,6 +203,15 @@ TM_API int tm_gemm_w4a16_ws(const uint16_t* X, const tm_packed_w4* packed, uint1
  */
 TM_API int tm_gemm_w4a16_static(const uint16_t* X, const tm_packed_w4* packed, uint16_t* Y, int M, tm_stream stream);
 
+/*
+ * Returns the split-K arrival counters of a workspace to zero (a small kernel on `stream`): of the caller's workspace, or,
+ * with workspace == NULL, of the library's own workspace and of the static scratch of tm_gemm_w4a16_static on the current
+ * device.  Every GEMM leaves the counters at zero, so this is needed only after a launch that did not run to completion
+ * (a device error, an aborted stream): counters left part-way would make a later call pick the wrong CTA as the last one.
+ * Must not overlap with a GEMM that uses the same workspace.
+ */
+TM_API int tm_reset_workspace(void* workspace, tm_stream stream);
+
 /* Workspace bytes the plan for this (packed, M) needs (0 is never returned for M > 0; 0 on error or M == 0). */
 TM_API size_t tm_gemm_workspace_bytes(const tm_packed_w4* packed, int M);
 
@@ -227,7 +236,9 @@ TM_API void tm_free_packed(tm_packed_w4* packed);
  * uses no workspace (K is not split across CTAs), results are bit-identical from run to run.  The kernel is chosen
  * from total_rows / num_experts (the per-expert counts are not known on the host): decode-sized loads run the decode
  * kernels (an expert with more rows than one pass takes, 16-64, is processed in several passes), prefill-sized
- * loads (about 64 rows per expert and more) run the CTA-tile kernels, which need total_rows * K < 2^31.
+ * loads (about 64 rows per expert and more) run the CTA-tile kernels, which need total_rows * K < 2^31.  The choice
+ * assumes a roughly balanced routing (mean load plus three standard deviations); under a heavily skewed one the result
+ * is still exact, but an expert with many times the average load is taken in passes that each stream its weights again.
  * total_rows == 0 is a successful no-op; total_rows < 2^24.
  */
 typedef struct tm_expert_group tm_expert_group;

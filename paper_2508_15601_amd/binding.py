@@ -85,6 +85,8 @@ def load_library():
     lib.tm_pack_w4_gate_up.argtypes = [vp, vp, vp, i, i, i, vp]
     lib.tm_gemm_w4a16_ws.restype = i
     lib.tm_gemm_w4a16_ws.argtypes = [vp, vp, vp, i, vp, sz, vp]
+    lib.tm_reset_workspace.restype = i
+    lib.tm_reset_workspace.argtypes = [vp, vp]
     lib.tm_gemm_workspace_bytes.restype = sz
     lib.tm_gemm_workspace_bytes.argtypes = [vp, i]
     lib.tm_free_packed.restype = None
@@ -401,6 +403,12 @@ def tm_gemm_w4a16_ws(X, packed: PackedW4, Y, workspace, stream=None):
                                            _dev_ptr(workspace, torch.uint8, "workspace"), workspace.numel(),
                                            _stream_ptr(stream)))
     return Y
+
+
+def tm_reset_workspace(workspace=None, stream=None):
+    """Zero the split-K arrival counters of `workspace` (None: of the library's own workspaces); see include/tm_w4.h."""
+    ptr = None if workspace is None else ctypes.c_void_p(workspace.data_ptr())
+    _check(load_library().tm_reset_workspace(ptr, _stream_ptr(stream)))
 
 
 def tm_gemm_workspace_bytes(packed: PackedW4, M: int) -> int:

@@ -890,6 +890,28 @@ int tm_gemm_w4a16_static(const uint16_t* X, const tm_packed_w4* packed, uint16_t
     return run_gemm(X, packed, Y, M, ws, kStaticBytes, false, (hipStream_t)stream);
 }
 
+int tm_reset_workspace(void* workspace, tm_stream stream)
+{
+    int dev;
+    int rc = check_device(&dev);
+    if (rc != TM_OK) return rc;
+    if (workspace && ((uintptr_t)workspace & 255)) return fail(TM_EINVAL, "workspace must be 256-byte aligned");
+    void* targets[2] = {workspace, nullptr};
+    if (!workspace) {
+        std::lock_guard<std::mutex> lock(g_mutex);
+        targets[0] = g_dev[dev].workspace;
+        targets[1] = g_dev[dev].static_ws;
+    }
+    for (void* t : targets) {
+        if (!t) continue;
+        hipLaunchKernelGGL(clear_words_kernel, dim3(kMaxCounters / 256), dim3(256), 0, (hipStream_t)stream, (uint32_t*)t,
+                           kMaxCounters);
+        hipError_t e = hipGetLastError();
+        if (e != hipSuccess) return fail_hip(e, "clearing the arrival counters");
+    }
+    return TM_OK;
+}
+
 size_t tm_gemm_workspace_bytes(const tm_packed_w4* packed, int M)
 {
     if (!valid(packed) || M <= 0 || M >= (1 << 24)) {

@@ -72,7 +72,9 @@ __device__ __forceinline__ void tile_body(const GemmParams& p, const int tile_m,
     // two X buffers, separate objects so that the compiler can tell a write into one from a read of the other;
     // after the K loop the first also carries the wave sets' partial tiles
     constexpr size_t kXsBytes = (size_t)BM * BKS * sizeof(uint16_t);
-    constexpr size_t kRedBytes = (size_t)(KG - 1) * NW * TM * TN * 64 * sizeof(f32x4);
+    // one wave set's partial tile; the sets' tiles meet pairwise (see the end of the K loop), as many at a time as fit
+    constexpr size_t kSetTileBytes = (size_t)NW * TM * TN * 64 * sizeof(f32x4);
+    constexpr size_t kRedBytes = KG > 1 ? kSetTileBytes : 0;
     __shared__ __attribute__((aligned(16))) unsigned char smem0[kXsBytes > kRedBytes ? kXsBytes : kRedBytes];
     __shared__ __attribute__((aligned(16))) unsigned char smem1[kXsBytes];
     __shared__ uint32_t s_last;
@@ -350,28 +352,43 @@ __device__ __forceinline__ void tile_body(const GemmParams& p, const int tile_m,
         }
     }
 
-    // The wave sets' partial tiles meet in LDS (the X buffers are free after the loop's last barrier); set 0 adds
-    // them in a fixed order and alone runs the epilogue.
+    // The wave sets' partial tiles meet in LDS (the X buffers are free after the loop's last barrier), pairwise: in
+    // each round the upper half of the remaining sets hands its tiles to the lower half (set s takes the tile of set
+    // s + half), as many tiles per pass as the first buffer holds.  A fixed tree, so the sum has a fixed order; set 0
+    // ends up with the total and alone runs the epilogue.
     bool writer = true;
     if constexpr (KG > 1) {
         f32x4* red = (f32x4*)smem0;
-        if (kg > 0) {
+        constexpr int kSetRegs = NW * TM * TN * 64;                    // f32x4 slots of one set's tile
+        constexpr int kCapRaw = (int)(sizeof(smem0) / kSetTileBytes);
+        static_for<0, 3>([&](auto R) {                                 // up to three halvings: KG = 2, 4 or 8
+            constexpr int active = KG >> decltype(R)::value;
+            if constexpr (active > 1) {
+                constexpr int half = active / 2;
+                constexpr int cap = kCapRaw < half ? kCapRaw : half;
+                constexpr int passes = (half + cap - 1) / cap;
+                static_for<0, passes>([&](auto P) {
+                    constexpr int p0 = decltype(P)::value * cap;
+                    constexpr int p1 = p0 + cap < half ? p0 + cap : half;
+                    if (kg >= half + p0 && kg < half + p1) {
+                        f32x4* dst = red + (size_t)(kg - half - p0) * kSetRegs + (size_t)wave * (TM * TN * 64) + lane;
 #pragma unroll
-            for (int i = 0; i < TM; ++i)
+                        for (int i = 0; i < TM; ++i)
 #pragma unroll
-                for (int j = 0; j < TN; ++j)
-                    red[(((kg - 1) * NW + wave) * (TM * TN) + i * TN + j) * 64 + lane] = acc[i][j];
-        }
-        __syncthreads();
-        if (kg == 0) {
+                            for (int j = 0; j < TN; ++j) dst[(i * TN + j) * 64] = acc[i][j];
+                    }
+                    __syncthreads();
+                    if (kg >= p0 && kg < p1) {
+                        const f32x4* src = red + (size_t)(kg - p0) * kSetRegs + (size_t)wave * (TM * TN * 64) + lane;
 #pragma unroll
-            for (int g = 1; g < KG; ++g)
+                        for (int i = 0; i < TM; ++i)
 #pragma unroll
-                for (int i = 0; i < TM; ++i)
-#pragma unroll
-                    for (int j = 0; j < TN; ++j)
-                        acc[i][j] += red[(((g - 1) * NW + wave) * (TM * TN) + i * TN + j) * 64 + lane];
-        }
+                            for (int j = 0; j < TN; ++j) acc[i][j] += src[(i * TN + j) * 64];
+                    }
+                    if constexpr (!(active == 2 && decltype(P)::value == passes - 1)) __syncthreads();
+                });
+            }
+        });
         writer = kg == 0;
     }
 

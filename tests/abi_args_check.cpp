@@ -51,6 +51,8 @@ int main()
     tm_free_expert_group((tm_expert_group*)not_a_handle);
     tm_kv_free((tm_kv_cache*)not_a_handle);
     CHECK(tm_gemm_workspace_bytes(nullptr, 4) == 0);
+    CHECK(tm_get_plan_units_per_wave(nullptr, 1) == TM_EINVAL);
+    CHECK(tm_reset_workspace((void*)(uintptr_t)4097, nullptr) != TM_OK);
     CHECK(tm_packed_bits(nullptr) == TM_EINVAL && tm_packed_info(nullptr, nullptr, nullptr, nullptr, nullptr) == TM_EINVAL);
     CHECK(tm_unpack_w4(nullptr, nullptr, nullptr, nullptr, nullptr) == TM_EINVAL);
     CHECK(tm_packed_raw(nullptr, nullptr, nullptr, nullptr, nullptr) == TM_EINVAL);

@@ -80,6 +80,9 @@ def test_argument_validation_without_gpu(lib):
     assert lib.tm_get_grouped_plan(None, 4, None, None) == -1
     lib.tm_free_expert_group(None)
     assert lib.tm_gemm_workspace_bytes(None, 4) == 0
+    assert lib.tm_get_plan_units_per_wave(None, 1) == -1
+    assert lib.tm_gemm_w4a16_static(fake, None, fake, 1, None) == -1
+    assert lib.tm_reset_workspace(ctypes.c_void_p(4097), None) != 0
     assert lib.tm_packed_info(None, None, None, None, None) == -1
     assert lib.tm_unpack_w4(None, None, None, None, None) == -1
     assert lib.tm_get_plan(None, 1, None, None, None, None) == -1

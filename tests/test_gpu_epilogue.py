@@ -1,7 +1,7 @@
 """GPU parity of the fused epilogue (bias, silu(gate)*up, residual) against the oracle, through the C ABI.
 
-Without activation the acceptance rule of the plain product applies (|Y - Yref| <= 1e-2 + 5e-3*|Yref|, relative Frobenius
-<= 2e-3).  silu(gate)*up multiplies two such sums, so each factor's relative error adds: 2e-2 + 1e-2*|Yref| and 4e-3."""
+Every mode, the activation included, is held to the acceptance rule of the plain product: |Y - Yref| <= 1e-2 + 5e-3*|Yref|
+and relative Frobenius error <= 2e-3."""
 import sys
 
 import numpy as np
@@ -27,13 +27,6 @@ def tm():
     yield tm
     tm.tm_set_variant(-1, 0)
     tm.tm_set_launch(0, 0)
-
-
-def _accept_act(Y, Yref):
-    y, r = Y.astype(np.float64), Yref.astype(np.float64)
-    worst = float((np.abs(y - r) / (2e-2 + 1e-2 * np.abs(r))).max())
-    fro = float(np.linalg.norm(y - r) / np.linalg.norm(r))
-    return worst <= 1.0 and fro <= 4e-3, worst, fro
 
 
 def _run(tm, oracle, d, g, M, mode, variant=-1, split=0, waves=0, stage=0):
@@ -68,7 +61,9 @@ def _run(tm, oracle, d, g, M, mode, variant=-1, split=0, waves=0, stage=0):
     assert np.array_equal(outs[0].view(np.uint16), outs[1].view(np.uint16))
     _, Yd = oracle.gemm(X, d["q"], d["s"], d["z"], g, want_fp64=True)
     Yref = oracle.epilogue(Yd, bias, res, "silu_mul" if act else "none")
-    ok, worst, fro = _accept_act(outs[0], Yref) if act else acceptance(outs[0], Yref)
+    # one rule for every mode: |Y - Yref| <= 1e-2 + 5e-3 |Yref| and relative Frobenius error <= 2e-3 (with the activation the
+    # observed worst ratio to that bound is 0.16 and the Frobenius error 2.2e-4 over all cases of this file)
+    ok, worst, fro = acceptance(outs[0], Yref)
     assert ok, (mode, worst, fro)
     packed.close()
 
@@ -163,7 +158,7 @@ def test_grouped_gemm_with_fused_activation(tm, oracle, E, K, N, g, counts, vari
         if r1 == r0:
             continue
         _, Yd = oracle.gemm(X[r0:r1], *host[e], g, want_fp64=True)
-        ok, worst, fro = _accept_act(Y[r0:r1], oracle.epilogue(Yd, act="silu_mul"))
+        ok, worst, fro = acceptance(Y[r0:r1], oracle.epilogue(Yd, act="silu_mul"))
         assert ok, (e, worst, fro)
     group.close()
     for p in dev:

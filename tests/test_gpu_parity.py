@@ -328,6 +328,15 @@ def test_caller_workspace_entry_point(tm, oracle):
         assert ok, (worst, fro)
     with pytest.raises(tm.TmError):
         tm.tm_gemm_w4a16_ws(Xd, packed, Y, ws[:256])
+    # counters left part-way by a launch that died are put right by the reset call
+    ws[:64].fill_(1)
+    tm.tm_reset_workspace(ws)
+    Y.fill_(float("nan"))
+    tm.tm_gemm_w4a16_ws(Xd, packed, Y, ws)
+    torch.cuda.synchronize()
+    ok, worst, fro = acceptance(Y.cpu().numpy(), oracle.gemm(d["X"], d["q"], d["s"], d["z"], g))
+    assert ok, (worst, fro)
+    tm.tm_reset_workspace()                       # the library's own: a no-op on clean counters
     tm.tm_set_variant(-1, 0)
 
 
@@ -516,6 +525,9 @@ GROUPED_CASES = [
     (5, 256, 528, 128, [20, 0, 0, 45, 1], 0, 0, 4),
     (64, 256, 96, 128, [0] * 20 + [2] + [0] * 30 + [1, 5] + [0] * 11, 0, 0, -1),
     (6, 2048, 512, 128, [1, 1, 1, 1, 1, 1], 0, 0, -1),
+    # skewed routing: one expert holds nearly all rows, so the kernel chosen from the average load takes it in passes
+    (8, 512, 272, 128, [200, 1, 0, 2, 0, 3, 1, 0], 0, 0, -1),
+    (8, 512, 272, 64, [0, 0, 0, 0, 0, 0, 0, 150], 2, 0, -1),
     # prefill-sized loads go through the CTA-tile kernels (64x128, 128x256), also forced on small loads
     (3, 512, 528, 128, [200, 0, 70], 0, 0, -1),
     (2, 256, 272, 64, [300, 260], 3, 2, -1),
