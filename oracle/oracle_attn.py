@@ -1,4 +1,4 @@
-"""Reference (oracle) for decode attention over a quantised KV cache.  TEST INFRASTRUCTURE ONLY: imported by tests/,
+"""Reference (oracle) for attention over a quantised KV cache: one decoding step, and a chunk of prompt tokens.  TEST INFRASTRUCTURE ONLY: imported by tests/,
 __graft_entry__.smoke() and bench.py's cpu_baseline leg, never by the GPU library or its binding.
 
 Plain numpy, fp64 throughout, one loop per (sequence, head); no blocking, no online softmax, no fused dequantisation.
@@ -62,6 +62,32 @@ def attn_decode(Q, Kq, Ks, Kz, Vq, Vs, Vz, lens, scale: float) -> np.ndarray:
             e = np.exp(sc - sc.max())
             p = e / e.sum()
             O[b, h] = (p @ V).astype(np.float16)
+    return O
+
+
+def attn_prefill(Q, Kq, Ks, Kz, Vq, Vs, Vz, positions, counts, scale: float) -> np.ndarray:
+    """Attention of a chunk of prompt tokens over the quantised cache (paper Sec. 3.3: the attention pipeline serves the
+    prefill phase as it serves decoding; the evaluation of Sec. 5.3 times both).  Q float16 [B, n, Hq, D]: query token i of
+    sequence b sits at cache position positions[b] + i, its own key and value already cached, and attends causally over
+    cache tokens 0 .. positions[b] + i.  counts int [B]: query tokens each sequence really has (rows past that stay 0).
+    O[b, i, h] = softmax(scale * K^[:L] q) V^[:L],  L = positions[b] + i + 1, in fp64, rounded once to float16.
+    The definition written out, one query row at a time: no mask matrix, no blocking, no online softmax."""
+    Q = np.asarray(Q)
+    B, n, Hq, D = Q.shape
+    Hkv = Kq.shape[1]
+    G = Hq // Hkv
+    O = np.zeros((B, n, Hq, D), np.float16)
+    for b in range(B):
+        for i in range(min(n, int(counts[b]))):
+            L = int(positions[b]) + i + 1
+            for h in range(Hq):
+                kv = h // G
+                K = kv_dequant(Kq[b, kv, :L], Ks[b, kv, :L], Kz[b, kv, :L])          # [L, D]
+                V = kv_dequant(Vq[b, kv, :L], Vs[b, kv, :L], Vz[b, kv, :L])
+                sc = (K @ Q[b, i, h].astype(np.float64)) * float(scale)
+                e = np.exp(sc - sc.max())
+                p = e / e.sum()
+                O[b, i, h] = (p @ V).astype(np.float16)
     return O
 
 

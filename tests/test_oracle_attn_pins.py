@@ -160,3 +160,53 @@ def test_attn_decode_4bit_codes_against_torch_sdpa():
     Vd = torch.from_numpy(oa.kv_dequant(*vq)).double().repeat_interleave(Hq // Hkv, dim=1)
     ref = torch.nn.functional.scaled_dot_product_attention(torch.from_numpy(Q).double()[:, :, None, :], Kd, Vd, scale=0.1)
     assert np.allclose(O.astype(np.float64), ref[:, :, 0].numpy(), rtol=2e-3, atol=1e-3)
+
+
+def test_attn_prefill_against_torch_sdpa_causal():
+    """Whole prompt from position 0: PyTorch's fp64 attention with its causal mask on the dequantised cache."""
+    import torch
+    rng = np.random.default_rng(11)
+    for bits in (8, 4):
+        B, Hq, Hkv, T, D = 2, 4, 2, 37, 128
+        K = rng.standard_normal((B, Hkv, T, D)).astype(np.float16)
+        V = rng.standard_normal((B, Hkv, T, D)).astype(np.float16)
+        kq, vq = oa.kv_quantise(K, bits), oa.kv_quantise(V, bits)
+        Q = rng.standard_normal((B, T, Hq, D)).astype(np.float16)
+        O = oa.attn_prefill(Q, *kq, *vq, np.zeros(B, np.int32), np.full(B, T), 0.09)
+        Kd = torch.from_numpy(oa.kv_dequant(*kq)).repeat_interleave(Hq // Hkv, dim=1)      # [B, Hq, T, D]
+        Vd = torch.from_numpy(oa.kv_dequant(*vq)).repeat_interleave(Hq // Hkv, dim=1)
+        Qt = torch.from_numpy(Q.astype(np.float64)).permute(0, 2, 1, 3)                    # [B, Hq, T, D]
+        ref = torch.nn.functional.scaled_dot_product_attention(Qt, Kd, Vd, is_causal=True, scale=0.09).permute(0, 2, 1, 3).numpy()
+        assert np.abs(O.astype(np.float64) - ref).max() <= 1e-3 * np.abs(ref).max() + 1e-3       # one fp16 rounding apart
+
+
+def test_attn_prefill_chunks_positions_and_closed_forms():
+    rng = np.random.default_rng(12)
+    B, Hq, Hkv, T, D = 2, 4, 2, 29, 128
+    kq = oa.kv_quantise(rng.standard_normal((B, Hkv, T, D)).astype(np.float16))
+    vq = oa.kv_quantise(rng.standard_normal((B, Hkv, T, D)).astype(np.float16))
+    Q = rng.standard_normal((B, T, Hq, D)).astype(np.float16)
+    full = oa.attn_prefill(Q, *kq, *vq, np.zeros(B, np.int32), np.full(B, T), 0.1)
+    # a later chunk of the same prompt: query tokens 10 .. 17 of sequence 0, 20 .. 24 of sequence 1 (ragged counts)
+    pos, cnt = np.array([10, 20]), np.array([8, 5])
+    Qc = np.zeros((B, 8, Hq, D), np.float16)
+    for b in range(B):
+        Qc[b, :cnt[b]] = Q[b, pos[b]:pos[b] + cnt[b]]
+    part = oa.attn_prefill(Qc, *kq, *vq, pos, cnt, 0.1)
+    for b in range(B):
+        assert np.array_equal(part[b, :cnt[b]], full[b, pos[b]:pos[b] + cnt[b]])
+        assert not part[b, cnt[b]:].any()                                            # rows past the count stay zero
+    # the last token of a chunk is a decoding step over the same context
+    dec = oa.attn_decode(Q[:, T - 1], *kq, *vq, np.full(B, T), 0.1)
+    assert np.array_equal(dec, full[:, T - 1])
+    # the first prompt token sees only itself: its output is its own value row
+    V = oa.kv_dequant(*vq)
+    assert np.array_equal(full[1, 0, 3], V[1, 1, 0].astype(np.float16))
+    # zero queries: uniform weights over the causal prefix -> running mean of the values
+    O0 = oa.attn_prefill(np.zeros_like(Q), *kq, *vq, np.zeros(B, np.int32), np.full(B, T), 0.1)
+    for i in (0, 4, T - 1):
+        assert np.allclose(O0[0, i, 2].astype(np.float64), V[0, 1, :i + 1].mean(axis=0), rtol=2e-3, atol=2e-3)
+    # causality: changing later cache entries leaves earlier outputs alone
+    kq2 = (kq[0].copy(), kq[1], kq[2]); kq2[0][:, :, 15:] = 0
+    early = oa.attn_prefill(Q, *kq2, *vq, np.zeros(B, np.int32), np.full(B, T), 0.1)
+    assert np.array_equal(early[:, :15], full[:, :15]) and not np.array_equal(early[:, 15:], full[:, 15:])
