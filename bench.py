@@ -382,6 +382,52 @@ def attn_table(tm, torch, iters=50, q_heads=32, kv_heads=8, only=None, bits=8, e
     return rows
 
 
+# Prefill attention: a whole prompt's queries over the quantised cache the same call sequence has just filled (causal), in
+# the same head geometry: (batch, prompt length).  A dense contraction: priced against the fp16 MFMA peak, with the
+# causal half of the score matrix as the flop count (QK^T and PV, 2 flops per multiply-add).
+ATTN_PREFILL_SHAPES = [(1, 512), (1, 2048), (1, 8192), (4, 2048), (16, 512)]
+
+
+def attn_prefill_table(tm, torch, iters=20, q_heads=32, kv_heads=8, bits=8, only=None):
+    import numpy as np
+    rows = []
+    rng = np.random.default_rng(0)
+    for B, T in ATTN_PREFILL_SHAPES:
+        if only is not None and (B, T) != only:
+            continue
+        c = tm.tm_kv_create(B, kv_heads, T, bits)
+        n = B * kv_heads * c.capacity
+        pairs = (rng.uniform(0.005, 0.05, 2 * n).astype(np.float16).view(np.uint16).astype(np.uint32)
+                 | (rng.integers(0, 256, 2 * n).astype(np.float16).view(np.uint16).astype(np.uint32) << 16))
+        k, v, p, cb, pb = tm.tm_kv_raw(c)
+        for ptr in (k, v):
+            t = torch.randint(0, 256, (cb,), dtype=torch.uint8, device="cuda")
+            tm.tm_bench_copy_raw(ptr, t.data_ptr(), cb)
+        t = torch.from_numpy(pairs.view(np.uint8)).cuda()
+        tm.tm_bench_copy_raw(p, t.data_ptr(), pb)
+        torch.cuda.synchronize()
+        Q = torch.randn((B, T, q_heads, 128), device="cuda").to(torch.float16)
+        O = torch.empty_like(Q)
+        pos = torch.zeros((B,), dtype=torch.int32, device="cuda")
+
+        def step():
+            tm.tm_attn_prefill(Q, c, pos, O, 0.08838834764831845)
+
+        it = max(3, min(iters, int(2e11 / (B * q_heads * 128 * 2.0 * T * (T + 1)))))
+        ev_ms, _ = time_steps(torch, step, it, 2, graph_steps=0)
+        sec = ev_ms / it * 1e-3
+        flops = B * q_heads * 128 * 2.0 * T * (T + 1)                  # 4 * D flops per (query, key) pair with key <= query
+        bytes_ = B * kv_heads * T * (2 * 128 * bits // 8 + 8) + 2 * B * T * q_heads * 128 * 2
+        rows.append({"batch": B, "prompt": T, "q_heads": q_heads, "kv_heads": kv_heads, "kv_bits": bits, "us": sec * 1e6,
+                     "TFLOPs": flops / sec / 1e12, "mfma_frac": flops / sec / 1e12 / MFMA_F16_PEAK_TFLOPS,
+                     "GBps": bytes_ / sec / 1e9, "tokens_per_s": B * T / sec})
+        log(f"attn prefill KV{bits}  batch {B:3d} prompt {T:6d}  {sec * 1e6:10.1f} us  {flops / sec / 1e12:7.1f} TFLOP/s "
+            f"({100 * flops / sec / 1e12 / MFMA_F16_PEAK_TFLOPS:4.1f} % of the fp16 MFMA peak)  {B * T / sec / 1e6:7.2f} M tokens/s")
+        c.close()
+        torch.cuda.empty_cache()
+    return rows
+
+
 def epilogue_table(tm, torch, wl, iters=100):
     """Fused epilogue against the same work done as a second pass over Y (PyTorch elementwise kernels, same HIP graph):
     the gated MLP's fused gate+up projection with silu(gate)*up, and its down projection with the residual add."""
@@ -821,6 +867,7 @@ def main():
                           "cpu_baseline": None if args.no_cpu_baseline else attn_cpu_baseline(),
                           "store": None if only is not None else [attn_store_row(tm, torch, eager=args.eager), attn_store_row(tm, torch, bits=4, eager=args.eager)],
                           "fp16_cache_library": attn_companion(torch, iters=min(args.steps, 20)) if args.attn_companion else None,
+                          "prefill": None if only is not None else attn_prefill_table(tm, torch) + attn_prefill_table(tm, torch, bits=4),
                           "rows": table}))
         return
 

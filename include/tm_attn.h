@@ -78,6 +78,22 @@ TM_API int tm_kv_append(tm_kv_cache* cache, const uint16_t* K_new, const uint16_
 TM_API int tm_attn_decode(const uint16_t* Q, const tm_kv_cache* cache, const int32_t* lens, uint16_t* O, int q_heads,
                           float scale, int max_len, tm_stream stream);
 
+/*
+ * A chunk of prompt tokens (the prefill side of the attention pipeline, paper Sec. 3.3; Sec. 4.2 and 4.4 apply as at a
+ * decoding step).  Q fp16 [batch][count][q_heads][128] and O fp16 of the same shape, both 16-byte aligned: query token i
+ * of sequence b sits at cache position positions[b] + i (positions: int32 [batch], device) and attends causally over
+ * cache tokens 0 .. positions[b] + i; its own key and value must already be in the cache (tm_kv_append first, on the same
+ * stream).  counts (int32 [batch], device, or NULL = every sequence has `count` tokens) gives the query tokens each
+ * sequence really has, so that prompts of different lengths share one call: rows i >= counts[b] of O, and rows whose
+ * position falls outside [0, capacity), are left untouched.  q_heads and scale as for tm_attn_decode; 1 <= count <= 65535
+ * * (16 / (q_heads / kv_heads)).  One CTA takes 16 / (q_heads / kv_heads) consecutive tokens of one KV head and streams
+ * the cache up to the last of them; the context is not split, so a short chunk far into a long context is served by few
+ * CTAs (use tm_attn_decode per token there).  Never allocates, uses no workspace, results are bit-identical from run to
+ * run.
+ */
+TM_API int tm_attn_prefill(const uint16_t* Q, const tm_kv_cache* cache, const int32_t* positions, const int32_t* counts,
+                           int count, uint16_t* O, int q_heads, float scale, tm_stream stream);
+
 /* Test hook: the cache's device buffers and sizes (host out-pointers, any may be NULL); memory stays owned by the cache. */
 TM_API int tm_kv_raw(const tm_kv_cache* cache, void** k_codes, void** v_codes, void** pairs, size_t* code_bytes,
                      size_t* pair_bytes);

@@ -53,6 +53,8 @@ def load_library():
     lib.tm_kv_append.argtypes = [vp, vp, vp, vp, i, vp]
     lib.tm_attn_decode.restype = i
     lib.tm_attn_decode.argtypes = [vp, vp, vp, vp, i, ctypes.c_float, i, vp]
+    lib.tm_attn_prefill.restype = i
+    lib.tm_attn_prefill.argtypes = [vp, vp, vp, vp, i, vp, i, ctypes.c_float, vp]
     lib.tm_kv_raw.restype = i
     lib.tm_kv_raw.argtypes = [vp, vp, vp, vp, vp, vp]
     lib.tm_pack_w4_actorder.restype = vp
@@ -542,6 +544,18 @@ def tm_attn_decode(Q, cache: KvCache, lens, O, scale: float, max_len: int = 0, s
     _check(load_library().tm_attn_decode(_dev_ptr(Q, torch.float16, "Q"), cache.handle, _dev_ptr(lens, torch.int32, "lens"),
                                          _dev_ptr(O, torch.float16, "O"), Q.shape[1], float(scale), int(max_len),
                                          _stream_ptr(stream)))
+    return O
+
+
+def tm_attn_prefill(Q, cache: KvCache, positions, O, scale: float, counts=None, stream=None):
+    """Causal attention of a chunk of prompt tokens over the cache: Q, O fp16 [batch][count][q_heads][128] device tensors,
+    positions int32 [batch], counts int32 [batch] or None (see include/tm_attn.h)."""
+    import torch
+    if Q.dim() != 4 or Q.shape[3] != 128 or tuple(O.shape) != tuple(Q.shape):
+        raise ValueError("Q and O must be [batch][count][q_heads][128]")
+    cp = None if counts is None else _dev_ptr(counts, torch.int32, "counts")
+    _check(load_library().tm_attn_prefill(_dev_ptr(Q, torch.float16, "Q"), cache.handle, _dev_ptr(positions, torch.int32, "positions"),
+                                          cp, Q.shape[1], _dev_ptr(O, torch.float16, "O"), Q.shape[2], scale, _stream_ptr(stream)))
     return O
 
 

@@ -29,6 +29,7 @@ namespace {
 
 constexpr int kHeadDim = 128;
 constexpr float kNegBig = -1.0e30f;     // "minus infinity" that stays finite under subtraction
+constexpr float kMaskFloor = -1.0e20f;  // far below any score, far above kNegBig: exp2(kNegBig - kMaskFloor) is 0
 constexpr int kNonTemporal = 2;         // cache-policy bit of a buffer load: streamed once, do not keep
 
 // 2^x by the hardware instruction alone: arguments here are <= 0 and a result below the smallest normal number may
@@ -668,10 +669,12 @@ __device__ __forceinline__ void process_tokens_packed(const BlockRegs& r, int sb
     }
 }
 
+// len: tokens the lane's query column attends over (the same in every lane at a decoding step; at prefill every column
+// has its own causal limit); len_all: the largest of them, wave-uniform.
 template <int BITS, bool PACK>
 __device__ __forceinline__ void process_block(const BlockRegs& r, const uint32_t* sz_slot, const f16x8 (&qf)[4],
-                                              float qsum, const f32x4& neg_qbias, const Magic& mg, int blk, int len, int lane,
-                                              SoftmaxState& st, f32x4 (&acc)[8])
+                                              float qsum, const f32x4& neg_qbias, const Magic& mg, int blk, int len, int len_all,
+                                              int lane, SoftmaxState& st, f32x4 (&acc)[8])
 {
     constexpr int TOK = 256 / BITS;
     const int t0 = blk * TOK;
@@ -681,13 +684,13 @@ __device__ __forceinline__ void process_block(const BlockRegs& r, const uint32_t
     if constexpr (PACK) {
         process_tokens_packed<BITS, true>(r, 0, sz_slot, qf, qsum, neg_qbias, mg, t0, len, lane, st, acc);
         if constexpr (BITS == 4) {
-            if (t0 + 32 < len)
+            if (t0 + 32 < len_all)
                 process_tokens_packed<4, true>(r, 1, sz_slot + 64, qf, qsum, neg_qbias, mg, t0 + 32, len, lane, st, acc);
         }
     } else {
         process_tokens<BITS, true>(r, 0, sz_slot, qf, qsum, neg_qbias, mg, t0, len, lane, st, acc);
         if constexpr (BITS == 4) {
-            if (t0 + 32 < len) process_tokens<4, true>(r, 1, sz_slot + 64, qf, qsum, neg_qbias, mg, t0 + 32, len, lane, st, acc);
+            if (t0 + 32 < len_all) process_tokens<4, true>(r, 1, sz_slot + 64, qf, qsum, neg_qbias, mg, t0 + 32, len, lane, st, acc);
         }
     }
 }
@@ -705,12 +708,19 @@ __device__ __forceinline__ void store_out4(uint16_t* O, int b, int q_heads, int 
 constexpr int kPartialFloats = 32 + kHeadDim * 16;
 constexpr int kMergeHere = 8;            // splits the last-arriving CTA merges itself (all their loads in flight at once)
 
-template <int BITS, bool PACK>
+// PREFILL: the same kernel over a chunk of prompt tokens (paper Sec. 3.3: one attention pipeline for both phases).  The 16
+// query columns of a CTA are then 16 / G consecutive tokens x the G query heads of the KV head (column c = token c / G,
+// head c % G), blockIdx.z counts such token groups instead of context splits, `lens` holds the cache position of every
+// sequence's first query token, and each column attends causally over the cache up to its own token: the length that
+// masks scores becomes a per-lane value, everything else - loading pipeline, head alignment, biased codes - is shared.
+template <int BITS, bool PACK, bool PREFILL = false>
 __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))) void attn_decode_kernel(AttnCache kv, const uint16_t* __restrict__ Q,
                                                           const int32_t* __restrict__ lens, uint16_t* __restrict__ O,
                                                           int q_heads, float scale_log2e, int blocks_per_split,
-                                                          int splits, int merge_here)
+                                                          int splits, int merge_here, const int32_t* __restrict__ counts = nullptr,
+                                                          int count = 1)
 {
+    static_assert(!(PREFILL && PACK), "prompt chunks use all 16 query columns");
     __shared__ float sm_ml[4][2][16];
     __shared__ float sm_out[4][8][4][64];
     // scale/zero words of the blocks in flight: [wave][64 words]; one array per ring slot so that the compiler can tell
@@ -725,21 +735,41 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))) voi
     const int hk = blockIdx.x, b = blockIdx.y, split = blockIdx.z;
     const int G = q_heads / kv.heads;
     const size_t bh = (size_t)b * kv.heads + hk;
-    // the splits cover blocks_per_split * splits blocks (the host's max_len): a longer sequence is cut there, never read
-    // half-way
-    const int len = min(min(max(lens[b], 0), kv.cap), blocks_per_split * splits * TOK);
-    const int nblk = (len + TOK - 1) / TOK;
-    const int blk0 = split * blocks_per_split;
-    const int blk1 = min(nblk, blk0 + blocks_per_split);
+    int len, len_all;                                        // this lane's column; the CTA's longest column
+    int tok = 0, head = c;                                   // query token (within the chunk) and head (within G) of column c
+    bool real;
+    if constexpr (PREFILL) {
+        const int tpg = 16 / G;                              // tokens per CTA
+        const int tq = c / G;
+        head = c - tq * G;
+        tok = split * tpg + tq;
+        const int cnt = counts ? min(max(counts[b], 0), count) : count;
+        const int first = split * tpg;                       // first token of this group
+        if (first >= cnt) return;                            // (uniform) nothing to do for this sequence
+        const int pos0 = lens[b];
+        const int pos = pos0 + tok;
+        real = tq < tpg && tok < cnt && pos >= 0 && pos < kv.cap;
+        len = real ? pos + 1 : 0;
+        len_all = min(max(pos0 + min(cnt, first + tpg), 0), kv.cap);
+        if (!real) tok = first;                              // an address that exists
+    } else {
+        // the splits cover blocks_per_split * splits blocks (the host's max_len): a longer sequence is cut there
+        len = min(min(max(lens[b], 0), kv.cap), blocks_per_split * splits * TOK);
+        len_all = len;
+        real = (PACK ? (c & 7) : c) < G;
+    }
+    const int nblk = (len_all + TOK - 1) / TOK;
+    const int blk0 = PREFILL ? 0 : split * blocks_per_split;
+    const int blk1 = PREFILL ? nblk : min(nblk, blk0 + blocks_per_split);
 
     // Order of the prologue: the query's raw loads, then at once the first two blocks of the KV memory loading pipeline,
     // and only then the arithmetic on the query, which so runs under the blocks' latency (loads return in order, so the
     // query must be requested first).
-    const int qc = PACK ? (c & 7) : c;                       // the query head of operand column c
-    const bool real = qc < G;
+    const int qc = PREFILL ? head : (PACK ? (c & 7) : c);    // the query head of operand column c
     f16x8 qraw[4];
     {
-        const uint16_t* qp = Q + ((size_t)b * q_heads + (size_t)hk * G + (real ? qc : 0)) * kHeadDim + 32 * h;
+        const size_t qrow = PREFILL ? (size_t)b * count + tok : (size_t)b;
+        const uint16_t* qp = Q + (qrow * q_heads + (size_t)hk * G + (real ? qc : 0)) * kHeadDim + 32 * h;
 #pragma unroll
         for (int tt = 0; tt < 4; ++tt) qraw[tt] = *(const f16x8*)(qp + 8 * tt);
     }
@@ -788,7 +818,9 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))) voi
     }
     const f32x4 neg_qbias = {-qbias, -qbias, -qbias, -qbias};
 
-    SoftmaxState st{kNegBig, 0.f, 0.f};
+    // (at prefill a wave may meet blocks in which some column has no live token yet: the running maximum then starts
+    // above the mask value, so that masked scores still turn into zero probabilities)
+    SoftmaxState st{PREFILL ? kMaskFloor : kNegBig, 0.f, 0.f};
     f32x4 acc[8];
 #pragma unroll
     for (int i = 0; i < 8; ++i) acc[i] = f32x4{0.f, 0.f, 0.f, 0.f};
@@ -796,15 +828,15 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))) voi
     if (blk < blk1) {
         while (true) {
             load_block<BITS>(r2, z2, rs, blk + 8 < blk1 ? blk + 8 : nblk, lane);
-            process_block<BITS, PACK>(r0, z0, qf, qsum, neg_qbias, mg, blk, len, lane, st, acc);
+            process_block<BITS, PACK>(r0, z0, qf, qsum, neg_qbias, mg, blk, len, len_all, lane, st, acc);
             blk += 4;
             if (blk >= blk1) break;
             load_block<BITS>(r0, z0, rs, blk + 8 < blk1 ? blk + 8 : nblk, lane);
-            process_block<BITS, PACK>(r1, z1, qf, qsum, neg_qbias, mg, blk, len, lane, st, acc);
+            process_block<BITS, PACK>(r1, z1, qf, qsum, neg_qbias, mg, blk, len, len_all, lane, st, acc);
             blk += 4;
             if (blk >= blk1) break;
             load_block<BITS>(r1, z1, rs, blk + 8 < blk1 ? blk + 8 : nblk, lane);
-            process_block<BITS, PACK>(r2, z2, qf, qsum, neg_qbias, mg, blk, len, lane, st, acc);
+            process_block<BITS, PACK>(r2, z2, qf, qsum, neg_qbias, mg, blk, len, len_all, lane, st, acc);
             blk += 4;
             if (blk >= blk1) break;
         }
@@ -849,10 +881,15 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))) voi
                 for (int w = 0; w < 4; ++w) v += sm_out[w][i][rr][lane] * f[w];
                 o[rr] = v * inv;
             }
-            if (c < G) store_out4(O, b, q_heads, hk * G + c, 16 * i + 4 * h, o);
+            if constexpr (PREFILL) {
+                if (real) store_out4(O, b * count + tok, q_heads, hk * G + head, 16 * i + 4 * h, o);
+            } else {
+                if (c < G) store_out4(O, b, q_heads, hk * G + c, 16 * i + 4 * h, o);
+            }
         }
         return;
     }
+    if constexpr (PREFILL) return;                           // prompt chunks are never split along the context
 
     // Split context: this CTA's maximum, denominator and unnormalised rows go to the workspace - values of row tile i,
     // register rr at float 32 + (4*i + rr)*64 + lane, so that writer and reader touch whole 256-byte lines - as
@@ -1048,6 +1085,24 @@ hipError_t launch_attn_decode(const AttnCache& kv, const uint16_t* Q, const int3
     hipError_t e = hipGetLastError();
     if (e != hipSuccess || splits == 1 || merge_here) return e;
     hipLaunchKernelGGL(attn_merge_kernel, dim3(kv.heads, kv.batch, 8), dim3(256), 0, stream, kv, O, q_heads, splits);
+    return hipGetLastError();
+}
+
+hipError_t launch_attn_prefill(const AttnCache& kv, const uint16_t* Q, const int32_t* positions, const int32_t* counts,
+                               int count, uint16_t* O, int q_heads, float scale, hipStream_t stream)
+{
+    const int G = q_heads / kv.heads;
+    const int tpg = 16 / G;                                  // query tokens per CTA
+    const int groups = (count + tpg - 1) / tpg;
+    if (kv.heads > 65535 || kv.batch > 65535 || groups > 65535 || groups < 1) return hipErrorInvalidValue;
+    const float scale_log2e = scale * 1.4426950408889634f;
+    const dim3 grid(kv.heads, kv.batch, groups);
+    if (kv.bits == 8)
+        hipLaunchKernelGGL((attn_decode_kernel<8, false, true>), grid, dim3(256), 0, stream, kv, Q, positions, O, q_heads,
+                           scale_log2e, 0, 1, 0, counts, count);
+    else
+        hipLaunchKernelGGL((attn_decode_kernel<4, false, true>), grid, dim3(256), 0, stream, kv, Q, positions, O, q_heads,
+                           scale_log2e, 0, 1, 0, counts, count);
     return hipGetLastError();
 }
 

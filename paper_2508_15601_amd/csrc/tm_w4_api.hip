@@ -1185,6 +1185,29 @@ int tm_attn_decode(const uint16_t* Q, const tm_kv_cache* cache, const int32_t* l
     return TM_OK;
 }
 
+int tm_attn_prefill(const uint16_t* Q, const tm_kv_cache* cache, const int32_t* positions, const int32_t* counts, int count,
+                    uint16_t* O, int q_heads, float scale, tm_stream stream)
+{
+    if (!valid_kv(cache)) return fail(TM_EINVAL, "cache handle is null or invalid");
+    if (!Q || !O || !positions) return fail(TM_EINVAL, "Q, O or positions is null");
+    if (((uintptr_t)Q & 15) || ((uintptr_t)O & 15) || ((uintptr_t)positions & 3) || ((uintptr_t)counts & 3))
+        return fail(TM_EINVAL, "misaligned Q, O, positions or counts");
+    const int hk = cache->kv.heads;
+    if (q_heads <= 0 || q_heads % hk || q_heads / hk > 16)
+        return fail(TM_EINVAL, "q_heads = %d must be 1..16 times the cache's %d heads", q_heads, hk);
+    if (!(scale > 0.0f) || !(scale < 1.0e6f)) return fail(TM_EINVAL, "scale out of range");
+    const int tpg = 16 / (q_heads / hk);
+    if (count <= 0 || count > 65535 * tpg) return fail(TM_EINVAL, "count = %d out of range (1..%d)", count, 65535 * tpg);
+    if ((uint64_t)cache->kv.batch * (uint64_t)count >= (1ull << 31)) return fail(TM_EINVAL, "batch * count too large");
+    int dev;
+    int rc = check_device(&dev);
+    if (rc != TM_OK) return rc;
+    if (dev != cache->device) return fail(TM_EINVAL, "cache lives on device %d, current device is %d", cache->device, dev);
+    hipError_t e = launch_attn_prefill(cache->kv, Q, positions, counts, count, O, q_heads, scale, (hipStream_t)stream);
+    if (e != hipSuccess) return fail_hip(e, "attention launch");
+    return TM_OK;
+}
+
 int tm_kv_raw(const tm_kv_cache* cache, void** k_codes, void** v_codes, void** pairs, size_t* code_bytes, size_t* pair_bytes)
 {
     if (!valid_kv(cache)) return fail(TM_EINVAL, "cache handle is null or invalid");

@@ -92,6 +92,8 @@ hipError_t launch_kv_append(const AttnCache& kv, const uint16_t* Kn, const uint1
                             int count, hipStream_t stream);
 hipError_t launch_attn_decode(const AttnCache& kv, const uint16_t* Q, const int32_t* lens, uint16_t* O, int q_heads,
                               float scale, int max_len, int num_cu, hipStream_t stream);
+hipError_t launch_attn_prefill(const AttnCache& kv, const uint16_t* Q, const int32_t* positions, const int32_t* counts,
+                               int count, uint16_t* O, int q_heads, float scale, hipStream_t stream);
 hipError_t launch_skinny(const GemmParams& p, const Plan& plan, int group, hipStream_t stream);
 hipError_t launch_stream(const GemmParams& p, const Plan& plan, int group, hipStream_t stream);
 hipError_t stream_setup();                                             // once per device, outside any capture

@@ -79,6 +79,7 @@ int main()
     CHECK(tm_kv_create(1, 1, 1 << 30, 8) == nullptr);
     CHECK(tm_kv_append(nullptr, fake16, fake16, (const int32_t*)fake32, 1, nullptr) == TM_EINVAL);
     CHECK(tm_attn_decode(fake16, nullptr, (const int32_t*)fake32, out16, 8, 0.1f, 0, nullptr) == TM_EINVAL);
+    CHECK(tm_attn_prefill(fake16, nullptr, (const int32_t*)fake32, nullptr, 4, out16, 8, 0.1f, nullptr) == TM_EINVAL);
     CHECK(tm_kv_raw(nullptr, nullptr, nullptr, nullptr, nullptr, nullptr) == TM_EINVAL);
     tm_kv_free(nullptr);
     CHECK(strncmp(tm_version(), "tm_w4", 5) == 0);

@@ -73,6 +73,7 @@ def test_argument_validation_without_gpu(lib):
     assert lib.tm_kv_create(0, 1, 32, 8) is None and lib.tm_kv_create(1, 1, 32, 4) is None
     assert lib.tm_kv_append(None, fake, fake, fake, 1, None) == -1
     assert lib.tm_attn_decode(fake, None, fake, fake, 8, 0.1, 0, None) == -1
+    assert lib.tm_attn_prefill(fake, None, fake, None, 4, fake, 8, ctypes.c_float(0.1), None) == -1
     assert lib.tm_kv_raw(None, None, None, None, None, None) == -1
     lib.tm_kv_free(None)
     assert lib.tm_group_experts(None, 2) is None and lib.tm_group_experts(fake, 0) is None

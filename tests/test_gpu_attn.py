@@ -322,3 +322,94 @@ def test_attn_hip_graph_replay_matches_eager(tm, bits, T):
     ok, worst, fro = _close(O_eager[:1].cpu().numpy(), Oref)
     assert ok, (worst, fro)
     cache.close()
+
+
+# ------------------------------------------------------------------ a chunk of prompt tokens (prefill)
+
+PREFILL_CASES = [
+    # B, Hq, Hkv, cached tokens T, positions, counts (None: all), query rows n
+    (1, 4, 1, 40, [0], None, 40),                         # whole prompt, G = 4
+    (3, 8, 2, 96, [0, 0, 0], [70, 1, 33], 70),            # ragged prompt lengths in one call
+    (2, 4, 4, 50, [0, 0], [50, 17], 50),                  # G = 1: sixteen tokens per CTA
+    (2, 16, 1, 45, [0, 0], None, 45),                     # G = 16: one token per CTA
+    (2, 6, 2, 37, [0, 0], [37, 20], 37),                  # G = 3: five tokens per CTA, one column idle
+    (2, 8, 1, 64, [0, 0], None, 64),                      # G = 8
+    (3, 8, 2, 130, [40, 0, 100], [20, 5, 17], 20),        # later chunks of longer prompts (chunked prefill)
+    (2, 8, 2, 300, [0, 150], [300, 150], 300),            # several blocks per wave, ragged tail
+]
+
+
+@pytest.mark.parametrize("bits", [8, 4])
+@pytest.mark.parametrize("B,Hq,Hkv,T,positions,counts,n", PREFILL_CASES)
+def test_attn_prefill_against_oracle(tm, B, Hq, Hkv, T, positions, counts, n, bits):
+    import torch
+    _say(f"attn prefill B={B} Hq={Hq} Hkv={Hkv} T={T} positions={positions} counts={counts} n={n} bits={bits}")
+    rng = np.random.default_rng(B * 1000 + Hq * 10 + T + bits)
+    _, K, V, _ = wa.draw(B, Hq, Hkv, T, seed=T + Hq)
+    Q = rng.standard_normal((B, n, Hq, 128)).astype(np.float16)
+    kq, vq = oa.kv_quantise(K, bits), oa.kv_quantise(V, bits)
+    cache = tm.tm_kv_create(B, Hkv, T, bits)
+    tm.tm_kv_append(cache, _dev(np.ascontiguousarray(K.transpose(0, 2, 1, 3))), _dev(np.ascontiguousarray(V.transpose(0, 2, 1, 3))),
+                    torch.zeros(B, dtype=torch.int32, device="cuda"))
+    pos = np.array(positions, np.int32)
+    cnt = np.full(B, n, np.int32) if counts is None else np.array(counts, np.int32)
+    scale = 1.0 / np.sqrt(128.0)
+    outs = []
+    for _ in range(2):
+        O = torch.full((B, n, Hq, 128), float("nan"), dtype=torch.float16, device="cuda")
+        tm.tm_attn_prefill(_dev(Q), cache, _dev(pos), O, scale, counts=None if counts is None else _dev(cnt))
+        torch.cuda.synchronize()
+        outs.append(O.cpu().numpy())
+    assert np.array_equal(outs[0].view(np.uint16), outs[1].view(np.uint16))        # run-to-run identical
+    Oref = oa.attn_prefill(Q, *kq, *vq, pos, cnt, scale)
+    for b in range(B):
+        assert np.isnan(outs[0][b, cnt[b]:]).all()                                 # rows past the count are left alone
+        ok, worst, fro = _close(outs[0][b, :cnt[b]], Oref[b, :cnt[b]])
+        assert ok, (b, worst, fro)
+    cache.close()
+
+
+@pytest.mark.parametrize("bits", [8, 4])
+def test_attn_prefill_long_prompt_sampled(tm, bits):
+    """A 2048-token prompt in the benchmark's head geometry (32 query / 8 KV heads), as bench.py launches it; the oracle
+    checks sampled query rows, the first and last of them included."""
+    import torch
+    _say(f"attn prefill long prompt bits={bits}")
+    B, Hq, Hkv, T = 1, 32, 8, 2048
+    rng = np.random.default_rng(bits)
+    _, K, V, _ = wa.draw(B, Hq, Hkv, T, seed=3)
+    Q = rng.standard_normal((B, T, Hq, 128)).astype(np.float16)
+    kq, vq = oa.kv_quantise(K, bits), oa.kv_quantise(V, bits)
+    cache = tm.tm_kv_create(B, Hkv, T, bits)
+    tm.tm_kv_append(cache, _dev(np.ascontiguousarray(K.transpose(0, 2, 1, 3))), _dev(np.ascontiguousarray(V.transpose(0, 2, 1, 3))),
+                    torch.zeros(B, dtype=torch.int32, device="cuda"))
+    O = torch.full((B, T, Hq, 128), float("nan"), dtype=torch.float16, device="cuda")
+    tm.tm_attn_prefill(_dev(Q), cache, torch.zeros(B, dtype=torch.int32, device="cuda"), O, 128 ** -0.5)
+    torch.cuda.synchronize()
+    O = O.cpu().numpy()
+    assert not np.isnan(O).any()
+    rows = np.unique(np.concatenate([[0, 1, 31, 32, 33, 63, 64, T - 1], rng.integers(0, T, 24)]))
+    for i in rows:                                          # row i as a one-token chunk at position i
+        ref = oa.attn_prefill(Q[:, i:i + 1], *kq, *vq, np.array([i], np.int32), np.array([1], np.int32), 128 ** -0.5)
+        ok, worst, fro = _close(O[:, i:i + 1], ref)
+        assert ok, (int(i), worst, fro)
+    cache.close()
+
+
+def test_attn_prefill_argument_checks(tm):
+    import torch
+    cache = tm.tm_kv_create(1, 2, 64, 8)
+    Q = torch.zeros((1, 4, 8, 128), dtype=torch.float16, device="cuda")
+    pos = torch.zeros(1, dtype=torch.int32, device="cuda")
+    with pytest.raises(tm.TmError):
+        tm.tm_attn_prefill(Q, cache, pos, torch.empty_like(Q), 0.0)               # scale
+    with pytest.raises(tm.TmError):
+        tm.tm_attn_prefill(torch.zeros((1, 4, 7, 128), dtype=torch.float16, device="cuda"), cache, pos,
+                           torch.zeros((1, 4, 7, 128), dtype=torch.float16, device="cuda"), 0.1)   # heads not a multiple
+    # positions outside the cache: nothing is written, nothing faults
+    O = torch.full((1, 4, 8, 128), float("nan"), dtype=torch.float16, device="cuda")
+    tm.tm_attn_prefill(Q, cache, torch.full((1,), 64, dtype=torch.int32, device="cuda"), O, 0.1)
+    tm.tm_attn_prefill(Q, cache, torch.full((1,), -9, dtype=torch.int32, device="cuda"), O, 0.1)
+    torch.cuda.synchronize()
+    assert torch.isnan(O).all()
+    cache.close()
