@@ -639,6 +639,25 @@ CEILING_SHORTLIST = [(0, 256, 1, 0), (1, 1024, 8, 1), (1, 1024, 4, 3), (2, 512, 
                      (4, 512, 2, 1), (8, 256, 2, 1), (8, 256, 1, 1), (16, 256, 1, 1)]
 
 
+def l2_feed_table(tm, torch, iters=20):
+    """How fast the compute units can be fed from the L2, apart from HBM: every CTA of a one-CTA-per-CU launch reads the
+    whole of a 2 MB buffer (the way every CTA of a GEMM reads all of X), for several amounts of bytes in flight per CU."""
+    n = 2 << 20
+    src = torch.randint(0, 255, (n,), dtype=torch.uint8, device="cuda")
+    sink = torch.zeros(16, dtype=torch.int32, device="cuda")
+    rows = []
+    for block, unroll in ((256, 1), (256, 4), (512, 4), (1024, 2), (1024, 8)):
+        def step():
+            tm.tm_bench_read_shape(src.data_ptr(), n, sink, 256, block, unroll, tm.TM_READ_SHARED | tm.TM_READ_NONTEMPORAL)
+        ev_ms, _ = time_steps(torch, step, iters, 3, graph_steps=iters)
+        us = ev_ms / iters * 1e3
+        rows.append({"block": block, "loads_in_flight_per_thread": unroll, "bytes_in_flight_per_cu": block * unroll * 16,
+                     "us": us, "GBps_per_cu": n / us / 1e3, "TBps_chip": 256 * n / us / 1e6})
+        log(f"L2 feed, 256 CTAs x {block} threads x {unroll} loads in flight ({block * unroll * 16 // 1024:3d} KiB per CU): "
+            f"{n / us / 1e3:6.1f} GB/s per CU, {256 * n / us / 1e6:5.1f} TB/s over the chip")
+    return rows
+
+
 def ceiling_sizes(wl):
     """(label, packed weight + scale/zero bytes) of every distinct weight matrix of the benchmark configurations."""
     out, seen = [], set()
@@ -787,14 +806,20 @@ def main():
         return
 
     if args.workload == "ceiling":
-        rows = ceiling_table(tm, torch, ceiling_sizes(wl), iters=min(args.steps, 100), full=args.ceiling_full)
+        sizes = ceiling_sizes(wl)
+        if args.only:                                   # --only cfg2_qkv: one byte count (a profiler run per size)
+            sizes = [sz for sz in sizes if sz[0] == args.only]
+            if not sizes:
+                raise SystemExit(f"--only {args.only}: no such weight matrix; have {[n for n, _ in ceiling_sizes(wl)]}")
+        rows = ceiling_table(tm, torch, sizes, iters=min(args.steps, 100), full=args.ceiling_full)
         empty = empty_launch_us(tm, torch)
         log(f"empty kernel node: {empty:.2f} us")
+        l2 = None if args.only else l2_feed_table(tm, torch)
         if args.sweep_out:
             os.makedirs(os.path.dirname(os.path.abspath(args.sweep_out)), exist_ok=True)
             json.dump(rows, open(args.sweep_out, "w"), indent=1)
         print(json.dumps({"metric": "read-only streaming ceiling at the byte counts of the benchmark's weight matrices", "workload": "ceiling",
-                          "n_gpus": 1, "empty_launch_us": empty, "rows": [r for r in rows if r.get("best")]}))
+                          "n_gpus": 1, "empty_launch_us": empty, "l2_feed": l2, "rows": [r for r in rows if r.get("best")]}))
         return
 
     if args.workload == "pack":
@@ -981,7 +1006,9 @@ def main():
         roofline = {"bound": "mfma", "achieved": ach, "peak": MFMA_F16_PEAK_TFLOPS, "unit": "TFLOP/s",
                     "frac": ach / MFMA_F16_PEAK_TFLOPS, "traffic": None}
     plan = tm.tm_get_plan(dom.packed[0], dom.Ms[-1])
-    roofline["kernel"] = f"{plan['name']} on {dom.case.name.rsplit('_M', 1)[0]} (K={dom.case.K}, N={dom.case.N}), M in {list(dom.Ms)}"
+    form = (f", one-shot form: stream_kernel with {plan['name'].split('x')[-1]}-column strips, {plan['one_shot_units_per_wave']} units per wave, "
+            f"{plan['block'] // 64} waves" if plan.get("one_shot_units_per_wave", 0) > 0 else "")
+    roofline["kernel"] = f"{plan['name']}{form} on {dom.case.name.rsplit('_M', 1)[0]} (K={dom.case.K}, N={dom.case.N}), M in {list(dom.Ms)}"
     roofline["avg_launch_us"] = dom_launch_s * 1e6
     roofline["algorithmic_bytes_per_launch"] = dom_B
     roofline["flops_per_launch"] = dom_F

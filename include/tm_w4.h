@@ -309,10 +309,13 @@ TM_API int tm_bench_read(const void* src, size_t bytes, void* sink, tm_stream st
  * The same read-only stream in a chosen launch shape, to find the best streaming shape at a given byte count (the
  * ceiling a weight-streaming kernel of that size can be held against): `grid` CTAs of `block` threads (a multiple of 64,
  * at most 1024), `unroll` (1, 2, 4, 8 or 16) 128-bit loads in flight per thread; flags bit 0 = non-temporal loads,
- * bit 1 = every CTA reads one contiguous slice of the buffer instead of interleaving with the others.
+ * bit 1 = every CTA reads one contiguous slice of the buffer instead of interleaving with the others, bit 2 = every CTA
+ * reads the whole buffer (the way every CTA of a GEMM reads all of X; `grid` x `bytes` are then moved in total, and a
+ * buffer that stays in the L2 measures how fast the compute units can be fed from there; bit 1 is ignored).
  */
 #define TM_READ_NONTEMPORAL 1
 #define TM_READ_CHUNKED 2
+#define TM_READ_SHARED 4
 TM_API int tm_bench_read_shape(const void* src, size_t bytes, void* sink, int grid, int block, int unroll, int flags,
                                tm_stream stream);
 

@@ -239,6 +239,7 @@ def tm_pack_w8_fp8(qweight, scales, K: int, N: int, group: int, stream=None) -> 
 
 
 TM_LAYOUT_N8, TM_LAYOUT_N8_INTERLEAVED, TM_LAYOUT_K8 = 0, 1, 2
+TM_READ_NONTEMPORAL, TM_READ_CHUNKED, TM_READ_SHARED = 1, 2, 4        # flags of tm_bench_read_shape
 
 
 def tm_pack_w4_layout(qweight, scales, zeros, K: int, N: int, group: int, layout: int, stream=None) -> PackedW4:

@@ -1067,7 +1067,7 @@ int tm_bench_read_shape(const void* src, size_t bytes, void* sink, int grid, int
     if ((bytes & 15) || ((uintptr_t)src & 15) || ((uintptr_t)sink & 3)) return fail(TM_EINVAL, "need 16-byte multiples");
     if (grid < 1 || grid > (1 << 20) || block < 64 || block > 1024 || block % 64) return fail(TM_EINVAL, "grid or block out of range");
     if (unroll != 1 && unroll != 2 && unroll != 4 && unroll != 8 && unroll != 16) return fail(TM_EINVAL, "unroll must be 1, 2, 4, 8 or 16");
-    if (flags & ~3) return fail(TM_EINVAL, "unknown flags");
+    if (flags & ~7) return fail(TM_EINVAL, "unknown flags");
     hipError_t e = launch_read_shape(src, bytes, sink, (unsigned)grid, (unsigned)block, unroll, flags, (hipStream_t)stream);
     if (e != hipSuccess) return fail_hip(e, "read launch");
     return TM_OK;

@@ -222,6 +222,34 @@ __global__ void read_shape_kernel(const u32x4* __restrict__ src, size_t n16, uin
     if (x == 0x9E3779B9u) *sink = x;               // practically never taken; keeps the loads alive
 }
 
+// Every CTA reads the WHOLE buffer (as every CTA of a GEMM reads all of X): with a buffer that stays in the L2 this
+// measures how fast a compute unit can be fed from the L2, apart from HBM.  CTA b starts a b-th of the way in and
+// wraps, so that the CTAs do not all ask for the same line at the same moment.
+template <int U, bool NT>
+__global__ void read_shared_kernel(const u32x4* __restrict__ src, size_t n16, uint32_t* sink)
+{
+    const size_t threads = blockDim.x;
+    const size_t rot = (n16 / gridDim.x) * blockIdx.x;
+    u32x4 acc = {0, 0, 0, 0};
+    for (size_t i = threadIdx.x; i < n16; i += threads * U) {
+        u32x4 v[U];
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+            size_t at = i + u * threads;
+            v[u] = u32x4{0, 0, 0, 0};
+            if (at < n16) {
+                at += rot;
+                if (at >= n16) at -= n16;
+                v[u] = NT ? __builtin_nontemporal_load(src + at) : src[at];
+            }
+        }
+#pragma unroll
+        for (int u = 0; u < U; ++u) acc ^= v[u];
+    }
+    uint32_t x = acc.x ^ acc.y ^ acc.z ^ acc.w;
+    if (x == 0x9E3779B9u) *sink = x;
+}
+
 // Activation-order checkpoints: row i of the matrix that gets packed is row perm[i] of the checkpoint, so that the
 // rows of one K-group become consecutive.  N-major words move whole; a K-major word is rebuilt from eight rows.
 __global__ __launch_bounds__(256) void permute_rows_kernel(const uint32_t* __restrict__ in, const int32_t* __restrict__ perm,
@@ -405,6 +433,11 @@ static void launch_read_u(const void* src, size_t n16, void* sink, unsigned grid
 {
     const u32x4* p = (const u32x4*)src;
     uint32_t* sk = (uint32_t*)sink;
+    if (flags & 4) {
+        if (flags & 1) hipLaunchKernelGGL((read_shared_kernel<U, true>), dim3(grid), dim3(block), 0, stream, p, n16, sk);
+        else hipLaunchKernelGGL((read_shared_kernel<U, false>), dim3(grid), dim3(block), 0, stream, p, n16, sk);
+        return;
+    }
     switch (flags & 3) {
         case 0: hipLaunchKernelGGL((read_shape_kernel<U, false, false>), dim3(grid), dim3(block), 0, stream, p, n16, sk); break;
         case 1: hipLaunchKernelGGL((read_shape_kernel<U, true, false>), dim3(grid), dim3(block), 0, stream, p, n16, sk); break;
