@@ -238,6 +238,28 @@ __device__ __forceinline__ void ld_partial2(const float* p, float& a, float& b)
     a = __builtin_bit_cast(float, (uint32_t)u);
     b = __builtin_bit_cast(float, (uint32_t)(u >> 32));
 }
+// Sum over the K splits of one pair of neighbouring outputs, in split order (a fixed order: the result does not depend
+// on which CTA arrives last).  The loads of four splits are issued before the first add: each of them is a round trip
+// past the caches, and a loop of load-then-add over a split count known only at run time pays those trips one after the
+// other.  first = address of the pair in split 0, stride = floats between consecutive splits.
+__device__ __forceinline__ void sum_partials2(const float* first, size_t stride, int split, float& v0, float& v1)
+{
+    v0 = 0.f;
+    v1 = 0.f;
+    for (int s0 = 0; s0 < split; s0 += 4) {
+        float a[4], b[4];
+#pragma unroll
+        for (int u = 0; u < 4; ++u) ld_partial2(first + (size_t)min(s0 + u, split - 1) * stride, a[u], b[u]);
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {
+            if (s0 + u < split) {                  // uniform over the launch
+                v0 += a[u];
+                v1 += b[u];
+            }
+        }
+    }
+}
+
 __device__ __forceinline__ void wait_stores_done()
 {
     asm volatile("s_waitcnt vmcnt(0)" ::: "memory");           // this wave's write-through stores have completed

@@ -216,13 +216,8 @@ __device__ __forceinline__ void skinny_reduce(const GemmParams& p, f32x4 (&acc)[
                     const int m = mt * 16 + row;
                     if (m >= p.M || col >= ntw * 16) continue;
                     const int n = nt0 * 16 + col;
-                    float v0 = 0.f, v1 = 0.f;
-                    for (int s = 0; s < p.split; ++s) {
-                        float a, b;
-                        ld_partial2(p.partial + ((size_t)s * p.M + m) * p.N + n, a, b);
-                        v0 += a;
-                        v1 += b;
-                    }
+                    float v0, v1;
+                    sum_partials2(p.partial + (size_t)m * p.N + n, (size_t)p.M * p.N, p.split, v0, v1);
                     store_pair(p, m, n, v0, v1);
                 }
             }

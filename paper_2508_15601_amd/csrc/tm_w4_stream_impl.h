@@ -98,13 +98,8 @@ __device__ __forceinline__ void stream_reduce(const GemmParams& p, const f32x4 (
                 const int m = 4 * (pl >> 4) + (jr & 3);
                 if (jr < NTW * 4 && m < p.M) {
                     const int n = (nt0 + (jr >> 2)) * 16 + (pl & 15);
-                    float v0 = 0.f, v1 = 0.f;
-                    for (int s = 0; s < p.split; ++s) {
-                        float a, b;
-                        ld_partial2(p.partial + ((size_t)s * p.M + m) * p.N + n, a, b);
-                        v0 += a;
-                        v1 += b;
-                    }
+                    float v0, v1;
+                    sum_partials2(p.partial + (size_t)m * p.N + n, (size_t)p.M * p.N, p.split, v0, v1);
                     store_pair(p, m, n, v0, v1);
                 }
             }

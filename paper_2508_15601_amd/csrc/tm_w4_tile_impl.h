@@ -430,23 +430,47 @@ __device__ __forceinline__ void tile_body(const GemmParams& p, const int tile_m,
     }
     __syncthreads();
     if (!s_last) return;
+    // The last CTA adds the partial tiles in split order.  Every load is a round trip past the caches, so the loads of a
+    // whole row of tiles and of up to four splits are issued before the first add (the accumulators are dead by now:
+    // their registers hold the loaded values).
+    const size_t split_stride = (size_t)p.M * p.N;
+    constexpr int UB = (TM <= 8 && TN <= 4) ? 4 : 1;       // splits per batch; the largest tiles have no registers to spare
 #pragma unroll
     for (int i = 0; i < TM; ++i) {
         const int m = m0 + i * 16 + c;
         if (m >= p.M || !writer) continue;
+        float v[TN][4];
+#pragma unroll
+        for (int j = 0; j < TN; ++j)
+#pragma unroll
+            for (int r = 0; r < 4; ++r) v[j][r] = 0.f;
+        for (int s0 = 0; s0 < p.split; s0 += UB) {
+            float a[UB][TN][4];
+#pragma unroll
+            for (int u = 0; u < UB; ++u) {
+                const float* row = p.partial + (size_t)min(s0 + u, p.split - 1) * split_stride + (size_t)m * p.N + 4 * h;
+#pragma unroll
+                for (int j = 0; j < TN; ++j) {
+                    const int nt = min(nt0 + j, nt_end - 1);           // tiles past the edge re-read the last one
+                    ld_partial2(row + nt * 16, a[u][j][0], a[u][j][1]);
+                    ld_partial2(row + nt * 16 + 2, a[u][j][2], a[u][j][3]);
+                }
+            }
+#pragma unroll
+            for (int u = 0; u < UB; ++u) {
+                if (s0 + u < p.split) {
+#pragma unroll
+                    for (int j = 0; j < TN; ++j)
+#pragma unroll
+                        for (int r = 0; r < 4; ++r) v[j][r] += a[u][j][r];
+                }
+            }
+        }
 #pragma unroll
         for (int j = 0; j < TN; ++j) {
             const int nt = nt0 + j;
             if (nt >= nt_end) continue;
-            float v[4] = {0.f, 0.f, 0.f, 0.f};
-            for (int s = 0; s < p.split; ++s) {
-                const float* src = p.partial + ((size_t)s * p.M + m) * p.N + nt * 16 + 4 * h;
-                float a0, a1, a2, a3;
-                ld_partial2(src, a0, a1);
-                ld_partial2(src + 2, a2, a3);
-                v[0] += a0; v[1] += a1; v[2] += a2; v[3] += a3;
-            }
-            store_quad(p, m, nt * 16 + 4 * h, v[0], v[1], v[2], v[3]);
+            store_quad(p, m, nt * 16 + 4 * h, v[j][0], v[j][1], v[j][2], v[j][3]);
         }
     }
     if (tid == 0) __hip_atomic_store(&p.counters[tile], 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
