@@ -248,12 +248,77 @@ Plan make_plan(const tm_packed_w4* h, int M, int num_cu)
             }
         }
     }
-    if (is_skinny(variant) && M > skinny_rows(variant))        // a forced skinny variant must still cover M
-        variant = M <= 32 ? kSkinny32x64 : (M <= 64 ? kSkinny64x64 : (w8 ? kTile64x128 : kTile64x256));
-    pl.variant = variant;
     const size_t out_bytes = (size_t)M * h->N * sizeof(float);
     int max_split_ws = (int)(kPartialBudget / (out_bytes ? out_bytes : 1));
     if (max_split_ws < 1) max_split_ws = 1;
+    // 16 < M <= 64, 4-bit codes: the one-shot decode kernels with a ring of X pieces per wave, one strip per CU.  Every
+    // CTA streams the X rows of its K slice through its CU's load path, so where that is more than about 192 KiB the
+    // strips are made wider and K is split across CTAs instead (narrow outputs: each CTA then reads a part of X only).
+    // A forced 16-row decode variant fixes the strip width (and the forced split the split) instead; the forced 32- and
+    // 64-row variants keep meaning the ring-buffered kernels.
+    if (h->bits == 4 && M > 16 && M <= 64 && g_force_stage != 1 && (uint64_t)M * h->K * 2u < (1ull << 31) &&
+        (g_force_variant < 0 || (is_skinny(g_force_variant) && skinny_rows(g_force_variant) == 16))) {
+        int ntw, strips, split;
+        if (g_force_variant >= 0) {
+            ntw = skinny_ntw(g_force_variant);
+            strips = ceil_div(NT, ntw);
+            split = g_force_split > 0 ? g_force_split : 1;
+        } else {
+            // measured at M = 32: N = 8192, K = 8192 13.9 us on 32-column strips with no split against 16.7 with wider
+            // strips and split 2; N = 4096, K = 11008 12.9 us on 64-column strips with split 4 against 14.7 with no split
+            const int per_cu = ceil_div(NT, num_cu);
+            split = 1;
+            if (NT < num_cu) {
+                ntw = 1;
+                strips = NT;
+                split = ceil_div(num_cu, NT);
+            } else if (per_cu <= 1 && (size_t)M * h->K * 2 > 256 * 1024) {
+                ntw = 4;
+                strips = ceil_div(NT, ntw);
+                split = ceil_div(num_cu, strips);
+            } else if (per_cu <= 2) {
+                ntw = per_cu;
+                strips = num_cu;
+            } else {
+                // wide outputs stay with the CTA tiles (4096 x 22016: 17.4 against 16.3 us at M = 32, 27.9 against
+                // 20.5 us at M = 64)
+                ntw = 0;
+                strips = 1;
+            }
+            if (g_force_split > 0) split = g_force_split;
+        }
+        if (split > KU) split = KU;
+        if (split > max_split_ws) split = max_split_ws;
+        if (split < 1) split = 1;
+        const int kps = ceil_div(KU, split);
+        split = ceil_div(KU, kps);
+        const int widest = ceil_div(NT, strips);
+        // chosen automatically only where CTAs of 16 waves fit: with 8 waves and two ring slots the refills are not
+        // covered (4096 x 22016 at M = 32: 17.4 us against 16.7 us on the 32 x 96 tiles)
+        const int tries[2] = {g_force_waves >= 8 ? g_force_waves : (M > 32 ? 8 : 16),
+                              g_force_waves >= 8 ? g_force_waves : ((g_force_variant < 0 && M <= 32) ? 16 : 8)};
+        for (int w : tries) {
+            const int ni = ntw > 0 && widest <= 8 && strips <= kMaxCounters ? rows_units_per_wave(M, widest, h->group, kps, w) : 0;
+            if (ni > 0) {
+                pl.variant = M <= 32 ? kSkinny32x64 : kSkinny64x64;     // in name only: the strip width is NT / strips
+                pl.split = split;
+                pl.ku_per_split = kps;
+                pl.strips = strips;
+                pl.stage_steps = 2;
+                pl.kgroups = 1;
+                pl.stream_ni = ni;
+                pl.tiles_m = 1;
+                pl.tiles_n = strips;
+                pl.block = (unsigned)w * 64;
+                pl.grid = (unsigned)(strips * split);
+                pl.ws_bytes = kCounterBytes + (split > 1 ? (size_t)split * out_bytes : 0);
+                return pl;
+            }
+        }
+    }
+    if (is_skinny(variant) && M > skinny_rows(variant))        // a forced skinny variant must still cover M
+        variant = M <= 32 ? kSkinny32x64 : (M <= 64 ? kSkinny64x64 : (w8 ? kTile64x128 : kTile64x256));
+    pl.variant = variant;
     int split = 1;
     if (is_skinny(variant)) {
         const int ntw = skinny_ntw(variant);
@@ -472,7 +537,7 @@ int run_gemm(const uint16_t* X, const tm_packed_w4* h, uint16_t* Y, int M, void*
     hipError_t e = h->bits == 8 ? (!is_skinny(pl.variant) ? launch_tile_8bit(p, pl, h->group, h->fp8, stream)
                                    : h->fp8 ? launch_skinny_f8(p, pl, h->group, stream)
                                             : launch_skinny_w8(p, pl, h->group, stream))
-                   : pl.stream_ni > 0      ? launch_stream(p, pl, h->group, stream)
+                   : pl.stream_ni > 0      ? (M > 16 ? launch_rows(p, pl, h->group, stream) : launch_stream(p, pl, h->group, stream))
                    : is_skinny(pl.variant) ? launch_skinny(p, pl, h->group, stream)
                                            : launch_tile(p, pl, h->group, stream);
     if (e != hipSuccess) return fail_hip(e, "kernel launch");

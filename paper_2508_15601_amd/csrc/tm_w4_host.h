@@ -65,7 +65,8 @@ struct Plan {
     int strips;           // skinny kernels: number of column strips the 16-column tiles are dealt into
     int stage_steps;      // tile kernels: MFMA steps (32 rows of K each) per pipeline stage and wave set: 2, 4 or 8
     int kgroups;          // tile kernels: sets of four waves per CTA, each taking its own slice of every stage
-    int stream_ni;        // decode kernels: > 0 = the one-shot kernel with this many packed units per wave
+    int stream_ni;        // decode kernels: > 0 = the one-shot kernel with this many packed units per wave (the form
+                          // with a ring of X pieces when M > 16)
     int tiles_m, tiles_n;
     unsigned grid;
     unsigned block;
@@ -100,6 +101,10 @@ hipError_t stream_setup();                                             // once p
 int stream_units_per_wave(int ntw, int group, int kus, int waves);     // 0: no one-shot kernel is built for this shape
 constexpr size_t kStreamLdsBudget = 156 * 1024;                       // of the 160 KiB of a CU
 size_t stream_lds(int ni, int mp_log, int ntw, int waves, int* red_off);
+hipError_t launch_rows(const GemmParams& p, const Plan& plan, int group, hipStream_t stream);      // 16 < M <= 64
+hipError_t launch_rows32(const GemmParams& p, const Plan& plan, int group, hipStream_t stream);
+hipError_t launch_rows64(const GemmParams& p, const Plan& plan, int group, hipStream_t stream);
+int rows_units_per_wave(int M, int ntw, int group, int kus, int waves);        // 0: no such kernel is built for this shape
 hipError_t launch_skinny_w8(const GemmParams& p, const Plan& plan, int group, hipStream_t stream);
 hipError_t launch_skinny_f8(const GemmParams& p, const Plan& plan, int group, hipStream_t stream);
 hipError_t launch_skinny_grouped(const GroupedParams& gp, int variant, int experts, int group, hipStream_t stream);

@@ -29,16 +29,6 @@ namespace {
 constexpr int kPanelN = 8;                 // output tiles per panel row (XCD-local rasterisation)
 
 
-// compile-time loop: f(std::integral_constant<int, I>{}) for I = B .. E-1
-template <int B, int E, class F>
-__device__ __forceinline__ void static_for(F&& f)
-{
-    if constexpr (B < E) {
-        f(std::integral_constant<int, B>{});
-        static_for<B + 1, E>(f);
-    }
-}
-
 // CTA tile = (TM*16) rows x (NW*TN*16) columns; wave w of NW owns columns [w*TN*16, (w+1)*TN*16) and all rows.
 // KG > 1 puts KG such sets of NW waves into one CTA: set kg multiplies the kg-th slice (32*KW rows of K) of every
 // stage, and the KG partial tiles meet in LDS at the end.  That doubles or quadruples the waves per SIMD, which

@@ -263,6 +263,83 @@ def test_decode_kernel_forms(tm, oracle, form, variant, M, K, N, g, waves, split
     packed.close()
 
 
+def _x_ring_built(M, ntw, g, kus, NT):
+    """The library's rule for which X-ring kernels exist, restated: registers for the weights in flight, the accumulators
+    and one step of fragments within 128 per lane (CTAs of 16 waves, two row tiles only) or 250 (CTAs of 8 waves)."""
+    tm_rows, gpu = (2 if M <= 32 else 4), 128 // g
+    ntw = -(-NT // -(-NT // ntw))                       # widest strip after the tiles are dealt evenly
+    for waves in ((16, 8) if tm_rows == 2 else (8,)):
+        ni = next((b for b in (1, 2, 3, 4, 6, 8) if b >= -(-kus // waves)), None)
+        if ni is None:
+            continue
+        regs = ni * ntw * (4 + gpu) + tm_rows * ntw * 4 + 4 * tm_rows + 3 * ntw + 28
+        if (regs <= 128 if waves == 16 else (regs <= 250 if tm_rows == 4 else 128 < regs <= 250)):
+            return True
+    return False
+
+
+# 16 < M <= 64: the one-shot kernels with a ring of X pieces per wave (two row tiles per wave up to M = 32, four beyond).  A forced 16-row variant fixes the strip width;
+# every width, CTAs of 8 and 16 waves, K ranges that leave waves a unit short or without any, strips of two widths, K
+# split across CTAs, both group sizes the kernels are built for, the smallest and the largest row count.
+@pytest.mark.parametrize("variant", [0, 1, 14, 2, 15, 16])
+@pytest.mark.parametrize("M,K,N,g,split", [(17, 1152, 336, 128, 1), (32, 2048, 528, 64, 1), (24, 1536, 1040, 128, 2),
+                                           (31, 4096, 272, 128, 1), (32, 2560, 2064, 64, 3), (20, 1024, 80, 64, 1),
+                                           (32, 8192, 512, 128, 1), (33, 1152, 336, 128, 1), (64, 2048, 528, 64, 2),
+                                           (50, 4096, 272, 128, 1), (64, 1536, 1040, 64, 3), (47, 11008, 256, 128, 4)])
+def test_decode_kernels_with_x_ring(tm, oracle, variant, M, K, N, g, split):
+    d = _random_problem(variant * 37 + M + K, M, K, N, g)
+    packed = gu.pack(d, g)
+    tm.tm_set_variant(variant, split)
+    tm.tm_set_launch(0, 0)                  # 16 waves per CTA where a wave's share fits 128 registers, else 8
+    try:
+        plan = tm.tm_get_plan(packed, M)
+        _say(f"x-ring variant={variant} M={M} K={K} N={N} g={g} split={split} plan={plan}")
+        # where a wave's share of the weights exceeds its registers even in CTAs of 8 waves no such kernel is built and
+        # the ring-buffered form takes the launch
+        assert (plan["one_shot_units_per_wave"] > 0) == _x_ring_built(M, {0: 1, 1: 2, 14: 3, 2: 4, 15: 6, 16: 8}[variant], g,
+                                                                      -(-(K // 128) // split), N // 16), plan
+        Y = gu.gemm(packed, d["X"])
+        Y2 = gu.gemm(packed, d["X"])
+    finally:
+        tm.tm_set_variant(-1, 0)
+        tm.tm_set_launch(0, 0)
+    ok, worst, fro = acceptance(Y, oracle.gemm(d["X"], d["q"], d["s"], d["z"], g))
+    assert ok, (plan, worst, fro)
+    assert np.array_equal(Y.view(np.uint16), Y2.view(np.uint16))
+    packed.close()
+
+
+def test_x_ring_form_is_taken_and_exact(tm, oracle):
+    """The benchmark's narrow layers at M = 32 and 64 run the X-ring kernels (one_shot_units_per_wave > 0 in the plan), and
+    those kernels give the oracle's bits on integer-exact and one-hot inputs."""
+    import torch
+    for K, N, g in ((11008, 4096, 128), (8192, 8192, 64)):
+        qw = torch.zeros((K, N // 8), dtype=torch.int32, device="cuda")
+        s = torch.ones((K // g, N), dtype=torch.float16, device="cuda")
+        packed = tm.tm_pack_w4(qw, s, None, K, N, g)
+        for M in (32, 64):
+            plan = tm.tm_get_plan(packed, M)
+            _say(f"x-ring plan K={K} N={N} M={M}: {plan}")
+            assert plan["one_shot_units_per_wave"] > 0, (K, N, M, plan)
+        packed.close()
+    rng = np.random.default_rng(5)
+    M, K, N, g = 29, 1280, 400, 128
+    q = rng.integers(0, 16, (K, N), dtype=np.uint8)
+    z = rng.integers(0, 16, (K // g, N)).astype(np.float16)
+    s = np.exp2(rng.integers(-3, 2, (K // g, N))).astype(np.float16)         # power-of-two scales: every product exact
+    X = rng.integers(-3, 4, (M, K)).astype(np.float16)
+    X[5] = 0
+    X[5, 777] = 1                                                           # a one-hot row picks out one dequantised row
+    d = {"q": q, "s": s, "z": z, "X": X, "qweight": wl.pack_interchange(q)}
+    packed = gu.pack(d, g)
+    plan = tm.tm_get_plan(packed, M)
+    assert plan["one_shot_units_per_wave"] > 0, plan
+    Y = gu.gemm(packed, X)
+    Yref = oracle.gemm(X, q, s, z, g)
+    assert np.array_equal(Y.view(np.uint16), Yref.view(np.uint16))
+    packed.close()
+
+
 def test_decode_configs_take_the_one_shot_form(tm):
     """The benchmark's decode layers (M <= 16 at K = 4096 and 8192; K = 11008 at M = 1) run the one-shot kernels."""
     import torch

@@ -56,18 +56,25 @@ def env():
     return torch, tm, thrash
 
 
-@pytest.mark.parametrize("layer,M", [("cfg3_down", 16), ("cfg3_down", 32), ("cfg3_down", 64), ("cfg5_sweep", 32)])
-def test_split_k_merge_repeats_bit_for_bit(env, layer, M):
+# (layer, M, forced split): 0 = the split the dispatcher picks by itself; the 8192 x 8192 layer at M = 32 runs unsplit by
+# default and is split here, so that its kernel's hand-over is covered as well
+@pytest.mark.parametrize("layer,M,split", [("cfg3_down", 16, 0), ("cfg3_down", 32, 0), ("cfg3_down", 64, 0), ("cfg5_sweep", 32, 2),
+                                           ("cfg5_sweep", 64, 2)])
+def test_split_k_merge_repeats_bit_for_bit(env, layer, M, split):
     torch, tm, thrash = env
     big = wl.case_by_name({"cfg3_down": "cfg3_down_M64", "cfg5_sweep": "cfg5_sweep_M1024"}[layer])
     d = wl.make(big)
     packed = gu.pack(d, big.group)
-    plan = tm.tm_get_plan(packed, M)
-    _say(f"stress split-K {layer} M={M} plan={plan}")
-    assert plan["split_k"] > 1, "the case is meant to cross CTAs"
-    X = gu.to_dev(d["X"][:M])
-    Y = torch.empty((M, big.N), dtype=torch.float16, device="cuda")
-    _repeat(torch, lambda: tm.tm_gemm_w4a16(X, packed, Y), Y, thrash, f"{layer} M={M}")
+    tm.tm_set_variant(-1, split)
+    try:
+        plan = tm.tm_get_plan(packed, M)
+        _say(f"stress split-K {layer} M={M} plan={plan}")
+        assert plan["split_k"] > 1, "the case is meant to cross CTAs"
+        X = gu.to_dev(d["X"][:M])
+        Y = torch.empty((M, big.N), dtype=torch.float16, device="cuda")
+        _repeat(torch, lambda: tm.tm_gemm_w4a16(X, packed, Y), Y, thrash, f"{layer} M={M}")
+    finally:
+        tm.tm_set_variant(-1, 0)
     packed.close()
 
 
