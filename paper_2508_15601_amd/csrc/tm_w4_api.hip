@@ -242,8 +242,12 @@ Plan make_plan(const tm_packed_w4* h, int M, int num_cu)
                 // the tallest tile that still gives every CU a CTA (measured at K = N = 8192: M = 1024 runs 131 us on
                 // 256 CTAs of 128 x 256 against 134-139 us on 512 CTAs of 128 x 128; M = 512 is within 5 % on all
                 // of 64 x 128, 64 x 256 and 128 x 128)
+                // below that, the tile with the most rows that still does (a converted fragment feeds one MFMA per
+                // 16 rows of the tile): K = N = 8192 at M = 128 runs 27.2 us on 256 tiles of 64 x 64 against 29.0 us on
+                // 256 tiles of 32 x 128 (same box)
                 if (ctas(kTile128x256) >= num_cu) variant = kTile128x256;
                 else if (ctas(kTile64x128) >= num_cu) variant = kTile64x128;
+                else if (ctas(kTile64x64) >= num_cu) variant = kTile64x64;
                 else variant = kTile32x128;
             }
         }
@@ -375,8 +379,10 @@ Plan make_plan(const tm_packed_w4* h, int M, int num_cu)
         // Wave sets per CTA (each takes its own slice of every stage): short tiles take four (two for the
         // 96-column tiles, whose sets are two waves wide) unless there are two or more CTAs per CU anyway.
         int kg = 1;
-        if (tile_bn(variant) == 96) kg = 2;
-        else if (bm <= 64 && (long)pl.tiles_m * pl.tiles_n * split < 2L * num_cu) kg = 4;
+        if (tile_two_waves(variant)) kg = tile_bn(variant) == 96 ? 2 : 4;
+        // (64-row tiles: two sets with 128-deep stages measured ahead of four sets with 64-deep ones, 40.2 against
+        // 42.0 us at K = N = 8192, M = 256)
+        else if (bm <= 64 && (long)pl.tiles_m * pl.tiles_n * split < 2L * num_cu) kg = bm == 64 ? 2 : 4;
         if (bm <= 64 && kg > 1 && g_force_stage <= 1) steps = 4;
         if (g_force_waves >= 4) kg = g_force_waves * 64 / tile_threads(variant);
         if (!tile_has_kgroups(variant, kg)) kg = tile_has_kgroups(variant, 1) ? 1 : 4;
@@ -1104,6 +1110,8 @@ const char* tm_variant_name(int variant)
         case kTile32x128: return "tile32x128";
         case kTile32x96: return "tile32x96";
         case kTile64x96: return "tile64x96";
+        case kTile64x64: return "tile64x64";
+        case kTile128x64: return "tile128x64";
         default: return "";
     }
 }

@@ -32,7 +32,9 @@ enum Variant {
     kSkinny64x64 = 19,
     kTile32x96 = 20,    // CTA tiles of two waves x three 16-column tiles, always with several wave sets per CTA
     kTile64x96 = 21,
-    kNumVariants = 22
+    kTile64x64 = 22,    // CTA tiles of two waves x two 16-column tiles, with several wave sets per CTA: more rows per
+    kTile128x64 = 23,   // converted fragment where a wider tile would leave compute units without a CTA
+    kNumVariants = 24
 };
 inline bool is_skinny(int v) { return v <= kSkinny32x64 || (v >= kSkinny16x48 && v <= kSkinny64x64); }
 inline int skinny_rows(int v) { return (v == kSkinny32x32 || v == kSkinny32x64) ? 32 : (v >= kSkinny64x32 && v <= kSkinny64x64) ? 64 : 16; }
@@ -48,15 +50,16 @@ inline int skinny_ntw(int v)
         default: return 8;
     }
 }
-inline int tile_bm(int v) { return (v == kTile32x256 || v == kTile32x128 || v == kTile32x96) ? 32 : ((v == kTile64x256 || v == kTile64x128 || v == kTile64x96) ? 64 : ((v == kTile128x256 || v == kTile128x128 || v == kTile128x512) ? 128 : (v == kTile192x256 ? 192 : 256))); }
-inline int tile_threads(int v) { return (v == kTile32x96 || v == kTile64x96) ? 128 : 256; }     // of one wave set
+inline int tile_bm(int v) { return (v == kTile32x256 || v == kTile32x128 || v == kTile32x96) ? 32 : ((v == kTile64x256 || v == kTile64x128 || v == kTile64x96 || v == kTile64x64) ? 64 : ((v == kTile128x256 || v == kTile128x128 || v == kTile128x512 || v == kTile128x64) ? 128 : (v == kTile192x256 ? 192 : 256))); }
+inline bool tile_two_waves(int v) { return v == kTile32x96 || v == kTile64x96 || v == kTile64x64 || v == kTile128x64; }
+inline int tile_threads(int v) { return tile_two_waves(v) ? 128 : 256; }     // of one wave set
 // wave sets per CTA (in-CTA split of every K stage) a tile variant is built with, besides 1
 inline bool tile_has_kgroups(int v, int kg)
 {
-    if (v == kTile32x96 || v == kTile64x96) return kg == 2 || kg == 4;
+    if (tile_two_waves(v)) return kg == 2 || kg == 4;
     return kg == 1 || (kg == 2 && (v == kTile32x128 || v == kTile64x128 || v == kTile128x128)) || (kg == 4 && (v == kTile32x128 || v == kTile64x128));
 }
-inline int tile_bn(int v) { return (v == kTile32x96 || v == kTile64x96) ? 96 : (v == kTile64x128 || v == kTile128x128 || v == kTile32x128) ? 128 : (v == kTile128x512 ? 512 : 256); }
+inline int tile_bn(int v) { return (v == kTile64x64 || v == kTile128x64) ? 64 : (v == kTile32x96 || v == kTile64x96) ? 96 : (v == kTile64x128 || v == kTile128x128 || v == kTile32x128) ? 128 : (v == kTile128x512 ? 512 : 256); }
 
 struct Plan {
     int variant;

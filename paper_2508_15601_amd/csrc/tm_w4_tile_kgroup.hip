@@ -45,6 +45,8 @@ hipError_t launch_tile_kgroup(const GemmParams& p, const Plan& plan, int group, 
             case kTile128x128: return launch_depth_kg<8, 2, 2>(p, plan, group, stream);
             case kTile32x96: return launch_depth_kg<2, 3, 2, 2>(p, plan, group, stream);
             case kTile64x96: return launch_depth_kg<4, 3, 2, 2>(p, plan, group, stream);
+            case kTile64x64: return launch_depth_kg<4, 2, 2, 2>(p, plan, group, stream);
+            case kTile128x64: return launch_depth_kg<8, 2, 2, 2>(p, plan, group, stream);
             default: return hipErrorInvalidValue;
         }
     }
@@ -54,6 +56,8 @@ hipError_t launch_tile_kgroup(const GemmParams& p, const Plan& plan, int group, 
             case kTile64x128: return launch_depth_kg<4, 2, 4>(p, plan, group, stream);
             case kTile32x96: return launch_depth_kg<2, 3, 4, 2>(p, plan, group, stream);
             case kTile64x96: return launch_depth_kg<4, 3, 4, 2>(p, plan, group, stream);
+            case kTile64x64: return launch_depth_kg<4, 2, 4, 2>(p, plan, group, stream);
+            case kTile128x64: return launch_depth_kg<8, 2, 4, 2>(p, plan, group, stream);
             default: return hipErrorInvalidValue;
         }
     }

@@ -144,7 +144,7 @@ def test_gemm_from_layouts(tm, oracle, layout):
 
 # ------------------------------------------------------------------ GEMM: exact special cases
 
-@pytest.mark.parametrize("variant", [-1] + list(range(22)))
+@pytest.mark.parametrize("variant", [-1] + list(range(24)))
 def test_one_hot_rows_return_dequantised_weights_bit_exactly(tm, oracle, variant):
     """X = one-hot rows: a single non-zero product per output, so the fp16-dequantised weight must come back
     exactly; pins layout, nibble order, group indexing and the conversion constants on the device."""
@@ -213,10 +213,11 @@ def test_small_shapes_auto_plan(tm, oracle, M, K, N, g):
                                                  (11, 1, 0), (11, 2, 0), (12, 1, 0), (13, 1, 0), (13, 2, 0),
                                                  (14, 1, 8), (14, 2, 16), (15, 1, 16), (15, 3, 0), (15, 1, 8), (16, 1, 0), (16, 2, 16), (16, 2, 8),
                                                  (17, 1, 0), (17, 2, 0), (18, 1, 0), (18, 3, 0), (19, 1, 0), (19, 2, 0),
-                                                 (20, 1, 0), (20, 2, 0), (21, 1, 0), (21, 3, 0)])
+                                                 (20, 1, 0), (20, 2, 0), (21, 1, 0), (21, 3, 0),
+                                                 (22, 1, 0), (22, 2, 4), (23, 1, 0), (23, 3, 8)])
 @pytest.mark.parametrize("g,stage", [(32, 0), (64, 2), (128, 4), (64, 8)])
 def test_every_variant_and_split(tm, oracle, variant, split, waves, g, stage):
-    M = {0: 13, 1: 9, 2: 16, 3: 29, 4: 32, 5: 30, 6: 50, 8: 300, 9: 70, 11: 200, 12: 130, 13: 33, 14: 7, 15: 16, 16: 11, 17: 40, 18: 64, 19: 57, 20: 30, 21: 60}.get(variant, 150)
+    M = {0: 13, 1: 9, 2: 16, 3: 29, 4: 32, 5: 30, 6: 50, 8: 300, 9: 70, 11: 200, 12: 130, 13: 33, 14: 7, 15: 16, 16: 11, 17: 40, 18: 64, 19: 57, 20: 30, 21: 60, 22: 61, 23: 120}.get(variant, 150)
     tm.tm_set_launch(waves, stage)
     K, N = 1152, 336
     d = _random_problem(variant * 10 + split, M, K, N, g)
@@ -357,7 +358,7 @@ def test_decode_configs_take_the_one_shot_form(tm):
 
 # (variant, waves per CTA): 128-column tiles with two or four sets of four waves, 96-column tiles with two or four
 # sets of two waves; the 128-row tile is built with two sets only
-WAVE_SETS = [(13, 8), (13, 16), (9, 8), (9, 16), (10, 8), (20, 4), (20, 8), (21, 4), (21, 8)]
+WAVE_SETS = [(13, 8), (13, 16), (9, 8), (9, 16), (10, 8), (20, 4), (20, 8), (21, 4), (21, 8), (22, 4), (22, 8), (23, 4), (23, 8)]
 
 
 @pytest.mark.parametrize("variant,waves", WAVE_SETS)
@@ -365,7 +366,7 @@ WAVE_SETS = [(13, 8), (13, 16), (9, 8), (9, 16), (10, 8), (20, 4), (20, 8), (21,
 @pytest.mark.parametrize("g,split", [(32, 1), (64, 2), (128, 1), (128, 3)])
 def test_tile_wave_sets(tm, oracle, variant, waves, stage, g, split):
     """Tile kernels with several wave sets per CTA, each set multiplying its own slice of every K stage."""
-    M = {13: 33, 9: 70, 10: 150, 20: 31, 21: 50}[variant]
+    M = {13: 33, 9: 70, 10: 150, 20: 31, 21: 50, 22: 59, 23: 128}[variant]
     K, N = 1536, 336                         # 12 packed units: whole stages for every depth up to four units
     d = _random_problem(variant * 100 + waves + stage + split, M, K, N, g)
     packed = gu.pack(d, g)
