@@ -276,6 +276,8 @@ Plan make_plan(const tm_packed_w4* h, int M, int num_cu)
                 ntw = 1;
                 strips = NT;
                 split = ceil_div(num_cu, NT);
+                const int max_by_k = KU / 16 > 0 ? KU / 16 : 1;      // every wave of a CTA keeps at least one unit
+                if (split > max_by_k) split = max_by_k;
             } else if (per_cu <= 1 && (size_t)M * h->K * 2 > 256 * 1024) {
                 ntw = 4;
                 strips = ceil_div(NT, ntw);
