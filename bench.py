@@ -1,7 +1,7 @@
 #!/usr/bin/env python3
 """Benchmark of the W4A16 GEMM hot path on one MI355X.
 
-    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload decode|mlp_decode|prefill|sweep|companion|moe|w8|attn|epilogue|layer|pack|copy]
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload decode|mlp_decode|prefill|sweep|shapes|ceiling|companion|moe|w8|attn|epilogue|layer|pack|copy]
                     [--sweep-out FILE] [--no-cpu-baseline] [--no-prefill]
 
 A "step" is one pass of the fused GEMM over every (layer, M) pair of the workload, weights already packed
@@ -639,6 +639,57 @@ CEILING_SHORTLIST = [(0, 256, 1, 0), (1, 1024, 8, 1), (1, 1024, 4, 3), (2, 512, 
                      (4, 512, 2, 1), (8, 256, 2, 1), (8, 256, 1, 1), (16, 256, 1, 1)]
 
 
+# Layer shapes of other published models than the benchmark's (K, N, group): the dispatcher's thresholds were fitted on
+# the benchmark's five configurations, these show what it does elsewhere.  Random codes: timing only.
+OTHER_SHAPES = [("13B qkv", 5120, 15360, 128), ("13B gate_up", 5120, 27648, 128), ("13B down", 13824, 5120, 128),
+                ("8B-GQA qkv", 4096, 6144, 128), ("8B-GQA gate_up", 4096, 28672, 128), ("8B-GQA down", 14336, 4096, 128),
+                ("70B-GQA qkv", 8192, 10240, 128), ("70B down", 28672, 8192, 128), ("7B-28h gate_up", 3584, 37888, 128),
+                ("7B-28h down", 18944, 3584, 128), ("small g64", 2048, 8192, 64)]
+OTHER_MS = (1, 8, 16, 32, 64, 128, 512)
+
+
+def other_shapes_table(tm, torch, wl, iters=50):
+    rows = []
+    for label, K, N, g in OTHER_SHAPES:
+        wbytes = K * N // 2 + 4 * K * N // g
+        copies = max(2, -(-ROTATE_BYTES // wbytes))
+        packed = []
+        for _ in range(copies):
+            qw = torch.randint(-2 ** 31, 2 ** 31 - 1, (K, N // 8), dtype=torch.int32, device="cuda")
+            sc = (torch.rand((K // g, N), device="cuda") * 0.02 + 0.001).to(torch.float16)
+            z = torch.randint(0, 16, (K // g, N), device="cuda").to(torch.float16)
+            packed.append(tm.tm_pack_w4(qw, sc, z, K, N, g))
+            del qw, sc, z
+        for M in OTHER_MS:
+            X = [torch.randn((M, K), device="cuda").to(torch.float16) for _ in range(2)]
+            Y = [torch.empty((M, N), dtype=torch.float16, device="cuda") for _ in range(2)]
+            turn = [0]
+
+            def step():
+                i = turn[0]
+                turn[0] += 1
+                tm.tm_gemm_w4a16(X[i % 2], packed[i % copies], Y[i % 2])
+
+            it = iters if M <= 128 else max(10, iters // 5)
+            ev_ms, _ = time_steps(torch, step, it, 3, graph_steps=it)
+            t = ev_ms / it * 1e-3
+            B, F = wl.algorithmic_bytes(M, K, N, g), wl.flops(M, K, N)
+            hbm_frac, mfma_frac = B / t / 1e9 / HBM_PEAK_GBPS, F / t / 1e12 / MFMA_F16_PEAK_TFLOPS
+            bound = "hbm" if B / (HBM_PEAK_GBPS * 1e9) >= F / (MFMA_F16_PEAK_TFLOPS * 1e12) else "mfma"
+            plan = tm.tm_get_plan(packed[0], M)
+            rows.append({"layer": label, "K": K, "N": N, "group": g, "M": M, "us": t * 1e6, "GBps": B / t / 1e9, "TFLOPs": F / t / 1e12,
+                         "bound": bound, "frac": hbm_frac if bound == "hbm" else mfma_frac, "variant": plan["name"],
+                         "split_k": plan["split_k"], "grid": plan["grid"], "one_shot": plan["one_shot_units_per_wave"]})
+            log(f"{label:15s} {K:6d} x {N:6d} M={M:4d}: {t * 1e6:8.2f} us  {B / t / 1e9:6.0f} GB/s  {F / t / 1e12:7.1f} TF  "
+                f"{100 * rows[-1]['frac']:4.1f} % of the {bound} roofline  {plan['name']} split {plan['split_k']} grid {plan['grid']}"
+                f"{' one-shot' if plan['one_shot_units_per_wave'] else ''}")
+        for pk in packed:
+            pk.close()
+        del packed
+        torch.cuda.empty_cache()
+    return rows
+
+
 def l2_feed_table(tm, torch, iters=20):
     """How fast the compute units can be fed from the L2, apart from HBM: every CTA of a one-CTA-per-CU launch reads the
     whole of a 2 MB buffer (the way every CTA of a GEMM reads all of X), for several amounts of bytes in flight per CU."""
@@ -762,7 +813,7 @@ def main():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=200)
     ap.add_argument("--warmup", type=int, default=20)
-    ap.add_argument("--workload", default="decode", choices=sorted(WORKLOADS) + ["sweep", "ceiling", "copy", "companion", "pack", "moe", "w8", "attn", "epilogue", "layer"])
+    ap.add_argument("--workload", default="decode", choices=sorted(WORKLOADS) + ["sweep", "shapes", "ceiling", "copy", "companion", "pack", "moe", "w8", "attn", "epilogue", "layer"])
     ap.add_argument("--sweep-out", default=None, help="with --workload sweep: write the per-shape table here (JSON)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--ceiling-full", action="store_true", help="with --workload ceiling: sweep every launch shape, not the short list")
@@ -803,6 +854,15 @@ def main():
         print(json.dumps({"metric": "plain copy (counter calibration)", "bytes_read": n, "bytes_written": n,
                           "steps": args.steps, "ms_per_step": ev_ms / args.steps,
                           "GBps_read_plus_write": 2 * n / (ev_ms / args.steps * 1e-3) / 1e9}))
+        return
+
+    if args.workload == "shapes":
+        rows = other_shapes_table(tm, torch, wl, iters=min(args.steps, 50))
+        if args.sweep_out:
+            os.makedirs(os.path.dirname(os.path.abspath(args.sweep_out)), exist_ok=True)
+            json.dump(rows, open(args.sweep_out, "w"), indent=1)
+        print(json.dumps({"metric": "W4A16 GEMM on layer shapes outside the benchmark configurations", "workload": "shapes",
+                          "n_gpus": 1, "data": "synthetic (random codes)", "rows": rows}))
         return
 
     if args.workload == "ceiling":

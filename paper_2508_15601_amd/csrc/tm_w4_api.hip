@@ -282,7 +282,7 @@ Plan make_plan(const tm_packed_w4* h, int M, int num_cu)
                 ntw = 4;
                 strips = ceil_div(NT, ntw);
                 split = ceil_div(num_cu, strips);
-            } else if (per_cu <= 2) {
+            } else if (per_cu <= 3) {
                 ntw = per_cu;
                 strips = num_cu;
             } else {
@@ -429,6 +429,40 @@ Plan make_plan(const tm_packed_w4* h, int M, int num_cu)
                 pl.stream_ni = ni;
                 pl.block = (unsigned)w * 64;
                 break;
+            }
+        }
+    }
+    // Decode layers whose slice of X does not fit the one-shot form as planned (K beyond 8192 at M = 8 ... 16, or more
+    // packed units per wave than a wave can hold): wider strips with K split over two, four or eight CTAs, about one CTA per CU
+    // in all, if the one-shot form fits then.  Each CTA streams a half or a quarter of X, and the one-shot kernels
+    // outrun the ring-buffered ones by more than the merge costs (K = 11008, N = 4096, M = 8: 8.8 against 10.4 us;
+    // K = 14336, N = 4096: 11.1 us at M = 16 this way against 13.1 us at M = 8 without).
+    if (is_skinny(variant) && skinny_rows(variant) == 16 && h->bits == 4 && M <= 16 && pl.stream_ni == 0 && split == 1 &&
+        g_force_variant < 0 && g_force_split == 0 && g_force_stage != 1 && NT <= 2 * num_cu) {
+        int mp_log = 0;
+        while ((1 << mp_log) < M) ++mp_log;
+        for (int sp = 2; sp <= 8 && pl.stream_ni == 0; sp *= 2) {
+            const int ntw = ceil_div(NT * sp, num_cu);
+            const int strips = ceil_div(NT, ntw);
+            if (ntw > 8 || sp > KU || sp > max_split_ws) break;
+            const int kps = ceil_div(KU, sp);
+            const int widest = ceil_div(NT, strips);
+            for (int w : {16, 8}) {
+                const int ni = stream_units_per_wave(widest, h->group, kps, g_force_waves >= 8 ? g_force_waves : w);
+                int red_off;
+                if (ni > 0 && stream_lds(ni, mp_log, widest, g_force_waves >= 8 ? g_force_waves : w, &red_off) <= kStreamLdsBudget) {
+                    pl.variant = widest <= 1 ? kSkinny16x16 : widest <= 2 ? kSkinny16x32 : widest <= 3 ? kSkinny16x48
+                               : widest <= 4 ? kSkinny16x64 : widest <= 6 ? kSkinny16x96 : kSkinny16x128;
+                    variant = pl.variant;
+                    pl.stream_ni = ni;
+                    pl.block = (unsigned)(g_force_waves >= 8 ? g_force_waves : w) * 64;
+                    pl.strips = strips;
+                    pl.tiles_n = strips;
+                    pl.ku_per_split = kps;
+                    split = ceil_div(KU, kps);
+                    pl.split = split;
+                    break;
+                }
             }
         }
     }

@@ -239,7 +239,7 @@ __global__ __launch_bounds__(MAXW * 64) void rows_kernel(GemmParams p)
 // in CTAs of 8 (built only where 16 do not fit), and the reduction needs at most eight column tiles.
 constexpr bool rows_built(int tm, int ntw, int gpu, int ni, int maxw)
 {
-    const int regs = ni * ntw * (4 + gpu) + tm * ntw * 4 + 4 * tm + 3 * ntw + 28;
+    const int regs = ni * ntw * (4 + gpu) + tm * ntw * 4 + 4 * tm + 3 * ntw + 24;
     // four row tiles: the two slot arrays of 16 waves would need 256 KiB of LDS, so CTAs of 8 waves only
     if (tm == 4) return ntw <= 8 && gpu <= 2 && maxw == 8 && regs <= 250;
     return ntw <= 8 && gpu <= 2 && (maxw == 16 ? regs <= 128 : (regs > 128 && regs <= 250));

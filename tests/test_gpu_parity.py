@@ -69,6 +69,40 @@ def test_pack_bit_exact_against_oracle_unpack(tm, oracle, K, N, g):
         packed.close()
 
 
+def test_pack_round_trips_on_random_shapes(tm, oracle):
+    """Sixteen shapes drawn at random (K a multiple of 128 up to 2048, N a multiple of 16 up to 1264, every group size,
+    every interchange layout): the oracle's inverse of the library layout returns the codes, and the library's own
+    inverse returns the canonical words."""
+    import torch
+    rng = np.random.default_rng(2024)
+    for it in range(16):
+        g = int(rng.choice([32, 64, 128]))
+        K = 128 * int(rng.integers(1, 17))
+        N = 16 * int(rng.integers(1, 80))
+        layout = int(rng.integers(0, 3))
+        if layout != 0:
+            N = max(N // 16 * 16, 16)
+        _say(f"random pack #{it}: K={K} N={N} g={g} layout={layout}")
+        q = rng.integers(0, 16, (K, N), dtype=np.uint8)
+        s = rng.uniform(0.001, 0.02, (K // g, N)).astype(np.float16)
+        z = rng.integers(0, 16, (K // g, N)).astype(np.float16)
+        if layout == 0:
+            packed = gu.pack({"q": q, "qweight": wl.pack_interchange(q), "s": s, "z": z}, g)
+        else:
+            if N % 8:
+                continue
+            qw, zs = wl.encode_layout(q, z, layout)
+            packed = tm.tm_pack_w4_layout(torch.from_numpy(qw.view(np.int32)).cuda(), gu.to_dev(s),
+                                          torch.from_numpy(zs.view(np.int32)).cuda(), K, N, g, layout)
+        wbuf, szbuf = tm.tm_packed_raw(packed)
+        q2, s2, z2 = oracle.unpack_packed(wbuf, szbuf, K, N, g)
+        assert np.array_equal(q2, q)
+        assert np.array_equal(s2.view(np.uint16), s.view(np.uint16)) and np.array_equal(z2.view(np.uint16), z.view(np.uint16))
+        qw2, _, _ = tm.tm_unpack_w4(packed)
+        assert np.array_equal(qw2.cpu().numpy().view(np.uint32), wl.pack_interchange(q))
+        packed.close()
+
+
 @pytest.mark.parametrize("layout", [0, 1, 2])
 @pytest.mark.parametrize("K,N,g", [(128, 16, 128), (256, 48, 32), (384, 2064, 64), (1024, 272, 128)])
 def test_pack_layouts_bit_exact(tm, oracle, K, N, g, layout):
@@ -273,7 +307,7 @@ def _x_ring_built(M, ntw, g, kus, NT):
         ni = next((b for b in (1, 2, 3, 4, 6, 8) if b >= -(-kus // waves)), None)
         if ni is None:
             continue
-        regs = ni * ntw * (4 + gpu) + tm_rows * ntw * 4 + 4 * tm_rows + 3 * ntw + 28
+        regs = ni * ntw * (4 + gpu) + tm_rows * ntw * 4 + 4 * tm_rows + 3 * ntw + 24
         if (regs <= 128 if waves == 16 else (regs <= 250 if tm_rows == 4 else 128 < regs <= 250)):
             return True
     return False
@@ -342,10 +376,12 @@ def test_x_ring_form_is_taken_and_exact(tm, oracle):
 
 
 def test_decode_configs_take_the_one_shot_form(tm):
-    """The benchmark's decode layers (M <= 16 at K = 4096 and 8192; K = 11008 at M = 1) run the one-shot kernels."""
+    """The benchmark's decode layers (M <= 16) and deep or narrow layers of other models run the one-shot kernels."""
     import torch
     for K, N, g, Ms in ((4096, 4096, 128, (1, 16)), (4096, 12288, 128, (1, 16)), (4096, 22016, 128, (1, 16)),
-                        (11008, 4096, 128, (1,)), (8192, 8192, 64, (1, 8))):
+                        (11008, 4096, 128, (1, 8, 16)), (8192, 8192, 64, (1, 8, 16)),
+                        # layers of other models: deep K, or fewer column tiles than compute units (K split across CTAs)
+                        (13824, 5120, 128, (1, 16)), (18944, 3584, 128, (1, 16))):
         qw = torch.zeros((K, N // 8), dtype=torch.int32, device="cuda")
         s = torch.ones((K // g, N), dtype=torch.float16, device="cuda")
         packed = tm.tm_pack_w4(qw, s, None, K, N, g)
