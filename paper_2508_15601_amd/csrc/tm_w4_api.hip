@@ -282,7 +282,7 @@ Plan make_plan(const tm_packed_w4* h, int M, int num_cu)
                 ntw = 4;
                 strips = ceil_div(NT, ntw);
                 split = ceil_div(num_cu, strips);
-            } else if (per_cu <= 3) {
+            } else if (per_cu <= 4) {
                 ntw = per_cu;
                 strips = num_cu;
             } else {
