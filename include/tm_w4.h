@@ -116,8 +116,8 @@ TM_API tm_packed_w4* tm_pack_w4_actorder(const void* qweight, const uint16_t* sc
  * of the weight width (Sec. 3.3, Sec. 4.1).  qweight is u32 [K][N/4], byte t (bits 8t..8t+7) of word (k, j) =
  * q[k][4j + t], codes 0..255; scales fp16 [K/group][N]; zeros fp16 [K/group][N], integer-valued in [0, 255], or NULL for
  * the symmetric zero-point 128.  Shapes, groups, alignment, ownership and errors as for tm_pack_w4_on.  The handle works
- * with tm_gemm_w4a16 / tm_gemm_w4a16_ws, tm_packed_info, tm_packed_raw, tm_get_plan and tm_free_packed; tm_unpack_w4 and
- * tm_group_experts take 4-bit handles only (TM_EUNSUPPORTED).
+ * with tm_gemm_w4a16 / tm_gemm_w4a16_ws, tm_packed_info, tm_packed_raw, tm_get_plan, tm_free_packed and
+ * tm_group_experts (all experts of a group in one format); tm_unpack_w4 takes 4-bit handles only (TM_EUNSUPPORTED).
  *
  * Packed layout: units of 16 columns x 64 rows (1 KiB); unit (nt, ks) is the 256 words from ((nt*(K/64))+ks)*256;
  * word 4*lane + 2*tt + hf (lane = 16*h + c, tt, hf in 0..1) holds column 16*nt + c, rows 64*ks + 32*tt + 8*h + 4*hf + b
@@ -226,7 +226,7 @@ TM_API void tm_free_packed(tm_packed_w4* packed);
  *     Y[r][:] = X[r][:] * dequant(expert e),   offsets[e] <= r < offsets[e+1],   e = 0 .. num_experts-1
  *
  * tm_group_experts (offline, once per layer): `experts` is a HOST array of num_experts handles (1..65535) with equal
- * K, N, group and device; it allocates a small device table of their buffer addresses (synchronous copy).  The group
+ * K, N, group, device and weight format (4-bit, 8-bit integer or FP8 codes; not activation-order handles); it allocates a small device table of their buffer addresses (synchronous copy).  The group
  * borrows the handles: they must outlive it.  Returns NULL on error.  tm_free_expert_group releases the table only.
  *
  * tm_gemm_w4a16_grouped (online): X fp16 [total_rows][K], Y fp16 [total_rows][N], both 16-byte aligned; offsets is a

@@ -140,6 +140,8 @@ struct tm_expert_group {
     uint32_t magic;
     int experts, K, N, group, device;
     bool gate_up;      // every expert is a gate/up handle with interleaved columns
+    int bits;          // 4 or 8 bits per code, the same for every expert
+    bool fp8;          // 8-bit codes are FP8 E4M3 values
     uint64_t* table;   // device: per expert, address of the packed weights and of the scale/zero words
 };
 
@@ -829,8 +831,12 @@ tm_expert_group* tm_group_experts(const tm_packed_w4* const* experts, int num_ex
             fail(TM_EINVAL, "expert %d: handle is null or invalid", e);
             return nullptr;
         }
-        if (experts[e]->bits != 4 || experts[e]->perm) {
-            fail(TM_EUNSUPPORTED, "expert %d: grouped GEMM takes 4-bit weights in plain row order only", e);
+        if (experts[e]->perm) {
+            fail(TM_EUNSUPPORTED, "expert %d: grouped GEMM takes weights in plain row order only", e);
+            return nullptr;
+        }
+        if (experts[e]->bits != experts[0]->bits || experts[e]->fp8 != experts[0]->fp8) {
+            fail(TM_EINVAL, "expert %d differs from expert 0 in weight format", e);
             return nullptr;
         }
         if (experts[e]->gate_up != experts[0]->gate_up) {
@@ -873,6 +879,8 @@ tm_expert_group* tm_group_experts(const tm_packed_w4* const* experts, int num_ex
     g->experts = num_experts;
     g->K = experts[0]->K;
     g->gate_up = experts[0]->gate_up;
+    g->bits = experts[0]->bits;
+    g->fp8 = experts[0]->fp8;
     g->N = experts[0]->N;
     g->group = experts[0]->group;
     g->device = dev;
@@ -912,7 +920,7 @@ static int run_grouped(const uint16_t* X, const tm_expert_group* group, const in
     gp.offsets = offsets;
     gp.K = group->K;
     gp.N = group->N;
-    gp.KU = group->K / kUnitK;
+    gp.KU = group->bits == 8 ? group->K / 64 : group->K / kUnitK;
     gp.NT = group->N / kUnitN;
     gp.G = group->K / group->group;
     gp.strips = strips;
@@ -923,9 +931,15 @@ static int run_grouped(const uint16_t* X, const tm_expert_group* group, const in
     gp.act = act == TM_ACT_SILU_MUL ? 1 : 0;
     if (!is_skinny(variant) && (uint64_t)total_rows * (uint64_t)group->K >= (1ull << 31))
         return fail(TM_EINVAL, "total_rows*K must be below 2^31 for prefill-sized expert loads");
-    hipError_t e = is_skinny(variant)
-                       ? launch_skinny_grouped(gp, variant, group->experts, group->group, (hipStream_t)stream)
-                       : launch_tile_grouped(gp, variant, group->experts, group->group, (hipStream_t)stream);
+    hipError_t e;
+    if (group->bits == 8) {
+        e = !is_skinny(variant) ? launch_tile_grouped_8bit(gp, variant, group->experts, group->group, group->fp8, (hipStream_t)stream)
+            : group->fp8       ? launch_skinny_grouped_f8(gp, variant, group->experts, group->group, (hipStream_t)stream)
+                               : launch_skinny_grouped_w8(gp, variant, group->experts, group->group, (hipStream_t)stream);
+    } else {
+        e = is_skinny(variant) ? launch_skinny_grouped(gp, variant, group->experts, group->group, (hipStream_t)stream)
+                               : launch_tile_grouped(gp, variant, group->experts, group->group, (hipStream_t)stream);
+    }
     if (e != hipSuccess) return fail_hip(e, "grouped kernel launch");
     return TM_OK;
 }

@@ -113,6 +113,9 @@ hipError_t launch_skinny_f8(const GemmParams& p, const Plan& plan, int group, hi
 hipError_t launch_skinny_grouped(const GroupedParams& gp, int variant, int experts, int group, hipStream_t stream);
 hipError_t launch_tile_8bit(const GemmParams& p, const Plan& plan, int group, bool fp8, hipStream_t stream);
 hipError_t launch_tile_grouped(const GroupedParams& gp, int variant, int experts, int group, hipStream_t stream);
+hipError_t launch_skinny_grouped_w8(const GroupedParams& gp, int variant, int experts, int group, hipStream_t stream);
+hipError_t launch_skinny_grouped_f8(const GroupedParams& gp, int variant, int experts, int group, hipStream_t stream);
+hipError_t launch_tile_grouped_8bit(const GroupedParams& gp, int variant, int experts, int group, bool fp8, hipStream_t stream);
 hipError_t launch_tile(const GemmParams& p, const Plan& plan, int group, hipStream_t stream);
 hipError_t launch_tile_small(const GemmParams& p, const Plan& plan, int group, hipStream_t stream);
 hipError_t launch_tile_large(const GemmParams& p, const Plan& plan, int group, hipStream_t stream);

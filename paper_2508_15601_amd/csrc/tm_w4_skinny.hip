@@ -13,37 +13,9 @@
 
 namespace tmw4 {
 
-namespace {
-
-template <int TM, int NTW, int D128, int DSMALL>
-hipError_t launch_grouped_cfg(const GroupedParams& gp, int experts, int group, hipStream_t stream)
-{
-    dim3 grid(gp.strips, gp.total_rows < experts ? gp.total_rows : experts), block(512);
-    size_t lds = (size_t)8 * NTW * 4 * 64 * sizeof(float);
-    switch (group) {
-        case 128: hipLaunchKernelGGL((skinny_grouped_kernel<TM, NTW, 1, D128, 8>), grid, block, lds, stream, gp); break;
-        case 64: hipLaunchKernelGGL((skinny_grouped_kernel<TM, NTW, 2, DSMALL, 8>), grid, block, lds, stream, gp); break;
-        case 32: hipLaunchKernelGGL((skinny_grouped_kernel<TM, NTW, 4, DSMALL, 8>), grid, block, lds, stream, gp); break;
-        default: return hipErrorInvalidValue;
-    }
-    return hipGetLastError();
-}
-
-}  // namespace
-
-// Eight-wave CTAs only: with one grid row per expert there are several CTAs per CU to overlap.
 hipError_t launch_skinny_grouped(const GroupedParams& gp, int variant, int experts, int group, hipStream_t stream)
 {
-    if (experts <= 0 || experts > 65535 || gp.strips <= 0) return hipErrorInvalidValue;
-    switch (variant) {
-        case kSkinny16x16: return launch_grouped_cfg<1, 1, 4, 4>(gp, experts, group, stream);
-        case kSkinny16x32: return launch_grouped_cfg<1, 2, 4, 4>(gp, experts, group, stream);
-        case kSkinny16x64: return launch_grouped_cfg<1, 4, 2, 2>(gp, experts, group, stream);
-        case kSkinny16x128: return launch_grouped_cfg<1, 8, 2, 1>(gp, experts, group, stream);
-        case kSkinny32x64: return launch_grouped_cfg<2, 4, 2, 2>(gp, experts, group, stream);
-        case kSkinny64x64: return launch_grouped_cfg<4, 4, 1, 1>(gp, experts, group, stream);
-        default: return hipErrorInvalidValue;
-    }
+    return launch_skinny_grouped_fmt<4>(gp, variant, experts, group, stream);
 }
 
 hipError_t launch_skinny(const GemmParams& p, const Plan& plan, int group, hipStream_t stream)

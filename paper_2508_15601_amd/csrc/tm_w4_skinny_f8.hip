@@ -9,4 +9,9 @@ hipError_t launch_skinny_f8(const GemmParams& p, const Plan& plan, int group, hi
     return launch_skinny_8bit<kFmtFp8>(p, plan, group, stream);
 }
 
+hipError_t launch_skinny_grouped_f8(const GroupedParams& gp, int variant, int experts, int group, hipStream_t stream)
+{
+    return launch_skinny_grouped_fmt<kFmtFp8>(gp, variant, experts, group, stream);
+}
+
 }  // namespace tmw4

@@ -301,7 +301,7 @@ __global__ __launch_bounds__(MAXW * 64) void skinny_kernel(GemmParams p)
 // are this same GEMM once per expert): rows [offsets[e], offsets[e+1]) of X and Y belong to expert e, whose packed
 // weights the pointer table names.  blockIdx.x is the strip, blockIdx.y selects among the experts that have rows.
 // Experts with more than 16*TM rows are taken 16*TM rows at a time.
-template <int TM, int NTW, int GPU, int D, int MAXW>
+template <int TM, int NTW, int GPU, int D, int MAXW, int BITS = 4>
 __global__ __launch_bounds__(MAXW * 64) void skinny_grouped_kernel(GroupedParams gp)
 {
     extern __shared__ float red[];
@@ -367,7 +367,7 @@ __global__ __launch_bounds__(MAXW * 64) void skinny_grouped_kernel(GroupedParams
         p.X = gp.X + (size_t)m0 * gp.K;
         p.Y = gp.Y + (size_t)m0 * p.ldy;
         p.M = min(16 * TM, r1 - m0);
-        skinny_body<TM, NTW, GPU, D, 4>(p, blockIdx.x, 0, red, s_last);
+        skinny_body<TM, NTW, GPU, D, BITS>(p, blockIdx.x, 0, red, s_last);
     }
 }
 
@@ -386,6 +386,36 @@ hipError_t launch_cfg(const GemmParams& p, const Plan& plan, int group, hipStrea
         default: return hipErrorInvalidValue;
     }
     return hipGetLastError();
+}
+
+template <int TM, int NTW, int D128, int DSMALL, int BITS = 4>
+hipError_t launch_grouped_cfg(const GroupedParams& gp, int experts, int group, hipStream_t stream)
+{
+    dim3 grid(gp.strips, gp.total_rows < experts ? gp.total_rows : experts), block(512);
+    size_t lds = (size_t)8 * NTW * 4 * 64 * sizeof(float);
+    switch (group) {
+        case 128: hipLaunchKernelGGL((skinny_grouped_kernel<TM, NTW, 1, D128, 8, BITS>), grid, block, lds, stream, gp); break;
+        case 64: hipLaunchKernelGGL((skinny_grouped_kernel<TM, NTW, 2, DSMALL, 8, BITS>), grid, block, lds, stream, gp); break;
+        case 32: hipLaunchKernelGGL((skinny_grouped_kernel<TM, NTW, 4, DSMALL, 8, BITS>), grid, block, lds, stream, gp); break;
+        default: return hipErrorInvalidValue;
+    }
+    return hipGetLastError();
+}
+
+// Eight-wave CTAs only: with one grid row per expert there are several CTAs per CU to overlap.
+template <int BITS>
+hipError_t launch_skinny_grouped_fmt(const GroupedParams& gp, int variant, int experts, int group, hipStream_t stream)
+{
+    if (experts <= 0 || experts > 65535 || gp.strips <= 0) return hipErrorInvalidValue;
+    switch (variant) {
+        case kSkinny16x16: return launch_grouped_cfg<1, 1, 4, 4, BITS>(gp, experts, group, stream);
+        case kSkinny16x32: return launch_grouped_cfg<1, 2, 4, 4, BITS>(gp, experts, group, stream);
+        case kSkinny16x64: return launch_grouped_cfg<1, 4, 2, 2, BITS>(gp, experts, group, stream);
+        case kSkinny16x128: return launch_grouped_cfg<1, 8, 2, BITS == 4 ? 1 : 2, BITS>(gp, experts, group, stream);
+        case kSkinny32x64: return launch_grouped_cfg<2, 4, 2, 2, BITS>(gp, experts, group, stream);
+        case kSkinny64x64: return launch_grouped_cfg<4, 4, BITS == 4 ? 1 : 2, 1, BITS>(gp, experts, group, stream);
+        default: return hipErrorInvalidValue;
+    }
 }
 
 // The strip widths the dispatcher uses for the 8-bit formats (BITS = kFmtInt8 or kFmtFp8).

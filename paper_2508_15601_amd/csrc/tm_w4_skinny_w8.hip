@@ -9,4 +9,9 @@ hipError_t launch_skinny_w8(const GemmParams& p, const Plan& plan, int group, hi
     return launch_skinny_8bit<kFmtInt8>(p, plan, group, stream);
 }
 
+hipError_t launch_skinny_grouped_w8(const GroupedParams& gp, int variant, int experts, int group, hipStream_t stream)
+{
+    return launch_skinny_grouped_fmt<kFmtInt8>(gp, variant, experts, group, stream);
+}
+
 }  // namespace tmw4

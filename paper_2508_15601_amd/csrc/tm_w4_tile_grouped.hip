@@ -8,7 +8,7 @@ namespace tmw4 {
 
 namespace {
 
-template <int TM, int TN, int NW, int GPU, int KW, int PD = (TM <= 8 ? 2 : 1)>
+template <int TM, int TN, int NW, int GPU, int KW, int FMT = kFmtInt4, int PD = (TM <= 8 ? 2 : 1)>
 __global__ __launch_bounds__(NW * 64) void tile_grouped_kernel(GroupedParams gp)
 {
     constexpr int BM = TM * 16;
@@ -86,14 +86,15 @@ __global__ __launch_bounds__(NW * 64) void tile_grouped_kernel(GroupedParams gp)
     p.ku_per_split = gp.KU;
     p.tiles_m = (p.M + BM - 1) / BM;
     p.tiles_n = gp.tiles_n;
-    tile_body<TM, TN, NW, GPU, KW, PD, 1>(p, tile_m, tile_n, 0);
+    tile_body<TM, TN, NW, GPU, KW, PD, 1, FMT>(p, tile_m, tile_n, 0);
 }
 
-template <int TM, int TN, int KW>
+template <int TM, int TN, int KW, int FMT = kFmtInt4>
 hipError_t launch_grouped_shape(GroupedParams gp, int experts, int group, hipStream_t stream)
 {
     constexpr int BM = TM * 16, BN = 4 * TN * 16;
-    if ((gp.KU * 4) % KW) return hipErrorInvalidValue;                       // whole stages
+    constexpr int SPU = FMT == kFmtInt4 ? 4 : 2;                             // MFMA steps per packed unit
+    if ((gp.KU * SPU) % KW) return hipErrorInvalidValue;                     // whole stages
     if ((uint64_t)gp.total_rows * (uint64_t)gp.K >= (1ull << 31)) return hipErrorInvalidValue;   // 32-bit X offsets
     gp.tiles_n = (gp.N + BN - 1) / BN;
     // every expert with rows adds at most one partly filled row tile
@@ -102,9 +103,9 @@ hipError_t launch_grouped_shape(GroupedParams gp, int experts, int group, hipStr
     if (tiles <= 0 || tiles > (1l << 30)) return hipErrorInvalidValue;
     dim3 grid((unsigned)(((tiles + 7) / 8) * 8)), block(256);
     switch (group) {
-        case 128: hipLaunchKernelGGL((tile_grouped_kernel<TM, TN, 4, 1, KW>), grid, block, 0, stream, gp); break;
-        case 64: hipLaunchKernelGGL((tile_grouped_kernel<TM, TN, 4, 2, KW>), grid, block, 0, stream, gp); break;
-        case 32: hipLaunchKernelGGL((tile_grouped_kernel<TM, TN, 4, 4, KW>), grid, block, 0, stream, gp); break;
+        case 128: hipLaunchKernelGGL((tile_grouped_kernel<TM, TN, 4, 1, KW, FMT>), grid, block, 0, stream, gp); break;
+        case 64: hipLaunchKernelGGL((tile_grouped_kernel<TM, TN, 4, 2, KW, FMT>), grid, block, 0, stream, gp); break;
+        case 32: hipLaunchKernelGGL((tile_grouped_kernel<TM, TN, 4, 4, KW, FMT>), grid, block, 0, stream, gp); break;
         default: return hipErrorInvalidValue;
     }
     return hipGetLastError();
@@ -118,6 +119,21 @@ hipError_t launch_tile_grouped(const GroupedParams& gp, int variant, int experts
     switch (variant) {
         case kTile64x128: return launch_grouped_shape<4, 2, 4>(gp, experts, group, stream);
         case kTile128x256: return launch_grouped_shape<8, 4, 2>(gp, experts, group, stream);
+        default: return hipErrorInvalidValue;
+    }
+}
+
+// The 8-bit formats (integer codes, FP8 E4M3): the same two tile shapes.
+hipError_t launch_tile_grouped_8bit(const GroupedParams& gp, int variant, int experts, int group, bool fp8, hipStream_t stream)
+{
+    if (experts <= 0) return hipErrorInvalidValue;
+    switch (variant) {
+        case kTile64x128:
+            return fp8 ? launch_grouped_shape<4, 2, 4, kFmtFp8>(gp, experts, group, stream)
+                       : launch_grouped_shape<4, 2, 4, kFmtInt8>(gp, experts, group, stream);
+        case kTile128x256:
+            return fp8 ? launch_grouped_shape<8, 4, 2, kFmtFp8>(gp, experts, group, stream)
+                       : launch_grouped_shape<8, 4, 2, kFmtInt8>(gp, experts, group, stream);
         default: return hipErrorInvalidValue;
     }
 }
