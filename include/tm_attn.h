@@ -19,7 +19,9 @@
  *
  * Conventions as in tm_w4.h: plain C ABI, DEVICE pointers unless marked host, fp16 as uint16_t bit patterns, nothing
  * synchronises, work is enqueued on the given stream, negative tm_status codes with tm_last_error().
- * Head dimension is 128.  Grouped-query attention: q_heads = G * kv_heads, 1 <= G <= 16.
+ * Head dimension is 128.  Grouped-query attention: q_heads = G * kv_heads, 1 <= G <= 128 (a KV head's G query heads are
+ * taken sixteen at a time - the sixteen columns of a matrix-core tile - in passes that follow each other on the stream;
+ * up to G = 16 that is one pass).
  */
 #ifndef TM_ATTN_H
 #define TM_ATTN_H
@@ -86,7 +88,7 @@ TM_API int tm_attn_decode(const uint16_t* Q, const tm_kv_cache* cache, const int
  * stream).  counts (int32 [batch], device, or NULL = every sequence has `count` tokens) gives the query tokens each
  * sequence really has, so that prompts of different lengths share one call: rows i >= counts[b] of O, and rows whose
  * position falls outside [0, capacity), are left untouched.  q_heads and scale as for tm_attn_decode; 1 <= count <= 65535
- * * (16 / (q_heads / kv_heads)).  One CTA takes 16 / (q_heads / kv_heads) consecutive tokens of one KV head and streams
+ * * (16 / min(G, 16)), G = q_heads / kv_heads.  One CTA takes 16 / min(G, 16) consecutive tokens of one KV head and streams
  * the cache up to the last of them; the context is not split, so a short chunk far into a long context is served by few
  * CTAs (use tm_attn_decode per token there).  Never allocates, uses no workspace, results are bit-identical from run to
  * run.

@@ -717,8 +717,8 @@ template <int BITS, bool PACK, bool PREFILL = false>
 __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))) void attn_decode_kernel(AttnCache kv, const uint16_t* __restrict__ Q,
                                                           const int32_t* __restrict__ lens, uint16_t* __restrict__ O,
                                                           int q_heads, float scale_log2e, int blocks_per_split,
-                                                          int splits, int merge_here, const int32_t* __restrict__ counts = nullptr,
-                                                          int count = 1)
+                                                          int splits, int merge_here, int head0, int gw,
+                                                          const int32_t* __restrict__ counts = nullptr, int count = 1)
 {
     static_assert(!(PREFILL && PACK), "prompt chunks use all 16 query columns");
     __shared__ float sm_ml[4][2][16];
@@ -733,7 +733,11 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))) voi
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int c = lane & 15, h = lane >> 4;
     const int hk = blockIdx.x, b = blockIdx.y, split = blockIdx.z;
-    const int G = q_heads / kv.heads;
+    // A launch covers query heads head0 .. head0 + gw - 1 (gw <= 16) of every KV head's group of q_heads / kv.heads:
+    // larger groups take one launch per sixteen heads.  G is the width the columns are laid out for, hq the first query
+    // head of this CTA.
+    const int G = gw;
+    const int hq = hk * (q_heads / kv.heads) + head0;
     const size_t bh = (size_t)b * kv.heads + hk;
     int len, len_all;                                        // this lane's column; the CTA's longest column
     int tok = 0, head = c;                                   // query token (within the chunk) and head (within G) of column c
@@ -769,7 +773,7 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))) voi
     f16x8 qraw[4];
     {
         const size_t qrow = PREFILL ? (size_t)b * count + tok : (size_t)b;
-        const uint16_t* qp = Q + (qrow * q_heads + (size_t)hk * G + (real ? qc : 0)) * kHeadDim + 32 * h;
+        const uint16_t* qp = Q + (qrow * q_heads + (size_t)hq + (real ? qc : 0)) * kHeadDim + 32 * h;
 #pragma unroll
         for (int tt = 0; tt < 4; ++tt) qraw[tt] = *(const f16x8*)(qp + 8 * tt);
     }
@@ -882,9 +886,9 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))) voi
                 o[rr] = v * inv;
             }
             if constexpr (PREFILL) {
-                if (real) store_out4(O, b * count + tok, q_heads, hk * G + head, 16 * i + 4 * h, o);
+                if (real) store_out4(O, b * count + tok, q_heads, hq + head, 16 * i + 4 * h, o);
             } else {
-                if (c < G) store_out4(O, b, q_heads, hk * G + c, 16 * i + 4 * h, o);
+                if (c < G) store_out4(O, b, q_heads, hq + c, 16 * i + 4 * h, o);
             }
         }
         return;
@@ -955,7 +959,7 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))) voi
     for (int ii = 0; ii < 2; ++ii) {
 #pragma unroll
         for (int rr = 0; rr < 4; ++rr) o[ii][rr] *= invg;
-        if (c < G) store_out4(O, b, q_heads, hk * G + c, 16 * (2 * wave + ii) + 4 * h, o[ii]);
+        if (c < G) store_out4(O, b, q_heads, hq + c, 16 * (2 * wave + ii) + 4 * h, o[ii]);
     }
     if (tid == 0) __hip_atomic_store(&kv.counters[bh], 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
 }
@@ -964,12 +968,14 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))) voi
 // Phase 1 (every CTA, all threads): running maximum and denominator over the splits, four splits per thread, reduced
 // through LDS; the per-split factors exp2(m_s - M) / L stay in LDS.  Phase 2: thread (m, dd) sums dimension
 // 16*chunk + dd of query head m over the splits.
-__global__ __launch_bounds__(256) void attn_merge_kernel(AttnCache kv, uint16_t* __restrict__ O, int q_heads, int splits)
+__global__ __launch_bounds__(256) void attn_merge_kernel(AttnCache kv, uint16_t* __restrict__ O, int q_heads, int splits,
+                                                         int head0, int gw)
 {
     __shared__ float red[16][16];
     __shared__ float fac[64][16];                  // splits <= 64
     const int hk = blockIdx.x, b = blockIdx.y, chunk = blockIdx.z;
-    const int G = q_heads / kv.heads;
+    const int G = gw;
+    const int hq = hk * (q_heads / kv.heads) + head0;
     const size_t bh = (size_t)b * kv.heads + hk;
     const float* base = kv.partial + (size_t)bh * splits * kPartialFloats;
     const int m = threadIdx.x & 15, g = threadIdx.x >> 4;
@@ -1008,7 +1014,7 @@ __global__ __launch_bounds__(256) void attn_merge_kernel(AttnCache kv, uint16_t*
     float v = 0.f;
 #pragma unroll 8
     for (int s = 0; s < splits; ++s) v += ld_partial(base + (size_t)s * kPartialFloats + at) * fac[s][m];
-    O[((size_t)b * q_heads + (size_t)hk * G + m) * kHeadDim + d] = f32_to_f16_bits(v * inv);
+    O[((size_t)b * q_heads + (size_t)hq + m) * kHeadDim + d] = f32_to_f16_bits(v * inv);
 }
 
 }  // namespace
@@ -1069,41 +1075,56 @@ hipError_t launch_attn_decode(const AttnCache& kv, const uint16_t* Q, const int3
     // eight CTAs
     const int merge_here = splits > 1 && splits <= kMergeHere;
     const dim3 grid(kv.heads, kv.batch, splits);
-    const bool pack = q_heads / kv.heads <= 8;               // both score tiles share one softmax pass
-    if (kv.bits == 8 && pack)
-        hipLaunchKernelGGL((attn_decode_kernel<8, true>), grid, dim3(256), 0, stream, kv, Q, lens, O, q_heads, scale_log2e, bps,
-                           splits, merge_here);
-    else if (kv.bits == 8)
-        hipLaunchKernelGGL((attn_decode_kernel<8, false>), grid, dim3(256), 0, stream, kv, Q, lens, O, q_heads, scale_log2e, bps,
-                           splits, merge_here);
-    else if (pack)
-        hipLaunchKernelGGL((attn_decode_kernel<4, true>), grid, dim3(256), 0, stream, kv, Q, lens, O, q_heads, scale_log2e, bps,
-                           splits, merge_here);
-    else
-        hipLaunchKernelGGL((attn_decode_kernel<4, false>), grid, dim3(256), 0, stream, kv, Q, lens, O, q_heads, scale_log2e, bps,
-                           splits, merge_here);
-    hipError_t e = hipGetLastError();
-    if (e != hipSuccess || splits == 1 || merge_here) return e;
-    hipLaunchKernelGGL(attn_merge_kernel, dim3(kv.heads, kv.batch, 8), dim3(256), 0, stream, kv, O, q_heads, splits);
-    return hipGetLastError();
+    // one pass per sixteen query heads of a KV head's group (the sixteen columns of an MFMA tile); the passes follow
+    // each other on the stream and share the cache's split workspace
+    const int group = q_heads / kv.heads;
+    for (int head0 = 0; head0 < group; head0 += 16) {
+        const int gw = group - head0 < 16 ? group - head0 : 16;
+        const bool pack = gw <= 8;                           // both score tiles share one softmax pass
+        if (kv.bits == 8 && pack)
+            hipLaunchKernelGGL((attn_decode_kernel<8, true>), grid, dim3(256), 0, stream, kv, Q, lens, O, q_heads, scale_log2e,
+                               bps, splits, merge_here, head0, gw);
+        else if (kv.bits == 8)
+            hipLaunchKernelGGL((attn_decode_kernel<8, false>), grid, dim3(256), 0, stream, kv, Q, lens, O, q_heads, scale_log2e,
+                               bps, splits, merge_here, head0, gw);
+        else if (pack)
+            hipLaunchKernelGGL((attn_decode_kernel<4, true>), grid, dim3(256), 0, stream, kv, Q, lens, O, q_heads, scale_log2e,
+                               bps, splits, merge_here, head0, gw);
+        else
+            hipLaunchKernelGGL((attn_decode_kernel<4, false>), grid, dim3(256), 0, stream, kv, Q, lens, O, q_heads, scale_log2e,
+                               bps, splits, merge_here, head0, gw);
+        hipError_t e = hipGetLastError();
+        if (e != hipSuccess) return e;
+        if (splits > 1 && !merge_here) {
+            hipLaunchKernelGGL(attn_merge_kernel, dim3(kv.heads, kv.batch, 8), dim3(256), 0, stream, kv, O, q_heads, splits, head0, gw);
+            e = hipGetLastError();
+            if (e != hipSuccess) return e;
+        }
+    }
+    return hipSuccess;
 }
 
 hipError_t launch_attn_prefill(const AttnCache& kv, const uint16_t* Q, const int32_t* positions, const int32_t* counts,
                                int count, uint16_t* O, int q_heads, float scale, hipStream_t stream)
 {
-    const int G = q_heads / kv.heads;
-    const int tpg = 16 / G;                                  // query tokens per CTA
-    const int groups = (count + tpg - 1) / tpg;
-    if (kv.heads > 65535 || kv.batch > 65535 || groups > 65535 || groups < 1) return hipErrorInvalidValue;
+    const int group = q_heads / kv.heads;
     const float scale_log2e = scale * 1.4426950408889634f;
-    const dim3 grid(kv.heads, kv.batch, groups);
-    if (kv.bits == 8)
-        hipLaunchKernelGGL((attn_decode_kernel<8, false, true>), grid, dim3(256), 0, stream, kv, Q, positions, O, q_heads,
-                           scale_log2e, 0, 1, 0, counts, count);
-    else
-        hipLaunchKernelGGL((attn_decode_kernel<4, false, true>), grid, dim3(256), 0, stream, kv, Q, positions, O, q_heads,
-                           scale_log2e, 0, 1, 0, counts, count);
-    return hipGetLastError();
+    for (int head0 = 0; head0 < group; head0 += 16) {        // one pass per sixteen query heads of a group, as at decode
+        const int gw = group - head0 < 16 ? group - head0 : 16;
+        const int tpg = 16 / gw;                             // query tokens per CTA
+        const int groups = (count + tpg - 1) / tpg;
+        if (kv.heads > 65535 || kv.batch > 65535 || groups > 65535 || groups < 1) return hipErrorInvalidValue;
+        const dim3 grid(kv.heads, kv.batch, groups);
+        if (kv.bits == 8)
+            hipLaunchKernelGGL((attn_decode_kernel<8, false, true>), grid, dim3(256), 0, stream, kv, Q, positions, O, q_heads,
+                               scale_log2e, 0, 1, 0, head0, gw, counts, count);
+        else
+            hipLaunchKernelGGL((attn_decode_kernel<4, false, true>), grid, dim3(256), 0, stream, kv, Q, positions, O, q_heads,
+                               scale_log2e, 0, 1, 0, head0, gw, counts, count);
+        hipError_t e = hipGetLastError();
+        if (e != hipSuccess) return e;
+    }
+    return hipSuccess;
 }
 
 }  // namespace tmw4

@@ -1295,8 +1295,8 @@ int tm_attn_decode(const uint16_t* Q, const tm_kv_cache* cache, const int32_t* l
     if (!Q || !O || !lens) return fail(TM_EINVAL, "Q, O or lens is null");
     if (((uintptr_t)Q & 15) || ((uintptr_t)O & 15) || ((uintptr_t)lens & 3)) return fail(TM_EINVAL, "misaligned Q, O or lens");
     const int hk = cache->kv.heads;
-    if (q_heads <= 0 || q_heads % hk || q_heads / hk > 16)
-        return fail(TM_EINVAL, "q_heads = %d must be 1..16 times the cache's %d heads", q_heads, hk);
+    if (q_heads <= 0 || q_heads % hk || q_heads / hk > 128)
+        return fail(TM_EINVAL, "q_heads = %d must be 1..128 times the cache's %d heads", q_heads, hk);
     if (!(scale > 0.0f) || !(scale < 1.0e6f)) return fail(TM_EINVAL, "scale out of range");
     if (max_len <= 0 || max_len > cache->kv.cap) max_len = cache->kv.cap;
     int dev;
@@ -1316,10 +1316,10 @@ int tm_attn_prefill(const uint16_t* Q, const tm_kv_cache* cache, const int32_t* 
     if (((uintptr_t)Q & 15) || ((uintptr_t)O & 15) || ((uintptr_t)positions & 3) || ((uintptr_t)counts & 3))
         return fail(TM_EINVAL, "misaligned Q, O, positions or counts");
     const int hk = cache->kv.heads;
-    if (q_heads <= 0 || q_heads % hk || q_heads / hk > 16)
-        return fail(TM_EINVAL, "q_heads = %d must be 1..16 times the cache's %d heads", q_heads, hk);
+    if (q_heads <= 0 || q_heads % hk || q_heads / hk > 128)
+        return fail(TM_EINVAL, "q_heads = %d must be 1..128 times the cache's %d heads", q_heads, hk);
     if (!(scale > 0.0f) || !(scale < 1.0e6f)) return fail(TM_EINVAL, "scale out of range");
-    const int tpg = 16 / (q_heads / hk);
+    const int tpg = 16 / (q_heads / hk < 16 ? q_heads / hk : 16);     // tokens per CTA in the widest pass
     if (count <= 0 || count > 65535 * tpg) return fail(TM_EINVAL, "count = %d out of range (1..%d)", count, 65535 * tpg);
     if ((uint64_t)cache->kv.batch * (uint64_t)count >= (1ull << 31)) return fail(TM_EINVAL, "batch * count too large");
     int dev;

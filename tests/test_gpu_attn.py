@@ -130,6 +130,10 @@ ATTN_CASES = [
     (1, 64, 8, 640, None),
     (2, 4, 2, 64, [33, 64]),               # a 4-bit block whose second half holds one token / is full
     (1, 8, 2, 8200, [8161]),               # split context ending in the first half of a 64-token block
+    # more than sixteen query heads per KV head: one pass per sixteen heads (a last pass of 16, of 4, of 8 heads)
+    (2, 32, 1, 300, None),
+    (1, 40, 2, 5000, [5000]),              # 20 per KV head, split context merged by the second kernel
+    (2, 48, 2, 700, [700, 90]),            # 24 per KV head, split context merged in the kernel
 ]
 
 
@@ -336,6 +340,7 @@ PREFILL_CASES = [
     (2, 8, 1, 64, [0, 0], None, 64),                      # G = 8
     (3, 8, 2, 130, [40, 0, 100], [20, 5, 17], 20),        # later chunks of longer prompts (chunked prefill)
     (2, 8, 2, 300, [0, 150], [300, 150], 300),            # several blocks per wave, ragged tail
+    (2, 40, 2, 90, [0, 30], [60, 33], 60),                # G = 20: a pass of sixteen heads and one of four
 ]
 
 
