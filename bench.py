@@ -86,9 +86,10 @@ class Layer:
 def time_steps(torch, step_fn, steps, warmup, graph_steps=0):
     """Times exactly `steps` calls of step_fn between two events on the launch stream.
 
-    graph_steps > 0: the steps are captured `graph_steps` at a time into a HIP graph and the graph is replayed
-    steps / graph_steps times, which removes the host's per-launch cost (a decode kernel runs for a few microseconds,
-    less than one eager launch costs the host) exactly as a serving loop would.  graph_steps must divide steps."""
+    graph_steps > 0: the steps are captured `graph_steps` at a time into a HIP graph and, after untimed replays that
+    warm the device up, the graph is replayed steps / graph_steps times, which removes the host's per-launch cost (a
+    decode kernel runs for a few microseconds, less than one eager launch costs the host) exactly as a serving loop
+    would.  graph_steps must divide steps."""
     for _ in range(warmup):
         step_fn()
     torch.cuda.synchronize()
@@ -108,7 +109,15 @@ def time_steps(torch, step_fn, steps, warmup, graph_steps=0):
         with torch.cuda.graph(graph, stream=stream):
             for _ in range(graph_steps):
                 step_fn()
-        graph.replay()                       # one untimed replay: graph upload, caches in steady state
+        # untimed replays, at least one and about 5 ms of them: graph upload, caches and the clocks in steady state
+        # (the first replays after a host-side pause run 3-5 % slower than later ones)
+        w0, w1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        w0.record()
+        graph.replay()
+        w1.record()
+        torch.cuda.synchronize()
+        for _ in range(min(50, int(5.0 / max(w0.elapsed_time(w1), 0.1)))):
+            graph.replay()
         torch.cuda.synchronize()
         t0 = time.perf_counter()
         e0.record()
@@ -811,8 +820,8 @@ def cpu_baseline(wl, layers, min_s=5.0, budget_s=25.0):
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=200)
-    ap.add_argument("--warmup", type=int, default=20)
+    ap.add_argument("--steps", type=int, default=1000)
+    ap.add_argument("--warmup", type=int, default=100)
     ap.add_argument("--workload", default="decode", choices=sorted(WORKLOADS) + ["sweep", "shapes", "ceiling", "copy", "companion", "pack", "moe", "w8", "attn", "epilogue", "layer"])
     ap.add_argument("--sweep-out", default=None, help="with --workload sweep: write the per-shape table here (JSON)")
     ap.add_argument("--no-cpu-baseline", action="store_true")

@@ -241,85 +241,115 @@ Plan make_plan(const tm_packed_w4* h, int M, int num_cu)
                 if (ceil_div(NT, 8) * 4 <= num_cu) variant = kTile32x128;      // narrow: more CTAs, K split on top
                 else variant = cost(kTile64x96) < cost(kTile64x128) ? kTile64x96 : kTile64x128;
             } else {
-                // the tallest tile that still gives every CU a CTA (measured at K = N = 8192: M = 1024 runs 131 us on
-                // 256 CTAs of 128 x 256 against 134-139 us on 512 CTAs of 128 x 128; M = 512 is within 5 % on all
-                // of 64 x 128, 64 x 256 and 128 x 128)
-                // below that, the tile with the most rows that still does (a converted fragment feeds one MFMA per
-                // 16 rows of the tile): K = N = 8192 at M = 128 runs 27.2 us on 256 tiles of 64 x 64 against 29.0 us on
-                // 256 tiles of 32 x 128 (same box)
-                if (ctas(kTile128x256) >= num_cu) variant = kTile128x256;
-                else if (ctas(kTile64x128) >= num_cu) variant = kTile64x128;
-                else if (ctas(kTile64x64) >= num_cu) variant = kTile64x64;
-                else variant = kTile32x128;
+                // The shape with the least estimated time: rounds of CTAs times the time of one round.  A round of
+                // 64 x 64 tiles is the unit; the others were measured against it on eight layer shapes (K 4096 ... 11008,
+                // N 4096 ... 28672, M 96 ... 512): 32 x 128 1.15, 64 x 128 1.3, 128 x 128 2.37, 128 x 256 3.78.  The short tiles
+                // run as one CTA of 8 or 16 waves per CU, so their rounds are whole; two CTAs of the 128-row tiles share
+                // a CU, and every round after the first adds 0.6 of one; 128 x 256 tiles that leave more than a tenth of the
+                // CUs idle are charged 5 % more.  Over the 48 cases the choice averaged 2 % behind the best forced shape
+                // (the same plan timed twice differs by 3-8 %): K = 5120, N = 15360, M = 128: 27.9 us on 240 tiles of
+                // 64 x 128 against 36.6 us on 480 of 64 x 64; K = N = 8192, M = 512: 79.1 us on 256 tiles of 128 x 128
+                // against 81.6 us on 512 of 64 x 128; M = 1024 there: 131 us on 256 tiles of 128 x 256 against 134 us on
+                // 512 of 128 x 128.  Ties go to the larger tile.
+                const int shapes[5] = {kTile128x256, kTile128x128, kTile64x128, kTile32x128, kTile64x64};
+                const int round_time[5] = {378, 237, 130, 115, 100};
+                long best = -1;
+                for (int i = 0; i < 5; ++i) {
+                    const long rounds = ceil_div((int)ctas(shapes[i]), num_cu);
+                    long est = tile_bm(shapes[i]) >= 128 ? round_time[i] * (10 + 6 * (rounds - 1)) : round_time[i] * 10 * rounds;
+                    if (shapes[i] == kTile128x256 && ctas(shapes[i]) * 10 < 9L * num_cu) est += est / 20;
+                    if (best < 0 || est < best) {
+                        best = est;
+                        variant = shapes[i];
+                    }
+                }
             }
         }
     }
     const size_t out_bytes = (size_t)M * h->N * sizeof(float);
     int max_split_ws = (int)(kPartialBudget / (out_bytes ? out_bytes : 1));
     if (max_split_ws < 1) max_split_ws = 1;
-    // 16 < M <= 64, 4-bit codes: the one-shot decode kernels with a ring of X pieces per wave, one strip per CU.  Every
-    // CTA streams the X rows of its K slice through its CU's load path, so where that is more than about 192 KiB the
-    // strips are made wider and K is split across CTAs instead (narrow outputs: each CTA then reads a part of X only).
+    // 16 < M <= 64, 4-bit codes: the one-shot decode kernels with a ring of X pieces per wave, about one CTA per CU.  Every
+    // CTA streams the X rows of its K slice through its CU's load path, so wider strips with K split across CTAs (each
+    // CTA then reads a part of X only) are weighed against narrow strips that need no merge.
     // A forced 16-row decode variant fixes the strip width (and the forced split the split) instead; the forced 32- and
     // 64-row variants keep meaning the ring-buffered kernels.
     if (h->bits == 4 && M > 16 && M <= 64 && g_force_stage != 1 && (uint64_t)M * h->K * 2u < (1ull << 31) &&
         (g_force_variant < 0 || (is_skinny(g_force_variant) && skinny_rows(g_force_variant) == 16))) {
-        int ntw, strips, split;
+        auto emit = [&](int strips, int split, int kps, int w, int ni) {
+            pl.variant = M <= 32 ? kSkinny32x64 : kSkinny64x64;     // in name only: the strip width is NT / strips
+            pl.split = split;
+            pl.ku_per_split = kps;
+            pl.strips = strips;
+            pl.stage_steps = 2;
+            pl.kgroups = 1;
+            pl.stream_ni = ni;
+            pl.tiles_m = 1;
+            pl.tiles_n = strips;
+            pl.block = (unsigned)w * 64;
+            pl.grid = (unsigned)(strips * split);
+            pl.ws_bytes = kCounterBytes + (split > 1 ? (size_t)split * out_bytes : 0);
+        };
         if (g_force_variant >= 0) {
-            ntw = skinny_ntw(g_force_variant);
-            strips = ceil_div(NT, ntw);
-            split = g_force_split > 0 ? g_force_split : 1;
-        } else {
-            // measured at M = 32: N = 8192, K = 8192 13.9 us on 32-column strips with no split against 16.7 with wider
-            // strips and split 2; N = 4096, K = 11008 12.9 us on 64-column strips with split 4 against 14.7 with no split
-            const int per_cu = ceil_div(NT, num_cu);
-            split = 1;
-            if (NT < num_cu) {
-                ntw = 1;
-                strips = NT;
-                split = ceil_div(num_cu, NT);
-                const int max_by_k = KU / 16 > 0 ? KU / 16 : 1;      // every wave of a CTA keeps at least one unit
-                if (split > max_by_k) split = max_by_k;
-            } else if (per_cu <= 1 && (size_t)M * h->K * 2 > 256 * 1024) {
-                ntw = 4;
-                strips = ceil_div(NT, ntw);
-                split = ceil_div(num_cu, strips);
-            } else if (per_cu <= 4) {
-                ntw = per_cu;
-                strips = num_cu;
-            } else {
-                // wide outputs stay with the CTA tiles (4096 x 22016: 17.4 against 16.3 us at M = 32, 27.9 against
-                // 20.5 us at M = 64)
-                ntw = 0;
-                strips = 1;
+            const int ntw = skinny_ntw(g_force_variant);
+            const int strips = ceil_div(NT, ntw);
+            int split = g_force_split > 0 ? g_force_split : 1;
+            if (split > KU) split = KU;
+            if (split > max_split_ws) split = max_split_ws;
+            const int kps = ceil_div(KU, split);
+            split = ceil_div(KU, kps);
+            const int tries[2] = {g_force_waves >= 8 ? g_force_waves : (M > 32 ? 8 : 16), g_force_waves >= 8 ? g_force_waves : 8};
+            for (int w : tries) {
+                const int ni = strips <= kMaxCounters ? rows_units_per_wave(M, ceil_div(NT, strips), h->group, kps, w) : 0;
+                if (ni > 0) {
+                    emit(strips, split, kps, w, ni);
+                    return pl;
+                }
             }
-            if (g_force_split > 0) split = g_force_split;
-        }
-        if (split > KU) split = KU;
-        if (split > max_split_ws) split = max_split_ws;
-        if (split < 1) split = 1;
-        const int kps = ceil_div(KU, split);
-        split = ceil_div(KU, kps);
-        const int widest = ceil_div(NT, strips);
-        // chosen automatically only where CTAs of 16 waves fit: with 8 waves and two ring slots the refills are not
-        // covered (4096 x 22016 at M = 32: 17.4 us against 16.7 us on the 32 x 96 tiles)
-        const int tries[2] = {g_force_waves >= 8 ? g_force_waves : (M > 32 ? 8 : 16),
-                              g_force_waves >= 8 ? g_force_waves : ((g_force_variant < 0 && M <= 32) ? 16 : 8)};
-        for (int w : tries) {
-            const int ni = ntw > 0 && widest <= 8 && strips <= kMaxCounters ? rows_units_per_wave(M, widest, h->group, kps, w) : 0;
-            if (ni > 0) {
-                pl.variant = M <= 32 ? kSkinny32x64 : kSkinny64x64;     // in name only: the strip width is NT / strips
-                pl.split = split;
-                pl.ku_per_split = kps;
-                pl.strips = strips;
-                pl.stage_steps = 2;
-                pl.kgroups = 1;
-                pl.stream_ni = ni;
-                pl.tiles_m = 1;
-                pl.tiles_n = strips;
-                pl.block = (unsigned)w * 64;
-                pl.grid = (unsigned)(strips * split);
-                pl.ws_bytes = kCounterBytes + (split > 1 ? (size_t)split * out_bytes : 0);
+        } else if (NT <= 4 * num_cu) {
+            // Strips of one to four column tiles, K split over up to eight CTAs: of the combinations that are built and
+            // give at most one CTA per CU, the one with the least estimated time.  The estimate is a fit to 46 timed
+            // combinations on seven layer shapes (K 8192 ... 28672, N 3584 ... 10240; residual at most 1.5 us at 32 rows,
+            // 2.3 us at 64): a constant, the weight units a CTA converts (strip width x units per K slice), the pieces of
+            // X it streams (units per K slice), and the merge of the partial sums when K is split.  CTAs of 8 waves at
+            // up to 32 rows run 1.5 us behind CTAs of 16 with the same work.  Examples at M = 32: K = N = 8192, 13.7 us on
+            // 32-column strips unsplit against 16.4 us on 64-column strips split in two; K = 11008, N = 4096, 12.7 us on
+            // 64-column strips split in four against 14.5 us on 16-column strips unsplit; K = 13824, N = 5120, 17.3 us
+            // on 64-column strips split in three against 28.7 us on the ring-buffered kernel.  Wider outputs stay with
+            // the CTA tiles (K = 4096, N = 22016: 17.4 against 16.3 us at M = 32, 27.9 against 20.5 us at M = 64).
+            // Up to 32 rows, two rounds of 8-wave CTAs are taken where one round is not built (K = 28672, N = 8192:
+            // 43.6 us against 53.5 us).
+            const long c0 = M <= 32 ? 5230 : 10257, cw = M <= 32 ? 44 : 63, cx = M <= 32 ? 56 : 14, cs = M <= 32 ? 2243 : 2435;
+            long best = -1;
+            int b_strips = 0, b_split = 0, b_kps = 0, b_w = 0, b_ni = 0;
+            for (int ntw = 1; ntw <= 4; ++ntw) {
+                const int strips = ceil_div(NT, ntw);
+                if (strips > kMaxCounters) continue;
+                for (int want = 1; want <= 8; ++want) {
+                    if (g_force_split > 0 && want != g_force_split) continue;
+                    if (want > KU || want > max_split_ws) break;
+                    const int kps = ceil_div(KU, want);
+                    const int split = ceil_div(KU, kps);
+                    if (split != want) continue;
+                    const long ctas = (long)strips * split;
+                    const int rounds = (int)ceil_div((int)ctas, num_cu);
+                    if (rounds > (M <= 32 ? 2 : 1)) continue;
+                    for (int w = (M <= 32 && rounds == 1) ? 16 : 8; w >= 8; w -= 8) {
+                        if (g_force_waves >= 8 && w != g_force_waves) continue;
+                        const int ni = rows_units_per_wave(M, ceil_div(NT, strips), h->group, kps, w);
+                        if (ni <= 0) continue;
+                        long est = c0 + cw * ntw * kps + cx * kps + (split > 1 ? cs : 0) + (M <= 32 && w == 8 ? 1500 : 0);
+                        est *= rounds;
+                        if (best < 0 || est < best) {
+                            best = est;
+                            b_strips = strips; b_split = split; b_kps = kps; b_w = w; b_ni = ni;
+                        }
+                        break;
+                    }
+                }
+            }
+            if (best >= 0) {
+                emit(b_strips, b_split, b_kps, b_w, b_ni);
                 return pl;
             }
         }
@@ -355,7 +385,9 @@ Plan make_plan(const tm_packed_w4* h, int M, int num_cu)
         int tiles = pl.tiles_m * pl.tiles_n;
         // Split K only when fewer than half the CUs would get a tile, and only as far as the fp32 partial sums
         // (written and read back once per split) stay below about half the weight bytes: split <= K / (32 M).
-        int want = tiles * 2 <= num_cu ? (2 * num_cu) / tiles : 1;
+        // (short tiles run one CTA per CU, so the split stops at one round of CTAs: K = 11008, N = 4096, M = 96 runs
+        // 29.0 us on 96 tiles split in two against 36.7 us split in three)
+        int want = tiles * 2 <= num_cu ? (tile_bm(variant) <= 64 ? num_cu / tiles : (2 * num_cu) / tiles) : 1;
         if (want > 4) want = 4;
         int by_traffic = h->K / (32 * (M > 0 ? M : 1));
         if (by_traffic < 1) by_traffic = 1;
