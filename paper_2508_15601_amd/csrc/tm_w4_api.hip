@@ -308,18 +308,20 @@ Plan make_plan(const tm_packed_w4* h, int M, int num_cu)
             }
         } else if (NT <= 4 * num_cu) {
             // Strips of one to four column tiles, K split over up to eight CTAs: of the combinations that are built and
-            // give at most one CTA per CU, the one with the least estimated time.  The estimate is a fit to 46 timed
-            // combinations on seven layer shapes (K 8192 ... 28672, N 3584 ... 10240; residual at most 1.5 us at 32 rows,
-            // 2.3 us at 64): a constant, the weight units a CTA converts (strip width x units per K slice), the pieces of
-            // X it streams (units per K slice), and the merge of the partial sums when K is split.  CTAs of 8 waves at
-            // up to 32 rows run 1.5 us behind CTAs of 16 with the same work.  Examples at M = 32: K = N = 8192, 13.7 us on
+            // give at most one CTA per CU, the one with the least estimated time.  The estimate is a fit to 146 timed
+            // combinations on fourteen layer shapes (K 1536 ... 28672, N 1024 ... 10240; rms residual 0.6 us at 32 rows,
+            // 0.9 us at 64; it ranks the fastest measured combination first on all of them): a constant, the weight
+            // units a CTA converts (strip width x units per K slice), the pieces of X it streams (units per K slice),
+            // and the merge of the partial sums when K is split, growing with the split.  CTAs of 8 waves at up to 32
+            // rows run 1.5 us behind CTAs of 16 with the same work.  Examples at M = 32: K = N = 8192, 13.7 us on
             // 32-column strips unsplit against 16.4 us on 64-column strips split in two; K = 11008, N = 4096, 12.7 us on
             // 64-column strips split in four against 14.5 us on 16-column strips unsplit; K = 13824, N = 5120, 17.3 us
-            // on 64-column strips split in three against 28.7 us on the ring-buffered kernel.  Wider outputs stay with
-            // the CTA tiles (K = 4096, N = 22016: 17.4 against 16.3 us at M = 32, 27.9 against 20.5 us at M = 64).
-            // Up to 32 rows, two rounds of 8-wave CTAs are taken where one round is not built (K = 28672, N = 8192:
-            // 43.6 us against 53.5 us).
-            const long c0 = M <= 32 ? 5230 : 10257, cw = M <= 32 ? 44 : 63, cx = M <= 32 ? 56 : 14, cs = M <= 32 ? 2243 : 2435;
+            // on 64-column strips split in three against 28.7 us on the ring-buffered kernel; K = 4096, N = 1024, 6.3 us
+            // unsplit on 64 CTAs against 7.1 us split in four.  Wider outputs stay with the CTA tiles (K = 4096,
+            // N = 22016: 17.4 against 16.3 us at M = 32, 27.9 against 20.5 us at M = 64).  Up to 32 rows, two rounds of
+            // 8-wave CTAs are taken where one round is not built (K = 28672, N = 8192: 43.6 us against 53.5 us).
+            const long c0 = M <= 32 ? 3224 : 4222, cw = M <= 32 ? 52 : 87, cx = M <= 32 ? 65 : 47;
+            const long cs = M <= 32 ? 2354 : 3375, cm = M <= 32 ? 258 : 243;
             long best = -1;
             int b_strips = 0, b_split = 0, b_kps = 0, b_w = 0, b_ni = 0;
             for (int ntw = 1; ntw <= 4; ++ntw) {
@@ -338,7 +340,7 @@ Plan make_plan(const tm_packed_w4* h, int M, int num_cu)
                         if (g_force_waves >= 8 && w != g_force_waves) continue;
                         const int ni = rows_units_per_wave(M, ceil_div(NT, strips), h->group, kps, w);
                         if (ni <= 0) continue;
-                        long est = c0 + cw * ntw * kps + cx * kps + (split > 1 ? cs : 0) + (M <= 32 && w == 8 ? 1500 : 0);
+                        long est = c0 + cw * ntw * kps + cx * kps + (split > 1 ? cs + cm * (split - 1) : 0) + (M <= 32 && w == 8 ? 1500 : 0);
                         est *= rounds;
                         if (best < 0 || est < best) {
                             best = est;
