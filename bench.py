@@ -83,6 +83,11 @@ class Layer:
         tm.tm_gemm_w4a16(self.X[M][i % 4], self.packed[i % self.copies], self.Y[M][i % 4])
 
 
+# untimed graph replays before every timed region: about this many milliseconds of them, at most this many replays
+WARM_MS = 20.0
+WARM_REPLAYS_MAX = 400
+
+
 def time_steps(torch, step_fn, steps, warmup, graph_steps=0):
     """Times exactly `steps` calls of step_fn between two events on the launch stream.
 
@@ -109,14 +114,14 @@ def time_steps(torch, step_fn, steps, warmup, graph_steps=0):
         with torch.cuda.graph(graph, stream=stream):
             for _ in range(graph_steps):
                 step_fn()
-        # untimed replays, at least one and about 5 ms of them: graph upload, caches and the clocks in steady state
-        # (the first replays after a host-side pause run 3-5 % slower than later ones)
+        # untimed replays, at least one and some milliseconds of them (WARM_MS): graph upload, caches and the clocks in steady state
+        # (the first 5-10 ms after a host-side pause run 3-10 % slower than the steady state that follows)
         w0, w1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
         w0.record()
         graph.replay()
         w1.record()
         torch.cuda.synchronize()
-        for _ in range(min(50, int(5.0 / max(w0.elapsed_time(w1), 0.1)))):
+        for _ in range(min(WARM_REPLAYS_MAX, int(WARM_MS / max(w0.elapsed_time(w1), 0.05)))):
             graph.replay()
         torch.cuda.synchronize()
         t0 = time.perf_counter()

@@ -501,6 +501,22 @@ Plan make_plan(const tm_packed_w4* h, int M, int num_cu)
                 }
             }
         }
+        // Still no one-shot form (K beyond about 24000 on outputs wider than one strip per CU): the ring-buffered
+        // kernel on 64-column strips with K split so that every CU gets one CTA, because each CTA streams the rows
+        // of X of its own K slice only (K = 28672, N = 8192: 26.4 against 32.9 us at M = 8, 31.1 against 37.1 us at
+        // M = 16 on 32-column strips unsplit).
+        const int strips4 = ceil_div(NT, 4);
+        int sp = num_cu / strips4;
+        if (sp > max_split_ws) sp = max_split_ws;
+        if (sp > 8) sp = 8;
+        if (pl.stream_ni == 0 && M > 4 && (size_t)M * h->K * 2 > 256 * 1024 && sp >= 2 && KU / sp >= 16) {
+            pl.variant = variant = kSkinny16x64;
+            pl.strips = pl.tiles_n = strips4;
+            pl.ku_per_split = ceil_div(KU, sp);
+            split = ceil_div(KU, pl.ku_per_split);
+            pl.split = split;
+            pl.block = (M > 8 ? 8u : 16u) * 64u;
+        }
     }
     if (is_skinny(variant)) {
         pl.grid = (unsigned)(pl.tiles_n * split);

@@ -392,6 +392,31 @@ def test_decode_configs_take_the_one_shot_form(tm):
         packed.close()
 
 
+def test_very_deep_decode_layer_splits_k(tm, oracle):
+    """K so deep that no split of eight or less brings a CTA's slice of X into LDS, on an output wider than one strip per
+    compute unit: the ring-buffered kernel with K split across CTAs.  Integer-valued inputs with power-of-two scales and
+    sparse activation rows keep every product and partial sum exact, so the result must equal the oracle's bit for bit."""
+    rng = np.random.default_rng(77)
+    M, K, N, g = 12, 24576, 4352, 128
+    q = rng.integers(0, 16, (K, N), dtype=np.uint8)
+    z = rng.integers(0, 16, (K // g, N)).astype(np.float16)
+    s = np.exp2(rng.integers(-3, 2, (K // g, N))).astype(np.float16)
+    X = np.zeros((M, K), dtype=np.float16)
+    for m in range(M):
+        X[m, rng.choice(K, 64, replace=False)] = rng.integers(-2, 3, 64).astype(np.float16)
+    d = {"q": q, "s": s, "z": z, "X": X, "qweight": wl.pack_interchange(q)}
+    packed = gu.pack(d, g)
+    plan = tm.tm_get_plan(packed, M)
+    _say(f"very deep decode layer K={K} N={N} M={M}: {plan}")
+    assert plan["one_shot_units_per_wave"] == 0 and plan["split_k"] >= 2 and plan["name"] == "skinny16x64", plan
+    Y = gu.gemm(packed, X)
+    Yref = oracle.gemm(X, q, s, z, g)
+    assert np.array_equal(Y.view(np.uint16), Yref.view(np.uint16))
+    Y2 = gu.gemm(packed, X)
+    assert np.array_equal(Y.view(np.uint16), Y2.view(np.uint16))
+    packed.close()
+
+
 # (variant, waves per CTA): 128-column tiles with two or four sets of four waves, 96-column tiles with two or four
 # sets of two waves; the 128-row tile is built with two sets only
 WAVE_SETS = [(13, 8), (13, 16), (9, 8), (9, 16), (10, 8), (20, 4), (20, 8), (21, 4), (21, 8), (22, 4), (22, 8), (23, 4), (23, 8)]
