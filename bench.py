@@ -792,7 +792,7 @@ def empty_launch_us(tm, torch, iters=200):
     return ev_ms / iters * 1e3
 
 
-def cpu_baseline(wl, layers, min_s=5.0, budget_s=25.0):
+def cpu_baseline(wl, layers, min_s=12.0, budget_s=25.0):
     """The oracle as it stands, timed on this host's cores over the same workload: whole passes over every
     (layer, M) pair are repeated until at least `min_s` seconds have been spent; a single GEMM too large for
     `budget_s` is cut to its first rows (and the sample string says so)."""

@@ -257,6 +257,8 @@ Plan make_plan(const tm_packed_w4* h, int M, int num_cu)
                 for (int i = 0; i < 5; ++i) {
                     const long rounds = ceil_div((int)ctas(shapes[i]), num_cu);
                     long est = tile_bm(shapes[i]) >= 128 ? round_time[i] * (10 + 6 * (rounds - 1)) : round_time[i] * 10 * rounds;
+                    // a single round of 128-row tiles runs with two wave sets per CTA: 12 % (128 x 128) and 5 % (128 x 256) faster
+                    if (rounds == 1 && tile_bm(shapes[i]) >= 128) est = shapes[i] == kTile128x128 ? est * 88 / 100 : est * 95 / 100;
                     if (shapes[i] == kTile128x256 && ctas(shapes[i]) * 10 < 9L * num_cu) est += est / 20;
                     if (best < 0 || est < best) {
                         best = est;
@@ -421,6 +423,9 @@ Plan make_plan(const tm_packed_w4* h, int M, int num_cu)
         // (64-row tiles: two sets with 128-deep stages measured ahead of four sets with 64-deep ones, 40.2 against
         // 42.0 us at K = N = 8192, M = 256)
         else if (bm <= 64 && (long)pl.tiles_m * pl.tiles_n * split < 2L * num_cu) kg = bm == 64 ? 2 : 4;
+        // (128-row tiles with at most one CTA per CU: two sets, 7-14 % faster than one - K = N = 8192, M = 384: 60 against
+        // 70 us on 192 tiles of 128 x 128; slower once CTAs run in two rounds, K = 4096, N = 28672, M = 256: 72 against 64 us)
+        else if ((variant == kTile128x128 || variant == kTile128x256) && (long)pl.tiles_m * pl.tiles_n * split <= num_cu) kg = 2;
         if (bm <= 64 && kg > 1 && g_force_stage <= 1) steps = 4;
         if (g_force_waves >= 4) kg = g_force_waves * 64 / tile_threads(variant);
         if (!tile_has_kgroups(variant, kg)) kg = tile_has_kgroups(variant, 1) ? 1 : 4;

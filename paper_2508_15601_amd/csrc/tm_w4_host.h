@@ -57,7 +57,7 @@ inline int tile_threads(int v) { return tile_two_waves(v) ? 128 : 256; }     // 
 inline bool tile_has_kgroups(int v, int kg)
 {
     if (tile_two_waves(v)) return kg == 2 || kg == 4;
-    return kg == 1 || (kg == 2 && (v == kTile32x128 || v == kTile64x128 || v == kTile128x128)) || (kg == 4 && (v == kTile32x128 || v == kTile64x128));
+    return kg == 1 || (kg == 2 && (v == kTile32x128 || v == kTile64x128 || v == kTile128x128 || v == kTile128x256)) || (kg == 4 && (v == kTile32x128 || v == kTile64x128));
 }
 inline int tile_bn(int v) { return (v == kTile64x64 || v == kTile128x64) ? 64 : (v == kTile32x96 || v == kTile64x96) ? 96 : (v == kTile64x128 || v == kTile128x128 || v == kTile32x128) ? 128 : (v == kTile128x512 ? 512 : 256); }
 

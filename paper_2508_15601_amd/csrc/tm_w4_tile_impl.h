@@ -64,7 +64,11 @@ __device__ __forceinline__ void tile_body(const GemmParams& p, const int tile_m,
     constexpr size_t kXsBytes = (size_t)BM * BKS * sizeof(uint16_t);
     // one wave set's partial tile; the sets' tiles meet pairwise (see the end of the K loop), as many at a time as fit
     constexpr size_t kSetTileBytes = (size_t)NW * TM * TN * 64 * sizeof(f32x4);
-    constexpr size_t kRedBytes = KG > 1 ? kSetTileBytes : 0;
+    // (a tile of more than 64 KiB is handed over in row parts, so that the buffer stays at 64 KiB)
+    constexpr size_t kRedCap = 64 * 1024;
+    constexpr int kRedParts = kSetTileBytes > kRedCap ? (int)(kSetTileBytes / kRedCap) : 1;
+    static_assert(kSetTileBytes <= kRedCap || (kSetTileBytes % kRedCap == 0 && TM % kRedParts == 0), "set tile parts");
+    constexpr size_t kRedBytes = KG > 1 ? kSetTileBytes / kRedParts : 0;
     __shared__ __attribute__((aligned(16))) unsigned char smem0[kXsBytes > kRedBytes ? kXsBytes : kRedBytes];
     __shared__ __attribute__((aligned(16))) unsigned char smem1[kXsBytes];
     __shared__ uint32_t s_last;
@@ -353,7 +357,29 @@ __device__ __forceinline__ void tile_body(const GemmParams& p, const int tile_m,
         constexpr int kCapRaw = (int)(sizeof(smem0) / kSetTileBytes);
         static_for<0, 3>([&](auto R) {                                 // up to three halvings: KG = 2, 4 or 8
             constexpr int active = KG >> decltype(R)::value;
-            if constexpr (active > 1) {
+            if constexpr (active > 1 && kRedParts > 1) {
+                // one pair of sets at a time, TM / kRedParts row tiles per hand-over
+                constexpr int half = active / 2;
+                constexpr int kRows = TM / kRedParts;
+                static_for<0, half * kRedParts>([&](auto P) {
+                    constexpr int pair = decltype(P)::value / kRedParts, part = decltype(P)::value % kRedParts;
+                    f32x4* slot = red + (size_t)wave * (kRows * TN * 64) + lane;
+                    if (kg == half + pair) {
+#pragma unroll
+                        for (int i = 0; i < kRows; ++i)
+#pragma unroll
+                            for (int j = 0; j < TN; ++j) slot[(i * TN + j) * 64] = acc[part * kRows + i][j];
+                    }
+                    __syncthreads();
+                    if (kg == pair) {
+#pragma unroll
+                        for (int i = 0; i < kRows; ++i)
+#pragma unroll
+                            for (int j = 0; j < TN; ++j) acc[part * kRows + i][j] += slot[(i * TN + j) * 64];
+                    }
+                    if constexpr (!(active == 2 && decltype(P)::value == half * kRedParts - 1)) __syncthreads();
+                });
+            } else if constexpr (active > 1) {
                 constexpr int half = active / 2;
                 constexpr int cap = kCapRaw < half ? kCapRaw : half;
                 constexpr int passes = (half + cap - 1) / cap;

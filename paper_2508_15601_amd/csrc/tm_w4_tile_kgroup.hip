@@ -17,13 +17,14 @@ hipError_t launch_depth_kg(const GemmParams& p, const Plan& plan, int group, hip
     constexpr int BM = TM * 16;
     constexpr int WAVES = NW * KG;
     // two X buffers of BM rows x (32 * steps * KG + pad) halves must fit the 160 KiB of LDS; CTAs of 16 waves
-    // have 128 registers per lane, which bounds the stage depth they are built with
+    // have 128 registers per lane, which bounds the stage depth they are built with (the 128 x 256 tile, 128
+    // accumulator registers per lane, is built with 64-deep stages only)
     switch (plan.stage_steps) {
         case 2:
             if constexpr (BM * (64 * KG + 16) * 4 <= 160 * 1024) return launch_shape<TM, TN, NW, 2, KG>(p, plan, group, stream);
             return hipErrorInvalidValue;
         case 4:
-            if constexpr ((WAVES < 16 || TM <= 2) && BM * (128 * KG + 16) * 4 <= 160 * 1024)
+            if constexpr ((WAVES < 16 || TM <= 2) && TM * TN <= 16 && BM * (128 * KG + 16) * 4 <= 160 * 1024)
                 return launch_shape<TM, TN, NW, 4, KG>(p, plan, group, stream);
             return hipErrorInvalidValue;
         case 8:
@@ -43,6 +44,7 @@ hipError_t launch_tile_kgroup(const GemmParams& p, const Plan& plan, int group, 
             case kTile32x128: return launch_depth_kg<2, 2, 2>(p, plan, group, stream);
             case kTile64x128: return launch_depth_kg<4, 2, 2>(p, plan, group, stream);
             case kTile128x128: return launch_depth_kg<8, 2, 2>(p, plan, group, stream);
+            case kTile128x256: return launch_depth_kg<8, 4, 2>(p, plan, group, stream);
             case kTile32x96: return launch_depth_kg<2, 3, 2, 2>(p, plan, group, stream);
             case kTile64x96: return launch_depth_kg<4, 3, 2, 2>(p, plan, group, stream);
             case kTile64x64: return launch_depth_kg<4, 2, 2, 2>(p, plan, group, stream);

@@ -418,8 +418,8 @@ def test_very_deep_decode_layer_splits_k(tm, oracle):
 
 
 # (variant, waves per CTA): 128-column tiles with two or four sets of four waves, 96-column tiles with two or four
-# sets of two waves; the 128-row tile is built with two sets only
-WAVE_SETS = [(13, 8), (13, 16), (9, 8), (9, 16), (10, 8), (20, 4), (20, 8), (21, 4), (21, 8), (22, 4), (22, 8), (23, 4), (23, 8)]
+# sets of two waves; the 128-row tiles are built with two sets only (the 128 x 256 one hands its set tile over in two parts)
+WAVE_SETS = [(13, 8), (13, 16), (9, 8), (9, 16), (10, 8), (7, 8), (20, 4), (20, 8), (21, 4), (21, 8), (22, 4), (22, 8), (23, 4), (23, 8)]
 
 
 @pytest.mark.parametrize("variant,waves", WAVE_SETS)
@@ -427,7 +427,7 @@ WAVE_SETS = [(13, 8), (13, 16), (9, 8), (9, 16), (10, 8), (20, 4), (20, 8), (21,
 @pytest.mark.parametrize("g,split", [(32, 1), (64, 2), (128, 1), (128, 3)])
 def test_tile_wave_sets(tm, oracle, variant, waves, stage, g, split):
     """Tile kernels with several wave sets per CTA, each set multiplying its own slice of every K stage."""
-    M = {13: 33, 9: 70, 10: 150, 20: 31, 21: 50, 22: 59, 23: 128}[variant]
+    M = {13: 33, 9: 70, 10: 150, 7: 200, 20: 31, 21: 50, 22: 59, 23: 128}[variant]
     K, N = 1536, 336                         # 12 packed units: whole stages for every depth up to four units
     d = _random_problem(variant * 100 + waves + stage + split, M, K, N, g)
     packed = gu.pack(d, g)
