@@ -429,9 +429,14 @@ Plan make_plan(const tm_packed_w4* h, int M, int num_cu)
         if (bm <= 64 && kg > 1 && g_force_stage <= 1) steps = 4;
         if (g_force_waves >= 4) kg = g_force_waves * 64 / tile_threads(variant);
         if (!tile_has_kgroups(variant, kg)) kg = tile_has_kgroups(variant, 1) ? 1 : 4;
-        if (w8) {                                  // the 8-bit tiles are built in one depth each, one wave set
+        if (w8) {
+            // the 8-bit tiles are built in one depth each, with one or two wave sets (four on the 32-row tile; one set
+            // fewer at group 32, where the kernels with the most sets would spill registers)
             steps = variant == kTile128x256 ? 2 : 4;
-            kg = 1;
+            const int most = variant == kTile32x128 ? 4 : 2;
+            if (kg > most) kg = most;
+            if (h->group == 32 && variant != kTile64x128 && kg == most) kg /= 2;
+            if (kg < 1) kg = 1;
         }
         // both X buffers (bm rows x (32*steps*kg + 16) halves each) must fit the 160 KiB of LDS
         while (kg > 1 && 2L * bm * (32 * steps * kg + 16) * 2 > 160 * 1024) {
@@ -443,10 +448,12 @@ Plan make_plan(const tm_packed_w4* h, int M, int num_cu)
         if (kg > 1 && waves_total > 8 && steps == 8) steps = 4;
         if (tile_bn(variant) == 96 && steps == 8) steps = 4;       // three tiles per wave: no registers for 256-deep stages
         if (kg == 2 && bm == 64 && steps == 8 && h->group == 32) steps = 4;
-        // the kernels assume whole stages: a stage is steps*kg/4 packed units when that is one or more
-        while (steps * kg > 4 && KU % (steps * kg / 4)) {
+        // the kernels assume whole stages: a stage is steps*kg/4 packed units when that is one or more (steps*kg/2 units
+        // of the 8-bit formats, whose depth is fixed)
+        while (!w8 && steps * kg > 4 && KU % (steps * kg / 4)) {
             if (steps > 2) steps /= 2; else kg /= 2;
         }
+        while (w8 && kg > 1 && KU % (steps * kg / 2)) kg /= 2;
         const int ups = steps * kg / (w8 ? 2 : 4);  // packed units per stage
         if (ups > 1 && pl.ku_per_split % ups) pl.ku_per_split += ups - pl.ku_per_split % ups;
         pl.stage_steps = steps;

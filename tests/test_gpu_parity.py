@@ -882,7 +882,7 @@ def test_w8_gemm_against_oracle(tm, oracle, M, K, N, variant, split, g):
     packed = _pack_w8(tm, q, s, z, g)
     tm.tm_set_variant(variant, split)
     try:
-        for waves in ((0, 8, 16) if M <= 16 else (0,)):
+        for waves in (0, 8, 16):     # decode kernels: waves per CTA; CTA tiles: two and four wave sets
             tm.tm_set_launch(waves, 0)
             Y = gu.gemm(packed, X)
             ok, worst, fro = acceptance(Y, oracle.gemm(X, q, s, z, g))
@@ -971,7 +971,7 @@ def test_fp8_gemm_against_oracle(tm, oracle, M, K, N, variant, split, g):
     packed = tm.tm_pack_w8_fp8(gu.to_dev(wl.pack_interchange8(q)), gu.to_dev(s), K, N, g)
     tm.tm_set_variant(variant, split)
     try:
-        for waves in ((0, 8, 16) if M <= 16 else (0,)):
+        for waves in (0, 8, 16):     # decode kernels: waves per CTA; CTA tiles: two and four wave sets
             tm.tm_set_launch(waves, 0)
             ok, worst, fro = acceptance(gu.gemm(packed, X), oracle.gemm_fp8(X, q, s, g))
             assert ok, (waves, worst, fro)
