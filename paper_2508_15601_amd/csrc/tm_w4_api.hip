@@ -377,10 +377,37 @@ Plan make_plan(const tm_packed_w4* h, int M, int num_cu)
         pl.tiles_n = strips;
         pl.strips = strips;
         pl.block = (unsigned)waves * 64;
-        if (strips * 2 <= num_cu) {                // too few strips: split K across CTAs as well
-            int want = ceil_div(num_cu, strips);
+        if (strips * 2 <= num_cu) {                // too few strips: split K across CTAs as well, up to one CTA per CU
+            int want = num_cu / strips;            // (one more would put some CUs through two CTAs in a row)
             int max_by_k = KU / waves > 0 ? KU / waves : 1;
             split = want < max_by_k ? want : max_by_k;
+            // Decode shapes: the smallest split with which the one-shot form fits, none if it fits unsplit.  These
+            // layers are a few megabytes, so a launch is mostly latency, and the merge of split partial sums (two more
+            // dependent trips through memory, about 2 us) costs more than the shorter K slices save: K = 4096,
+            // N = 2048, M = 1 runs 3.6-3.9 us on 128 unsplit CTAs against 5.1-5.9 us on 256 split in two; K = 8192,
+            // N = 1024 4.8 against 5.3-5.9 us split in four.  Where X is too large for the unsplit form (K = 12800,
+            // N = 1536, M = 16: 15.4 us on the ring-buffered kernel) the split that brings it into LDS wins even with
+            // more CTAs than CUs (10.0 us split in four, 384 CTAs, against 11.1 us on the ring-buffered kernel split in two).
+            if (g_force_variant < 0 && g_force_split == 0 && g_force_stage != 1 && g_force_waves == 0 && h->bits == 4 &&
+                M <= 16 && skinny_rows(variant) == 16) {
+                const int widest = ceil_div(NT, strips);
+                int mp_log = 0;
+                while ((1 << mp_log) < M) ++mp_log;
+                for (int sp = 1; sp <= 8 && strips * sp <= 2 * num_cu && sp <= KU && sp <= max_split_ws; ++sp) {
+                    const int kps = ceil_div(KU, sp);
+                    if (ceil_div(KU, kps) != sp) continue;
+                    bool fits = false;
+                    for (int w : {16, 8}) {
+                        const int ni = stream_units_per_wave(widest, h->group, kps, w);
+                        int red_off;
+                        if (ni > 0 && stream_lds(ni, mp_log, widest, w, &red_off) <= kStreamLdsBudget) fits = true;
+                    }
+                    if (fits) {
+                        split = sp;
+                        break;
+                    }
+                }
+            }
         }
     } else {
         pl.tiles_m = ceil_div(M, tile_bm(variant));

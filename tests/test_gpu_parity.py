@@ -240,6 +240,33 @@ def test_small_shapes_auto_plan(tm, oracle, M, K, N, g):
     assert ok, (worst, fro)
 
 
+@pytest.mark.parametrize("seed", range(18))
+def test_random_layer_shapes_auto_plan(tm, oracle, seed):
+    """Layer-sized shapes drawn at random (K 1536 ... 14336, N 1024 ... 12288, every row-count regime): whatever plan the
+    dispatcher's cost models pick - strip width and K split of the decode kernels, tile shape and wave sets above 64
+    rows - must launch and meet the oracle.  Codes, zero-points and scales are drawn directly (no quantiser run)."""
+    rng = np.random.default_rng(4000 + seed)
+    K = 128 * int(rng.integers(12, 113))
+    N = 16 * int(rng.integers(64, 769))
+    while K * N > 36_000_000:
+        N = (N // 32) * 16
+    g = int(rng.choice([32, 64, 128, 128]))
+    M = int([1, 5, 16, 24, 32, 48, 64, 96, 128, 200, 384, 512, 17, 33, 65, 300, 8, 256][seed])
+    q = rng.integers(0, 16, (K, N), dtype=np.uint8)
+    z = rng.integers(0, 16, (K // g, N)).astype(np.float16)
+    s = (rng.random((K // g, N)) * 0.02 + 0.001).astype(np.float16)
+    X = rng.standard_normal((M, K)).astype(np.float16)
+    d = {"q": q, "s": s, "z": z, "X": X, "qweight": wl.pack_interchange(q)}
+    packed = gu.pack(d, g)
+    plan = tm.tm_get_plan(packed, M)
+    _say(f"random layer seed={seed} M={M} K={K} N={N} g={g} plan={plan}")
+    Y = gu.gemm(packed, X)
+    Yref = oracle.gemm(X, q, s, z, g)
+    ok, worst, fro = acceptance(Y, Yref)
+    assert ok, (worst, fro, plan)
+    packed.close()
+
+
 @pytest.mark.parametrize("variant,split,waves", [(0, 1, 8), (0, 2, 16), (0, 5, 8), (1, 1, 16), (1, 3, 8), (2, 1, 8),
                                                  (2, 2, 16), (3, 1, 8), (3, 3, 16), (4, 1, 16), (4, 2, 8), (5, 1, 0),
                                                  (5, 3, 0), (6, 1, 0), (6, 2, 0), (7, 1, 0), (7, 3, 0), (8, 1, 0),

@@ -37,9 +37,9 @@ def test_static_scratch_entry_point_matches_the_allocating_one():
     # deep and narrow layers: too few column strips to fill the chip, so the plan splits K across CTAs and the
     # partial sums and arrival counters go through the scratch array
     big = wl.make(wl.Case("static_big", 48, 8192, 1024, 128, seed=11))
-    small = wl.make(wl.Case("static_small", 5, 2048, 512, 64, seed=12))
+    small = wl.make(wl.Case("static_small", 12, 12800, 512, 64, seed=12))
     pb, ps = gu.pack(big, 128), gu.pack(small, 64)
-    for name, packed, d, M in (("first", pb, big, 48), ("second, smaller", ps, small, 5), ("first again", pb, big, 20)):
+    for name, packed, d, M in (("first", pb, big, 48), ("second, smaller", ps, small, 12), ("first again", pb, big, 20)):
         plan = tm.tm_get_plan(packed, M)
         _say(f"static entry point, {name}: M={M} K={packed.K} N={packed.N} plan={plan}")
         assert plan["split_k"] > 1, "the case is meant to use the scratch array"
