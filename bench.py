@@ -658,7 +658,11 @@ CEILING_SHORTLIST = [(0, 256, 1, 0), (1, 1024, 8, 1), (1, 1024, 4, 3), (2, 512, 
 OTHER_SHAPES = [("13B qkv", 5120, 15360, 128), ("13B gate_up", 5120, 27648, 128), ("13B down", 13824, 5120, 128),
                 ("8B-GQA qkv", 4096, 6144, 128), ("8B-GQA gate_up", 4096, 28672, 128), ("8B-GQA down", 14336, 4096, 128),
                 ("70B-GQA qkv", 8192, 10240, 128), ("70B down", 28672, 8192, 128), ("7B-28h gate_up", 3584, 37888, 128),
-                ("7B-28h down", 18944, 3584, 128), ("small g64", 2048, 8192, 64)]
+                ("7B-28h down", 18944, 3584, 128), ("small g64", 2048, 8192, 64),
+                # one GPU's share of a 70B model under 8-way tensor parallelism (column-parallel layers cut along N,
+                # row-parallel ones along K)
+                ("70B/8 qkv", 8192, 1280, 128), ("70B/8 attn_out", 1024, 8192, 128), ("70B/8 gate_up", 8192, 7168, 128),
+                ("70B/8 down", 3584, 8192, 128)]
 OTHER_MS = (1, 8, 16, 32, 64, 128, 512)
 
 

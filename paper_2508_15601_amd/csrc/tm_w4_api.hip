@@ -414,21 +414,44 @@ Plan make_plan(const tm_packed_w4* h, int M, int num_cu)
         pl.tiles_n = ceil_div(h->N, tile_bn(variant));
         pl.block = (unsigned)tile_threads(variant);
         int tiles = pl.tiles_m * pl.tiles_n;
-        // Split K only when fewer than half the CUs would get a tile, and only as far as the fp32 partial sums
-        // (written and read back once per split) stay below about half the weight bytes: split <= K / (32 M).
-        // (short tiles run one CTA per CU, so the split stops at one round of CTAs: K = 11008, N = 4096, M = 96 runs
-        // 29.0 us on 96 tiles split in two against 36.7 us split in three)
-        int want = tiles * 2 <= num_cu ? (tile_bm(variant) <= 64 ? num_cu / tiles : (2 * num_cu) / tiles) : 1;
-        if (want > 4) want = 4;
-        int by_traffic = h->K / (32 * (M > 0 ? M : 1));
-        if (by_traffic < 1) by_traffic = 1;
-        if (want > by_traffic) want = by_traffic;
-        int max_by_k = KU / 4 > 0 ? KU / 4 : 1;    // keep at least four units per CTA
-        split = want < max_by_k ? want : max_by_k;
+        // Split K only when fewer than half the CUs would get a tile, at most up to one round of CTAs, and as far as an
+        // estimate of the launch says it pays: a fixed part, the K loop of one CTA (per 1024 rows of K: 2.4 us on the
+        // 64 x 64 tile, more on the larger ones), and for a split the hand-over of the partial tiles (three dependent
+        // trips through memory, about 2.5 us, plus the traffic of the partial sums).  Measured: K = N = 4096, M = 128
+        // 12.9 us split in two against 14.5 us unsplit; K = 8192, N = 2048, M = 128 13.9 us split in four against
+        // 23.7 us; K = 5120, N = 2560 14.0 us split in three against 18.0 us; K = 16384, N = 1024 16-17 us split in six
+        // against 42 us.
+        if (tiles * 2 <= num_cu) {
+            const int v = variant;
+            // ns per 128 rows of K
+            const long ck = v == kTile64x64 ? 300 : v == kTile32x128 || v == kTile32x96 ? 315 : v == kTile64x128 || v == kTile64x96 ? 390
+                          : v == kTile128x64 ? 410 : v == kTile128x128 ? 630 : 1080;
+            const long tile_bytes = (long)tile_bm(v) * tile_bn(v) * 4;
+            const int smax = num_cu / tiles < 8 ? num_cu / tiles : 8;
+            long best = -1;
+            for (int sp = 1; sp <= smax; ++sp) {
+                const int kps = ceil_div(KU, sp);
+                if (sp > 1 && (kps < 4 || ceil_div(KU, kps) != sp)) continue;
+                long est = 5500 + ck * kps / (w8 ? 2 : 1);                                   // 8-bit units are 64 rows
+                if (sp > 1) est += 2500 + 300 * sp + sp * tiles * tile_bytes / 4000;         // 4 MB of partial sums per us
+                if (best < 0 || est < best) {
+                    best = est;
+                    split = sp;
+                }
+            }
+        }
     }
     if (g_force_split > 0) split = g_force_split;
     if (pl.tiles_m * pl.tiles_n > kMaxCounters) split = 1;     // one arrival counter per output tile
     if (split > KU) split = KU;
+    // bytes of one K slice's partial sums: M x N floats in output order (decode kernels), whole tiles in the CTA-tile
+    // kernels' own order
+    size_t slice_bytes = out_bytes;
+    if (!is_skinny(variant)) {
+        slice_bytes = (size_t)pl.tiles_m * pl.tiles_n * tile_bm(variant) * tile_bn(variant) * sizeof(float);
+        max_split_ws = (int)(kPartialBudget / slice_bytes);
+        if (max_split_ws < 1) max_split_ws = 1;
+    }
     if (split > max_split_ws) split = max_split_ws;
     if (split < 1) split = 1;
     pl.ku_per_split = ceil_div(KU, split);
@@ -563,7 +586,7 @@ Plan make_plan(const tm_packed_w4* h, int M, int num_cu)
         int chunk = ceil_div(pl.tiles_m * pl.tiles_n, 8);      // tiles are dealt to the 8 XCDs in equal chunks
         pl.grid = (unsigned)(chunk * 8 * split);
     }
-    pl.ws_bytes = kCounterBytes + (split > 1 ? (size_t)split * out_bytes : 0);
+    pl.ws_bytes = kCounterBytes + (split > 1 ? (size_t)split * slice_bytes : 0);
     return pl;
 }
 

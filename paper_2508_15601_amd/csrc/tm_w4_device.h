@@ -36,7 +36,8 @@ struct GemmParams {
     const u32x4* W;           // packed weights, one u32x4 per (unit, lane)
     const uint32_t* SZ;       // packed scale|zero<<16 words
     uint16_t* Y;              // fp16 [M][N]
-    float* partial;           // split-K partial sums [split][M][N] (fp32)
+    float* partial;           // split-K partial sums (fp32): [split][M][N] in the decode kernels, [split][tile] whole
+                              // tiles in accumulator order in the CTA-tile kernels
     uint32_t* counters;       // split-K arrival counters, zero between launches
     int M, K, N;
     int KU;                   // K / 128

@@ -425,18 +425,23 @@ __device__ __forceinline__ void tile_body(const GemmParams& p, const int tile_m,
     }
 
     const int tile = tile_m + tile_n * p.tiles_m;          // counter index
+    // Partial tiles live in the workspace in accumulator order, [split][tile][wave][row tile][column tile][half][lane]
+    // pairs of floats: only CTAs of the same tile exchange them, so the layout is free, and in this one every store and
+    // load instruction of a wave covers 512 consecutive bytes (in output order a wave's 8-byte pieces would fall into
+    // sixteen different rows).  Rows and columns past the edges of Y are stored and summed like the rest and never
+    // written to Y.
+    constexpr size_t kTileFloats = (size_t)BM * BN;
+    const size_t tile_slot = (size_t)tile * kTileFloats + (size_t)wave * (TM * TN * 256) + (size_t)lane * 2;
+    const size_t split_stride = (size_t)p.tiles_m * p.tiles_n * kTileFloats;
+    if (writer) {
+        float* dst = p.partial + (size_t)sk * split_stride + tile_slot;
 #pragma unroll
-    for (int i = 0; i < TM; ++i) {
-        const int m = m0 + i * 16 + c;
-        if (m >= p.M || !writer) continue;
+        for (int i = 0; i < TM; ++i)
 #pragma unroll
-        for (int j = 0; j < TN; ++j) {
-            const int nt = nt0 + j;
-            if (nt >= nt_end) continue;
-            float* dst = p.partial + ((size_t)sk * p.M + m) * p.N + nt * 16 + 4 * h;
-            st_partial2(dst, acc[i][j][0], acc[i][j][1]);
-            st_partial2(dst + 2, acc[i][j][2], acc[i][j][3]);
-        }
+            for (int j = 0; j < TN; ++j) {
+                st_partial2(dst + (i * TN + j) * 256, acc[i][j][0], acc[i][j][1]);
+                st_partial2(dst + (i * TN + j) * 256 + 128, acc[i][j][2], acc[i][j][3]);
+            }
     }
     wait_stores_done();
     __syncthreads();
@@ -446,47 +451,66 @@ __device__ __forceinline__ void tile_body(const GemmParams& p, const int tile_m,
     }
     __syncthreads();
     if (!s_last) return;
-    // The last CTA adds the partial tiles in split order.  Every load is a round trip past the caches, so the loads of a
-    // whole row of tiles and of up to four splits are issued before the first add (the accumulators are dead by now:
+    // The last CTA adds the partial tiles in split order.  Every load is a round trip past the caches (1.5-2 us), so the
+    // work is spread and batched: wave set kg takes the row tiles kg, kg + KG, ... (any set can - the sums come from
+    // global memory, not from its accumulators, and its waves cover the same columns as set 0's), and the loads of RB
+    // row tiles x up to UB splits x all column tiles are issued before the first add (the accumulators are dead by now:
     // their registers hold the loaded values).
-    const size_t split_stride = (size_t)p.M * p.N;
     constexpr int UB = (TM <= 8 && TN <= 4) ? 4 : 1;       // splits per batch; the largest tiles have no registers to spare
+    constexpr int RC = (TM + KG - 1) / KG;                 // row tiles per wave set
+    constexpr int RBmax = 64 / (UB * TN * 4) > 0 ? 64 / (UB * TN * 4) : 1;
+    constexpr int RB = RBmax < RC ? RBmax : RC;            // row tiles per batch
 #pragma unroll
-    for (int i = 0; i < TM; ++i) {
-        const int m = m0 + i * 16 + c;
-        if (m >= p.M || !writer) continue;
-        float v[TN][4];
+    for (int r0 = 0; r0 < RC; r0 += RB) {
+        float v[RB][TN][4];
+        int mrow[RB], irow[RB];
+        bool live[RB];
 #pragma unroll
-        for (int j = 0; j < TN; ++j)
+        for (int rr = 0; rr < RB; ++rr) {
+            const int i = kg + (r0 + rr) * KG;
+            const int m = m0 + i * 16 + c;
+            live[rr] = r0 + rr < RC && i < TM && m < p.M;
+            mrow[rr] = m;
+            irow[rr] = i < TM ? i : 0;                     // row tiles past the last re-read the first
 #pragma unroll
-            for (int r = 0; r < 4; ++r) v[j][r] = 0.f;
+            for (int j = 0; j < TN; ++j)
+#pragma unroll
+                for (int r = 0; r < 4; ++r) v[rr][j][r] = 0.f;
+        }
         for (int s0 = 0; s0 < p.split; s0 += UB) {
-            float a[UB][TN][4];
+            float a[RB][UB][TN][4];
 #pragma unroll
-            for (int u = 0; u < UB; ++u) {
-                const float* row = p.partial + (size_t)min(s0 + u, p.split - 1) * split_stride + (size_t)m * p.N + 4 * h;
+            for (int rr = 0; rr < RB; ++rr)
 #pragma unroll
-                for (int j = 0; j < TN; ++j) {
-                    const int nt = min(nt0 + j, nt_end - 1);           // tiles past the edge re-read the last one
-                    ld_partial2(row + nt * 16, a[u][j][0], a[u][j][1]);
-                    ld_partial2(row + nt * 16 + 2, a[u][j][2], a[u][j][3]);
+                for (int u = 0; u < UB; ++u) {
+                    const float* src = p.partial + (size_t)min(s0 + u, p.split - 1) * split_stride + tile_slot + (size_t)irow[rr] * (TN * 256);
+#pragma unroll
+                    for (int j = 0; j < TN; ++j) {
+                        ld_partial2(src + j * 256, a[rr][u][j][0], a[rr][u][j][1]);
+                        ld_partial2(src + j * 256 + 128, a[rr][u][j][2], a[rr][u][j][3]);
+                    }
                 }
-            }
 #pragma unroll
             for (int u = 0; u < UB; ++u) {
                 if (s0 + u < p.split) {
 #pragma unroll
-                    for (int j = 0; j < TN; ++j)
+                    for (int rr = 0; rr < RB; ++rr)
 #pragma unroll
-                        for (int r = 0; r < 4; ++r) v[j][r] += a[u][j][r];
+                        for (int j = 0; j < TN; ++j)
+#pragma unroll
+                            for (int r = 0; r < 4; ++r) v[rr][j][r] += a[rr][u][j][r];
                 }
             }
         }
 #pragma unroll
-        for (int j = 0; j < TN; ++j) {
-            const int nt = nt0 + j;
-            if (nt >= nt_end) continue;
-            store_quad(p, m, nt * 16 + 4 * h, v[j][0], v[j][1], v[j][2], v[j][3]);
+        for (int rr = 0; rr < RB; ++rr) {
+            if (!live[rr]) continue;
+#pragma unroll
+            for (int j = 0; j < TN; ++j) {
+                const int nt = nt0 + j;
+                if (nt >= nt_end) continue;
+                store_quad(p, mrow[rr], nt * 16 + 4 * h, v[rr][j][0], v[rr][j][1], v[rr][j][2], v[rr][j][3]);
+            }
         }
     }
     if (tid == 0) __hip_atomic_store(&p.counters[tile], 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
