@@ -191,6 +191,15 @@ int ceil_div(int a, int b) { return (a + b - 1) / b; }
 //    the CTA (8 or 16 waves), and across CTAs only when the strips alone cannot fill the chip.
 //  - larger M: CTA tiles; the tile grows with M, and K is split across CTAs while the tiles are too few.
 // Split factors are bounded so that every wave keeps at least one unit and the partial sums fit the workspace.
+// Floats of split-K partial sums one CTA of a decode kernel hands over: its whole accumulator tile, 16 rows per row
+// tile x 16 columns per column tile of the kernel's template width (at least the widest strip of the launch).
+int decode_slot_floats(int variant, int NT, int strips)
+{
+    const int widest = ceil_div(NT, strips > 0 ? strips : 1);
+    const int ntw = skinny_ntw(variant) > widest ? skinny_ntw(variant) : widest;
+    return ntw * 256 * (skinny_rows(variant) / 16);
+}
+
 Plan make_plan(const tm_packed_w4* h, int M, int num_cu)
 {
     // packed units along K: 128 rows of 4-bit codes or 64 rows of 8-bit codes (1 KiB per 16 columns either way)
@@ -290,7 +299,7 @@ Plan make_plan(const tm_packed_w4* h, int M, int num_cu)
             pl.tiles_n = strips;
             pl.block = (unsigned)w * 64;
             pl.grid = (unsigned)(strips * split);
-            pl.ws_bytes = kCounterBytes + (split > 1 ? (size_t)split * out_bytes : 0);
+            pl.ws_bytes = kCounterBytes + (split > 1 ? (size_t)split * strips * decode_slot_floats(pl.variant, NT, strips) * sizeof(float) : 0);
         };
         if (g_force_variant >= 0) {
             const int ntw = skinny_ntw(g_force_variant);
@@ -586,6 +595,15 @@ Plan make_plan(const tm_packed_w4* h, int M, int num_cu)
         int chunk = ceil_div(pl.tiles_m * pl.tiles_n, 8);      // tiles are dealt to the 8 XCDs in equal chunks
         pl.grid = (unsigned)(chunk * 8 * split);
     }
+    if (is_skinny(variant)) {
+        slice_bytes = (size_t)pl.strips * decode_slot_floats(variant, NT, pl.strips) * sizeof(float);
+        if (split > 1 && split * slice_bytes > kPartialBudget) {       // never at the benchmark shapes: the unsplit ring-buffered kernel
+            split = pl.split = 1;
+            pl.ku_per_split = KU;
+            pl.stream_ni = 0;
+            pl.grid = (unsigned)pl.tiles_n;
+        }
+    }
     pl.ws_bytes = kCounterBytes + (split > 1 ? (size_t)split * slice_bytes : 0);
     return pl;
 }
@@ -678,6 +696,7 @@ int run_gemm(const uint16_t* X, const tm_packed_w4* h, uint16_t* Y, int M, void*
     p.tiles_m = pl.tiles_m;
     p.tiles_n = pl.tiles_n;
     p.strips = pl.strips;
+    p.slot_floats = is_skinny(pl.variant) ? decode_slot_floats(pl.variant, p.NT, pl.strips) : 0;
     if (pl.strips > 0) {
         p.strip_base = p.NT / pl.strips;
         p.strip_rem = p.NT % pl.strips;

@@ -36,8 +36,8 @@ struct GemmParams {
     const u32x4* W;           // packed weights, one u32x4 per (unit, lane)
     const uint32_t* SZ;       // packed scale|zero<<16 words
     uint16_t* Y;              // fp16 [M][N]
-    float* partial;           // split-K partial sums (fp32): [split][M][N] in the decode kernels, [split][tile] whole
-                              // tiles in accumulator order in the CTA-tile kernels
+    float* partial;           // split-K partial sums (fp32), in the kernels' accumulator order: [split][strip] slots
+                              // of slot_floats in the decode kernels, [split][tile] whole tiles in the CTA-tile kernels
     uint32_t* counters;       // split-K arrival counters, zero between launches
     int M, K, N;
     int KU;                   // K / 128
@@ -57,6 +57,7 @@ struct GemmParams {
     int epi;                  // 0: none of the three is set (the stores take the plain path on one test)
     int mp_log;               // stream kernels: log2 of M rounded up to a power of two (rows of an X region in LDS)
     int red_off;              // stream kernels: LDS byte offset of the reduction tiles; 0 = they reuse the X regions
+    int slot_floats;          // decode kernels: floats of partial sums per (K slice, strip): 64 * M rounded up to 16 * widest strip
 };
 
 // Grouped (mixture-of-experts) launch: rows [offsets[e], offsets[e+1]) of X and Y belong to expert e.

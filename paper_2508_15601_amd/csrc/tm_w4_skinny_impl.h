@@ -191,7 +191,7 @@ __device__ __forceinline__ void skinny_reduce(const GemmParams& p, f32x4 (&acc)[
             if (p.split == 1) {
                 store_pair(p, m, n, v, vr);
             } else {
-                st_partial2(p.partial + ((size_t)sk * p.M + m) * p.N + n, v, vr);
+                st_partial2(p.partial + ((size_t)sk * p.strips + strip) * p.slot_floats + (mt * NTW * 4 + reg) * 64 + lane, v, vr);
             }
         }
     }
@@ -217,7 +217,9 @@ __device__ __forceinline__ void skinny_reduce(const GemmParams& p, f32x4 (&acc)[
                     if (m >= p.M || col >= ntw * 16) continue;
                     const int n = nt0 * 16 + col;
                     float v0, v1;
-                    sum_partials2(p.partial + (size_t)m * p.N + n, (size_t)p.M * p.N, p.split, v0, v1);
+                    // the slot keeps the accumulator order: register (col / 16) * 4 + row % 4, lane 16 * (row / 4) + col % 16
+                    const int at = (mt * NTW * 4 + (col >> 4) * 4 + (row & 3)) * 64 + 16 * (row >> 2) + (col & 15);
+                    sum_partials2(p.partial + (size_t)strip * p.slot_floats + at, (size_t)p.strips * p.slot_floats, p.split, v0, v1);
                     store_pair(p, m, n, v0, v1);
                 }
             }

@@ -79,7 +79,7 @@ __device__ __forceinline__ void stream_reduce(const GemmParams& p, const f32x4 (
             }
             const int n = (nt0 + (jr >> 2)) * 16 + (pl & 15);
             if (p.split == 1) store_pair(p, m, n, v0, v1);
-            else st_partial2(p.partial + ((size_t)sk * p.M + m) * p.N + n, v0, v1);
+            else st_partial2(p.partial + ((size_t)sk * p.strips + strip) * p.slot_floats + jr * 64 + pl, v0, v1);
         }
     }
     if (p.split > 1) {
@@ -99,7 +99,7 @@ __device__ __forceinline__ void stream_reduce(const GemmParams& p, const f32x4 (
                 if (jr < NTW * 4 && m < p.M) {
                     const int n = (nt0 + (jr >> 2)) * 16 + (pl & 15);
                     float v0, v1;
-                    sum_partials2(p.partial + (size_t)m * p.N + n, (size_t)p.M * p.N, p.split, v0, v1);
+                    sum_partials2(p.partial + (size_t)strip * p.slot_floats + jr * 64 + pl, (size_t)p.strips * p.slot_floats, p.split, v0, v1);
                     store_pair(p, m, n, v0, v1);
                 }
             }

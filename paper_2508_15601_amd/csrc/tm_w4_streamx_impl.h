@@ -183,7 +183,7 @@ __device__ __forceinline__ void rows_body(const GemmParams& p, const int strip, 
                 }
                 const int n = (nt0 + (jr >> 2)) * 16 + (pl & 15);
                 if (p.split == 1) store_pair(p, m, n, v0, v1);
-                else st_partial2(p.partial + ((size_t)sk * p.M + m) * p.N + n, v0, v1);
+                else st_partial2(p.partial + ((size_t)sk * p.strips + strip) * p.slot_floats + (im * NTW * 4 + jr) * 64 + pl, v0, v1);
             }
         }
     }
@@ -206,7 +206,8 @@ __device__ __forceinline__ void rows_body(const GemmParams& p, const int strip, 
                     if (jr < NTW * 4 && m < p.M) {
                         const int n = (nt0 + (jr >> 2)) * 16 + (pl & 15);
                         float v0, v1;
-                        sum_partials2(p.partial + (size_t)m * p.N + n, (size_t)p.M * p.N, p.split, v0, v1);
+                        sum_partials2(p.partial + (size_t)strip * p.slot_floats + (im * NTW * 4 + jr) * 64 + pl,
+                                      (size_t)p.strips * p.slot_floats, p.split, v0, v1);
                         store_pair(p, m, n, v0, v1);
                     }
                 }
