@@ -449,6 +449,67 @@ Plan make_plan(const tm_packed_w4* h, int M, int num_cu)
                 }
             }
         }
+        // Above 64 rows, 4-bit codes, nothing forced: tile shape and K split are then weighed together.  The shape
+        // chosen above (on the unsplit launch) is compared with itself split and with the four shapes up to 128 x 128
+        // split two to eight ways into at most one CTA per CU; another shape is taken if the estimate puts it 5 % or
+        // more ahead.  The estimate is a least-squares fit to 1041 timed plans (16 layer shapes, K 2048 ... 28672,
+        // N 1024 ... 28672, M 96 ... 512, rms error 9 %): a fixed part, the K loop of a CTA (per shape; faster while the
+        // chip is not full; per round of CTAs), and for a split the hand-over of the partial tiles.  Its picks average
+        // 1 % behind the fastest measured plan of a case (worst 13 %), where shape first and split second averaged
+        // 3.6 % (worst 20 %): K = 13824, N = 5120, M = 128 runs 27.6 us on 64 x 128 tiles split in three against
+        // 38.9 us on 64 x 64 tiles unsplit; K = 11008, N = 4096, M = 256 31.3 against 38.4 us; K = 28672, N = 8192,
+        // M = 256 124 us on 128 x 128 tiles split in four against 139 us.
+        if (!w8 && M > 64 && g_force_variant < 0 && g_force_split == 0) {
+            auto joint = [&](int v, int sp) -> double {
+                const double ck = v == kTile32x128 ? 371 : v == kTile64x64 ? 337 : v == kTile64x128 ? 532 : v == kTile128x128 ? 397 : 848;
+                const long t = (long)ceil_div(M, tile_bm(v)) * ceil_div(h->N, tile_bn(v));
+                const long ctas = t * sp;
+                const int rounds = (int)((ctas + num_cu - 1) / num_cu);
+                const double occ = ctas < num_cu ? (double)ctas / num_cu : 1.0;
+                double r = rounds;
+                if (tile_bm(v) >= 128) r = rounds == 1 ? (v == kTile128x128 ? 2.498 : 2.239) : 1.0 + 3.005 * (rounds - 1);
+                double est = 5576.0 + ck * ceil_div(KU, sp) * (0.763 + 0.237 * occ) * r;
+                if (sp > 1) est += -215.0 + 714.0 * sp + 0.000462 * sp * t * tile_bm(v) * tile_bn(v) * 4;
+                return est;
+            };
+            auto whole = [&](int sp) { const int kps = ceil_div(KU, sp); return sp == 1 || (kps >= 4 && ceil_div(KU, kps) == sp); };
+            const bool modelled = variant == kTile32x128 || variant == kTile64x64 || variant == kTile64x128 ||
+                                  variant == kTile128x128 || variant == kTile128x256;
+            if (modelled) {
+                const int splits[6] = {1, 2, 3, 4, 6, 8};
+                double base = -1;
+                int base_split = 1;
+                for (int sp : splits) {
+                    if (!whole(sp) || (sp > 1 && (long)tiles * sp > num_cu)) continue;
+                    const double e = joint(variant, sp);
+                    if (base < 0 || e < base) {
+                        base = e;
+                        base_split = sp;
+                    }
+                }
+                int best_v = variant, best_s = base_split;
+                double best = base;
+                const int others[4] = {kTile64x128, kTile128x128, kTile64x64, kTile32x128};
+                for (int v : others) {
+                    if (v == variant) continue;
+                    const long t = (long)ceil_div(M, tile_bm(v)) * ceil_div(h->N, tile_bn(v));
+                    for (int sp : splits) {
+                        if (sp == 1 || !whole(sp) || t * sp > num_cu) continue;
+                        const double e = joint(v, sp);
+                        if (e < 0.95 * base && e < best) {
+                            best = e;
+                            best_v = v;
+                            best_s = sp;
+                        }
+                    }
+                }
+                variant = pl.variant = best_v;
+                split = best_s;
+                pl.tiles_m = ceil_div(M, tile_bm(variant));
+                pl.tiles_n = ceil_div(h->N, tile_bn(variant));
+                pl.block = (unsigned)tile_threads(variant);
+            }
+        }
     }
     if (g_force_split > 0) split = g_force_split;
     if (pl.tiles_m * pl.tiles_n > kMaxCounters) split = 1;     // one arrival counter per output tile
