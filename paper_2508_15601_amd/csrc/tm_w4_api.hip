@@ -90,6 +90,7 @@ int ensure_workspace(int dev)
     // so that the first GEMM on any stream finds the counters at zero.
     if (e == hipSuccess) e = hipStreamSynchronize(nullptr);
     if (e == hipSuccess) e = stream_setup();       // per-kernel LDS limits of the one-shot decode kernels
+    if (e == hipSuccess) e = stream_grouped_setup();
     if (e != hipSuccess) {
         (void)hipFree(ws);
         return fail_hip(e, "workspace set-up");
@@ -1087,6 +1088,49 @@ void tm_free_expert_group(tm_expert_group* group)
     delete group;
 }
 
+// Decode batches of 4-bit experts (at most about sixteen rows per expert): the one-shot kernels, launched as the
+// single-GEMM plan of one expert at sixteen rows would launch them, once per expert that has rows (8 experts of
+// 4096 x 28672, 2 rows: 27 us against 32 us on the ring-buffered grouped kernel).  False: no such plan.
+static bool grouped_one_shot(const tm_expert_group* group, int variant, int strips, int num_cu, Plan* one)
+{
+    if (group->bits != 4 || !is_skinny(variant) || skinny_rows(variant) != 16 || g_force_variant >= 0 || g_force_stage == 1) return false;
+    const int KU = group->K / kUnitK, NT = group->N / kUnitN;
+    // large experts: the strips the single-GEMM plan of one expert takes at sixteen rows, as long as a CTA still streams
+    // 128 KiB of weights or more (8 experts of 4096 x 28672, 8 rows: 63.9 us on 256 strips per expert against 70.5 us
+    // on the 224 strips of the grouped plan); small experts keep the grouped plan's wider strips (128 experts of
+    // 4096 x 3072, 32 rows: 44 us on 24 strips per expert against 65 us on 192)
+    {
+        tm_packed_w4 shape{};
+        shape.K = group->K;
+        shape.N = group->N;
+        shape.group = group->group;
+        shape.bits = 4;
+        const Plan single = make_plan(&shape, 16, num_cu);
+        if (single.stream_ni > 0 && single.split == 1 && is_skinny(single.variant) && skinny_rows(single.variant) == 16 &&
+            (size_t)group->K * group->N / 2 / single.strips >= 128 * 1024) {
+            *one = single;
+            return true;
+        }
+    }
+    const int widest = ceil_div(NT, strips);
+    if (widest > 8) return false;
+    for (int w : {16, 8}) {
+        if (g_force_waves >= 8 && w != g_force_waves) continue;
+        const int ni = stream_units_per_wave(widest, group->group, KU, w);
+        int red_off;
+        if (ni > 0 && stream_lds(ni, 4, widest, w, &red_off) <= kStreamLdsBudget) {
+            *one = Plan{};
+            one->variant = variant;
+            one->strips = strips;
+            one->split = 1;
+            one->stream_ni = ni;
+            one->block = (unsigned)w * 64;
+            return true;
+        }
+    }
+    return false;
+}
+
 static int run_grouped(const uint16_t* X, const tm_expert_group* group, const int32_t* offsets, uint16_t* Y, int total_rows,
                        int act, tm_stream stream)
 {
@@ -1124,6 +1168,17 @@ static int run_grouped(const uint16_t* X, const tm_expert_group* group, const in
     if (!is_skinny(variant) && (uint64_t)total_rows * (uint64_t)group->K >= (1ull << 31))
         return fail(TM_EINVAL, "total_rows*K must be below 2^31 for prefill-sized expert loads");
     hipError_t e;
+    Plan one;
+    if (grouped_one_shot(group, variant, strips, g_dev[dev].num_cu, &one)) {
+        int red_off;
+        gp.strips = one.strips;
+        gp.strip_base = gp.NT / one.strips;
+        gp.strip_rem = gp.NT % one.strips;
+        gp.lds_bytes = (int)stream_lds(one.stream_ni, 4, ceil_div(gp.NT, one.strips), (int)one.block / 64, &red_off);
+        e = launch_stream_grouped(gp, group->experts, group->group, one.stream_ni, (int)one.block, (hipStream_t)stream);
+        if (e != hipSuccess) return fail_hip(e, "grouped kernel launch");
+        return TM_OK;
+    }
     if (group->bits == 8) {
         e = !is_skinny(variant) ? launch_tile_grouped_8bit(gp, variant, group->experts, group->group, group->fp8, (hipStream_t)stream)
             : group->fp8       ? launch_skinny_grouped_f8(gp, variant, group->experts, group->group, (hipStream_t)stream)

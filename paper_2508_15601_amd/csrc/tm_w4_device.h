@@ -70,6 +70,7 @@ struct GroupedParams {
     int strip_base, strip_rem;  // as in GemmParams
     int tiles_n, mtiles;        // tile kernels: column tiles, and the upper bound of row tiles over all experts
     int act;                    // 1: gate/up experts, Y[r][n/2] = silu(gate) * up, row stride N/2
+    int lds_bytes;              // one-shot decode kernels: dynamic LDS of the launch
 };
 
 // Quantised KV cache of the attention kernels: 8-bit codes, one scale/zero pair per token and head.

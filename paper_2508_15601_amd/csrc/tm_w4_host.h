@@ -101,6 +101,8 @@ hipError_t launch_attn_prefill(const AttnCache& kv, const uint16_t* Q, const int
 hipError_t launch_skinny(const GemmParams& p, const Plan& plan, int group, hipStream_t stream);
 hipError_t launch_stream(const GemmParams& p, const Plan& plan, int group, hipStream_t stream);
 hipError_t stream_setup();                                             // once per device, outside any capture
+hipError_t stream_grouped_setup();                                     // the same for the grouped form
+hipError_t launch_stream_grouped(const GroupedParams& gp, int experts, int group, int ni, int block, hipStream_t stream);
 int stream_units_per_wave(int ntw, int group, int kus, int waves);     // 0: no one-shot kernel is built for this shape
 constexpr size_t kStreamLdsBudget = 156 * 1024;                       // of the 160 KiB of a CU
 size_t stream_lds(int ni, int mp_log, int ntw, int waves, int* red_off);

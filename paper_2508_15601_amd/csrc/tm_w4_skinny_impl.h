@@ -299,24 +299,18 @@ __global__ __launch_bounds__(MAXW * 64) void skinny_kernel(GemmParams p)
     skinny_body<TM, NTW, GPU, D, BITS>(p, blockIdx.x, blockIdx.y, red, s_last);
 }
 
-// Grouped form for mixture-of-experts layers (the paper's evaluation covers MoE models, Sec. 5.1; their expert GEMMs
-// are this same GEMM once per expert): rows [offsets[e], offsets[e+1]) of X and Y belong to expert e, whose packed
-// weights the pointer table names.  blockIdx.x is the strip, blockIdx.y selects among the experts that have rows.
-// Experts with more than 16*TM rows are taken 16*TM rows at a time.
-template <int TM, int NTW, int GPU, int D, int MAXW, int BITS = 4>
-__global__ __launch_bounds__(MAXW * 64) void skinny_grouped_kernel(GroupedParams gp)
+// The `which`-th expert that has rows: its row range and the addresses of its packed weights and scale/zero words.
+// Every wave scans the offsets 64 experts at a time; each lane also fetches its candidate's two table entries, so that the
+// scan, the row range and the buffer addresses cost a single round trip to memory.
+struct ExpertRows {
+    int r0, r1;
+    uint64_t w, sz;
+    bool found;
+};
+__device__ __forceinline__ ExpertRows find_expert(const GroupedParams& gp, int which, int lane)
 {
-    extern __shared__ float red[];
-    __shared__ uint32_t s_last;
-    // blockIdx.y counts experts that have rows, not experts: the grid is only as tall as the number of experts that
-    // can be active (min(experts, rows)), and every wave finds "its" expert by scanning the offsets 64 experts at a
-    // time.  Each lane also fetches its candidate's two table entries, so that the scan, the row range and the
-    // buffer addresses cost a single round trip to memory.
-    const int lane = threadIdx.x & 63;
-    int want = blockIdx.y;                          // index among the experts with rows that is still to be skipped
-    int r0 = 0, r1 = 0;
-    uint64_t wptr = 0, szptr = 0;
-    bool found = false;
+    ExpertRows er{0, 0, 0, 0, false};
+    int want = which;                               // index among the experts with rows that is still to be skipped
     for (int base = 0; base < gp.experts; base += 64) {
         const int e = base + lane;
         int a = 0, b = 0;
@@ -336,21 +330,26 @@ __global__ __launch_bounds__(MAXW * 64) void skinny_grouped_kernel(GroupedParams
             const int before = __popcll(mask & ((1ull << lane) - 1ull));
             const uint64_t hit = __ballot(has_rows && before == want);
             const int src = __builtin_ctzll(hit);   // exactly one lane
-            r0 = __builtin_amdgcn_readlane(a, src);
-            r1 = __builtin_amdgcn_readlane(b, src);
-            wptr = ((uint64_t)(uint32_t)__builtin_amdgcn_readlane((int)(tw >> 32), src) << 32) |
+            er.r0 = __builtin_amdgcn_readlane(a, src);
+            er.r1 = __builtin_amdgcn_readlane(b, src);
+            er.w = ((uint64_t)(uint32_t)__builtin_amdgcn_readlane((int)(tw >> 32), src) << 32) |
                    (uint32_t)__builtin_amdgcn_readlane((int)(uint32_t)tw, src);
-            szptr = ((uint64_t)(uint32_t)__builtin_amdgcn_readlane((int)(ts >> 32), src) << 32) |
+            er.sz = ((uint64_t)(uint32_t)__builtin_amdgcn_readlane((int)(ts >> 32), src) << 32) |
                     (uint32_t)__builtin_amdgcn_readlane((int)(uint32_t)ts, src);
-            found = true;
+            er.found = true;
             break;
         }
         want -= count;
     }
-    if (!found) return;                             // fewer experts have rows than the grid is tall
+    return er;
+}
+
+// What of a launch's parameters is the same for every expert.
+__device__ __forceinline__ GemmParams expert_params(const GroupedParams& gp, const ExpertRows& er)
+{
     GemmParams p{};
-    p.W = (const u32x4*)wptr;
-    p.SZ = (const uint32_t*)szptr;
+    p.W = (const u32x4*)er.w;
+    p.SZ = (const uint32_t*)er.sz;
     p.K = gp.K;
     p.N = gp.N;
     p.ldy = gp.act ? gp.N / 2 : gp.N;
@@ -364,6 +363,24 @@ __global__ __launch_bounds__(MAXW * 64) void skinny_grouped_kernel(GroupedParams
     p.strips = gp.strips;
     p.strip_base = gp.strip_base;
     p.strip_rem = gp.strip_rem;
+    return p;
+}
+
+// Grouped form for mixture-of-experts layers (the paper's evaluation covers MoE models, Sec. 5.1; their expert GEMMs
+// are this same GEMM once per expert): rows [offsets[e], offsets[e+1]) of X and Y belong to expert e, whose packed
+// weights the pointer table names.  blockIdx.x is the strip, blockIdx.y selects among the experts that have rows
+// (the grid is only as tall as the number of experts that can be active, min(experts, rows)).
+// Experts with more than 16*TM rows are taken 16*TM rows at a time.
+template <int TM, int NTW, int GPU, int D, int MAXW, int BITS = 4>
+__global__ __launch_bounds__(MAXW * 64) void skinny_grouped_kernel(GroupedParams gp)
+{
+    extern __shared__ float red[];
+    __shared__ uint32_t s_last;
+    const ExpertRows er = find_expert(gp, blockIdx.y, threadIdx.x & 63);
+    const int r0 = er.r0, r1 = er.r1;
+    const bool found = er.found;
+    if (!found) return;                             // fewer experts have rows than the grid is tall
+    GemmParams p = expert_params(gp, er);
     for (int m0 = r0; m0 < r1; m0 += 16 * TM) {
         if (m0 != r0) __syncthreads();             // the previous chunk's reads of red are done
         p.X = gp.X + (size_t)m0 * gp.K;

@@ -281,6 +281,40 @@ __global__ __launch_bounds__(MAXW * 64) void stream_kernel(GemmParams p)
     stream_body<NTW, GPU, NI, MAXW>(p, strip, sk, nt0, stream_smem, s_last);
 }
 
+// Grouped (mixture-of-experts) form of the one-shot kernels: blockIdx.y selects among the experts that have rows, as in
+// skinny_grouped_kernel; an expert's rows are taken sixteen at a time, each pass a one-shot GEMM of its own (so the form
+// is meant for decode batches, where an expert seldom has more than sixteen rows).  The LDS of the launch is sized for
+// sixteen rows; the reduction tiles lie behind the X regions of the pass where both fit.
+template <int NTW, int GPU, int NI, int MAXW>
+__global__ __launch_bounds__(MAXW * 64) void stream_grouped_kernel(GroupedParams gp)
+{
+    extern __shared__ __attribute__((aligned(16))) unsigned char stream_smem[];
+    __shared__ uint32_t s_last;
+    const ExpertRows er = find_expert(gp, blockIdx.y, threadIdx.x & 63);
+    if (!er.found) return;                          // fewer experts have rows than the grid is tall
+    GemmParams p = expert_params(gp, er);
+    const int strip = blockIdx.x;
+    const int nt0 = strip * gp.strip_base + min(strip, gp.strip_rem);
+    const bool narrow = NTW > 1 && strip >= gp.strip_rem && gp.strip_base < NTW;      // CTA-uniform
+    for (int m0 = er.r0; m0 < er.r1; m0 += 16) {
+        if (m0 != er.r0) __syncthreads();           // the previous pass is done with LDS
+        p.X = gp.X + (size_t)m0 * gp.K;
+        p.Y = gp.Y + (size_t)m0 * p.ldy;
+        p.M = min(16, er.r1 - m0);
+        p.mp_log = p.M > 8 ? 4 : p.M > 4 ? 3 : p.M > 2 ? 2 : p.M > 1 ? 1 : 0;
+        const int x_bytes = ((((NI << p.mp_log) + 3) >> 2) << 10) * MAXW;
+        const int red_bytes = MAXW * NTW * 4 * 64 * (int)sizeof(float);
+        p.red_off = x_bytes + red_bytes <= gp.lds_bytes ? x_bytes : 0;
+        if constexpr (NTW > 1) {
+            if (narrow) {
+                stream_body<NTW - 1, GPU, NI, MAXW>(p, strip, 0, nt0, stream_smem, s_last);
+                continue;
+            }
+        }
+        stream_body<NTW, GPU, NI, MAXW>(p, strip, 0, nt0, stream_smem, s_last);
+    }
+}
+
 // LDS layout of a launch: the waves' X regions (whole 1 KiB load instructions each), and the waves' reduction tiles
 // behind them if both fit into `budget` bytes, else in the same place (red_off = 0).
 inline size_t stream_lds_bytes(int ni, int mp_log, int ntw, int waves, size_t budget, int* red_off)
@@ -331,6 +365,30 @@ hipError_t stream_raise_one()
     }
 }
 
+template <int NTW, int GPU, int NI, int MAXW>
+hipError_t launch_stream_grouped_one(const GroupedParams& gp, int experts, int block, hipStream_t stream)
+{
+    if constexpr (stream_built(NTW, GPU, NI, MAXW)) {
+        dim3 grid(gp.strips, gp.total_rows < experts ? gp.total_rows : experts);
+        if (block != MAXW * 64) return hipErrorInvalidValue;
+        hipLaunchKernelGGL((stream_grouped_kernel<NTW, GPU, NI, MAXW>), grid, dim3(block), gp.lds_bytes, stream, gp);
+        return hipGetLastError();
+    } else {
+        return hipErrorInvalidValue;
+    }
+}
+
+template <int NTW, int GPU, int NI, int MAXW>
+hipError_t stream_grouped_raise_one()
+{
+    if constexpr (stream_built(NTW, GPU, NI, MAXW)) {
+        return hipFuncSetAttribute((const void*)stream_grouped_kernel<NTW, GPU, NI, MAXW>,
+                                   hipFuncAttributeMaxDynamicSharedMemorySize, (int)kStreamLdsBudget);
+    } else {
+        return hipSuccess;
+    }
+}
+
 template <int NTW, int NI, int MAXW>
 hipError_t launch_stream_cfg(const GemmParams& p, const Plan& plan, int group, size_t lds, hipStream_t stream)
 {
@@ -338,6 +396,17 @@ hipError_t launch_stream_cfg(const GemmParams& p, const Plan& plan, int group, s
         case 128: return launch_stream_one<NTW, 1, NI, MAXW>(p, plan, lds, stream);
         case 64: return launch_stream_one<NTW, 2, NI, MAXW>(p, plan, lds, stream);
         case 32: return launch_stream_one<NTW, 4, NI, MAXW>(p, plan, lds, stream);
+        default: return hipErrorInvalidValue;
+    }
+}
+
+template <int NTW, int NI, int MAXW>
+hipError_t launch_stream_grouped_cfg(const GroupedParams& gp, int experts, int group, int block, hipStream_t stream)
+{
+    switch (group) {
+        case 128: return launch_stream_grouped_one<NTW, 1, NI, MAXW>(gp, experts, block, stream);
+        case 64: return launch_stream_grouped_one<NTW, 2, NI, MAXW>(gp, experts, block, stream);
+        case 32: return launch_stream_grouped_one<NTW, 4, NI, MAXW>(gp, experts, block, stream);
         default: return hipErrorInvalidValue;
     }
 }
