@@ -240,18 +240,22 @@ def test_small_shapes_auto_plan(tm, oracle, M, K, N, g):
     assert ok, (worst, fro)
 
 
-@pytest.mark.parametrize("seed", range(18))
+@pytest.mark.parametrize("seed", range(36))
 def test_random_layer_shapes_auto_plan(tm, oracle, seed):
-    """Layer-sized shapes drawn at random (K 1536 ... 14336, N 1024 ... 12288, every row-count regime): whatever plan the
+    """Layer-sized shapes drawn at random (K 1536 ... 28672, N 256 ... 12288, every row-count regime): whatever plan the
     dispatcher's cost models pick - strip width and K split of the decode kernels, tile shape and wave sets above 64
     rows - must launch and meet the oracle.  Codes, zero-points and scales are drawn directly (no quantiser run)."""
     rng = np.random.default_rng(4000 + seed)
-    K = 128 * int(rng.integers(12, 113))
-    N = 16 * int(rng.integers(64, 769))
+    if seed < 18:
+        K = 128 * int(rng.integers(12, 113))
+        N = 16 * int(rng.integers(64, 769))
+    else:                                        # deep and narrow: K up to 28672, the K-split plans
+        K = 128 * int(rng.integers(64, 225))
+        N = 16 * int(rng.integers(16, 129))
     while K * N > 36_000_000:
         N = (N // 32) * 16
     g = int(rng.choice([32, 64, 128, 128]))
-    M = int([1, 5, 16, 24, 32, 48, 64, 96, 128, 200, 384, 512, 17, 33, 65, 300, 8, 256][seed])
+    M = int([1, 5, 16, 24, 32, 48, 64, 96, 128, 200, 384, 512, 17, 33, 65, 300, 8, 256][seed % 18])
     q = rng.integers(0, 16, (K, N), dtype=np.uint8)
     z = rng.integers(0, 16, (K // g, N)).astype(np.float16)
     s = (rng.random((K // g, N)) * 0.02 + 0.001).astype(np.float16)
