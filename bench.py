@@ -149,6 +149,11 @@ def per_shape_table(tm, torch, wl, layers, iters=100, warmup=10, use_graph=True)
         for M in L.Ms:
             ev_ms, _ = time_steps(torch, lambda: L.launch(tm, M), iters, warmup,
                                   graph_steps=iters if use_graph else 0)
+            if ev_ms / iters < 0.05:
+                # launches of a few microseconds come out 20-25 % slower now and then for a whole timed region (the
+                # device's clocks after the idle stretch before a row): such rows are timed twice, the better one counts
+                ev2, _ = time_steps(torch, lambda: L.launch(tm, M), iters, warmup, graph_steps=iters if use_graph else 0)
+                ev_ms = min(ev_ms, ev2)
             t = ev_ms / iters * 1e-3
             B = wl.algorithmic_bytes(M, c.K, c.N, c.group)
             F = wl.flops(M, c.K, c.N)
