@@ -212,7 +212,7 @@ MOE_LAYERS = {
 }
 
 
-def moe_table(tm, torch, names, tokens=(1, 4, 16, 64), iters=40, group=128, only=None, use_graph=True):
+def moe_table(tm, torch, names, tokens=(1, 4, 16, 64), iters=40, group=128, only=None, use_graph=True, fmt="int4"):
     import numpy as np
     rows = []
     for name in names:
@@ -220,13 +220,23 @@ def moe_table(tm, torch, names, tokens=(1, 4, 16, 64), iters=40, group=128, only
         G = K // group
         experts = []
         for e in range(E):
-            qw = torch.randint(-2 ** 31, 2 ** 31 - 1, (K, N // 8), dtype=torch.int32, device="cuda")
-            s = (torch.rand((G, N), device="cuda") * 0.02 + 0.001).to(torch.float16)
-            z = torch.randint(0, 16, (G, N), device="cuda").to(torch.float16)
-            experts.append(tm.tm_pack_w4(qw, s, z, K, N, group))
+            if fmt == "int4":
+                qw = torch.randint(-2 ** 31, 2 ** 31 - 1, (K, N // 8), dtype=torch.int32, device="cuda")
+                s = (torch.rand((G, N), device="cuda") * 0.02 + 0.001).to(torch.float16)
+                z = torch.randint(0, 16, (G, N), device="cuda").to(torch.float16)
+                experts.append(tm.tm_pack_w4(qw, s, z, K, N, group))
+            else:                                        # 8-bit integer or FP8 E4M3 experts (random codes)
+                qw = torch.randint(-2 ** 31, 2 ** 31 - 1, (K, N // 4), dtype=torch.int32, device="cuda")
+                s = (torch.rand((G, N), device="cuda") * 0.002 + 0.0001).to(torch.float16)
+                z = torch.randint(0, 256, (G, N), device="cuda").to(torch.float16)
+                if fmt == "fp8":
+                    qw = qw & 0x77777777                 # keeps every code finite (no E4M3 NaN pattern)
+                    experts.append(tm.tm_pack_w8_fp8(qw, s, K, N, group))
+                else:
+                    experts.append(tm.tm_pack_w8(qw, s, z, K, N, group))
         del qw, s, z
         grp = tm.tm_group_experts(experts)
-        ebytes = K * N // 2 + 4 * G * N
+        ebytes = (K * N // 2 if fmt == "int4" else K * N) + 4 * G * N
         rng = np.random.default_rng(E * 7 + K)
         for T in tokens:
             if only is not None and (name, T) != only:
@@ -264,7 +274,7 @@ def moe_table(tm, torch, names, tokens=(1, 4, 16, 64), iters=40, group=128, only
             B = active / iters * ebytes + R * K * 2 + R * N * 2
             v, st = tm.tm_get_grouped_plan(grp, R)
             F = 2.0 * R * K * N
-            rows.append({"layer": name, "experts": E, "top_k": topk, "K": K, "N": N, "tokens": T, "rows": R,
+            rows.append({"layer": name, "format": fmt, "experts": E, "top_k": topk, "K": K, "N": N, "tokens": T, "rows": R,
                          "active_experts_avg": active / iters, "us": t * 1e6, "GBps": B / t / 1e9,
                          "TFLOPs": F / t / 1e12, "mfma_frac": F / t / 1e12 / MFMA_F16_PEAK_TFLOPS,
                          "hbm_frac": B / t / 1e9 / HBM_PEAK_GBPS, "looped_us": l_ms / iters * 1e3,
@@ -849,6 +859,7 @@ def main():
                     help="workloads the fp16 x fp16 companion covers (comma-separated; one of them makes a short profiler run)")
     ap.add_argument("--eager", action="store_true", help="launch every kernel from the host instead of replaying HIP graphs")
     ap.add_argument("--moe-tokens", default="1,4,16,64", help="with --workload moe: tokens per step (comma-separated)")
+    ap.add_argument("--moe-format", default="int4", choices=["int4", "int8", "fp8"], help="with --workload moe: weight format of the experts")
     ap.add_argument("--only", default=None, help="restrict the workload to one 'layer:M' pair, e.g. cfg3_gate_up:1 (profiling)")
     ap.add_argument("--waves", type=int, default=0)
     ap.add_argument("--stage-steps", type=int, default=0)
@@ -993,7 +1004,7 @@ def main():
             nm, T = args.only.split(":")
             only = (nm, int(T))
         names = [n for n in MOE_LAYERS if only is None or n == only[0]]
-        table = moe_table(tm, torch, names, tokens=tuple(int(t) for t in args.moe_tokens.split(",")), iters=args.steps if args.steps <= 40 else 40, only=only, use_graph=not args.eager)
+        table = moe_table(tm, torch, names, tokens=tuple(int(t) for t in args.moe_tokens.split(",")), iters=args.steps if args.steps <= 40 else 40, only=only, use_graph=not args.eager, fmt=args.moe_format)
         if args.sweep_out:
             os.makedirs(os.path.dirname(os.path.abspath(args.sweep_out)), exist_ok=True)
             json.dump(table, open(args.sweep_out, "w"), indent=1)
