@@ -201,14 +201,13 @@ int decode_slot_floats(int variant, int NT, int strips)
     return ntw * 256 * (skinny_rows(variant) / 16);
 }
 
-Plan make_plan(const tm_packed_w4* h, int M, int num_cu)
+// Which kernel family and shape a launch takes when nothing is forced (a forced variant is checked against the weight
+// format and passed through).
+static int choose_variant(const tm_packed_w4* h, int M, int num_cu, int NT)
 {
-    // packed units along K: 128 rows of 4-bit codes or 64 rows of 8-bit codes (1 KiB per 16 columns either way)
-    const int KU = h->bits == 8 ? h->K / 64 : h->K / kUnitK, NT = h->N / kUnitN;
-    Plan pl{};
+    const bool w8 = h->bits == 8;
     int variant = g_force_variant;
     // 8-bit formats: the decode kernels up to 64 rows, three CTA-tile shapes above
-    const bool w8 = h->bits == 8;
     if (w8 && variant >= 0 && !(variant == kSkinny16x16 || variant == kSkinny16x32 || variant == kSkinny16x48 ||
                                 variant == kSkinny16x64 || variant == kSkinny16x96 || variant == kSkinny16x128 ||
                                 variant == kSkinny32x64 || variant == kSkinny64x64 || variant == kTile32x128 ||
@@ -278,14 +277,17 @@ Plan make_plan(const tm_packed_w4* h, int M, int num_cu)
             }
         }
     }
-    const size_t out_bytes = (size_t)M * h->N * sizeof(float);
-    int max_split_ws = (int)(kPartialBudget / (out_bytes ? out_bytes : 1));
-    if (max_split_ws < 1) max_split_ws = 1;
-    // 16 < M <= 64, 4-bit codes: the one-shot decode kernels with a ring of X pieces per wave, about one CTA per CU.  Every
-    // CTA streams the X rows of its K slice through its CU's load path, so wider strips with K split across CTAs (each
-    // CTA then reads a part of X only) are weighed against narrow strips that need no merge.
-    // A forced 16-row decode variant fixes the strip width (and the forced split the split) instead; the forced 32- and
-    // 64-row variants keep meaning the ring-buffered kernels.
+    return variant;
+}
+
+// The plan of the one-shot decode kernels with an X ring, if they take the launch (true, `pl` complete).
+// 16 < M <= 64, 4-bit codes: the one-shot decode kernels with a ring of X pieces per wave, about one CTA per CU.  Every
+// CTA streams the X rows of its K slice through its CU's load path, so wider strips with K split across CTAs (each
+// CTA then reads a part of X only) are weighed against narrow strips that need no merge.
+// A forced 16-row decode variant fixes the strip width (and the forced split the split) instead; the forced 32- and
+// 64-row variants keep meaning the ring-buffered kernels.
+static bool plan_x_ring(const tm_packed_w4* h, int M, int num_cu, int KU, int NT, int max_split_ws, Plan& pl)
+{
     if (h->bits == 4 && M > 16 && M <= 64 && g_force_stage != 1 && (uint64_t)M * h->K * 2u < (1ull << 31) &&
         (g_force_variant < 0 || (is_skinny(g_force_variant) && skinny_rows(g_force_variant) == 16))) {
         auto emit = [&](int strips, int split, int kps, int w, int ni) {
@@ -315,7 +317,7 @@ Plan make_plan(const tm_packed_w4* h, int M, int num_cu)
                 const int ni = strips <= kMaxCounters ? rows_units_per_wave(M, ceil_div(NT, strips), h->group, kps, w) : 0;
                 if (ni > 0) {
                     emit(strips, split, kps, w, ni);
-                    return pl;
+                    return true;
                 }
             }
         } else if (NT <= 4 * num_cu) {
@@ -364,10 +366,91 @@ Plan make_plan(const tm_packed_w4* h, int M, int num_cu)
             }
             if (best >= 0) {
                 emit(b_strips, b_split, b_kps, b_w, b_ni);
-                return pl;
+                return true;
             }
         }
     }
+    return false;
+}
+
+// Above 64 rows, 4-bit codes, nothing forced: tile shape and K split are weighed together.  The shape
+// chosen above (on the unsplit launch) is compared with itself split and with the four shapes up to 128 x 128
+// split two to eight ways into at most one CTA per CU; another shape is taken if the estimate puts it 5 % or
+// more ahead.  The estimate is a least-squares fit to 1041 timed plans (16 layer shapes, K 2048 ... 28672,
+// N 1024 ... 28672, M 96 ... 512, rms error 9 %): a fixed part, the K loop of a CTA (per shape; faster while the
+// chip is not full; per round of CTAs), and for a split the hand-over of the partial tiles.  Its picks average
+// 1 % behind the fastest measured plan of a case (worst 13 %), where shape first and split second averaged
+// 3.6 % (worst 20 %): K = 13824, N = 5120, M = 128 runs 27.6 us on 64 x 128 tiles split in three against
+// 38.9 us on 64 x 64 tiles unsplit; K = 11008, N = 4096, M = 256 31.3 against 38.4 us; K = 28672, N = 8192,
+// M = 256 124 us on 128 x 128 tiles split in four against 139 us.
+static void weigh_tile_shape_and_split(const tm_packed_w4* h, int M, int num_cu, int KU, int& variant, int& split, Plan& pl)
+{
+    const bool w8 = h->bits == 8;
+    const int tiles = pl.tiles_m * pl.tiles_n;
+    if (!w8 && M > 64 && g_force_variant < 0 && g_force_split == 0) {
+        auto joint = [&](int v, int sp) -> double {
+            const double ck = v == kTile32x128 ? 371 : v == kTile64x64 ? 337 : v == kTile64x128 ? 532 : v == kTile128x128 ? 397 : 848;
+            const long t = (long)ceil_div(M, tile_bm(v)) * ceil_div(h->N, tile_bn(v));
+            const long ctas = t * sp;
+            const int rounds = (int)((ctas + num_cu - 1) / num_cu);
+            const double occ = ctas < num_cu ? (double)ctas / num_cu : 1.0;
+            double r = rounds;
+            if (tile_bm(v) >= 128) r = rounds == 1 ? (v == kTile128x128 ? 2.498 : 2.239) : 1.0 + 3.005 * (rounds - 1);
+            double est = 5576.0 + ck * ceil_div(KU, sp) * (0.763 + 0.237 * occ) * r;
+            if (sp > 1) est += -215.0 + 714.0 * sp + 0.000462 * sp * t * tile_bm(v) * tile_bn(v) * 4;
+            return est;
+        };
+        auto whole = [&](int sp) { const int kps = ceil_div(KU, sp); return sp == 1 || (kps >= 4 && ceil_div(KU, kps) == sp); };
+        const bool modelled = variant == kTile32x128 || variant == kTile64x64 || variant == kTile64x128 ||
+                              variant == kTile128x128 || variant == kTile128x256;
+        if (modelled) {
+            const int splits[6] = {1, 2, 3, 4, 6, 8};
+            double base = -1;
+            int base_split = 1;
+            for (int sp : splits) {
+                if (!whole(sp) || (sp > 1 && (long)tiles * sp > num_cu)) continue;
+                const double e = joint(variant, sp);
+                if (base < 0 || e < base) {
+                    base = e;
+                    base_split = sp;
+                }
+            }
+            int best_v = variant, best_s = base_split;
+            double best = base;
+            const int others[4] = {kTile64x128, kTile128x128, kTile64x64, kTile32x128};
+            for (int v : others) {
+                if (v == variant) continue;
+                const long t = (long)ceil_div(M, tile_bm(v)) * ceil_div(h->N, tile_bn(v));
+                for (int sp : splits) {
+                    if (sp == 1 || !whole(sp) || t * sp > num_cu) continue;
+                    const double e = joint(v, sp);
+                    if (e < 0.95 * base && e < best) {
+                        best = e;
+                        best_v = v;
+                        best_s = sp;
+                    }
+                }
+            }
+            variant = pl.variant = best_v;
+            split = best_s;
+            pl.tiles_m = ceil_div(M, tile_bm(variant));
+            pl.tiles_n = ceil_div(h->N, tile_bn(variant));
+            pl.block = (unsigned)tile_threads(variant);
+        }
+    }
+}
+
+Plan make_plan(const tm_packed_w4* h, int M, int num_cu)
+{
+    // packed units along K: 128 rows of 4-bit codes or 64 rows of 8-bit codes (1 KiB per 16 columns either way)
+    const int KU = h->bits == 8 ? h->K / 64 : h->K / kUnitK, NT = h->N / kUnitN;
+    Plan pl{};
+    const bool w8 = h->bits == 8;
+    int variant = choose_variant(h, M, num_cu, NT);
+    const size_t out_bytes = (size_t)M * h->N * sizeof(float);
+    int max_split_ws = (int)(kPartialBudget / (out_bytes ? out_bytes : 1));
+    if (max_split_ws < 1) max_split_ws = 1;
+    if (plan_x_ring(h, M, num_cu, KU, NT, max_split_ws, pl)) return pl;
     if (is_skinny(variant) && M > skinny_rows(variant))        // a forced skinny variant must still cover M
         variant = M <= 32 ? kSkinny32x64 : (M <= 64 ? kSkinny64x64 : (w8 ? kTile64x128 : kTile64x256));
     pl.variant = variant;
@@ -450,67 +533,7 @@ Plan make_plan(const tm_packed_w4* h, int M, int num_cu)
                 }
             }
         }
-        // Above 64 rows, 4-bit codes, nothing forced: tile shape and K split are then weighed together.  The shape
-        // chosen above (on the unsplit launch) is compared with itself split and with the four shapes up to 128 x 128
-        // split two to eight ways into at most one CTA per CU; another shape is taken if the estimate puts it 5 % or
-        // more ahead.  The estimate is a least-squares fit to 1041 timed plans (16 layer shapes, K 2048 ... 28672,
-        // N 1024 ... 28672, M 96 ... 512, rms error 9 %): a fixed part, the K loop of a CTA (per shape; faster while the
-        // chip is not full; per round of CTAs), and for a split the hand-over of the partial tiles.  Its picks average
-        // 1 % behind the fastest measured plan of a case (worst 13 %), where shape first and split second averaged
-        // 3.6 % (worst 20 %): K = 13824, N = 5120, M = 128 runs 27.6 us on 64 x 128 tiles split in three against
-        // 38.9 us on 64 x 64 tiles unsplit; K = 11008, N = 4096, M = 256 31.3 against 38.4 us; K = 28672, N = 8192,
-        // M = 256 124 us on 128 x 128 tiles split in four against 139 us.
-        if (!w8 && M > 64 && g_force_variant < 0 && g_force_split == 0) {
-            auto joint = [&](int v, int sp) -> double {
-                const double ck = v == kTile32x128 ? 371 : v == kTile64x64 ? 337 : v == kTile64x128 ? 532 : v == kTile128x128 ? 397 : 848;
-                const long t = (long)ceil_div(M, tile_bm(v)) * ceil_div(h->N, tile_bn(v));
-                const long ctas = t * sp;
-                const int rounds = (int)((ctas + num_cu - 1) / num_cu);
-                const double occ = ctas < num_cu ? (double)ctas / num_cu : 1.0;
-                double r = rounds;
-                if (tile_bm(v) >= 128) r = rounds == 1 ? (v == kTile128x128 ? 2.498 : 2.239) : 1.0 + 3.005 * (rounds - 1);
-                double est = 5576.0 + ck * ceil_div(KU, sp) * (0.763 + 0.237 * occ) * r;
-                if (sp > 1) est += -215.0 + 714.0 * sp + 0.000462 * sp * t * tile_bm(v) * tile_bn(v) * 4;
-                return est;
-            };
-            auto whole = [&](int sp) { const int kps = ceil_div(KU, sp); return sp == 1 || (kps >= 4 && ceil_div(KU, kps) == sp); };
-            const bool modelled = variant == kTile32x128 || variant == kTile64x64 || variant == kTile64x128 ||
-                                  variant == kTile128x128 || variant == kTile128x256;
-            if (modelled) {
-                const int splits[6] = {1, 2, 3, 4, 6, 8};
-                double base = -1;
-                int base_split = 1;
-                for (int sp : splits) {
-                    if (!whole(sp) || (sp > 1 && (long)tiles * sp > num_cu)) continue;
-                    const double e = joint(variant, sp);
-                    if (base < 0 || e < base) {
-                        base = e;
-                        base_split = sp;
-                    }
-                }
-                int best_v = variant, best_s = base_split;
-                double best = base;
-                const int others[4] = {kTile64x128, kTile128x128, kTile64x64, kTile32x128};
-                for (int v : others) {
-                    if (v == variant) continue;
-                    const long t = (long)ceil_div(M, tile_bm(v)) * ceil_div(h->N, tile_bn(v));
-                    for (int sp : splits) {
-                        if (sp == 1 || !whole(sp) || t * sp > num_cu) continue;
-                        const double e = joint(v, sp);
-                        if (e < 0.95 * base && e < best) {
-                            best = e;
-                            best_v = v;
-                            best_s = sp;
-                        }
-                    }
-                }
-                variant = pl.variant = best_v;
-                split = best_s;
-                pl.tiles_m = ceil_div(M, tile_bm(variant));
-                pl.tiles_n = ceil_div(h->N, tile_bn(variant));
-                pl.block = (unsigned)tile_threads(variant);
-            }
-        }
+        weigh_tile_shape_and_split(h, M, num_cu, KU, variant, split, pl);
     }
     if (g_force_split > 0) split = g_force_split;
     if (pl.tiles_m * pl.tiles_n > kMaxCounters) split = 1;     // one arrival counter per output tile
