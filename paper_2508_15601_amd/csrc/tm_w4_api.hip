@@ -227,7 +227,9 @@ static int choose_variant(const tm_packed_w4* h, int M, int num_cu, int NT)
         if (M <= 16) {
             // One CTA per CU: the column tiles are dealt evenly over min(NT, #CU) strips (widths differ by at most
             // one tile), because a CU sustains only ~25 GB/s of weight traffic and the slowest CU sets the time.
-            const int per_cu = ceil_div(NT, num_cu);
+            // Outputs wider than eight column tiles per CU (the widest strip) go in two or more whole rounds of CTAs.
+            const int rounds = ceil_div(ceil_div(NT, 8), num_cu);
+            const int per_cu = ceil_div(NT, rounds * num_cu);
             variant = per_cu <= 1 ? kSkinny16x16 : per_cu <= 2 ? kSkinny16x32 : per_cu <= 3 ? kSkinny16x48
                     : per_cu <= 4 ? kSkinny16x64 : per_cu <= 6 ? kSkinny16x96 : kSkinny16x128;
             // Deep-and-narrow layers with many rows: every strip re-reads all M*K activations, which then outweighs
@@ -461,6 +463,9 @@ Plan make_plan(const tm_packed_w4* h, int M, int num_cu)
         int strips = ceil_div(NT, ntw);
         if (g_force_variant < 0 && M <= 16 && NT >= num_cu && strips < num_cu && !(variant == kSkinny16x64 && NT / num_cu <= 1))
             strips = num_cu;
+        // wider than one round of the widest strips: whole rounds of evenly dealt strips, not one round and a remainder
+        // (K = 3584, N = 37888, 2368 column tiles: 512 strips of 4-5 tiles instead of 296 of 8)
+        if (g_force_variant < 0 && M <= 16 && NT > 8 * num_cu) strips = num_cu * ceil_div(ceil_div(NT, 8), num_cu);
         int waves = (strips <= num_cu && KU >= 32) ? 16 : 8;
         // many rows on wide strips: 8 waves with a deeper register ring measured 2-3 % faster than 16 waves
         if (M > 8 && ntw >= 3 && skinny_rows(variant) == 16) waves = 8;

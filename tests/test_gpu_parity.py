@@ -226,6 +226,8 @@ SMALL = [
     # M, K, N, group           several tiles in every dimension plus ragged tails
     (1, 128, 16, 128), (3, 384, 80, 64), (16, 1152, 272, 128), (17, 384, 528, 32), (33, 1152, 80, 128),
     (64, 640, 272, 64), (65, 384, 272, 128), (130, 1152, 528, 64), (300, 640, 400, 128), (257, 384, 272, 32),
+    # more than eight column tiles per compute unit: decode strips in two whole rounds
+    (5, 512, 33040, 128), (16, 384, 41008, 64),
 ]
 
 
@@ -412,7 +414,9 @@ def test_decode_configs_take_the_one_shot_form(tm):
     for K, N, g, Ms in ((4096, 4096, 128, (1, 16)), (4096, 12288, 128, (1, 16)), (4096, 22016, 128, (1, 16)),
                         (11008, 4096, 128, (1, 8, 16)), (8192, 8192, 64, (1, 8, 16)),
                         # layers of other models: deep K, or fewer column tiles than compute units (K split across CTAs)
-                        (13824, 5120, 128, (1, 16)), (18944, 3584, 128, (1, 16))):
+                        (13824, 5120, 128, (1, 16)), (18944, 3584, 128, (1, 16)),
+                        # more column tiles than eight per compute unit: two whole rounds of strips
+                        (3584, 37888, 128, (1, 16))):
         qw = torch.zeros((K, N // 8), dtype=torch.int32, device="cuda")
         s = torch.ones((K // g, N), dtype=torch.float16, device="cuda")
         packed = tm.tm_pack_w4(qw, s, None, K, N, g)
