@@ -742,6 +742,73 @@ def l2_feed_table(tm, torch, iters=20):
     return rows
 
 
+def clock_under_load(tm, torch, step_fn, graph_steps, micros=3000):
+    """Shader clock the chip holds while step_fn's launches run: a one-wave kernel, launched on a second stream ahead of
+    the work so that it has its wave slot, sleeps through the untimed replays that precede every timed region and
+    then reads the shader clock counter and the constant-rate counter around `micros` microseconds of further replays.
+    Two streams may share a hardware queue, in which case the probe and the work run one after the other: events on both
+    streams tell, and the measurement is repeated on another stream then.  None if no attempt overlapped."""
+    out = torch.zeros(16, dtype=torch.int32, device="cuda")
+    main = torch.cuda.Stream()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.stream(main):
+        with torch.cuda.graph(graph, stream=main):
+            for _ in range(graph_steps):
+                step_fn()
+        w0, w1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        w0.record()
+        graph.replay()
+        w1.record()
+        torch.cuda.synchronize()
+        one_ms = max(w0.elapsed_time(w1), 0.02)
+    probe_ms = WARM_MS + micros * 1e-3
+    for _ in range(6):
+        side = torch.cuda.Stream()
+        m0, m1, s1 = (torch.cuda.Event(enable_timing=True) for _ in range(3))
+        khz = tm.tm_bench_clock(out, micros, delay_micros=int(WARM_MS * 1000), stream=side)
+        s1.record(side)
+        with torch.cuda.stream(main):
+            m0.record()
+            for _ in range(int((probe_ms + 4.0) / one_ms) + 1):     # replays to outlast the probe by a few milliseconds
+                graph.replay()
+            m1.record()
+        torch.cuda.synchronize()
+        # the probe ran beside the work if it ended its own length after the work began, and before the work ended
+        if m0.elapsed_time(s1) > 0.9 * probe_ms and s1.elapsed_time(m1) > 0.0:
+            ticks = out.cpu().numpy().astype("uint32")
+            return float(ticks[0]) / (float(ticks[1]) / (khz * 1e3)) / 1e9 if ticks[1] else None
+    return None
+
+
+def mfma_ceiling_table(tm, torch, target_ms=1.0, num_cu=256):
+    """What the matrix pipes sustain on this chip in a kernel of fp16 16x16x32 MFMAs only (eight independent accumulators
+    per wave, operands in registers): one CTA per CU with one, two and four waves per SIMD; zero operands, one operand
+    pair for all instructions, and a different pair per instruction (the case a GEMM is held against).
+    Every launch is sized to about `target_ms` (a prefill launch takes 1.5 ms) and timed like the GEMM rows; the shader
+    clock held under the load follows from the two device counters the first wave reads around its loop."""
+    out = torch.zeros(16, dtype=torch.int32, device="cuda")
+    wall_khz = tm.tm_bench_clock(out, 1)                     # frequency of the constant-rate counter
+    torch.cuda.synchronize()
+    rows = []
+    for waves_per_simd, pattern in ((1, 0), (1, 1), (1, 2), (2, 2), (4, 2)):
+        block = 256 * waves_per_simd
+        iters = int(target_ms * 1e-3 * 2.4e9 / (128 * waves_per_simd))
+        def step():
+            tm.tm_bench_mfma(out, num_cu, block, iters, pattern)
+        ev_ms, _ = time_steps(torch, step, 10, 3, graph_steps=10)
+        us = ev_ms / 10 * 1e3
+        ticks = out.cpu().numpy().astype("uint32")
+        flops = num_cu * (block // 64) * iters * 8 * 16384.0
+        ghz = float(ticks[0]) / (float(ticks[1]) / (wall_khz * 1e3)) / 1e9 if ticks[1] else None
+        rows.append({"waves_per_simd": waves_per_simd, "operands": ("zeros", "one pair of values", "eight pairs of values")[pattern],
+                     "iters": iters, "us": us, "TFLOPs": flops / us / 1e6, "frac_of_peak": flops / us / 1e6 / MFMA_F16_PEAK_TFLOPS,
+                     "shader_clock_GHz": ghz, "shader_clocks_per_us_of_launch": float(ticks[0]) / us, "first_wave_clocks_per_mfma": float(ticks[0]) / (iters * 8)})
+        log(f"MFMA only, {waves_per_simd} wave(s) per SIMD, {rows[-1]['operands']:21s}: {us:8.1f} us, {rows[-1]['TFLOPs']:7.1f} TFLOP/s "
+            f"({100 * rows[-1]['frac_of_peak']:4.1f} % of {MFMA_F16_PEAK_TFLOPS:.0f}), shader clock {ghz:.2f} GHz, "
+            f"{rows[-1]['first_wave_clocks_per_mfma']:.1f} clocks per MFMA in the first wave")
+    return rows
+
+
 def ceiling_sizes(wl):
     """(label, packed weight + scale/zero bytes) of every distinct weight matrix of the benchmark configurations."""
     out, seen = [], set()
@@ -909,11 +976,12 @@ def main():
         empty = empty_launch_us(tm, torch)
         log(f"empty kernel node: {empty:.2f} us")
         l2 = None if args.only else l2_feed_table(tm, torch)
+        mfma = None if args.only else mfma_ceiling_table(tm, torch)
         if args.sweep_out:
             os.makedirs(os.path.dirname(os.path.abspath(args.sweep_out)), exist_ok=True)
             json.dump(rows, open(args.sweep_out, "w"), indent=1)
         print(json.dumps({"metric": "read-only streaming ceiling at the byte counts of the benchmark's weight matrices", "workload": "ceiling",
-                          "n_gpus": 1, "empty_launch_us": empty, "l2_feed": l2, "rows": [r for r in rows if r.get("best")]}))
+                          "n_gpus": 1, "empty_launch_us": empty, "l2_feed": l2, "mfma_only": mfma, "rows": [r for r in rows if r.get("best")]}))
         return
 
     if args.workload == "pack":
@@ -1121,6 +1189,19 @@ def main():
         roofline["read_ceiling_shape"] = {k: ceil[k] for k in ("grid", "block", "unroll", "nontemporal", "chunked")}
         roofline["frac_of_read_ceiling"] = ach / ceil["GBps"]
         roofline["empty_launch_us"] = empty_launch_us(tm, torch)
+    if not args.no_ceiling and dom_graph > 0:
+        # the shader clock held while the dominant kernel runs (the data-sheet peaks are quoted at 2.4 GHz)
+        roofline["shader_clock_GHz_under_load"] = clock_under_load(tm, torch, dom_step, dom_graph)
+    if not hbm_bound and not args.no_ceiling:
+        # a kernel of MFMAs only, timed the same way: what the matrix pipes deliver at the clock this chip holds under
+        # that load, beside the data-sheet peak at 2.4 GHz
+        best = max(mfma_ceiling_table(tm, torch), key=lambda r: r["TFLOPs"] if r["operands"] == "eight pairs of values" else 0.0)
+        roofline["mfma_ceiling_TFLOPs"] = best["TFLOPs"]
+        roofline["mfma_ceiling_shader_clock_GHz"] = best["shader_clock_GHz"]
+        roofline["mfma_ceiling_shape"] = {"waves_per_simd": best["waves_per_simd"], "operands": best["operands"]}
+        roofline["frac_of_mfma_ceiling"] = ach / best["TFLOPs"]
+        if roofline.get("shader_clock_GHz_under_load"):
+            roofline["frac_of_peak_at_held_clock"] = ach / (MFMA_F16_PEAK_TFLOPS * roofline["shader_clock_GHz_under_load"] / 2.4)
 
     out = {
         "metric": METRIC, "value": gbps if hbm_bound else tflops, "unit": "GB/s" if hbm_bound else "TFLOP/s",

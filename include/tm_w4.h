@@ -319,6 +319,27 @@ TM_API int tm_bench_read(const void* src, size_t bytes, void* sink, tm_stream st
 TM_API int tm_bench_read_shape(const void* src, size_t bytes, void* sink, int grid, int block, int unroll, int flags,
                                tm_stream stream);
 
+/*
+ * A kernel of matrix instructions only, to find what the matrix pipes sustain at the clock the chip holds under that load
+ * (the ceiling an MFMA-bound kernel can be held against, beside the data-sheet peak): `grid` CTAs of `block` threads
+ * (a multiple of 64, at most 1024), every wave issuing `iters` x 8 independent 16x16x32 fp16 MFMAs (16 384 flop each) on
+ * register operands; pattern 0 = zero operands, 1 = operands that differ per lane, the same for every instruction,
+ * 2 = a different operand pair for each of the eight instructions (the operand latches switch as they do in a GEMM).  `out` is a 16-byte aligned device
+ * location of four 32-bit words: word 0 receives the shader clock counter's advance over the first wave's loop, word 1
+ * the advance of the constant-rate counter (`hipDeviceAttributeWallClockRate`) over the same loop.
+ */
+TM_API int tm_bench_mfma(void* out, int grid, int block, int iters, int pattern, tm_stream stream);
+
+/*
+ * One wave that sleeps through `delay_micros` (0 ... 100000) microseconds of the constant-rate counter, then watches the
+ * shader clock counter for `micros` (1 ... 20000) microseconds and writes both counters' advance over that stretch to
+ * `out` (16-byte aligned device location: word 0 shader clocks, word 1 constant-rate ticks).  Launched on a second stream
+ * *before* other work is queued it gives the clock the chip holds under that work (a launch that fills the register
+ * file would keep a later probe waiting until it has drained); it takes no LDS, one wave slot and a few registers, and
+ * ends by itself.  Returns the constant-rate counter's frequency in kHz (positive) or a negative error code.
+ */
+TM_API int tm_bench_clock(void* out, int delay_micros, int micros, tm_stream stream);
+
 TM_API const char* tm_last_error(void);
 TM_API const char* tm_version(void);
 

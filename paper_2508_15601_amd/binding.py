@@ -113,6 +113,10 @@ def load_library():
     lib.tm_bench_copy.argtypes = [vp, vp, sz, vp]
     lib.tm_bench_read.restype = i
     lib.tm_bench_read.argtypes = [vp, sz, vp, vp]
+    lib.tm_bench_clock.restype = i
+    lib.tm_bench_clock.argtypes = [vp, i, i, vp]
+    lib.tm_bench_mfma.restype = i
+    lib.tm_bench_mfma.argtypes = [vp, i, i, i, i, vp]
     lib.tm_bench_read_shape.restype = i
     lib.tm_bench_read_shape.argtypes = [vp, sz, vp, i, i, i, i, vp]
     lib.tm_last_error.restype = c.c_char_p
@@ -480,6 +484,20 @@ def tm_bench_read(src, sink, stream=None):
     nbytes = src.numel() * src.element_size()
     _check(load_library().tm_bench_read(ctypes.c_void_p(src.data_ptr()), nbytes, ctypes.c_void_p(sink.data_ptr()),
                                         _stream_ptr(stream)))
+
+
+def tm_bench_clock(out, micros: int, delay_micros: int = 0, stream=None) -> int:
+    """A one-wave launch that waits `delay_micros`, then watches the shader clock for `micros` microseconds
+    (include/tm_w4.h); `out` is an int32 device tensor of at least 4 elements.  Returns the constant-rate counter's
+    frequency in kHz."""
+    khz = load_library().tm_bench_clock(ctypes.c_void_p(out.data_ptr()), delay_micros, micros, _stream_ptr(stream))
+    _check(min(khz, 0))
+    return khz
+
+
+def tm_bench_mfma(out, grid: int, block: int, iters: int, pattern: int = 1, stream=None):
+    """A launch of matrix instructions only (include/tm_w4.h); `out` is an int32 device tensor of at least 4 elements."""
+    _check(load_library().tm_bench_mfma(ctypes.c_void_p(out.data_ptr()), grid, block, iters, pattern, _stream_ptr(stream)))
 
 
 def tm_bench_read_shape(src_ptr: int, nbytes: int, sink, grid: int, block: int, unroll: int, flags: int = 0, stream=None):

@@ -1471,6 +1471,39 @@ int tm_bench_read_shape(const void* src, size_t bytes, void* sink, int grid, int
     return TM_OK;
 }
 
+int tm_bench_mfma(void* out, int grid, int block, int iters, int pattern, tm_stream stream)
+{
+    if (!out || ((uintptr_t)out & 15)) return fail(TM_EINVAL, "out must be a 16-byte aligned device location");
+    if (grid < 1 || grid > (1 << 16) || block < 64 || block > 1024 || block % 64) return fail(TM_EINVAL, "grid or block out of range");
+    if (iters < 1 || iters > (1 << 22)) return fail(TM_EINVAL, "iters = %d out of range", iters);
+    if (pattern < 0 || pattern > 2) return fail(TM_EINVAL, "pattern must be 0, 1 or 2");
+    int dev;
+    int rc = check_device(&dev);
+    if (rc != TM_OK) return rc;
+    hipError_t e = launch_mfma_loop(out, (unsigned)grid, (unsigned)block, iters, pattern, (hipStream_t)stream);
+    if (e != hipSuccess) return fail_hip(e, "mfma loop launch");
+    return TM_OK;
+}
+
+int tm_bench_clock(void* out, int delay_micros, int micros, tm_stream stream)
+{
+    if (!out || ((uintptr_t)out & 15)) return fail(TM_EINVAL, "out must be a 16-byte aligned device location");
+    if (micros < 1 || micros > 20000) return fail(TM_EINVAL, "micros = %d out of range (1 ... 20000)", micros);
+    if (delay_micros < 0 || delay_micros > 100000) return fail(TM_EINVAL, "delay_micros = %d out of range (0 ... 100000)", delay_micros);
+    int dev;
+    int rc = check_device(&dev);
+    if (rc != TM_OK) return rc;
+    int khz = 0;
+    hipError_t e = hipDeviceGetAttribute(&khz, hipDeviceAttributeWallClockRate, dev);
+    if (e != hipSuccess || khz <= 0) return fail(TM_EHIP, "no constant-rate counter frequency for device %d", dev);
+    const uint32_t delay = (uint32_t)((double)delay_micros * khz / 1000.0);
+    const uint32_t ticks = (uint32_t)((double)micros * khz / 1000.0);
+    // a round sleeps about a thousand shader clocks (0.3 ... 1 us): eight rounds per microsecond bound the kernel's life
+    e = launch_clock_probe(out, delay, ticks, (delay_micros + micros) * 8 + 64, (hipStream_t)stream);
+    if (e != hipSuccess) return fail_hip(e, "clock probe launch");
+    return khz;
+}
+
 const char* tm_last_error(void) { return g_error; }
 
 const char* tm_version(void) { return "tm_w4 0.1 (gfx950)"; }

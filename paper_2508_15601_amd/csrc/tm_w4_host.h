@@ -89,6 +89,8 @@ hipError_t launch_unpack(const uint32_t* w, const uint32_t* sz, uint32_t* qweigh
                          uint16_t* zeros_out, int K, int N, int group, hipStream_t stream);
 hipError_t launch_copy(void* dst, const void* src, size_t bytes, hipStream_t stream);
 hipError_t launch_read(const void* src, size_t bytes, void* sink, hipStream_t stream);
+hipError_t launch_clock_probe(void* out, uint32_t delay, uint32_t ticks, int max_rounds, hipStream_t stream);
+hipError_t launch_mfma_loop(void* out, unsigned grid, unsigned block, int iters, int pattern, hipStream_t stream);
 hipError_t launch_read_shape(const void* src, size_t bytes, void* sink, unsigned grid, unsigned block, int unroll, int flags,
                              hipStream_t stream);
 

@@ -188,6 +188,76 @@ __global__ __launch_bounds__(256) void read16_kernel(const u32x4* __restrict__ s
     if (v == 0x9E3779B9u) *sink = v;               // practically never taken; keeps the loads alive
 }
 
+// A loop of nothing but matrix instructions: eight independent 16x16x32 fp16 MFMAs per iteration and wave, operands in
+// registers.  What the matrix pipes of this chip sustain at the clock it holds under that load; the first wave also
+// reports how far the shader clock counter and the constant-rate counter advanced over its loop.  pattern 0: zero
+// operands (the pipes switch the least); 1: values in (-1, 1) that differ per lane and element, the same pair of
+// operands for every instruction; 2: a different pair for each of the eight instructions of an iteration, so that the
+// operand latches switch with every instruction, as they do in a GEMM.
+__global__ __launch_bounds__(1024) void mfma_loop_kernel(int iters, int pattern, uint32_t* out)
+{
+    const uint32_t lane = threadIdx.x & 63;
+    f16x8 a[8], b[8];
+#pragma unroll
+    for (int j = 0; j < 8; ++j) {
+#pragma unroll
+        for (int i = 0; i < 8; ++i) {
+            const uint32_t h = ((lane * 8u + (uint32_t)i + 1u) * 2654435761u) ^ (pattern == 2 ? (uint32_t)j * 0x9E3779B9u : 0u);
+            const float va = pattern ? (float)((int)(h >> 20 & 255) - 128) * (1.0f / 128.0f) : 0.0f;
+            const float vb = pattern ? (float)((int)(h >> 8 & 255) - 128) * (1.0f / 128.0f) : 0.0f;
+            a[j][i] = (_Float16)va;
+            b[j][i] = (_Float16)vb;
+        }
+    }
+    f32x4 acc[8];
+#pragma unroll
+    for (int j = 0; j < 8; ++j) acc[j] = f32x4{0.f, 0.f, 0.f, 0.f};
+    const uint64_t c0 = clock64(), r0 = wall_clock64();
+    for (int it = 0; it < iters; ++it) {
+#pragma unroll
+        for (int j = 0; j < 8; ++j) acc[j] = mfma16x16x32(a[j], b[j], acc[j]);
+    }
+    const uint64_t c1 = clock64(), r1 = wall_clock64();
+    float sum = 0.f;
+#pragma unroll
+    for (int j = 0; j < 8; ++j) sum += acc[j][0] + acc[j][1] + acc[j][2] + acc[j][3];
+    if (blockIdx.x == 0 && threadIdx.x == 0) {
+        out[0] = (uint32_t)(c1 - c0);
+        out[1] = (uint32_t)(r1 - r0);
+    }
+    if (sum == 12345.6789f) out[2] = 1;            // practically never taken; keeps the loop alive
+}
+
+// One wave that does nothing but watch two counters: it sleeps through `delay` ticks of the constant-rate counter, then
+// records how far the shader clock counter and the constant-rate counter advance over the next `ticks`.  Launched on a
+// second stream *before* other work (it needs a wave slot and a few registers, which a launch that fills the register
+// file leaves to nobody), it reports the shader clock the chip holds under that work.  Ends by itself: the loop is
+// bounded by its iteration count whatever the counters do.
+__global__ __launch_bounds__(64) void clock_probe_kernel(uint32_t delay, uint32_t ticks, int max_rounds, uint32_t* out)
+{
+    const uint64_t start = wall_clock64();
+    uint64_t c0 = clock64(), r0 = start, c1 = c0, r1 = r0;
+    bool watching = delay == 0;
+    for (int i = 0; i < max_rounds; ++i) {
+        __builtin_amdgcn_s_sleep(16);              // about a thousand clocks asleep per round: no issue slots taken
+        c1 = clock64();
+        r1 = wall_clock64();
+        if (!watching) {
+            if (r1 - start >= delay) {
+                watching = true;
+                c0 = c1;
+                r0 = r1;
+            }
+        } else if (r1 - r0 >= ticks) {
+            break;
+        }
+    }
+    if (threadIdx.x == 0) {
+        out[0] = watching ? (uint32_t)(c1 - c0) : 0u;
+        out[1] = watching ? (uint32_t)(r1 - r0) : 0u;
+    }
+}
+
 // The read-only stream in a chosen launch shape, for finding the best streaming shape of this chip at a given byte
 // count: every thread keeps U 128-bit loads in flight per round; CHUNKED gives each CTA one contiguous slice of the
 // buffer (as a weight-streaming CTA has) instead of interleaving the CTAs; NT uses the non-temporal load policy.
@@ -459,6 +529,18 @@ hipError_t launch_read_shape(const void* src, size_t bytes, void* sink, unsigned
         case 16: launch_read_u<16>(src, n16, sink, grid, block, flags, stream); break;
         default: return hipErrorInvalidValue;
     }
+    return hipGetLastError();
+}
+
+hipError_t launch_mfma_loop(void* out, unsigned grid, unsigned block, int iters, int pattern, hipStream_t stream)
+{
+    hipLaunchKernelGGL(mfma_loop_kernel, dim3(grid), dim3(block), 0, stream, iters, pattern, (uint32_t*)out);
+    return hipGetLastError();
+}
+
+hipError_t launch_clock_probe(void* out, uint32_t delay, uint32_t ticks, int max_rounds, hipStream_t stream)
+{
+    hipLaunchKernelGGL(clock_probe_kernel, dim3(1), dim3(64), 0, stream, delay, ticks, max_rounds, (uint32_t*)out);
     return hipGetLastError();
 }
 

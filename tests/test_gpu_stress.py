@@ -100,3 +100,31 @@ def test_attention_split_merge_repeats_bit_for_bit(env, bits, B, T):
     lens = torch.full((B,), T, dtype=torch.int32, device="cuda")
     _repeat(torch, lambda: tm.tm_attn_decode(Q, cache, lens, O, 128 ** -0.5, max_len=T), O, thrash, f"KV{bits} {B}x{T}")
     cache.close()
+
+
+def test_measurement_helpers_mfma_loop_and_clock_probe(env):
+    """The two measurement kernels end by themselves and report plausible counters: the MFMA-only loop issues 16-clock
+    instructions back to back (16-20 clocks per MFMA and SIMD with one wave per SIMD), and the clock probe sees a shader
+    clock between 0.5 and 3 GHz over the stretch it was asked to watch."""
+    torch, tm, _ = env
+    out = torch.zeros(16, dtype=torch.int32, device="cuda")
+    iters = 2000
+    tm.tm_bench_mfma(out, 256, 256, iters, 2)
+    torch.cuda.synchronize()
+    ticks = out.cpu().numpy().astype("uint32")
+    assert 15.0 <= ticks[0] / (iters * 8) <= 24.0, ticks[:2]
+    assert ticks[1] > 0
+    out.zero_()
+    khz = tm.tm_bench_clock(out, 500, delay_micros=200)
+    torch.cuda.synchronize()
+    ticks = out.cpu().numpy().astype("uint32")
+    assert khz > 0
+    watched_us = ticks[1] / (khz * 1e3) * 1e6
+    assert 500 <= watched_us < 2500, watched_us
+    ghz = ticks[0] / (watched_us * 1e3)
+    assert 0.5 < ghz < 3.0, ghz
+    for bad in (lambda: tm.tm_bench_clock(out, 0), lambda: tm.tm_bench_clock(out, 30000), lambda: tm.tm_bench_clock(out, 100, delay_micros=-1),
+                lambda: tm.tm_bench_mfma(out, 0, 256, 10), lambda: tm.tm_bench_mfma(out, 256, 100, 10),
+                lambda: tm.tm_bench_mfma(out, 256, 256, 0), lambda: tm.tm_bench_mfma(out, 256, 256, 10, 3)):
+        with pytest.raises(tm.TmError):
+            bad()
