@@ -599,8 +599,12 @@ Plan make_plan(const tm_packed_w4* h, int M, int num_cu)
         if (kg == 2 && bm == 64 && steps == 8 && h->group == 32) steps = 4;
         // the kernels assume whole stages: a stage is steps*kg/4 packed units when that is one or more (steps*kg/2 units
         // of the 8-bit formats, whose depth is fixed)
+        // (four two-wave sets with 128-deep stages give up two sets before they give up depth: K = 11008, N = 4096,
+        // M = 256 on 64 x 64 tiles runs 35.0 us with two sets of 128-deep stages against 38.2 us with four of 64-deep ones)
         while (!w8 && steps * kg > 4 && KU % (steps * kg / 4)) {
-            if (steps > 2) steps /= 2; else kg /= 2;
+            if (kg == 4 && steps == 4 && tile_two_waves(variant) && g_force_waves < 4) kg = 2;
+            else if (steps > 2) steps /= 2;
+            else kg /= 2;
         }
         while (w8 && kg > 1 && KU % (steps * kg / 2)) kg /= 2;
         const int ups = steps * kg / (w8 ? 2 : 4);  // packed units per stage

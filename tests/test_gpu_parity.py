@@ -482,6 +482,29 @@ def test_tile_wave_sets(tm, oracle, variant, waves, stage, g, split):
     assert np.array_equal(Y.view(np.uint16), Y2.view(np.uint16))
 
 
+@pytest.mark.parametrize("variant,M", [(22, 100), (22, 250), (23, 130), (13, 40), (9, 120)])
+@pytest.mark.parametrize("split", [1, 2])
+def test_tile_sets_when_k_is_no_multiple_of_the_full_stage(tm, oracle, variant, M, split):
+    """22 packed units along K (a multiple of two, not of four): the tiles that would take four wave sets with 128-deep
+    stages must shrink the stage; the two-wave tiles give up two of their sets and keep the depth."""
+    K, N, g = 22 * 128, 1040, 128
+    d = _random_problem(4100 + variant + M + split, M, K, N, g)
+    packed = gu.pack(d, g)
+    tm.tm_set_variant(variant, split)
+    plan = tm.tm_get_plan(packed, M)
+    _say(f"odd stage count variant={variant} M={M} split={split} plan={plan}")
+    assert plan["variant"] == variant
+    if variant == 22:
+        assert plan["block"] == 256, plan               # two sets of two waves (the 128-row tile's stages are 64 deep anyway)
+    Y = gu.gemm(packed, d["X"])
+    Y2 = gu.gemm(packed, d["X"])
+    tm.tm_set_variant(-1, 0)
+    Yref = oracle.gemm(d["X"], d["q"], d["s"], d["z"], g)
+    ok, worst, fro = acceptance(Y, Yref)
+    assert ok, (worst, fro)
+    assert np.array_equal(Y.view(np.uint16), Y2.view(np.uint16))
+
+
 def test_caller_workspace_entry_point(tm, oracle):
     import torch
     M, K, N, g = 20, 1152, 336, 128
