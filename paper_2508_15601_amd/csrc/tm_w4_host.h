@@ -52,7 +52,7 @@ inline int skinny_ntw(int v)
 }
 inline int tile_bm(int v) { return (v == kTile32x256 || v == kTile32x128 || v == kTile32x96) ? 32 : ((v == kTile64x256 || v == kTile64x128 || v == kTile64x96 || v == kTile64x64) ? 64 : ((v == kTile128x256 || v == kTile128x128 || v == kTile128x512 || v == kTile128x64) ? 128 : (v == kTile192x256 ? 192 : 256))); }
 inline bool tile_two_waves(int v) { return v == kTile32x96 || v == kTile64x96 || v == kTile64x64 || v == kTile128x64; }
-inline int tile_threads(int v) { return tile_two_waves(v) ? 128 : 256; }     // of one wave set
+inline int tile_threads(int v) { return v == kTile128x512 ? 512 : tile_two_waves(v) ? 128 : 256; }     // of one wave set
 // wave sets per CTA (in-CTA split of every K stage) a tile variant is built with, besides 1
 inline bool tile_has_kgroups(int v, int kg)
 {

@@ -9,7 +9,8 @@ hipError_t launch_tile_large(const GemmParams& p, const Plan& plan, int group, h
     switch (plan.variant) {
         case kTile256x256: return launch_shape<16, 4, 4, 2>(p, plan, group, stream);
         case kTile192x256: return launch_shape<12, 4, 4, 2>(p, plan, group, stream);
-        case kTile128x512: return launch_shape<8, 8, 4, 2>(p, plan, group, stream);
+        // eight waves of 128 x 64: one CTA per CU, the X stage loaded once for 512 columns
+        case kTile128x512: return launch_shape<8, 4, 8, 2>(p, plan, group, stream);
         default: return hipErrorInvalidValue;
     }
 }

@@ -277,7 +277,7 @@ def test_random_layer_shapes_auto_plan(tm, oracle, seed):
                                                  (2, 2, 16), (3, 1, 8), (3, 3, 16), (4, 1, 16), (4, 2, 8), (5, 1, 0),
                                                  (5, 3, 0), (6, 1, 0), (6, 2, 0), (7, 1, 0), (7, 3, 0), (8, 1, 0),
                                                  (8, 2, 0), (9, 1, 0), (9, 2, 0), (10, 1, 0), (10, 3, 0),
-                                                 (11, 1, 0), (11, 2, 0), (12, 1, 0), (13, 1, 0), (13, 2, 0),
+                                                 (11, 1, 0), (11, 2, 0), (12, 1, 0), (12, 2, 0), (12, 3, 0), (13, 1, 0), (13, 2, 0),
                                                  (14, 1, 8), (14, 2, 16), (15, 1, 16), (15, 3, 0), (15, 1, 8), (16, 1, 0), (16, 2, 16), (16, 2, 8),
                                                  (17, 1, 0), (17, 2, 0), (18, 1, 0), (18, 3, 0), (19, 1, 0), (19, 2, 0),
                                                  (20, 1, 0), (20, 2, 0), (21, 1, 0), (21, 3, 0),
