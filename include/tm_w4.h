@@ -296,6 +296,14 @@ TM_API int tm_set_variant(int variant, int split_k);
  *                their kernels where they would take the one-shot form.
  */
 TM_API int tm_set_launch(int waves, int stage_steps);
+/*
+ * The matrix instruction of the prefill CTA tiles (128 x 256 and 128 x 512, unsplit, one wave set): 0 = automatic and 16 =
+ * the 16x16x32 form every other kernel uses; 32 = the 32x32x16 form (a second build of the same pipeline, measured 10 %
+ * slower on this chip and therefore never chosen automatically).  A sweep and test setting like the two above.
+ * tm_get_plan_mfma_shape reports which of the two a launch of M rows takes (16 or 32; negative = error).
+ */
+TM_API int tm_set_mfma_shape(int shape);
+TM_API int tm_get_plan_mfma_shape(const tm_packed_w4* packed, int M);
 TM_API const char* tm_variant_name(int variant);
 
 /*

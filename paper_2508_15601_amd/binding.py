@@ -105,6 +105,10 @@ def load_library():
     lib.tm_get_plan_units_per_wave.argtypes = [vp, i]
     lib.tm_set_variant.restype = i
     lib.tm_set_variant.argtypes = [i, i]
+    lib.tm_set_mfma_shape.restype = i
+    lib.tm_set_mfma_shape.argtypes = [i]
+    lib.tm_get_plan_mfma_shape.restype = i
+    lib.tm_get_plan_mfma_shape.argtypes = [vp, i]
     lib.tm_set_launch.restype = i
     lib.tm_set_launch.argtypes = [i, i]
     lib.tm_variant_name.restype = c.c_char_p
@@ -458,12 +462,19 @@ def tm_get_plan(packed: PackedW4, M: int) -> dict:
     upw = lib.tm_get_plan_units_per_wave(packed.handle, M)
     if upw < 0:
         raise TmError(upw, tm_last_error())
+    shape = lib.tm_get_plan_mfma_shape(packed.handle, M)
+    if shape < 0:
+        raise TmError(shape, tm_last_error())
     return {"variant": v.value, "name": lib.tm_variant_name(v.value).decode(), "split_k": s.value,
-            "grid": g.value, "block": b.value, "one_shot_units_per_wave": upw}
+            "grid": g.value, "block": b.value, "one_shot_units_per_wave": upw, "mfma_shape": shape}
 
 
 def tm_set_variant(variant: int = -1, split_k: int = 0):
     _check(load_library().tm_set_variant(variant, split_k))
+
+
+def tm_set_mfma_shape(shape: int = 0):
+    _check(load_library().tm_set_mfma_shape(shape))
 
 
 def tm_set_launch(waves: int = 0, stage_steps: int = 0):

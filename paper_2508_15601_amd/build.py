@@ -9,7 +9,7 @@ PKG = os.path.dirname(os.path.abspath(__file__))
 ROOT = os.path.dirname(PKG)
 CSRC = os.path.join(PKG, "csrc")
 LIB = os.path.join(PKG, "libtm_w4.so")
-SOURCES = ["tm_w4_api.hip", "tm_w4_pack.hip", "tm_w4_skinny.hip", "tm_w4_stream.hip", "tm_w4_stream_grouped.hip", "tm_w4_streamx.hip", "tm_w4_streamx64.hip", "tm_w4_skinny_w8.hip", "tm_w4_skinny_f8.hip", "tm_w4_tile_small.hip", "tm_w4_tile_large.hip",
+SOURCES = ["tm_w4_api.hip", "tm_w4_pack.hip", "tm_w4_skinny.hip", "tm_w4_stream.hip", "tm_w4_stream_grouped.hip", "tm_w4_streamx.hip", "tm_w4_streamx64.hip", "tm_w4_skinny_w8.hip", "tm_w4_skinny_f8.hip", "tm_w4_tile_small.hip", "tm_w4_tile_large.hip", "tm_w4_tile32.hip",
            "tm_w4_tile_kgroup.hip", "tm_w4_tile_grouped.hip", "tm_w4_tile_w8.hip", "tm_attn.hip"]
 # per-file extra flags (see the header comment of each file)
 EXTRA = {"tm_w4_tile_small.hip": ["-mllvm", "-amdgpu-mfma-vgpr-form=1"],

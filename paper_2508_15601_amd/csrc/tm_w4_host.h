@@ -70,6 +70,7 @@ struct Plan {
     int kgroups;          // tile kernels: sets of four waves per CTA, each taking its own slice of every stage
     int stream_ni;        // decode kernels: > 0 = the one-shot kernel with this many packed units per wave (the form
                           // with a ring of X pieces when M > 16)
+    int mfma32;           // tile kernels: 1 = the launch runs on the 32x32x16 matrix instruction (tm_w4_tile32.hip)
     int tiles_m, tiles_n;
     unsigned grid;
     unsigned block;
@@ -121,6 +122,7 @@ hipError_t launch_skinny_grouped_w8(const GroupedParams& gp, int variant, int ex
 hipError_t launch_skinny_grouped_f8(const GroupedParams& gp, int variant, int experts, int group, hipStream_t stream);
 hipError_t launch_tile_grouped_8bit(const GroupedParams& gp, int variant, int experts, int group, bool fp8, hipStream_t stream);
 hipError_t launch_tile(const GemmParams& p, const Plan& plan, int group, hipStream_t stream);
+hipError_t launch_tile32(const GemmParams& p, const Plan& plan, int group, hipStream_t stream);
 hipError_t launch_tile_small(const GemmParams& p, const Plan& plan, int group, hipStream_t stream);
 hipError_t launch_tile_large(const GemmParams& p, const Plan& plan, int group, hipStream_t stream);
 hipError_t launch_tile_kgroup(const GemmParams& p, const Plan& plan, int group, hipStream_t stream);

@@ -17,6 +17,7 @@ hipError_t launch_tile_large(const GemmParams& p, const Plan& plan, int group, h
 
 hipError_t launch_tile(const GemmParams& p, const Plan& plan, int group, hipStream_t stream)
 {
+    if (plan.mfma32) return launch_tile32(p, plan, group, stream);
     if (plan.kgroups > 1) return launch_tile_kgroup(p, plan, group, stream);
     return (plan.variant == kTile256x256 || plan.variant == kTile192x256 || plan.variant == kTile128x512) ? launch_tile_large(p, plan, group, stream)
                                         : launch_tile_small(p, plan, group, stream);

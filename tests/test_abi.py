@@ -91,6 +91,7 @@ def test_argument_validation_without_gpu(lib):
     assert lib.tm_set_variant(99, 0) == -1 and lib.tm_set_variant(-1, 0) == 0
     assert lib.tm_variant_name(0) == b"skinny16x16" and lib.tm_variant_name(99) == b""
     assert lib.tm_set_launch(5, 0) == -1 and lib.tm_set_launch(0, 3) == -1 and lib.tm_set_launch(0, 0) == 0
+    assert lib.tm_set_mfma_shape(8) == -1 and lib.tm_set_mfma_shape(0) == 0 and lib.tm_get_plan_mfma_shape(None, 1) == -1
     assert lib.tm_bench_copy(None, None, 16, None) == -1
     assert lib.tm_bench_mfma(None, 256, 256, 10, 1, None) == -1 and lib.tm_bench_clock(None, 0, 100, None) == -1
     assert tm.tm_version().startswith("tm_w4")

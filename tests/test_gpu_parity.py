@@ -220,6 +220,69 @@ def test_integer_exact_case(tm, oracle, M, variant, split):
     assert np.array_equal(Y.view(np.uint16), Yref.view(np.uint16))
 
 
+# The two prefill tiles exist with the 16x16x32 and with the 32x32x16 matrix instruction (the latter on request only):
+# both forms of both tiles, exact cases first.
+@pytest.mark.parametrize("shape", [16, 32])
+@pytest.mark.parametrize("variant", [7, 12])
+def test_prefill_tiles_both_mfma_shapes_exact_cases(tm, oracle, variant, shape):
+    K, N, g = 384, 80, 64
+    d = _random_problem(5, 1, K, N, g)
+    packed = gu.pack(d, g)
+    tm.tm_set_variant(variant, 1)
+    tm.tm_set_launch(4 if variant == 7 else 8, 0)        # one wave set (a launch this small would take two)
+    tm.tm_set_mfma_shape(shape)
+    try:
+        plan = tm.tm_get_plan(packed, 16)
+        _say(f"mfma shape={shape} variant={variant} plan={plan}")
+        assert plan["variant"] == variant and plan["mfma_shape"] == shape
+        for k0 in range(0, K, 16):                       # one-hot rows: the dequantised weights come back exactly
+            X = np.zeros((16, K), np.float16)
+            X[np.arange(16), np.arange(k0, k0 + 16)] = 1.0
+            Y = gu.gemm(packed, X)
+            assert np.array_equal(Y.view(np.uint16), oracle.gemm(X, d["q"], d["s"], d["z"], g).view(np.uint16)), k0
+        rng = np.random.default_rng(variant + shape)     # unit scales, small integers: any summation order is exact
+        M, K2, N2, g2 = 150, 512, 1040, 128
+        q = rng.integers(0, 16, (K2, N2), dtype=np.uint8)
+        z = rng.integers(0, 16, (K2 // g2, N2)).astype(np.float16)
+        s1 = np.ones((K2 // g2, N2), np.float16)
+        X = (rng.integers(-1, 2, (M, K2)) * (rng.random((M, K2)) < 0.25)).astype(np.float16)
+        packed2 = gu.pack({"q": q, "s": s1, "z": z, "qweight": wl.pack_interchange(q)}, g2)
+        Y = gu.gemm(packed2, X)
+        Yref = oracle.gemm(X, q, s1, z, g2)
+        assert np.abs(Yref.astype(np.float64)).max() < 2048
+        assert np.array_equal(Y.view(np.uint16), Yref.view(np.uint16))
+    finally:
+        tm.tm_set_variant(-1, 0)
+        tm.tm_set_launch(0, 0)
+        tm.tm_set_mfma_shape(0)
+
+
+@pytest.mark.parametrize("shape", [16, 32])
+@pytest.mark.parametrize("variant", [7, 12])
+@pytest.mark.parametrize("M,K,N,g", [(130, 1152, 528, 64), (300, 640, 400, 128), (257, 384, 272, 32), (128, 2816, 1040, 128),
+                                     (513, 1024, 1552, 64)])
+def test_prefill_tiles_both_mfma_shapes(tm, oracle, variant, shape, M, K, N, g):
+    """Ragged rows and columns, every group size, K of 3 ... 22 packed units, several CTA tiles in both directions."""
+    d = _random_problem(variant * 7 + shape + M, M, K, N, g)
+    packed = gu.pack(d, g)
+    tm.tm_set_variant(variant, 1)
+    tm.tm_set_launch(4 if variant == 7 else 8, 0)        # one wave set (a launch this small would take two)
+    tm.tm_set_mfma_shape(shape)
+    try:
+        plan = tm.tm_get_plan(packed, M)
+        _say(f"mfma shape={shape} variant={variant} M={M} K={K} N={N} g={g} plan={plan}")
+        assert plan["variant"] == variant and plan["mfma_shape"] == shape
+        Y = gu.gemm(packed, d["X"])
+        Y2 = gu.gemm(packed, d["X"])
+    finally:
+        tm.tm_set_variant(-1, 0)
+        tm.tm_set_launch(0, 0)
+        tm.tm_set_mfma_shape(0)
+    ok, worst, fro = acceptance(Y, oracle.gemm(d["X"], d["q"], d["s"], d["z"], g))
+    assert ok, (worst, fro)
+    assert np.array_equal(Y.view(np.uint16), Y2.view(np.uint16))
+
+
 # ------------------------------------------------------------------ GEMM: tolerance parity on ragged small shapes
 
 SMALL = [
