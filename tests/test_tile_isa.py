@@ -21,7 +21,8 @@ UNITS = {"tm_w4_tile_small": ["-mllvm", "-amdgpu-mfma-vgpr-form=1"],
          "tm_w4_tile_kgroup": ["-mllvm", "-amdgpu-mfma-vgpr-form=1"],
          "tm_w4_tile_grouped": ["-mllvm", "-amdgpu-mfma-vgpr-form=1"],
          "tm_w4_tile_w8": ["-mllvm", "-amdgpu-mfma-vgpr-form=1"],
-         "tm_w4_tile_large": []}
+         "tm_w4_tile_large": [],
+         "tm_w4_tile32": []}
 VMCNT_MAX = 63          # six-bit counter: a wave cannot have more loads outstanding, so a larger bound is no wait at all
 
 
@@ -36,7 +37,7 @@ def _assembly(unit, extra, outdir):
 
 def _stage_regions(text):
     """(kernel name, instructions of one barrier-terminated region) for every region that loads into LDS."""
-    for m in re.finditer(r"^(_ZN4tmw4[^\n]*tile_kernel[^\n]*):\s*;[^\n]*\n(.*?)^\.Lfunc_end", text, re.S | re.M):
+    for m in re.finditer(r"^(_ZN4tmw4[^\n]*tile(?:32)?_kernel[^\n]*):\s*;[^\n]*\n(.*?)^\.Lfunc_end", text, re.S | re.M):
         region = []
         for line in m.group(2).splitlines():
             t = line.strip()
@@ -77,4 +78,4 @@ def test_stage_end_wait_covers_the_direct_to_lds_loads(tmp_path):
             if ds:
                 assert any(t.startswith("s_waitcnt") and "lgkmcnt(0)" in t for t in reg[ds[-1] + 1:]), (name, "LDS reads")
             checked += 1
-    assert checked > 500        # every instantiation has a prologue and PD*(PD+1) unrolled stages
+    assert checked > 1200        # every instantiation has a prologue and PD*(PD+1) unrolled stages
