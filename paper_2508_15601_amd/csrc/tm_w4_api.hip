@@ -204,6 +204,17 @@ int decode_slot_floats(int variant, int NT, int strips)
 
 // Which kernel family and shape a launch takes when nothing is forced (a forced variant is checked against the weight
 // format and passed through).
+// Deep and narrow layers at 33 ... 64 rows (K of 80 packed units or more, N such that 64 x 64 tiles with K split in four
+// make about one CTA per CU): the 64 x 64 CTA tile with its split outruns the decode kernels with an X ring, whose CTAs
+// each stream a quarter of a long X (K = 11008, N = 4096: 15.7 against 17.7 us at M = 64, 15.2 against 16.4 us at M = 40;
+// K = 14336: 18.5 against 19.6 us; at K = 8192 and below the X ring wins or ties).
+static bool deep_narrow_tile64(const tm_packed_w4* h, int M, int num_cu)
+{
+    const long t = ceil_div(h->N, 64);
+    return h->bits == 4 && M > 32 && M <= 64 && h->K / kUnitK >= 80 && t * 4 <= num_cu && t * 8 > num_cu &&
+           g_force_variant < 0 && g_force_split == 0 && g_force_waves == 0 && g_force_stage == 0;
+}
+
 static int choose_variant(const tm_packed_w4* h, int M, int num_cu, int NT)
 {
     const bool w8 = h->bits == 8;
@@ -250,7 +261,8 @@ static int choose_variant(const tm_packed_w4* h, int M, int num_cu, int NT)
             if (M <= 32) {
                 variant = cost(kTile32x96) < cost(kTile32x128) ? kTile32x96 : kTile32x128;
             } else if (M <= 64) {
-                if (ceil_div(NT, 8) * 4 <= num_cu) variant = kTile32x128;      // narrow: more CTAs, K split on top
+                if (deep_narrow_tile64(h, M, num_cu)) variant = kTile64x64;
+                else if (ceil_div(NT, 8) * 4 <= num_cu) variant = kTile32x128;      // narrow: more CTAs, K split on top
                 else variant = cost(kTile64x96) < cost(kTile64x128) ? kTile64x96 : kTile64x128;
             } else {
                 // The shape with the least estimated time: rounds of CTAs times the time of one round.  A round of
@@ -299,6 +311,7 @@ static int choose_variant(const tm_packed_w4* h, int M, int num_cu, int NT)
 // 64-row variants keep meaning the ring-buffered kernels.
 static bool plan_x_ring(const tm_packed_w4* h, int M, int num_cu, int KU, int NT, int max_split_ws, Plan& pl)
 {
+    if (deep_narrow_tile64(h, M, num_cu)) return false;
     if (h->bits == 4 && M > 16 && M <= 64 && g_force_stage != 1 && (uint64_t)M * h->K * 2u < (1ull << 31) &&
         (g_force_variant < 0 || (is_skinny(g_force_variant) && skinny_rows(g_force_variant) == 16))) {
         auto emit = [&](int strips, int split, int kps, int w, int ni) {
