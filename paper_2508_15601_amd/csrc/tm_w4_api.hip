@@ -247,7 +247,9 @@ static int choose_variant(const tm_packed_w4* h, int M, int num_cu, int NT)
             // Deep-and-narrow layers with many rows: every strip re-reads all M*K activations, which then outweighs
             // the weights; 64-column strips with K split over four CTAs read a quarter of X each (measured
             // 11.2 vs 14.2 us at K=11008, N=4096, M=16; not a gain at K=4096).
-            if (per_cu <= 1 && M > 8 && h->K >= 8192 && NT >= num_cu) variant = kSkinny16x64;
+            // (at K = 8192 exactly, split in two: 32-column strips, which make one CTA per CU where 64-column ones make one
+            // per two - K = 8192, N = 4096, M = 16: 8.3 against 9.8 us)
+            if (per_cu <= 1 && M > 8 && h->K >= 8192 && NT >= num_cu) variant = h->K == 8192 ? kSkinny16x32 : kSkinny16x64;
         } else if (M <= 32 && ceil_div(NT, 4) * 2 <= num_cu) {
             // narrow outputs (N <= 8192 on 256 CUs): 64-column strips with K split across CTAs so that every
             // CU gets one CTA; each CTA then re-reads only its K slice of X
